@@ -1,0 +1,25 @@
+"""Builds liblstm_int_oracle.so (plain C, gcc -O2, OpenMP over batch rows).
+
+TEST INFRASTRUCTURE.  Run: python oracle/build.py
+"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB = os.path.join(HERE, "liblstm_int_oracle.so")
+
+
+def build(force=True):
+    src = os.path.join(HERE, "lstm_int_oracle.c")
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(
+        os.path.getmtime(src), os.path.getmtime(os.path.join(HERE, "lstm_int_oracle.h"))
+    ):
+        return LIB
+    cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+           "-Wall", "-Wextra", "-o", LIB, src, "-lm"]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())
