@@ -1,0 +1,199 @@
+/*
+ * lstm_int -- integer-only LSTM (arXiv 2101.05453) for AMD MI355X (gfx950).
+ *
+ * C ABI of the shared library liblstm_int.so.  Two phases, as in the paper:
+ *   offline  (Secs. 3.2-3.3, Table 2, Sec. 6): float parameters + collected
+ *            statistics -> integer model            -> lstm_int_prepare
+ *   online   (Secs. 3.2.4-3.2.9, integer-execution figures): int8 in, int8
+ *            out, no floating-point operation on the path -> lstm_int_forward
+ *
+ * Notation: T timesteps, B batch rows, L layers, I layer input width, N cells,
+ * H layer output width (H = N unless PROJECTION), gate order i, f, z, o as in
+ * eqs. (1)-(5) of Sec. 2.  All tensors are row-major and dense.
+ *
+ * Every function returns 0 on success or a negative LSTM_INT_E_* code; no
+ * exception crosses this boundary and the library keeps no global state
+ * besides the models it hands out.
+ */
+#ifndef LSTM_INT_H
+#define LSTM_INT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Variant switches, Sec. 2 (last paragraph) and the columns of Table 2. */
+#define LSTM_INT_CIFG 1u        /* i = 1 - f; the i-gate tensors are absent   */
+#define LSTM_INT_PEEPHOLE 2u    /* P . c terms on gates i, f (c^{t-1}), o (c^t) */
+#define LSTM_INT_LAYER_NORM 4u  /* norm() . L + b on every gate               */
+#define LSTM_INT_PROJECTION 8u  /* h = W_proj m + b_proj                      */
+
+#define LSTM_INT_OK 0
+#define LSTM_INT_E_INVALID_ARG (-1)  /* NULL, shape or flag inconsistency       */
+#define LSTM_INT_E_UNSUPPORTED (-2)  /* outside the limits stated at prepare    */
+#define LSTM_INT_E_BAD_RANGE (-3)    /* min > max, NaN/Inf in a parameter       */
+#define LSTM_INT_E_OUT_OF_MEMORY (-4)
+#define LSTM_INT_E_DEVICE (-5)       /* HIP error, or host-only model           */
+#define LSTM_INT_E_WORKSPACE (-6)    /* workspace too small or misaligned       */
+
+typedef struct lstm_int_model lstm_int_model;
+
+/*
+ * Float parameters of one layer (eqs. 1-7) and the statistics of a
+ * calibration run (Sec. 4).  Every pointer is HOST memory, caller-owned,
+ * read-only, and may be freed once lstm_int_prepare returns.
+ * Under CIFG index 0 of W, R, b, P, Lw must be NULL (the dagger rows of
+ * Table 2); P only with PEEPHOLE; Lw only with LAYER_NORM; Wproj only with
+ * PROJECTION (bproj may be NULL = zeros).
+ */
+typedef struct {
+  int32_t input_size;  /* I */
+  int32_t num_cells;   /* N */
+  int32_t output_size; /* H; must equal N without PROJECTION */
+  uint32_t flags;
+  const float *W[4];  /* [N, I] input weights, i,f,z,o */
+  const float *R[4];  /* [N, H] recurrent weights */
+  const float *b[4];  /* [N] gate bias (applied after norm() with LAYER_NORM) */
+  const float *P[3];  /* [N] peephole weights, i,f,o */
+  const float *Lw[4]; /* [N] layer-norm weights */
+  const float *Wproj; /* [H, N] */
+  const float *bproj; /* [H] */
+  float x_min, x_max; /* range of the layer input; ignored for layers > 0,  */
+                      /* which take the previous layer's h quantization     */
+  float h_min, h_max; /* range of the layer output h */
+  float m_min, m_max; /* range of the hidden state m (PROJECTION only) */
+  float c_absmax;     /* max |c|; extended to a power of two (Sec. 3.2.2) */
+  float g_absmax[4];  /* max |W x + R h + P.c| per gate (LAYER_NORM only) */
+} lstm_int_layer_params;
+
+/*
+ * Host views of everything prepare derived for one layer, valid until the
+ * model is destroyed.  Gate-indexed arrays have 4 slots (i,f,z,o); slot 0 is
+ * zero under CIFG.  An effective scale s is held as (M, e), s ~= M * 2^(e-31)
+ * with 2^30 <= M < 2^31, and applied as
+ *   rescale(a) = sat32(floor(a * M / 2^(31-e) + 1/2)).
+ */
+typedef struct {
+  int32_t I, N, H, G; /* G = 4, or 3 under CIFG */
+  uint32_t flags;
+  int32_t m_c; /* the cell state is Q(m_c).(15 - m_c) */
+  int32_t zp_x, zp_h, zp_m; /* real = s * (q - zp) */
+  double s_x, s_h, s_m, s_c, s_Wp;
+  double s_W[4], s_R[4], s_P[3], s_L[4], s_g[4];
+  int32_t Mx[4], ex[4];   /* W x     -> gate scale (Sec. 3.2.4 / 3.2.5) */
+  int32_t Mh[4], eh[4];   /* R h + b -> gate scale */
+  int32_t Mc[3], ec[3];   /* P . c   -> gate scale; i, f, o */
+  int32_t Mln[4], eln[4]; /* layer norm, second stage -> Q3.12 (Sec. 3.2.6) */
+  int32_t Mm, em;         /* o . tanh(c) -> m (Sec. 3.2.7) */
+  int32_t Mp, ep;         /* projection -> h (Sec. 3.2.8) */
+  const int8_t *Wq;       /* [4][N][I] */
+  const int8_t *Rq;       /* [4][N][H] */
+  const int32_t *qb;      /* [4][N] */
+  const int16_t *Pq;      /* [3][N] */
+  const int16_t *Lq;      /* [4][N] */
+  const int8_t *Wpq;      /* [H][N]; NULL without PROJECTION */
+  const int32_t *qbp;     /* [H];    NULL without PROJECTION */
+  const int32_t *bx_fold; /* [4][N]  -zp_x * sum_k Wq            (Sec. 6) */
+  const int32_t *bh_fold; /* [4][N]  (no LN: qb) - zp_h * sum_k Rq        */
+  const int32_t *bp_fold; /* [H]     qbp - zp_m * sum_n Wpq; NULL w/o proj */
+} lstm_int_layer_quant;
+
+/*
+ * Optional dumps of one layer's intermediate integer tensors, for parity
+ * checks.  DEVICE pointers, caller-owned, each may be NULL.  Gate-indexed
+ * tensors have 4 slots; under CIFG slot 0 of tx/th/g/ln is not written and
+ * slot 0 of act holds the coupled input gate.
+ */
+typedef struct {
+  int32_t layer;
+  int16_t *tx;  /* [T,B,4,N] rescaled W x term            */
+  int16_t *th;  /* [T,B,4,N] rescaled R h (+ b) term      */
+  int16_t *g;   /* [T,B,4,N] gate sum (Secs. 3.2.4/3.2.5) */
+  int16_t *ln;  /* [T,B,4,N] layer-norm output, Q3.12     */
+  int16_t *act; /* [T,B,4,N] i,f,z,o after sigma/tanh, Q0.15 */
+  int16_t *c;   /* [T,B,N] cell state after the step      */
+  int8_t *m;    /* [T,B,N] hidden state                    */
+  int8_t *h;    /* [T,B,H] layer output                    */
+} lstm_int_trace;
+
+/*
+ * Offline phase (Table 2; Secs. 3.2.1-3.2.9; Sec. 6).  Quantizes the float
+ * parameters of num_layers stacked layers (layer l+1 reads layer l's h with
+ * its scale and zero point), derives every effective scale as (M, e), folds
+ * the zero points into the biases, and -- for device >= 0 -- uploads the
+ * packed weights to that HIP device.  device = -1 builds a host-only model
+ * (lstm_int_get_quant works, lstm_int_forward returns LSTM_INT_E_DEVICE).
+ * Limits (LSTM_INT_E_UNSUPPORTED): I, N, H <= 2^15 (safe accumulation depth,
+ * Sec. 3.1.1); N <= 4096 with LAYER_NORM; c_absmax <= 256; an effective scale
+ * outside [2^-32, 2^30); a bias so large that bias + 128 * sum|w| leaves
+ * int32.  On success *out owns host and device memory until
+ * lstm_int_destroy.
+ */
+int lstm_int_prepare(const lstm_int_layer_params *layers, int32_t num_layers,
+                     int32_t device, lstm_int_model **out);
+
+/* Fills *out with views into the model (no copy, no device access). */
+int lstm_int_get_quant(const lstm_int_model *model, int32_t layer,
+                       lstm_int_layer_quant *out);
+
+/* Device bytes lstm_int_forward needs for T steps of B rows (0 on error). */
+size_t lstm_int_workspace_bytes(const lstm_int_model *model, int32_t T, int32_t B);
+
+/*
+ * Online phase: T steps over B rows through all layers (the time loop and
+ * layer stack of Sec. 7 around the cell of Secs. 3.2.4-3.2.9).
+ *   x        DEVICE int8 [T,B,I0], quantized with layer 0's (s_x, zp_x)
+ *   y        DEVICE int8 [T,B,H_last], with the last layer's (s_h, zp_h)
+ *   h_state  DEVICE int8, layers concatenated, layer l is [B,H_l]; read as
+ *            h^{-1} and overwritten with h^{T-1}; NULL = start from real 0
+ *   c_state  DEVICE int16, likewise [B,N_l]; NULL = zeros
+ *   workspace DEVICE, >= lstm_int_workspace_bytes(model,T,B), 256-byte aligned
+ *   hip_stream a hipStream_t (NULL = the default stream)
+ *   trace    NULL, or dumps of one layer
+ * Allocates nothing, never synchronizes the host: all work is enqueued on
+ * hip_stream and touches only y, the state buffers, workspace and trace.
+ * T = 0 or B = 0 is a no-op.  Calls sharing a model must not overlap in time
+ * unless they use different workspaces and the same stream order.
+ */
+int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
+                     int32_t B, int8_t *y, int8_t *h_state, int16_t *c_state,
+                     void *workspace, size_t workspace_bytes, void *hip_stream,
+                     const lstm_int_trace *trace);
+
+/*
+ * Tuning knobs of the online phase; results never depend on them.
+ *   "path": 0 = choose automatically, 1 = one launch per operation and step,
+ *           2 = persistent recurrent kernel (weights resident on chip)
+ * Unknown keys or values give LSTM_INT_E_INVALID_ARG.
+ */
+int lstm_int_set_option(lstm_int_model *model, const char *key, int64_t value);
+
+/*
+ * Per-kernel device time of the forward calls made while profiling is on,
+ * measured with HIP events on the stream the kernels run on.
+ * lstm_int_profile_begin resets the counters and makes forward record events;
+ * lstm_int_profile_end synchronizes that stream and fills, per kernel class k
+ * (LSTM_INT_K_*), launches[k] and total_ms[k].  Profiling adds host work to
+ * forward; throughput is measured with it off.
+ */
+#define LSTM_INT_K_INPUT_GEMM 0 /* hoisted W x over all T, + rescale        */
+#define LSTM_INT_K_RECURRENT 1  /* R h per step (+ fused epilogue if any)   */
+#define LSTM_INT_K_CELL 2       /* gate sum, layer norm, activations, cell  */
+#define LSTM_INT_K_PROJECTION 3 /* W_proj m + requantization                */
+#define LSTM_INT_K_OTHER 4      /* state copies, padding                    */
+#define LSTM_INT_K_COUNT 5
+int lstm_int_profile_begin(lstm_int_model *model);
+int lstm_int_profile_end(lstm_int_model *model, int64_t launches[LSTM_INT_K_COUNT],
+                         double total_ms[LSTM_INT_K_COUNT]);
+
+void lstm_int_destroy(lstm_int_model *model);
+
+const char *lstm_int_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

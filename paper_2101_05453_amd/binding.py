@@ -1,0 +1,267 @@
+"""ctypes binding of liblstm_int.so: the same entry points as include/lstm_int.h.
+
+Argument marshalling only -- every step of the path runs in the library's
+kernels.  PyTorch supplies device memory and streams.  There is no fallback:
+if the library is missing or the call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblstm_int.so")
+
+CIFG, PEEPHOLE, LAYER_NORM, PROJECTION = 1, 2, 4, 8
+OK = 0
+E_INVALID_ARG, E_UNSUPPORTED, E_BAD_RANGE, E_OUT_OF_MEMORY, E_DEVICE, E_WORKSPACE = -1, -2, -3, -4, -5, -6
+K_INPUT_GEMM, K_RECURRENT, K_CELL, K_PROJECTION, K_OTHER, K_COUNT = 0, 1, 2, 3, 4, 5
+KERNEL_CLASSES = ("input_gemm", "recurrent", "cell", "projection", "other")
+
+_fp = C.POINTER(C.c_float)
+
+
+class LayerParams(C.Structure):
+    """lstm_int_layer_params"""
+    _fields_ = [
+        ("input_size", C.c_int32), ("num_cells", C.c_int32), ("output_size", C.c_int32),
+        ("flags", C.c_uint32),
+        ("W", _fp * 4), ("R", _fp * 4), ("b", _fp * 4), ("P", _fp * 3), ("Lw", _fp * 4),
+        ("Wproj", _fp), ("bproj", _fp),
+        ("x_min", C.c_float), ("x_max", C.c_float), ("h_min", C.c_float), ("h_max", C.c_float),
+        ("m_min", C.c_float), ("m_max", C.c_float), ("c_absmax", C.c_float),
+        ("g_absmax", C.c_float * 4),
+    ]
+
+
+class LayerQuant(C.Structure):
+    """lstm_int_layer_quant"""
+    _fields_ = [
+        ("I", C.c_int32), ("N", C.c_int32), ("H", C.c_int32), ("G", C.c_int32),
+        ("flags", C.c_uint32), ("m_c", C.c_int32),
+        ("zp_x", C.c_int32), ("zp_h", C.c_int32), ("zp_m", C.c_int32),
+        ("s_x", C.c_double), ("s_h", C.c_double), ("s_m", C.c_double), ("s_c", C.c_double),
+        ("s_Wp", C.c_double),
+        ("s_W", C.c_double * 4), ("s_R", C.c_double * 4), ("s_P", C.c_double * 3),
+        ("s_L", C.c_double * 4), ("s_g", C.c_double * 4),
+        ("Mx", C.c_int32 * 4), ("ex", C.c_int32 * 4),
+        ("Mh", C.c_int32 * 4), ("eh", C.c_int32 * 4),
+        ("Mc", C.c_int32 * 3), ("ec", C.c_int32 * 3),
+        ("Mln", C.c_int32 * 4), ("eln", C.c_int32 * 4),
+        ("Mm", C.c_int32), ("em", C.c_int32), ("Mp", C.c_int32), ("ep", C.c_int32),
+        ("Wq", C.POINTER(C.c_int8)), ("Rq", C.POINTER(C.c_int8)),
+        ("qb", C.POINTER(C.c_int32)), ("Pq", C.POINTER(C.c_int16)),
+        ("Lq", C.POINTER(C.c_int16)), ("Wpq", C.POINTER(C.c_int8)),
+        ("qbp", C.POINTER(C.c_int32)), ("bx_fold", C.POINTER(C.c_int32)),
+        ("bh_fold", C.POINTER(C.c_int32)), ("bp_fold", C.POINTER(C.c_int32)),
+    ]
+
+
+class Trace(C.Structure):
+    """lstm_int_trace"""
+    _fields_ = [("layer", C.c_int32)] + [
+        (n, C.c_void_p) for n in ("tx", "th", "g", "ln", "act", "c", "m", "h")
+    ]
+
+
+TRACE_FIELDS = ("tx", "th", "g", "ln", "act", "c", "m", "h")
+
+_lib = None
+
+
+class LstmIntError(RuntimeError):
+    def __init__(self, code, what):
+        msg = lib().lstm_int_strerror(code).decode() if _lib is not None else "?"
+        super().__init__(f"{what}: {msg} ({code})")
+        self.code = code
+
+
+def lib():
+    """Loads liblstm_int.so (built by paper_2101_05453_amd.build); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run python -m paper_2101_05453_amd.build")
+        L = C.CDLL(LIB_PATH)
+        L.lstm_int_prepare.restype = C.c_int
+        L.lstm_int_prepare.argtypes = [C.POINTER(LayerParams), C.c_int32, C.c_int32,
+                                       C.POINTER(C.c_void_p)]
+        L.lstm_int_get_quant.restype = C.c_int
+        L.lstm_int_get_quant.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerQuant)]
+        L.lstm_int_workspace_bytes.restype = C.c_size_t
+        L.lstm_int_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.lstm_int_forward.restype = C.c_int
+        L.lstm_int_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
+                                       C.POINTER(Trace)]
+        L.lstm_int_set_option.restype = C.c_int
+        L.lstm_int_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
+        L.lstm_int_profile_begin.restype = C.c_int
+        L.lstm_int_profile_begin.argtypes = [C.c_void_p]
+        L.lstm_int_profile_end.restype = C.c_int
+        L.lstm_int_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+        L.lstm_int_destroy.restype = None
+        L.lstm_int_destroy.argtypes = [C.c_void_p]
+        L.lstm_int_strerror.restype = C.c_char_p
+        L.lstm_int_strerror.argtypes = [C.c_int]
+        _lib = L
+    return _lib
+
+
+def _check(rc, what):
+    if rc != OK:
+        raise LstmIntError(rc, what)
+
+
+def marshal_layers(layers):
+    """LayerSpec-like objects -> (ctypes array of lstm_int_layer_params, keep-alive list)."""
+    arr = (LayerParams * len(layers))()
+    keep = []
+
+    def ptr(a):
+        if a is None:
+            return _fp()
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        keep.append(a)
+        return a.ctypes.data_as(_fp)
+
+    for p, s in zip(arr, layers):
+        p.input_size, p.num_cells, p.output_size = s.input_size, s.num_cells, s.output_size
+        p.flags = s.flags
+        for g in range(4):
+            p.W[g], p.R[g], p.b[g], p.Lw[g] = ptr(s.W[g]), ptr(s.R[g]), ptr(s.b[g]), ptr(s.Lw[g])
+        for j in range(3):
+            p.P[j] = ptr(s.P[j])
+        p.Wproj, p.bproj = ptr(s.Wproj), ptr(s.bproj)
+        p.x_min, p.x_max, p.h_min, p.h_max = s.x_min, s.x_max, s.h_min, s.h_max
+        p.m_min, p.m_max, p.c_absmax = s.m_min, s.m_max, s.c_absmax
+        for g in range(4):
+            p.g_absmax[g] = s.g_absmax[g]
+    return arr, keep
+
+
+def _view(ptr, shape, dtype):
+    if not ptr:
+        return None
+    n = int(np.prod(shape))
+    return np.ctypeslib.as_array(ptr, shape=(n,)).astype(dtype).reshape(shape).copy()
+
+
+class Model:
+    """Owns one lstm_int_model."""
+
+    def __init__(self, handle, num_layers, device):
+        self._h = handle
+        self.num_layers = num_layers
+        self.device = device
+
+    def __del__(self):
+        self.destroy()
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            lib().lstm_int_destroy(self._h)
+            self._h = None
+
+    # lstm_int_get_quant
+    def get_quant(self, layer):
+        q = LayerQuant()
+        _check(lib().lstm_int_get_quant(self._h, layer, C.byref(q)), "lstm_int_get_quant")
+        N, I, H = q.N, q.I, q.H
+        d = {k: getattr(q, k) for k in ("I", "N", "H", "G", "flags", "m_c", "zp_x", "zp_h", "zp_m",
+                                        "s_x", "s_h", "s_m", "s_c", "s_Wp", "Mm", "em", "Mp", "ep")}
+        for k in ("s_W", "s_R", "s_P", "s_L", "s_g", "Mx", "ex", "Mh", "eh", "Mc", "ec", "Mln", "eln"):
+            d[k] = list(getattr(q, k))
+        d["Wq"] = _view(q.Wq, (4, N, I), np.int8)
+        d["Rq"] = _view(q.Rq, (4, N, H), np.int8)
+        d["qb"] = _view(q.qb, (4, N), np.int32)
+        d["Pq"] = _view(q.Pq, (3, N), np.int16)
+        d["Lq"] = _view(q.Lq, (4, N), np.int16)
+        d["bx_fold"] = _view(q.bx_fold, (4, N), np.int32)
+        d["bh_fold"] = _view(q.bh_fold, (4, N), np.int32)
+        if q.flags & PROJECTION:
+            d["Wpq"] = _view(q.Wpq, (H, N), np.int8)
+            d["qbp"] = _view(q.qbp, (H,), np.int32)
+            d["bp_fold"] = _view(q.bp_fold, (H,), np.int32)
+        return d
+
+    def dims(self):
+        out = []
+        for l in range(self.num_layers):
+            q = LayerQuant()
+            _check(lib().lstm_int_get_quant(self._h, l, C.byref(q)), "lstm_int_get_quant")
+            out.append((q.I, q.N, q.H))
+        return out
+
+    # lstm_int_workspace_bytes
+    def workspace_bytes(self, T, B):
+        return lib().lstm_int_workspace_bytes(self._h, T, B)
+
+    # lstm_int_set_option
+    def set_option(self, key, value):
+        _check(lib().lstm_int_set_option(self._h, key.encode(), value), "lstm_int_set_option")
+
+    # lstm_int_profile_begin / lstm_int_profile_end
+    def profile_begin(self):
+        _check(lib().lstm_int_profile_begin(self._h), "lstm_int_profile_begin")
+
+    def profile_end(self):
+        n = (C.c_int64 * K_COUNT)()
+        ms = (C.c_double * K_COUNT)()
+        _check(lib().lstm_int_profile_end(self._h, n, ms), "lstm_int_profile_end")
+        return {k: {"launches": int(n[i]), "total_ms": float(ms[i])}
+                for i, k in enumerate(KERNEL_CLASSES)}
+
+    # lstm_int_forward, raw pointers
+    def forward_ptr(self, x_ptr, T, B, y_ptr, h_ptr, c_ptr, ws_ptr, ws_bytes, stream_ptr, trace=None):
+        _check(lib().lstm_int_forward(self._h, x_ptr, T, B, y_ptr, h_ptr, c_ptr, ws_ptr, ws_bytes,
+                                      stream_ptr, C.byref(trace) if trace is not None else None),
+               "lstm_int_forward")
+
+    # lstm_int_forward on torch device tensors
+    def forward(self, x, y=None, h_state=None, c_state=None, workspace=None, trace_layer=None):
+        """x: int8 CUDA tensor [T,B,I0].  Returns y (int8 [T,B,H_last]); with
+        trace_layer also a dict of that layer's intermediate tensors.  The call
+        is asynchronous on torch's current stream."""
+        import torch
+
+        assert x.is_cuda and x.dtype == torch.int8 and x.is_contiguous()
+        T, B, _ = x.shape
+        dims = self.dims()
+        if y is None:
+            y = torch.empty((T, B, dims[-1][2]), dtype=torch.int8, device=x.device)
+        need = self.workspace_bytes(T, B)
+        if workspace is None:
+            workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        tr, bufs = None, {}
+        if trace_layer is not None:
+            I, N, H = dims[trace_layer]
+            tr = Trace()
+            tr.layer = trace_layer
+            for f in TRACE_FIELDS:
+                shape = {"c": (T, B, N), "m": (T, B, N), "h": (T, B, H)}.get(f, (T, B, 4, N))
+                dt = torch.int8 if f in ("m", "h") else torch.int16
+                bufs[f] = torch.zeros(shape, dtype=dt, device=x.device)
+                setattr(tr, f, bufs[f].data_ptr())
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+        self.forward_ptr(x.data_ptr(), T, B, y.data_ptr(),
+                         h_state.data_ptr() if h_state is not None else None,
+                         c_state.data_ptr() if c_state is not None else None,
+                         workspace.data_ptr(), workspace.numel(), stream, tr)
+        return (y, bufs) if trace_layer is not None else y
+
+
+# lstm_int_prepare
+def prepare(layers, device=0):
+    """layers: LayerSpec-like objects with calibration statistics filled in.
+    device = -1 builds a host-only model (no GPU needed)."""
+    arr, keep = marshal_layers(layers)
+    h = C.c_void_p()
+    rc = lib().lstm_int_prepare(arr, len(layers), device, C.byref(h))
+    del keep
+    _check(rc, "lstm_int_prepare")
+    return Model(h, len(layers), device)
+
+
+def strerror(code):
+    return lib().lstm_int_strerror(code).decode()

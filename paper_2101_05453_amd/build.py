@@ -1,0 +1,49 @@
+"""Builds liblstm_int.so (HIP, gfx950) in-tree.  Run: python -m paper_2101_05453_amd.build"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "liblstm_int.so")
+SOURCES = ["prepare.cpp", "kernels.hip", "api.hip"]
+HOSTMATH_LIB = os.path.join(HERE, "liblstm_int_hostmath.so")
+
+# packed-fp32 instructions are disabled for all device code
+HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-Wall", "-Wno-unused-function"]
+
+
+def build(verbose=False):
+    """Compiles every source for gfx950 and links the shared library."""
+    objs = []
+    for src in SOURCES:
+        obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
+        cmd = ["hipcc", "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + HIP_FLAGS
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0 or verbose:
+            print(" ".join(cmd))
+            print(_filter(r.stderr))
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}")
+        objs.append(obj)
+    cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
+    subprocess.run(cmd, check=True)
+    build_hostmath()
+    return LIB
+
+
+def build_hostmath():
+    """Host-only build of the device math header, for CPU checks of it."""
+    cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-ffp-contract=off", "-o", HOSTMATH_LIB,
+           os.path.join(CSRC, "hostmath_shim.cpp"), os.path.join(CSRC, "prepare.cpp")]
+    subprocess.run(cmd, check=True)
+    return HOSTMATH_LIB
+
+
+def _filter(text):
+    return "\n".join(l for l in text.splitlines() if "packed-fp32-ops" not in l)
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

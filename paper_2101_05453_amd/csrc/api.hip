@@ -1,0 +1,469 @@
+// C ABI of liblstm_int (include/lstm_int.h): model lifetime, the upload of the
+// packed integer tensors, and the orchestration of the online phase.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+#include "model.h"
+
+using namespace lstm_int;
+
+namespace {
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Device-side tensors of one layer, all inside the model's single allocation.
+struct LayerDev {
+  int Ipad = 0, Hpad = 0, Npad = 0;  // K extents padded to 64
+  int GN = 0;                        // G * N output columns of the gate matmuls
+  int8_t *W = nullptr;               // [pad128(G*N), Ipad]  present gates, gate-major
+  int8_t *R = nullptr;               // [pad128(G*N), Hpad]
+  int8_t *Wproj = nullptr;           // [pad128(H), Npad]
+  int32_t *bx = nullptr, *bh = nullptr, *bp = nullptr;  // folded biases, padded like the rows
+  int16_t *Pq = nullptr, *Lq = nullptr;
+  int32_t *qb = nullptr;
+  const uint16_t *tanhc = nullptr;  // tanh table of the cell format Q(m_c).(15-m_c)
+  Requant rq_x, rq_h, rq_p;
+};
+
+struct Profile {
+  bool on = false;
+  hipStream_t stream = nullptr;
+  std::vector<hipEvent_t> ev;  // pairs (start, stop)
+  std::vector<int> cls;
+  size_t used = 0;  // pairs in use
+};
+
+}  // namespace
+
+struct lstm_int_model {
+  int device = -1;
+  std::vector<LayerHost> host;
+  std::vector<LayerDev> dev;
+  void *arena = nullptr;
+  const uint16_t *sig3 = nullptr, *tanh3 = nullptr;
+  int path = 0;
+  Profile prof;
+};
+
+namespace {
+
+struct Workspace {
+  size_t tx, out[2], xpad, th, mbuf, c, h0, total;
+};
+
+Workspace plan_workspace(const lstm_int_model *m, int64_t T, int64_t B) {
+  int maxGN = 0, maxHpad = 0, maxNpad = 0, maxN = 0;
+  for (size_t l = 0; l < m->host.size(); ++l) {
+    const LayerHost &h = m->host[l];
+    maxGN = std::max(maxGN, h.G * h.N);
+    maxHpad = std::max(maxHpad, round_up(h.H, 64));
+    maxNpad = std::max(maxNpad, round_up(h.N, 64));
+    maxN = std::max(maxN, h.N);
+  }
+  Workspace w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += align256(bytes);
+    return o;
+  };
+  w.tx = take((size_t)T * B * maxGN * 2);
+  w.out[0] = take((size_t)T * B * maxHpad);
+  w.out[1] = take((size_t)T * B * maxHpad);
+  w.xpad = take((size_t)T * B * round_up(m->host[0].I, 64));
+  w.th = take((size_t)B * maxGN * 2);
+  w.mbuf = take((size_t)B * maxNpad);
+  w.c = take((size_t)B * maxN * 2);
+  w.h0 = take((size_t)B * maxHpad);
+  w.total = off;
+  return w;
+}
+
+Requant make_requant(const int32_t *M, const int32_t *e, int first, int count, int cols_per_gate,
+                     int zp) {
+  Requant r;
+  r.all_hi = 1;
+  for (int g = 0; g < 4; ++g) {
+    const int src = first + (g < count ? g : count - 1);
+    r.M[g] = M[src];
+    r.r[g] = 31 - e[src];
+    if (r.r[g] < 33) r.all_hi = 0;
+  }
+  r.cols_per_gate = cols_per_gate;
+  r.zp = zp;
+  return r;
+}
+
+// Times each launch with a pair of events when profiling is on.
+struct Timed {
+  Profile &p;
+  hipStream_t s;
+  bool active;
+  Timed(Profile &prof, hipStream_t stream, int cls) : p(prof), s(stream), active(false) {
+    if (p.on && (p.used + 1) * 2 <= p.ev.size()) {
+      active = true;
+      p.cls[p.used] = cls;
+      p.stream = s;
+      (void)hipEventRecord(p.ev[2 * p.used], s);
+    }
+  }
+  ~Timed() {
+    if (active) {
+      (void)hipEventRecord(p.ev[2 * p.used + 1], s);
+      ++p.used;
+    }
+  }
+};
+
+int upload(lstm_int_model *m) {
+  if (hipSetDevice(m->device) != hipSuccess) return LSTM_INT_E_DEVICE;
+  const size_t L = m->host.size();
+  m->dev.resize(L);
+
+  // pass 1: sizes; pass 2: fill a host image of the arena, then one copy
+  std::vector<uint8_t> image;
+  bool need_tanh[9] = {false, false, false, false, false, false, false, false, false};
+  for (const LayerHost &h : m->host) need_tanh[h.m_c] = true;
+  need_tanh[3] = true;
+  size_t tab_off[9], sig_off = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+      size_t o = off;
+      off += align256(bytes);
+      return o;
+    };
+    sig_off = take(32769 * 2);
+    if (pass) fill_sigmoid_table(3, reinterpret_cast<uint16_t *>(image.data() + sig_off));
+    for (int mc = 0; mc <= 8; ++mc) {
+      if (!need_tanh[mc]) continue;
+      tab_off[mc] = take(32769 * 2);
+      if (pass) fill_tanh_table(mc, reinterpret_cast<uint16_t *>(image.data() + tab_off[mc]));
+    }
+    for (size_t l = 0; l < L; ++l) {
+      const LayerHost &h = m->host[l];
+      LayerDev &d = m->dev[l];
+      const int first = 4 - h.G;
+      d.Ipad = round_up(h.I, 64);
+      d.Hpad = round_up(h.H, 64);
+      d.Npad = round_up(h.N, 64);
+      d.GN = h.G * h.N;
+      const int rows = round_up(d.GN, 128);
+      const size_t oW = take((size_t)rows * d.Ipad), oR = take((size_t)rows * d.Hpad);
+      const size_t obx = take((size_t)rows * 4), obh = take((size_t)rows * 4);
+      const size_t oP = take((size_t)3 * h.N * 2), oL = take((size_t)4 * h.N * 2);
+      const size_t oqb = take((size_t)4 * h.N * 4);
+      size_t oWp = 0, obp = 0;
+      const int prow = round_up(h.H, 128);
+      if (h.projection()) {
+        oWp = take((size_t)prow * d.Npad);
+        obp = take((size_t)prow * 4);
+      }
+      if (!pass) continue;
+      uint8_t *base = image.data();
+      for (int g = first; g < 4; ++g) {
+        for (int n = 0; n < h.N; ++n) {
+          const size_t src = (size_t)g * h.N + n, dst = (size_t)(g - first) * h.N + n;
+          memcpy(base + oW + dst * d.Ipad, h.Wq.data() + src * h.I, h.I);
+          memcpy(base + oR + dst * d.Hpad, h.Rq.data() + src * h.H, h.H);
+          reinterpret_cast<int32_t *>(base + obx)[dst] = h.bx_fold[src];
+          reinterpret_cast<int32_t *>(base + obh)[dst] = h.bh_fold[src];
+        }
+      }
+      memcpy(base + oP, h.Pq.data(), (size_t)3 * h.N * 2);
+      memcpy(base + oL, h.Lq.data(), (size_t)4 * h.N * 2);
+      memcpy(base + oqb, h.qb.data(), (size_t)4 * h.N * 4);
+      if (h.projection()) {
+        for (int j = 0; j < h.H; ++j) {
+          memcpy(base + oWp + (size_t)j * d.Npad, h.Wpq.data() + (size_t)j * h.N, h.N);
+          reinterpret_cast<int32_t *>(base + obp)[j] = h.bp_fold[j];
+        }
+      }
+      uint8_t *dbase = static_cast<uint8_t *>(m->arena);
+      d.W = reinterpret_cast<int8_t *>(dbase + oW);
+      d.R = reinterpret_cast<int8_t *>(dbase + oR);
+      d.bx = reinterpret_cast<int32_t *>(dbase + obx);
+      d.bh = reinterpret_cast<int32_t *>(dbase + obh);
+      d.Pq = reinterpret_cast<int16_t *>(dbase + oP);
+      d.Lq = reinterpret_cast<int16_t *>(dbase + oL);
+      d.qb = reinterpret_cast<int32_t *>(dbase + oqb);
+      if (h.projection()) {
+        d.Wproj = reinterpret_cast<int8_t *>(dbase + oWp);
+        d.bp = reinterpret_cast<int32_t *>(dbase + obp);
+      }
+      d.tanhc = reinterpret_cast<const uint16_t *>(dbase + tab_off[h.m_c]);
+      d.rq_x = make_requant(h.Mx, h.ex, first, h.G, h.N, 0);
+      d.rq_h = make_requant(h.Mh, h.eh, first, h.G, h.N, 0);
+      if (h.projection()) d.rq_p = make_requant(&h.Mp, &h.ep, 0, 1, 1 << 28, h.zp_h);
+    }
+    if (!pass) {
+      image.assign(off, 0);
+      if (hipMalloc(&m->arena, off) != hipSuccess) {
+        m->arena = nullptr;
+        return LSTM_INT_E_OUT_OF_MEMORY;
+      }
+    }
+  }
+  if (hipMemcpy(m->arena, image.data(), image.size(), hipMemcpyHostToDevice) != hipSuccess)
+    return LSTM_INT_E_DEVICE;
+  const uint8_t *dbase = static_cast<const uint8_t *>(m->arena);
+  m->sig3 = reinterpret_cast<const uint16_t *>(dbase + sig_off);
+  m->tanh3 = reinterpret_cast<const uint16_t *>(dbase + tab_off[3]);
+  return LSTM_INT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lstm_int_prepare(const lstm_int_layer_params *layers, int32_t num_layers, int32_t device,
+                     lstm_int_model **out) {
+  if (!out) return LSTM_INT_E_INVALID_ARG;
+  *out = nullptr;
+  if (device < -1) return LSTM_INT_E_INVALID_ARG;
+  lstm_int_model *m = new (std::nothrow) lstm_int_model();
+  if (!m) return LSTM_INT_E_OUT_OF_MEMORY;
+  int rc;
+  try {
+    rc = prepare_host(layers, num_layers, m->host);
+    m->device = device;
+    if (rc == LSTM_INT_OK && device >= 0) rc = upload(m);
+  } catch (const std::bad_alloc &) {
+    rc = LSTM_INT_E_OUT_OF_MEMORY;
+  }
+  if (rc != LSTM_INT_OK) {
+    lstm_int_destroy(m);
+    return rc;
+  }
+  *out = m;
+  return LSTM_INT_OK;
+}
+
+int lstm_int_get_quant(const lstm_int_model *m, int32_t layer, lstm_int_layer_quant *q) {
+  if (!m || !q || layer < 0 || layer >= (int32_t)m->host.size()) return LSTM_INT_E_INVALID_ARG;
+  const LayerHost &h = m->host[layer];
+  memset(q, 0, sizeof(*q));
+  q->I = h.I; q->N = h.N; q->H = h.H; q->G = h.G;
+  q->flags = h.flags;
+  q->m_c = h.m_c;
+  q->zp_x = h.zp_x; q->zp_h = h.zp_h; q->zp_m = h.zp_m;
+  q->s_x = h.s_x; q->s_h = h.s_h; q->s_m = h.s_m; q->s_c = h.s_c; q->s_Wp = h.s_Wp;
+  for (int g = 0; g < 4; ++g) {
+    q->s_W[g] = h.s_W[g]; q->s_R[g] = h.s_R[g]; q->s_L[g] = h.s_L[g]; q->s_g[g] = h.s_g[g];
+    q->Mx[g] = h.Mx[g]; q->ex[g] = h.ex[g]; q->Mh[g] = h.Mh[g]; q->eh[g] = h.eh[g];
+    q->Mln[g] = h.Mln[g]; q->eln[g] = h.eln[g];
+  }
+  for (int j = 0; j < 3; ++j) {
+    q->s_P[j] = h.s_P[j]; q->Mc[j] = h.Mc[j]; q->ec[j] = h.ec[j];
+  }
+  q->Mm = h.Mm; q->em = h.em; q->Mp = h.Mp; q->ep = h.ep;
+  q->Wq = h.Wq.data(); q->Rq = h.Rq.data(); q->qb = h.qb.data();
+  q->Pq = h.Pq.data(); q->Lq = h.Lq.data();
+  q->bx_fold = h.bx_fold.data(); q->bh_fold = h.bh_fold.data();
+  if (h.projection()) {
+    q->Wpq = h.Wpq.data(); q->qbp = h.qbp.data(); q->bp_fold = h.bp_fold.data();
+  }
+  return LSTM_INT_OK;
+}
+
+size_t lstm_int_workspace_bytes(const lstm_int_model *m, int32_t T, int32_t B) {
+  if (!m || T < 0 || B < 0 || m->host.empty()) return 0;
+  if (T == 0 || B == 0) return 256;
+  return plan_workspace(m, T, B).total;
+}
+
+int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32_t B, int8_t *y,
+                     int8_t *h_state, int16_t *c_state, void *workspace, size_t workspace_bytes,
+                     void *hip_stream, const lstm_int_trace *trace) {
+  lstm_int_model *m = const_cast<lstm_int_model *>(cm);  // profiling counters only
+  if (!m || T < 0 || B < 0) return LSTM_INT_E_INVALID_ARG;
+  if (m->device < 0) return LSTM_INT_E_DEVICE;
+  if (T == 0 || B == 0) return LSTM_INT_OK;
+  if (!x || !y || !workspace) return LSTM_INT_E_INVALID_ARG;
+  const int L = (int)m->host.size();
+  if (trace && (trace->layer < 0 || trace->layer >= L)) return LSTM_INT_E_INVALID_ARG;
+  if ((int64_t)T * B > (int64_t)1 << 30) return LSTM_INT_E_UNSUPPORTED;
+  const Workspace ws = plan_workspace(m, T, B);
+  if (workspace_bytes < ws.total || (reinterpret_cast<uintptr_t>(workspace) & 255))
+    return LSTM_INT_E_WORKSPACE;
+  if (hipSetDevice(m->device) != hipSuccess) return LSTM_INT_E_DEVICE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  uint8_t *wsb = static_cast<uint8_t *>(workspace);
+  int16_t *tx = reinterpret_cast<int16_t *>(wsb + ws.tx);
+  int16_t *th = reinterpret_cast<int16_t *>(wsb + ws.th);
+  int8_t *mbuf = reinterpret_cast<int8_t *>(wsb + ws.mbuf);
+  int16_t *c = reinterpret_cast<int16_t *>(wsb + ws.c);
+  int8_t *h0 = reinterpret_cast<int8_t *>(wsb + ws.h0);
+  const int TB = T * B;
+
+  // layer 0 reads x in place when its rows are already 64-byte multiples
+  const int8_t *in = x;
+  int ld_in = m->host[0].I;
+  if ((m->host[0].I & 63) || (reinterpret_cast<uintptr_t>(x) & 15)) {
+    Timed t(m->prof, s, LSTM_INT_K_OTHER);
+    int8_t *xp = reinterpret_cast<int8_t *>(wsb + ws.xpad);
+    launch_copy_rows_i8(s, x, m->host[0].I, xp, m->dev[0].Ipad, TB, m->host[0].I, 0);
+    in = xp;
+    ld_in = m->dev[0].Ipad;
+  }
+
+  size_t h_off = 0, c_off = 0;
+  for (int l = 0; l < L; ++l) {
+    const LayerHost &h = m->host[l];
+    const LayerDev &d = m->dev[l];
+    const bool last = l == L - 1, proj = h.projection();
+    const lstm_int_trace *tr = (trace && trace->layer == l) ? trace : nullptr;
+    int8_t *out = reinterpret_cast<int8_t *>(wsb + ws.out[l & 1]);
+    const size_t step_out = (size_t)B * d.Hpad;
+
+    {  // initial state: given, or real 0 (q = zp_h) and c = 0
+      Timed t(m->prof, s, LSTM_INT_K_OTHER);
+      if (h_state)
+        launch_copy_rows_i8(s, h_state + h_off, h.H, h0, d.Hpad, B, h.H, 0);
+      else
+        launch_fill_rows_i8(s, h0, d.Hpad, B, h.H, h.zp_h, 0);
+      if (c_state)
+        launch_copy_i16(s, c_state + c_off, c, (int64_t)B * h.N);
+      else
+        launch_fill_i16(s, c, (int64_t)B * h.N, 0);
+    }
+    {  // W x for every (t, b) at once: it does not depend on t-1 (eqs. 1-5)
+      Timed t(m->prof, s, LSTM_INT_K_INPUT_GEMM);
+      launch_gemm_i16(s, in, ld_in, TB, d.W, d.Ipad, d.GN, d.bx, d.rq_x, tx, d.GN);
+    }
+    if (tr && tr->tx) launch_scatter_gates(s, tx, tr->tx, TB, h.G, h.N);
+
+    for (int t = 0; t < T; ++t) {
+      const int8_t *hprev = t == 0 ? h0 : out + (size_t)(t - 1) * step_out;
+      int8_t *hout = out + (size_t)t * step_out;
+      {
+        Timed tm(m->prof, s, LSTM_INT_K_RECURRENT);
+        launch_gemm_i16(s, hprev, d.Hpad, B, d.R, d.Hpad, d.GN, d.bh, d.rq_h, th, d.GN);
+      }
+      const size_t tg = (size_t)t * B * 4 * h.N, tn = (size_t)t * B * h.N;
+      if (tr && tr->th) launch_scatter_gates(s, th, tr->th + tg, B, h.G, h.N);
+      CellArgs a;
+      a.B = B; a.N = h.N; a.G = h.G; a.flags = (int32_t)h.flags; a.m_c = h.m_c;
+      a.tx = tx + (size_t)t * B * d.GN;
+      a.th = th;
+      a.c = c;
+      a.Pq = d.Pq; a.Lq = d.Lq; a.qb = d.qb;
+      for (int j = 0; j < 3; ++j) { a.Mc[j] = h.Mc[j]; a.rc[j] = 31 - h.ec[j]; }
+      for (int g = 0; g < 4; ++g) { a.Mln[g] = h.Mln[g]; a.rln[g] = 31 - h.eln[g]; }
+      a.Mm = h.Mm; a.rm = 31 - h.em; a.zp_m = h.zp_m;
+      a.sig_tab = m->sig3; a.tanh_tab = m->tanh3; a.tanhc_tab = d.tanhc;
+      a.m_out = proj ? mbuf : hout;
+      a.ld_m = proj ? d.Npad : d.Hpad;
+      a.m_out2 = (!proj && last) ? y + (size_t)t * B * h.H : nullptr;
+      a.ld_m2 = h.H;
+      a.tr_g = tr && tr->g ? tr->g + tg : nullptr;
+      a.tr_ln = tr && tr->ln ? tr->ln + tg : nullptr;
+      a.tr_act = tr && tr->act ? tr->act + tg : nullptr;
+      a.tr_c = tr && tr->c ? tr->c + tn : nullptr;
+      a.tr_m = tr && tr->m ? tr->m + tn : nullptr;
+      {
+        Timed tm(m->prof, s, LSTM_INT_K_CELL);
+        launch_cell(s, a);
+      }
+      if (proj) {
+        Timed tm(m->prof, s, LSTM_INT_K_PROJECTION);
+        launch_gemm_i8(s, mbuf, d.Npad, B, d.Wproj, d.Npad, h.H, d.bp, d.rq_p, hout, d.Hpad,
+                       last ? y + (size_t)t * B * h.H : nullptr, h.H);
+      }
+    }
+    {
+      Timed t(m->prof, s, LSTM_INT_K_OTHER);
+      if (tr && tr->h) launch_copy_rows_i8(s, out, d.Hpad, tr->h, h.H, TB, h.H, 0);
+      if (h_state)
+        launch_copy_rows_i8(s, out + (size_t)(T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
+                            h.H, 0);
+      if (c_state) launch_copy_i16(s, c, c_state + c_off, (int64_t)B * h.N);
+    }
+    h_off += (size_t)B * h.H;
+    c_off += (size_t)B * h.N;
+    in = out;
+    ld_in = d.Hpad;
+  }
+  return hipGetLastError() == hipSuccess ? LSTM_INT_OK : LSTM_INT_E_DEVICE;
+}
+
+int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
+  if (!m || !key) return LSTM_INT_E_INVALID_ARG;
+  if (!strcmp(key, "path")) {
+    if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
+    m->path = (int)value;
+    return LSTM_INT_OK;
+  }
+  return LSTM_INT_E_INVALID_ARG;
+}
+
+int lstm_int_profile_begin(lstm_int_model *m) {
+  if (!m) return LSTM_INT_E_INVALID_ARG;
+  if (m->device < 0) return LSTM_INT_E_DEVICE;
+  if (hipSetDevice(m->device) != hipSuccess) return LSTM_INT_E_DEVICE;
+  Profile &p = m->prof;
+  const size_t pairs = 1 << 14;
+  if (p.ev.empty()) {
+    p.ev.resize(2 * pairs);
+    p.cls.resize(pairs);
+    for (auto &e : p.ev)
+      if (hipEventCreate(&e) != hipSuccess) return LSTM_INT_E_DEVICE;
+  }
+  p.used = 0;
+  p.on = true;
+  return LSTM_INT_OK;
+}
+
+int lstm_int_profile_end(lstm_int_model *m, int64_t launches[LSTM_INT_K_COUNT],
+                         double total_ms[LSTM_INT_K_COUNT]) {
+  if (!m || !launches || !total_ms) return LSTM_INT_E_INVALID_ARG;
+  Profile &p = m->prof;
+  if (!p.on) return LSTM_INT_E_INVALID_ARG;
+  p.on = false;
+  for (int k = 0; k < LSTM_INT_K_COUNT; ++k) {
+    launches[k] = 0;
+    total_ms[k] = 0.0;
+  }
+  if (hipStreamSynchronize(p.stream) != hipSuccess) return LSTM_INT_E_DEVICE;
+  for (size_t i = 0; i < p.used; ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, p.ev[2 * i], p.ev[2 * i + 1]) != hipSuccess)
+      return LSTM_INT_E_DEVICE;
+    launches[p.cls[i]] += 1;
+    total_ms[p.cls[i]] += ms;
+  }
+  return LSTM_INT_OK;
+}
+
+void lstm_int_destroy(lstm_int_model *m) {
+  if (!m) return;
+  if (m->device >= 0) {
+    (void)hipSetDevice(m->device);
+    for (auto &e : m->prof.ev)
+      if (e) (void)hipEventDestroy(e);
+    if (m->arena) (void)hipFree(m->arena);
+  }
+  delete m;
+}
+
+const char *lstm_int_strerror(int code) {
+  switch (code) {
+    case LSTM_INT_OK: return "ok";
+    case LSTM_INT_E_INVALID_ARG: return "invalid argument";
+    case LSTM_INT_E_UNSUPPORTED: return "outside the supported limits";
+    case LSTM_INT_E_BAD_RANGE: return "bad range or non-finite parameter";
+    case LSTM_INT_E_OUT_OF_MEMORY: return "out of memory";
+    case LSTM_INT_E_DEVICE: return "HIP device error or host-only model";
+    case LSTM_INT_E_WORKSPACE: return "workspace too small or misaligned";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

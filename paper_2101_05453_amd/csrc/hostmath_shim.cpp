@@ -1,0 +1,38 @@
+// Host-only C entry points onto lstm_int_math.h, so that the arithmetic the
+// kernels run can be checked exhaustively on a CPU.  Not part of
+// liblstm_int.so.
+#include "lstm_int_math.h"
+#include "model.h"
+
+using namespace lstm_int;
+
+extern "C" {
+
+int32_t hm_rescale(int32_t a, int32_t M, int32_t r) { return rescale(a, M, r); }
+int32_t hm_rescale_hi(int32_t a, int32_t M, int32_t r) { return rescale_hi(a, M, r); }
+int64_t hm_isqrt(int64_t v) { return isqrt_u52(v); }
+
+// layer norm of one row through ln_row / ln_apply
+void hm_layernorm(const int16_t *q, int32_t n, const int16_t *qL, const int32_t *qb, int32_t M,
+                  int32_t r, int16_t *out) {
+  int64_t s1 = 0, s2 = 0;
+  for (int i = 0; i < n; ++i) {
+    s1 += q[i];
+    s2 += (int64_t)q[i] * q[i];
+  }
+  const LnRow row = ln_row(s1, s2, n);
+  for (int i = 0; i < n; ++i) out[i] = (int16_t)ln_apply(q[i], row, qL[i], qb[i], M, r);
+}
+
+void hm_sigmoid_table(int m, uint16_t *tab) { fill_sigmoid_table(m, tab); }
+void hm_tanh_table(int m, uint16_t *tab) { fill_tanh_table(m, tab); }
+int32_t hm_sigmoid(const uint16_t *tab, int32_t x) { return sigmoid_from_table(tab, x); }
+int32_t hm_tanh(const uint16_t *tab, int32_t x) { return tanh_from_table(tab, x); }
+int32_t hm_cifg(int32_t f) { return cifg_input_gate(f); }
+int32_t hm_cell_update(int32_t i, int32_t z, int32_t f, int32_t c, int32_t m_c) {
+  return cell_update(i, z, f, c, m_c);
+}
+int32_t hm_hidden(int32_t o, int32_t tc, int32_t M, int32_t r, int32_t zp) {
+  return hidden_state(o, tc, M, r, zp);
+}
+}

@@ -1,0 +1,410 @@
+// HIP kernels of the integer LSTM cell step for gfx950 (MI355X, wave64).
+//
+//   gemm_i8_kernel  int8 x int8 -> int32 on the 16x16x64 int8 MFMA, with the
+//                   requantization of Secs. 3.2.4-3.2.8 fused into the
+//                   epilogue (bias with folded zero point, Sec. 6).  Used for
+//                   the input term W x over all T*B rows at once, for the
+//                   recurrent term R h of one step, and for the projection.
+//   cell_kernel     everything between the gate matmuls and the hidden state
+//                   for one batch row per workgroup (layer-norm statistics by
+//                   wavefront reductions).
+#include "kernels.h"
+
+#include "lstm_int_math.h"
+
+namespace lstm_int {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// int8 GEMM.  The weight tile is the MFMA's first operand and the activation
+// tile its second, so a lane ends up with four consecutive output columns
+// (weight rows) of one activation row: D[4*(lane/16)+j][lane%16].
+// Both operands are K-contiguous in memory, which is exactly what the MFMA
+// wants from each lane (16 consecutive k bytes of one row); the same k
+// permutation applies to both, so the dot products do not depend on it.
+// ---------------------------------------------------------------------------
+constexpr int kLdsRow = 80;  // 64 data bytes + 16 pad: conflict-free b128 reads
+
+template <int BM, int BN, int WM, int WN, bool OUT8>
+__global__ __launch_bounds__(256) void gemm_i8_kernel(
+    const int8_t *__restrict__ A, int lda, int M, const int8_t *__restrict__ W, int kpad,
+    int ncols, const int32_t *__restrict__ bias, Requant rq, void *__restrict__ out, int ldc,
+    int8_t *__restrict__ out2, int ldc2) {
+  static_assert(WM * WN == 4, "four waves per workgroup");
+  constexpr int TM = BM / WM, TN = BN / WN;
+  constexpr int MI = TM / 16, NI = TN / 16;
+  static_assert(MI >= 1 && NI >= 1 && TM % 16 == 0 && TN % 16 == 0, "tile shape");
+  constexpr int XCH = BM * 4, WCH = BN * 4;  // 16-byte chunks per k-tile
+  constexpr int XPT = (XCH + 255) / 256, WPT = (WCH + 255) / 256;
+
+  __shared__ __attribute__((aligned(16))) int8_t Xs[BM * kLdsRow];
+  __shared__ __attribute__((aligned(16))) int8_t Ws[BN * kLdsRow];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int row_base = blockIdx.x * BM;  // activation rows
+  const int col_base = blockIdx.y * BN;  // weight rows = output columns
+
+  v4i acc[NI][MI];
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) acc[ni][mi] = v4i{0, 0, 0, 0};
+
+  int4 xreg[XPT], wreg[WPT];
+  const int KT = kpad >> 6;
+
+  auto load_tiles = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < XPT; ++i) {
+      const int c = tid + i * 256;
+      if (XCH % 256 == 0 || c < XCH) {
+        int r = row_base + (c >> 2);
+        r = r < M ? r : M - 1;  // rows past the end repeat the last one; never stored
+        xreg[i] = *reinterpret_cast<const int4 *>(A + (size_t)r * lda + (kt << 6) + ((c & 3) << 4));
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+      const int c = tid + i * 256;
+      if (WCH % 256 == 0 || c < WCH)
+        wreg[i] = *reinterpret_cast<const int4 *>(W + (size_t)(col_base + (c >> 2)) * kpad +
+                                                  (kt << 6) + ((c & 3) << 4));
+    }
+  };
+  auto store_tiles = [&]() {
+#pragma unroll
+    for (int i = 0; i < XPT; ++i) {
+      const int c = tid + i * 256;
+      if (XCH % 256 == 0 || c < XCH)
+        *reinterpret_cast<int4 *>(Xs + (c >> 2) * kLdsRow + ((c & 3) << 4)) = xreg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+      const int c = tid + i * 256;
+      if (WCH % 256 == 0 || c < WCH)
+        *reinterpret_cast<int4 *>(Ws + (c >> 2) * kLdsRow + ((c & 3) << 4)) = wreg[i];
+    }
+  };
+
+  load_tiles(0);
+  for (int kt = 0; kt < KT; ++kt) {
+    store_tiles();
+    __syncthreads();
+    if (kt + 1 < KT) load_tiles(kt + 1);  // in flight while the MFMAs run
+    v4i xf[MI], wf[NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+      xf[mi] = *reinterpret_cast<const v4i *>(Xs + (wm * TM + mi * 16 + (lane & 15)) * kLdsRow +
+                                              ((lane >> 4) << 4));
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+      wf[ni] = *reinterpret_cast<const v4i *>(Ws + (wn * TN + ni * 16 + (lane & 15)) * kLdsRow +
+                                              ((lane >> 4) << 4));
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+        acc[ni][mi] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
+    __syncthreads();
+  }
+
+  // epilogue: + bias, rescale, saturate, store
+  const int cpg = rq.cols_per_gate;
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) {
+    const int n0 = col_base + wn * TN + ni * 16 + ((lane >> 4) << 2);
+    const int4 b4 = *reinterpret_cast<const int4 *>(bias + n0);  // bias is padded like W
+    const int32_t bv[4] = {b4.x, b4.y, b4.z, b4.w};
+    int32_t Mg[4], rg[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + j;
+      const int g = (n >= cpg) + (n >= 2 * cpg) + (n >= 3 * cpg);
+      Mg[j] = rq.M[g];
+      rg[j] = rq.r[g];
+    }
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int m = row_base + wm * TM + mi * 16 + (lane & 15);
+      int32_t v[4];
+      if (rq.all_hi) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = rescale_hi(acc[ni][mi][j] + bv[j], Mg[j], rg[j]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = rescale(acc[ni][mi][j] + bv[j], Mg[j], rg[j]);
+      }
+      if (m >= M) continue;
+      if (OUT8) {
+        int8_t *o = reinterpret_cast<int8_t *>(out) + (size_t)m * ldc;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (n0 + j < ncols) {
+            const int8_t q = (int8_t)sat8(v[j] + rq.zp);
+            o[n0 + j] = q;
+            if (out2) out2[(size_t)m * ldc2 + n0 + j] = q;
+          }
+        }
+      } else {
+        int16_t *o = reinterpret_cast<int16_t *>(out) + (size_t)m * ldc;
+        if (n0 + 3 < ncols && (ldc & 3) == 0) {
+          short4 pk;
+          pk.x = (short)sat16(v[0]);
+          pk.y = (short)sat16(v[1]);
+          pk.z = (short)sat16(v[2]);
+          pk.w = (short)sat16(v[3]);
+          *reinterpret_cast<short4 *>(o + n0) = pk;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (n0 + j < ncols) o[n0 + j] = (int16_t)sat16(v[j]);
+        }
+      }
+    }
+  }
+}
+
+template <bool OUT8>
+static void launch_gemm(hipStream_t s, const int8_t *A, int lda, int M, const int8_t *W, int kpad,
+                        int ncols, const int32_t *bias, const Requant &rq, void *out, int ldc,
+                        int8_t *out2, int ldc2) {
+  if (M <= 0 || ncols <= 0) return;
+  const int ncols_pad = (ncols + 127) / 128 * 128;
+  if (M > 256) {
+    dim3 grid((M + 127) / 128, ncols_pad / 128);
+    hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, OUT8>), grid, dim3(256), 0, s, A, lda, M, W,
+                       kpad, ncols, bias, rq, out, ldc, out2, ldc2);
+  } else if (M > 32) {
+    dim3 grid((M + 63) / 64, ncols_pad / 64);
+    hipLaunchKernelGGL((gemm_i8_kernel<64, 64, 2, 2, OUT8>), grid, dim3(256), 0, s, A, lda, M, W,
+                       kpad, ncols, bias, rq, out, ldc, out2, ldc2);
+  } else {
+    dim3 grid((M + 31) / 32, ncols_pad / 128);
+    hipLaunchKernelGGL((gemm_i8_kernel<32, 128, 1, 4, OUT8>), grid, dim3(256), 0, s, A, lda, M, W,
+                       kpad, ncols, bias, rq, out, ldc, out2, ldc2);
+  }
+}
+
+void launch_gemm_i16(hipStream_t s, const int8_t *A, int lda, int M, const int8_t *W, int kpad,
+                     int ncols, const int32_t *bias, const Requant &rq, int16_t *out, int ldc) {
+  launch_gemm<false>(s, A, lda, M, W, kpad, ncols, bias, rq, out, ldc, nullptr, 0);
+}
+
+void launch_gemm_i8(hipStream_t s, const int8_t *A, int lda, int M, const int8_t *W, int kpad,
+                    int ncols, const int32_t *bias, const Requant &rq, int8_t *out, int ldc,
+                    int8_t *out2, int ldc2) {
+  launch_gemm<true>(s, A, lda, M, W, kpad, ncols, bias, rq, out, ldc, out2, ldc2);
+}
+
+// ---------------------------------------------------------------------------
+// Cell kernel: one workgroup (256 threads) per batch row.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;
+}
+
+// Sums (s1, s2) over the workgroup; the result is returned to every thread.
+__device__ __forceinline__ void block_sum2(int64_t &s1, int64_t &s2, int64_t *red /*[8]*/) {
+  s1 = wave_sum_i64(s1);
+  s2 = wave_sum_i64(s2);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();  // red may still be read from the previous use
+  if (lane == 0) {
+    red[wave] = s1;
+    red[4 + wave] = s2;
+  }
+  __syncthreads();
+  s1 = red[0] + red[1] + red[2] + red[3];
+  s2 = red[4] + red[5] + red[6] + red[7];
+}
+
+__global__ __launch_bounds__(256) void cell_kernel(CellArgs a) {
+  extern __shared__ __attribute__((aligned(16))) int16_t gs[];  // [4][N] with layer norm
+  __shared__ int64_t red[8];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int N = a.N, G = a.G, first = 4 - G;
+  const bool cifg = a.flags & 1u, ph = a.flags & 2u, ln = a.flags & 4u;
+  const int16_t *tx = a.tx + (size_t)b * G * N;
+  const int16_t *th = a.th + (size_t)b * G * N;
+  int16_t *c = a.c + (size_t)b * N;
+  const int32_t glo = ln ? -32767 : -32768;
+
+  // gate sum of gate slot g at cell n (Secs. 3.2.4 / 3.2.5); cval is the cell
+  // state the peephole reads (c^{t-1} for i and f, c^t for o)
+  auto gate_sum = [&](int g, int n, int32_t cval) -> int32_t {
+    const int col = (g - first) * N + n;
+    int32_t v = (int32_t)tx[col] + (int32_t)th[col];
+    if (ph && g != 2) {
+      const int j = g == 3 ? 2 : g;
+      v += sat16(rescale((int32_t)a.Pq[j * N + n] * cval, a.Mc[j], a.rc[j]));
+    }
+    return clamp_i32(v, glo, 32767);
+  };
+  auto trace16 = [&](int16_t *base, int g, int n, int32_t v) {
+    if (base) base[((size_t)b * 4 + g) * N + n] = (int16_t)v;
+  };
+
+  if (!ln) {
+    for (int n = tid; n < N; n += 256) {
+      const int32_t cold = c[n];
+      int32_t act[4];
+      for (int g = first; g < 3; ++g) {
+        const int32_t v = gate_sum(g, n, cold);
+        trace16(a.tr_g, g, n, v);
+        act[g] = g == 2 ? tanh_from_table(a.tanh_tab, v) : sigmoid_from_table(a.sig_tab, v);
+      }
+      if (cifg) act[0] = cifg_input_gate(act[1]);
+      const int32_t cnew = cell_update(act[0], act[2], act[1], cold, a.m_c);
+      const int32_t vo = gate_sum(3, n, cnew);
+      trace16(a.tr_g, 3, n, vo);
+      act[3] = sigmoid_from_table(a.sig_tab, vo);
+      const int32_t mq = hidden_state(act[3], tanh_from_table(a.tanhc_tab, cnew), a.Mm, a.rm, a.zp_m);
+      c[n] = (int16_t)cnew;
+      a.m_out[(size_t)b * a.ld_m + n] = (int8_t)mq;
+      if (a.m_out2) a.m_out2[(size_t)b * a.ld_m2 + n] = (int8_t)mq;
+      for (int g = 0; g < 4; ++g) trace16(a.tr_act, g, n, act[g]);
+      if (a.tr_c) a.tr_c[(size_t)b * N + n] = (int16_t)cnew;
+      if (a.tr_m) a.tr_m[(size_t)b * N + n] = (int8_t)mq;
+    }
+    return;
+  }
+
+  // ---- layer norm: statistics over the N cells of each gate row (Sec. 3.2.6)
+  __shared__ LnRow rows[4];
+  const int last_early = ph ? 2 : 3;  // with a peephole, o waits for c^t
+  for (int g = first; g <= last_early; ++g) {
+    int64_t s1 = 0, s2 = 0;
+    for (int n = tid; n < N; n += 256) {
+      const int32_t v = gate_sum(g, n, c[n]);
+      gs[g * N + n] = (int16_t)v;
+      trace16(a.tr_g, g, n, v);
+      s1 += v;
+      s2 += (int64_t)v * v;
+    }
+    block_sum2(s1, s2, red);
+    if (tid == 0) rows[g] = ln_row(s1, s2, N);
+  }
+  __syncthreads();
+  auto normed = [&](int g, int n) -> int32_t {
+    const int32_t v = ln_apply(gs[g * N + n], rows[g], a.Lq[g * N + n], a.qb[g * N + n], a.Mln[g],
+                               a.rln[g]);
+    trace16(a.tr_ln, g, n, v);
+    return v;
+  };
+  {
+    int64_t s1 = 0, s2 = 0;
+    for (int n = tid; n < N; n += 256) {
+      int32_t i = 0;
+      if (!cifg) i = sigmoid_from_table(a.sig_tab, normed(0, n));
+      const int32_t f = sigmoid_from_table(a.sig_tab, normed(1, n));
+      const int32_t z = tanh_from_table(a.tanh_tab, normed(2, n));
+      if (cifg) i = cifg_input_gate(f);
+      const int32_t cnew = cell_update(i, z, f, c[n], a.m_c);
+      c[n] = (int16_t)cnew;  // read back below by this same thread only
+      trace16(a.tr_act, 0, n, i);
+      trace16(a.tr_act, 1, n, f);
+      trace16(a.tr_act, 2, n, z);
+      if (a.tr_c) a.tr_c[(size_t)b * N + n] = (int16_t)cnew;
+      if (ph) {
+        const int32_t v = gate_sum(3, n, cnew);
+        gs[3 * N + n] = (int16_t)v;
+        trace16(a.tr_g, 3, n, v);
+        s1 += v;
+        s2 += (int64_t)v * v;
+      }
+    }
+    if (ph) {
+      block_sum2(s1, s2, red);
+      if (tid == 0) rows[3] = ln_row(s1, s2, N);
+      __syncthreads();
+    }
+  }
+  for (int n = tid; n < N; n += 256) {
+    const int32_t o = sigmoid_from_table(a.sig_tab, normed(3, n));
+    const int32_t mq = hidden_state(o, tanh_from_table(a.tanhc_tab, c[n]), a.Mm, a.rm, a.zp_m);
+    a.m_out[(size_t)b * a.ld_m + n] = (int8_t)mq;
+    if (a.m_out2) a.m_out2[(size_t)b * a.ld_m2 + n] = (int8_t)mq;
+    trace16(a.tr_act, 3, n, o);
+    if (a.tr_m) a.tr_m[(size_t)b * N + n] = (int8_t)mq;
+  }
+}
+
+void launch_cell(hipStream_t s, const CellArgs &a) {
+  if (a.B <= 0) return;
+  const size_t lds = (a.flags & 4u) ? (size_t)4 * a.N * sizeof(int16_t) : 0;
+  hipLaunchKernelGGL(cell_kernel, dim3(a.B), dim3(256), lds, s, a);
+}
+
+// ---------------------------------------------------------------------------
+// Small data-movement kernels
+// ---------------------------------------------------------------------------
+__global__ void copy_rows_i8_kernel(const int8_t *src, int ld_src, int8_t *dst, int ld_dst, int rows,
+                                    int cols, int value, int fill) {
+  const int64_t total = (int64_t)rows * ld_dst;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = i / ld_dst;
+    const int col = (int)(i - r * ld_dst);
+    dst[i] = col < cols ? (src ? src[r * ld_src + col] : (int8_t)value) : (int8_t)fill;
+  }
+}
+
+static int grid_for(int64_t total) {
+  int64_t g = (total + 255) / 256;
+  return (int)(g < 1 ? 1 : (g > 4096 ? 4096 : g));
+}
+
+void launch_copy_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *dst, int ld_dst,
+                         int rows, int cols, int fill) {
+  if (rows <= 0) return;
+  hipLaunchKernelGGL(copy_rows_i8_kernel, dim3(grid_for((int64_t)rows * ld_dst)), dim3(256), 0, s,
+                     src, ld_src, dst, ld_dst, rows, cols, 0, fill);
+}
+
+void launch_fill_rows_i8(hipStream_t s, int8_t *dst, int ld_dst, int rows, int cols, int value,
+                         int fill) {
+  if (rows <= 0) return;
+  hipLaunchKernelGGL(copy_rows_i8_kernel, dim3(grid_for((int64_t)rows * ld_dst)), dim3(256), 0, s,
+                     (const int8_t *)nullptr, 0, dst, ld_dst, rows, cols, value, fill);
+}
+
+__global__ void copy_i16_kernel(const int16_t *src, int16_t *dst, int64_t n, int value) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n;
+       i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = src ? src[i] : (int16_t)value;
+}
+
+void launch_copy_i16(hipStream_t s, const int16_t *src, int16_t *dst, int64_t n) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(copy_i16_kernel, dim3(grid_for(n)), dim3(256), 0, s, src, dst, n, 0);
+}
+
+void launch_fill_i16(hipStream_t s, int16_t *dst, int64_t n, int value) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(copy_i16_kernel, dim3(grid_for(n)), dim3(256), 0, s, (const int16_t *)nullptr,
+                     dst, n, value);
+}
+
+__global__ void scatter_gates_kernel(const int16_t *src, int16_t *dst, int rows, int G, int N) {
+  const int64_t per_row = (int64_t)G * N, total = rows * per_row;
+  const int first = 4 - G;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = i / per_row;
+    const int64_t col = i - r * per_row;  // gi * N + n
+    dst[r * 4 * N + (int64_t)first * N + col] = src[i];
+  }
+}
+
+void launch_scatter_gates(hipStream_t s, const int16_t *src, int16_t *dst, int rows, int G, int N) {
+  if (rows <= 0) return;
+  hipLaunchKernelGGL(scatter_gates_kernel, dim3(grid_for((int64_t)rows * G * N)), dim3(256), 0, s,
+                     src, dst, rows, G, N);
+}
+
+}  // namespace lstm_int

@@ -1,0 +1,144 @@
+"""GPU parity: the HIP library against the CPU oracle, bit for bit, through
+the C ABI.  Small shapes (several tiles, ragged tails, every variant) compare
+every intermediate integer tensor of every layer and step; the benchmark
+configurations C3-C5 run at full size on the GPU and are compared on sampled
+batch rows (rows never interact, so the oracle computes exactly those rows)."""
+import numpy as np
+import pytest
+
+import lstm_workloads as wl
+from parity_util import assert_equal, prepare_both, run_and_compare
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = [0, wl.LAYER_NORM, wl.PEEPHOLE, wl.PROJECTION, wl.CIFG,
+            wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION, wl.CIFG | wl.LAYER_NORM,
+            wl.CIFG | wl.PEEPHOLE | wl.PROJECTION,
+            wl.CIFG | wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION]
+
+
+@pytest.fixture(scope="module", autouse=True)
+def gpu():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2101_05453_amd import binding
+
+    binding.lib()  # fails loudly if liblstm_int.so is not built
+    yield
+
+
+@pytest.mark.parametrize("flags", VARIANTS)
+def test_variants_every_tensor(orc, flags):
+    """Ragged everything: I = 72 and H = 136 are not multiples of 64, N = 200
+    is not a multiple of the 256-thread row loop, B = 37 straddles tiles."""
+    H = 136 if flags & wl.PROJECTION else 200
+    print(f"variant flags={flags}", flush=True)
+    layers, x = wl.make_custom([72, H], 200, H, flags, 37, 5, seed=flags + 11, weight_param=0.08)
+    run_and_compare(orc, layers, x, f"variant{flags}")
+
+
+@pytest.mark.parametrize("flags", [0, wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION, wl.CIFG | wl.LAYER_NORM])
+def test_odd_sizes(orc, flags):
+    """N = 203 makes G*N odd (scalar int16 stores), I = 7, B = 1."""
+    H = 29 if flags & wl.PROJECTION else 203
+    print(f"odd flags={flags}", flush=True)
+    layers, x = wl.make_custom([7], 203, H, flags, 1, 4, seed=flags + 50, weight_param=0.2)
+    run_and_compare(orc, layers, x, f"odd{flags}")
+
+
+def test_c1_full(orc):
+    layers, x = wl.make_workload("C1")
+    run_and_compare(orc, layers, x, "C1")
+
+
+def test_c2_full(orc):
+    layers, x = wl.make_workload("C2")
+    run_and_compare(orc, layers, x, "C2", trace=True)
+
+
+@pytest.mark.parametrize("name,rows", [
+    ("C3", [0, 63, 64, 127]),
+    ("C4", [0, 100, 255]),
+    ("C5", [0, 511, 640, 1023]),
+])
+def test_benchmark_configs_full_size_sampled_rows(orc, name, rows):
+    print(f"{name} full size, oracle on rows {rows}", flush=True)
+    layers, x = wl.make_workload(name)
+    run_and_compare(orc, layers, x, name, trace=False, rows=rows)
+
+
+def test_split_sequence_carries_state(orc):
+    import torch
+
+    layers, x = wl.make_custom([40, 24], 96, 24, wl.LAYER_NORM | wl.PROJECTION, 9, 12, seed=77)
+    lib_model, orc_model, xq = prepare_both(orc, layers, x)
+    B = xq.shape[1]
+    dims = lib_model.dims()
+    xd = torch.from_numpy(xq).cuda()
+    y = lib_model.forward(xd)
+    hs = torch.cat([torch.full((B * d[2],), lib_model.get_quant(l)["zp_h"], dtype=torch.int8)
+                    for l, d in enumerate(dims)]).cuda()
+    cs = torch.zeros(sum(B * d[1] for d in dims), dtype=torch.int16).cuda()
+    ya = lib_model.forward(xd[:5].contiguous(), h_state=hs, c_state=cs)
+    yb = lib_model.forward(xd[5:].contiguous(), h_state=hs, c_state=cs)
+    torch.cuda.synchronize()
+    assert_equal("split", torch.cat([ya, yb]).cpu().numpy(), y.cpu().numpy())
+    assert_equal("split vs oracle", y.cpu().numpy(), orc.forward(orc_model, xq))
+
+
+def test_saturating_ranges(orc):
+    """Calibration ranges far too small: every clamp on the path is hit."""
+    import torch
+
+    layers, x = wl.make_custom([64], 128, 64, wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION, 8, 6, seed=5,
+                               weight_param=0.3)
+    from paper_2101_05453_amd import binding, calibration
+
+    calibration.collect_statistics(layers, x)
+    s = layers[0]
+    s.g_absmax = [v * 0.05 for v in s.g_absmax]
+    s.m_min, s.m_max, s.h_min, s.h_max, s.c_absmax = -0.02, 0.03, -0.05, 0.02, 0.4
+    lib_model = binding.prepare(layers, device=0)
+    orc_model = orc.prepare(layers)
+    q0 = lib_model.get_quant(0)
+    xq = calibration.quantize_input(x * 4, q0["s_x"], q0["zp_x"])
+    y, gtr = lib_model.forward(torch.from_numpy(xq).cuda(), trace_layer=0)
+    torch.cuda.synchronize()
+    yo, otr = orc.forward(orc_model, xq, trace_layer=0)
+    assert otr["g"].min() == -32767 and otr["g"].max() == 32767 and otr["m"].min() == -128 and otr["m"].max() == 127
+    assert_equal("sat.y", y.cpu().numpy(), yo)
+    for f in ("tx", "th", "g", "ln", "act", "c", "m", "h"):
+        assert_equal(f"sat.{f}", gtr[f].cpu().numpy(), otr[f])
+
+
+def test_empty_and_error_paths(orc):
+    import torch
+
+    from paper_2101_05453_amd import binding
+
+    layers, x = wl.make_custom([64], 64, 64, 0, 4, 3, seed=2)
+    lib_model, orc_model, xq = prepare_both(orc, layers, x)
+    xd = torch.from_numpy(xq).cuda()
+    assert lib_model.forward(xd[:0].contiguous()).shape == (0, 4, 64)
+    assert lib_model.forward(xd[:, :0].contiguous()).shape == (3, 0, 64)
+    ws = torch.empty(lib_model.workspace_bytes(3, 4) - 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.LstmIntError) as ei:
+        lib_model.forward(xd, workspace=ws)
+    assert ei.value.code == binding.E_WORKSPACE
+    # an input pointer that is not 16-byte aligned takes the padded-copy route
+    big = torch.zeros(xd.numel() + 16, dtype=torch.int8, device="cuda")
+    off = big[3:3 + xd.numel()].view(xd.shape)
+    off.copy_(xd)
+    y = lib_model.forward(off)
+    torch.cuda.synchronize()
+    assert_equal("unaligned", y.cpu().numpy(), orc.forward(orc_model, xq))
+
+
+def test_maximum_sizes(orc):
+    """Layer norm at its row limit N = 4096; accumulation depth 2^15."""
+    print("max sizes", flush=True)
+    layers, x = wl.make_custom([16], 4096, 4096, wl.LAYER_NORM, 2, 2, seed=8, weight_param=0.02)
+    run_and_compare(orc, layers, x, "ln4096", trace=True)
+    layers, x = wl.make_custom([32768], 16, 16, 0, 3, 2, seed=9, weight_param=0.01)
+    run_and_compare(orc, layers, x, "depth32768", trace=True)

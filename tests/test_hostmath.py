@@ -1,0 +1,122 @@
+"""The arithmetic the kernels run (csrc/lstm_int_math.h and the activation
+tables of prepare.cpp), compiled for the host, against the oracle: the same
+integers on exhaustive or adversarial ranges.  (The device build of the same
+header is covered by the GPU parity tests.)"""
+import ctypes as C
+import os
+import random
+
+import numpy as np
+import pytest
+
+from paper_2101_05453_amd import build as libbuild
+
+
+@pytest.fixture(scope="module")
+def hm():
+    if not os.path.exists(libbuild.HOSTMATH_LIB):
+        libbuild.build_hostmath()
+    L = C.CDLL(libbuild.HOSTMATH_LIB)
+    L.hm_isqrt.restype = C.c_int64
+    L.hm_isqrt.argtypes = [C.c_int64]
+    for f in ("hm_rescale", "hm_rescale_hi"):
+        getattr(L, f).restype = C.c_int32
+        getattr(L, f).argtypes = [C.c_int32] * 3
+    L.hm_layernorm.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    L.hm_sigmoid_table.argtypes = [C.c_int, C.c_void_p]
+    L.hm_tanh_table.argtypes = [C.c_int, C.c_void_p]
+    L.hm_sigmoid.argtypes = [C.c_void_p, C.c_int32]
+    L.hm_tanh.argtypes = [C.c_void_p, C.c_int32]
+    L.hm_cell_update.argtypes = [C.c_int32] * 5
+    L.hm_hidden.argtypes = [C.c_int32] * 5
+    return L
+
+
+def test_rescale_forms(orc, hm):
+    rnd = random.Random(0)
+    for _ in range(40000):
+        a = rnd.randrange(-2**31, 2**31)
+        M = rnd.randrange(2**30, 2**31)
+        e = rnd.randrange(-31, 31)
+        want = orc.rescale(a, M, e)
+        assert hm.hm_rescale(a, M, 31 - e) == want, (a, M, e)
+        if 31 - e >= 33:
+            assert hm.hm_rescale_hi(a, M, 31 - e) == want, (a, M, e)
+    for M in (2**30, 2**31 - 1, 1518500250):
+        for e in (-31, -2, -1, 0, 5, 30):
+            for a in list(range(-300, 300)) + [2**31 - 1, -2**31]:
+                assert hm.hm_rescale(a, M, 31 - e) == orc.rescale(a, M, e)
+                if 31 - e >= 33:
+                    assert hm.hm_rescale_hi(a, M, 31 - e) == orc.rescale(a, M, e)
+
+
+def test_isqrt(orc, hm):
+    rnd = random.Random(1)
+    vals = list(range(0, 5000)) + [rnd.randrange(0, 2**50) for _ in range(20000)]
+    vals += [r * r + d for r in (2**24, 2**25 - 1, 33554431) for d in (-1, 0, 1)]
+    for v in vals:
+        assert hm.hm_isqrt(v) == orc.isqrt(v), v
+
+
+@pytest.mark.parametrize("m", range(0, 9))
+def test_activation_tables_exhaustive(orc, hm, m):
+    sig = np.zeros(32769, np.uint16)
+    tnh = np.zeros(32769, np.uint16)
+    hm.hm_sigmoid_table(m, sig.ctypes.data)
+    hm.hm_tanh_table(m, tnh.ctypes.data)
+    for x in range(-32768, 32768):
+        assert hm.hm_sigmoid(sig.ctypes.data, x) == orc.int_sigmoid(x, m), (x, m)
+        assert hm.hm_tanh(tnh.ctypes.data, x) == orc.int_tanh(x, m), (x, m)
+
+
+def _ln_case(rng, n, kind):
+    if kind == "normal":
+        q = np.clip(rng.normal(rng.integers(-3000, 3000), rng.choice([3, 50, 2000, 12000]), size=n), -32767, 32767)
+    elif kind == "extreme":
+        q = rng.choice([-32767, 32767], size=n)
+    elif kind == "spike":
+        q = np.full(n, rng.integers(-32767, 32767))
+        q[rng.integers(0, n)] += rng.choice([-1, 1, 2, 500])
+        q = np.clip(q, -32767, 32767)
+    elif kind == "near_constant":
+        q = np.full(n, rng.integers(-32000, 32000)) + rng.integers(0, 2, size=n)
+    else:
+        q = np.full(n, rng.integers(-32767, 32767))
+    qL = rng.integers(-32767, 32768, size=n)
+    qb = rng.integers(-2**31 + 1, 2**31, size=n)
+    if kind == "extreme":
+        qL[:] = rng.choice([-32767, 32767], size=n)
+        qb[:] = rng.choice([-2**31 + 1, 2**31 - 1], size=n)
+    return q.astype(np.int16), qL.astype(np.int16), qb.astype(np.int32)
+
+
+def test_layernorm_matches_oracle(orc, hm):
+    rng = np.random.default_rng(5)
+    for trial in range(400):
+        n = int(rng.choice([1, 2, 3, 17, 64, 512, 1000, 2048, 4096]))
+        kind = ["normal", "extreme", "spike", "near_constant", "constant"][trial % 5]
+        q, qL, qb = _ln_case(rng, n, kind)
+        M, e = int(rng.integers(2**30, 2**31)), int(rng.integers(-12, 4))
+        want = orc.int_layernorm(q, qL, qb, M, e)
+        got = np.zeros(n, np.int16)
+        hm.hm_layernorm(q.ctypes.data, n, qL.ctypes.data, qb.ctypes.data, M, 31 - e, got.ctypes.data)
+        assert (got == want).all(), (trial, n, kind)
+
+
+def test_cell_update_and_hidden(orc, hm):
+    rnd = random.Random(3)
+    edge = [-32768, -32767, -1, 0, 1, 32767]
+    for m_c in range(0, 9):
+        cases = [(i, z, f, c) for i in (0, 1, 32767) for z in edge for f in (0, 1, 32767) for c in edge]
+        cases += [(rnd.randrange(0, 32768), rnd.randrange(-32768, 32768), rnd.randrange(0, 32768),
+                   rnd.randrange(-32768, 32768)) for _ in range(3000)]
+        for i, z, f, c in cases:
+            want = max(-32768, min(32767, orc.rsh_r(i * z, 15 + m_c) + orc.rsh_r(f * c, 15)))
+            assert hm.hm_cell_update(i, z, f, c, m_c) == want
+    for _ in range(5000):
+        o, tc = rnd.randrange(0, 32768), rnd.randrange(-32768, 32768)
+        M, e, zp = rnd.randrange(2**30, 2**31), rnd.randrange(-26, -18), rnd.randrange(-128, 128)
+        want = max(-128, min(127, orc.rescale(o * tc, M, e) + zp))
+        assert hm.hm_hidden(o, tc, M, 31 - e, zp) == want
+    for f in (0, 1, 16384, 32767):
+        assert hm.hm_cifg(f) == min(32768 - f, 32767)
