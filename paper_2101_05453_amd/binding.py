@@ -186,11 +186,14 @@ class Model:
         return d
 
     def dims(self):
+        if getattr(self, "_dims", None):
+            return self._dims
         out = []
         for l in range(self.num_layers):
             q = LayerQuant()
             _check(lib().lstm_int_get_quant(self._h, l, C.byref(q)), "lstm_int_get_quant")
             out.append((q.I, q.N, q.H))
+        self._dims = out
         return out
 
     # lstm_int_workspace_bytes
