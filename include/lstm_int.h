@@ -165,11 +165,39 @@ int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
 
 /*
  * Tuning knobs of the online phase; results never depend on them.
- *   "path": 0 = choose automatically, 1 = one launch per operation and step,
- *           2 = persistent recurrent kernel (weights resident on chip)
+ *   "path": 0 = choose per layer (default): the persistent recurrent kernel
+ *               where the layer shape allows it (N % 8 == 0, N <= 2048,
+ *               H <= 1024, batch within one launch, no trace of that layer),
+ *               otherwise one launch per operation and step;
+ *           1 = always one launch per operation and step;
+ *           2 = same as 0.
+ *   "spin_limit": polls after which a wait inside the persistent kernel gives
+ *           up (every workgroup then leaves the kernel and the status word of
+ *           lstm_int_device_status becomes nonzero).
+ *   "phase_timing": nonzero makes workgroup 0 of the persistent kernel add the
+ *           time it spends in each of its phases to 16 device counters
+ *           (diagnostics; read them with lstm_int_phase_ticks).
  * Unknown keys or values give LSTM_INT_E_INVALID_ARG.
  */
 int lstm_int_set_option(lstm_int_model *model, const char *key, int64_t value);
+
+/*
+ * Blocking read of the model's device status word: 0 = every persistent
+ * kernel so far ran to completion; nonzero = a wait gave up (1) or the
+ * workgroups of a group were not placed on one XCD (2), and the outputs of
+ * that call are not valid.  The word is sticky.  Synchronizes the device.
+ */
+int lstm_int_device_status(const lstm_int_model *model, int32_t *status);
+
+/*
+ * Diagnostics: blocking read of the 16 phase counters of "phase_timing", in
+ * ticks of the 100 MHz device wall clock, summed over all steps and launches
+ * since the option was set.  Phases: 0 load h and W x terms, 1 R h (MFMA),
+ * 2 gate sums and statistics, 3 wait, 4 statistics to (mean, sigma),
+ * 5 layer norm, sigma/tanh, cell, 6 output gate and hidden state, 7 wait,
+ * 8 projection, 9 wait.
+ */
+int lstm_int_phase_ticks(const lstm_int_model *model, int64_t ticks[16]);
 
 /*
  * Per-kernel device time of the forward calls made while profiling is on,

@@ -96,6 +96,10 @@ def lib():
                                        C.POINTER(Trace)]
         L.lstm_int_set_option.restype = C.c_int
         L.lstm_int_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
+        L.lstm_int_device_status.restype = C.c_int
+        L.lstm_int_device_status.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+        L.lstm_int_phase_ticks.restype = C.c_int
+        L.lstm_int_phase_ticks.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
         L.lstm_int_profile_begin.restype = C.c_int
         L.lstm_int_profile_begin.argtypes = [C.c_void_p]
         L.lstm_int_profile_end.restype = C.c_int
@@ -203,6 +207,18 @@ class Model:
     # lstm_int_set_option
     def set_option(self, key, value):
         _check(lib().lstm_int_set_option(self._h, key.encode(), value), "lstm_int_set_option")
+
+    # lstm_int_device_status
+    def device_status(self):
+        v = C.c_int32()
+        _check(lib().lstm_int_device_status(self._h, C.byref(v)), "lstm_int_device_status")
+        return v.value
+
+    # lstm_int_phase_ticks
+    def phase_ticks(self):
+        t = (C.c_int64 * 16)()
+        _check(lib().lstm_int_phase_ticks(self._h, t), "lstm_int_phase_ticks")
+        return list(t)
 
     # lstm_int_profile_begin / lstm_int_profile_end
     def profile_begin(self):

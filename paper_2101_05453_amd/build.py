@@ -5,7 +5,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblstm_int.so")
-SOURCES = ["prepare.cpp", "kernels.hip", "api.hip"]
+SOURCES = ["prepare.cpp", "kernels.hip", "persistent.hip", "rec_inst_8.hip", "rec_inst_20.hip",
+           "rec_inst_32.hip", "api.hip"]
 HOSTMATH_LIB = os.path.join(HERE, "liblstm_int_hostmath.so")
 
 # packed-fp32 instructions are disabled for all device code
@@ -14,19 +15,25 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contra
              "-Wall", "-Wno-unused-function"]
 
 
+def _compile(src, verbose):
+    obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
+    cmd = ["hipcc", "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + HIP_FLAGS
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0 or verbose:
+        print(" ".join(cmd))
+        print(_filter(r.stderr))
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {src}")
+    return obj
+
+
 def build(verbose=False):
-    """Compiles every source for gfx950 and links the shared library."""
-    objs = []
-    for src in SOURCES:
-        obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-        cmd = ["hipcc", "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + HIP_FLAGS
-        r = subprocess.run(cmd, capture_output=True, text=True)
-        if r.returncode != 0 or verbose:
-            print(" ".join(cmd))
-            print(_filter(r.stderr))
-        if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}")
-        objs.append(obj)
+    """Compiles every source for gfx950 (translation units in parallel) and
+    links the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+        objs = list(pool.map(lambda s: _compile(s, verbose), SOURCES))
     cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
     subprocess.run(cmd, check=True)
     build_hostmath()

@@ -9,7 +9,9 @@
 #include <vector>
 
 #include "kernels.h"
+#include "lstm_int_math.h"
 #include "model.h"
+#include "persistent.h"
 
 using namespace lstm_int;
 
@@ -20,7 +22,9 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // Device-side tensors of one layer, all inside the model's single allocation.
 struct LayerDev {
-  int Ipad = 0, Hpad = 0, Npad = 0;  // K extents padded to 64
+  // K extents padded to 64.  Hpad is padded to 128 so that the rows of a step's
+  // h never share a 128-byte cache line with another step's (see persistent.hip).
+  int Ipad = 0, Hpad = 0, Npad = 0;
   int GN = 0;                        // G * N output columns of the gate matmuls
   int8_t *W = nullptr;               // [pad128(G*N), Ipad]  present gates, gate-major
   int8_t *R = nullptr;               // [pad128(G*N), Hpad]
@@ -29,7 +33,19 @@ struct LayerDev {
   int16_t *Pq = nullptr, *Lq = nullptr;
   int32_t *qb = nullptr;
   const uint16_t *tanhc = nullptr;  // tanh table of the cell format Q(m_c).(15-m_c)
+  const uint8_t *tanhc_blob = nullptr;  // its compressed copy, and block shift (-1: none)
+  int sh_tanhc = -1;
   Requant rq_x, rq_h, rq_p;
+  // persistent path (persistent.h): tile-ordered copies; p2 = shape is eligible
+  bool p2 = false;
+  int GS = 0, ks = 0, Ncp = 0, ptiles = 0, npadp = 0;
+  int8_t *W2 = nullptr;     // [GS*8][32][Ipad]
+  int32_t *bx2 = nullptr;   // [GS*8][32]
+  int4 *R2 = nullptr;       // [GS][4][2][ks][64]
+  int32_t *bh4 = nullptr, *qb4 = nullptr;  // [4][Ncp]
+  int16_t *Lq4 = nullptr, *Pq3 = nullptr;  // [4][Ncp], [3][Ncp]
+  int8_t *Wp2 = nullptr;    // [ptiles][32][npadp]
+  int32_t *bp2 = nullptr;   // [ptiles][32]
 };
 
 struct Profile {
@@ -48,22 +64,33 @@ struct lstm_int_model {
   std::vector<LayerDev> dev;
   void *arena = nullptr;
   const uint16_t *sig3 = nullptr, *tanh3 = nullptr;
+  const uint8_t *sig3_blob = nullptr, *tanh3_blob = nullptr;
+  int sh_sig3 = -1, sh_tanh3 = -1;
+  int *status = nullptr;  // device word raised by the persistent kernel when a wait gives up
   int path = 0;
+  int spin_limit = 1 << 21;
+  int phase_timing = 0;
   Profile prof;
 };
 
 namespace {
 
 struct Workspace {
-  size_t tx, out[2], xpad, th, mbuf, c, h0, total;
+  size_t tx, out[2], xpad, th, mbuf, c, h0, sync, m2, total;
 };
+constexpr size_t kSyncBytes = 256 * 64 * 4 + 256 * 4 * 256 * 8;  // counters + statistics accumulators
 
 Workspace plan_workspace(const lstm_int_model *m, int64_t T, int64_t B) {
-  int maxGN = 0, maxHpad = 0, maxNpad = 0, maxN = 0;
+  int maxGN = 0, maxHpad = 0, maxNpad = 0, maxN = 0, maxNpadp = 0;
   for (size_t l = 0; l < m->host.size(); ++l) {
     const LayerHost &h = m->host[l];
     maxGN = std::max(maxGN, h.G * h.N);
-    maxHpad = std::max(maxHpad, round_up(h.H, 64));
+    // the persistent path stores 4 gate slots over GS*64 cells, batch padded to 32
+    if (!m->dev.empty() && m->dev[l].p2) {
+      maxGN = std::max(maxGN, 4 * m->dev[l].Ncp);
+      if (h.projection()) maxNpadp = std::max(maxNpadp, m->dev[l].npadp);
+    }
+    maxHpad = std::max(maxHpad, round_up(h.H, 128));
     maxNpad = std::max(maxNpad, round_up(h.N, 64));
     maxN = std::max(maxN, h.N);
   }
@@ -74,7 +101,7 @@ Workspace plan_workspace(const lstm_int_model *m, int64_t T, int64_t B) {
     off += align256(bytes);
     return o;
   };
-  w.tx = take((size_t)T * B * maxGN * 2);
+  w.tx = take((size_t)T * ((B + 31) / 32 * 32) * maxGN * 2);
   w.out[0] = take((size_t)T * B * maxHpad);
   w.out[1] = take((size_t)T * B * maxHpad);
   w.xpad = take((size_t)T * B * round_up(m->host[0].I, 64));
@@ -82,6 +109,8 @@ Workspace plan_workspace(const lstm_int_model *m, int64_t T, int64_t B) {
   w.mbuf = take((size_t)B * maxNpad);
   w.c = take((size_t)B * maxN * 2);
   w.h0 = take((size_t)B * maxHpad);
+  w.sync = take(kSyncBytes);
+  w.m2 = take((size_t)T * B * maxNpadp);
   w.total = off;
   return w;
 }
@@ -132,7 +161,8 @@ int upload(lstm_int_model *m) {
   bool need_tanh[9] = {false, false, false, false, false, false, false, false, false};
   for (const LayerHost &h : m->host) need_tanh[h.m_c] = true;
   need_tanh[3] = true;
-  size_t tab_off[9], sig_off = 0;
+  size_t tab_off[9], blob_off[9], sig_off = 0, sig_blob_off = 0;
+  int sh_tab[9] = {-1, -1, -1, -1, -1, -1, -1, -1, -1}, sh_sig = -1;
   for (int pass = 0; pass < 2; ++pass) {
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -141,18 +171,30 @@ int upload(lstm_int_model *m) {
       return o;
     };
     sig_off = take(32769 * 2);
-    if (pass) fill_sigmoid_table(3, reinterpret_cast<uint16_t *>(image.data() + sig_off));
+    sig_blob_off = take(kLutBlobBytes);
+    const size_t status_off = take(256);
+    if (pass) {
+      fill_sigmoid_table(3, reinterpret_cast<uint16_t *>(image.data() + sig_off));
+      sh_sig = compress_table(reinterpret_cast<const uint16_t *>(image.data() + sig_off),
+                              image.data() + sig_blob_off);
+      m->status = reinterpret_cast<int *>(static_cast<uint8_t *>(m->arena) + status_off);
+    }
     for (int mc = 0; mc <= 8; ++mc) {
       if (!need_tanh[mc]) continue;
       tab_off[mc] = take(32769 * 2);
-      if (pass) fill_tanh_table(mc, reinterpret_cast<uint16_t *>(image.data() + tab_off[mc]));
+      blob_off[mc] = take(kLutBlobBytes);
+      if (pass) {
+        fill_tanh_table(mc, reinterpret_cast<uint16_t *>(image.data() + tab_off[mc]));
+        sh_tab[mc] = compress_table(reinterpret_cast<const uint16_t *>(image.data() + tab_off[mc]),
+                                    image.data() + blob_off[mc]);
+      }
     }
     for (size_t l = 0; l < L; ++l) {
       const LayerHost &h = m->host[l];
       LayerDev &d = m->dev[l];
       const int first = 4 - h.G;
       d.Ipad = round_up(h.I, 64);
-      d.Hpad = round_up(h.H, 64);
+      d.Hpad = round_up(h.H, 128);
       d.Npad = round_up(h.N, 64);
       d.GN = h.G * h.N;
       const int rows = round_up(d.GN, 128);
@@ -166,8 +208,71 @@ int upload(lstm_int_model *m) {
         oWp = take((size_t)prow * d.Npad);
         obp = take((size_t)prow * 4);
       }
+      // tile-ordered copies for the persistent path
+      int ks = 0, rt = 0, grp = 0;
+      d.p2 = rec_supported(h.N, h.H, (int)h.flags, 32, &ks, &rt, &grp);
+      size_t oW2 = 0, obx2 = 0, oR2 = 0, obh4 = 0, oqb4 = 0, oLq4 = 0, oPq3 = 0, oWp2 = 0, obp2 = 0;
+      if (d.p2) {
+        d.GS = (h.N + 63) / 64;
+        d.ks = ks;
+        d.Ncp = d.GS * 64;
+        d.ptiles = h.projection() ? (h.H + 31) / 32 : 0;
+        d.npadp = round_up(h.N, 128);
+        oW2 = take((size_t)d.GS * 8 * 32 * d.Ipad);
+        obx2 = take((size_t)d.GS * 8 * 32 * 4);
+        oR2 = take((size_t)d.GS * 4 * 2 * ks * 64 * 16);
+        obh4 = take((size_t)4 * d.Ncp * 4);
+        oqb4 = take((size_t)4 * d.Ncp * 4);
+        oLq4 = take((size_t)4 * d.Ncp * 2);
+        oPq3 = take((size_t)3 * d.Ncp * 2);
+        if (h.projection()) {
+          oWp2 = take((size_t)d.ptiles * 32 * d.npadp);
+          obp2 = take((size_t)d.ptiles * 32 * 4);
+        }
+      }
       if (!pass) continue;
       uint8_t *base = image.data();
+      if (d.p2) {
+        for (int g = first; g < 4; ++g) {
+          for (int n = 0; n < h.N; ++n) {
+            const size_t src = (size_t)g * h.N + n;
+            const size_t trow = (size_t)(n / 8) * 32 + 8 * g + (n % 8);  // tile row rho = 8*gate + cell%8
+            memcpy(base + oW2 + trow * d.Ipad, h.Wq.data() + src * h.I, h.I);
+            reinterpret_cast<int32_t *>(base + obx2)[trow] = h.bx_fold[src];
+            reinterpret_cast<int32_t *>(base + obh4)[(size_t)g * d.Ncp + n] = h.bh_fold[src];
+            reinterpret_cast<int32_t *>(base + oqb4)[(size_t)g * d.Ncp + n] = h.qb[src];
+            reinterpret_cast<int16_t *>(base + oLq4)[(size_t)g * d.Ncp + n] = h.Lq[src];
+            // recurrent weights: [member][wave][tile][ks][lane][16], lane = rho + 32 * (k / 16 % 2)
+            const int member = n / 64, wave = (n % 64) / 16, tl = (n % 16) / 8, rho = 8 * g + (n % 8);
+            for (int k = 0; k < h.H; ++k) {
+              const int kstep = k / 32, lane = rho + 32 * ((k % 32) / 16), byte = k % 16;
+              const size_t o = ((((size_t)(member * 4 + wave) * 2 + tl) * ks + kstep) * 64 + lane) * 16 + byte;
+              base[oR2 + o] = (uint8_t)h.Rq[src * h.H + k];
+            }
+          }
+        }
+        for (int j = first; j < 3; ++j)
+          for (int n = 0; n < h.N; ++n)
+            reinterpret_cast<int16_t *>(base + oPq3)[(size_t)j * d.Ncp + n] = h.Pq[(size_t)j * h.N + n];
+        if (h.projection()) {
+          for (int pcol = 0; pcol < h.H; ++pcol) {
+            memcpy(base + oWp2 + (size_t)pcol * d.npadp, h.Wpq.data() + (size_t)pcol * h.N, h.N);
+            reinterpret_cast<int32_t *>(base + obp2)[pcol] = h.bp_fold[pcol];
+          }
+        }
+        uint8_t *db = static_cast<uint8_t *>(m->arena);
+        d.W2 = reinterpret_cast<int8_t *>(db + oW2);
+        d.bx2 = reinterpret_cast<int32_t *>(db + obx2);
+        d.R2 = reinterpret_cast<int4 *>(db + oR2);
+        d.bh4 = reinterpret_cast<int32_t *>(db + obh4);
+        d.qb4 = reinterpret_cast<int32_t *>(db + oqb4);
+        d.Lq4 = reinterpret_cast<int16_t *>(db + oLq4);
+        d.Pq3 = reinterpret_cast<int16_t *>(db + oPq3);
+        if (h.projection()) {
+          d.Wp2 = reinterpret_cast<int8_t *>(db + oWp2);
+          d.bp2 = reinterpret_cast<int32_t *>(db + obp2);
+        }
+      }
       for (int g = first; g < 4; ++g) {
         for (int n = 0; n < h.N; ++n) {
           const size_t src = (size_t)g * h.N + n, dst = (size_t)(g - first) * h.N + n;
@@ -199,6 +304,8 @@ int upload(lstm_int_model *m) {
         d.bp = reinterpret_cast<int32_t *>(dbase + obp);
       }
       d.tanhc = reinterpret_cast<const uint16_t *>(dbase + tab_off[h.m_c]);
+      d.tanhc_blob = dbase + blob_off[h.m_c];
+      d.sh_tanhc = sh_tab[h.m_c];
       d.rq_x = make_requant(h.Mx, h.ex, first, h.G, h.N, 0);
       d.rq_h = make_requant(h.Mh, h.eh, first, h.G, h.N, 0);
       if (h.projection()) d.rq_p = make_requant(&h.Mp, &h.ep, 0, 1, 1 << 28, h.zp_h);
@@ -216,6 +323,11 @@ int upload(lstm_int_model *m) {
   const uint8_t *dbase = static_cast<const uint8_t *>(m->arena);
   m->sig3 = reinterpret_cast<const uint16_t *>(dbase + sig_off);
   m->tanh3 = reinterpret_cast<const uint16_t *>(dbase + tab_off[3]);
+  m->sig3_blob = dbase + sig_blob_off;
+  m->tanh3_blob = dbase + blob_off[3];
+  m->sh_sig3 = sh_sig;
+  m->sh_tanh3 = sh_tab[3];
+  if (rec_init() != hipSuccess) return LSTM_INT_E_DEVICE;
   return LSTM_INT_OK;
 }
 
@@ -323,6 +435,95 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
     int8_t *out = reinterpret_cast<int8_t *>(wsb + ws.out[l & 1]);
     const size_t step_out = (size_t)B * d.Hpad;
 
+    // persistent path: eligible shape, no dump requested for this layer, batch fits one launch
+    int p2_ks = 0, p2_rt = 0, p2_groups = 0;
+    bool use_p2 = m->path != 1 && !tr && d.p2 && (reinterpret_cast<uintptr_t>(y) & 3) == 0 &&
+                  rec_supported(h.N, h.H, (int)h.flags, B, &p2_ks, &p2_rt, &p2_groups);
+    RecArgs ra;
+    if (use_p2) {
+      memset(&ra, 0, sizeof(ra));
+      ra.T = T; ra.B = B; ra.N = h.N; ra.H = h.H; ra.Hpad = d.Hpad; ra.flags = (int)h.flags; ra.m_c = h.m_c;
+      ra.GS = d.GS; ra.groups = p2_groups; ra.rows_pg = 32 * p2_rt; ra.ks = d.ks; ra.Ncp = d.Ncp;
+      ra.Bp = round_up(B, 32);
+      ra.R2 = d.R2; ra.bh4 = d.bh4; ra.Lq4 = d.Lq4; ra.qb4 = d.qb4; ra.Pq3 = d.Pq3;
+      ra.all_hi = 1;
+      for (int g = 0; g < 4; ++g) {
+        const int sg = g < 4 - h.G ? 4 - h.G : g;  // an absent gate borrows valid numbers; its rows are zero
+        ra.Mh[g] = h.Mh[sg]; ra.rh[g] = 31 - h.eh[sg];
+        if (ra.rh[g] < 32) ra.all_hi = 0;
+        ra.Mln[g] = h.Mln[sg]; ra.rln[g] = 31 - h.eln[sg];
+      }
+      for (int j = 0; j < 3; ++j) { ra.Mc[j] = h.Mc[j]; ra.rc[j] = 31 - h.ec[j]; }
+      ra.Mm = h.Mm; ra.rm = 31 - h.em; ra.zp_m = h.zp_m;
+      ra.sig_tab = m->sig3; ra.tanh_tab = m->tanh3; ra.tanhc_tab = d.tanhc;
+      ra.sig_blob = m->sig3_blob; ra.tanh_blob = m->tanh3_blob; ra.tanhc_blob = d.tanhc_blob;
+      ra.sh_sig = m->sh_sig3; ra.sh_tanh = m->sh_tanh3; ra.sh_tanhc = d.sh_tanhc;
+      ra.Wp2 = d.Wp2; ra.bp2 = d.bp2; ra.ptiles = d.ptiles; ra.npadp = d.npadp;
+      ra.Mp = h.Mp; ra.rp = 31 - h.ep; ra.zp_h = h.zp_h;
+      ra.tx2 = reinterpret_cast<const int4 *>(tx);
+      ra.h0 = h0; ra.out = out; ra.y = last ? y : nullptr;
+      ra.mbuf = reinterpret_cast<int8_t *>(wsb + ws.m2);
+      ra.c_in = c_state ? c_state + c_off : nullptr;
+      ra.c_out = c_state ? c_state + c_off : nullptr;
+      ra.counters = reinterpret_cast<unsigned *>(wsb + ws.sync);
+      ra.acc = reinterpret_cast<unsigned long long *>(wsb + ws.sync + 256 * 64 * 4);
+      ra.status = m->status;
+      ra.spin_limit = m->spin_limit;
+      ra.ticks = m->phase_timing ? reinterpret_cast<long long *>(m->status + 16) : nullptr;
+      // the kernel's short forms of rescale need shifts >= 32, its tables must compress
+      bool ok = ra.rm >= 32 && (!proj || ra.rp >= 32) && ra.sh_sig >= 0 && ra.sh_tanh >= 0 && ra.sh_tanhc >= 0;
+      for (int g = 4 - h.G; g < 4; ++g)
+        if (h.layer_norm() && ra.rln[g] < 32) ok = false;
+      for (int j = 4 - h.G; j < 3; ++j)
+        if (h.peephole() && ra.rc[j] < 32) ok = false;
+      if (!ok || rec_lds_bytes(ra) > 160 * 1024) use_p2 = false;
+    }
+    if (use_p2) {
+      {
+        Timed t(m->prof, s, LSTM_INT_K_OTHER);
+        if (h_state)
+          launch_copy_rows_i8(s, h_state + h_off, h.H, h0, d.Hpad, B, h.H, 0);
+        else
+          launch_fill_rows_i8(s, h0, d.Hpad, B, h.H, h.zp_h, 0);
+      }
+      {
+        Timed t(m->prof, s, LSTM_INT_K_INPUT_GEMM);
+        InGemmArgs ga;
+        memset(&ga, 0, sizeof(ga));
+        ga.A = in; ga.lda = ld_in; ga.T = T; ga.B = B; ga.Bp = ra.Bp;
+        ga.W2 = d.W2; ga.kpad = d.Ipad; ga.tiles = d.GS * 8; ga.bx2 = d.bx2;
+        ga.all_hi = 1;
+        for (int g = 0; g < 4; ++g) {
+          const int sg = g < 4 - h.G ? 4 - h.G : g;
+          ga.M[g] = h.Mx[sg]; ga.r[g] = 31 - h.ex[sg];
+          if (ga.r[g] < 32) ga.all_hi = 0;
+        }
+        ga.tx2 = reinterpret_cast<int4 *>(tx);
+        launch_in_gemm(s, ga);
+      }
+      // batch rows beyond one launch's groups run in further launches (rows never interact)
+      for (int b0 = 0; b0 < B; b0 += p2_groups * ra.rows_pg) {
+        {
+          Timed t(m->prof, s, LSTM_INT_K_OTHER);
+          launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), (int64_t)(kSyncBytes / 2), 0);
+        }
+        ra.batch0 = b0;
+        ra.groups = std::min(p2_groups, (B - b0 + ra.rows_pg - 1) / ra.rows_pg);
+        Timed t(m->prof, s, LSTM_INT_K_RECURRENT);
+        if (launch_rec(s, ra) != hipSuccess) return LSTM_INT_E_DEVICE;
+      }
+      {
+        Timed t(m->prof, s, LSTM_INT_K_OTHER);
+        if (h_state)
+          launch_copy_rows_i8(s, out + (size_t)(T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
+                              h.H, 0);
+      }
+      h_off += (size_t)B * h.H;
+      c_off += (size_t)B * h.N;
+      in = out;
+      ld_in = d.Hpad;
+      continue;
+    }
     {  // initial state: given, or real 0 (q = zp_h) and c = 0
       Timed t(m->prof, s, LSTM_INT_K_OTHER);
       if (h_state)
@@ -351,6 +552,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       if (tr && tr->th) launch_scatter_gates(s, th, tr->th + tg, B, h.G, h.N);
       CellArgs a;
       a.B = B; a.N = h.N; a.G = h.G; a.flags = (int32_t)h.flags; a.m_c = h.m_c;
+      a.inv_n = 1.0 / (double)h.N;
       a.tx = tx + (size_t)t * B * d.GN;
       a.th = th;
       a.c = c;
@@ -397,11 +599,41 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
 int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
   if (!m || !key) return LSTM_INT_E_INVALID_ARG;
   if (!strcmp(key, "path")) {
-    if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
+    if (value < 0 || value > 2) return LSTM_INT_E_INVALID_ARG;
     m->path = (int)value;
     return LSTM_INT_OK;
   }
+  if (!strcmp(key, "phase_timing")) {
+    m->phase_timing = value != 0;
+    if (m->device >= 0 && hipMemset(m->status + 16, 0, 16 * sizeof(long long)) != hipSuccess)
+      return LSTM_INT_E_DEVICE;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "spin_limit")) {
+    if (value < 1 || value > (1 << 30)) return LSTM_INT_E_INVALID_ARG;
+    m->spin_limit = (int)value;
+    return LSTM_INT_OK;
+  }
   return LSTM_INT_E_INVALID_ARG;
+}
+
+int lstm_int_device_status(const lstm_int_model *m, int32_t *status) {
+  if (!m || !status) return LSTM_INT_E_INVALID_ARG;
+  if (m->device < 0) return LSTM_INT_E_DEVICE;
+  if (hipSetDevice(m->device) != hipSuccess) return LSTM_INT_E_DEVICE;
+  int v = 0;
+  if (hipMemcpy(&v, m->status, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return LSTM_INT_E_DEVICE;
+  *status = v;
+  return LSTM_INT_OK;
+}
+
+int lstm_int_phase_ticks(const lstm_int_model *m, int64_t ticks[16]) {
+  if (!m || !ticks) return LSTM_INT_E_INVALID_ARG;
+  if (m->device < 0) return LSTM_INT_E_DEVICE;
+  if (hipSetDevice(m->device) != hipSuccess) return LSTM_INT_E_DEVICE;
+  if (hipMemcpy(ticks, m->status + 16, 16 * sizeof(long long), hipMemcpyDeviceToHost) != hipSuccess)
+    return LSTM_INT_E_DEVICE;
+  return LSTM_INT_OK;
 }
 
 int lstm_int_profile_begin(lstm_int_model *m) {

@@ -20,14 +20,39 @@ void hm_layernorm(const int16_t *q, int32_t n, const int16_t *qL, const int32_t 
     s1 += q[i];
     s2 += (int64_t)q[i] * q[i];
   }
-  const LnRow row = ln_row(s1, s2, n);
+  const LnRow row = ln_row(s1, s2, n, 1.0 / (double)n);
   for (int i = 0; i < n; ++i) out[i] = (int16_t)ln_apply(q[i], row, qL[i], qb[i], M, r);
+}
+
+// the per-row-prepared form used by the persistent kernel (second-stage shift >= 32)
+void hm_layernorm2(const int16_t *q, int32_t n, const int16_t *qL, const int32_t *qb, int32_t M,
+                   int32_t r, int16_t *out) {
+  int64_t s1 = 0, s2 = 0;
+  for (int i = 0; i < n; ++i) {
+    s1 += q[i];
+    s2 += (int64_t)q[i] * q[i];
+  }
+  const LnRow2 row = ln_row2(ln_row(s1, s2, n, 1.0 / (double)n));
+  for (int i = 0; i < n; ++i) out[i] = (int16_t)ln_apply2(q[i], row, (double)qL[i], (double)qb[i], M, r);
+}
+int32_t hm_cell_update32(int32_t i, int32_t z, int32_t f, int32_t c, int32_t m_c) {
+  return cell_update32(i, z, f, c, m_c);
 }
 
 void hm_sigmoid_table(int m, uint16_t *tab) { fill_sigmoid_table(m, tab); }
 void hm_tanh_table(int m, uint16_t *tab) { fill_tanh_table(m, tab); }
 int32_t hm_sigmoid(const uint16_t *tab, int32_t x) { return sigmoid_from_table(tab, x); }
 int32_t hm_tanh(const uint16_t *tab, int32_t x) { return tanh_from_table(tab, x); }
+int hm_compress(const uint16_t *tab, uint8_t *blob) { return compress_table(tab, blob); }
+int32_t hm_sigmoid_lut(const uint16_t *tab, const uint8_t *blob, int sh, int32_t x) {
+  Lut t{blob, reinterpret_cast<const uint16_t *>(blob + kLutDomain), tab, sh < 0 ? 0 : sh, sh < 0 ? 0 : kLutDomain};
+  return sigmoid_from_lut(t, x);
+}
+int32_t hm_tanh_lut(const uint16_t *tab, const uint8_t *blob, int sh, int32_t x) {
+  Lut t{blob, reinterpret_cast<const uint16_t *>(blob + kLutDomain), tab, sh < 0 ? 0 : sh, sh < 0 ? 0 : kLutDomain};
+  return tanh_from_lut(t, x);
+}
+int32_t hm_rescale_ge32(int32_t a, int32_t M, int32_t r) { return rescale_ge32(a, M, r); }
 int32_t hm_cifg(int32_t f) { return cifg_input_gate(f); }
 int32_t hm_cell_update(int32_t i, int32_t z, int32_t f, int32_t c, int32_t m_c) {
   return cell_update(i, z, f, c, m_c);

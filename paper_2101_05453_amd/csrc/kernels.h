@@ -33,6 +33,7 @@ void launch_gemm_i8(hipStream_t s, const int8_t *A, int lda, int M, const int8_t
 // (3.2.9), cell update and hidden state (3.2.7).
 struct CellArgs {
   int32_t B, N, G, flags, m_c;
+  double inv_n;       // 1.0 / N
   const int16_t *tx;  // [B, G*N] of this step
   const int16_t *th;  // [B, G*N]
   int16_t *c;         // [B, N] in/out

@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void cell_kernel(CellArgs a) {
       s2 += (int64_t)v * v;
     }
     block_sum2(s1, s2, red);
-    if (tid == 0) rows[g] = ln_row(s1, s2, N);
+    if (tid == 0) rows[g] = ln_row(s1, s2, N, a.inv_n);
   }
   __syncthreads();
   auto normed = [&](int g, int n) -> int32_t {
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(256) void cell_kernel(CellArgs a) {
     }
     if (ph) {
       block_sum2(s1, s2, red);
-      if (tid == 0) rows[3] = ln_row(s1, s2, N);
+      if (tid == 0) rows[3] = ln_row(s1, s2, N, a.inv_n);
       __syncthreads();
     }
   }

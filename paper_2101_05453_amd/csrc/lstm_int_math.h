@@ -7,6 +7,7 @@
 // a table), the comment states why the result is the same integer.
 #pragma once
 
+#include <math.h>
 #include <stdint.h>
 
 #if defined(__HIPCC__)
@@ -50,20 +51,38 @@ LSTM_HD int32_t rescale_hi(int32_t a, int32_t M, int32_t r) {
   return (hi + ((int32_t)1 << (r - 33))) >> (r - 32);
 }
 
+// The same for r >= 32, where the result is below 2^31 in magnitude and needs
+// no saturation: one 64-bit multiply-add and one shift.
+LSTM_HD int32_t rescale_ge32(int32_t a, int32_t M, int32_t r) {
+  return (int32_t)(((int64_t)a * (int64_t)M + ((int64_t)1 << (r - 1))) >> r);
+}
+
 // floor((a + 2^(k-1)) / 2^k), k >= 1
 LSTM_HD int32_t rsh_round(int32_t a, int32_t k) {
   return (int32_t)(((int64_t)a + ((int64_t)1 << (k - 1))) >> k);
 }
 
+// floor(num / d) for |num| < 2^51 and 1 <= d < 2^26, with inv_d = 1.0 / d in
+// double.  num is exact in double; the product with the rounded reciprocal is
+// off by less than 2^-1 of a unit (relative error 2^-52 on a quotient below
+// 2^51), so its floor misses by at most one, and the exact integer remainder
+// corrects it.
+LSTM_HD int64_t floor_div_recip(int64_t num, int32_t d, double inv_d) {
+  int64_t q = (int64_t)floor((double)num * inv_d);
+  const int64_t rem = num - q * d;
+  if (rem < 0) {
+    --q;
+  } else if (rem >= d) {
+    ++q;
+  }
+  return q;
+}
+
 // floor(sqrt(v)), 0 <= v < 2^52: the double root is within one of the
-// answer; the two comparisons settle it exactly.
+// answer; the comparisons settle it exactly.
 LSTM_HD int64_t isqrt_u52(int64_t v) {
   if (v <= 0) return 0;
-#if defined(__HIP_DEVICE_COMPILE__)
-  int64_t r = (int64_t)__dsqrt_rn((double)v);
-#else
-  int64_t r = (int64_t)__builtin_sqrt((double)v);
-#endif
+  int64_t r = (int64_t)sqrt((double)v);
   while (r * r > v) --r;
   while ((r + 1) * (r + 1) <= v) ++r;
   return r;
@@ -82,16 +101,15 @@ struct LnRow {
   double inv_sigma;  // 1 / sigma rounded to double (unused when sigma == 0)
 };
 
-LSTM_HD int64_t floor_div_pos(int64_t a, int64_t d) {  // d > 0
-  int64_t q = a / d;
-  if (a % d < 0) --q;
-  return q;
-}
-
-LSTM_HD LnRow ln_row(int64_t S1, int64_t S2, int32_t n) {
+// S2 * 2^20 can reach 2^62, too wide for the reciprocal division; with
+// S2 = a n + r (0 <= r < n) the quotient is a 2^20 + floor((r 2^20 + n/2)/n),
+// and both divisions have numerators below 2^44.
+LSTM_HD LnRow ln_row(int64_t S1, int64_t S2, int32_t n, double inv_n) {
   LnRow r;
-  int64_t mean = floor_div_pos(S1 * 1024 + (n >> 1), n);
-  int64_t var = floor_div_pos(S2 * 1048576 + (n >> 1), n) - mean * mean;
+  const int64_t mean = floor_div_recip(S1 * 1024 + (n >> 1), n, inv_n);
+  const int64_t a = floor_div_recip(S2, n, inv_n);
+  const int64_t low = floor_div_recip(((S2 - a * n) << 20) + (n >> 1), n, inv_n);
+  int64_t var = (a << 20) + low - mean * mean;
   if (var < 0) var = 0;
   r.mean = (int32_t)mean;
   r.sigma = (int32_t)isqrt_u52(var);
@@ -101,36 +119,73 @@ LSTM_HD LnRow ln_row(int64_t S1, int64_t S2, int32_t n) {
 
 // One element: q' = floor((2^10 (2^10 q - mean) + floor(sigma/2)) / sigma),
 // q'' = sat32(floor((q' qL + qb + 2^9) / 2^10)), out = sat16(rescale(q'')).
-// The quotient is taken as floor(num * (1/sigma)) in double and corrected by
-// the integer remainder: |num| < 2^38 is exact in double and the two
-// roundings move the product by less than 2^-14, so the floor is off by at
-// most one, which the remainder test repairs.
+// All of it in double, every step exact: the numerator is an integer below
+// 2^37; its product with the rounded reciprocal is within 2^-15 of the
+// quotient, so the floor misses by at most one, and the remainder -- an
+// integer below 2^27 in magnitude, which one fused multiply-add returns
+// exactly -- corrects it.  |q' qL + qb| < 2^53 and the division by 2^10 is a
+// power of two, so the second stage is exact as well.
 LSTM_HD int32_t ln_apply(int32_t q, const LnRow &row, int32_t qL, int32_t qb, int32_t M_ln,
                          int32_t r_ln) {
-  int64_t qn = 0;
+  double qn = 0.0;
   if (row.sigma != 0) {
-    int64_t num = (((int64_t)q << 10) - row.mean) * 1024 + (row.sigma >> 1);
-#if defined(__HIP_DEVICE_COMPILE__)
-    qn = (int64_t)floor((double)num * row.inv_sigma);
-#else
-    qn = (int64_t)__builtin_floor((double)num * row.inv_sigma);
-#endif
-    int64_t rem = num - qn * row.sigma;
-    if (rem < 0) {
-      --qn;
-    } else if (rem >= row.sigma) {
-      ++qn;
+    const double sg = (double)row.sigma;
+    const double num = (double)(q * 1024 - row.mean) * 1024.0 + (double)(row.sigma >> 1);
+    qn = floor(num * row.inv_sigma);
+    const double rem = fma(-qn, sg, num);
+    if (rem < 0.0) {
+      qn -= 1.0;
+    } else if (rem >= sg) {
+      qn += 1.0;
     }
   }
-  int64_t t = qn * (int64_t)qL + (int64_t)qb;
-  int32_t q2 = sat32_from64((t + 512) >> 10);
-  return sat16(rescale(q2, M_ln, r_ln));
+  const double t = fma(qn, (double)qL, (double)qb);
+  double q2 = floor((t + 512.0) * (1.0 / 1024.0));
+  q2 = q2 < -2147483648.0 ? -2147483648.0 : (q2 > 2147483647.0 ? 2147483647.0 : q2);
+  return sat16(rescale((int32_t)q2, M_ln, r_ln));
+}
+
+// The same element with the row's constants prepared once per row:
+//   c0 = -2^10 mean + floor(sigma/2), so that 2^20 q + c0 is the numerator.
+struct LnRow2 {
+  double inv_sigma, c0, sigma;
+  int32_t nonzero, pad;
+};
+LSTM_HD LnRow2 ln_row2(const LnRow &r) {
+  LnRow2 o;
+  o.inv_sigma = r.inv_sigma;
+  o.c0 = (double)(-(int64_t)r.mean * 1024 + (r.sigma >> 1));
+  o.sigma = (double)r.sigma;
+  o.nonzero = r.sigma != 0;
+  o.pad = 0;
+  return o;
+}
+// Requires the second-stage shift r_ln >= 32.  qL, qb are the layer-norm
+// weight and bias of the cell as doubles (exact: 16 and 32 bit integers).
+LSTM_HD int32_t ln_apply2(int32_t q, const LnRow2 &row, double qL, double qb, int32_t M_ln, int32_t r_ln) {
+  const double num = fma((double)q, 1048576.0, row.c0);
+  double qn = floor(num * row.inv_sigma);
+  const double rem = fma(-qn, row.sigma, num);
+  qn += rem < 0.0 ? -1.0 : (rem >= row.sigma ? 1.0 : 0.0);
+  qn = row.nonzero ? qn : 0.0;
+  const double t = fma(qn, qL, qb);
+  double q2 = floor(fma(t, 1.0 / 1024.0, 0.5));  // floor((t + 512) / 1024), exact
+  q2 = q2 < -2147483648.0 ? -2147483648.0 : (q2 > 2147483647.0 ? 2147483647.0 : q2);
+  return sat16(rescale_ge32((int32_t)q2, M_ln, r_ln));
+}
+
+// Cell update with 32-bit intermediates: |i z| <= 2^30 and the rounding terms
+// are below 2^23, so nothing leaves int32.
+LSTM_HD int32_t cell_update32(int32_t i, int32_t z, int32_t f, int32_t c, int32_t m_c) {
+  const int32_t iz = (i * z + ((int32_t)1 << (14 + m_c))) >> (15 + m_c);
+  const int32_t fc = (f * c + 16384) >> 15;
+  return sat16(iz + fc);
 }
 
 // ---------------------------------------------------------------------------
 // sigma and tanh, Sec. 3.2.1: int16 in Q(m).(15-m) -> Q0.15.  The device
 // reads them from tables indexed by |x| (0..32768) that hold the value before
-// mirroring and clamping, 0..32768; ActTables (activations.h) fills them.
+// mirroring and clamping, 0..32768 (fill_sigmoid_table / fill_tanh_table).
 //   sigma: x >= 0 -> min(v, 32767);      x < 0 -> 32768 - v
 //   tanh:  x >= 0 -> min(v, 32767);      x < 0 -> -v
 LSTM_HD int32_t sigmoid_from_table(const uint16_t *tab, int32_t x) {
@@ -141,6 +196,31 @@ LSTM_HD int32_t sigmoid_from_table(const uint16_t *tab, int32_t x) {
 LSTM_HD int32_t tanh_from_table(const uint16_t *tab, int32_t x) {
   int32_t a = x < 0 ? -x : x;
   int32_t v = tab[a];
+  return x < 0 ? -v : (v > 32767 ? 32767 : v);
+}
+
+// Compressed copy of the first kLutDomain entries of such a table, small
+// enough for LDS: tab[a] = base[a >> sh] + delta[a] with 8-bit deltas (the
+// tables are monotone, so a block of 2^sh entries that rises by at most 255
+// compresses exactly).  Entries at or beyond `lim` come from the full table.
+constexpr int kLutDomain = 16384;
+constexpr int kLutBlobBytes = kLutDomain + 2 * (kLutDomain >> 3);  // deltas, then bases (sh >= 3)
+struct Lut {
+  const uint8_t *delta;   // [kLutDomain]
+  const uint16_t *base;   // [kLutDomain >> sh]
+  const uint16_t *full;   // [32769]
+  int32_t sh, lim;        // lim = kLutDomain, or 0 when the table does not compress
+};
+LSTM_HD int32_t lut_mag(const Lut &t, int32_t a) {
+  if (a < t.lim) return (int32_t)t.base[a >> t.sh] + (int32_t)t.delta[a];
+  return t.full[a];
+}
+LSTM_HD int32_t sigmoid_from_lut(const Lut &t, int32_t x) {
+  const int32_t v = lut_mag(t, x < 0 ? -x : x);
+  return x < 0 ? 32768 - v : (v > 32767 ? 32767 : v);
+}
+LSTM_HD int32_t tanh_from_lut(const Lut &t, int32_t x) {
+  const int32_t v = lut_mag(t, x < 0 ? -x : x);
   return x < 0 ? -v : (v > 32767 ? 32767 : v);
 }
 

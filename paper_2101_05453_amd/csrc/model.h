@@ -45,6 +45,10 @@ int quantize_multiplier(double s, int32_t *M, int32_t *e);
 // 0..32768, for inputs in Q(m).(15-m) (Sec. 3.2.1).  Values lie in 0..32768.
 void fill_sigmoid_table(int m, uint16_t *tab /*[32769]*/);
 void fill_tanh_table(int m, uint16_t *tab /*[32769]*/);
+// Compresses the first 16384 entries of a table into `blob` (16384 deltas, then
+// the bases); returns the block shift (3..6), or -1 if no shift >= 3 keeps the
+// deltas within 8 bits.
+int compress_table(const uint16_t *tab, uint8_t *blob /*[kLutBlobBytes]*/);
 // exp(-y / 2^15) in Q0.31, y >= 0 (exposed for host-side checks)
 int64_t exp_neg_q31(int64_t y);
 

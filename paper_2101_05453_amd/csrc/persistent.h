@@ -1,0 +1,81 @@
+// Launch interface of the persistent recurrent path (gfx950): the input GEMM
+// that writes the W x terms in the tile order of the recurrent kernel, and the
+// recurrent kernel itself, which runs all T steps of one layer in one launch
+// with the recurrent weights resident in registers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lstm_int {
+
+// Tile order shared by the two kernels.  Cells are taken in tiles of 8; the 32
+// weight rows of a tile are ordered rho = 8*gate + cell_in_tile, which makes a
+// 32x32 MFMA leave each lane with all four gates of four cells of one batch
+// row.  The W x terms of (t, b) are stored as int16 in
+//   tx2[(t*Bp + b) / 32][cell tile][half][lane][8]
+// with lane = b % 32 + 32 * ((cell % 8) / 4), half 0 = gates i,f, half 1 =
+// gates z,o, and the 8 values = [gate in half][cell % 4].
+struct InGemmArgs {
+  const int8_t *A;  // activations [T*B, lda]
+  int lda, T, B, Bp;
+  const int8_t *W2;  // [tiles][32][kpad] tile-ordered weight rows
+  int kpad, tiles;   // tiles % 4 == 0
+  const int32_t *bx2;  // [tiles][32]
+  int32_t M[4], r[4], all_hi;
+  int4 *tx2;
+};
+void launch_in_gemm(hipStream_t s, const InGemmArgs &a);
+
+struct RecArgs {
+  int T, B, N, H, Hpad, flags, m_c;
+  int GS;         // workgroups (compute units) per group = cells / 64
+  int groups;     // groups in this launch, each owns rows_pg batch rows
+  int batch0;     // first batch row of this launch
+  int rows_pg;    // 32 * RT
+  int ks;         // 32-wide k steps held in registers (template KS)
+  int Ncp;        // GS * 64
+  int Bp;         // B rounded up to 32
+  const int4 *R2;      // [GS][4 waves][2 tiles][ks][64 lanes] 16 bytes each
+  const int32_t *bh4;  // [4][Ncp]
+  const int16_t *Lq4;  // [4][Ncp]
+  const int32_t *qb4;  // [4][Ncp]
+  const int16_t *Pq3;  // [3][Ncp]
+  int32_t Mh[4], rh[4], all_hi;
+  int32_t Mc[3], rc[3];
+  int32_t Mln[4], rln[4];
+  int32_t Mm, rm, zp_m;
+  const uint16_t *sig_tab, *tanh_tab, *tanhc_tab;  // full tables [32769]
+  const uint8_t *sig_blob, *tanh_blob, *tanhc_blob;  // compressed copies for LDS (lstm_int_math.h)
+  int sh_sig, sh_tanh, sh_tanhc;                    // block shifts, -1 = not compressed
+  // projection
+  const int8_t *Wp2;   // [ptiles][32][npadp]
+  const int32_t *bp2;  // [ptiles][32]
+  int ptiles, npadp;
+  int32_t Mp, rp, zp_h;
+  // data
+  const int4 *tx2;
+  const int8_t *h0;  // [B, Hpad]
+  int8_t *out;       // [T, B, Hpad]
+  int8_t *y;         // [T, B, H] or NULL
+  int8_t *mbuf;      // [T, B, npadp] (projection only)
+  const int16_t *c_in;  // [B, N] or NULL (zeros)
+  int16_t *c_out;       // [B, N] or NULL
+  // synchronization scratch, zeroed before the launch
+  unsigned *counters;          // [groups][64]
+  unsigned long long *acc;     // [groups][2 rounds][2 (S1,S2)][rows_pg*4]
+  int *status;                 // [0] != 0: a wait gave up or the placement check failed
+  int spin_limit;
+  long long *ticks;  // NULL, or [16] phase timers of workgroup 0 (diagnostics)
+};
+
+// Whether a layer shape can take the persistent path; fills ks and rt.
+bool rec_supported(int N, int H, int flags, int B, int *ks, int *rt, int *groups);
+// Dynamic LDS bytes of the recurrent kernel for these arguments.
+size_t rec_lds_bytes(const RecArgs &a);
+// Returns hipSuccess or the launch error.
+hipError_t launch_rec(hipStream_t s, const RecArgs &a);
+// One-time per process: raises the kernels' dynamic LDS limits.
+hipError_t rec_init();
+
+}  // namespace lstm_int

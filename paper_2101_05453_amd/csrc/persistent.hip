@@ -1,0 +1,233 @@
+// Persistent recurrent path for gfx950 (MI355X).
+//
+//   in_gemm_kernel   W x for all (t, b) on the 32x32x32 int8 MFMA, rescaled to
+//                    int16 (Secs. 3.2.4/3.2.5, zero point folded per Sec. 6)
+//                    and stored in the tile order the recurrent kernel reads.
+//   rec_kernel       all T steps of one layer in ONE launch.  A group of GS
+//                    workgroups (one per compute unit, all on one XCD, so they
+//                    share an L2) owns rows_pg batch rows; each workgroup owns
+//                    64 cells and keeps its slice of R in registers as MFMA
+//                    operands for the whole sequence, and its slice of W_proj
+//                    in LDS.  Per step: R h on the MFMA, gate sums, layer-norm
+//                    statistics (wavefront reductions, then one atomic add per
+//                    row and gate), sigma/tanh, cell update, hidden state,
+//                    projection; groups synchronize through a counter in
+//                    global memory.  Batch rows never interact, so groups run
+//                    independently.
+//
+// Exchange between the workgroups of a group goes through buffers that are
+// written once per step, in 128-byte cache lines that nothing has read before
+// in the launch, so a compute unit's vector L1 cannot hold a stale copy: a
+// step's h rows and m rows are multiples of 128 bytes and 128-byte aligned.
+// Stores are complete (vmcnt(0)) before a workgroup arrives at the group
+// barrier.
+#include "persistent.h"
+
+#include "lstm_int_math.h"
+
+namespace lstm_int {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned long long u64;
+
+constexpr int kLdsRow = 80;  // 64 data bytes + 16 pad
+constexpr int kPrmLdsBytes = 128;  // sizeof(PrmLds) in rec_kernel.inc.h
+
+// ---------------------------------------------------------------------------
+// Input GEMM: block = 128 (t,b) rows x 4 weight tiles (32 cells), 4 waves 2x2,
+// each wave 64 rows x 2 tiles = 2x2 MFMA 32x32 blocks.  Weight tile rows are
+// the MFMA's first operand: D[rho][row], rho = 8*gate + 4*(lane/32) + c.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void in_gemm_kernel(InGemmArgs a) {
+  __shared__ __attribute__((aligned(16))) int8_t Xs[128 * kLdsRow];
+  __shared__ __attribute__((aligned(16))) int8_t Ws[128 * kLdsRow];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int row_base = blockIdx.x * 128;  // padded rows m' = t * Bp + b
+  const int tile_base = blockIdx.y * 4;
+  const int rows_total = a.T * a.Bp;
+
+  // the two activation rows and two weight rows this thread stages per k tile
+  const int8_t *xsrc[2];
+  const int8_t *wsrc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = tid + i * 256;
+    int m = row_base + (c >> 2);
+    m = m < rows_total ? m : rows_total - 1;
+    const int t = m / a.Bp;
+    int b = m - t * a.Bp;
+    b = b < a.B ? b : a.B - 1;  // padded rows repeat the last real one; never read back
+    xsrc[i] = a.A + ((size_t)t * a.B + b) * a.lda + ((c & 3) << 4);
+    wsrc[i] = a.W2 + ((size_t)tile_base * 32 + (c >> 2)) * a.kpad + ((c & 3) << 4);
+  }
+
+  v16i acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+  const int KT = a.kpad >> 6;
+  int4 xreg[2], wreg[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    xreg[i] = *reinterpret_cast<const int4 *>(xsrc[i]);
+    wreg[i] = *reinterpret_cast<const int4 *>(wsrc[i]);
+  }
+  for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = tid + i * 256;
+      *reinterpret_cast<int4 *>(Xs + (c >> 2) * kLdsRow + ((c & 3) << 4)) = xreg[i];
+      *reinterpret_cast<int4 *>(Ws + (c >> 2) * kLdsRow + ((c & 3) << 4)) = wreg[i];
+    }
+    __syncthreads();
+    if (kt + 1 < KT) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        xreg[i] = *reinterpret_cast<const int4 *>(xsrc[i] + ((kt + 1) << 6));
+        wreg[i] = *reinterpret_cast<const int4 *>(wsrc[i] + ((kt + 1) << 6));
+      }
+    }
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      v4i xf[2], wf[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        xf[i] = *reinterpret_cast<const v4i *>(Xs + (wm * 64 + i * 32 + (lane & 31)) * kLdsRow +
+                                               kk * 32 + ((lane >> 5) << 4));
+        wf[i] = *reinterpret_cast<const v4i *>(Ws + (wn * 64 + i * 32 + (lane & 31)) * kLdsRow +
+                                               kk * 32 + ((lane >> 5) << 4));
+      }
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+          acc[ti][mi] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ti], xf[mi], acc[ti][mi], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // epilogue: lane holds gates 0..3 x cells 4*(lane/32)+0..3 of row (lane%32)
+#pragma unroll
+  for (int ti = 0; ti < 2; ++ti) {
+    const int tile = tile_base + wn * 2 + ti;
+    int32_t bias[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int4 b4 =
+          *reinterpret_cast<const int4 *>(a.bx2 + (size_t)tile * 32 + g * 8 + ((lane >> 5) << 2));
+      bias[g * 4 + 0] = b4.x; bias[g * 4 + 1] = b4.y; bias[g * 4 + 2] = b4.z; bias[g * 4 + 3] = b4.w;
+    }
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+      const int m0 = row_base + wm * 64 + mi * 32;  // multiple of 32
+      if (m0 >= rows_total) continue;
+      int4 *dst = a.tx2 + (((size_t)(m0 >> 5) * a.tiles + tile) * 2) * 64 + lane;
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        int32_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int idx = half * 8 + e;  // = 4 * gate + c
+          const int g = idx >> 2;
+          const int32_t s = acc[ti][mi][idx] + bias[idx];
+          v[e] = sat16(a.all_hi ? rescale_ge32(s, a.M[g], a.r[g]) : rescale(s, a.M[g], a.r[g]));
+        }
+        int4 pk;
+        pk.x = (v[0] & 0xFFFF) | (v[1] << 16);
+        pk.y = (v[2] & 0xFFFF) | (v[3] << 16);
+        pk.z = (v[4] & 0xFFFF) | (v[5] << 16);
+        pk.w = (v[6] & 0xFFFF) | (v[7] << 16);
+        dst[half * 64] = pk;
+      }
+    }
+  }
+}
+
+void launch_in_gemm(hipStream_t s, const InGemmArgs &a) {
+  if (a.T <= 0 || a.B <= 0) return;
+  dim3 grid((a.T * a.Bp + 127) / 128, a.tiles / 4);
+  hipLaunchKernelGGL(in_gemm_kernel, grid, dim3(256), 0, s, a);
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+static const int kKS[] = {8, 20, 32};
+
+bool rec_supported(int N, int H, int flags, int B, int *ks, int *rt, int *groups) {
+  if (N % 8 != 0 || N > 2048 || B < 1) return false;
+  if (!(flags & 8) && H != N) return false;
+  const int GS = (N + 63) / 64;
+  const int need = (((H + 127) / 128) * 128) / 32;  // Hpad / 32
+  int k = 0;
+  for (int cand : kKS)
+    if (!k && cand >= need) k = cand;
+  if (!k) return false;
+  const int max_groups = 8 * (32 / GS);
+  // 64 rows per group when 32 would need more than one launch; the largest
+  // register-resident slice (k = 32) leaves no room for the second row tile
+  int r = ((B + 31) / 32 > max_groups && k < 32) ? 2 : 1;
+  int g = (B + 32 * r - 1) / (32 * r);
+  if (g > max_groups) g = max_groups;  // the rest of the batch goes to further launches
+  *ks = k;
+  *rt = r;
+  *groups = g;
+  return true;
+}
+
+size_t rec_lds_bytes(const RecArgs &a) {
+  const int items = (a.rows_pg / 32) * 128;
+  const bool proj = a.flags & 8;
+  size_t tile = (size_t)a.rows_pg * (a.ks * 32 + 16);
+  if (proj && tile < 4 * 16 * 64 * 4) tile = 4 * 16 * 64 * 4;
+  size_t n = tile + (size_t)4 * items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 2 +
+             kPrmLdsBytes + 32;
+  n += (a.tanhc_blob != a.tanh_blob ? 3 : 2) * (size_t)kLutBlobBytes;
+  if (proj) {
+    const int per_cu = (a.ptiles + a.GS - 1) / a.GS;
+    n += (size_t)per_cu * 32 * (a.npadp + 16);
+  }
+  return n;
+}
+
+typedef void (*rec_fn)(RecArgs);
+rec_fn rec_pick_8(int rt, int fl);   // rec_inst_8.hip
+rec_fn rec_pick_20(int rt, int fl);  // rec_inst_20.hip
+rec_fn rec_pick_32(int rt, int fl);  // rec_inst_32.hip
+static rec_fn pick(int ks, int rt, int fl) {
+  if (ks == 8) return rec_pick_8(rt, fl);
+  if (ks == 20) return rec_pick_20(rt, fl);
+  if (ks == 32) return rec_pick_32(rt, fl);
+  return nullptr;
+}
+
+hipError_t rec_init() {
+  for (int ks : kKS)
+    for (int rt = 1; rt <= 2; ++rt)
+      for (int fl = 0; fl < 8; ++fl) {
+        rec_fn fn = pick(ks, rt, fl);
+        if (!fn) continue;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+      }
+  return hipSuccess;
+}
+
+hipError_t launch_rec(hipStream_t s, const RecArgs &a) {
+  rec_fn fn = pick(a.ks, a.rows_pg / 32, a.flags & 7);
+  if (!fn) return hipErrorInvalidValue;
+  const int slots = a.GS * ((a.groups + 7) / 8);
+  RecArgs args = a;
+  void *params[] = {&args};
+  return hipLaunchCooperativeKernel(reinterpret_cast<const void *>(fn), dim3(8 * slots), dim3(256), params,
+                                    (unsigned)rec_lds_bytes(a), s);
+}
+
+}  // namespace lstm_int

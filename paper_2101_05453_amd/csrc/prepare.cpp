@@ -8,6 +8,7 @@
 #include <cstring>
 #include <limits>
 
+#include "lstm_int_math.h"
 #include "model.h"
 
 namespace lstm_int {
@@ -259,6 +260,25 @@ int64_t exp_neg_q31(int64_t y) {
   for (int bit = 0; bit < 8; ++bit)
     if (v & (1u << (12 + bit))) acc = mul_q31(acc, kExpPow2[bit]);
   return (int64_t)acc;
+}
+
+int compress_table(const uint16_t *tab, uint8_t *blob) {
+  for (int sh = 6; sh >= 3; --sh) {
+    bool ok = true;
+    for (int a = 0; a < kLutDomain && ok; ++a) {
+      const int d = (int)tab[a] - (int)tab[(a >> sh) << sh];
+      ok = d >= 0 && d <= 255;
+    }
+    if (!ok) continue;
+    memset(blob, 0, kLutBlobBytes);
+    uint16_t *base = reinterpret_cast<uint16_t *>(blob + kLutDomain);
+    for (int a = 0; a < kLutDomain; ++a) {
+      blob[a] = (uint8_t)(tab[a] - tab[(a >> sh) << sh]);
+      if ((a & ((1 << sh) - 1)) == 0) base[a >> sh] = tab[a];
+    }
+    return sh;
+  }
+  return -1;
 }
 
 void fill_sigmoid_table(int m, uint16_t *tab) {

@@ -1,0 +1,651 @@
+// Device code of the persistent recurrent kernel (see persistent.hip for the
+// design).  Included by the rec_inst_*.hip translation units, which
+// instantiate it for their k depth.
+#pragma once
+
+#include <type_traits>
+
+#include "lstm_int_math.h"
+#include "persistent.h"
+
+namespace lstm_int {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned long long u64;
+
+// ---------------------------------------------------------------------------
+// Recurrent kernel
+// ---------------------------------------------------------------------------
+
+// Barrier among the GS workgroups of a group.  Every wave first waits for its
+// own stores (vmcnt(0)); thread 0 then adds one to the group's counter and
+// polls it.  Gives up after spin_limit polls (or when another workgroup gave
+// up), raising the status word so that every workgroup leaves the kernel.
+__device__ __forceinline__ bool group_sync(unsigned *counter, unsigned &epoch, int GS, int *status,
+                                           int spin_limit, int *lds_flag) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (GS == 1) return true;
+  epoch += (unsigned)GS;
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int ok = 1, budget = spin_limit;
+    while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch) {
+      if (--budget <= 0 || __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+        __hip_atomic_store(status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ok = 0;
+        break;
+      }
+    }
+    *lds_flag = ok;
+  }
+  __syncthreads();
+  return *lds_flag != 0;
+}
+
+// Per-layer constants, kept in LDS and read where they are used: as kernel
+// arguments they would all be live in scalar registers across the time loop.
+struct PrmLds {  // 128 bytes (kPrmLdsBytes in persistent.hip)
+  int32_t Mh[4], rh[4], Mc[4], rc[4], Mln[4], rln[4];
+  int32_t Mm, rm, zp_m, Mp, rp, zp_h, m_c, glo;
+};
+
+static_assert(sizeof(PrmLds) == 128, "rec_lds_bytes assumes 128 bytes");
+
+// |x| -> table value from the compressed copy in LDS; `a` must be below kLutDomain
+__device__ __forceinline__ int32_t lut_lds(const uint8_t *blob, int sh, int32_t a) {
+  return (int32_t)reinterpret_cast<const uint16_t *>(blob + kLutDomain)[a >> sh] + (int32_t)blob[a];
+}
+
+__device__ __forceinline__ int32_t abs_i32(int32_t v) { return v < 0 ? -v : v; }
+// table value t = tab[|x|] -> sigma(x), tanh(x) (Sec. 3.2.1 output clamp)
+__device__ __forceinline__ int32_t mirror_sigmoid(int32_t x, int32_t t) {
+  return x < 0 ? 32768 - t : (t > 32767 ? 32767 : t);
+}
+__device__ __forceinline__ int32_t mirror_tanh(int32_t x, int32_t t) {
+  return x < 0 ? -t : (t > 32767 ? 32767 : t);
+}
+
+// FL: bit 0 CIFG, bit 1 peephole, bit 2 layer norm (compile time, so that the
+// per-element code carries no tests of them); the projection is a runtime flag.
+template <int KS, int RT, int FL>
+__global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, b2 = lane >> 5;
+  constexpr bool cifg = FL & 1, ph = FL & 2, ln = FL & 4;
+  const bool proj = a.flags & 8;
+  const int GS = a.GS;
+
+  // placement: workgroup w runs on XCD w % 8; the workgroups of a group share one
+  const int wg = blockIdx.x;
+  const int xcd = wg & 7, slot = wg >> 3;
+  const int group = xcd + 8 * (slot / GS), member = slot % GS;
+  if (group >= a.groups) return;
+  {
+    // XCC_ID register (id 20), bits 3:0
+    const unsigned xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));
+    if ((int)(xcc & 7) != xcd && GS > 1 && tid == 0)
+      __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  constexpr int rows_pg = 32 * RT;
+  constexpr int items = RT * 128;  // (rt, gate, row) layer-norm rows of the group
+  const int row0 = a.batch0 + group * rows_pg;  // first batch row of the group
+
+  // ---- LDS carve-up (rec_lds_bytes mirrors it)
+  constexpr int LS = KS * 32 + 16;  // h tile row stride
+  uint8_t *p = lds;
+  int8_t *hT = reinterpret_cast<int8_t *>(p);
+  int32_t *pred = reinterpret_cast<int32_t *>(p);  // projection partials reuse the h tile between steps
+  {
+    const size_t tile_bytes = (size_t)rows_pg * LS, pred_bytes = proj ? 4 * 16 * 64 * 4 : 0;
+    p += tile_bytes > pred_bytes ? tile_bytes : pred_bytes;
+  }
+  u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)4 * items * 8;
+  LnRow2 *lnrow = reinterpret_cast<LnRow2 *>(p);         p += (size_t)items * sizeof(LnRow2);
+  double *LdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;  // layer-norm weights as doubles
+  double *bdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;  // layer-norm biases as doubles
+  int16_t *PqL = reinterpret_cast<int16_t *>(p);         p += 4 * 64 * 2;  // 3 used
+  PrmLds *prm = reinterpret_cast<PrmLds *>(p);           p += sizeof(PrmLds);
+  int *flag = reinterpret_cast<int *>(p);                p += 16;
+  const int dump_off = (int)(p - lds);                   p += 16;  // sink for staging chunks outside the tile
+  // compressed sigma / tanh tables (lstm_int_math.h); the cell-format tanh shares the gate one if equal
+  const bool share_tanh = a.tanhc_blob == a.tanh_blob;
+  const uint8_t *lutS = p;                               p += kLutBlobBytes;
+  const uint8_t *lutT = p;                               p += kLutBlobBytes;
+  const uint8_t *lutC = share_tanh ? lutT : p;           p += share_tanh ? 0 : kLutBlobBytes;
+  int8_t *WpL = reinterpret_cast<int8_t *>(p);
+  const int WLS = a.npadp + 16;  // W_proj tile row stride in LDS
+  const int my_ptiles = proj ? (a.ptiles > member ? (a.ptiles - member + GS - 1) / GS : 0) : 0;
+  const int sh_sig = a.sh_sig, sh_tanh = a.sh_tanh, sh_tanhc = a.sh_tanhc;
+
+  // ---- one-time loads: R slice and its biases -> registers, other per-cell
+  // parameters, the tables and the W_proj tiles -> LDS
+  v4i Wf[2][KS];
+  {
+    const int4 *src = a.R2 + ((size_t)(member * 4 + wave) * 2) * KS * 64 + lane;
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int4 w = src[(size_t)(tl * KS + ks) * 64];
+        Wf[tl][ks] = v4i{w.x, w.y, w.z, w.w};
+      }
+  }
+  const int cell_w = wave * 16 + 4 * b2;  // + tile * 8 + c, within the workgroup's 64 cells
+  int32_t bhr[2][16];                     // folded recurrent bias of [tile][4*gate + c]
+#pragma unroll
+  for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int4 b4 = *reinterpret_cast<const int4 *>(a.bh4 + (size_t)g * a.Ncp + member * 64 + cell_w + tl * 8);
+      bhr[tl][g * 4 + 0] = b4.x; bhr[tl][g * 4 + 1] = b4.y; bhr[tl][g * 4 + 2] = b4.z; bhr[tl][g * 4 + 3] = b4.w;
+    }
+  {
+    const int g = tid >> 6, n = tid & 63;  // 256 threads = 4 gates x 64 cells
+    const size_t idx = (size_t)g * a.Ncp + member * 64 + n;
+    LdL[tid] = ln ? (double)a.Lq4[idx] : 0.0;
+    bdL[tid] = ln ? (double)a.qb4[idx] : 0.0;
+    PqL[tid] = (ph && g < 3) ? a.Pq3[idx] : 0;
+  }
+  if (tid < 4) {
+    prm->Mh[tid] = a.Mh[tid]; prm->rh[tid] = a.rh[tid];
+    prm->Mc[tid] = tid < 3 ? a.Mc[tid] : 0; prm->rc[tid] = tid < 3 ? a.rc[tid] : 32;
+    prm->Mln[tid] = a.Mln[tid]; prm->rln[tid] = a.rln[tid];
+  }
+  if (tid == 0) {
+    prm->Mm = a.Mm; prm->rm = a.rm; prm->zp_m = a.zp_m;
+    prm->Mp = a.Mp; prm->rp = a.rp; prm->zp_h = a.zp_h;
+    prm->m_c = a.m_c; prm->glo = ln ? -32767 : -32768;
+  }
+  for (int i = tid; i < rows_pg * LS / 16; i += 256) reinterpret_cast<int4 *>(hT)[i] = int4{0, 0, 0, 0};
+  for (int i = tid; i < kLutBlobBytes / 16; i += 256) {
+    reinterpret_cast<int4 *>(const_cast<uint8_t *>(lutS))[i] = reinterpret_cast<const int4 *>(a.sig_blob)[i];
+    reinterpret_cast<int4 *>(const_cast<uint8_t *>(lutT))[i] = reinterpret_cast<const int4 *>(a.tanh_blob)[i];
+    if (!share_tanh)
+      reinterpret_cast<int4 *>(const_cast<uint8_t *>(lutC))[i] = reinterpret_cast<const int4 *>(a.tanhc_blob)[i];
+  }
+  for (int pt = 0; pt < my_ptiles; ++pt) {
+    const int8_t *src = a.Wp2 + (size_t)(member + pt * GS) * 32 * a.npadp;
+    const int chunks_per_row = a.npadp >> 4;
+    for (int i = tid; i < 32 * chunks_per_row; i += 256) {
+      const int r = i / chunks_per_row, c = i - r * chunks_per_row;
+      *reinterpret_cast<int4 *>(WpL + ((size_t)pt * 32 + r) * WLS + (c << 4)) =
+          *reinterpret_cast<const int4 *>(src + (size_t)r * a.npadp + (c << 4));
+    }
+  }
+
+  // cell state of this lane's 8 cells x RT row tiles, kept in registers
+  int32_t creg[RT][2][4];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl) {
+      const int row = row0 + rt * 32 + col;
+      const int n0 = member * 64 + cell_w + tl * 8;
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        creg[rt][tl][c] = (a.c_in && row < a.B && n0 + c < a.N) ? a.c_in[(size_t)row * a.N + n0 + c] : 0;
+    }
+
+  // h tile staging: chunk j of this thread is 16 bytes of one tile row
+  constexpr int CPR = KS * 2;                       // 16-byte chunks per tile row
+  constexpr int NCH = (RT * 32 * CPR + 255) / 256;  // chunks per thread
+  int hsrc[NCH], hdst[NCH];  // byte offsets; chunks outside the tile read offset 0 and land in a dump slot
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int i = tid + j * 256;
+    const int r = i / CPR, c = i - r * CPR;
+    int row = row0 + r;
+    row = row < a.B ? row : a.B - 1;
+    const bool valid = r < rows_pg && (c << 4) < a.Hpad;
+    hsrc[j] = valid ? row * a.Hpad + (c << 4) : 0;
+    hdst[j] = valid ? r * LS + (c << 4) : dump_off;
+  }
+
+  // projection bias of this thread's four outputs of its first tile
+  int32_t bpr[4] = {0, 0, 0, 0};
+  if (my_ptiles > 0) {
+    const int4 b4 = *reinterpret_cast<const int4 *>(a.bp2 + member * 32 + 8 * (tid >> 6) + 4 * ((tid & 63) >> 5));
+    bpr[0] = b4.x; bpr[1] = b4.y; bpr[2] = b4.z; bpr[3] = b4.w;
+  }
+
+  __syncthreads();  // LDS contents above are in place before the first step
+
+  unsigned epoch = 0;
+  unsigned *counter = a.counters + group * 64;
+  u64 *accS = a.acc + (size_t)group * 4 * 256;  // [round][S1|S2][item], item < 256
+  int64_t prevS[2][2] = {{0, 0}, {0, 0}};       // this thread's item, per round: S1, S2
+  const double inv_n = 1.0 / (double)a.N;
+  const int g_first = cifg ? 1 : 0;
+
+  // optional phase timing of workgroup 0 (diagnostics): 100 MHz wall clock ticks per phase
+  long long tick_last = 0;
+#define TICK(i)                                            \
+  do {                                                     \
+    if (a.ticks && wg == 0 && tid == 0) {                  \
+      asm volatile("" ::: "memory");                       \
+      const long long now = (long long)wall_clock64();     \
+      a.ticks[i] += now - tick_last;                       \
+      tick_last = now;                                     \
+    }                                                      \
+  } while (0)
+  if (a.ticks && wg == 0 && tid == 0) tick_last = (long long)wall_clock64();
+
+  // the two 16-byte W x pieces of (rt, tile) for step t
+  auto tx_ptr = [&](int t, int rt, int tl) -> const int4 * {
+    size_t rb = ((size_t)t * a.Bp + row0 + rt * 32) >> 5;
+    const size_t rbmax = ((size_t)a.T * a.Bp) >> 5;
+    rb = rb < rbmax ? rb : rbmax - 1;
+    return a.tx2 + ((rb * (size_t)(GS * 8) + member * 8 + wave * 2 + tl) * 2) * 64 + lane;
+  };
+
+
+  for (int t = 0; t < a.T; ++t) {
+    // ---- h^{t-1} rows of the group -> LDS; W x terms of this step -> registers
+    {
+      const int8_t *hp = t == 0 ? a.h0 : a.out + (size_t)(t - 1) * a.B * a.Hpad;
+      int4 hv[NCH];
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) hv[j] = *reinterpret_cast<const int4 *>(hp + hsrc[j]);
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) *reinterpret_cast<int4 *>(lds + hdst[j]) = hv[j];
+    }
+    int4 txv[RT][2][2];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl) {
+        const int4 *src = tx_ptr(t, rt, tl);
+        txv[rt][tl][0] = src[0];
+        txv[rt][tl][1] = src[64];
+      }
+    __syncthreads();
+    TICK(0);
+
+    // ---- R h on the MFMA: acc[rt][tile][4*gate + c]
+    v16i acc[RT][2];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[rt][tl][v] = 0;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const v4i hf = *reinterpret_cast<const v4i *>(hT + (size_t)(rt * 32 + col) * LS + ks * 32 + (b2 << 4));
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl)
+          acc[rt][tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Wf[tl][ks], hf, acc[rt][tl], 0, 0, 0);
+      }
+    }
+    TICK(1);
+
+    // ---- gate sums (Secs. 3.2.4/3.2.5) and layer-norm partial statistics.
+    // With a peephole the o gate keeps tx + th here and is finished after c^t.
+    const int32_t glo = prm->glo;
+    auto gate_sums = [&](auto fast_tag) {
+      constexpr bool FAST = decltype(fast_tag)::value;  // every shift of the R h rescale is >= 32
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        int32_t s1[4] = {0, 0, 0, 0};
+        int64_t s2[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl) {
+          const int32_t txw[8] = {txv[rt][tl][0].x, txv[rt][tl][0].y, txv[rt][tl][0].z, txv[rt][tl][0].w,
+                                  txv[rt][tl][1].x, txv[rt][tl][1].y, txv[rt][tl][1].z, txv[rt][tl][1].w};
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int32_t Mg = prm->Mh[g], rg = prm->rh[g];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const int idx = g * 4 + c;
+              const int32_t s = acc[rt][tl][idx] + bhr[tl][idx];
+              const int32_t th = sat16(FAST ? rescale_ge32(s, Mg, rg) : rescale(s, Mg, rg));
+              const int32_t w = txw[idx >> 1];
+              const int32_t tx = (idx & 1) ? (w >> 16) : (int32_t)(int16_t)(w & 0xFFFF);
+              int32_t v = tx + th;
+              if (ph && g < 2) {
+                const int cl = cell_w + tl * 8 + c;
+                v += sat16(rescale_ge32((int32_t)PqL[g * 64 + cl] * creg[rt][tl][c], prm->Mc[g], prm->rc[g]));
+              }
+              if (!(ph && g == 3)) v = clamp_i32(v, glo, 32767);
+              acc[rt][tl][idx] = v;
+              s1[g] += v;
+              s2[g] += (int64_t)v * v;
+            }
+          }
+        }
+        if (ln) {
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            // 16 cells of this wave: the two lanes of a row (lane, lane ^ 32)
+            int64_t pk = (s2[g] << 24) + s1[g];
+            pk += __shfl_xor(pk, 32, 64);
+            if (b2 == 0) red[(size_t)wave * items + (rt * 4 + g) * 32 + col] = (u64)pk;
+          }
+        }
+      }
+    };
+    if (a.all_hi) gate_sums(std::true_type{}); else gate_sums(std::false_type{});
+
+    auto publish_stats = [&](int round, int g_lo, int g_hi) {
+      __syncthreads();
+      if (tid < items) {
+        const int g = (tid >> 5) & 3;
+        if (g >= g_lo && g <= g_hi) {
+          const int64_t pk = (int64_t)(red[tid] + red[items + tid] + red[2 * items + tid] + red[3 * items + tid]);
+          const int64_t v1 = ((pk + (1 << 23)) & 0xFFFFFF) - (1 << 23);  // signed low 24 bits
+          const int64_t v2 = (pk - v1) >> 24;
+          __hip_atomic_fetch_add(&accS[(round * 2 + 0) * 256 + tid], (u64)v1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(&accS[(round * 2 + 1) * 256 + tid], (u64)v2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    };
+    auto collect_stats = [&](int round, int g_lo, int g_hi) {
+      if (tid < items) {
+        const int g = (tid >> 5) & 3;
+        if (g >= g_lo && g <= g_hi) {
+          const int64_t c1 = (int64_t)__hip_atomic_load(&accS[(round * 2 + 0) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const int64_t c2 = (int64_t)__hip_atomic_load(&accS[(round * 2 + 1) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const LnRow r = ln_row(c1 - prevS[round][0], c2 - prevS[round][1], a.N, inv_n);
+          prevS[round][0] = c1;
+          prevS[round][1] = c2;
+          lnrow[tid] = ln_row2(r);
+        }
+      }
+      __syncthreads();
+    };
+    TICK(2);
+    if (ln) {
+      publish_stats(0, g_first, ph ? 2 : 3);
+      if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, flag)) return;
+      TICK(3);
+      collect_stats(0, g_first, ph ? 2 : 3);
+      TICK(4);
+    }
+
+    // ---- layer norm, sigma/tanh, cell update (Secs. 3.2.6, 3.2.1, 3.2.9, 3.2.7),
+    // in stages over all of the lane's cells so that the table reads of a stage
+    // are in flight together
+    auto gate_in = [&](int rt, int tl, int g, int c) -> int32_t {
+      const int32_t v = acc[rt][tl][g * 4 + c];
+      if (!ln) return v;
+      const int cl = cell_w + tl * 8 + c;
+      return ln_apply2(v, lnrow[(rt * 4 + g) * 32 + col], LdL[g * 64 + cl], bdL[g * 64 + cl], prm->Mln[g],
+                       prm->rln[g]);
+    };
+    int32_t xi[RT][2][4], xf[RT][2][4], xz[RT][2][4], xo[RT][2][4];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          xi[rt][tl][c] = cifg ? 0 : gate_in(rt, tl, 0, c);
+          xf[rt][tl][c] = gate_in(rt, tl, 1, c);
+          xz[rt][tl][c] = gate_in(rt, tl, 2, c);
+          xo[rt][tl][c] = ph ? 0 : gate_in(rt, tl, 3, c);
+        }
+    // sigma / tanh from the LDS tables, all reads of the stage in flight together;
+    // a value beyond the compressed domain (rare) sends the wave to the full tables
+    {
+      int over = 0;
+      int32_t tf[RT][2][4], tz[RT][2][4], ti[RT][2][4], to[RT][2][4];
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int32_t mf = abs_i32(xf[rt][tl][c]), mz = abs_i32(xz[rt][tl][c]);
+            const int32_t mi = abs_i32(xi[rt][tl][c]), mo = abs_i32(xo[rt][tl][c]);
+            over |= (mf | mz | mi | mo) >= kLutDomain;  // all four are non-negative and below 2^16
+            tf[rt][tl][c] = lut_lds(lutS, sh_sig, mf < kLutDomain ? mf : kLutDomain - 1);
+            tz[rt][tl][c] = lut_lds(lutT, sh_tanh, mz < kLutDomain ? mz : kLutDomain - 1);
+            ti[rt][tl][c] = cifg ? 0 : lut_lds(lutS, sh_sig, mi < kLutDomain ? mi : kLutDomain - 1);
+            to[rt][tl][c] = ph ? 0 : lut_lds(lutS, sh_sig, mo < kLutDomain ? mo : kLutDomain - 1);
+          }
+      if (__builtin_amdgcn_ballot_w64(over != 0) != 0) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+          for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const int32_t mf = abs_i32(xf[rt][tl][c]), mz = abs_i32(xz[rt][tl][c]);
+              const int32_t mi = abs_i32(xi[rt][tl][c]), mo = abs_i32(xo[rt][tl][c]);
+              if (mf >= kLutDomain) tf[rt][tl][c] = a.sig_tab[mf];
+              if (mz >= kLutDomain) tz[rt][tl][c] = a.tanh_tab[mz];
+              if (!cifg && mi >= kLutDomain) ti[rt][tl][c] = a.sig_tab[mi];
+              if (!ph && mo >= kLutDomain) to[rt][tl][c] = a.sig_tab[mo];
+            }
+      }
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            xf[rt][tl][c] = mirror_sigmoid(xf[rt][tl][c], tf[rt][tl][c]);
+            xz[rt][tl][c] = mirror_tanh(xz[rt][tl][c], tz[rt][tl][c]);
+            xi[rt][tl][c] = mirror_sigmoid(xi[rt][tl][c], ti[rt][tl][c]);
+            xo[rt][tl][c] = mirror_sigmoid(xo[rt][tl][c], to[rt][tl][c]);
+          }
+    }
+    const int32_t m_c = prm->m_c;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      int32_t s1 = 0;
+      int64_t s2 = 0;
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int32_t f = xf[rt][tl][c];
+          const int32_t i = cifg ? cifg_input_gate(f) : xi[rt][tl][c];
+          const int32_t cnew = cell_update32(i, xz[rt][tl][c], f, creg[rt][tl][c], m_c);
+          creg[rt][tl][c] = cnew;
+          if (ph) {  // finish the o gate sum with P_o . c^t (eq. 5)
+            const int cl = cell_w + tl * 8 + c;
+            int32_t v = acc[rt][tl][12 + c] +
+                        sat16(rescale_ge32((int32_t)PqL[2 * 64 + cl] * cnew, prm->Mc[2], prm->rc[2]));
+            v = clamp_i32(v, glo, 32767);
+            acc[rt][tl][12 + c] = v;
+            s1 += v;
+            s2 += (int64_t)v * v;
+          }
+        }
+      if (ph && ln) {
+        int64_t pk = (s2 << 24) + s1;
+        pk += __shfl_xor(pk, 32, 64);
+        if (b2 == 0) red[(size_t)wave * items + (rt * 4 + 3) * 32 + col] = (u64)pk;
+      }
+    }
+    TICK(5);
+    if (ph) {
+      if (ln) {
+        publish_stats(1, 3, 3);
+        if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, flag)) return;
+        collect_stats(1, 3, 3);
+      }
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) xo[rt][tl][c] = gate_in(rt, tl, 3, c);
+    }
+
+    // ---- hidden state (Sec. 3.2.7); m is int8.  tanh of the new cell state in its
+    // own format (Sec. 3.2.2), and with a peephole the sigma of the o gate
+    int32_t tc[RT][2][4];
+    {
+      int over = 0;
+      int32_t to[RT][2][4];
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int32_t mc = abs_i32(creg[rt][tl][c]), mo = ph ? abs_i32(xo[rt][tl][c]) : 0;
+            over |= (mc | mo) >= kLutDomain;
+            tc[rt][tl][c] = lut_lds(lutC, sh_tanhc, mc < kLutDomain ? mc : kLutDomain - 1);
+            to[rt][tl][c] = ph ? lut_lds(lutS, sh_sig, mo < kLutDomain ? mo : kLutDomain - 1) : 0;
+          }
+      if (__builtin_amdgcn_ballot_w64(over != 0) != 0) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+          for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const int32_t mc = abs_i32(creg[rt][tl][c]), mo = ph ? abs_i32(xo[rt][tl][c]) : 0;
+              if (mc >= kLutDomain) tc[rt][tl][c] = a.tanhc_tab[mc];
+              if (ph && mo >= kLutDomain) to[rt][tl][c] = a.sig_tab[mo];
+            }
+      }
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            tc[rt][tl][c] = mirror_tanh(creg[rt][tl][c], tc[rt][tl][c]);
+            if (ph) xo[rt][tl][c] = mirror_sigmoid(xo[rt][tl][c], to[rt][tl][c]);
+          }
+    }
+    int8_t *mdst = proj ? a.mbuf + (size_t)t * a.B * a.npadp : a.out + (size_t)t * a.B * a.Hpad;
+    const int mld = proj ? a.npadp : a.Hpad;
+    const int32_t Mm = prm->Mm, rm = prm->rm, zp_m = prm->zp_m;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int row = row0 + rt * 32 + col;
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl) {
+        const int n0 = member * 64 + cell_w + tl * 8;
+        uint32_t pk = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int32_t mq = sat8(rescale_ge32(xo[rt][tl][c] * tc[rt][tl][c], Mm, rm) + zp_m);
+          pk |= (uint32_t)(mq & 0xFF) << (8 * c);
+        }
+        if (row < a.B && n0 < a.N) {  // N % 8 == 0: the four cells are valid together
+          *reinterpret_cast<uint32_t *>(mdst + (size_t)row * mld + n0) = pk;
+          if (!proj && a.y) {
+            int8_t *yd = a.y + ((size_t)t * a.B + row) * a.H + n0;  // H = N, a multiple of 4
+            *reinterpret_cast<uint32_t *>(yd) = pk;
+          }
+        }
+      }
+    }
+    TICK(6);
+    if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, flag)) return;
+    TICK(7);
+
+    // ---- projection (Sec. 3.2.8): tile pt of 32 outputs, K = N split over the four waves
+    if (proj) {
+      const int per_wave = a.npadp >> 7;  // 32-wide k steps per wave, at most 16 (N <= 2048)
+      const int32_t Mp = prm->Mp, rp = prm->rp, zp_h = prm->zp_h;
+      for (int pt = 0; pt < my_ptiles; ++pt) {
+        const int ptile = member + pt * GS;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          int row = row0 + rt * 32 + col;
+          row = row < a.B ? row : a.B - 1;
+          const int8_t *mrow = a.mbuf + ((size_t)t * a.B + row) * a.npadp + (b2 << 4) + wave * per_wave * 32;
+          const int8_t *wrow = WpL + ((size_t)pt * 32 + col) * WLS + (b2 << 4) + wave * per_wave * 32;
+          int4 mv[16];
+#pragma unroll
+          for (int k = 0; k < 16; ++k) {
+            const int kk = k < per_wave ? k : per_wave - 1;  // steps past the end re-read the last one
+            mv[k] = *reinterpret_cast<const int4 *>(mrow + kk * 32);
+          }
+          v16i pacc;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) pacc[v] = 0;
+#pragma unroll
+          for (int k = 0; k < 16; ++k) {
+            const int kk = k < per_wave ? k : per_wave - 1;
+            v4i wf = *reinterpret_cast<const v4i *>(wrow + kk * 32);
+            if (k >= per_wave) wf = v4i{0, 0, 0, 0};  // ... against zero weights
+            pacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, v4i{mv[k].x, mv[k].y, mv[k].z, mv[k].w}, pacc, 0, 0, 0);
+          }
+#pragma unroll
+          for (int v = 0; v < 16; ++v) pred[(wave * 16 + v) * 64 + lane] = pacc[v];
+          __syncthreads();
+          {
+            // thread (q = tid / 64, lane' = tid % 64): outputs 8q + 4*(lane'/32) + 0..3 of row lane' % 32
+            const int q = tid >> 6, l2 = tid & 63;
+            const int p0 = ptile * 32 + 8 * q + 4 * (l2 >> 5);
+            const int orow = row0 + rt * 32 + (l2 & 31);
+            uint32_t pk = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const int v = 4 * q + c;
+              const int32_t s = pred[(0 * 16 + v) * 64 + l2] + pred[(1 * 16 + v) * 64 + l2] +
+                                pred[(2 * 16 + v) * 64 + l2] + pred[(3 * 16 + v) * 64 + l2] +
+                                (pt == 0 ? bpr[c] : a.bp2[p0 + c]);
+              const int32_t hq = sat8(rescale_ge32(s, Mp, rp) + zp_h);
+              pk |= (uint32_t)(hq & 0xFF) << (8 * c);
+            }
+            if (orow < a.B && p0 < a.H) {
+              int8_t *od = a.out + ((size_t)t * a.B + orow) * a.Hpad + p0;
+              if (p0 + 3 < a.H) {
+                *reinterpret_cast<uint32_t *>(od) = pk;
+              } else {
+                for (int c = 0; c < 4 && p0 + c < a.H; ++c) od[c] = (int8_t)(pk >> (8 * c));
+              }
+              if (a.y) {
+                int8_t *yd = a.y + ((size_t)t * a.B + orow) * a.H + p0;
+                for (int c = 0; c < 4 && p0 + c < a.H; ++c) yd[c] = (int8_t)(pk >> (8 * c));
+              }
+            }
+          }
+          __syncthreads();
+        }
+      }
+      TICK(8);
+      if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, flag)) return;
+      TICK(9);
+    }
+  }
+#undef TICK
+
+  if (a.c_out) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl) {
+        const int row = row0 + rt * 32 + col;
+        const int n0 = member * 64 + cell_w + tl * 8;
+        if (row < a.B && n0 < a.N)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) a.c_out[(size_t)row * a.N + n0 + c] = (int16_t)creg[rt][tl][c];
+      }
+  }
+}
+
+
+typedef void (*rec_fn)(RecArgs);
+
+// kernel for (rt, flags & 7) at k depth KS
+template <int KS>
+rec_fn rec_pick_ks(int rt, int fl) {
+#define LSTM_REC_CASE(R, F) \
+  if (rt == R && fl == F) return rec_kernel<KS, R, F>;
+  LSTM_REC_CASE(1, 0) LSTM_REC_CASE(1, 1) LSTM_REC_CASE(1, 2) LSTM_REC_CASE(1, 3)
+  LSTM_REC_CASE(1, 4) LSTM_REC_CASE(1, 5) LSTM_REC_CASE(1, 6) LSTM_REC_CASE(1, 7)
+  if (KS < 32) {
+    LSTM_REC_CASE(2, 0) LSTM_REC_CASE(2, 1) LSTM_REC_CASE(2, 2) LSTM_REC_CASE(2, 3)
+    LSTM_REC_CASE(2, 4) LSTM_REC_CASE(2, 5) LSTM_REC_CASE(2, 6) LSTM_REC_CASE(2, 7)
+  }
+#undef LSTM_REC_CASE
+  return nullptr;
+}
+
+}  // namespace lstm_int

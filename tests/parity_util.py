@@ -54,8 +54,11 @@ def run_and_compare(orc, layers, x, name, trace=True, rows=None, with_state=True
         hs = torch.cat([torch.full((B * d[2],), lib_model.get_quant(l)["zp_h"], dtype=torch.int8)
                         for l, d in enumerate(dims)]).cuda()
         cs = torch.zeros(sum(B * d[1] for d in dims), dtype=torch.int16).cuda()
-    y = lib_model.forward(xd, h_state=hs, c_state=cs)
+    # a workspace full of garbage: nothing may depend on what a previous call left behind
+    ws = torch.randint(-128, 128, (lib_model.workspace_bytes(T, B),), dtype=torch.int8, device="cuda").view(torch.uint8)
+    y = lib_model.forward(xd, h_state=hs, c_state=cs, workspace=ws)
     torch.cuda.synchronize()
+    assert lib_model.device_status() == 0, "a wait inside the persistent kernel gave up"
     y = y.cpu().numpy()
     sel = list(range(B)) if rows is None else list(rows)
     xs = np.ascontiguousarray(xq[:, sel])

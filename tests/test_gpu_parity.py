@@ -80,8 +80,9 @@ def test_split_sequence_carries_state(orc):
     hs = torch.cat([torch.full((B * d[2],), lib_model.get_quant(l)["zp_h"], dtype=torch.int8)
                     for l, d in enumerate(dims)]).cuda()
     cs = torch.zeros(sum(B * d[1] for d in dims), dtype=torch.int16).cuda()
-    ya = lib_model.forward(xd[:5].contiguous(), h_state=hs, c_state=cs)
-    yb = lib_model.forward(xd[5:].contiguous(), h_state=hs, c_state=cs)
+    junk = lambda T: torch.randint(0, 256, (lib_model.workspace_bytes(T, B),), dtype=torch.uint8, device="cuda")
+    ya = lib_model.forward(xd[:5].contiguous(), h_state=hs, c_state=cs, workspace=junk(5))
+    yb = lib_model.forward(xd[5:].contiguous(), h_state=hs, c_state=cs, workspace=junk(7))
     torch.cuda.synchronize()
     assert_equal("split", torch.cat([ya, yb]).cpu().numpy(), y.cpu().numpy())
     assert_equal("split vs oracle", y.cpu().numpy(), orc.forward(orc_model, xq))

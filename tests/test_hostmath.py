@@ -27,6 +27,13 @@ def hm():
     L.hm_tanh_table.argtypes = [C.c_int, C.c_void_p]
     L.hm_sigmoid.argtypes = [C.c_void_p, C.c_int32]
     L.hm_tanh.argtypes = [C.c_void_p, C.c_int32]
+    L.hm_layernorm2.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    L.hm_cell_update32.argtypes = [C.c_int32] * 5
+    L.hm_compress.argtypes = [C.c_void_p, C.c_void_p]
+    L.hm_sigmoid_lut.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32]
+    L.hm_tanh_lut.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32]
+    L.hm_rescale_ge32.restype = C.c_int32
+    L.hm_rescale_ge32.argtypes = [C.c_int32] * 3
     L.hm_cell_update.argtypes = [C.c_int32] * 5
     L.hm_hidden.argtypes = [C.c_int32] * 5
     return L
@@ -48,6 +55,36 @@ def test_rescale_forms(orc, hm):
                 assert hm.hm_rescale(a, M, 31 - e) == orc.rescale(a, M, e)
                 if 31 - e >= 33:
                     assert hm.hm_rescale_hi(a, M, 31 - e) == orc.rescale(a, M, e)
+
+
+def test_rescale_ge32(orc, hm):
+    rnd = random.Random(9)
+    for _ in range(40000):
+        a = rnd.randrange(-2**31, 2**31)
+        M = rnd.randrange(2**30, 2**31)
+        e = rnd.randrange(-31, 0)  # r = 31 - e >= 32
+        assert hm.hm_rescale_ge32(a, M, 31 - e) == orc.rescale(a, M, e), (a, M, e)
+    for a in list(range(-5, 6)) + [2**31 - 1, -2**31, 2**30, -2**30]:
+        for M in (2**30, 2**31 - 1, 2**30 + 1):
+            assert hm.hm_rescale_ge32(a, M, 32) == orc.rescale(a, M, -1)
+
+
+@pytest.mark.parametrize("m", range(0, 9))
+def test_compressed_tables_exhaustive(orc, hm, m):
+    """The LDS form of the tables (8-bit deltas on block bases, full table
+    beyond the compressed domain) returns the oracle's value for every input."""
+    for kind in ("sigmoid", "tanh"):
+        tab = np.zeros(32769, np.uint16)
+        getattr(hm, f"hm_{kind}_table")(m, tab.ctypes.data)
+        blob = np.zeros(16384 + 2 * 2048, np.uint8)
+        sh = hm.hm_compress(tab.ctypes.data, blob.ctypes.data)
+        assert sh in (-1, 3, 4, 5, 6)
+        if m == 3:
+            assert sh >= 3  # the gate formats always compress
+        f = getattr(hm, f"hm_{kind}_lut")
+        want = orc.int_sigmoid if kind == "sigmoid" else orc.int_tanh
+        for x in list(range(-32768, 32768, 3)) + [-16385, -16384, -16383, 16383, 16384, 16385, 32767]:
+            assert f(tab.ctypes.data, blob.ctypes.data, sh, x) == want(x, m), (kind, m, x)
 
 
 def test_isqrt(orc, hm):
@@ -101,6 +138,10 @@ def test_layernorm_matches_oracle(orc, hm):
         got = np.zeros(n, np.int16)
         hm.hm_layernorm(q.ctypes.data, n, qL.ctypes.data, qb.ctypes.data, M, 31 - e, got.ctypes.data)
         assert (got == want).all(), (trial, n, kind)
+        if e <= -1:  # the per-row-prepared form needs a second-stage shift >= 32
+            got2 = np.zeros(n, np.int16)
+            hm.hm_layernorm2(q.ctypes.data, n, qL.ctypes.data, qb.ctypes.data, M, 31 - e, got2.ctypes.data)
+            assert (got2 == want).all(), (trial, n, kind)
 
 
 def test_cell_update_and_hidden(orc, hm):
@@ -113,6 +154,7 @@ def test_cell_update_and_hidden(orc, hm):
         for i, z, f, c in cases:
             want = max(-32768, min(32767, orc.rsh_r(i * z, 15 + m_c) + orc.rsh_r(f * c, 15)))
             assert hm.hm_cell_update(i, z, f, c, m_c) == want
+            assert hm.hm_cell_update32(i, z, f, c, m_c) == want
     for _ in range(5000):
         o, tc = rnd.randrange(0, 32768), rnd.randrange(-32768, 32768)
         M, e, zp = rnd.randrange(2**30, 2**31), rnd.randrange(-26, -18), rnd.randrange(-128, 128)
