@@ -21,20 +21,31 @@ PEAK_INT8_TOPS = 5000.0  # MI355X dense int8 MFMA, TOP/s (published)
 PEAK_HBM_GBS = 8000.0  # MI355X HBM3E, GB/s (published)
 
 
-def algorithmic_work(q, B, T):
-    """Per-launch algorithmic int8 ops / bytes of each kernel class for one
-    layer (what the operation must move or multiply at the storage types the
-    method fixes: int8 weights and activations, int16 gate terms and cell)."""
+def algorithmic_work(q, B, T, persistent):
+    """Algorithmic int8 ops / bytes of each kernel class for one layer: what the
+    operation must move or multiply at the storage types the method fixes (int8
+    weights and activations, int16 gate terms and cell state)."""
     I, N, H, G = q["I"], q["N"], q["H"], q["G"]
     proj = bool(q["flags"] & 8)
-    return {
+    Hout = H
+    w = {
         # one launch covers all T*B rows
-        "input_gemm": {"ops": 2.0 * T * B * G * N * I, "bytes": G * N * I + T * B * I + 2.0 * T * B * G * N},
-        # one launch per step
-        "recurrent": {"ops": 2.0 * B * G * N * H, "bytes": G * N * H + B * H + 2.0 * B * G * N},
-        "cell": {"ops": 0.0, "bytes": 2.0 * B * G * N * 2 + 4.0 * B * N + B * N},
-        "projection": {"ops": 2.0 * B * H * N if proj else 0.0, "bytes": (H * N + B * N + B * H) if proj else 0.0},
+        "input_gemm": {"ops": 2.0 * T * B * G * N * I, "bytes": G * N * I + T * B * I + 2.0 * T * B * G * N,
+                       "launches": 1},
     }
+    if persistent:
+        # one launch runs all T steps; per step: weights once, W x terms, cell
+        # state in and out, h in, h out
+        step = G * N * H + (Hout * N if proj else 0) + 2.0 * B * G * N + 4.0 * B * N + B * H + B * Hout
+        ops = 2.0 * B * (G * N * H + (Hout * N if proj else 0))
+        w["recurrent"] = {"ops": ops * T, "bytes": step * T, "launches": 1}
+    else:
+        w["recurrent"] = {"ops": 2.0 * B * G * N * H * T, "bytes": (G * N * H + B * H + 2.0 * B * G * N) * T,
+                          "launches": T}
+        w["cell"] = {"ops": 0.0, "bytes": (2.0 * B * G * N * 2 + 4.0 * B * N + B * N) * T, "launches": T}
+        if proj:
+            w["projection"] = {"ops": 2.0 * B * H * N * T, "bytes": (H * N + B * N + B * H) * T, "launches": T}
+    return w
 
 
 def main():
@@ -44,6 +55,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--path", type=int, default=0, help="0 auto, 1 one launch per operation and step")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="only run a plain device copy of MIB MiB (a known-size reference for rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (batch rows would shard across GPUs "
@@ -56,11 +70,22 @@ def main():
     from paper_2101_05453_amd import binding, calibration
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": n, "copies": 3}))
+        return
     binding.lib()
     cfg = wl.CONFIGS[args.config]
     layers, x = wl.make_workload(args.config)
     calibration.collect_statistics(layers, x)  # statistics from the first 16 rows (Sec. 4)
     model = binding.prepare(layers, device=0)
+    model.set_option("path", args.path)
     L = model.num_layers
     quants = [model.get_quant(l) for l in range(L)]
     xq = calibration.quantize_input(x, quants[0]["s_x"], quants[0]["zp_x"])
@@ -89,28 +114,23 @@ def main():
     for _ in range(args.steps):
         step()
     prof = model.profile_end()
-    work = {k: {"ops": 0.0, "bytes": 0.0, "launches": 0} for k in ("input_gemm", "recurrent", "cell", "projection")}
+    persistent = prof["cell"]["launches"] == 0  # the per-step path launches a cell kernel per step
+    work = {}
     for q in quants:
-        w = algorithmic_work(q, B, T)
-        for k in work:
-            n = 1 if k == "input_gemm" else T
-            if k == "projection" and not (q["flags"] & 8):
-                n = 0
-            work[k]["ops"] += w[k]["ops"] * n
-            work[k]["bytes"] += w[k]["bytes"] * n
-            work[k]["launches"] += n
+        for k, v in algorithmic_work(q, B, T, persistent).items():
+            e = work.setdefault(k, {"ops": 0.0, "bytes": 0.0, "launches": 0})
+            for f in e:
+                e[f] += v[f]
     kernels = {}
     for k, w in work.items():
         p = prof[k]
         if not p["launches"]:
             continue
-        avg_ms = p["total_ms"] / p["launches"]
-        ent = {"launches_per_step": w["launches"], "avg_us": avg_ms * 1e3,
-               "ms_per_step": p["total_ms"] / args.steps}
-        if w["launches"]:
-            ent["gbps"] = w["bytes"] / w["launches"] / (avg_ms * 1e-3) / 1e9
-            ent["tops"] = w["ops"] / w["launches"] / (avg_ms * 1e-3) / 1e12
-        kernels[k] = ent
+        per_step_ms = p["total_ms"] / args.steps
+        kernels[k] = {"launches_per_step": p["launches"] // args.steps, "avg_us": p["total_ms"] / p["launches"] * 1e3,
+                      "ms_per_step": per_step_ms,
+                      "gbps": w["bytes"] / (per_step_ms * 1e-3) / 1e9,
+                      "tops": w["ops"] / (per_step_ms * 1e-3) / 1e12}
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     d = kernels[dominant]
     if dominant == "input_gemm":
@@ -119,7 +139,8 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": d["gbps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": d["gbps"] / PEAK_HBM_GBS}
-    roof.update({"kernel": dominant, "avg_launch_us": d["avg_us"], "traffic": None, "kernels": kernels})
+    roof.update({"kernel": dominant, "avg_launch_us": d["avg_us"], "traffic": None,
+                 "path": "persistent" if persistent else "per-step", "kernels": kernels})
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):  # HBM bytes per launch from rocprofv3 --pmc runs (see profiles/)
         rec = json.load(open(tpath)).get(args.config, {}).get(dominant)
@@ -142,17 +163,27 @@ def main():
         import oracle
 
         cores = min(oracle.max_threads(), 16, B)
-        Ts = min(T, 16)
         om = oracle.prepare(layers)
-        xs = np.ascontiguousarray(xq[:Ts, :cores])
+        probe_T = min(T, 4)
+        t0 = time.perf_counter()
+        oracle.forward(om, np.ascontiguousarray(xq[:probe_T, :cores]), threads=cores)
+        rate = cores * probe_T * L / (time.perf_counter() - t0)  # cell-steps/s of the probe
+        # about 15 s of work: whole sequences of as many rows as that allows (multiples of the thread count)
+        rows = int(max(cores, min(B, (15.0 * rate / (T * L)) // cores * cores)))
+        Ts = T if rows * T * L <= 30.0 * rate else max(1, int(15.0 * rate / (rows * L)))
+        xs = np.ascontiguousarray(xq[:Ts, :rows])
         t0 = time.perf_counter()
         oracle.forward(om, xs, threads=cores)
         dto = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": cores * Ts * L / dto, "unit": "cell-steps/s", "cores": cores,
+        out["cpu_baseline"] = {"value": rows * Ts * L / dto, "unit": "cell-steps/s", "cores": cores,
                                "kind": "oracle",
-                               "sample": f"first {cores} batch rows x first {Ts} steps x {L} layers of "
+                               "sample": f"first {rows} batch rows x first {Ts} steps x {L} layers of "
                                          f"{args.config}, {dto:.1f} s"}
-    print(json.dumps(out))
+    print(json.dumps(out), flush=True)
+    # release device objects in order before the interpreter tears down
+    del xd, y, ws
+    model.destroy()
+    torch.cuda.synchronize()
 
 
 if __name__ == "__main__":

@@ -163,9 +163,9 @@ class Model:
         self.destroy()
 
     def destroy(self):
-        if getattr(self, "_h", None):
-            lib().lstm_int_destroy(self._h)
-            self._h = None
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.lstm_int_destroy(self._h)
+        self._h = None
 
     # lstm_int_get_quant
     def get_quant(self, layer):
