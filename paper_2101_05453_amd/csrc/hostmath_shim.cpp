@@ -33,7 +33,12 @@ void hm_layernorm2(const int16_t *q, int32_t n, const int16_t *qL, const int32_t
     s2 += (int64_t)q[i] * q[i];
   }
   const LnRow2 row = ln_row2(ln_row(s1, s2, n, 1.0 / (double)n));
-  for (int i = 0; i < n; ++i) out[i] = (int16_t)ln_apply2(q[i], row, (double)qL[i], (double)qb[i], M, r);
+  const RescaleHi p = rescale_hi_prepare(M, r);
+  for (int i = 0; i < n; ++i)
+    out[i] = (int16_t)ln_apply2(q[i], row, ln_weight_scaled(qL[i]), ln_bias_scaled(qb[i]), p);
+}
+int32_t hm_rescale_sat16_pre(int32_t a, int32_t M, int32_t r) {
+  return rescale_sat16_pre(a, rescale_hi_prepare(M, r));
 }
 int32_t hm_cell_update32(int32_t i, int32_t z, int32_t f, int32_t c, int32_t m_c) {
   return cell_update32(i, z, f, c, m_c);

@@ -9,6 +9,7 @@
 
 #include <math.h>
 #include <stdint.h>
+#include <string.h>
 
 #if defined(__HIPCC__)
 #include <hip/hip_runtime.h>
@@ -145,33 +146,79 @@ LSTM_HD int32_t ln_apply(int32_t q, const LnRow &row, int32_t qL, int32_t qb, in
   return sat16(rescale((int32_t)q2, M_ln, r_ln));
 }
 
-// The same element with the row's constants prepared once per row:
-//   c0 = -2^10 mean + floor(sigma/2), so that 2^20 q + c0 is the numerator.
+// The same element with everything that does not depend on it prepared ahead.
+// Per row:   c0 = -2^10 mean + floor(sigma/2) + 1/2, so that 2^20 q + c0 is the
+// numerator plus one half.  The numerator n is an integer, so no multiple of
+// sigma lies in (n, n + 1/2]: floor((n + 1/2) / sigma) = floor(n / sigma), and
+// (n + 1/2) / sigma stays at least 1/(2 sigma) away from every integer, while
+// its product with the rounded reciprocal is off by less than 2^-52 of a
+// quotient below 2^37 / sigma, i.e. by less than 2^-15 / sigma.  The floor of
+// that product is therefore exact and needs no remainder correction.  A row
+// with sigma = 0 has 1/sigma = 0 here, which gives q' = 0 as required.
+// Per cell:  qLs = qL / 2^10 and qbs = qb / 2^10 + 2^-11 (both exact), so that
+// one fused multiply-add gives (q' qL + qb) / 2^10 + 2^-11 exactly (44 bits).
+// That value is a multiple of 2^-10 plus 2^-11, never halfway between two
+// integers, and rounding it to the nearest integer is floor((q' qL + qb + 2^9)
+// / 2^10).  The rounding is done by adding 1.5 * 2^52, whose sum holds the
+// integer in its low mantissa bits; clamping to the int32 range first is the
+// same as clamping afterwards because the bounds are integers.
 struct LnRow2 {
-  double inv_sigma, c0, sigma;
-  int32_t nonzero, pad;
+  double inv_sigma, c0;
 };
 LSTM_HD LnRow2 ln_row2(const LnRow &r) {
   LnRow2 o;
-  o.inv_sigma = r.inv_sigma;
-  o.c0 = (double)(-(int64_t)r.mean * 1024 + (r.sigma >> 1));
-  o.sigma = (double)r.sigma;
-  o.nonzero = r.sigma != 0;
-  o.pad = 0;
+  o.inv_sigma = r.sigma ? r.inv_sigma : 0.0;
+  o.c0 = (double)(-(int64_t)r.mean * 1024 + (r.sigma >> 1)) + 0.5;
   return o;
 }
-// Requires the second-stage shift r_ln >= 32.  qL, qb are the layer-norm
-// weight and bias of the cell as doubles (exact: 16 and 32 bit integers).
-LSTM_HD int32_t ln_apply2(int32_t q, const LnRow2 &row, double qL, double qb, int32_t M_ln, int32_t r_ln) {
+LSTM_HD double ln_weight_scaled(int32_t qL) { return (double)qL * (1.0 / 1024.0); }
+LSTM_HD double ln_bias_scaled(int32_t qb) { return (double)qb * (1.0 / 1024.0) + (1.0 / 2048.0); }
+// Second-stage rescale constants for a shift r >= 32 (a is below 2^31 in
+// magnitude after the shift by k = 33 - r <= 1 only if |a| < 2^30; the
+// layer-norm value that is not, saturates the 16-bit result either way, see
+// rescale_sat16_pre).
+struct RescaleHi {
+  int32_t M, add, sh, k;  // k: left shift of the operand; add = 2^(r + k - 33); sh = r + k - 32
+};
+LSTM_HD RescaleHi rescale_hi_prepare(int32_t M, int32_t r) {
+  RescaleHi o;
+  o.M = M;
+  o.k = r < 33 ? 33 - r : 0;
+  o.add = (int32_t)1 << (r + o.k - 33);
+  o.sh = r + o.k - 32;
+  return o;
+}
+// sat16(rescale(a, M, r)) for 3 <= r <= 62 from the high word of one 32-bit
+// product.  For r >= 33 this is rescale_hi.  For r < 33 the operand is shifted
+// left by k = 33 - r first, which is exact if |a| < 2^(31-k); a larger |a| is
+// clamped to [-2^(31-k), 2^(31-k) - 1] before, which does not change the saturated result:
+// (2^(31-k) - 1) * M / 2^r >= (2^31 - 2^k) 2^30 / 2^33 = 2^28 - 2^(k-3) > 2^15 for k <= 30.
+LSTM_HD int32_t rescale_sat16_pre(int32_t a, const RescaleHi &p) {
+  const int32_t lim = (int32_t)(0x7FFFFFFFu >> p.k);
+  a = clamp_i32(a, -lim - 1, lim) << p.k;
+#if defined(__HIP_DEVICE_COMPILE__)
+  const int32_t hi = __mulhi(a, p.M);
+#else
+  const int32_t hi = (int32_t)(((int64_t)a * (int64_t)p.M) >> 32);
+#endif
+  return sat16((hi + p.add) >> p.sh);
+}
+LSTM_HD int32_t f64_low_word(double w) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __double2loint(w);
+#else
+  int64_t bits;
+  memcpy(&bits, &w, 8);
+  return (int32_t)bits;
+#endif
+}
+LSTM_HD int32_t ln_apply2(int32_t q, const LnRow2 &row, double qLs, double qbs, const RescaleHi &p) {
   const double num = fma((double)q, 1048576.0, row.c0);
-  double qn = floor(num * row.inv_sigma);
-  const double rem = fma(-qn, row.sigma, num);
-  qn += rem < 0.0 ? -1.0 : (rem >= row.sigma ? 1.0 : 0.0);
-  qn = row.nonzero ? qn : 0.0;
-  const double t = fma(qn, qL, qb);
-  double q2 = floor(fma(t, 1.0 / 1024.0, 0.5));  // floor((t + 512) / 1024), exact
-  q2 = q2 < -2147483648.0 ? -2147483648.0 : (q2 > 2147483647.0 ? 2147483647.0 : q2);
-  return sat16(rescale_ge32((int32_t)q2, M_ln, r_ln));
+  const double qn = floor(num * row.inv_sigma);
+  double v = fma(qn, qLs, qbs);
+  v = fmin(fmax(v, -2147483648.0), 2147483647.0);
+  const int32_t q2 = f64_low_word(v + 6755399441055744.0);
+  return rescale_sat16_pre(q2, p);
 }
 
 // Cell update with 32-bit intermediates: |i z| <= 2^30 and the rounding terms

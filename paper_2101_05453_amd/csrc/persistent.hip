@@ -32,7 +32,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned long long u64;
 
 constexpr int kLdsRow = 80;  // 64 data bytes + 16 pad
-constexpr int kPrmLdsBytes = 128;  // sizeof(PrmLds) in rec_kernel.inc.h
+constexpr int kPrmLdsBytes = 192;  // sizeof(PrmLds) in rec_kernel.inc.h
 
 // ---------------------------------------------------------------------------
 // Input GEMM: block = 128 (t,b) rows x 4 weight tiles (32 cells), 4 waves 2x2,
@@ -184,10 +184,10 @@ bool rec_supported(int N, int H, int flags, int B, int *ks, int *rt, int *groups
 size_t rec_lds_bytes(const RecArgs &a) {
   const int items = (a.rows_pg / 32) * 128;
   const bool proj = a.flags & 8;
-  size_t tile = (size_t)a.rows_pg * (a.ks * 32 + 16);
+  size_t tile = ((size_t)a.rows_pg * (a.ks * 32 + 16) + 1023) / 1024 * 1024;
   if (proj && tile < 4 * 16 * 64 * 4) tile = 4 * 16 * 64 * 4;
   size_t n = tile + (size_t)4 * items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 2 +
-             kPrmLdsBytes + 32;
+             kPrmLdsBytes + 16 + 16 * 8;
   n += (a.tanhc_blob != a.tanh_blob ? 3 : 2) * (size_t)kLutBlobBytes;
   if (proj) {
     const int per_cu = (a.ptiles + a.GS - 1) / a.GS;

@@ -46,12 +46,14 @@ __device__ __forceinline__ bool group_sync(unsigned *counter, unsigned &epoch, i
 
 // Per-layer constants, kept in LDS and read where they are used: as kernel
 // arguments they would all be live in scalar registers across the time loop.
-struct PrmLds {  // 128 bytes (kPrmLdsBytes in persistent.hip)
-  int32_t Mh[4], rh[4], Mc[4], rc[4], Mln[4], rln[4];
+struct PrmLds {  // 192 bytes (kPrmLdsBytes in persistent.hip)
+  int32_t Mh[4], rh[4], Mc[4], rc[4];
+  RescaleHi ln[4];
   int32_t Mm, rm, zp_m, Mp, rp, zp_h, m_c, glo;
+  int32_t pad[8];
 };
 
-static_assert(sizeof(PrmLds) == 128, "rec_lds_bytes assumes 128 bytes");
+static_assert(sizeof(PrmLds) == 192, "rec_lds_bytes assumes 192 bytes");
 
 // |x| -> table value from the compressed copy in LDS; `a` must be below kLutDomain
 __device__ __forceinline__ int32_t lut_lds(const uint8_t *blob, int sh, int32_t a) {
@@ -70,7 +72,7 @@ __device__ __forceinline__ int32_t mirror_tanh(int32_t x, int32_t t) {
 // FL: bit 0 CIFG, bit 1 peephole, bit 2 layer norm (compile time, so that the
 // per-element code carries no tests of them); the projection is a runtime flag.
 template <int KS, int RT, int FL>
-__global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void rec_kernel(RecArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, b2 = lane >> 5;
@@ -99,17 +101,18 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
   int8_t *hT = reinterpret_cast<int8_t *>(p);
   int32_t *pred = reinterpret_cast<int32_t *>(p);  // projection partials reuse the h tile between steps
   {
-    const size_t tile_bytes = (size_t)rows_pg * LS, pred_bytes = proj ? 4 * 16 * 64 * 4 : 0;
+    const size_t tile_bytes = ((size_t)rows_pg * LS + 1023) / 1024 * 1024;  // whole 1 KB wave chunks
+    const size_t pred_bytes = proj ? 4 * 16 * 64 * 4 : 0;
     p += tile_bytes > pred_bytes ? tile_bytes : pred_bytes;
   }
   u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)4 * items * 8;
   LnRow2 *lnrow = reinterpret_cast<LnRow2 *>(p);         p += (size_t)items * sizeof(LnRow2);
-  double *LdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;  // layer-norm weights as doubles
-  double *bdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;  // layer-norm biases as doubles
+  double *LdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;  // layer-norm weights / 2^10 as doubles
+  double *bdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;  // layer-norm biases / 2^10 + 2^-11 as doubles
   int16_t *PqL = reinterpret_cast<int16_t *>(p);         p += 4 * 64 * 2;  // 3 used
   PrmLds *prm = reinterpret_cast<PrmLds *>(p);           p += sizeof(PrmLds);
   int *flag = reinterpret_cast<int *>(p);                p += 16;
-  const int dump_off = (int)(p - lds);                   p += 16;  // sink for staging chunks outside the tile
+  u64 *tickL = reinterpret_cast<u64 *>(p);               p += 16 * 8;  // phase timers
   // compressed sigma / tanh tables (lstm_int_math.h); the cell-format tanh shares the gate one if equal
   const bool share_tanh = a.tanhc_blob == a.tanh_blob;
   const uint8_t *lutS = p;                               p += kLutBlobBytes;
@@ -131,6 +134,7 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
       for (int ks = 0; ks < KS; ++ks) {
         const int4 w = src[(size_t)(tl * KS + ks) * 64];
         Wf[tl][ks] = v4i{w.x, w.y, w.z, w.w};
+        asm volatile("" : "+a"(Wf[tl][ks]));  // resident in accumulation registers for the whole launch
       }
   }
   const int cell_w = wave * 16 + 4 * b2;  // + tile * 8 + c, within the workgroup's 64 cells
@@ -145,14 +149,14 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
   {
     const int g = tid >> 6, n = tid & 63;  // 256 threads = 4 gates x 64 cells
     const size_t idx = (size_t)g * a.Ncp + member * 64 + n;
-    LdL[tid] = ln ? (double)a.Lq4[idx] : 0.0;
-    bdL[tid] = ln ? (double)a.qb4[idx] : 0.0;
+    LdL[tid] = ln ? ln_weight_scaled(a.Lq4[idx]) : 0.0;
+    bdL[tid] = ln ? ln_bias_scaled(a.qb4[idx]) : 0.0;
     PqL[tid] = (ph && g < 3) ? a.Pq3[idx] : 0;
   }
   if (tid < 4) {
     prm->Mh[tid] = a.Mh[tid]; prm->rh[tid] = a.rh[tid];
     prm->Mc[tid] = tid < 3 ? a.Mc[tid] : 0; prm->rc[tid] = tid < 3 ? a.rc[tid] : 32;
-    prm->Mln[tid] = a.Mln[tid]; prm->rln[tid] = a.rln[tid];
+    prm->ln[tid] = rescale_hi_prepare(a.Mln[tid], ln ? a.rln[tid] : 33);
   }
   if (tid == 0) {
     prm->Mm = a.Mm; prm->rm = a.rm; prm->zp_m = a.zp_m;
@@ -189,19 +193,21 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
         creg[rt][tl][c] = (a.c_in && row < a.B && n0 + c < a.N) ? a.c_in[(size_t)row * a.N + n0 + c] : 0;
     }
 
-  // h tile staging: chunk j of this thread is 16 bytes of one tile row
-  constexpr int CPR = KS * 2;                       // 16-byte chunks per tile row
-  constexpr int NCH = (RT * 32 * CPR + 255) / 256;  // chunks per thread
-  int hsrc[NCH], hdst[NCH];  // byte offsets; chunks outside the tile read offset 0 and land in a dump slot
+  // h tile staging by global -> LDS loads (no registers in between): wave
+  // instruction (wave + 4 j) fills bytes [1024 c, 1024 (c + 1)) of the tile,
+  // lane l its 16 bytes at 16 l; the lane's source is wherever that byte range
+  // falls in the padded [row][LS] tile (pad bytes and the tail read offset 0
+  // and hold garbage that only ever meets zero weights)
+  constexpr int TILE_KB = (rows_pg * LS + 1023) / 1024;
+  constexpr int NCH = (TILE_KB + 3) / 4;  // chunks per wave
+  int hsrc[NCH];
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    const int i = tid + j * 256;
-    const int r = i / CPR, c = i - r * CPR;
+    const int o = (wave + 4 * j) * 1024 + lane * 16;
+    const int r = o / LS, c = o - r * LS;
     int row = row0 + r;
     row = row < a.B ? row : a.B - 1;
-    const bool valid = r < rows_pg && (c << 4) < a.Hpad;
-    hsrc[j] = valid ? row * a.Hpad + (c << 4) : 0;
-    hdst[j] = valid ? r * LS + (c << 4) : dump_off;
+    hsrc[j] = (r < rows_pg && c < a.Hpad) ? row * a.Hpad + c : 0;
   }
 
   // projection bias of this thread's four outputs of its first tile
@@ -211,6 +217,7 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
     bpr[0] = b4.x; bpr[1] = b4.y; bpr[2] = b4.z; bpr[3] = b4.w;
   }
 
+  if (tid < 16) tickL[tid] = 0;
   __syncthreads();  // LDS contents above are in place before the first step
 
   unsigned epoch = 0;
@@ -220,18 +227,22 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
   const double inv_n = 1.0 / (double)a.N;
   const int g_first = cifg ? 1 : 0;
 
-  // optional phase timing of workgroup 0 (diagnostics): 100 MHz wall clock ticks per phase
+  // optional phase timing of workgroup 0 (diagnostics): 100 MHz wall clock
+  // ticks per phase, summed in LDS (an add that returns nothing, so the timer
+  // waits for no memory) and written out after the last step
   long long tick_last = 0;
-#define TICK(i)                                            \
-  do {                                                     \
-    if (a.ticks && wg == 0 && tid == 0) {                  \
-      asm volatile("" ::: "memory");                       \
-      const long long now = (long long)wall_clock64();     \
-      a.ticks[i] += now - tick_last;                       \
-      tick_last = now;                                     \
-    }                                                      \
+  const bool timing = a.ticks && wg == 0 && tid == 0;
+#define TICK(i)                                                                           \
+  do {                                                                                    \
+    if (timing) {                                                                         \
+      asm volatile("" ::: "memory");                                                      \
+      const long long now = (long long)wall_clock64();                                    \
+      __hip_atomic_fetch_add(&tickL[i], (u64)(now - tick_last), __ATOMIC_RELAXED,         \
+                             __HIP_MEMORY_SCOPE_WORKGROUP);                               \
+      tick_last = now;                                                                    \
+    }                                                                                     \
   } while (0)
-  if (a.ticks && wg == 0 && tid == 0) tick_last = (long long)wall_clock64();
+  if (timing) tick_last = (long long)wall_clock64();
 
   // the two 16-byte W x pieces of (rt, tile) for step t
   auto tx_ptr = [&](int t, int rt, int tl) -> const int4 * {
@@ -246,12 +257,15 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
     // ---- h^{t-1} rows of the group -> LDS; W x terms of this step -> registers
     {
       const int8_t *hp = t == 0 ? a.h0 : a.out + (size_t)(t - 1) * a.B * a.Hpad;
-      int4 hv[NCH];
 #pragma unroll
-      for (int j = 0; j < NCH; ++j) hv[j] = *reinterpret_cast<const int4 *>(hp + hsrc[j]);
-#pragma unroll
-      for (int j = 0; j < NCH; ++j) *reinterpret_cast<int4 *>(lds + hdst[j]) = hv[j];
+      for (int j = 0; j < NCH; ++j)
+        if (wave + 4 * j < TILE_KB)
+          __builtin_amdgcn_global_load_lds(
+              (const __attribute__((address_space(1))) void *)(hp + hsrc[j]),
+              (__attribute__((address_space(3))) void *)(lds + (wave + 4 * j) * 1024), 16, 0, 0);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
+    __syncthreads();
     int4 txv[RT][2][2];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
@@ -261,7 +275,6 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
         txv[rt][tl][0] = src[0];
         txv[rt][tl][1] = src[64];
       }
-    __syncthreads();
     TICK(0);
 
     // ---- R h on the MFMA: acc[rt][tile][4*gate + c]
@@ -272,14 +285,29 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
       for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[rt][tl][v] = 0;
+    {
+      constexpr int DEPTH = 4;  // h fragments in flight ahead of the MFMAs
+      v4i hf[RT][DEPTH];
+      const int8_t *hbase = hT + (size_t)col * LS + (b2 << 4);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+      for (int ks = 0; ks < DEPTH && ks < KS; ++ks)
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        const v4i hf = *reinterpret_cast<const v4i *>(hT + (size_t)(rt * 32 + col) * LS + ks * 32 + (b2 << 4));
+        for (int rt = 0; rt < RT; ++rt)
+          hf[rt][ks] = *reinterpret_cast<const v4i *>(hbase + (size_t)rt * 32 * LS + ks * 32);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int tl = 0; tl < 2; ++tl)
-          acc[rt][tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Wf[tl][ks], hf, acc[rt][tl], 0, 0, 0);
+      for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+          for (int tl = 0; tl < 2; ++tl)
+            acc[rt][tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Wf[tl][ks], hf[rt][ks % DEPTH], acc[rt][tl], 0, 0, 0);
+          if (ks + DEPTH < KS)
+            hf[rt][ks % DEPTH] = *reinterpret_cast<const v4i *>(hbase + (size_t)rt * 32 * LS + (ks + DEPTH) * 32);
+        }
+        // keep the LDS reads DEPTH iterations ahead of their MFMAs: without
+        // this the instruction scheduler sinks each read next to its use
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     TICK(1);
@@ -375,8 +403,8 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
       const int32_t v = acc[rt][tl][g * 4 + c];
       if (!ln) return v;
       const int cl = cell_w + tl * 8 + c;
-      return ln_apply2(v, lnrow[(rt * 4 + g) * 32 + col], LdL[g * 64 + cl], bdL[g * 64 + cl], prm->Mln[g],
-                       prm->rln[g]);
+      return ln_apply2(v, lnrow[(rt * 4 + g) * 32 + col], LdL[g * 64 + cl], bdL[g * 64 + cl],
+                       prm->ln[g]);
     };
     int32_t xi[RT][2][4], xf[RT][2][4], xz[RT][2][4], xo[RT][2][4];
 #pragma unroll
@@ -615,6 +643,8 @@ __global__ __launch_bounds__(256) void rec_kernel(RecArgs a) {
     }
   }
 #undef TICK
+  if (timing)
+    for (int i = 0; i < 16; ++i) a.ticks[i] += (long long)tickL[i];
 
   if (a.c_out) {
 #pragma unroll

@@ -29,6 +29,8 @@ def hm():
     L.hm_tanh.argtypes = [C.c_void_p, C.c_int32]
     L.hm_layernorm2.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     L.hm_cell_update32.argtypes = [C.c_int32] * 5
+    L.hm_rescale_sat16_pre.argtypes = [C.c_int32] * 3
+    L.hm_rescale_sat16_pre.restype = C.c_int32
     L.hm_compress.argtypes = [C.c_void_p, C.c_void_p]
     L.hm_sigmoid_lut.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32]
     L.hm_tanh_lut.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32]
@@ -133,15 +135,37 @@ def test_layernorm_matches_oracle(orc, hm):
         n = int(rng.choice([1, 2, 3, 17, 64, 512, 1000, 2048, 4096]))
         kind = ["normal", "extreme", "spike", "near_constant", "constant"][trial % 5]
         q, qL, qb = _ln_case(rng, n, kind)
-        M, e = int(rng.integers(2**30, 2**31)), int(rng.integers(-12, 4))
+        M, e = int(rng.integers(2**30, 2**31)), int(rng.integers(-24, 4))
         want = orc.int_layernorm(q, qL, qb, M, e)
         got = np.zeros(n, np.int16)
         hm.hm_layernorm(q.ctypes.data, n, qL.ctypes.data, qb.ctypes.data, M, 31 - e, got.ctypes.data)
         assert (got == want).all(), (trial, n, kind)
-        if e <= -1:  # the per-row-prepared form needs a second-stage shift >= 32
+        if True:  # the per-row-prepared form used by the persistent kernel
             got2 = np.zeros(n, np.int16)
             hm.hm_layernorm2(q.ctypes.data, n, qL.ctypes.data, qb.ctypes.data, M, 31 - e, got2.ctypes.data)
             assert (got2 == want).all(), (trial, n, kind)
+
+
+def test_rescale_sat16_from_high_word(orc, hm):
+    # sat16(rescale(a, M, r)) from one 32-bit high product, with the operand
+    # shifted (and clamped) first when r < 33
+    rnd = random.Random(11)
+    edge = [-2**31, -2**31 + 1, -2**30 - 1, -2**30, -2**30 + 1, -65537, -32769, -32768, -2, -1, 0, 1, 2, 32767,
+            32768, 65536, 2**30 - 1, 2**30, 2**30 + 1, 2**31 - 2, 2**31 - 1]
+    for r in range(3, 63):
+        e = 31 - r
+        Ms = [2**30, 2**31 - 1, 2**30 + 1] + [rnd.randrange(2**30, 2**31) for _ in range(6)]
+        for M in Ms:
+            vals = edge + [rnd.randrange(-2**31, 2**31) for _ in range(40)]
+            # values around the saturation and rounding boundaries of this scale
+            for y in (-32769, -32768, -32767, -1, 0, 1, 32766, 32767, 32768):
+                a0 = (2 * y + 1) * 2**r // (2 * M)
+                vals += [a0 + d for d in (-2, -1, 0, 1, 2)]
+            for a in vals:
+                if not -2**31 <= a < 2**31:
+                    continue
+                want = max(-32768, min(32767, orc.rescale(a, M, e)))
+                assert hm.hm_rescale_sat16_pre(a, M, r) == want, (a, M, r)
 
 
 def test_cell_update_and_hidden(orc, hm):
