@@ -70,6 +70,7 @@ struct lstm_int_model {
   int path = 0;
   int spin_limit = 1 << 21;
   int phase_timing = 0;
+  int num_cus = 256;
   Profile prof;
 };
 
@@ -153,6 +154,9 @@ struct Timed {
 
 int upload(lstm_int_model *m) {
   if (hipSetDevice(m->device) != hipSuccess) return LSTM_INT_E_DEVICE;
+  if (hipDeviceGetAttribute(&m->num_cus, hipDeviceAttributeMultiprocessorCount, m->device) != hipSuccess ||
+      m->num_cus < 1)
+    return LSTM_INT_E_DEVICE;
   const size_t L = m->host.size();
   m->dev.resize(L);
 
@@ -327,7 +331,7 @@ int upload(lstm_int_model *m) {
   m->tanh3_blob = dbase + blob_off[3];
   m->sh_sig3 = sh_sig;
   m->sh_tanh3 = sh_tab[3];
-  if (rec_init() != hipSuccess) return LSTM_INT_E_DEVICE;
+  if (rec_init() != hipSuccess || in_gemm_init() != hipSuccess) return LSTM_INT_E_DEVICE;
   return LSTM_INT_OK;
 }
 
@@ -499,7 +503,10 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
           if (ga.r[g] < 32) ga.all_hi = 0;
         }
         ga.tx2 = reinterpret_cast<int4 *>(tx);
-        launch_in_gemm(s, ga);
+        if (in_gemm_ws_supported(ga))
+          launch_in_gemm_ws(s, ga, m->num_cus);
+        else
+          launch_in_gemm(s, ga);
       }
       // batch rows beyond one launch's groups run in further launches (rows never interact)
       for (int b0 = 0; b0 < B; b0 += p2_groups * ra.rows_pg) {

@@ -1,0 +1,292 @@
+// Input GEMM of the persistent path for gfx950 (MI355X): W x for every (t, b)
+// of a layer in one launch (the input contribution has no dependence on the
+// recurrence and is hoisted out of the time loop), rescaled to int16
+// (Secs. 3.2.4/3.2.5, zero point folded into the bias per Sec. 6) and stored
+// in the tile order the recurrent kernel reads (persistent.h).
+//
+// Weights stay put: a workgroup owns 8 weight tiles (256 weight rows = the 64
+// cells of one recurrent-kernel workgroup, 4 gates each), every wave keeps its
+// two tiles over the whole k depth in registers as MFMA operands, and the
+// workgroup streams over blocks of 32 (t, b) rows.  The activation block goes
+// global -> LDS without passing through registers, three blocks ahead; the MFMA
+// of block i runs interleaved with the requantization and the stores of block
+// i - 1, whose accumulators were copied out of the MFMA's registers.
+//
+// Work split: workgroup id -> (part, column block) with part = id % parts, so
+// that the workgroups of one part -- which read the same activation rows --
+// sit on the same XCDs and share their L2.
+#include "persistent.h"
+
+#include "lstm_int_math.h"
+
+namespace lstm_int {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef short v2s __attribute__((ext_vector_type(2)));
+
+namespace {
+
+// sat16(rescale(s, M, r)) of two values, packed; PRE = some shift is below 33
+template <bool PRE>
+__device__ __forceinline__ int32_t requant2(int32_t s0, int32_t s1, const RescaleHi &p0, const RescaleHi &p1) {
+  if (PRE) {
+    const int32_t l0 = (int32_t)(0x7FFFFFFFu >> p0.k), l1 = (int32_t)(0x7FFFFFFFu >> p1.k);
+    s0 = clamp_i32(s0, -l0 - 1, l0) << p0.k;
+    s1 = clamp_i32(s1, -l1 - 1, l1) << p1.k;
+  }
+  const int32_t v0 = (__mulhi(s0, p0.M) + p0.add) >> p0.sh;
+  const int32_t v1 = (__mulhi(s1, p1.M) + p1.add) >> p1.sh;
+  // both halves saturate to int16
+  const v2s pk = __builtin_amdgcn_cvt_pk_i16(v0, v1);
+  return __builtin_bit_cast(int32_t, pk);
+}
+
+template <int KS, bool PRE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void in_gemm_ws_kernel(InGemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  constexpr int LS = KS * 32 + 16;                      // activation row stride in LDS
+  constexpr int TILE_KB = (32 * LS + 1023) / 1024;      // one block of 32 rows, in 1 KB wave loads
+  constexpr int NCH = (TILE_KB + 3) / 4;                // loads per wave (the same for every wave)
+  constexpr int BUF = NCH * 4096;                       // one stage; bytes beyond the block are padding
+  constexpr int NST = 4;                                // stages: loads run three blocks ahead
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, b2 = lane >> 5;
+  const int part = blockIdx.x % a.parts, cb = blockIdx.x / a.parts;
+  const int nrb = (a.T * a.Bp) >> 5;
+  const int per = (nrb + a.parts - 1) / a.parts;
+  const int rb0 = part * per;
+  const int rb1 = rb0 + per < nrb ? rb0 + per : nrb;
+  if (rb0 >= rb1) return;  // the whole workgroup
+
+  // ---- this wave's two weight tiles, all of k, as MFMA operands
+  v4i Wf[2][KS];
+  int32_t bias[2][16];
+#pragma unroll
+  for (int tl = 0; tl < 2; ++tl) {
+    const int tile = cb * 8 + wave * 2 + tl;
+    const int8_t *wrow = a.W2 + ((size_t)tile * 32 + col) * a.kpad + (b2 << 4);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      // kpad is a multiple of 64: a 32-byte k step is inside the row or entirely beyond it
+      const int4 w = *reinterpret_cast<const int4 *>(wrow + (ks * 32 < a.kpad ? ks * 32 : 0));
+      const bool in = ks * 32 < a.kpad;
+      Wf[tl][ks] = v4i{in ? w.x : 0, in ? w.y : 0, in ? w.z : 0, in ? w.w : 0};
+      asm volatile("" : "+a"(Wf[tl][ks]));  // resident in accumulation registers for the whole launch
+    }
+    // the lane's 16 results of a tile: index 4*gate + c <-> tile row 8*gate + 4*(lane/32) + c
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int4 b4 = *reinterpret_cast<const int4 *>(a.bx2 + (size_t)tile * 32 + g * 8 + (b2 << 2));
+      bias[tl][g * 4 + 0] = b4.x; bias[tl][g * 4 + 1] = b4.y; bias[tl][g * 4 + 2] = b4.z; bias[tl][g * 4 + 3] = b4.w;
+    }
+  }
+  RescaleHi rs[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) rs[g] = a.rs[g];
+
+  // ---- activation block -> LDS: wave load (wave + 4 j) fills bytes
+  // [1024 c, 1024 (c + 1)) of the padded [32][LS] block, lane l its 16 bytes at
+  // 16 l.  Bytes outside the rows' first kpad bytes (row padding, the tail of
+  // the stage) read the start of the buffer; they meet zero weights only.
+  // Every wave issues exactly NCH loads per block, so that the number of vector
+  // memory operations in flight behind a given block's loads is a constant.
+  int lrow[NCH], lcol[NCH];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int o = (wave + 4 * j) * 1024 + lane * 16;
+    const int r = o / LS, c = o - r * LS;
+    const bool in = r < 32 && c < a.kpad;
+    lrow[j] = in ? r : 0;  // padding reads (row 0, byte 0) of the block
+    lcol[j] = in ? c : 0;
+  }
+  // the block to be loaded next: (t, first b) of its rows, advanced by 32 rows per block
+  int st_rb = rb0, st_t = (rb0 << 5) / a.Bp, st_b = (rb0 << 5) - st_t * a.Bp;
+  const int8_t *st_base = a.A + (size_t)st_t * a.B * a.lda;
+  auto stage_one = [&](int slot, int j) {
+    int b = st_b + lrow[j];
+    b = b < a.B ? b : a.B - 1;  // padded rows repeat the last real one; their results are never read
+    const unsigned off = (unsigned)(b * a.lda + lcol[j]);  // within one t: below B * lda < 2^31
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(st_base + off),
+                                     (__attribute__((address_space(3))) void *)(lds + slot * BUF + (wave + 4 * j) * 1024),
+                                     16, 0, 0);
+  };
+  auto stage_advance = [&]() {
+    if (st_rb + 1 >= rb1) return;  // past the end: the last block again, into a stage nobody reads
+    ++st_rb;
+    st_b += 32;
+    if (st_b >= a.Bp) {
+      st_b = 0;
+      st_base += (size_t)a.B * a.lda;
+    }
+  };
+
+  // requantize and store the pieces [p_lo, p_hi) of a finished block: piece
+  // p = (tile, half, pair) -> two results -> one packed word; four pieces make
+  // the 16 bytes of (tile, half).  The accumulators start from the bias.
+  int32_t word[4];
+  auto pieces = [&](const v16i (&pv)[2], int p_lo, int p_hi, int rb_prev) {
+#pragma unroll
+    for (int p = p_lo; p < p_hi; ++p) {
+      const int tl = p >> 3, half = (p >> 2) & 1, pair = p & 3;
+      const int i0 = half * 8 + pair * 2, i1 = i0 + 1;  // = 4 * gate + c
+      word[pair] = requant2<PRE>(pv[tl][i0], pv[tl][i1], rs[i0 >> 2], rs[i1 >> 2]);
+      if (pair == 3) {
+        const int tile = cb * 8 + wave * 2 + tl;
+        int4 *dst = a.tx2 + (((size_t)rb_prev * a.tiles + tile) * 2 + half) * 64 + lane;
+        *dst = int4{word[0], word[1], word[2], word[3]};
+      }
+    }
+  };
+
+  // One block: 2 * KS MFMAs; under them, in the issue slots they leave free,
+  // the loads of the block three ahead and the requantization of the previous
+  // block.  Vector memory operations complete in the order issued; a block
+  // issues NCH loads and (all but the first) four stores, so at the top of
+  // block i everything up to the loads of block i + 1 is complete once at most
+  // the operations of block i - 1 -- NCH + 4, or NCH after the first block --
+  // are in flight.  Past the barrier that holds for every wave's part of block
+  // i + 1, and every wave has finished reading block i - 1, whose stage the
+  // loads of block i + 3 overwrite.  The first operands of block i + 1 can
+  // therefore be read at the end of block i, ahead of the next barrier.
+  constexpr int DEPTH = 4;
+  v4i xf[DEPTH];
+  auto first_operands = [&](int slot) {
+    const uint8_t *xbase = lds + slot * BUF + col * LS + (b2 << 4);
+#pragma unroll
+    for (int ks = 0; ks < DEPTH && ks < KS; ++ks) xf[ks] = *reinterpret_cast<const v4i *>(xbase + ks * 32);
+  };
+  auto block = [&](int rb, int slot, v16i (&acc)[2], const v16i (&prev)[2], auto have_prev_tag, auto stores_tag) {
+    constexpr bool HAVE = decltype(have_prev_tag)::value;
+    if (decltype(stores_tag)::value)
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCH + 4) : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCH) : "memory");
+    // a bare barrier: __syncthreads() would also wait for the stores in flight
+    // (its release fence), and nothing here is exchanged through global memory
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    const uint8_t *xbase = lds + slot * BUF + col * LS + (b2 << 4);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl) {
+        if (ks == 0) {
+          v16i c0;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) c0[v] = bias[tl][v];
+          acc[tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Wf[tl][ks], xf[ks % DEPTH], c0, 0, 0, 0);
+        } else {
+          acc[tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Wf[tl][ks], xf[ks % DEPTH], acc[tl], 0, 0, 0);
+        }
+      }
+      if (ks + DEPTH < KS) xf[ks % DEPTH] = *reinterpret_cast<const v4i *>(xbase + (ks + DEPTH) * 32);
+      if (ks < NCH) stage_one((slot + NST - 1) % NST, ks);
+      if (HAVE) pieces(prev, ks * 16 / KS, (ks + 1) * 16 / KS, rb - 1);
+      // keep the LDS reads DEPTH steps ahead and the other work spread over the k loop
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    stage_advance();
+    first_operands((slot + 1) % NST);
+  };
+
+  static_assert(NCH <= KS, "one load per k step");
+  static_assert(NCH + 4 <= 63, "vmcnt field");
+  for (int i = 0; i < NST - 1; ++i) {
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) stage_one(i, j);
+    stage_advance();
+  }
+  // blocks 0 and 1 of the part are loaded before anything else is issued
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCH) : "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  first_operands(0);
+  v16i accA[2], accB[2];
+  block(rb0, 0, accA, accB, std::false_type{}, std::false_type{});
+  int rb = rb0 + 1, slot = 1;
+  if (rb < rb1) {
+    block(rb, slot, accB, accA, std::true_type{}, std::false_type{});  // the first block stored nothing
+    ++rb;
+    slot = (slot + 1) % NST;
+  }
+  // pairs of blocks, so that the two accumulator sets alternate statically
+  for (; rb + 1 < rb1; rb += 2, slot = (slot + 2) % NST) {
+    block(rb, slot, accA, accB, std::true_type{}, std::true_type{});
+    block(rb + 1, (slot + 1) % NST, accB, accA, std::true_type{}, std::true_type{});
+  }
+  if (rb < rb1) {
+    block(rb, slot, accA, accB, std::true_type{}, std::true_type{});
+    pieces(accA, 0, 16, rb);
+  } else {
+    // the last block ran on accB if at least two blocks ran, else on accA
+    if (rb1 - rb0 >= 2)
+      pieces(accB, 0, 16, rb1 - 1);
+    else
+      pieces(accA, 0, 16, rb1 - 1);
+  }
+}
+
+template <int KS>
+constexpr unsigned lds_bytes_ks() {  // NST stages of NCH * 4 KB
+  return 4u * ((((32 * (KS * 32 + 16) + 1023) / 1024) + 3) / 4) * 4096;
+}
+
+template <int KS>
+hipError_t init_ks() {
+  static_assert(lds_bytes_ks<KS>() <= 160 * 1024, "activation stages exceed LDS");
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(in_gemm_ws_kernel<KS, true>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes_ks<KS>());
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(in_gemm_ws_kernel<KS, false>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes_ks<KS>());
+}
+
+template <int KS>
+void launch_ks(hipStream_t s, const InGemmArgs &a, int grid, bool pre) {
+  if (pre)
+    hipLaunchKernelGGL((in_gemm_ws_kernel<KS, true>), dim3(grid), dim3(256), lds_bytes_ks<KS>(), s, a);
+  else
+    hipLaunchKernelGGL((in_gemm_ws_kernel<KS, false>), dim3(grid), dim3(256), lds_bytes_ks<KS>(), s, a);
+}
+
+}  // namespace
+
+hipError_t in_gemm_init() {
+  hipError_t e = init_ks<8>();
+  if (e == hipSuccess) e = init_ks<16>();
+  if (e == hipSuccess) e = init_ks<20>();
+  if (e == hipSuccess) e = init_ks<32>();
+  return e;
+}
+
+bool in_gemm_ws_supported(const InGemmArgs &a) {
+  if (a.kpad > 1024 || a.kpad % 64 != 0 || a.tiles % 8 != 0) return false;
+  if ((long long)a.B * a.lda >= (1ll << 31)) return false;  // 32-bit offsets within one t
+  for (int g = 0; g < 4; ++g)
+    if (a.r[g] < 3 || a.r[g] > 62) return false;
+  return true;
+}
+
+void launch_in_gemm_ws(hipStream_t s, const InGemmArgs &a0, int num_cus) {
+  if (a0.T <= 0 || a0.B <= 0) return;
+  InGemmArgs a = a0;
+  bool pre = false;
+  for (int g = 0; g < 4; ++g) {
+    a.rs[g] = rescale_hi_prepare(a.M[g], a.r[g]);
+    pre = pre || a.rs[g].k != 0;
+  }
+  const int cbs = a.tiles / 8;
+  const int nrb = (a.T * a.Bp) >> 5;
+  int parts = num_cus / cbs;
+  if (parts < 1) parts = 1;
+  if (parts > nrb) parts = nrb;
+  a.parts = parts;
+  const int grid = parts * cbs;
+  if (a.kpad <= 256) launch_ks<8>(s, a, grid, pre);
+  else if (a.kpad <= 512) launch_ks<16>(s, a, grid, pre);
+  else if (a.kpad <= 640) launch_ks<20>(s, a, grid, pre);
+  else launch_ks<32>(s, a, grid, pre);
+}
+
+}  // namespace lstm_int

@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "lstm_int_math.h"
+
 namespace lstm_int {
 
 // Tile order shared by the two kernels.  Cells are taken in tiles of 8; the 32
@@ -24,8 +26,17 @@ struct InGemmArgs {
   const int32_t *bx2;  // [tiles][32]
   int32_t M[4], r[4], all_hi;
   int4 *tx2;
+  // filled by launch_in_gemm_ws
+  int parts;          // row partitions; workgroup id -> (id % parts, id / parts)
+  RescaleHi rs[4];    // per gate, prepared from (M, r)
 };
+// one workgroup per 128 rows x 4 tiles, operands staged per 64-byte k tile
+// (any k depth, any shifts)
 void launch_in_gemm(hipStream_t s, const InGemmArgs &a);
+// weights resident in registers (in_gemm.hip); needs in_gemm_ws_supported(a)
+hipError_t in_gemm_init();
+bool in_gemm_ws_supported(const InGemmArgs &a);
+void launch_in_gemm_ws(hipStream_t s, const InGemmArgs &a, int num_cus);
 
 struct RecArgs {
   int T, B, N, H, Hpad, flags, m_c;
