@@ -441,7 +441,8 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
 
     // persistent path: eligible shape, no dump requested for this layer, batch fits one launch
     int p2_ks = 0, p2_rt = 0, p2_groups = 0;
-    bool use_p2 = m->path != 1 && !tr && d.p2 && (reinterpret_cast<uintptr_t>(y) & 3) == 0 &&
+    // (and at most 2^14 steps: the statistics words of the kernel count up over the launch)
+    bool use_p2 = m->path != 1 && !tr && d.p2 && T <= (1 << 14) && (reinterpret_cast<uintptr_t>(y) & 3) == 0 &&
                   rec_supported(h.N, h.H, (int)h.flags, B, &p2_ks, &p2_rt, &p2_groups);
     RecArgs ra;
     if (use_p2) {

@@ -74,6 +74,7 @@ __device__ __forceinline__ int32_t mirror_tanh(int32_t x, int32_t t) {
 template <int KS, int RT, int FL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void rec_kernel(RecArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const long long t_start = (long long)wall_clock64();
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, b2 = lane >> 5;
   constexpr bool cifg = FL & 1, ph = FL & 2, ln = FL & 4;
@@ -218,6 +219,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
 
   if (tid < 16) tickL[tid] = 0;
+  if (tid == 0) *flag = 1;
   __syncthreads();  // LDS contents above are in place before the first step
 
   unsigned epoch = 0;
@@ -242,7 +244,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       tick_last = now;                                                                    \
     }                                                                                     \
   } while (0)
-  if (timing) tick_last = (long long)wall_clock64();
+  if (timing) {
+    tick_last = t_start;
+    __hip_atomic_store(&a.ticks[15], t_start, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  TICK(10);  // everything before the first step
 
   // the two 16-byte W x pieces of (rt, tile) for step t
   auto tx_ptr = [&](int t, int rt, int tl) -> const int4 * {
@@ -360,6 +366,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     };
     if (a.all_hi) gate_sums(std::true_type{}); else gate_sums(std::false_type{});
 
+    // Layer-norm statistics of a row are summed over the group's workgroups by
+    // atomic adds into two 64-bit words per (row, gate), which are never reset:
+    // the reader subtracts what it read the step before.  The top byte of each
+    // word counts the adds, so the words themselves tell when every workgroup of
+    // the group has contributed and no separate barrier is needed.  Value field
+    // (56 bits): S1 + 2^22 >= 0 per add, at most 2^23; S2 at most 2^36 per add;
+    // with at most 32 adds per step the fields hold more than 2^14 steps.
+    constexpr u64 kValMask = ((u64)1 << 56) - 1;
     auto publish_stats = [&](int round, int g_lo, int g_hi) {
       __syncthreads();
       if (tid < items) {
@@ -368,31 +382,48 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           const int64_t pk = (int64_t)(red[tid] + red[items + tid] + red[2 * items + tid] + red[3 * items + tid]);
           const int64_t v1 = ((pk + (1 << 23)) & 0xFFFFFF) - (1 << 23);  // signed low 24 bits
           const int64_t v2 = (pk - v1) >> 24;
-          __hip_atomic_fetch_add(&accS[(round * 2 + 0) * 256 + tid], (u64)v1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_fetch_add(&accS[(round * 2 + 1) * 256 + tid], (u64)v2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(&accS[(round * 2 + 0) * 256 + tid], ((u64)1 << 56) + (u64)(v1 + (1 << 22)),
+                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(&accS[(round * 2 + 1) * 256 + tid], ((u64)1 << 56) + (u64)v2, __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
         }
       }
     };
-    auto collect_stats = [&](int round, int g_lo, int g_hi) {
+    // false: a wait gave up (status word raised), every thread leaves the kernel
+    auto collect_stats = [&](int round, int g_lo, int g_hi) -> bool {
       if (tid < items) {
         const int g = (tid >> 5) & 3;
         if (g >= g_lo && g <= g_hi) {
-          const int64_t c1 = (int64_t)__hip_atomic_load(&accS[(round * 2 + 0) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          const int64_t c2 = (int64_t)__hip_atomic_load(&accS[(round * 2 + 1) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          const LnRow r = ln_row(c1 - prevS[round][0], c2 - prevS[round][1], a.N, inv_n);
-          prevS[round][0] = c1;
-          prevS[round][1] = c2;
-          lnrow[tid] = ln_row2(r);
+          const u64 expect = (u64)(((unsigned)GS * (unsigned)(t + 1)) & 0xFFu);
+          u64 c1, c2;
+          int budget = a.spin_limit;
+          for (;;) {
+            c1 = __hip_atomic_load(&accS[(round * 2 + 0) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c2 = __hip_atomic_load(&accS[(round * 2 + 1) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((c1 >> 56) == expect && (c2 >> 56) == expect) break;
+            if (--budget <= 0 || __hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+              __hip_atomic_store(a.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              *flag = 0;
+              break;
+            }
+          }
+          c1 &= kValMask;
+          c2 &= kValMask;
+          const int64_t S1 = (int64_t)((c1 - (u64)prevS[round][0]) & kValMask) - (int64_t)GS * (1 << 22);
+          const int64_t S2 = (int64_t)((c2 - (u64)prevS[round][1]) & kValMask);
+          prevS[round][0] = (int64_t)c1;
+          prevS[round][1] = (int64_t)c2;
+          lnrow[tid] = ln_row2(ln_row(S1, S2, a.N, inv_n));
         }
       }
       __syncthreads();
+      return *flag != 0;
     };
     TICK(2);
     if (ln) {
       publish_stats(0, g_first, ph ? 2 : 3);
-      if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, flag)) return;
       TICK(3);
-      collect_stats(0, g_first, ph ? 2 : 3);
+      if (!collect_stats(0, g_first, ph ? 2 : 3)) return;
       TICK(4);
     }
 
@@ -497,8 +528,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (ph) {
       if (ln) {
         publish_stats(1, 3, 3);
-        if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, flag)) return;
-        collect_stats(1, 3, 3);
+        if (!collect_stats(1, 3, 3)) return;
       }
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
@@ -644,7 +674,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
 #undef TICK
   if (timing)
-    for (int i = 0; i < 16; ++i) a.ticks[i] += (long long)tickL[i];
+    for (int i = 0; i < 11; ++i) a.ticks[i] += (long long)tickL[i];
+  if (a.ticks && tid == 0) {
+    // spread of the workgroups' lifetimes against workgroup 0's start (maxima over all launches)
+    const long long t0 = __hip_atomic_load(&a.ticks[15], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const long long t_end = (long long)wall_clock64();
+    if (wg == 0) a.ticks[11] += t_end - t_start;
+    __hip_atomic_fetch_max(&a.ticks[12], t_start - t0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_max(&a.ticks[13], t_end - t0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_max(&a.ticks[14], t0 - t_start, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 
   if (a.c_out) {
 #pragma unroll
