@@ -451,11 +451,11 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.GS = d.GS; ra.groups = p2_groups; ra.rows_pg = 32 * p2_rt; ra.ks = d.ks; ra.Ncp = d.Ncp;
       ra.Bp = round_up(B, 32);
       ra.R2 = d.R2; ra.bh4 = d.bh4; ra.Lq4 = d.Lq4; ra.qb4 = d.qb4; ra.Pq3 = d.Pq3;
-      ra.all_hi = 1;
+      ra.pre_h = 0;
       for (int g = 0; g < 4; ++g) {
         const int sg = g < 4 - h.G ? 4 - h.G : g;  // an absent gate borrows valid numbers; its rows are zero
         ra.Mh[g] = h.Mh[sg]; ra.rh[g] = 31 - h.eh[sg];
-        if (ra.rh[g] < 32) ra.all_hi = 0;
+        if (ra.rh[g] < 33) ra.pre_h = 1;
         ra.Mln[g] = h.Mln[sg]; ra.rln[g] = 31 - h.eln[sg];
       }
       for (int j = 0; j < 3; ++j) { ra.Mc[j] = h.Mc[j]; ra.rc[j] = 31 - h.ec[j]; }
@@ -475,12 +475,13 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.status = m->status;
       ra.spin_limit = m->spin_limit;
       ra.ticks = m->phase_timing ? reinterpret_cast<long long *>(m->status + 16) : nullptr;
-      // the kernel's short forms of rescale need shifts >= 32, its tables must compress
-      bool ok = ra.rm >= 32 && (!proj || ra.rp >= 32) && ra.sh_sig >= 0 && ra.sh_tanh >= 0 && ra.sh_tanhc >= 0;
+      // the kernel's one-product form of rescale needs shifts in [3, 62], its tables must compress
+      auto shift_ok = [](int r) { return r >= 3 && r <= 62; };
+      bool ok = shift_ok(ra.rm) && (!proj || shift_ok(ra.rp)) && ra.sh_sig >= 0 && ra.sh_tanh >= 0 && ra.sh_tanhc >= 0;
       for (int g = 4 - h.G; g < 4; ++g)
-        if (h.layer_norm() && ra.rln[g] < 32) ok = false;
+        if (!shift_ok(ra.rh[g]) || (h.layer_norm() && !shift_ok(ra.rln[g]))) ok = false;
       for (int j = 4 - h.G; j < 3; ++j)
-        if (h.peephole() && ra.rc[j] < 32) ok = false;
+        if (h.peephole() && !shift_ok(ra.rc[j])) ok = false;
       if (!ok || rec_lds_bytes(ra) > 160 * 1024) use_p2 = false;
     }
     if (use_p2) {

@@ -193,9 +193,14 @@ LSTM_HD RescaleHi rescale_hi_prepare(int32_t M, int32_t r) {
 // left by k = 33 - r first, which is exact if |a| < 2^(31-k); a larger |a| is
 // clamped to [-2^(31-k), 2^(31-k) - 1] before, which does not change the saturated result:
 // (2^(31-k) - 1) * M / 2^r >= (2^31 - 2^k) 2^30 / 2^33 = 2^28 - 2^(k-3) > 2^15 for k <= 30.
+template <bool PRE = true>
 LSTM_HD int32_t rescale_sat16_pre(int32_t a, const RescaleHi &p) {
-  const int32_t lim = (int32_t)(0x7FFFFFFFu >> p.k);
-  a = clamp_i32(a, -lim - 1, lim) << p.k;
+  if (PRE) {  // PRE = false: the caller knows that p.k == 0
+    const int32_t lim = (int32_t)(0x7FFFFFFFu >> p.k);
+    a = a < lim ? a : lim;
+    a = a > -lim - 1 ? a : -lim - 1;
+    a <<= p.k;
+  }
 #if defined(__HIP_DEVICE_COMPILE__)
   const int32_t hi = __mulhi(a, p.M);
 #else

@@ -52,7 +52,8 @@ struct RecArgs {
   const int16_t *Lq4;  // [4][Ncp]
   const int32_t *qb4;  // [4][Ncp]
   const int16_t *Pq3;  // [3][Ncp]
-  int32_t Mh[4], rh[4], all_hi;
+  int32_t Mh[4], rh[4];
+  int32_t pre_h;  // some rh is below 33
   int32_t Mc[3], rc[3];
   int32_t Mln[4], rln[4];
   int32_t Mm, rm, zp_m;

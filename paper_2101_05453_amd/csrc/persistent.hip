@@ -32,7 +32,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned long long u64;
 
 constexpr int kLdsRow = 80;  // 64 data bytes + 16 pad
-constexpr int kPrmLdsBytes = 192;  // sizeof(PrmLds) in rec_kernel.inc.h
+constexpr int kPrmLdsBytes = 256;  // sizeof(PrmLds) in rec_kernel.inc.h
 
 // ---------------------------------------------------------------------------
 // Input GEMM: block = 128 (t,b) rows x 4 weight tiles (32 cells), 4 waves 2x2,

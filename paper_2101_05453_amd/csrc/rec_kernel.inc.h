@@ -46,14 +46,14 @@ __device__ __forceinline__ bool group_sync(unsigned *counter, unsigned &epoch, i
 
 // Per-layer constants, kept in LDS and read where they are used: as kernel
 // arguments they would all be live in scalar registers across the time loop.
-struct PrmLds {  // 192 bytes (kPrmLdsBytes in persistent.hip)
-  int32_t Mh[4], rh[4], Mc[4], rc[4];
-  RescaleHi ln[4];
-  int32_t Mm, rm, zp_m, Mp, rp, zp_h, m_c, glo;
-  int32_t pad[8];
+struct PrmLds {  // 256 bytes (kPrmLdsBytes in persistent.hip)
+  RescaleHi h[4], c[4], ln[4];  // R h terms, peephole terms, layer-norm second stage
+  RescaleHi m, p;               // hidden state, projection
+  int32_t zp_m, zp_h, m_c, glo;
+  int32_t pad[4];
 };
 
-static_assert(sizeof(PrmLds) == 192, "rec_lds_bytes assumes 192 bytes");
+static_assert(sizeof(PrmLds) == 256, "rec_lds_bytes assumes 256 bytes");
 
 // |x| -> table value from the compressed copy in LDS; `a` must be below kLutDomain
 __device__ __forceinline__ int32_t lut_lds(const uint8_t *blob, int sh, int32_t a) {
@@ -155,13 +155,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     PqL[tid] = (ph && g < 3) ? a.Pq3[idx] : 0;
   }
   if (tid < 4) {
-    prm->Mh[tid] = a.Mh[tid]; prm->rh[tid] = a.rh[tid];
-    prm->Mc[tid] = tid < 3 ? a.Mc[tid] : 0; prm->rc[tid] = tid < 3 ? a.rc[tid] : 32;
+    prm->h[tid] = rescale_hi_prepare(a.Mh[tid], a.rh[tid]);
+    prm->c[tid] = rescale_hi_prepare(tid < 3 && ph ? a.Mc[tid] : 0, tid < 3 && ph ? a.rc[tid] : 33);
     prm->ln[tid] = rescale_hi_prepare(a.Mln[tid], ln ? a.rln[tid] : 33);
   }
   if (tid == 0) {
-    prm->Mm = a.Mm; prm->rm = a.rm; prm->zp_m = a.zp_m;
-    prm->Mp = a.Mp; prm->rp = a.rp; prm->zp_h = a.zp_h;
+    prm->m = rescale_hi_prepare(a.Mm, a.rm);
+    prm->p = rescale_hi_prepare(proj ? a.Mp : 0, proj ? a.rp : 33);
+    prm->zp_m = a.zp_m; prm->zp_h = a.zp_h;
     prm->m_c = a.m_c; prm->glo = ln ? -32767 : -32768;
   }
   for (int i = tid; i < rows_pg * LS / 16; i += 256) reinterpret_cast<int4 *>(hT)[i] = int4{0, 0, 0, 0};
@@ -290,7 +291,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
       for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[rt][tl][v] = 0;
+        for (int v = 0; v < 16; ++v) acc[rt][tl][v] = bhr[tl][v];
     {
       constexpr int DEPTH = 4;  // h fragments in flight ahead of the MFMAs
       v4i hf[RT][DEPTH];
@@ -307,7 +308,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         for (int rt = 0; rt < RT; ++rt) {
 #pragma unroll
           for (int tl = 0; tl < 2; ++tl)
-            acc[rt][tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Wf[tl][ks], hf[rt][ks % DEPTH], acc[rt][tl], 0, 0, 0);
+            acc[rt][tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Wf[tl][ks], hf[rt][ks % DEPTH], acc[rt][tl], 0, 0, 0);  // acc starts from the folded bias
           if (ks + DEPTH < KS)
             hf[rt][ks % DEPTH] = *reinterpret_cast<const v4i *>(hbase + (size_t)rt * 32 * LS + (ks + DEPTH) * 32);
         }
@@ -320,36 +321,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
     // ---- gate sums (Secs. 3.2.4/3.2.5) and layer-norm partial statistics.
     // With a peephole the o gate keeps tx + th here and is finished after c^t.
-    const int32_t glo = prm->glo;
-    auto gate_sums = [&](auto fast_tag) {
-      constexpr bool FAST = decltype(fast_tag)::value;  // every shift of the R h rescale is >= 32
+    constexpr int32_t glo = ln ? -32767 : -32768;  // layer norm takes symmetric gate sums
+    auto gate_sums = [&](auto pre_tag) {
+      constexpr bool PRE = decltype(pre_tag)::value;  // some shift of the R h rescale is below 33
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         int32_t s1[4] = {0, 0, 0, 0};
-        int64_t s2[4] = {0, 0, 0, 0};
+        uint32_t s2[4][2] = {{0, 0}, {0, 0}, {0, 0}, {0, 0}};  // four squares of 16-bit values fit 32 bits
 #pragma unroll
         for (int tl = 0; tl < 2; ++tl) {
           const int32_t txw[8] = {txv[rt][tl][0].x, txv[rt][tl][0].y, txv[rt][tl][0].z, txv[rt][tl][0].w,
                                   txv[rt][tl][1].x, txv[rt][tl][1].y, txv[rt][tl][1].z, txv[rt][tl][1].w};
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            const int32_t Mg = prm->Mh[g], rg = prm->rh[g];
+            const RescaleHi pg = prm->h[g];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
               const int idx = g * 4 + c;
-              const int32_t s = acc[rt][tl][idx] + bhr[tl][idx];
-              const int32_t th = sat16(FAST ? rescale_ge32(s, Mg, rg) : rescale(s, Mg, rg));
+              const int32_t th = rescale_sat16_pre<PRE>(acc[rt][tl][idx], pg);
               const int32_t w = txw[idx >> 1];
               const int32_t tx = (idx & 1) ? (w >> 16) : (int32_t)(int16_t)(w & 0xFFFF);
               int32_t v = tx + th;
               if (ph && g < 2) {
                 const int cl = cell_w + tl * 8 + c;
-                v += sat16(rescale_ge32((int32_t)PqL[g * 64 + cl] * creg[rt][tl][c], prm->Mc[g], prm->rc[g]));
+                v += rescale_sat16_pre((int32_t)PqL[g * 64 + cl] * creg[rt][tl][c], prm->c[g]);
               }
               if (!(ph && g == 3)) v = clamp_i32(v, glo, 32767);
               acc[rt][tl][idx] = v;
               s1[g] += v;
-              s2[g] += (int64_t)v * v;
+              s2[g][tl] += (uint32_t)v * (uint32_t)v;
             }
           }
         }
@@ -357,14 +357,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             // 16 cells of this wave: the two lanes of a row (lane, lane ^ 32)
-            int64_t pk = (s2[g] << 24) + s1[g];
+            int64_t pk = ((int64_t)((u64)s2[g][0] + (u64)s2[g][1]) << 24) + s1[g];
             pk += __shfl_xor(pk, 32, 64);
             if (b2 == 0) red[(size_t)wave * items + (rt * 4 + g) * 32 + col] = (u64)pk;
           }
         }
       }
     };
-    if (a.all_hi) gate_sums(std::true_type{}); else gate_sums(std::false_type{});
+    if (a.pre_h) gate_sums(std::true_type{}); else gate_sums(std::false_type{});
 
     // Layer-norm statistics of a row are summed over the group's workgroups by
     // atomic adds into two 64-bit words per (row, gate), which are never reset:
@@ -511,7 +511,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           if (ph) {  // finish the o gate sum with P_o . c^t (eq. 5)
             const int cl = cell_w + tl * 8 + c;
             int32_t v = acc[rt][tl][12 + c] +
-                        sat16(rescale_ge32((int32_t)PqL[2 * 64 + cl] * cnew, prm->Mc[2], prm->rc[2]));
+                        rescale_sat16_pre((int32_t)PqL[2 * 64 + cl] * cnew, prm->c[2]);
             v = clamp_i32(v, glo, 32767);
             acc[rt][tl][12 + c] = v;
             s1 += v;
@@ -579,7 +579,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
     int8_t *mdst = proj ? a.mbuf + (size_t)t * a.B * a.npadp : a.out + (size_t)t * a.B * a.Hpad;
     const int mld = proj ? a.npadp : a.Hpad;
-    const int32_t Mm = prm->Mm, rm = prm->rm, zp_m = prm->zp_m;
+    const RescaleHi pm = prm->m;
+    const int32_t zp_m = prm->zp_m;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       const int row = row0 + rt * 32 + col;
@@ -589,7 +590,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         uint32_t pk = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          const int32_t mq = sat8(rescale_ge32(xo[rt][tl][c] * tc[rt][tl][c], Mm, rm) + zp_m);
+          // sat8 of the sum is unchanged by the 16-bit clamp before it: |zp| <= 128
+          const int32_t mq = sat8(rescale_sat16_pre(xo[rt][tl][c] * tc[rt][tl][c], pm) + zp_m);
           pk |= (uint32_t)(mq & 0xFF) << (8 * c);
         }
         if (row < a.B && n0 < a.N) {  // N % 8 == 0: the four cells are valid together
@@ -608,7 +610,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // ---- projection (Sec. 3.2.8): tile pt of 32 outputs, K = N split over the four waves
     if (proj) {
       const int per_wave = a.npadp >> 7;  // 32-wide k steps per wave, at most 16 (N <= 2048)
-      const int32_t Mp = prm->Mp, rp = prm->rp, zp_h = prm->zp_h;
+      const RescaleHi pp = prm->p;
+      const int32_t zp_h = prm->zp_h;
       for (int pt = 0; pt < my_ptiles; ++pt) {
         const int ptile = member + pt * GS;
 #pragma unroll
@@ -648,7 +651,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
               const int32_t s = pred[(0 * 16 + v) * 64 + l2] + pred[(1 * 16 + v) * 64 + l2] +
                                 pred[(2 * 16 + v) * 64 + l2] + pred[(3 * 16 + v) * 64 + l2] +
                                 (pt == 0 ? bpr[c] : a.bp2[p0 + c]);
-              const int32_t hq = sat8(rescale_ge32(s, Mp, rp) + zp_h);
+              const int32_t hq = sat8(rescale_sat16_pre(s, pp) + zp_h);
               pk |= (uint32_t)(hq & 0xFF) << (8 * c);
             }
             if (orow < a.B && p0 < a.H) {

@@ -88,6 +88,42 @@ def test_split_sequence_carries_state(orc):
     assert_equal("split vs oracle", y.cpu().numpy(), orc.forward(orc_model, xq))
 
 
+@pytest.mark.parametrize("I", [40, 300, 520, 700, 1100])
+def test_input_gemm_k_depths(orc, I):
+    """One input size per register-depth class of the weight-resident input
+    GEMM (k up to 256, 512, 640, 1024 bytes) and one beyond it, which takes the
+    tiled GEMM; B = 70 leaves a ragged last block of rows."""
+    print(f"input size {I}", flush=True)
+    layers, x = wl.make_custom([I], 64, 64, 0, 70, 3, seed=I, weight_param=0.05)
+    run_and_compare(orc, layers, x, f"in{I}", trace=False)
+
+
+@pytest.mark.parametrize("steps", [8, 16, 24, 32, 40, 48])
+def test_input_gemm_blocks_per_workgroup(orc, steps):
+    """N = 2048 gives 32 column blocks, so the rows are split into 8 parts and a
+    workgroup streams steps/8 blocks of 32 rows: 1 to 6, covering the start-up
+    and the drain of its load and store pipeline."""
+    print(f"steps {steps}", flush=True)
+    layers, x = wl.make_custom([64], 2048, 64, wl.PROJECTION | wl.LAYER_NORM, 32, steps, seed=steps,
+                               weight_param=0.05)
+    run_and_compare(orc, layers, x, f"blocks{steps}", trace=False)
+
+
+def test_small_shifts(orc):
+    """Large weights push the effective scales of the gate terms to 1/4 and
+    above, i.e. rescale shifts below 33, where the one-product form of rescale
+    pre-shifts (and clamps) its operand."""
+    print("small shifts", flush=True)
+    from paper_2101_05453_amd import binding, calibration
+
+    layers, x = wl.make_custom([48], 128, 128, wl.PEEPHOLE, 40, 6, seed=77, weight_param=0.6)
+    calibration.collect_statistics(layers, x)
+    q = binding.prepare(layers, device=0).get_quant(0)
+    shifts = [31 - e for e in q["ex"] + q["eh"]]
+    assert min(shifts) < 33, shifts
+    run_and_compare(orc, layers, x, "small_shifts")
+
+
 def test_saturating_ranges(orc):
     """Calibration ranges far too small: every clamp on the path is hit."""
     import torch
