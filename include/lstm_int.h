@@ -174,6 +174,9 @@ int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
  *   "spin_limit": polls after which a wait inside the persistent kernel gives
  *           up (every workgroup then leaves the kernel and the status word of
  *           lstm_int_device_status becomes nonzero).
+ *   "poll_sleep", "stats_sleep": pause between two polls of a group barrier /
+ *           of the layer-norm statistics words inside the persistent kernel,
+ *           in units of 64 clocks (0..1024; defaults 8 and 0).
  *   "phase_timing": nonzero makes workgroup 0 of the persistent kernel add the
  *           time it spends in each of its phases to 16 device counters
  *           (diagnostics; read them with lstm_int_phase_ticks).

@@ -78,6 +78,7 @@ struct RecArgs {
   unsigned long long *acc;     // [groups][2 rounds][2 (S1,S2)][rows_pg*4]
   int *status;                 // [0] != 0: a wait gave up or the placement check failed
   int spin_limit;
+  int poll_sleep, stats_sleep;  // pauses between two polls of a barrier / of the statistics words, x 64 clocks
   long long *ticks;  // NULL, or [16] phase timers of workgroup 0 (diagnostics)
 };
 

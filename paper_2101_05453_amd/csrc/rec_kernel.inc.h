@@ -20,28 +20,35 @@ typedef unsigned long long u64;
 
 // Barrier among the GS workgroups of a group.  Every wave first waits for its
 // own stores (vmcnt(0)); thread 0 then adds one to the group's counter and
-// polls it.  Gives up after spin_limit polls (or when another workgroup gave
-// up), raising the status word so that every workgroup leaves the kernel.
+// polls it, pausing poll_sleep x 64 clocks between polls: the polls of all the
+// group's workgroups go to one L2 channel, the one that also serves the
+// arrivals, and polling at full rate delays those (measured: every poller
+// added made the barrier slower).  Gives up after spin_limit polls (or when
+// another workgroup gave up), raising the status word so that every workgroup
+// leaves the kernel; lds_flag[0] is then 0 for good.
 __device__ __forceinline__ bool group_sync(unsigned *counter, unsigned &epoch, int GS, int *status,
-                                           int spin_limit, int *lds_flag) {
+                                           int spin_limit, int poll_sleep, int *lds_flag) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (GS == 1) return true;
   epoch += (unsigned)GS;
   if (threadIdx.x == 0) {
     __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    int ok = 1, budget = spin_limit;
-    while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch) {
-      if (--budget <= 0 || __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+    int budget = spin_limit;
+    for (;;) {
+      const unsigned c = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int st = __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((int)(c - epoch) >= 0) break;
+      if (--budget <= 0 || st != 0) {
         __hip_atomic_store(status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        ok = 0;
+        lds_flag[0] = 0;
         break;
       }
+      for (int i = 0; i < poll_sleep; ++i) __builtin_amdgcn_s_sleep(1);
     }
-    *lds_flag = ok;
   }
   __syncthreads();
-  return *lds_flag != 0;
+  return lds_flag[0] != 0;
 }
 
 // Per-layer constants, kept in LDS and read where they are used: as kernel
@@ -220,7 +227,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
 
   if (tid < 16) tickL[tid] = 0;
-  if (tid == 0) *flag = 1;
+  if (tid == 0) {
+    flag[0] = 1;
+    flag[1] = 0;
+  }
   __syncthreads();  // LDS contents above are in place before the first step
 
   unsigned epoch = 0;
@@ -406,6 +416,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
               *flag = 0;
               break;
             }
+            for (int i = 0; i < a.stats_sleep; ++i) __builtin_amdgcn_s_sleep(1);
           }
           c1 &= kValMask;
           c2 &= kValMask;
@@ -604,7 +615,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     }
     TICK(6);
-    if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, flag)) return;
+    if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, a.poll_sleep, flag)) return;
     TICK(7);
 
     // ---- projection (Sec. 3.2.8): tile pt of 32 outputs, K = N split over the four waves
@@ -671,7 +682,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
       }
       TICK(8);
-      if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, flag)) return;
+      if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, a.poll_sleep, flag)) return;
       TICK(9);
     }
   }
