@@ -193,14 +193,16 @@ LSTM_HD RescaleHi rescale_hi_prepare(int32_t M, int32_t r) {
 // left by k = 33 - r first, which is exact if |a| < 2^(31-k); a larger |a| is
 // clamped to [-2^(31-k), 2^(31-k) - 1] before, which does not change the saturated result:
 // (2^(31-k) - 1) * M / 2^r >= (2^31 - 2^k) 2^30 / 2^33 = 2^28 - 2^(k-3) > 2^15 for k <= 30.
+// the operand's clamp and left shift, a no-op when p.k == 0
+LSTM_HD int32_t rescale_preshift(int32_t a, const RescaleHi &p) {
+  const int32_t lim = (int32_t)(0x7FFFFFFFu >> p.k);
+  a = a < lim ? a : lim;
+  a = a > -lim - 1 ? a : -lim - 1;
+  return a << p.k;
+}
 template <bool PRE = true>
 LSTM_HD int32_t rescale_sat16_pre(int32_t a, const RescaleHi &p) {
-  if (PRE) {  // PRE = false: the caller knows that p.k == 0
-    const int32_t lim = (int32_t)(0x7FFFFFFFu >> p.k);
-    a = a < lim ? a : lim;
-    a = a > -lim - 1 ? a : -lim - 1;
-    a <<= p.k;
-  }
+  if (PRE) a = rescale_preshift(a, p);  // PRE = false: the caller knows that p.k == 0, or has shifted already
 #if defined(__HIP_DEVICE_COMPILE__)
   const int32_t hi = __mulhi(a, p.M);
 #else
@@ -217,13 +219,16 @@ LSTM_HD int32_t f64_low_word(double w) {
   return (int32_t)bits;
 #endif
 }
-LSTM_HD int32_t ln_apply2(int32_t q, const LnRow2 &row, double qLs, double qbs, const RescaleHi &p) {
+// the layer-norm value before its second-stage rescale
+LSTM_HD int32_t ln_second_stage(int32_t q, const LnRow2 &row, double qLs, double qbs) {
   const double num = fma((double)q, 1048576.0, row.c0);
   const double qn = floor(num * row.inv_sigma);
   double v = fma(qn, qLs, qbs);
   v = fmin(fmax(v, -2147483648.0), 2147483647.0);
-  const int32_t q2 = f64_low_word(v + 6755399441055744.0);
-  return rescale_sat16_pre(q2, p);
+  return f64_low_word(v + 6755399441055744.0);
+}
+LSTM_HD int32_t ln_apply2(int32_t q, const LnRow2 &row, double qLs, double qbs, const RescaleHi &p) {
+  return rescale_sat16_pre(ln_second_stage(q, row, qLs, qbs), p);
 }
 
 // Cell update with 32-bit intermediates: |i z| <= 2^30 and the rounding terms

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   int8_t *hT = reinterpret_cast<int8_t *>(p);
   int32_t *pred = reinterpret_cast<int32_t *>(p);  // projection partials reuse the h tile between steps
   {
-    const size_t tile_bytes = ((size_t)rows_pg * LS + 1023) / 1024 * 1024;  // whole 1 KB wave chunks
+    const size_t tile_bytes = ((size_t)rows_pg * LS + 4095) / 4096 * 4096;  // every wave loads the same number of 1 KB chunks
     const size_t pred_bytes = proj ? 4 * 16 * 64 * 4 : 0;
     p += tile_bytes > pred_bytes ? tile_bytes : pred_bytes;
   }
@@ -239,6 +239,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   int64_t prevS[2][2] = {{0, 0}, {0, 0}};       // this thread's item, per round: S1, S2
   const double inv_n = 1.0 / (double)a.N;
   const int g_first = cifg ? 1 : 0;
+  // uniform: some shift of the layer norm's second stage / of the hidden state's rescale is below 33
+  const bool pre_ln = ln && (a.rln[0] < 33 || a.rln[1] < 33 || a.rln[2] < 33 || a.rln[3] < 33);
+  const bool pre_m = a.rm < 33;
 
   // optional phase timing of workgroup 0 (diagnostics): 100 MHz wall clock
   // ticks per phase, summed in LDS (an add that returns nothing, so the timer
@@ -275,9 +278,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     {
       const int8_t *hp = t == 0 ? a.h0 : a.out + (size_t)(t - 1) * a.B * a.Hpad;
 #pragma unroll
-      for (int j = 0; j < NCH; ++j)
-        if (wave + 4 * j < TILE_KB)
-          __builtin_amdgcn_global_load_lds(
+      for (int j = 0; j < NCH; ++j)  // chunks past the tile land in its padding
+        __builtin_amdgcn_global_load_lds(
               (const __attribute__((address_space(1))) void *)(hp + hsrc[j]),
               (__attribute__((address_space(3))) void *)(lds + (wave + 4 * j) * 1024), 16, 0, 0);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -439,72 +441,115 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
 
     // ---- layer norm, sigma/tanh, cell update (Secs. 3.2.6, 3.2.1, 3.2.9, 3.2.7),
-    // in stages over all of the lane's cells so that the table reads of a stage
-    // are in flight together
-    auto gate_in = [&](int rt, int tl, int g, int c) -> int32_t {
-      const int32_t v = acc[rt][tl][g * 4 + c];
-      if (!ln) return v;
-      const int cl = cell_w + tl * 8 + c;
-      return ln_apply2(v, lnrow[(rt * 4 + g) * 32 + col], LdL[g * 64 + cl], bdL[g * 64 + cl],
-                       prm->ln[g]);
+    // in batches of one weight tile (up to 4 gates x 4 cells of a row).  Every
+    // LDS read of a batch is issued before the first use of any of them: the
+    // scheduling barriers keep the compiler from sinking each read next to its
+    // use, which exposes one LDS round trip per element (measured: more than
+    // half of this phase).
+    // gates of `gmask` (bit g) of tile (rt, tl): gate sums -> layer norm -> xv[g][c]
+    auto normalize = [&](int rt, int tl, int gmask, const LnRow2 (&lr)[4], int32_t (&xv)[4][4]) {
+      if (ln) {
+#pragma unroll
+        for (int gp = 0; gp < 4; gp += 2) {  // two gates per batch of reads: 16 doubles in flight
+          if (!(gmask >> gp & 3)) continue;
+          double wL[2][4], wb[2][4];
+          RescaleHi pl[2];
+#pragma unroll
+          for (int g = gp; g < gp + 2; ++g)
+            if (gmask >> g & 1) {
+              pl[g - gp] = prm->ln[g];
+#pragma unroll
+              for (int c = 0; c < 4; ++c) {
+                wL[g - gp][c] = LdL[g * 64 + cell_w + tl * 8 + c];
+                wb[g - gp][c] = bdL[g * 64 + cell_w + tl * 8 + c];
+              }
+            }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int g = gp; g < gp + 2; ++g)
+            if (gmask >> g & 1)
+#pragma unroll
+              for (int c = 0; c < 4; ++c)
+                xv[g][c] = ln_second_stage(acc[rt][tl][g * 4 + c], lr[g], wL[g - gp][c], wb[g - gp][c]);
+          if (pre_ln) {  // some second-stage shift is below 33 (uniform; rare)
+#pragma unroll
+            for (int g = gp; g < gp + 2; ++g)
+              if (gmask >> g & 1)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) xv[g][c] = rescale_preshift(xv[g][c], pl[g - gp]);
+          }
+#pragma unroll
+          for (int g = gp; g < gp + 2; ++g)
+            if (gmask >> g & 1)
+#pragma unroll
+              for (int c = 0; c < 4; ++c) xv[g][c] = rescale_sat16_pre<false>(xv[g][c], pl[g - gp]);
+        }
+      } else {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          if (gmask >> g & 1)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) xv[g][c] = acc[rt][tl][g * 4 + c];
+      }
     };
+    // table values of |xv[g][c]| for the gates of gmask: blob/shift/full table per gate
+    auto lookup = [&](int gmask, const int32_t (&xv)[4][4], const uint8_t *const (&blob)[4], const int (&shf)[4],
+                      const uint16_t *const (&full)[4], int32_t (&tv)[4][4]) {
+      int32_t mag[4][4];
+      uint32_t base[4][4], delta[4][4];
+      int over = 0;
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        if (gmask >> g & 1)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            mag[g][c] = abs_i32(xv[g][c]);  // below 2^16
+            over |= mag[g][c];
+            const int32_t ai = mag[g][c] < kLutDomain ? mag[g][c] : kLutDomain - 1;
+            base[g][c] = reinterpret_cast<const uint16_t *>(blob[g] + kLutDomain)[ai >> shf[g]];
+            delta[g][c] = blob[g][ai];
+          }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        if (gmask >> g & 1)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) tv[g][c] = (int32_t)(base[g][c] + delta[g][c]);
+      // a value beyond the compressed domain (rare) sends the wave to the full tables
+      if (__builtin_amdgcn_ballot_w64(over >= kLutDomain) != 0) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          if (gmask >> g & 1)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+              if (mag[g][c] >= kLutDomain) tv[g][c] = full[g][mag[g][c]];
+      }
+    };
+    const uint8_t *const gate_blob[4] = {lutS, lutS, lutT, lutS};
+    const int gate_sh[4] = {sh_sig, sh_sig, sh_tanh, sh_sig};
+    const uint16_t *const gate_full[4] = {a.sig_tab, a.sig_tab, a.tanh_tab, a.sig_tab};
+    constexpr int gates_now = (cifg ? 0 : 1) | 2 | 4 | (ph ? 0 : 8);  // with a peephole the o gate waits for c^t
     int32_t xi[RT][2][4], xf[RT][2][4], xz[RT][2][4], xo[RT][2][4];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
+    for (int rt = 0; rt < RT; ++rt) {
+      LnRow2 lr[4];
+      if (ln) {
 #pragma unroll
-      for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          xi[rt][tl][c] = cifg ? 0 : gate_in(rt, tl, 0, c);
-          xf[rt][tl][c] = gate_in(rt, tl, 1, c);
-          xz[rt][tl][c] = gate_in(rt, tl, 2, c);
-          xo[rt][tl][c] = ph ? 0 : gate_in(rt, tl, 3, c);
-        }
-    // sigma / tanh from the LDS tables, all reads of the stage in flight together;
-    // a value beyond the compressed domain (rare) sends the wave to the full tables
-    {
-      int over = 0;
-      int32_t tf[RT][2][4], tz[RT][2][4], ti[RT][2][4], to[RT][2][4];
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const int32_t mf = abs_i32(xf[rt][tl][c]), mz = abs_i32(xz[rt][tl][c]);
-            const int32_t mi = abs_i32(xi[rt][tl][c]), mo = abs_i32(xo[rt][tl][c]);
-            over |= (mf | mz | mi | mo) >= kLutDomain;  // all four are non-negative and below 2^16
-            tf[rt][tl][c] = lut_lds(lutS, sh_sig, mf < kLutDomain ? mf : kLutDomain - 1);
-            tz[rt][tl][c] = lut_lds(lutT, sh_tanh, mz < kLutDomain ? mz : kLutDomain - 1);
-            ti[rt][tl][c] = cifg ? 0 : lut_lds(lutS, sh_sig, mi < kLutDomain ? mi : kLutDomain - 1);
-            to[rt][tl][c] = ph ? 0 : lut_lds(lutS, sh_sig, mo < kLutDomain ? mo : kLutDomain - 1);
-          }
-      if (__builtin_amdgcn_ballot_w64(over != 0) != 0) {
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-          for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              const int32_t mf = abs_i32(xf[rt][tl][c]), mz = abs_i32(xz[rt][tl][c]);
-              const int32_t mi = abs_i32(xi[rt][tl][c]), mo = abs_i32(xo[rt][tl][c]);
-              if (mf >= kLutDomain) tf[rt][tl][c] = a.sig_tab[mf];
-              if (mz >= kLutDomain) tz[rt][tl][c] = a.tanh_tab[mz];
-              if (!cifg && mi >= kLutDomain) ti[rt][tl][c] = a.sig_tab[mi];
-              if (!ph && mo >= kLutDomain) to[rt][tl][c] = a.sig_tab[mo];
-            }
+        for (int g = 0; g < 4; ++g) lr[g] = lnrow[(rt * 4 + g) * 32 + col];
       }
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
+      for (int tl = 0; tl < 2; ++tl) {
+        int32_t xv[4][4], tv[4][4];
+        normalize(rt, tl, gates_now, lr, xv);
+        lookup(gates_now, xv, gate_blob, gate_sh, gate_full, tv);
 #pragma unroll
-        for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            xf[rt][tl][c] = mirror_sigmoid(xf[rt][tl][c], tf[rt][tl][c]);
-            xz[rt][tl][c] = mirror_tanh(xz[rt][tl][c], tz[rt][tl][c]);
-            xi[rt][tl][c] = mirror_sigmoid(xi[rt][tl][c], ti[rt][tl][c]);
-            xo[rt][tl][c] = mirror_sigmoid(xo[rt][tl][c], to[rt][tl][c]);
-          }
+        for (int c = 0; c < 4; ++c) {
+          xi[rt][tl][c] = cifg ? 0 : mirror_sigmoid(xv[0][c], tv[0][c]);
+          xf[rt][tl][c] = mirror_sigmoid(xv[1][c], tv[1][c]);
+          xz[rt][tl][c] = mirror_tanh(xv[2][c], tv[2][c]);
+          xo[rt][tl][c] = ph ? 0 : mirror_sigmoid(xv[3][c], tv[3][c]);
+        }
+      }
     }
     const int32_t m_c = prm->m_c;
 #pragma unroll
@@ -541,52 +586,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         publish_stats(1, 3, 3);
         if (!collect_stats(1, 3, 3)) return;
       }
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-          for (int c = 0; c < 4; ++c) xo[rt][tl][c] = gate_in(rt, tl, 3, c);
     }
 
     // ---- hidden state (Sec. 3.2.7); m is int8.  tanh of the new cell state in its
-    // own format (Sec. 3.2.2), and with a peephole the sigma of the o gate
+    // own format (Sec. 3.2.2), and with a peephole the layer norm and sigma of the o gate
     int32_t tc[RT][2][4];
     {
-      int over = 0;
-      int32_t to[RT][2][4];
+      const uint8_t *const hid_blob[4] = {lutC, lutC, lutC, lutS};
+      const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_tanhc, sh_sig};
+      const uint16_t *const hid_full[4] = {a.tanhc_tab, a.tanhc_tab, a.tanhc_tab, a.sig_tab};
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
+      for (int rt = 0; rt < RT; ++rt) {
+        LnRow2 lr[4];
+        if (ph && ln) lr[3] = lnrow[(rt * 4 + 3) * 32 + col];
+        // one batch per row tile: c^t of both weight tiles in slots 0 and 1, the o gate sums in 2 and 3
+        int32_t xv[4][4], tv[4][4], ov[2][4][4];
+#pragma unroll
+        for (int tl = 0; tl < 2; ++tl) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) xv[tl][c] = creg[rt][tl][c];
+          if (ph) {
+            normalize(rt, tl, 8, lr, ov[tl]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) xv[2 + tl][c] = ov[tl][3][c];
+          }
+        }
+        const uint8_t *const blob2[4] = {hid_blob[0], hid_blob[0], hid_blob[3], hid_blob[3]};
+        const int sh2[4] = {hid_sh[0], hid_sh[0], hid_sh[3], hid_sh[3]};
+        const uint16_t *const full2[4] = {hid_full[0], hid_full[0], hid_full[3], hid_full[3]};
+        lookup(ph ? 15 : 3, xv, blob2, sh2, full2, tv);
 #pragma unroll
         for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            const int32_t mc = abs_i32(creg[rt][tl][c]), mo = ph ? abs_i32(xo[rt][tl][c]) : 0;
-            over |= (mc | mo) >= kLutDomain;
-            tc[rt][tl][c] = lut_lds(lutC, sh_tanhc, mc < kLutDomain ? mc : kLutDomain - 1);
-            to[rt][tl][c] = ph ? lut_lds(lutS, sh_sig, mo < kLutDomain ? mo : kLutDomain - 1) : 0;
+            tc[rt][tl][c] = mirror_tanh(xv[tl][c], tv[tl][c]);
+            if (ph) xo[rt][tl][c] = mirror_sigmoid(xv[2 + tl][c], tv[2 + tl][c]);
           }
-      if (__builtin_amdgcn_ballot_w64(over != 0) != 0) {
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-          for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              const int32_t mc = abs_i32(creg[rt][tl][c]), mo = ph ? abs_i32(xo[rt][tl][c]) : 0;
-              if (mc >= kLutDomain) tc[rt][tl][c] = a.tanhc_tab[mc];
-              if (ph && mo >= kLutDomain) to[rt][tl][c] = a.sig_tab[mo];
-            }
       }
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            tc[rt][tl][c] = mirror_tanh(creg[rt][tl][c], tc[rt][tl][c]);
-            if (ph) xo[rt][tl][c] = mirror_sigmoid(xo[rt][tl][c], to[rt][tl][c]);
-          }
     }
     int8_t *mdst = proj ? a.mbuf + (size_t)t * a.B * a.npadp : a.out + (size_t)t * a.B * a.Hpad;
     const int mld = proj ? a.npadp : a.Hpad;
@@ -602,7 +638,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           // sat8 of the sum is unchanged by the 16-bit clamp before it: |zp| <= 128
-          const int32_t mq = sat8(rescale_sat16_pre(xo[rt][tl][c] * tc[rt][tl][c], pm) + zp_m);
+          int32_t om = xo[rt][tl][c] * tc[rt][tl][c];  // below 2^30 in magnitude
+          if (pre_m) om = rescale_preshift(om, pm);
+          const int32_t mq = sat8(rescale_sat16_pre<false>(om, pm) + zp_m);
           pk |= (uint32_t)(mq & 0xFF) << (8 * c);
         }
         if (row < a.B && n0 < a.N) {  // N % 8 == 0: the four cells are valid together
@@ -640,12 +678,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           v16i pacc;
 #pragma unroll
           for (int v = 0; v < 16; ++v) pacc[v] = 0;
+          if (per_wave == 16) {  // N = 2048: no padding step, no operand select
 #pragma unroll
-          for (int k = 0; k < 16; ++k) {
-            const int kk = k < per_wave ? k : per_wave - 1;
-            v4i wf = *reinterpret_cast<const v4i *>(wrow + kk * 32);
-            if (k >= per_wave) wf = v4i{0, 0, 0, 0};  // ... against zero weights
-            pacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, v4i{mv[k].x, mv[k].y, mv[k].z, mv[k].w}, pacc, 0, 0, 0);
+            for (int k = 0; k < 16; ++k) {
+              const v4i wf = *reinterpret_cast<const v4i *>(wrow + k * 32);
+              pacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, v4i{mv[k].x, mv[k].y, mv[k].z, mv[k].w}, pacc, 0, 0, 0);
+            }
+          } else {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+              const int kk = k < per_wave ? k : per_wave - 1;
+              v4i wf = *reinterpret_cast<const v4i *>(wrow + kk * 32);
+              if (k >= per_wave) wf = v4i{0, 0, 0, 0};  // ... against zero weights
+              pacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, v4i{mv[k].x, mv[k].y, mv[k].z, mv[k].w}, pacc, 0, 0, 0);
+            }
           }
 #pragma unroll
           for (int v = 0; v < 16; ++v) pred[(wave * 16 + v) * 64 + lane] = pacc[v];
