@@ -39,6 +39,8 @@ struct LayerDev {
   // persistent path (persistent.h): tile-ordered copies; p2 = shape is eligible
   bool p2 = false;
   int GS = 0, ks = 0, Ncp = 0, ptiles = 0, npadp = 0;
+  // per gate: bound of |W x + b'x| and |R h + b'h| over all inputs, max over rows of |b'| + 128 sum |w|
+  int64_t amax_x[4] = {0, 0, 0, 0}, amax_h[4] = {0, 0, 0, 0};
   int8_t *W2 = nullptr;     // [GS*8][32][Ipad]
   int32_t *bx2 = nullptr;   // [GS*8][32]
   int4 *R2 = nullptr;       // [GS][4][2][ks][64]
@@ -153,6 +155,15 @@ struct Timed {
   }
 };
 
+// How the one-product rescale must treat an operand bounded by amax in magnitude
+// when the shift is r: 0 = as it is (r >= 33), 1 = shifted left by 33 - r (the
+// shifted bound still fits 32 bits), 2 = clamped first.
+int preshift_mode(int r, int64_t amax) {
+  if (r >= 33) return 0;
+  const int k = 33 - r;
+  return (k < 31 && (amax << k) <= 0x7FFFFFFFll) ? 1 : 2;
+}
+
 int upload(lstm_int_model *m) {
   if (hipSetDevice(m->device) != hipSuccess) return LSTM_INT_E_DEVICE;
   if (hipDeviceGetAttribute(&m->num_cus, hipDeviceAttributeMultiprocessorCount, m->device) != hipSuccess ||
@@ -242,6 +253,11 @@ int upload(lstm_int_model *m) {
           for (int n = 0; n < h.N; ++n) {
             const size_t src = (size_t)g * h.N + n;
             const size_t trow = (size_t)(n / 8) * 32 + 8 * g + (n % 8);  // tile row rho = 8*gate + cell%8
+            int64_t sx = 0, sh = 0;
+            for (int k = 0; k < h.I; ++k) sx += std::abs((int)h.Wq[src * h.I + k]);
+            for (int k = 0; k < h.H; ++k) sh += std::abs((int)h.Rq[src * h.H + k]);
+            d.amax_x[g] = std::max<int64_t>(d.amax_x[g], (int64_t)std::llabs((long long)h.bx_fold[src]) + 128 * sx);
+            d.amax_h[g] = std::max<int64_t>(d.amax_h[g], (int64_t)std::llabs((long long)h.bh_fold[src]) + 128 * sh);
             memcpy(base + oW2 + trow * d.Ipad, h.Wq.data() + src * h.I, h.I);
             reinterpret_cast<int32_t *>(base + obx2)[trow] = h.bx_fold[src];
             reinterpret_cast<int32_t *>(base + obh4)[(size_t)g * d.Ncp + n] = h.bh_fold[src];
@@ -456,7 +472,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       for (int g = 0; g < 4; ++g) {
         const int sg = g < 4 - h.G ? 4 - h.G : g;  // an absent gate borrows valid numbers; its rows are zero
         ra.Mh[g] = h.Mh[sg]; ra.rh[g] = 31 - h.eh[sg];
-        if (ra.rh[g] < 33) ra.pre_h = 1;
+        ra.pre_h = std::max(ra.pre_h, preshift_mode(ra.rh[g], d.amax_h[sg]));
         ra.Mln[g] = h.Mln[sg]; ra.rln[g] = 31 - h.eln[sg];
       }
       for (int j = 0; j < 3; ++j) { ra.Mc[j] = h.Mc[j]; ra.rc[j] = 31 - h.ec[j]; }
@@ -502,10 +518,12 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
         ga.A = in; ga.lda = ld_in; ga.T = T; ga.B = B; ga.Bp = ra.Bp;
         ga.W2 = d.W2; ga.kpad = d.Ipad; ga.tiles = d.GS * 8; ga.bx2 = d.bx2;
         ga.all_hi = 1;
+        ga.pre = 0;
         for (int g = 0; g < 4; ++g) {
           const int sg = g < 4 - h.G ? 4 - h.G : g;
           ga.M[g] = h.Mx[sg]; ga.r[g] = 31 - h.ex[sg];
           if (ga.r[g] < 32) ga.all_hi = 0;
+          ga.pre = std::max(ga.pre, preshift_mode(ga.r[g], d.amax_x[sg]));
         }
         ga.tx2 = reinterpret_cast<int4 *>(tx);
         if (in_gemm_ws_supported(ga))

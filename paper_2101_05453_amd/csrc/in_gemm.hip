@@ -27,13 +27,16 @@ typedef short v2s __attribute__((ext_vector_type(2)));
 
 namespace {
 
-// sat16(rescale(s, M, r)) of two values, packed; PRE = some shift is below 33
-template <bool PRE>
+// sat16(rescale(s, M, r)) of two values, packed; PRE = operand treatment (InGemmArgs::pre)
+template <int PRE>
 __device__ __forceinline__ int32_t requant2(int32_t s0, int32_t s1, const RescaleHi &p0, const RescaleHi &p1) {
-  if (PRE) {
-    const int32_t l0 = (int32_t)(0x7FFFFFFFu >> p0.k), l1 = (int32_t)(0x7FFFFFFFu >> p1.k);
-    s0 = clamp_i32(s0, -l0 - 1, l0) << p0.k;
-    s1 = clamp_i32(s1, -l1 - 1, l1) << p1.k;
+  if (PRE == 2) {
+    s0 = rescale_preshift(s0, p0);
+    s1 = rescale_preshift(s1, p1);
+  }
+  if (PRE == 1) {
+    s0 <<= p0.k;
+    s1 <<= p1.k;
   }
   const int32_t v0 = (__mulhi(s0, p0.M) + p0.add) >> p0.sh;
   const int32_t v1 = (__mulhi(s1, p1.M) + p1.add) >> p1.sh;
@@ -42,7 +45,7 @@ __device__ __forceinline__ int32_t requant2(int32_t s0, int32_t s1, const Rescal
   return __builtin_bit_cast(int32_t, pk);
 }
 
-template <int KS, bool PRE>
+template <int KS, int PRE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void in_gemm_ws_kernel(InGemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   constexpr int LS = KS * 32 + 16;                      // activation row stride in LDS
@@ -235,19 +238,25 @@ constexpr unsigned lds_bytes_ks() {  // NST stages of NCH * 4 KB
 template <int KS>
 hipError_t init_ks() {
   static_assert(lds_bytes_ks<KS>() <= 160 * 1024, "activation stages exceed LDS");
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(in_gemm_ws_kernel<KS, true>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(in_gemm_ws_kernel<KS, 0>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes_ks<KS>());
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void *>(in_gemm_ws_kernel<KS, false>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes_ks<KS>());
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(in_gemm_ws_kernel<KS, 1>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes_ks<KS>());
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(in_gemm_ws_kernel<KS, 2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes_ks<KS>());
+  return e;
 }
 
 template <int KS>
-void launch_ks(hipStream_t s, const InGemmArgs &a, int grid, bool pre) {
-  if (pre)
-    hipLaunchKernelGGL((in_gemm_ws_kernel<KS, true>), dim3(grid), dim3(256), lds_bytes_ks<KS>(), s, a);
+void launch_ks(hipStream_t s, const InGemmArgs &a, int grid) {
+  if (a.pre == 0)
+    hipLaunchKernelGGL((in_gemm_ws_kernel<KS, 0>), dim3(grid), dim3(256), lds_bytes_ks<KS>(), s, a);
+  else if (a.pre == 1)
+    hipLaunchKernelGGL((in_gemm_ws_kernel<KS, 1>), dim3(grid), dim3(256), lds_bytes_ks<KS>(), s, a);
   else
-    hipLaunchKernelGGL((in_gemm_ws_kernel<KS, false>), dim3(grid), dim3(256), lds_bytes_ks<KS>(), s, a);
+    hipLaunchKernelGGL((in_gemm_ws_kernel<KS, 2>), dim3(grid), dim3(256), lds_bytes_ks<KS>(), s, a);
 }
 
 }  // namespace
@@ -271,10 +280,9 @@ bool in_gemm_ws_supported(const InGemmArgs &a) {
 void launch_in_gemm_ws(hipStream_t s, const InGemmArgs &a0, int num_cus) {
   if (a0.T <= 0 || a0.B <= 0) return;
   InGemmArgs a = a0;
-  bool pre = false;
   for (int g = 0; g < 4; ++g) {
     a.rs[g] = rescale_hi_prepare(a.M[g], a.r[g]);
-    pre = pre || a.rs[g].k != 0;
+    if (a.rs[g].k != 0 && a.pre == 0) a.pre = 2;  // a caller that proved no bound
   }
   const int cbs = a.tiles / 8;
   const int nrb = (a.T * a.Bp) >> 5;
@@ -283,10 +291,10 @@ void launch_in_gemm_ws(hipStream_t s, const InGemmArgs &a0, int num_cus) {
   if (parts > nrb) parts = nrb;
   a.parts = parts;
   const int grid = parts * cbs;
-  if (a.kpad <= 256) launch_ks<8>(s, a, grid, pre);
-  else if (a.kpad <= 512) launch_ks<16>(s, a, grid, pre);
-  else if (a.kpad <= 640) launch_ks<20>(s, a, grid, pre);
-  else launch_ks<32>(s, a, grid, pre);
+  if (a.kpad <= 256) launch_ks<8>(s, a, grid);
+  else if (a.kpad <= 512) launch_ks<16>(s, a, grid);
+  else if (a.kpad <= 640) launch_ks<20>(s, a, grid);
+  else launch_ks<32>(s, a, grid);
 }
 
 }  // namespace lstm_int

@@ -200,9 +200,12 @@ LSTM_HD int32_t rescale_preshift(int32_t a, const RescaleHi &p) {
   a = a > -lim - 1 ? a : -lim - 1;
   return a << p.k;
 }
-template <bool PRE = true>
+// PRE: 2 = clamp and shift the operand (any operand), 1 = shift only (the caller
+// knows that the shifted operand fits 32 bits), 0 = neither (p.k == 0, or done already)
+template <int PRE = 2>
 LSTM_HD int32_t rescale_sat16_pre(int32_t a, const RescaleHi &p) {
-  if (PRE) a = rescale_preshift(a, p);  // PRE = false: the caller knows that p.k == 0, or has shifted already
+  if (PRE == 2) a = rescale_preshift(a, p);
+  if (PRE == 1) a <<= p.k;
 #if defined(__HIP_DEVICE_COMPILE__)
   const int32_t hi = __mulhi(a, p.M);
 #else

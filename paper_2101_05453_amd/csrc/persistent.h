@@ -27,6 +27,7 @@ struct InGemmArgs {
   int32_t M[4], r[4], all_hi;
   int4 *tx2;
   // filled by launch_in_gemm_ws
+  int pre;            // operand treatment of the rescale: 0 none, 1 left shift, 2 clamp and left shift
   int parts;          // row partitions; workgroup id -> (id % parts, id / parts)
   RescaleHi rs[4];    // per gate, prepared from (M, r)
 };
@@ -53,7 +54,7 @@ struct RecArgs {
   const int32_t *qb4;  // [4][Ncp]
   const int16_t *Pq3;  // [3][Ncp]
   int32_t Mh[4], rh[4];
-  int32_t pre_h;  // some rh is below 33
+  int32_t pre_h;  // operand treatment of the R h rescale: 0 none, 1 left shift, 2 clamp and left shift
   int32_t Mc[3], rc[3];
   int32_t Mln[4], rln[4];
   int32_t Mm, rm, zp_m;

@@ -191,7 +191,7 @@ size_t rec_lds_bytes(const RecArgs &a) {
   n += (a.tanhc_blob != a.tanh_blob ? 3 : 2) * (size_t)kLutBlobBytes;
   if (proj) {
     const int per_cu = (a.ptiles + a.GS - 1) / a.GS;
-    n += (size_t)per_cu * 32 * (a.npadp + 16);
+    n += ((size_t)per_cu * 32 * (a.npadp + 16) + 1023) / 1024 * 1024;  // loaded in whole 1 KB chunks
   }
   return n;
 }

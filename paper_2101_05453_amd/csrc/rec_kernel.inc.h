@@ -173,20 +173,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     prm->m_c = a.m_c; prm->glo = ln ? -32767 : -32768;
   }
   for (int i = tid; i < rows_pg * LS / 16; i += 256) reinterpret_cast<int4 *>(hT)[i] = int4{0, 0, 0, 0};
-  for (int i = tid; i < kLutBlobBytes / 16; i += 256) {
-    reinterpret_cast<int4 *>(const_cast<uint8_t *>(lutS))[i] = reinterpret_cast<const int4 *>(a.sig_blob)[i];
-    reinterpret_cast<int4 *>(const_cast<uint8_t *>(lutT))[i] = reinterpret_cast<const int4 *>(a.tanh_blob)[i];
-    if (!share_tanh)
-      reinterpret_cast<int4 *>(const_cast<uint8_t *>(lutC))[i] = reinterpret_cast<const int4 *>(a.tanhc_blob)[i];
-  }
-  for (int pt = 0; pt < my_ptiles; ++pt) {
-    const int8_t *src = a.Wp2 + (size_t)(member + pt * GS) * 32 * a.npadp;
-    const int chunks_per_row = a.npadp >> 4;
-    for (int i = tid; i < 32 * chunks_per_row; i += 256) {
-      const int r = i / chunks_per_row, c = i - r * chunks_per_row;
-      *reinterpret_cast<int4 *>(WpL + ((size_t)pt * 32 + r) * WLS + (c << 4)) =
-          *reinterpret_cast<const int4 *>(src + (size_t)r * a.npadp + (c << 4));
+  // tables and W_proj tiles: global -> LDS loads, all in flight together
+  {
+    auto dma = [&](const void *src, const void *dst) {
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                       (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    };
+    static_assert(kLutBlobBytes % 1024 == 0, "whole 1 KB chunks");
+    for (int c = wave; c < kLutBlobBytes / 1024; c += 4) {
+      dma(a.sig_blob + c * 1024 + lane * 16, lutS + c * 1024);
+      dma(a.tanh_blob + c * 1024 + lane * 16, lutT + c * 1024);
+      if (!share_tanh) dma(a.tanhc_blob + c * 1024 + lane * 16, lutC + c * 1024);
     }
+    // the workgroup's tiles pt = 0.. are rows [32 pt, 32 pt + 32) of one [rows][WLS] block in LDS;
+    // bytes of the row padding and past the last row read the start of the weights
+    const int wp_rows = my_ptiles * 32;
+    const int wp_chunks = (wp_rows * WLS + 1023) >> 10;
+    for (int c = wave; c < wp_chunks; c += 4) {
+      const int o = c * 1024 + lane * 16;
+      const int r = o / WLS, col_b = o - r * WLS;
+      const int8_t *src = a.Wp2;
+      if (r < wp_rows && col_b < a.npadp) {
+        const int pt = r >> 5;
+        src = a.Wp2 + ((size_t)(member + pt * GS) * 32 + (r & 31)) * a.npadp + col_b;
+      }
+      dma(src, WpL + c * 1024);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
 
   // cell state of this lane's 8 cells x RT row tiles, kept in registers
@@ -335,7 +348,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // With a peephole the o gate keeps tx + th here and is finished after c^t.
     constexpr int32_t glo = ln ? -32767 : -32768;  // layer norm takes symmetric gate sums
     auto gate_sums = [&](auto pre_tag) {
-      constexpr bool PRE = decltype(pre_tag)::value;  // some shift of the R h rescale is below 33
+      constexpr int PRE = decltype(pre_tag)::value;  // operand treatment of the R h rescale (RecArgs::pre_h)
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         int32_t s1[4] = {0, 0, 0, 0};
@@ -376,7 +389,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
       }
     };
-    if (a.pre_h) gate_sums(std::true_type{}); else gate_sums(std::false_type{});
+    if (a.pre_h == 0)
+      gate_sums(std::integral_constant<int, 0>{});
+    else if (a.pre_h == 1)
+      gate_sums(std::integral_constant<int, 1>{});
+    else
+      gate_sums(std::integral_constant<int, 2>{});
 
     // Layer-norm statistics of a row are summed over the group's workgroups by
     // atomic adds into two 64-bit words per (row, gate), which are never reset:
@@ -482,7 +500,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           for (int g = gp; g < gp + 2; ++g)
             if (gmask >> g & 1)
 #pragma unroll
-              for (int c = 0; c < 4; ++c) xv[g][c] = rescale_sat16_pre<false>(xv[g][c], pl[g - gp]);
+              for (int c = 0; c < 4; ++c) xv[g][c] = rescale_sat16_pre<0>(xv[g][c], pl[g - gp]);
         }
       } else {
 #pragma unroll
@@ -640,7 +658,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           // sat8 of the sum is unchanged by the 16-bit clamp before it: |zp| <= 128
           int32_t om = xo[rt][tl][c] * tc[rt][tl][c];  // below 2^30 in magnitude
           if (pre_m) om = rescale_preshift(om, pm);
-          const int32_t mq = sat8(rescale_sat16_pre<false>(om, pm) + zp_m);
+          const int32_t mq = sat8(rescale_sat16_pre<0>(om, pm) + zp_m);
           pk |= (uint32_t)(mq & 0xFF) << (8 * c);
         }
         if (row < a.B && n0 < a.N) {  // N % 8 == 0: the four cells are valid together
