@@ -114,7 +114,7 @@ Workspace plan_workspace(const lstm_int_model *m, int64_t T, int64_t B) {
   w.c = take((size_t)B * maxN * 2);
   w.h0 = take((size_t)B * maxHpad);
   w.sync = take(kSyncBytes);
-  w.m2 = take((size_t)T * B * maxNpadp);
+  w.m2 = take((size_t)T * round_up(B, 32) * maxNpadp);
   w.total = off;
   return w;
 }

@@ -71,7 +71,7 @@ struct RecArgs {
   const int8_t *h0;  // [B, Hpad]
   int8_t *out;       // [T, B, Hpad]
   int8_t *y;         // [T, B, H] or NULL
-  int8_t *mbuf;      // [T, B, npadp] (projection only)
+  int8_t *mbuf;      // [T][Bp / 32][npadp / 32][32 rows][32 cells] (projection only)
   const int16_t *c_in;  // [B, N] or NULL (zeros)
   int16_t *c_out;       // [B, N] or NULL
   // synchronization scratch, zeroed before the launch

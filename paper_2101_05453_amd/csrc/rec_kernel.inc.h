@@ -642,8 +642,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           }
       }
     }
-    int8_t *mdst = proj ? a.mbuf + (size_t)t * a.B * a.npadp : a.out + (size_t)t * a.B * a.Hpad;
-    const int mld = proj ? a.npadp : a.Hpad;
+    // Without a projection m is h and goes to the layer output [T, B, Hpad].  With one it goes to the
+    // exchange buffer in the order the projection reads it: [t][row tile][k step][row % 32][32 cells],
+    // so that a wave's load of one k step is one contiguous KB of whole cache lines.
+    int8_t *mdst = proj ? a.mbuf + (size_t)t * a.Bp * a.npadp : a.out + (size_t)t * a.B * a.Hpad;
     const RescaleHi pm = prm->m;
     const int32_t zp_m = prm->zp_m;
 #pragma unroll
@@ -662,7 +664,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           pk |= (uint32_t)(mq & 0xFF) << (8 * c);
         }
         if (row < a.B && n0 < a.N) {  // N % 8 == 0: the four cells are valid together
-          *reinterpret_cast<uint32_t *>(mdst + (size_t)row * mld + n0) = pk;
+          const size_t off = proj ? ((((size_t)(row >> 5) * (a.npadp >> 5) + (n0 >> 5)) * 32 + (row & 31)) * 32 + (n0 & 31))
+                                  : (size_t)row * a.Hpad + n0;
+          *reinterpret_cast<uint32_t *>(mdst + off) = pk;
           if (!proj && a.y) {
             int8_t *yd = a.y + ((size_t)t * a.B + row) * a.H + n0;  // H = N, a multiple of 4
             *reinterpret_cast<uint32_t *>(yd) = pk;
@@ -683,15 +687,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const int ptile = member + pt * GS;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-          int row = row0 + rt * 32 + col;
-          row = row < a.B ? row : a.B - 1;
-          const int8_t *mrow = a.mbuf + ((size_t)t * a.B + row) * a.npadp + (b2 << 4) + wave * per_wave * 32;
+          // rows of the tile beyond the batch were never written; their results are not stored either
+          const int8_t *mrow = a.mbuf + (size_t)t * a.Bp * a.npadp +
+                               ((((size_t)((row0 >> 5) + rt) * (a.npadp >> 5) + wave * per_wave) * 32 + col) << 5) +
+                               (b2 << 4);
           const int8_t *wrow = WpL + ((size_t)pt * 32 + col) * WLS + (b2 << 4) + wave * per_wave * 32;
           int4 mv[16];
 #pragma unroll
           for (int k = 0; k < 16; ++k) {
             const int kk = k < per_wave ? k : per_wave - 1;  // steps past the end re-read the last one
-            mv[k] = *reinterpret_cast<const int4 *>(mrow + kk * 32);
+            mv[k] = *reinterpret_cast<const int4 *>(mrow + kk * 1024);
           }
           v16i pacc;
 #pragma unroll
