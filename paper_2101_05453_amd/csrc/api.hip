@@ -71,7 +71,8 @@ struct lstm_int_model {
   int *status = nullptr;  // device word raised by the persistent kernel when a wait gives up
   int path = 0;
   int spin_limit = 1 << 21;
-  int poll_sleep = 8, stats_sleep = 0;  // pauses between polls, in units of 64 clocks
+  int poll_sleep = 4, stats_sleep = 0;  // pauses between polls, in units of 64 clocks
+  int idle_sleep = 64, idle_poll_sleep = 12;
   int phase_timing = 0;
   int num_cus = 256;
   Profile prof;
@@ -493,6 +494,8 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.spin_limit = m->spin_limit;
       ra.poll_sleep = m->poll_sleep;
       ra.stats_sleep = m->stats_sleep;
+      ra.idle_sleep = m->idle_sleep;
+      ra.idle_poll_sleep = m->idle_poll_sleep;
       ra.ticks = m->phase_timing ? reinterpret_cast<long long *>(m->status + 16) : nullptr;
       // the kernel's one-product form of rescale needs shifts in [3, 62], its tables must compress
       auto shift_ok = [](int r) { return r >= 3 && r <= 62; };
@@ -639,9 +642,12 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
       return LSTM_INT_E_DEVICE;
     return LSTM_INT_OK;
   }
-  if (!strcmp(key, "poll_sleep") || !strcmp(key, "stats_sleep")) {
+  if (!strcmp(key, "poll_sleep") || !strcmp(key, "stats_sleep") || !strcmp(key, "idle_sleep") ||
+      !strcmp(key, "idle_poll_sleep")) {
     if (value < 0 || value > 1024) return LSTM_INT_E_INVALID_ARG;
-    (key[0] == 'p' ? m->poll_sleep : m->stats_sleep) = (int)value;
+    int &dst = !strcmp(key, "poll_sleep") ? m->poll_sleep : !strcmp(key, "stats_sleep") ? m->stats_sleep
+               : !strcmp(key, "idle_sleep") ? m->idle_sleep : m->idle_poll_sleep;
+    dst = (int)value;
     return LSTM_INT_OK;
   }
   if (!strcmp(key, "spin_limit")) {

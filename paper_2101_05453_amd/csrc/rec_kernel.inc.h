@@ -27,13 +27,15 @@ typedef unsigned long long u64;
 // another workgroup gave up), raising the status word so that every workgroup
 // leaves the kernel; lds_flag[0] is then 0 for good.
 __device__ __forceinline__ bool group_sync(unsigned *counter, unsigned &epoch, int GS, int *status,
-                                           int spin_limit, int poll_sleep, int *lds_flag) {
+                                           int spin_limit, int first_sleep, int poll_sleep, int *lds_flag) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (GS == 1) return true;
   epoch += (unsigned)GS;
   if (threadIdx.x == 0) {
     __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // a workgroup that knows the others have work left before they arrive keeps off the counter meanwhile
+    for (int i = 0; i < first_sleep; ++i) __builtin_amdgcn_s_sleep(1);
     int budget = spin_limit;
     for (;;) {
       const unsigned c = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -675,7 +677,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     }
     TICK(6);
-    if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, a.poll_sleep, flag)) return;
+    if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, 0, a.poll_sleep, flag)) return;
     TICK(7);
 
     // ---- projection (Sec. 3.2.8): tile pt of 32 outputs, K = N split over the four waves
@@ -751,7 +753,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
       }
       TICK(8);
-      if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, a.poll_sleep, flag)) return;
+      if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, my_ptiles == 0 ? a.idle_sleep : 0,
+                      my_ptiles == 0 ? a.idle_poll_sleep : a.poll_sleep, flag))
+        return;
       TICK(9);
     }
   }
