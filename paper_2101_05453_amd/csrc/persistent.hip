@@ -184,9 +184,9 @@ bool rec_supported(int N, int H, int flags, int B, int *ks, int *rt, int *groups
 size_t rec_lds_bytes(const RecArgs &a) {
   const int items = (a.rows_pg / 32) * 128;
   const bool proj = a.flags & 8;
-  size_t tile = ((size_t)a.rows_pg * (a.ks * 32 + 16) + 4095) / 4096 * 4096;
+  size_t tile = (((size_t)a.rows_pg * (a.ks * 32 + 16) + 1023) / 1024 + 1) * 1024;
   if (proj && tile < 4 * 16 * 64 * 4) tile = 4 * 16 * 64 * 4;
-  size_t n = tile + (size_t)4 * items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 2 +
+  size_t n = tile + (size_t)4 * items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 2 + 4 * 64 * 4 +
              kPrmLdsBytes + 16 + 16 * 8;
   n += (a.tanhc_blob != a.tanh_blob ? 3 : 2) * (size_t)kLutBlobBytes;
   if (proj) {

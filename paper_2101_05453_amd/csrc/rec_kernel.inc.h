@@ -111,7 +111,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   int8_t *hT = reinterpret_cast<int8_t *>(p);
   int32_t *pred = reinterpret_cast<int32_t *>(p);  // projection partials reuse the h tile between steps
   {
-    const size_t tile_bytes = ((size_t)rows_pg * LS + 4095) / 4096 * 4096;  // every wave loads the same number of 1 KB chunks
+    // whole 1 KB chunks, plus one that takes the loads past the tile (every wave issues the same number)
+    const size_t tile_bytes = (((size_t)rows_pg * LS + 1023) / 1024 + 1) * 1024;
     const size_t pred_bytes = proj ? 4 * 16 * 64 * 4 : 0;
     p += tile_bytes > pred_bytes ? tile_bytes : pred_bytes;
   }
@@ -120,6 +121,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   double *LdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;  // layer-norm weights / 2^10 as doubles
   double *bdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;  // layer-norm biases / 2^10 + 2^-11 as doubles
   int16_t *PqL = reinterpret_cast<int16_t *>(p);         p += 4 * 64 * 2;  // 3 used
+  int32_t *bhL = reinterpret_cast<int32_t *>(p);         p += 4 * 64 * 4;
   PrmLds *prm = reinterpret_cast<PrmLds *>(p);           p += sizeof(PrmLds);
   int *flag = reinterpret_cast<int *>(p);                p += 16;
   u64 *tickL = reinterpret_cast<u64 *>(p);               p += 16 * 8;  // phase timers
@@ -148,20 +150,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
   }
   const int cell_w = wave * 16 + 4 * b2;  // + tile * 8 + c, within the workgroup's 64 cells
-  int32_t bhr[2][16];                     // folded recurrent bias of [tile][4*gate + c]
-#pragma unroll
-  for (int tl = 0; tl < 2; ++tl)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int4 b4 = *reinterpret_cast<const int4 *>(a.bh4 + (size_t)g * a.Ncp + member * 64 + cell_w + tl * 8);
-      bhr[tl][g * 4 + 0] = b4.x; bhr[tl][g * 4 + 1] = b4.y; bhr[tl][g * 4 + 2] = b4.z; bhr[tl][g * 4 + 3] = b4.w;
-    }
   {
     const int g = tid >> 6, n = tid & 63;  // 256 threads = 4 gates x 64 cells
     const size_t idx = (size_t)g * a.Ncp + member * 64 + n;
     LdL[tid] = ln ? ln_weight_scaled(a.Lq4[idx]) : 0.0;
     bdL[tid] = ln ? ln_bias_scaled(a.qb4[idx]) : 0.0;
     PqL[tid] = (ph && g < 3) ? a.Pq3[idx] : 0;
+    bhL[tid] = a.bh4[idx];  // folded recurrent bias, the accumulators' initial value each step
   }
   if (tid < 4) {
     prm->h[tid] = rescale_hi_prepare(a.Mh[tid], a.rh[tid]);
@@ -293,10 +288,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     {
       const int8_t *hp = t == 0 ? a.h0 : a.out + (size_t)(t - 1) * a.B * a.Hpad;
 #pragma unroll
-      for (int j = 0; j < NCH; ++j)  // chunks past the tile land in its padding
+      for (int j = 0; j < NCH; ++j)  // chunks past the tile land in the spare chunk behind it
         __builtin_amdgcn_global_load_lds(
               (const __attribute__((address_space(1))) void *)(hp + hsrc[j]),
-              (__attribute__((address_space(3))) void *)(lds + (wave + 4 * j) * 1024), 16, 0, 0);
+              (__attribute__((address_space(3))) void *)(lds + (wave + 4 * j < TILE_KB ? wave + 4 * j : TILE_KB) * 1024),
+              16, 0, 0);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __syncthreads();
@@ -318,7 +314,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
       for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[rt][tl][v] = bhr[tl][v];
+        for (int v = 0; v < 16; ++v) acc[rt][tl][v] = bhL[(v >> 2) * 64 + cell_w + tl * 8 + (v & 3)];
     {
       constexpr int DEPTH = 4;  // h fragments in flight ahead of the MFMAs
       v4i hf[RT][DEPTH];
@@ -467,15 +463,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // use, which exposes one LDS round trip per element (measured: more than
     // half of this phase).
     // gates of `gmask` (bit g) of tile (rt, tl): gate sums -> layer norm -> xv[g][c]
+    constexpr int LNB = KS >= 32 ? 1 : 2;  // the deepest register-resident R leaves room for less
     auto normalize = [&](int rt, int tl, int gmask, const LnRow2 (&lr)[4], int32_t (&xv)[4][4]) {
       if (ln) {
 #pragma unroll
-        for (int gp = 0; gp < 4; gp += 2) {  // two gates per batch of reads: 16 doubles in flight
-          if (!(gmask >> gp & 3)) continue;
-          double wL[2][4], wb[2][4];
-          RescaleHi pl[2];
+        for (int gp = 0; gp < 4; gp += LNB) {  // LNB gates per batch of reads: 8 LNB doubles in flight
+          if (!(gmask >> gp & ((1 << LNB) - 1))) continue;
+          double wL[LNB][4], wb[LNB][4];
+          RescaleHi pl[LNB];
 #pragma unroll
-          for (int g = gp; g < gp + 2; ++g)
+          for (int g = gp; g < gp + LNB; ++g)
             if (gmask >> g & 1) {
               pl[g - gp] = prm->ln[g];
 #pragma unroll
@@ -486,20 +483,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             }
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int g = gp; g < gp + 2; ++g)
+          for (int g = gp; g < gp + LNB; ++g)
             if (gmask >> g & 1)
 #pragma unroll
               for (int c = 0; c < 4; ++c)
                 xv[g][c] = ln_second_stage(acc[rt][tl][g * 4 + c], lr[g], wL[g - gp][c], wb[g - gp][c]);
           if (pre_ln) {  // some second-stage shift is below 33 (uniform; rare)
 #pragma unroll
-            for (int g = gp; g < gp + 2; ++g)
+            for (int g = gp; g < gp + LNB; ++g)
               if (gmask >> g & 1)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) xv[g][c] = rescale_preshift(xv[g][c], pl[g - gp]);
           }
 #pragma unroll
-          for (int g = gp; g < gp + 2; ++g)
+          for (int g = gp; g < gp + LNB; ++g)
             if (gmask >> g & 1)
 #pragma unroll
               for (int c = 0; c < 4; ++c) xv[g][c] = rescale_sat16_pre<0>(xv[g][c], pl[g - gp]);
@@ -561,7 +558,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       for (int tl = 0; tl < 2; ++tl) {
         int32_t xv[4][4], tv[4][4];
         normalize(rt, tl, gates_now, lr, xv);
-        lookup(gates_now, xv, gate_blob, gate_sh, gate_full, tv);
+        if (KS >= 32) {  // the deepest register-resident R leaves room for two gates' reads at a time
+          lookup(gates_now & 3, xv, gate_blob, gate_sh, gate_full, tv);
+          lookup(gates_now & 12, xv, gate_blob, gate_sh, gate_full, tv);
+        } else {
+          lookup(gates_now, xv, gate_blob, gate_sh, gate_full, tv);
+        }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           xi[rt][tl][c] = cifg ? 0 : mirror_sigmoid(xv[0][c], tv[0][c]);

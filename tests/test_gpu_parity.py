@@ -68,6 +68,26 @@ def test_benchmark_configs_full_size_sampled_rows(orc, name, rows):
     run_and_compare(orc, layers, x, name, trace=False, rows=rows)
 
 
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_benchmark_configs_take_the_persistent_path(name):
+    """Every benchmark configuration must fit the persistent kernel (its LDS
+    budget at C4 is within a KB of the limit): no per-step cell kernel may run."""
+    import torch
+
+    from paper_2101_05453_amd import binding, calibration
+
+    layers, x = wl.make_workload(name, batch=None, steps=2, num_layers=2 if name == "C4" else None)
+    calibration.collect_statistics(layers, x)
+    model = binding.prepare(layers, device=0)
+    q0 = model.get_quant(0)
+    xd = torch.from_numpy(calibration.quantize_input(x, q0["s_x"], q0["zp_x"])).cuda()
+    model.profile_begin()
+    model.forward(xd)
+    prof = model.profile_end()
+    assert prof["recurrent"]["launches"] > 0 and prof["cell"]["launches"] == 0, prof
+    assert model.device_status() == 0
+
+
 def test_split_sequence_carries_state(orc):
     import torch
 
