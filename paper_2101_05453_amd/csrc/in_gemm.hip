@@ -137,7 +137,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       if (pair == 3) {
         const int tile = cb * 8 + wave * 2 + tl;
         int4 *dst = a.tx2 + (((size_t)rb_prev * a.tiles + tile) * 2 + half) * 64 + lane;
-        *dst = int4{word[0], word[1], word[2], word[3]};
+        // streaming store: 268 MB per C4 layer pass through, nothing of it is read again before the
+        // recurrent kernel, and the activation blocks and weights keep their place in L2
+        __builtin_nontemporal_store(v4i{word[0], word[1], word[2], word[3]}, reinterpret_cast<v4i *>(dst));
       }
     }
   };
