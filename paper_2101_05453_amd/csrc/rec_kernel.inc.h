@@ -302,8 +302,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
       for (int tl = 0; tl < 2; ++tl) {
         const int4 *src = tx_ptr(t, rt, tl);
-        txv[rt][tl][0] = src[0];
-        txv[rt][tl][1] = src[64];
+        // read once: a streaming load keeps the W x terms from displacing the exchange buffers in L2
+        const v4i t0 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src));
+        const v4i t1 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src + 64));
+        txv[rt][tl][0] = int4{t0.x, t0.y, t0.z, t0.w};
+        txv[rt][tl][1] = int4{t1.x, t1.y, t1.z, t1.w};
       }
     TICK(0);
 
