@@ -504,6 +504,13 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
         if (!shift_ok(ra.rh[g]) || (h.layer_norm() && !shift_ok(ra.rln[g]))) ok = false;
       for (int j = 4 - h.G; j < 3; ++j)
         if (h.peephole() && !shift_ok(ra.rc[j])) ok = false;
+      if (ok && ra.rows_pg == 64 && rec_lds_bytes(ra) > 160 * 1024) {
+        // two row tiles per group do not fit the LDS: one tile per group, more launches over the batch
+        p2_rt = 1;
+        ra.rows_pg = 32;
+        p2_groups = std::min(8 * (32 / d.GS), (B + 31) / 32);
+        ra.groups = p2_groups;
+      }
       if (!ok || rec_lds_bytes(ra) > 160 * 1024) use_p2 = false;
     }
     if (use_p2) {

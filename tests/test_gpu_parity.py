@@ -88,6 +88,21 @@ def test_benchmark_configs_take_the_persistent_path(name):
     assert model.device_status() == 0
 
 
+def test_batch_beyond_one_launch(orc):
+    """N = 2048 with a projection: 8 groups of 32 rows per launch (two row tiles
+    per group would not fit the LDS), so B = 300 runs in two launches, the
+    second with a ragged last group; still on the persistent path."""
+    import torch
+
+    print("batch beyond one launch", flush=True)
+    layers, x = wl.make_custom([64], 2048, 640, wl.LAYER_NORM | wl.PROJECTION, 300, 3, seed=21, weight_param=0.03)
+    lib_model, y = run_and_compare(orc, layers, x, "b300", trace=False, rows=[0, 31, 32, 255, 256, 257, 290, 299])
+    lib_model.profile_begin()
+    lib_model.forward(torch.zeros((3, 300, 64), dtype=torch.int8, device="cuda"))
+    prof = lib_model.profile_end()
+    assert prof["recurrent"]["launches"] == 2 and prof["cell"]["launches"] == 0, prof
+
+
 def test_split_sequence_carries_state(orc):
     import torch
 
