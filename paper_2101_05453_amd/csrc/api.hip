@@ -543,12 +543,14 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       }
       // batch rows beyond one launch's groups run in further launches (rows never interact)
       for (int b0 = 0; b0 < B; b0 += p2_groups * ra.rows_pg) {
-        {
-          Timed t(m->prof, s, LSTM_INT_K_OTHER);
-          launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), (int64_t)(kSyncBytes / 2), 0);
-        }
         ra.batch0 = b0;
         ra.groups = std::min(p2_groups, (B - b0 + ra.rows_pg - 1) / ra.rows_pg);
+        {
+          // all counters, and the statistics words of the groups of this launch (they follow the counters)
+          Timed t(m->prof, s, LSTM_INT_K_OTHER);
+          const int64_t bytes = 256 * 64 * 4 + (int64_t)ra.groups * 4 * 256 * 8;
+          launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), bytes / 2, 0);
+        }
         Timed t(m->prof, s, LSTM_INT_K_RECURRENT);
         if (launch_rec(s, ra) != hipSuccess) return LSTM_INT_E_DEVICE;
       }

@@ -162,13 +162,18 @@ LSTM_HD int32_t ln_apply(int32_t q, const LnRow &row, int32_t qL, int32_t qb, in
 // / 2^10).  The rounding is done by adding 1.5 * 2^52, whose sum holds the
 // integer in its low mantissa bits; clamping to the int32 range first is the
 // same as clamping afterwards because the bounds are integers.
+// Stored per row: a = 2^20 / sigma and b = c0 / sigma, so that the quotient estimate is one fused
+// multiply-add, q a + b.  Both products are rounded (relative error 2^-53 each, as is the fused
+// result), which moves the estimate by less than 3 * 2^-53 * 2^37 / sigma < 2^-14 / sigma, still far
+// inside the 1 / (2 sigma) margin above.
 struct LnRow2 {
-  double inv_sigma, c0;
+  double a, b;
 };
 LSTM_HD LnRow2 ln_row2(const LnRow &r) {
   LnRow2 o;
-  o.inv_sigma = r.sigma ? r.inv_sigma : 0.0;
-  o.c0 = (double)(-(int64_t)r.mean * 1024 + (r.sigma >> 1)) + 0.5;
+  const double inv = r.sigma ? r.inv_sigma : 0.0;
+  o.a = 1048576.0 * inv;
+  o.b = ((double)(-(int64_t)r.mean * 1024 + (r.sigma >> 1)) + 0.5) * inv;
   return o;
 }
 LSTM_HD double ln_weight_scaled(int32_t qL) { return (double)qL * (1.0 / 1024.0); }
@@ -224,8 +229,7 @@ LSTM_HD int32_t f64_low_word(double w) {
 }
 // the layer-norm value before its second-stage rescale
 LSTM_HD int32_t ln_second_stage(int32_t q, const LnRow2 &row, double qLs, double qbs) {
-  const double num = fma((double)q, 1048576.0, row.c0);
-  const double qn = floor(num * row.inv_sigma);
+  const double qn = floor(fma((double)q, row.a, row.b));
   double v = fma(qn, qLs, qbs);
   v = fmin(fmax(v, -2147483648.0), 2147483647.0);
   return f64_low_word(v + 6755399441055744.0);

@@ -676,7 +676,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           *reinterpret_cast<uint32_t *>(mdst + off) = pk;
           if (!proj && a.y) {
             int8_t *yd = a.y + ((size_t)t * a.B + row) * a.H + n0;  // H = N, a multiple of 4
-            *reinterpret_cast<uint32_t *>(yd) = pk;
+            __builtin_nontemporal_store(pk, reinterpret_cast<uint32_t *>(yd));  // not read again here
           }
         }
       }
