@@ -176,11 +176,14 @@ int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
  *           lstm_int_device_status becomes nonzero).
  *   "poll_sleep", "stats_sleep": pause between two polls of a group barrier /
  *           of the layer-norm statistics words inside the persistent kernel,
- *           in units of 64 clocks (0..1024; defaults 4 and 0).
+ *           in units of 64 clocks (0..1024; defaults 0 and 0).
+ *   "sync_sleep": pause before the first poll of the barrier at which all
+ *           workgroups of a group arrive together (the first polls would find
+ *           the count incomplete and delay the arrivals); -1 (default) = 16 for
+ *           groups of 16 workgroups and more, else 4.
  *   "idle_sleep", "idle_poll_sleep": the same for the workgroups that have no
  *           projection tile, at the barrier that follows the projection: pause
- *           before their first poll and between polls (defaults 64 and 12;
- *           their polls would otherwise delay the arrivals of the others).
+ *           before their first poll and between polls (defaults 64 and 12).
  *   "phase_timing": nonzero makes workgroup 0 of the persistent kernel add the
  *           time it spends in each of its phases to 16 device counters
  *           (diagnostics; read them with lstm_int_phase_ticks).

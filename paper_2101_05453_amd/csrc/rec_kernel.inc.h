@@ -682,7 +682,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     }
     TICK(6);
-    if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, 0, a.poll_sleep, flag)) return;
+    if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
     TICK(7);
 
     // ---- projection (Sec. 3.2.8): tile pt of 32 outputs, K = N split over the four waves
