@@ -177,6 +177,8 @@ int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
  *   "poll_sleep", "stats_sleep": pause between two polls of a group barrier /
  *           of the layer-norm statistics words inside the persistent kernel,
  *           in units of 64 clocks (0..1024; defaults 0 and 0).
+ *   "stats_first_sleep": pause before the first poll of the statistics words
+ *           (default 8).
  *   "sync_sleep": pause before the first poll of the barrier at which all
  *           workgroups of a group arrive together (the first polls would find
  *           the count incomplete and delay the arrivals); -1 (default) = 16 for

@@ -73,6 +73,7 @@ struct lstm_int_model {
   int spin_limit = 1 << 21;
   int poll_sleep = 0, stats_sleep = 0;  // pauses between polls, in units of 64 clocks
   int idle_sleep = 64, idle_poll_sleep = 12;
+  int stats_first_sleep = 8;
   int sync_sleep = -1;  // pause before the first poll where all arrive together; -1 = by group size
   int phase_timing = 0;
   int num_cus = 256;
@@ -496,6 +497,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.poll_sleep = m->poll_sleep;
       ra.stats_sleep = m->stats_sleep;
       ra.idle_sleep = m->idle_sleep;
+      ra.stats_first_sleep = m->stats_first_sleep;
       // the last arrival lands about 0.45 us after a workgroup's own in a group of 32, sooner in small groups
       ra.sync_sleep = m->sync_sleep >= 0 ? m->sync_sleep : (d.GS >= 16 ? 16 : 4);
       ra.idle_poll_sleep = m->idle_poll_sleep;
@@ -655,11 +657,12 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
     return LSTM_INT_OK;
   }
   if (!strcmp(key, "poll_sleep") || !strcmp(key, "stats_sleep") || !strcmp(key, "idle_sleep") ||
-      !strcmp(key, "idle_poll_sleep") || !strcmp(key, "sync_sleep")) {
+      !strcmp(key, "idle_poll_sleep") || !strcmp(key, "sync_sleep") || !strcmp(key, "stats_first_sleep")) {
     if (value < (strcmp(key, "sync_sleep") ? 0 : -1) || value > 1024) return LSTM_INT_E_INVALID_ARG;
     int &dst = !strcmp(key, "poll_sleep") ? m->poll_sleep : !strcmp(key, "stats_sleep") ? m->stats_sleep
                : !strcmp(key, "idle_sleep") ? m->idle_sleep
-               : !strcmp(key, "sync_sleep") ? m->sync_sleep : m->idle_poll_sleep;
+               : !strcmp(key, "sync_sleep") ? m->sync_sleep
+               : !strcmp(key, "stats_first_sleep") ? m->stats_first_sleep : m->idle_poll_sleep;
     dst = (int)value;
     return LSTM_INT_OK;
   }

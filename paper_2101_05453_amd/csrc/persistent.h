@@ -80,6 +80,7 @@ struct RecArgs {
   int *status;                 // [0] != 0: a wait gave up or the placement check failed
   int spin_limit;
   int poll_sleep, stats_sleep;  // pauses between two polls of a barrier / of the statistics words, x 64 clocks
+  int stats_first_sleep;  // pause before the first poll of the statistics words
   int sync_sleep;  // pause before the first poll of the barrier at which all workgroups arrive together
   int idle_sleep, idle_poll_sleep;  // workgroups without a projection tile, at the barrier after the projection:
                                     // pause before the first poll, and between polls

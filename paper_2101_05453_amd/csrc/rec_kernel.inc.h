@@ -428,6 +428,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           const u64 expect = (u64)(((unsigned)GS * (unsigned)(t + 1)) & 0xFFu);
           u64 c1, c2;
           int budget = a.spin_limit;
+          // the adds of the other workgroups need this long to land; a poll before that only delays them
+          for (int i = 0; i < a.stats_first_sleep; ++i) __builtin_amdgcn_s_sleep(1);
           for (;;) {
             c1 = __hip_atomic_load(&accS[(round * 2 + 0) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             c2 = __hip_atomic_load(&accS[(round * 2 + 1) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
