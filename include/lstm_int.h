@@ -186,6 +186,8 @@ int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
  *   "idle_sleep", "idle_poll_sleep": the same for the workgroups that have no
  *           projection tile, at the barrier that follows the projection: pause
  *           before their first poll and between polls (defaults 64 and 12).
+ *   "reset_status": clears the device status word (see lstm_int_device_status)
+ *           after a wait gave up; synchronizes the device.
  *   "phase_timing": nonzero makes workgroup 0 of the persistent kernel add the
  *           time it spends in each of its phases to 16 device counters
  *           (diagnostics; read them with lstm_int_phase_ticks).

@@ -650,6 +650,14 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
     m->path = (int)value;
     return LSTM_INT_OK;
   }
+  if (!strcmp(key, "reset_status")) {  // after a wait gave up: the word is sticky and stops every later kernel
+    if (m->device >= 0) {
+      if (hipSetDevice(m->device) != hipSuccess || hipDeviceSynchronize() != hipSuccess ||
+          hipMemset(m->status, 0, sizeof(int)) != hipSuccess)
+        return LSTM_INT_E_DEVICE;
+    }
+    return LSTM_INT_OK;
+  }
   if (!strcmp(key, "phase_timing")) {
     m->phase_timing = value != 0;
     if (m->device >= 0 && hipMemset(m->status + 16, 0, 16 * sizeof(long long)) != hipSuccess)
