@@ -13,11 +13,13 @@ HOSTMATH_LIB = os.path.join(HERE, "liblstm_int_hostmath.so")
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-Wall", "-Wno-unused-function"]
+# in_gemm.hip: MFMA results go to ordinary vector registers, where the requantization reads them without copies
+EXTRA_FLAGS = {"in_gemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src, verbose):
     obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-    cmd = ["hipcc", "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + HIP_FLAGS
+    cmd = ["hipcc", "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + HIP_FLAGS + EXTRA_FLAGS.get(src, [])
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0 or verbose:
         print(" ".join(cmd))

@@ -42,6 +42,7 @@ struct LayerDev {
   // per gate: bound of |W x + b'x| and |R h + b'h| over all inputs, max over rows of |b'| + 128 sum |w|
   int64_t amax_x[4] = {0, 0, 0, 0}, amax_h[4] = {0, 0, 0, 0};
   int8_t *W2 = nullptr;     // [GS*8][32][Ipad]
+  int8_t *W2f = nullptr;    // the same in MFMA operand order [GS*8][Ipad/32][64 lanes][16] (Ipad <= 1024), else NULL
   int32_t *bx2 = nullptr;   // [GS*8][32]
   int4 *R2 = nullptr;       // [GS][4][2][ks][64]
   int32_t *bh4 = nullptr, *qb4 = nullptr;  // [4][Ncp]
@@ -109,9 +110,10 @@ Workspace plan_workspace(const lstm_int_model *m, int64_t T, int64_t B) {
     return o;
   };
   w.tx = take((size_t)T * ((B + 31) / 32 * 32) * maxGN * 2);
-  w.out[0] = take((size_t)T * B * maxHpad);
-  w.out[1] = take((size_t)T * B * maxHpad);
-  w.xpad = take((size_t)T * B * round_up(m->host[0].I, 64));
+  // 32 rows of slack behind the activation buffers: the input GEMM reads whole blocks of 32 rows
+  w.out[0] = take(((size_t)T * B + 32) * maxHpad);
+  w.out[1] = take(((size_t)T * B + 32) * maxHpad);
+  w.xpad = take(((size_t)T * B + 32) * round_up(m->host[0].I, 64));
   w.th = take((size_t)B * maxGN * 2);
   w.mbuf = take((size_t)B * maxNpad);
   w.c = take((size_t)B * maxN * 2);
@@ -230,6 +232,7 @@ int upload(lstm_int_model *m) {
       // tile-ordered copies for the persistent path
       int ks = 0, rt = 0, grp = 0;
       d.p2 = rec_supported(h.N, h.H, (int)h.flags, 32, &ks, &rt, &grp);
+      size_t oW2f = 0;
       size_t oW2 = 0, obx2 = 0, oR2 = 0, obh4 = 0, oqb4 = 0, oLq4 = 0, oPq3 = 0, oWp2 = 0, obp2 = 0;
       if (d.p2) {
         d.GS = (h.N + 63) / 64;
@@ -238,6 +241,7 @@ int upload(lstm_int_model *m) {
         d.ptiles = h.projection() ? (h.H + 31) / 32 : 0;
         d.npadp = round_up(h.N, 128);
         oW2 = take((size_t)d.GS * 8 * 32 * d.Ipad);
+        if (d.Ipad <= 1024) oW2f = take((size_t)d.GS * 8 * 32 * d.Ipad);
         obx2 = take((size_t)d.GS * 8 * 32 * 4);
         oR2 = take((size_t)d.GS * 4 * 2 * ks * 64 * 16);
         obh4 = take((size_t)4 * d.Ncp * 4);
@@ -262,6 +266,14 @@ int upload(lstm_int_model *m) {
             d.amax_x[g] = std::max<int64_t>(d.amax_x[g], (int64_t)std::llabs((long long)h.bx_fold[src]) + 128 * sx);
             d.amax_h[g] = std::max<int64_t>(d.amax_h[g], (int64_t)std::llabs((long long)h.bh_fold[src]) + 128 * sh);
             memcpy(base + oW2 + trow * d.Ipad, h.Wq.data() + src * h.I, h.I);
+            if (d.Ipad <= 1024) {
+              // lane = rho + 32 * (k / 16 % 2) holds bytes k % 16 of k step k / 32
+              const int rho = 8 * g + (n % 8);
+              for (int k = 0; k < h.I; ++k) {
+                const size_t o = ((((size_t)(n / 8) * (d.Ipad / 32) + k / 32) * 64) + rho + 32 * ((k % 32) / 16)) * 16 + k % 16;
+                base[oW2f + o] = (uint8_t)h.Wq[src * h.I + k];
+              }
+            }
             reinterpret_cast<int32_t *>(base + obx2)[trow] = h.bx_fold[src];
             reinterpret_cast<int32_t *>(base + obh4)[(size_t)g * d.Ncp + n] = h.bh_fold[src];
             reinterpret_cast<int32_t *>(base + oqb4)[(size_t)g * d.Ncp + n] = h.qb[src];
@@ -286,6 +298,7 @@ int upload(lstm_int_model *m) {
         }
         uint8_t *db = static_cast<uint8_t *>(m->arena);
         d.W2 = reinterpret_cast<int8_t *>(db + oW2);
+        d.W2f = d.Ipad <= 1024 ? reinterpret_cast<int8_t *>(db + oW2f) : nullptr;
         d.bx2 = reinterpret_cast<int32_t *>(db + obx2);
         d.R2 = reinterpret_cast<int4 *>(db + oR2);
         d.bh4 = reinterpret_cast<int32_t *>(db + obh4);
@@ -439,10 +452,11 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
   int8_t *h0 = reinterpret_cast<int8_t *>(wsb + ws.h0);
   const int TB = T * B;
 
-  // layer 0 reads x in place when its rows are already 64-byte multiples
+  // layer 0 reads x in place when its rows are already 64-byte multiples and the batch fills whole
+  // blocks of 32 rows (the input GEMM reads whole blocks, up to 31 rows beyond the last real one)
   const int8_t *in = x;
   int ld_in = m->host[0].I;
-  if ((m->host[0].I & 63) || (reinterpret_cast<uintptr_t>(x) & 15)) {
+  if ((m->host[0].I & 63) || (reinterpret_cast<uintptr_t>(x) & 15) || (B & 31)) {
     Timed t(m->prof, s, LSTM_INT_K_OTHER);
     int8_t *xp = reinterpret_cast<int8_t *>(wsb + ws.xpad);
     launch_copy_rows_i8(s, x, m->host[0].I, xp, m->dev[0].Ipad, TB, m->host[0].I, 0);
@@ -531,7 +545,8 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
         InGemmArgs ga;
         memset(&ga, 0, sizeof(ga));
         ga.A = in; ga.lda = ld_in; ga.T = T; ga.B = B; ga.Bp = ra.Bp;
-        ga.W2 = d.W2; ga.kpad = d.Ipad; ga.tiles = d.GS * 8; ga.bx2 = d.bx2;
+        ga.a_slack = in != x;  // the workspace buffers have the slack, the caller's x need not
+        ga.W2 = d.W2; ga.W2f = d.W2f; ga.kpad = d.Ipad; ga.tiles = d.GS * 8; ga.bx2 = d.bx2;
         ga.all_hi = 1;
         ga.pre = 0;
         for (int g = 0; g < 4; ++g) {

@@ -20,15 +20,21 @@ namespace lstm_int {
 // gates z,o, and the 8 values = [gate in half][cell % 4].
 struct InGemmArgs {
   const int8_t *A;  // activations [T*B, lda]
+  int a_slack;       // the buffer is readable for 31 more rows behind row T*B - 1 (launch_in_gemm_ws needs it
+                     // when B is no multiple of 32: the padded rows of the last row block read them)
   int lda, T, B, Bp;
   const int8_t *W2;  // [tiles][32][kpad] tile-ordered weight rows
+  const int8_t *W2f; // the same as MFMA operands [tiles][kpad / 32][64 lanes][16]: lane = row + 32 * (k / 16 % 2)
+                     // holds bytes k % 16 of k step k / 32 (launch_in_gemm_ws reads this one)
   int kpad, tiles;   // tiles % 4 == 0
   const int32_t *bx2;  // [tiles][32]
   int32_t M[4], r[4], all_hi;
   int4 *tx2;
   // filled by launch_in_gemm_ws
   int pre;            // operand treatment of the rescale: 0 none, 1 left shift, 2 clamp and left shift
-  int parts;          // row partitions; workgroup id -> (id % parts, id / parts)
+  int parts;          // row partitions
+  int gp;             // part groups over the 8 XCDs (1, 2, 4 or 8; 0 on entry = chosen by the launch; 0 in the
+                      // kernel = workgroup id -> (id % parts, id / parts))
   RescaleHi rs[4];    // per gate, prepared from (M, r)
 };
 // one workgroup per 128 rows x 4 tiles, operands staged per 64-byte k tile

@@ -3,17 +3,20 @@
 //   in_gemm_kernel   W x for all (t, b) on the 32x32x32 int8 MFMA, rescaled to
 //                    int16 (Secs. 3.2.4/3.2.5, zero point folded per Sec. 6)
 //                    and stored in the tile order the recurrent kernel reads.
+//                    This file holds the general version (any input depth);
+//                    in_gemm.hip holds the one used for depths up to 1024.
 //   rec_kernel       all T steps of one layer in ONE launch.  A group of GS
 //                    workgroups (one per compute unit, all on one XCD, so they
 //                    share an L2) owns rows_pg batch rows; each workgroup owns
 //                    64 cells and keeps its slice of R in registers as MFMA
 //                    operands for the whole sequence, and its slice of W_proj
 //                    in LDS.  Per step: R h on the MFMA, gate sums, layer-norm
-//                    statistics (wavefront reductions, then one atomic add per
-//                    row and gate), sigma/tanh, cell update, hidden state,
-//                    projection; groups synchronize through a counter in
-//                    global memory.  Batch rows never interact, so groups run
-//                    independently.
+//                    statistics (wavefront reductions, then one 64-bit atomic
+//                    add per row and gate into words that also count their
+//                    contributions, so readers need no barrier), sigma/tanh,
+//                    cell update, hidden state, projection; groups synchronize
+//                    through a counter in global memory.  Batch rows never
+//                    interact, so groups run independently.
 //
 // Exchange between the workgroups of a group goes through buffers that are
 // written once per step, in 128-byte cache lines that nothing has read before
