@@ -14,7 +14,7 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contra
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-Wall", "-Wno-unused-function"]
 # in_gemm.hip: MFMA results go to ordinary vector registers, where the requantization reads them without copies
-EXTRA_FLAGS = {"in_gemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+EXTRA_FLAGS = {f: ["-mllvm", "-amdgpu-mfma-vgpr-form=1"] for f in ("in_gemm.hip", "rec_inst_8.hip", "rec_inst_20.hip", "rec_inst_32.hip")}
 
 
 def _compile(src, verbose):

@@ -140,14 +140,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   v4i Wf[2][KS];
   {
     const int4 *src = a.R2 + ((size_t)(member * 4 + wave) * 2) * KS * 64 + lane;
+    // all loads of a tile are in flight together before the first is moved to its place
 #pragma unroll
-    for (int tl = 0; tl < 2; ++tl)
+    for (int tl = 0; tl < 2; ++tl) {
+      int4 w[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) w[ks] = src[(size_t)(tl * KS + ks) * 64];
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const int4 w = src[(size_t)(tl * KS + ks) * 64];
-        Wf[tl][ks] = v4i{w.x, w.y, w.z, w.w};
+        Wf[tl][ks] = v4i{w[ks].x, w[ks].y, w[ks].z, w[ks].w};
         asm volatile("" : "+a"(Wf[tl][ks]));  // resident in accumulation registers for the whole launch
       }
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   const int cell_w = wave * 16 + 4 * b2;  // + tile * 8 + c, within the workgroup's 64 cells
   {
