@@ -135,6 +135,34 @@ typedef struct {
 int lstm_int_prepare(const lstm_int_layer_params *layers, int32_t num_layers,
                      int32_t device, lstm_int_model **out);
 
+/*
+ * Statistics of a calibration run for one layer (Sec. 4, post-training): the
+ * values lstm_int_layer_params carries as x_min .. g_absmax, in double.
+ */
+typedef struct {
+  double x_min, x_max, h_min, h_max, m_min, m_max, c_absmax, g_absmax[4];
+} lstm_int_layer_stats;
+
+/*
+ * Collects those statistics on the GPU (Sec. 4: the float model runs over
+ * representative inputs and ranges are logged at the nodes the execution
+ * figures mark "log").  Runs the float LSTM of Sec. 2 -- eqs. (1)-(7) with the
+ * variants of `flags`, h^0 = c^0 = 0 -- in double precision over
+ * x (DEVICE, float32 [T,B,I0]) for num_layers stacked layers whose float
+ * parameters are given as for lstm_int_prepare (HOST; the statistics fields
+ * of `layers` are ignored), and writes one lstm_int_layer_stats per layer to
+ * stats (HOST, caller-owned): min/max of the layer input, of h and of m,
+ * max |c|, and with LAYER_NORM max |W x + R h + P.c| per gate (else 0).
+ * y_float (DEVICE, double [T,B,H_last], may be NULL) receives the float
+ * output of the last layer.  Offline tooling: allocates and frees device
+ * memory, copies the parameters, and returns after the stream has drained.
+ * T*B*4*N and T*B*I must stay below 2^31 (LSTM_INT_E_UNSUPPORTED).
+ */
+int lstm_int_calibrate(const lstm_int_layer_params *layers, int32_t num_layers,
+                       int32_t device, const float *x, int32_t T, int32_t B,
+                       void *hip_stream, lstm_int_layer_stats *stats,
+                       double *y_float);
+
 /* Fills *out with views into the model (no copy, no device access). */
 int lstm_int_get_quant(const lstm_int_model *model, int32_t layer,
                        lstm_int_layer_quant *out);

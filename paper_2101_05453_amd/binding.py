@@ -34,6 +34,11 @@ class LayerParams(C.Structure):
     ]
 
 
+class LayerStats(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("x_min", "x_max", "h_min", "h_max", "m_min", "m_max", "c_absmax")] + [
+        ("g_absmax", C.c_double * 4)]
+
+
 class LayerQuant(C.Structure):
     """lstm_int_layer_quant"""
     _fields_ = [
@@ -104,6 +109,9 @@ def lib():
         L.lstm_int_profile_begin.argtypes = [C.c_void_p]
         L.lstm_int_profile_end.restype = C.c_int
         L.lstm_int_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+        L.lstm_int_calibrate.restype = C.c_int
+        L.lstm_int_calibrate.argtypes = [C.POINTER(LayerParams), C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
+                                         C.c_int32, C.c_void_p, C.POINTER(LayerStats), C.c_void_p]
         L.lstm_int_destroy.restype = None
         L.lstm_int_destroy.argtypes = [C.c_void_p]
         L.lstm_int_strerror.restype = C.c_char_p
@@ -280,6 +288,36 @@ def prepare(layers, device=0):
     del keep
     _check(rc, "lstm_int_prepare")
     return Model(h, len(layers), device)
+
+
+# lstm_int_calibrate
+def calibrate(layers, x, device=0, want_output=False, apply=True):
+    """Statistics of a float run on the GPU.  x: float32 CUDA tensor [T,B,I0]
+    (the calibration rows).  Returns the per-layer statistics as dicts (and the
+    float output of the last layer, a float64 CUDA tensor, with want_output);
+    with apply they are also written into the layer specs, ready for prepare."""
+    import torch
+
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    T, B, _ = x.shape
+    arr, keep = marshal_layers(layers)
+    st = (LayerStats * len(layers))()
+    y = torch.empty((T, B, layers[-1].output_size), dtype=torch.float64, device=x.device) if want_output else None
+    stream = torch.cuda.current_stream(x.device).cuda_stream
+    rc = lib().lstm_int_calibrate(arr, len(layers), device, x.data_ptr(), T, B, stream, st,
+                                  y.data_ptr() if y is not None else None)
+    del keep
+    _check(rc, "lstm_int_calibrate")
+    stats = []
+    for spec, r in zip(layers, st):
+        d = {k: getattr(r, k) for k in ("x_min", "x_max", "h_min", "h_max", "m_min", "m_max", "c_absmax")}
+        d["g_absmax"] = list(r.g_absmax)
+        stats.append(d)
+        if apply:
+            spec.x_min, spec.x_max, spec.h_min, spec.h_max = d["x_min"], d["x_max"], d["h_min"], d["h_max"]
+            spec.m_min, spec.m_max, spec.c_absmax = d["m_min"], d["m_max"], d["c_absmax"]
+            spec.g_absmax = list(d["g_absmax"])
+    return (stats, y) if want_output else stats
 
 
 def strerror(code):

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblstm_int.so")
 SOURCES = ["prepare.cpp", "kernels.hip", "persistent.hip", "in_gemm.hip", "rec_inst_8.hip", "rec_inst_20.hip",
-           "rec_inst_32.hip", "api.hip"]
+           "rec_inst_32.hip", "calibrate.hip", "api.hip"]
 HOSTMATH_LIB = os.path.join(HERE, "liblstm_int_hostmath.so")
 
 # packed-fp32 instructions are disabled for all device code

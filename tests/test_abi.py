@@ -122,3 +122,22 @@ def test_prepare_error_codes():
     two, _ = wl.make_custom([24, 40], 40, 40, 0, 1, 1)
     two[1].input_size = 41
     assert code(two) == binding.E_INVALID_ARG
+
+
+def test_calibrate_rejects_bad_arguments_before_touching_a_device():
+    lib = binding.lib()
+    layers, x = wl.make_custom([8], 16, 16, 0, 2, 2, seed=1)
+    arr, keep = binding.marshal_layers(layers)
+    st = (binding.LayerStats * 1)()
+    dummy = C.c_void_p(256)  # never dereferenced: every call below fails its argument checks first
+    assert lib.lstm_int_calibrate(arr, 0, 0, dummy, 2, 2, None, st, None) == -1
+    assert lib.lstm_int_calibrate(arr, 1, 0, None, 2, 2, None, st, None) == -1
+    assert lib.lstm_int_calibrate(arr, 1, 0, dummy, 0, 2, None, st, None) == -1
+    assert lib.lstm_int_calibrate(arr, 1, -1, dummy, 2, 2, None, st, None) == -1
+    assert lib.lstm_int_calibrate(arr, 1, 0, dummy, 2, 2, None, None, None) == -1
+    arr[0].output_size = 12  # without PROJECTION the output width is the cell count
+    assert lib.lstm_int_calibrate(arr, 1, 0, dummy, 2, 2, None, st, None) == -1
+    arr[0].output_size = 16
+    arr[0].num_cells = arr[0].output_size = 1 << 20  # T * B * 4 * N beyond the 32-bit index range
+    assert lib.lstm_int_calibrate(arr, 1, 0, dummy, 1 << 10, 2, None, st, None) == -2
+    del keep
