@@ -533,12 +533,16 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       if (!ok || rec_lds_bytes(ra) > 160 * 1024) use_p2 = false;
     }
     if (use_p2) {
+      // bytes of the synchronization region a launch over `groups` groups uses: all counters, and the
+      // statistics words of its groups (they follow the counters)
+      auto sync_bytes = [](int groups) { return (int64_t)256 * 64 * 4 + (int64_t)groups * 4 * 256 * 8; };
+      const int launch_rows = p2_groups * ra.rows_pg;
       {
+        // initial h (given, or real 0 = zp_h) and the cleared words of the first launch, in one kernel
         Timed t(m->prof, s, LSTM_INT_K_OTHER);
-        if (h_state)
-          launch_copy_rows_i8(s, h_state + h_off, h.H, h0, d.Hpad, B, h.H, 0);
-        else
-          launch_fill_rows_i8(s, h0, d.Hpad, B, h.H, h.zp_h, 0);
+        const int g0 = std::min(p2_groups, (B + ra.rows_pg - 1) / ra.rows_pg);
+        launch_init_layer(s, h_state ? h_state + h_off : nullptr, h.H, h0, d.Hpad, B, h.H, h.zp_h, wsb + ws.sync,
+                          sync_bytes(g0));
       }
       {
         Timed t(m->prof, s, LSTM_INT_K_INPUT_GEMM);
@@ -562,14 +566,12 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
           launch_in_gemm(s, ga);
       }
       // batch rows beyond one launch's groups run in further launches (rows never interact)
-      for (int b0 = 0; b0 < B; b0 += p2_groups * ra.rows_pg) {
+      for (int b0 = 0; b0 < B; b0 += launch_rows) {
         ra.batch0 = b0;
         ra.groups = std::min(p2_groups, (B - b0 + ra.rows_pg - 1) / ra.rows_pg);
-        {
-          // all counters, and the statistics words of the groups of this launch (they follow the counters)
+        if (b0 > 0) {
           Timed t(m->prof, s, LSTM_INT_K_OTHER);
-          const int64_t bytes = 256 * 64 * 4 + (int64_t)ra.groups * 4 * 256 * 8;
-          launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), bytes / 2, 0);
+          launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), sync_bytes(ra.groups) / 2, 0);
         }
         Timed t(m->prof, s, LSTM_INT_K_RECURRENT);
         if (launch_rec(s, ra) != hipSuccess) return LSTM_INT_E_DEVICE;

@@ -61,6 +61,10 @@ void launch_copy_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *d
 // dst [rows, ld_dst] <- value for the first cols bytes, `fill` for the rest
 void launch_fill_rows_i8(hipStream_t s, int8_t *dst, int ld_dst, int rows, int cols, int value,
                          int fill);
+// h0 [rows, ld_h0] <- h_src [rows, ld_src] (first cols bytes; NULL: all zp), padding bytes 0; and
+// sync_bytes (a multiple of 16) of zeros at sync -- one launch
+void launch_init_layer(hipStream_t s, const int8_t *h_src, int ld_src, int8_t *h0, int ld_h0, int rows, int cols,
+                       int zp, void *sync, int64_t sync_bytes);
 void launch_copy_i16(hipStream_t s, const int16_t *src, int16_t *dst, int64_t n);
 void launch_fill_i16(hipStream_t s, int16_t *dst, int64_t n, int value);
 // dump [rows, G*N] (present gates) into [rows, 4, N] gate slots first..3

@@ -373,6 +373,34 @@ void launch_fill_rows_i8(hipStream_t s, int8_t *dst, int ld_dst, int rows, int c
                      (const int8_t *)nullptr, 0, dst, ld_dst, rows, cols, value, fill);
 }
 
+// Start of a layer on the persistent path, in one launch: the initial hidden
+// state (given rows, or the code of real 0; padding bytes 0) and the
+// zeroed synchronization words.  Workgroups [0, zero_blocks) clear, the rest
+// write h.
+__global__ void init_layer_kernel(const int8_t *h_src, int ld_src, int8_t *h0, int ld_h0, int rows, int cols,
+                                  int zp, int4 *sync, int64_t sync_vec, int zero_blocks) {
+  if ((int)blockIdx.x < zero_blocks) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < sync_vec; i += (int64_t)zero_blocks * blockDim.x)
+      sync[i] = int4{0, 0, 0, 0};
+    return;
+  }
+  const int64_t total = (int64_t)rows * ld_h0;
+  const int64_t nb = gridDim.x - zero_blocks;
+  for (int64_t i = (blockIdx.x - zero_blocks) * (int64_t)blockDim.x + threadIdx.x; i < total; i += nb * blockDim.x) {
+    const int64_t r = i / ld_h0;
+    const int col = (int)(i - r * ld_h0);
+    h0[i] = col < cols ? (h_src ? h_src[r * ld_src + col] : (int8_t)zp) : (int8_t)0;
+  }
+}
+
+void launch_init_layer(hipStream_t s, const int8_t *h_src, int ld_src, int8_t *h0, int ld_h0, int rows, int cols,
+                       int zp, void *sync, int64_t sync_bytes) {
+  const int64_t vec = sync_bytes / 16;  // the region is a multiple of 16 bytes, 16-byte aligned
+  const int zb = grid_for(vec), hb = grid_for((int64_t)rows * ld_h0);
+  hipLaunchKernelGGL(init_layer_kernel, dim3(zb + hb), dim3(256), 0, s, h_src, ld_src, h0, ld_h0, rows, cols, zp,
+                     static_cast<int4 *>(sync), vec, zb);
+}
+
 __global__ void copy_i16_kernel(const int16_t *src, int16_t *dst, int64_t n, int value) {
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n;
        i += (int64_t)gridDim.x * blockDim.x)
