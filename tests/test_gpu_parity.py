@@ -169,6 +169,18 @@ def test_input_gemm_blocks_per_workgroup(orc, steps):
     run_and_compare(orc, layers, x, f"blocks{steps}", trace=False)
 
 
+@pytest.mark.parametrize("N", [64, 128, 192, 256, 512, 1024])
+def test_input_gemm_work_splits(orc, N):
+    """The input GEMM spreads (row part, column block) pairs over the eight XCDs;
+    the number of column blocks (N / 64) decides which split applies: 1, 2 and 3
+    column blocks fall back to the plain split, 4, 8 and 16 take the grouped one
+    with 64, 32 and 16 row parts.  42 steps x 48 rows = 63 blocks of 32 rows, so
+    parts get one block, or two, or none."""
+    print(f"cells {N}", flush=True)
+    layers, x = wl.make_custom([96], N, N, 0, 48, 42, seed=N, weight_param=0.05)
+    run_and_compare(orc, layers, x, f"split{N}", trace=False)
+
+
 def test_small_shifts(orc):
     """Large weights push the effective scales of the gate terms to 1/4 and
     above, i.e. rescale shifts below 33, where the one-product form of rescale
