@@ -192,7 +192,13 @@ int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
                      const lstm_int_trace *trace);
 
 /*
- * Tuning knobs of the online phase; results never depend on them.
+ * Options of the online phase.  One selects what is computed:
+ *   "reverse": 1 = every layer runs its recursion (eqs. 1-7) from time T - 1
+ *           down to 0, i.e. the stack applied to the time-reversed sequence,
+ *           outputs and traces stored at their positions in time (the
+ *           backward half of a bidirectional layer, Sec. 7); h_state and
+ *           c_state then enter at t = T - 1 and leave after t = 0.  Default 0.
+ * The others are tuning knobs; results never depend on them.
  *   "path": 0 = choose per layer (default): the persistent recurrent kernel
  *               where the layer shape allows it (N % 8 == 0, N <= 2048,
  *               H <= 1024, batch within one launch, no trace of that layer),

@@ -267,10 +267,21 @@ _TRACE_FIELDS = ("tx", "th", "g", "ln", "act", "c", "m", "h")
 
 
 def forward(model, xq, h_state=None, c_state=None, trace_layer=None, unfolded=False,
-            threads=None):
+            threads=None, reverse=False):
     """xq int8 [T,B,I0] -> y int8 [T,B,H_last].  States (flat arrays, layers
     concatenated) are updated in place when given.  With trace_layer, also
-    returns a dict of that layer's per-(t,b) integer tensors."""
+    returns a dict of that layer's per-(t,b) integer tensors.
+
+    reverse: the backward direction of a bidirectional layer (Sec. 7) -- the
+    same recursion over the time-reversed sequence, every per-step tensor
+    stored back at its position in time.  By definition: flip, run, flip."""
+    if reverse:
+        out = forward(model, np.ascontiguousarray(np.asarray(xq)[::-1]), h_state, c_state, trace_layer,
+                      unfolded, threads)
+        if trace_layer is None:
+            return np.ascontiguousarray(out[::-1])
+        y, bufs = out
+        return np.ascontiguousarray(y[::-1]), {k: np.ascontiguousarray(v[::-1]) for k, v in bufs.items()}
     xq = np.ascontiguousarray(xq, dtype=np.int8)
     T, B, I0 = xq.shape
     dims = model.dims()

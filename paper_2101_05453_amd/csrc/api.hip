@@ -71,6 +71,7 @@ struct lstm_int_model {
   int sh_sig3 = -1, sh_tanh3 = -1;
   int *status = nullptr;  // device word raised by the persistent kernel when a wait gives up
   int path = 0;
+  int reverse = 0;  // 1: every layer runs from time T - 1 down to 0
   int spin_limit = 1 << 21;
   int poll_sleep = 0, stats_sleep = 0;  // pauses between polls, in units of 64 clocks
   int idle_sleep = 64, idle_poll_sleep = 12;
@@ -481,6 +482,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
     RecArgs ra;
     if (use_p2) {
       memset(&ra, 0, sizeof(ra));
+      ra.reverse = m->reverse;
       ra.T = T; ra.B = B; ra.N = h.N; ra.H = h.H; ra.Hpad = d.Hpad; ra.flags = (int)h.flags; ra.m_c = h.m_c;
       ra.GS = d.GS; ra.groups = p2_groups; ra.rows_pg = 32 * p2_rt; ra.ks = d.ks; ra.Ncp = d.Ncp;
       ra.Bp = round_up(B, 32);
@@ -579,7 +581,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       {
         Timed t(m->prof, s, LSTM_INT_K_OTHER);
         if (h_state)
-          launch_copy_rows_i8(s, out + (size_t)(T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
+          launch_copy_rows_i8(s, out + (size_t)(m->reverse ? 0 : T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
                               h.H, 0);
       }
       h_off += (size_t)B * h.H;
@@ -605,8 +607,11 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
     }
     if (tr && tr->tx) launch_scatter_gates(s, tx, tr->tx, TB, h.G, h.N);
 
-    for (int t = 0; t < T; ++t) {
-      const int8_t *hprev = t == 0 ? h0 : out + (size_t)(t - 1) * step_out;
+    for (int step = 0; step < T; ++step) {
+      // position in time of this step and of the one before it
+      const int t = m->reverse ? T - 1 - step : step;
+      const int tprev = m->reverse ? t + 1 : t - 1;
+      const int8_t *hprev = step == 0 ? h0 : out + (size_t)tprev * step_out;
       int8_t *hout = out + (size_t)t * step_out;
       {
         Timed tm(m->prof, s, LSTM_INT_K_RECURRENT);
@@ -648,7 +653,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       Timed t(m->prof, s, LSTM_INT_K_OTHER);
       if (tr && tr->h) launch_copy_rows_i8(s, out, d.Hpad, tr->h, h.H, TB, h.H, 0);
       if (h_state)
-        launch_copy_rows_i8(s, out + (size_t)(T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
+        launch_copy_rows_i8(s, out + (size_t)(m->reverse ? 0 : T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
                             h.H, 0);
       if (c_state) launch_copy_i16(s, c, c_state + c_off, (int64_t)B * h.N);
     }
@@ -665,6 +670,11 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
   if (!strcmp(key, "path")) {
     if (value < 0 || value > 2) return LSTM_INT_E_INVALID_ARG;
     m->path = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "reverse")) {
+    if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
+    m->reverse = (int)value;
     return LSTM_INT_OK;
   }
   if (!strcmp(key, "reset_status")) {  // after a wait gave up: the word is sticky and stops every later kernel

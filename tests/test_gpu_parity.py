@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import lstm_workloads as wl
-from parity_util import assert_equal, prepare_both, run_and_compare
+from parity_util import assert_equal, compare_traces, prepare_both, run_and_compare
 
 pytestmark = pytest.mark.gpu
 
@@ -146,6 +146,47 @@ def test_split_sequence_carries_state(orc):
     torch.cuda.synchronize()
     assert_equal("split", torch.cat([ya, yb]).cpu().numpy(), y.cpu().numpy())
     assert_equal("split vs oracle", y.cpu().numpy(), orc.forward(orc_model, xq))
+
+
+@pytest.mark.parametrize("path", [0, 1])
+@pytest.mark.parametrize("flags", [0, wl.LAYER_NORM | wl.PROJECTION, wl.CIFG | wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION])
+def test_reverse_direction(orc, flags, path):
+    """Option "reverse": the recursion runs from t = T - 1 down to 0 (the backward
+    half of a bidirectional layer, Sec. 7), on both paths, two stacked layers,
+    states carried in and out, every traced tensor at its position in time."""
+    import torch
+
+    print(f"reverse flags {flags} path {path}", flush=True)
+    H = 40 if flags & wl.PROJECTION else 72
+    layers, x = wl.make_custom([24, H], 72, 40, flags, 37, 5, seed=11 + flags)
+    lib_model, orc_model, xq = prepare_both(orc, layers, x)
+    lib_model.set_option("reverse", 1)
+    lib_model.set_option("path", path)
+    T, B, _ = xq.shape
+    dims = lib_model.dims()
+    rng = np.random.Generator(np.random.PCG64(5))
+    h0 = rng.integers(-128, 128, sum(B * d[2] for d in dims), dtype=np.int8)
+    c0 = rng.integers(-3000, 3000, sum(B * d[1] for d in dims), dtype=np.int16)
+    xd = torch.from_numpy(xq).cuda()
+    for layer in range(2):
+        hs, cs = torch.from_numpy(h0.copy()).cuda(), torch.from_numpy(c0.copy()).cuda()
+        y, gtr = lib_model.forward(xd, h_state=hs, c_state=cs, trace_layer=layer)
+        torch.cuda.synchronize()
+        assert lib_model.device_status() == 0
+        ohs, ocs = h0.copy(), c0.copy()
+        yo, otr = orc.forward(orc_model, xq, h_state=ohs, c_state=ocs, trace_layer=layer, reverse=True)
+        assert_equal("rev.y", y.cpu().numpy(), yo)
+        assert_equal("rev.h_state", hs.cpu().numpy(), ohs)
+        assert_equal("rev.c_state", cs.cpu().numpy(), ocs)
+        compare_traces(f"rev.l{layer}", gtr, otr, flags)
+    # without a trace the persistent kernel runs (path 0): same outputs
+    hs, cs = torch.from_numpy(h0.copy()).cuda(), torch.from_numpy(c0.copy()).cuda()
+    y2 = lib_model.forward(xd, h_state=hs, c_state=cs)
+    torch.cuda.synchronize()
+    assert lib_model.device_status() == 0
+    assert_equal("rev.y untraced", y2.cpu().numpy(), yo)
+    assert_equal("rev.h_state untraced", hs.cpu().numpy(), ohs)
+    assert_equal("rev.c_state untraced", cs.cpu().numpy(), ocs)
 
 
 @pytest.mark.parametrize("I", [40, 300, 520, 700, 1100])

@@ -435,3 +435,30 @@ def test_empty_inputs(orc):
     m = orc.prepare(layers)
     assert orc.forward(m, np.zeros((0, 3, 24), np.int8)).shape == (0, 3, 40)
     assert orc.forward(m, np.zeros((4, 0, 24), np.int8)).shape == (4, 0, 40)
+
+
+def test_reverse_direction_runs_backward_in_time(orc):
+    """In the backward direction the output at time t depends on x[t..T-1] only:
+    changing x[0] leaves y[1:] alone, changing x[T-1] reaches y[0]; and with one
+    step the two directions coincide."""
+    import lstm_workloads as wl
+    from paper_2101_05453_amd import calibration
+
+    layers, x = wl.make_custom([12], 16, 16, wl.LAYER_NORM, 3, 6, seed=4)
+    calibration.collect_statistics(layers, x)
+    model = orc.prepare(layers)
+    q = model.layer(0)
+    xq = orc.quantize_input(x, q["s_x"], q["zp_x"])
+    y = orc.forward(model, xq, reverse=True)
+    x2 = xq.copy()
+    x2[0] = np.where(x2[0] > 0, x2[0] - 37, x2[0] + 37)
+    y2 = orc.forward(model, x2, reverse=True)
+    assert np.array_equal(y2[1:], y[1:]) and not np.array_equal(y2[0], y[0])
+    x3 = xq.copy()
+    x3[-1] = np.where(x3[-1] > 0, x3[-1] - 37, x3[-1] + 37)
+    y3 = orc.forward(model, x3, reverse=True)
+    assert not np.array_equal(y3[0], y[0])
+    # the forward direction has the opposite dependence
+    yf, yf2 = orc.forward(model, xq), orc.forward(model, x2)
+    assert not np.array_equal(yf2[-1], yf[-1])
+    assert np.array_equal(orc.forward(model, xq[:1], reverse=True), orc.forward(model, xq[:1]))
