@@ -71,7 +71,7 @@ struct lstm_int_model {
   int sh_sig3 = -1, sh_tanh3 = -1;
   int *status = nullptr;  // device word raised by the persistent kernel when a wait gives up
   int path = 0;
-  int reverse = 0;  // 1: every layer runs from time T - 1 down to 0
+  int reverse = 0;  // 1: the recursion runs from time T - 1 down to 0
   int spin_limit = 1 << 21;
   int poll_sleep = 0, stats_sleep = 0;  // pauses between polls, in units of 64 clocks
   int idle_sleep = 64, idle_poll_sleep = 12;
@@ -457,10 +457,17 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
   // blocks of 32 rows (the input GEMM reads whole blocks, up to 31 rows beyond the last real one)
   const int8_t *in = x;
   int ld_in = m->host[0].I;
-  if ((m->host[0].I & 63) || (reinterpret_cast<uintptr_t>(x) & 15) || (B & 31)) {
+  // A reverse run is the forward run on the time-flipped sequence: x is flipped on the way in, every
+  // buffer between the layers is then indexed by step (step k works at time T - 1 - k), and y (and the
+  // traces) are flipped back on the way out.  The kernels know nothing of it.
+  const bool rev = m->reverse != 0;
+  if ((m->host[0].I & 63) || (reinterpret_cast<uintptr_t>(x) & 15) || (B & 31) || rev) {
     Timed t(m->prof, s, LSTM_INT_K_OTHER);
     int8_t *xp = reinterpret_cast<int8_t *>(wsb + ws.xpad);
-    launch_copy_rows_i8(s, x, m->host[0].I, xp, m->dev[0].Ipad, TB, m->host[0].I, 0);
+    if (rev)
+      launch_flip_rows_i8(s, x, m->host[0].I, xp, m->dev[0].Ipad, T, B, m->host[0].I, 0);
+    else
+      launch_copy_rows_i8(s, x, m->host[0].I, xp, m->dev[0].Ipad, TB, m->host[0].I, 0);
     in = xp;
     ld_in = m->dev[0].Ipad;
   }
@@ -482,7 +489,6 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
     RecArgs ra;
     if (use_p2) {
       memset(&ra, 0, sizeof(ra));
-      ra.reverse = m->reverse;
       ra.T = T; ra.B = B; ra.N = h.N; ra.H = h.H; ra.Hpad = d.Hpad; ra.flags = (int)h.flags; ra.m_c = h.m_c;
       ra.GS = d.GS; ra.groups = p2_groups; ra.rows_pg = 32 * p2_rt; ra.ks = d.ks; ra.Ncp = d.Ncp;
       ra.Bp = round_up(B, 32);
@@ -502,7 +508,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.Wp2 = d.Wp2; ra.bp2 = d.bp2; ra.ptiles = d.ptiles; ra.npadp = d.npadp;
       ra.Mp = h.Mp; ra.rp = 31 - h.ep; ra.zp_h = h.zp_h;
       ra.tx2 = reinterpret_cast<const int4 *>(tx);
-      ra.h0 = h0; ra.out = out; ra.y = last ? y : nullptr;
+      ra.h0 = h0; ra.out = out; ra.y = (last && !rev) ? y : nullptr;
       ra.mbuf = reinterpret_cast<int8_t *>(wsb + ws.m2);
       ra.c_in = c_state ? c_state + c_off : nullptr;
       ra.c_out = c_state ? c_state + c_off : nullptr;
@@ -581,8 +587,9 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       {
         Timed t(m->prof, s, LSTM_INT_K_OTHER);
         if (h_state)
-          launch_copy_rows_i8(s, out + (size_t)(m->reverse ? 0 : T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
+          launch_copy_rows_i8(s, out + (size_t)(T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
                               h.H, 0);
+        if (last && rev) launch_flip_rows_i8(s, out, d.Hpad, y, h.H, T, B, h.H, 0);
       }
       h_off += (size_t)B * h.H;
       c_off += (size_t)B * h.N;
@@ -605,19 +612,23 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       Timed t(m->prof, s, LSTM_INT_K_INPUT_GEMM);
       launch_gemm_i16(s, in, ld_in, TB, d.W, d.Ipad, d.GN, d.bx, d.rq_x, tx, d.GN);
     }
-    if (tr && tr->tx) launch_scatter_gates(s, tx, tr->tx, TB, h.G, h.N);
+    if (tr && tr->tx) {
+      if (rev)  // step k -> time T - 1 - k
+        for (int k = 0; k < T; ++k)
+          launch_scatter_gates(s, tx + (size_t)k * B * d.GN, tr->tx + (size_t)(T - 1 - k) * B * 4 * h.N, B, h.G, h.N);
+      else
+        launch_scatter_gates(s, tx, tr->tx, TB, h.G, h.N);
+    }
 
-    for (int step = 0; step < T; ++step) {
-      // position in time of this step and of the one before it
-      const int t = m->reverse ? T - 1 - step : step;
-      const int tprev = m->reverse ? t + 1 : t - 1;
-      const int8_t *hprev = step == 0 ? h0 : out + (size_t)tprev * step_out;
+    for (int t = 0; t < T; ++t) {
+      const int8_t *hprev = t == 0 ? h0 : out + (size_t)(t - 1) * step_out;
       int8_t *hout = out + (size_t)t * step_out;
       {
         Timed tm(m->prof, s, LSTM_INT_K_RECURRENT);
         launch_gemm_i16(s, hprev, d.Hpad, B, d.R, d.Hpad, d.GN, d.bh, d.rq_h, th, d.GN);
       }
-      const size_t tg = (size_t)t * B * 4 * h.N, tn = (size_t)t * B * h.N;
+      const int tpos = rev ? T - 1 - t : t;  // position in time of step t, for the traces
+      const size_t tg = (size_t)tpos * B * 4 * h.N, tn = (size_t)tpos * B * h.N;
       if (tr && tr->th) launch_scatter_gates(s, th, tr->th + tg, B, h.G, h.N);
       CellArgs a;
       a.B = B; a.N = h.N; a.G = h.G; a.flags = (int32_t)h.flags; a.m_c = h.m_c;
@@ -632,7 +643,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       a.sig_tab = m->sig3; a.tanh_tab = m->tanh3; a.tanhc_tab = d.tanhc;
       a.m_out = proj ? mbuf : hout;
       a.ld_m = proj ? d.Npad : d.Hpad;
-      a.m_out2 = (!proj && last) ? y + (size_t)t * B * h.H : nullptr;
+      a.m_out2 = (!proj && last && !rev) ? y + (size_t)t * B * h.H : nullptr;
       a.ld_m2 = h.H;
       a.tr_g = tr && tr->g ? tr->g + tg : nullptr;
       a.tr_ln = tr && tr->ln ? tr->ln + tg : nullptr;
@@ -646,14 +657,20 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       if (proj) {
         Timed tm(m->prof, s, LSTM_INT_K_PROJECTION);
         launch_gemm_i8(s, mbuf, d.Npad, B, d.Wproj, d.Npad, h.H, d.bp, d.rq_p, hout, d.Hpad,
-                       last ? y + (size_t)t * B * h.H : nullptr, h.H);
+                       (last && !rev) ? y + (size_t)t * B * h.H : nullptr, h.H);
       }
     }
     {
       Timed t(m->prof, s, LSTM_INT_K_OTHER);
-      if (tr && tr->h) launch_copy_rows_i8(s, out, d.Hpad, tr->h, h.H, TB, h.H, 0);
+      if (tr && tr->h) {
+        if (rev)
+          launch_flip_rows_i8(s, out, d.Hpad, tr->h, h.H, T, B, h.H, 0);
+        else
+          launch_copy_rows_i8(s, out, d.Hpad, tr->h, h.H, TB, h.H, 0);
+      }
+      if (last && rev) launch_flip_rows_i8(s, out, d.Hpad, y, h.H, T, B, h.H, 0);
       if (h_state)
-        launch_copy_rows_i8(s, out + (size_t)(m->reverse ? 0 : T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
+        launch_copy_rows_i8(s, out + (size_t)(T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
                             h.H, 0);
       if (c_state) launch_copy_i16(s, c, c_state + c_off, (int64_t)B * h.N);
     }

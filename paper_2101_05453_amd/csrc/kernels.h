@@ -58,6 +58,9 @@ void launch_cell(hipStream_t s, const CellArgs &a);
 // bytes cols..ld_dst-1 of dst are set to `fill`.
 void launch_copy_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *dst, int ld_dst,
                          int rows, int cols, int fill);
+// dst [T*B, ld_dst] row (t, b) <- src row (T - 1 - t, b), first cols bytes; `fill` for the rest
+void launch_flip_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *dst, int ld_dst, int T, int B,
+                         int cols, int fill);
 // dst [rows, ld_dst] <- value for the first cols bytes, `fill` for the rest
 void launch_fill_rows_i8(hipStream_t s, int8_t *dst, int ld_dst, int rows, int cols, int value,
                          int fill);

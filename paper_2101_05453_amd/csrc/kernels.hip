@@ -354,6 +354,18 @@ __global__ void copy_rows_i8_kernel(const int8_t *src, int ld_src, int8_t *dst, 
   }
 }
 
+// dst row (t, b) <- src row (T - 1 - t, b): the time flip at the two ends of a reverse run
+__global__ void flip_rows_i8_kernel(const int8_t *src, int ld_src, int8_t *dst, int ld_dst, int T, int B, int cols,
+                                    int fill) {
+  const int64_t total = (int64_t)T * B * ld_dst;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = i / ld_dst;
+    const int col = (int)(i - r * ld_dst);
+    const int64_t t = r / B, b = r - t * B;
+    dst[i] = col < cols ? src[((T - 1 - t) * B + b) * ld_src + col] : (int8_t)fill;
+  }
+}
+
 static int grid_for(int64_t total) {
   int64_t g = (total + 255) / 256;
   return (int)(g < 1 ? 1 : (g > 4096 ? 4096 : g));
@@ -364,6 +376,13 @@ void launch_copy_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *d
   if (rows <= 0) return;
   hipLaunchKernelGGL(copy_rows_i8_kernel, dim3(grid_for((int64_t)rows * ld_dst)), dim3(256), 0, s,
                      src, ld_src, dst, ld_dst, rows, cols, 0, fill);
+}
+
+void launch_flip_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *dst, int ld_dst, int T, int B,
+                         int cols, int fill) {
+  if (T <= 0 || B <= 0) return;
+  hipLaunchKernelGGL(flip_rows_i8_kernel, dim3(grid_for((int64_t)T * B * ld_dst)), dim3(256), 0, s, src, ld_src, dst,
+                     ld_dst, T, B, cols, fill);
 }
 
 void launch_fill_rows_i8(hipStream_t s, int8_t *dst, int ld_dst, int rows, int cols, int value,

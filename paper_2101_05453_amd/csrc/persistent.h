@@ -47,7 +47,6 @@ void launch_in_gemm_ws(hipStream_t s, const InGemmArgs &a, int num_cus);
 
 struct RecArgs {
   int T, B, N, H, Hpad, flags, m_c;
-  int reverse;    // 1: the steps run from time T - 1 down to 0 (h and c carry in that direction)
   int GS;         // workgroups (compute units) per group = cells / 64
   int groups;     // groups in this launch, each owns rows_pg batch rows
   int batch0;     // first batch row of this launch

@@ -290,12 +290,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
 
   for (int t = 0; t < a.T; ++t) {
-    // position in time of step t and of the step before it (a reverse layer walks from T - 1 down)
-    const int tt = a.reverse ? a.T - 1 - t : t;
-    const int tprev = a.reverse ? tt + 1 : tt - 1;
     // ---- h^{t-1} rows of the group -> LDS; W x terms of this step -> registers
     {
-      const int8_t *hp = t == 0 ? a.h0 : a.out + (size_t)tprev * a.B * a.Hpad;
+      const int8_t *hp = t == 0 ? a.h0 : a.out + (size_t)(t - 1) * a.B * a.Hpad;
 #pragma unroll
       for (int j = 0; j < NCH; ++j)  // chunks past the tile land in the spare chunk behind it
         __builtin_amdgcn_global_load_lds(
@@ -310,7 +307,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
       for (int tl = 0; tl < 2; ++tl) {
-        const int4 *src = tx_ptr(tt, rt, tl);
+        const int4 *src = tx_ptr(t, rt, tl);
         // read once: a streaming load keeps the W x terms from displacing the exchange buffers in L2
         const v4i t0 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src));
         const v4i t1 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src + 64));
@@ -663,7 +660,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // Without a projection m is h and goes to the layer output [T, B, Hpad].  With one it goes to the
     // exchange buffer in the order the projection reads it: [t][row tile][k step][row % 32][32 cells],
     // so that a wave's load of one k step is one contiguous KB of whole cache lines.
-    int8_t *mdst = proj ? a.mbuf + (size_t)tt * a.Bp * a.npadp : a.out + (size_t)tt * a.B * a.Hpad;
+    int8_t *mdst = proj ? a.mbuf + (size_t)t * a.Bp * a.npadp : a.out + (size_t)t * a.B * a.Hpad;
     const RescaleHi pm = prm->m;
     const int32_t zp_m = prm->zp_m;
 #pragma unroll
@@ -686,7 +683,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                                   : (size_t)row * a.Hpad + n0;
           *reinterpret_cast<uint32_t *>(mdst + off) = pk;
           if (!proj && a.y) {
-            int8_t *yd = a.y + ((size_t)tt * a.B + row) * a.H + n0;  // H = N, a multiple of 4
+            int8_t *yd = a.y + ((size_t)t * a.B + row) * a.H + n0;  // H = N, a multiple of 4
             __builtin_nontemporal_store(pk, reinterpret_cast<uint32_t *>(yd));  // not read again here
           }
         }
@@ -706,7 +703,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
           // rows of the tile beyond the batch were never written; their results are not stored either
-          const int8_t *mrow = a.mbuf + (size_t)tt * a.Bp * a.npadp +
+          const int8_t *mrow = a.mbuf + (size_t)t * a.Bp * a.npadp +
                                ((((size_t)((row0 >> 5) + rt) * (a.npadp >> 5) + wave * per_wave) * 32 + col) << 5) +
                                (b2 << 4);
           const int8_t *wrow = WpL + ((size_t)pt * 32 + col) * WLS + (b2 << 4) + wave * per_wave * 32;
@@ -753,14 +750,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
               pk |= (uint32_t)(hq & 0xFF) << (8 * c);
             }
             if (orow < a.B && p0 < a.H) {
-              int8_t *od = a.out + ((size_t)tt * a.B + orow) * a.Hpad + p0;
+              int8_t *od = a.out + ((size_t)t * a.B + orow) * a.Hpad + p0;
               if (p0 + 3 < a.H) {
                 *reinterpret_cast<uint32_t *>(od) = pk;
               } else {
                 for (int c = 0; c < 4 && p0 + c < a.H; ++c) od[c] = (int8_t)(pk >> (8 * c));
               }
               if (a.y) {
-                int8_t *yd = a.y + ((size_t)tt * a.B + orow) * a.H + p0;
+                int8_t *yd = a.y + ((size_t)t * a.B + orow) * a.H + p0;
                 for (int c = 0; c < 4 && p0 + c < a.H; ++c) yd[c] = (int8_t)(pk >> (8 * c));
               }
             }
