@@ -213,7 +213,7 @@ static rec_fn pick(int ks, int rt, int fl) {
 hipError_t rec_init() {
   for (int ks : kKS)
     for (int rt = 1; rt <= 2; ++rt)
-      for (int fl = 0; fl < 8; ++fl) {
+      for (int fl = 0; fl < 16; ++fl) {
         rec_fn fn = pick(ks, rt, fl);
         if (!fn) continue;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
@@ -224,7 +224,7 @@ hipError_t rec_init() {
 }
 
 hipError_t launch_rec(hipStream_t s, const RecArgs &a) {
-  rec_fn fn = pick(a.ks, a.rows_pg / 32, a.flags & 7);
+  rec_fn fn = pick(a.ks, a.rows_pg / 32, (a.flags & 7) | ((a.flags & 8) ? 0 : 8));  // bit 3: no projection
   if (!fn) return hipErrorInvalidValue;
   const int slots = a.GS * ((a.groups + 7) / 8);
   RecArgs args = a;

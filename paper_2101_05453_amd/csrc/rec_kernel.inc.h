@@ -78,8 +78,9 @@ __device__ __forceinline__ int32_t mirror_tanh(int32_t x, int32_t t) {
   return x < 0 ? -t : (t > 32767 ? 32767 : t);
 }
 
-// FL: bit 0 CIFG, bit 1 peephole, bit 2 layer norm (compile time, so that the
-// per-element code carries no tests of them); the projection is a runtime flag.
+// FL: bit 0 CIFG, bit 1 peephole, bit 2 layer norm, bit 3 "no projection" (compile
+// time, so that the code carries no tests of them); with bit 3 clear the
+// projection is a runtime flag.
 template <int KS, int RT, int FL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void rec_kernel(RecArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -87,7 +88,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, b2 = lane >> 5;
   constexpr bool cifg = FL & 1, ph = FL & 2, ln = FL & 4;
-  const bool proj = a.flags & 8;
+  // bit 3: the layer is known to have no projection (measured: dropping the projection code from
+  // those kernels gains 1.7 % at C5, while fixing the flag to "on" at compile time loses 5 % at C4)
+  const bool proj = !(FL & 8) && (a.flags & 8);
   const int GS = a.GS;
 
   // placement: workgroup w runs on XCD w % 8; the workgroups of a group share one
@@ -809,9 +812,13 @@ rec_fn rec_pick_ks(int rt, int fl) {
   if (rt == R && fl == F) return rec_kernel<KS, R, F>;
   LSTM_REC_CASE(1, 0) LSTM_REC_CASE(1, 1) LSTM_REC_CASE(1, 2) LSTM_REC_CASE(1, 3)
   LSTM_REC_CASE(1, 4) LSTM_REC_CASE(1, 5) LSTM_REC_CASE(1, 6) LSTM_REC_CASE(1, 7)
+  LSTM_REC_CASE(1, 8) LSTM_REC_CASE(1, 9) LSTM_REC_CASE(1, 10) LSTM_REC_CASE(1, 11)
+  LSTM_REC_CASE(1, 12) LSTM_REC_CASE(1, 13) LSTM_REC_CASE(1, 14) LSTM_REC_CASE(1, 15)
   if (KS < 32) {
     LSTM_REC_CASE(2, 0) LSTM_REC_CASE(2, 1) LSTM_REC_CASE(2, 2) LSTM_REC_CASE(2, 3)
     LSTM_REC_CASE(2, 4) LSTM_REC_CASE(2, 5) LSTM_REC_CASE(2, 6) LSTM_REC_CASE(2, 7)
+    LSTM_REC_CASE(2, 8) LSTM_REC_CASE(2, 9) LSTM_REC_CASE(2, 10) LSTM_REC_CASE(2, 11)
+    LSTM_REC_CASE(2, 12) LSTM_REC_CASE(2, 13) LSTM_REC_CASE(2, 14) LSTM_REC_CASE(2, 15)
   }
 #undef LSTM_REC_CASE
   return nullptr;
