@@ -483,8 +483,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
 
     // persistent path: eligible shape, no dump requested for this layer, batch fits one launch
     int p2_ks = 0, p2_rt = 0, p2_groups = 0;
-    // (and at most 2^14 steps: the statistics words of the kernel count up over the launch)
-    bool use_p2 = m->path != 1 && !tr && d.p2 && T <= (1 << 14) && (reinterpret_cast<uintptr_t>(y) & 3) == 0 &&
+    bool use_p2 = m->path != 1 && !tr && d.p2 && (reinterpret_cast<uintptr_t>(y) & 3) == 0 &&
                   rec_supported(h.N, h.H, (int)h.flags, B, &p2_ks, &p2_rt, &p2_groups);
     RecArgs ra;
     if (use_p2) {
@@ -573,16 +572,31 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
         else
           launch_in_gemm(s, ga);
       }
-      // batch rows beyond one launch's groups run in further launches (rows never interact)
-      for (int b0 = 0; b0 < B; b0 += launch_rows) {
-        ra.batch0 = b0;
-        ra.groups = std::min(p2_groups, (B - b0 + ra.rows_pg - 1) / ra.rows_pg);
-        if (b0 > 0) {
-          Timed t(m->prof, s, LSTM_INT_K_OTHER);
-          launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), sync_bytes(ra.groups) / 2, 0);
+      // One launch takes at most 2^14 steps (the statistics words of the kernel count up over the
+      // launch); longer sequences run in pieces, h carried through the layer output and c through a
+      // buffer.  Batch rows beyond one launch's groups run in further launches (rows never interact).
+      constexpr int kMaxSteps = 1 << 14;
+      const int4 *tx2_all = ra.tx2;
+      int16_t *c_carry = c_state ? c_state + c_off : c;
+      for (int t0 = 0; t0 < T; t0 += kMaxSteps) {
+        const int tc = std::min(kMaxSteps, T - t0);
+        ra.T = tc;
+        ra.tx2 = tx2_all + (size_t)t0 * (ra.Bp / 32) * (d.GS * 8) * 2 * 64;
+        ra.h0 = t0 == 0 ? h0 : out + (size_t)(t0 - 1) * step_out;
+        ra.out = out + (size_t)t0 * step_out;
+        ra.y = (last && !rev) ? y + (size_t)t0 * B * h.H : nullptr;
+        ra.c_in = t0 == 0 ? (c_state ? c_state + c_off : nullptr) : c_carry;
+        ra.c_out = (c_state || t0 + tc < T) ? c_carry : nullptr;
+        for (int b0 = 0; b0 < B; b0 += launch_rows) {
+          ra.batch0 = b0;
+          ra.groups = std::min(p2_groups, (B - b0 + ra.rows_pg - 1) / ra.rows_pg);
+          if (b0 > 0 || t0 > 0) {
+            Timed t(m->prof, s, LSTM_INT_K_OTHER);
+            launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), sync_bytes(ra.groups) / 2, 0);
+          }
+          Timed t(m->prof, s, LSTM_INT_K_RECURRENT);
+          if (launch_rec(s, ra) != hipSuccess) return LSTM_INT_E_DEVICE;
         }
-        Timed t(m->prof, s, LSTM_INT_K_RECURRENT);
-        if (launch_rec(s, ra) != hipSuccess) return LSTM_INT_E_DEVICE;
       }
       {
         Timed t(m->prof, s, LSTM_INT_K_OTHER);

@@ -285,15 +285,17 @@ def test_empty_and_error_paths(orc):
     assert_equal("unaligned", y.cpu().numpy(), orc.forward(orc_model, xq))
 
 
-@pytest.mark.parametrize("T", [1 << 14, (1 << 14) + 1])
-def test_longest_sequences(orc, T):
+@pytest.mark.parametrize("T,flags,with_state", [(1 << 14, wl.LAYER_NORM, True), ((1 << 14) + 1, wl.LAYER_NORM, True),
+                                                ((1 << 14) + 1, wl.LAYER_NORM | wl.PROJECTION, False)])
+def test_longest_sequences(orc, T, flags, with_state):
     """2^14 steps is the most one launch of the persistent kernel takes (its
     layer-norm statistics words count up over the launch); one step more and
-    the layer runs on the per-step path.  Two workgroups per group, so the words
-    are in use."""
+    the layer runs in two pieces, h and c carried from one to the next (c through
+    the caller's state buffer, or through the workspace when there is none).  Two
+    workgroups per group, so the words are in use."""
     print(f"T {T}", flush=True)
-    layers, x = wl.make_custom([16], 128, 128, wl.LAYER_NORM, 3, T, seed=21)
-    run_and_compare(orc, layers, x, f"long{T}", trace=False)
+    layers, x = wl.make_custom([16], 128, 64, flags, 3, T, seed=21)
+    run_and_compare(orc, layers, x, f"long{T}", trace=False, with_state=with_state)
 
 
 def test_maximum_sizes(orc):
