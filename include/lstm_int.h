@@ -201,7 +201,8 @@ int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
  * The others are tuning knobs; results never depend on them.
  *   "path": 0 = choose per layer (default): the persistent recurrent kernel
  *               where the layer shape allows it (N % 8 == 0, N <= 2048,
- *               H <= 1024, batch within one launch, no trace of that layer),
+ *               H <= 1024, no trace of that layer; larger batches and
+ *               sequences beyond 2^14 steps run in several launches),
  *               otherwise one launch per operation and step;
  *           1 = always one launch per operation and step;
  *           2 = same as 0.
