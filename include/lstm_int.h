@@ -206,6 +206,15 @@ int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
  *               otherwise one launch per operation and step;
  *           1 = always one launch per operation and step;
  *           2 = same as 0.
+ *   "cooperative_launch": the persistent kernel needs all its workgroups (one
+ *           per compute unit, up to all of them) on the device at once.
+ *           0 (default) = plain launch: that holds when nothing else occupies
+ *           the device for long -- no second forward call of any model running
+ *           concurrently on another stream or from another process; if it does
+ *           not hold, the kernel's bounded waits give up and the call ends with
+ *           a nonzero device status instead of hanging.  1 = cooperative
+ *           launch: the runtime guarantees it, at 16-18 us more per layer and
+ *           launch (a third of a one-step call on an 8-layer stack).
  *   "spin_limit": polls after which a wait inside the persistent kernel gives
  *           up (every workgroup then leaves the kernel and the status word of
  *           lstm_int_device_status becomes nonzero).

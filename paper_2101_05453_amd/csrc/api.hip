@@ -72,6 +72,7 @@ struct lstm_int_model {
   int *status = nullptr;  // device word raised by the persistent kernel when a wait gives up
   int path = 0;
   int reverse = 0;  // 1: the recursion runs from time T - 1 down to 0
+  int cooperative = 0;  // 1: the persistent kernel is launched cooperatively
   int spin_limit = 1 << 21;
   int poll_sleep = 0, stats_sleep = 0;  // pauses between polls, in units of 64 clocks
   int idle_sleep = 64, idle_poll_sleep = 12;
@@ -512,6 +513,8 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.c_in = c_state ? c_state + c_off : nullptr;
       ra.c_out = c_state ? c_state + c_off : nullptr;
       ra.counters = reinterpret_cast<unsigned *>(wsb + ws.sync);
+      // the word shares the zeroed counter region: word 1 of group 0's block (word 0 is its barrier)
+      ra.tickets = m->cooperative ? nullptr : ra.counters + 1;
       ra.acc = reinterpret_cast<unsigned long long *>(wsb + ws.sync + 256 * 64 * 4);
       ra.status = m->status;
       ra.spin_limit = m->spin_limit;
@@ -595,7 +598,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
             launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), sync_bytes(ra.groups) / 2, 0);
           }
           Timed t(m->prof, s, LSTM_INT_K_RECURRENT);
-          if (launch_rec(s, ra) != hipSuccess) return LSTM_INT_E_DEVICE;
+          if (launch_rec(s, ra, m->cooperative != 0) != hipSuccess) return LSTM_INT_E_DEVICE;
         }
       }
       {
@@ -701,6 +704,11 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
   if (!strcmp(key, "path")) {
     if (value < 0 || value > 2) return LSTM_INT_E_INVALID_ARG;
     m->path = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "cooperative_launch")) {
+    if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
+    m->cooperative = (int)value;
     return LSTM_INT_OK;
   }
   if (!strcmp(key, "reverse")) {

@@ -82,6 +82,8 @@ struct RecArgs {
   int16_t *c_out;       // [B, N] or NULL
   // synchronization scratch, zeroed before the launch
   unsigned *counters;          // [groups][64]
+  unsigned *tickets;           // plain launch: one word (zeroed with the counters) through which the workgroups
+                               // agree on the rotation between workgroup id and XCD; NULL = cooperative launch
   unsigned long long *acc;     // [groups][2 rounds][2 (S1,S2)][rows_pg*4]
   int *status;                 // [0] != 0: a wait gave up or the placement check failed
   int spin_limit;
@@ -98,7 +100,7 @@ bool rec_supported(int N, int H, int flags, int B, int *ks, int *rt, int *groups
 // Dynamic LDS bytes of the recurrent kernel for these arguments.
 size_t rec_lds_bytes(const RecArgs &a);
 // Returns hipSuccess or the launch error.
-hipError_t launch_rec(hipStream_t s, const RecArgs &a);
+hipError_t launch_rec(hipStream_t s, const RecArgs &a, bool cooperative);
 // One-time per process: raises the kernels' dynamic LDS limits.
 hipError_t rec_init();
 

@@ -223,14 +223,21 @@ hipError_t rec_init() {
   return hipSuccess;
 }
 
-hipError_t launch_rec(hipStream_t s, const RecArgs &a) {
+hipError_t launch_rec(hipStream_t s, const RecArgs &a, bool cooperative) {
   rec_fn fn = pick(a.ks, a.rows_pg / 32, (a.flags & 7) | ((a.flags & 8) ? 0 : 8));  // bit 3: no projection
   if (!fn) return hipErrorInvalidValue;
   const int slots = a.GS * ((a.groups + 7) / 8);
   RecArgs args = a;
   void *params[] = {&args};
-  return hipLaunchCooperativeKernel(reinterpret_cast<const void *>(fn), dim3(8 * slots), dim3(256), params,
-                                    (unsigned)rec_lds_bytes(a), s);
+  // The kernel needs all its workgroups resident at once (one per compute unit).  A cooperative launch
+  // has the runtime guarantee that, at 16-18 us per launch (measured); a plain launch gets it from the
+  // in-order stream on a device nothing else occupies.  If the workgroups do not all arrive, the bounded
+  // waits give up and raise the status word: an error, not a hang.
+  if (cooperative)
+    return hipLaunchCooperativeKernel(reinterpret_cast<const void *>(fn), dim3(8 * slots), dim3(256), params,
+                                      (unsigned)rec_lds_bytes(a), s);
+  return hipLaunchKernel(reinterpret_cast<const void *>(fn), dim3(8 * slots), dim3(256), params,
+                         (unsigned)rec_lds_bytes(a), s);
 }
 
 }  // namespace lstm_int

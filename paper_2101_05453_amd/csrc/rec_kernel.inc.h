@@ -93,17 +93,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const bool proj = !(FL & 8) && (a.flags & 8);
   const int GS = a.GS;
 
-  // placement: workgroup w runs on XCD w % 8; the workgroups of a group share one
+  // Placement: the workgroups of a group share one XCD (one L2).  XCC_ID register (id 20), bits 3:0,
+  // is the XCD this workgroup runs on.
   const int wg = blockIdx.x;
-  const int xcd = wg & 7, slot = wg >> 3;
+  const int xcc = (int)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7);
+  const int slot = wg >> 3;
+  int xcd = wg & 7;
+  if (a.tickets) {
+    // Plain launch: the dispatcher deals workgroups out to the XCDs in turn, but starts wherever the
+    // kernel before stopped: workgroup w runs on XCD (w + r) % 8 with an r nobody knows beforehand.
+    // Each block of 8 consecutive workgroups still covers every XCD once, so (the XCD read from the
+    // hardware, w / 8) names a place exactly once -- provided all workgroups see the same r, which
+    // they check against each other through one word (0 = unset, else r + 1).
+    xcd = xcc;
+    if (tid == 0) {
+      unsigned expected = 0;
+      const unsigned mine = (unsigned)((xcc - wg) & 7) + 1;
+      if (!__hip_atomic_compare_exchange_strong(a.tickets, &expected, mine, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT) &&
+          expected != mine)
+        __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  } else if (xcc != xcd && GS > 1 && tid == 0) {
+    // cooperative launch: workgroup w runs on XCD w % 8
+    __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   const int group = xcd + 8 * (slot / GS), member = slot % GS;
   if (group >= a.groups) return;
-  {
-    // XCC_ID register (id 20), bits 3:0
-    const unsigned xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));
-    if ((int)(xcc & 7) != xcd && GS > 1 && tid == 0)
-      __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
   constexpr int rows_pg = 32 * RT;
   constexpr int items = RT * 128;  // (rt, gate, row) layer-norm rows of the group
   const int row0 = a.batch0 + group * rows_pg;  // first batch row of the group

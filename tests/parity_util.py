@@ -38,7 +38,7 @@ def compare_traces(name, gpu_tr, orc_tr, flags):
         assert_equal(f"{name}.{f}", g, o)
 
 
-def run_and_compare(orc, layers, x, name, trace=True, rows=None, with_state=True):
+def run_and_compare(orc, layers, x, name, trace=True, rows=None, with_state=True, options=None):
     """Full comparison on small problems (every traced tensor of every layer),
     or on a subset of batch rows (rows=...) for problems the oracle cannot
     finish whole: batch rows never interact, so the oracle runs only those
@@ -46,6 +46,8 @@ def run_and_compare(orc, layers, x, name, trace=True, rows=None, with_state=True
     import torch
 
     lib_model, orc_model, xq = prepare_both(orc, layers, x)
+    for key, value in (options or {}).items():
+        lib_model.set_option(key, value)
     T, B, _ = xq.shape
     dims = lib_model.dims()
     xd = torch.from_numpy(xq).cuda()

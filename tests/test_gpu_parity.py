@@ -38,6 +38,17 @@ def test_variants_every_tensor(orc, flags):
     run_and_compare(orc, layers, x, f"variant{flags}")
 
 
+@pytest.mark.parametrize("flags", [wl.LAYER_NORM | wl.PROJECTION, wl.CIFG | wl.LAYER_NORM | wl.PEEPHOLE])
+def test_cooperative_launch(orc, flags):
+    """Option "cooperative_launch": the persistent kernel launched through the
+    runtime's cooperative path (the default is a plain launch); 4 workgroups per
+    group, 3 groups, two layers."""
+    H = 136 if flags & wl.PROJECTION else 200
+    print(f"cooperative flags={flags}", flush=True)
+    layers, x = wl.make_custom([72, H], 200, H, flags, 70, 6, seed=flags + 31, weight_param=0.08)
+    run_and_compare(orc, layers, x, f"coop{flags}", trace=False, options={"cooperative_launch": 1})
+
+
 @pytest.mark.parametrize("flags", [0, wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION, wl.CIFG | wl.LAYER_NORM])
 def test_odd_sizes(orc, flags):
     """N = 203 makes G*N odd (scalar int16 stores), I = 7, B = 1."""
