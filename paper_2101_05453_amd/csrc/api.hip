@@ -513,8 +513,9 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.c_in = c_state ? c_state + c_off : nullptr;
       ra.c_out = c_state ? c_state + c_off : nullptr;
       ra.counters = reinterpret_cast<unsigned *>(wsb + ws.sync);
-      // the word shares the zeroed counter region: word 1 of group 0's block (word 0 is its barrier)
-      ra.tickets = m->cooperative ? nullptr : ra.counters + 1;
+      // the words share the zeroed counter region: bytes 8..15 of the blocks of groups 0..7 (bytes 0..3
+      // are the barrier counter)
+      ra.tickets = m->cooperative ? nullptr : reinterpret_cast<unsigned long long *>(ra.counters + 2);
       ra.acc = reinterpret_cast<unsigned long long *>(wsb + ws.sync + 256 * 64 * 4);
       ra.status = m->status;
       ra.spin_limit = m->spin_limit;

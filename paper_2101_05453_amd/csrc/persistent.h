@@ -82,8 +82,8 @@ struct RecArgs {
   int16_t *c_out;       // [B, N] or NULL
   // synchronization scratch, zeroed before the launch
   unsigned *counters;          // [groups][64]
-  unsigned *tickets;           // plain launch: one word (zeroed with the counters) through which the workgroups
-                               // agree on the rotation between workgroup id and XCD; NULL = cooperative launch
+  unsigned long long *tickets; // plain launch: [8 XCDs][32], word 0 of each (zeroed with the counters) sums up
+                               // the workgroups that ran there (rec_kernel.inc.h); NULL = cooperative launch
   unsigned long long *acc;     // [groups][2 rounds][2 (S1,S2)][rows_pg*4]
   int *status;                 // [0] != 0: a wait gave up or the placement check failed
   int spin_limit;

@@ -103,17 +103,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // Plain launch: the dispatcher deals workgroups out to the XCDs in turn, but starts wherever the
     // kernel before stopped: workgroup w runs on XCD (w + r) % 8 with an r nobody knows beforehand.
     // Each block of 8 consecutive workgroups still covers every XCD once, so (the XCD read from the
-    // hardware, w / 8) names a place exactly once -- provided all workgroups see the same r, which
-    // they check against each other through one word (0 = unset, else r + 1).
+    // hardware, w / 8) names a place exactly once -- if the dealing was strict, which every
+    // workgroup helps to check when it is done (end of the kernel).
     xcd = xcc;
-    if (tid == 0) {
-      unsigned expected = 0;
-      const unsigned mine = (unsigned)((xcc - wg) & 7) + 1;
-      if (!__hip_atomic_compare_exchange_strong(a.tickets, &expected, mine, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                __HIP_MEMORY_SCOPE_AGENT) &&
-          expected != mine)
-        __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
   } else if (xcc != xcd && GS > 1 && tid == 0) {
     // cooperative launch: workgroup w runs on XCD w % 8
     __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -804,6 +796,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __hip_atomic_fetch_max(&a.ticks[14], t0 - t_start, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
+  if (a.tickets && tid == 0) {
+    // Placement check of a plain launch, here and not at the start so that nothing waits for it: one
+    // 64-bit word per XCD, low half a sum of 2^(w / 8), high half a count of workgroups.  The workgroup
+    // that completes its XCD's count finds every place taken once (the sum is then all ones), or raises
+    // the status word; so does one that finds the count exceeded -- and an XCD that got too few leaves
+    // another with too many.  (The register is read again: kept from the start it would occupy a
+    // register across the time loop.)
+    const int xcc_now = (int)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7);
+    const unsigned places = gridDim.x >> 3;  // at most 32
+    const u64 mine = ((u64)1 << 32) + ((u64)1 << (wg >> 3));
+    const u64 now = __hip_atomic_fetch_add(&a.tickets[xcc_now * 32], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+    const unsigned count = (unsigned)(now >> 32);
+    const unsigned all = places >= 32 ? 0xFFFFFFFFu : (1u << places) - 1;
+    if (count > places || (count == places && (unsigned)now != all))
+      __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   if (a.c_out) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
