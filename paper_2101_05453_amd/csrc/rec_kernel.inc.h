@@ -110,8 +110,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // cooperative launch: workgroup w runs on XCD w % 8
     __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  // Placement check of a plain launch, made by every workgroup when it is done (not at the start, so
+  // that nothing waits for it): one 64-bit word per XCD, low half a sum of 2^(w / 8), high half a count
+  // of workgroups.  The workgroup that completes its XCD's count finds every place taken once (the sum
+  // is then all ones), or raises the status word; so does one that finds the count exceeded -- and an
+  // XCD that got too few leaves another with too many.  (The register is read again: kept from the
+  // start it would occupy a register across the time loop.)
+  auto placement_check = [&]() {
+    if (a.tickets && tid == 0) {
+      const int xcc_now = (int)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7);
+      const unsigned places = gridDim.x >> 3;  // at most 32
+      const u64 mine = ((u64)1 << 32) + ((u64)1 << (wg >> 3));
+      const u64 now =
+          __hip_atomic_fetch_add(&a.tickets[xcc_now * 32], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+      const unsigned count = (unsigned)(now >> 32);
+      const unsigned all = places >= 32 ? 0xFFFFFFFFu : (1u << places) - 1;
+      if (count > places || (count == places && (unsigned)now != all))
+        __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  };
   const int group = xcd + 8 * (slot / GS), member = slot % GS;
-  if (group >= a.groups) return;
+  if (group >= a.groups) {  // no rows for this workgroup
+    placement_check();
+    return;
+  }
   constexpr int rows_pg = 32 * RT;
   constexpr int items = RT * 128;  // (rt, gate, row) layer-norm rows of the group
   const int row0 = a.batch0 + group * rows_pg;  // first batch row of the group
@@ -796,22 +818,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __hip_atomic_fetch_max(&a.ticks[14], t0 - t_start, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
-  if (a.tickets && tid == 0) {
-    // Placement check of a plain launch, here and not at the start so that nothing waits for it: one
-    // 64-bit word per XCD, low half a sum of 2^(w / 8), high half a count of workgroups.  The workgroup
-    // that completes its XCD's count finds every place taken once (the sum is then all ones), or raises
-    // the status word; so does one that finds the count exceeded -- and an XCD that got too few leaves
-    // another with too many.  (The register is read again: kept from the start it would occupy a
-    // register across the time loop.)
-    const int xcc_now = (int)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7);
-    const unsigned places = gridDim.x >> 3;  // at most 32
-    const u64 mine = ((u64)1 << 32) + ((u64)1 << (wg >> 3));
-    const u64 now = __hip_atomic_fetch_add(&a.tickets[xcc_now * 32], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
-    const unsigned count = (unsigned)(now >> 32);
-    const unsigned all = places >= 32 ? 0xFFFFFFFFu : (1u << places) - 1;
-    if (count > places || (count == places && (unsigned)now != all))
-      __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
+  placement_check();
   if (a.c_out) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
