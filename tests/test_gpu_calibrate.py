@@ -75,6 +75,12 @@ def test_c2_statistics_give_the_same_integer_model(orc):
             assert got[k] == ref[k], k
 
 
+def test_c4_stack_statistics(orc):
+    """The 8-layer stack of the headline configuration, on its 16 calibration rows."""
+    layers, x = wl.make_workload("C4")
+    _compare(orc, layers, np.ascontiguousarray(x[:, :16]))
+
+
 def test_argument_errors():
     import torch
     from paper_2101_05453_amd import binding
