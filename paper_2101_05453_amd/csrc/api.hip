@@ -473,6 +473,17 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
     ld_in = m->dev[0].Ipad;
   }
 
+  // The final h of a layer on the persistent path goes to the caller's state buffer together with the
+  // next such layer's start (one launch less per layer), or at the latest when forward ends.
+  struct {
+    const int8_t *src = nullptr;
+    int ld = 0, cols = 0;
+    int8_t *dst = nullptr;
+  } pend;
+  auto flush_pending = [&]() {
+    if (pend.dst) launch_copy_rows_i8(s, pend.src, pend.ld, pend.dst, pend.cols, B, pend.cols, 0);
+    pend.dst = nullptr;
+  };
   size_t h_off = 0, c_off = 0;
   for (int l = 0; l < L; ++l) {
     const LayerHost &h = m->host[l];
@@ -553,7 +564,8 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
         Timed t(m->prof, s, LSTM_INT_K_OTHER);
         const int g0 = std::min(p2_groups, (B + ra.rows_pg - 1) / ra.rows_pg);
         launch_init_layer(s, h_state ? h_state + h_off : nullptr, h.H, h0, d.Hpad, B, h.H, h.zp_h, wsb + ws.sync,
-                          sync_bytes(g0));
+                          sync_bytes(g0), pend.src, pend.ld, pend.dst, pend.cols);
+        pend.dst = nullptr;
       }
       {
         Timed t(m->prof, s, LSTM_INT_K_INPUT_GEMM);
@@ -604,9 +616,12 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       }
       {
         Timed t(m->prof, s, LSTM_INT_K_OTHER);
-        if (h_state)
-          launch_copy_rows_i8(s, out + (size_t)(T - 1) * step_out, d.Hpad, h_state + h_off, h.H, B,
-                              h.H, 0);
+        if (h_state) {
+          pend.src = out + (size_t)(T - 1) * step_out;
+          pend.ld = d.Hpad;
+          pend.dst = h_state + h_off;
+          pend.cols = h.H;
+        }
         if (last && rev) launch_flip_rows_i8(s, out, d.Hpad, y, h.H, T, B, h.H, 0);
       }
       h_off += (size_t)B * h.H;
@@ -617,6 +632,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
     }
     {  // initial state: given, or real 0 (q = zp_h) and c = 0
       Timed t(m->prof, s, LSTM_INT_K_OTHER);
+      flush_pending();
       if (h_state)
         launch_copy_rows_i8(s, h_state + h_off, h.H, h0, d.Hpad, B, h.H, 0);
       else
@@ -697,6 +713,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
     in = out;
     ld_in = d.Hpad;
   }
+  flush_pending();
   return hipGetLastError() == hipSuccess ? LSTM_INT_OK : LSTM_INT_E_DEVICE;
 }
 

@@ -65,9 +65,11 @@ void launch_flip_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *d
 void launch_fill_rows_i8(hipStream_t s, int8_t *dst, int ld_dst, int rows, int cols, int value,
                          int fill);
 // h0 [rows, ld_h0] <- h_src [rows, ld_src] (first cols bytes; NULL: all zp), padding bytes 0; and
-// sync_bytes (a multiple of 16) of zeros at sync -- one launch
+// sync_bytes (a multiple of 16) of zeros at sync;
+// and, if c_dst is not NULL, c_dst [rows, c_cols] <- c_src [rows, c_ld_src] -- one launch
 void launch_init_layer(hipStream_t s, const int8_t *h_src, int ld_src, int8_t *h0, int ld_h0, int rows, int cols,
-                       int zp, void *sync, int64_t sync_bytes);
+                       int zp, void *sync, int64_t sync_bytes, const int8_t *c_src, int c_ld_src, int8_t *c_dst,
+                       int c_cols);
 void launch_copy_i16(hipStream_t s, const int16_t *src, int16_t *dst, int64_t n);
 void launch_fill_i16(hipStream_t s, int16_t *dst, int64_t n, int value);
 // dump [rows, G*N] (present gates) into [rows, 4, N] gate slots first..3

@@ -393,31 +393,46 @@ void launch_fill_rows_i8(hipStream_t s, int8_t *dst, int ld_dst, int rows, int c
 }
 
 // Start of a layer on the persistent path, in one launch: the initial hidden
-// state (given rows, or the code of real 0; padding bytes 0) and the
-// zeroed synchronization words.  Workgroups [0, zero_blocks) clear, the rest
-// write h.
+// state (given rows, or the code of real 0; padding bytes 0), the zeroed
+// synchronization words, and -- to save a launch -- a pending copy of rows
+// (the previous layer's final h on its way to the caller's state buffer).
+// Workgroups [0, zero_blocks) clear, the next h_blocks write h, the rest copy.
 __global__ void init_layer_kernel(const int8_t *h_src, int ld_src, int8_t *h0, int ld_h0, int rows, int cols,
-                                  int zp, int4 *sync, int64_t sync_vec, int zero_blocks) {
+                                  int zp, int4 *sync, int64_t sync_vec, int zero_blocks, int h_blocks,
+                                  const int8_t *c_src, int c_ld_src, int8_t *c_dst, int c_cols) {
   if ((int)blockIdx.x < zero_blocks) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < sync_vec; i += (int64_t)zero_blocks * blockDim.x)
       sync[i] = int4{0, 0, 0, 0};
     return;
   }
-  const int64_t total = (int64_t)rows * ld_h0;
-  const int64_t nb = gridDim.x - zero_blocks;
-  for (int64_t i = (blockIdx.x - zero_blocks) * (int64_t)blockDim.x + threadIdx.x; i < total; i += nb * blockDim.x) {
-    const int64_t r = i / ld_h0;
-    const int col = (int)(i - r * ld_h0);
-    h0[i] = col < cols ? (h_src ? h_src[r * ld_src + col] : (int8_t)zp) : (int8_t)0;
+  if ((int)blockIdx.x < zero_blocks + h_blocks) {
+    const int64_t total = (int64_t)rows * ld_h0;
+    for (int64_t i = (blockIdx.x - zero_blocks) * (int64_t)blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)h_blocks * blockDim.x) {
+      const int64_t r = i / ld_h0;
+      const int col = (int)(i - r * ld_h0);
+      h0[i] = col < cols ? (h_src ? h_src[r * ld_src + col] : (int8_t)zp) : (int8_t)0;
+    }
+    return;
+  }
+  const int64_t nb = gridDim.x - zero_blocks - h_blocks;
+  const int64_t total = (int64_t)rows * c_cols;  // the copy has the same number of rows (the batch)
+  for (int64_t i = (blockIdx.x - zero_blocks - h_blocks) * (int64_t)blockDim.x + threadIdx.x; i < total;
+       i += nb * blockDim.x) {
+    const int64_t r = i / c_cols;
+    const int col = (int)(i - r * c_cols);
+    c_dst[i] = c_src[r * c_ld_src + col];
   }
 }
 
 void launch_init_layer(hipStream_t s, const int8_t *h_src, int ld_src, int8_t *h0, int ld_h0, int rows, int cols,
-                       int zp, void *sync, int64_t sync_bytes) {
+                       int zp, void *sync, int64_t sync_bytes, const int8_t *c_src, int c_ld_src, int8_t *c_dst,
+                       int c_cols) {
   const int64_t vec = sync_bytes / 16;  // the region is a multiple of 16 bytes, 16-byte aligned
   const int zb = grid_for(vec), hb = grid_for((int64_t)rows * ld_h0);
-  hipLaunchKernelGGL(init_layer_kernel, dim3(zb + hb), dim3(256), 0, s, h_src, ld_src, h0, ld_h0, rows, cols, zp,
-                     static_cast<int4 *>(sync), vec, zb);
+  const int cb = c_dst ? grid_for((int64_t)rows * c_cols) : 0;
+  hipLaunchKernelGGL(init_layer_kernel, dim3(zb + hb + cb), dim3(256), 0, s, h_src, ld_src, h0, ld_h0, rows, cols, zp,
+                     static_cast<int4 *>(sync), vec, zb, hb, c_src, c_ld_src, c_dst, c_cols);
 }
 
 __global__ void copy_i16_kernel(const int16_t *src, int16_t *dst, int64_t n, int value) {
