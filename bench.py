@@ -153,7 +153,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": wl.describe(args.config), "cell_steps_per_step": cell_steps,
-                   "batch": B, "seq_len": T, "layers": L},
+                   "batch": B, "seq_len": T, "layers": L,
+                   "options": "library defaults (plain launch of the recurrent kernel)"},
         "roofline": roof,
     }
 
