@@ -45,6 +45,9 @@ struct LayerDev {
   int8_t *W2f = nullptr;    // the same in MFMA operand order [GS*8][Ipad/32][64 lanes][16] (Ipad <= 1024), else NULL
   int32_t *bx2 = nullptr;   // [GS*8][32]
   int4 *R2 = nullptr;       // [GS][4][2][ks][64]
+  bool p16 = false;         // the 16-row kernel takes this layer (small batches)
+  int ks16 = 0;
+  int4 *R2h = nullptr;      // [GS][4][4][ks16][64]
   int32_t *bh4 = nullptr, *qb4 = nullptr;  // [4][Ncp]
   int16_t *Lq4 = nullptr, *Pq3 = nullptr;  // [4][Ncp], [3][Ncp]
   int8_t *Wp2 = nullptr;    // [ptiles][32][npadp]
@@ -73,6 +76,7 @@ struct lstm_int_model {
   int path = 0;
   int reverse = 0;  // 1: the recursion runs from time T - 1 down to 0
   int cooperative = 0;  // 1: the persistent kernel is launched cooperatively
+  int rows16 = 1;       // 1: batches that fit one launch of the 16-row kernel take it
   int spin_limit = 1 << 21;
   int poll_sleep = 0, stats_sleep = 0;  // pauses between polls, in units of 64 clocks
   int idle_sleep = 64, idle_poll_sleep = 12;
@@ -234,7 +238,9 @@ int upload(lstm_int_model *m) {
       // tile-ordered copies for the persistent path
       int ks = 0, rt = 0, grp = 0;
       d.p2 = rec_supported(h.N, h.H, (int)h.flags, 32, &ks, &rt, &grp);
-      size_t oW2f = 0;
+      size_t oW2f = 0, oR2h = 0;
+      int ks16 = 0, grp16 = 0;
+      d.p16 = d.p2 && rec16_supported(h.N, h.H, (int)h.flags, 16, &ks16, &grp16);
       size_t oW2 = 0, obx2 = 0, oR2 = 0, obh4 = 0, oqb4 = 0, oLq4 = 0, oPq3 = 0, oWp2 = 0, obp2 = 0;
       if (d.p2) {
         d.GS = (h.N + 63) / 64;
@@ -246,6 +252,10 @@ int upload(lstm_int_model *m) {
         if (d.Ipad <= 1024) oW2f = take((size_t)d.GS * 8 * 32 * d.Ipad);
         obx2 = take((size_t)d.GS * 8 * 32 * 4);
         oR2 = take((size_t)d.GS * 4 * 2 * ks * 64 * 16);
+        if (d.p16) {
+          d.ks16 = ks16;
+          oR2h = take((size_t)d.GS * 4 * 4 * ks16 * 64 * 16);
+        }
         obh4 = take((size_t)4 * d.Ncp * 4);
         oqb4 = take((size_t)4 * d.Ncp * 4);
         oLq4 = take((size_t)4 * d.Ncp * 2);
@@ -287,6 +297,16 @@ int upload(lstm_int_model *m) {
               const size_t o = ((((size_t)(member * 4 + wave) * 2 + tl) * ks + kstep) * 64 + lane) * 16 + byte;
               base[oR2 + o] = (uint8_t)h.Rq[src * h.H + k];
             }
+            if (d.p16) {
+              // 16-row kernel: [member][wave][tile j][ks16][lane][16]; tile j of a wave holds cell
+              // 16 wave + 4 q + j of gate g in row 4 q + g, lane = row + 16 * (k / 16 % 4)
+              const int j = n % 4, trow16 = 4 * ((n % 16) / 4) + g;
+              for (int k = 0; k < h.H; ++k) {
+                const size_t o =
+                    ((((size_t)(member * 4 + wave) * 4 + j) * ks16 + k / 64) * 64 + trow16 + 16 * ((k % 64) / 16)) * 16 + k % 16;
+                base[oR2h + o] = (uint8_t)h.Rq[src * h.H + k];
+              }
+            }
           }
         }
         for (int j = first; j < 3; ++j)
@@ -303,6 +323,7 @@ int upload(lstm_int_model *m) {
         d.W2f = d.Ipad <= 1024 ? reinterpret_cast<int8_t *>(db + oW2f) : nullptr;
         d.bx2 = reinterpret_cast<int32_t *>(db + obx2);
         d.R2 = reinterpret_cast<int4 *>(db + oR2);
+        d.R2h = d.p16 ? reinterpret_cast<int4 *>(db + oR2h) : nullptr;
         d.bh4 = reinterpret_cast<int32_t *>(db + obh4);
         d.qb4 = reinterpret_cast<int32_t *>(db + oqb4);
         d.Lq4 = reinterpret_cast<int16_t *>(db + oLq4);
@@ -366,7 +387,7 @@ int upload(lstm_int_model *m) {
   m->tanh3_blob = dbase + blob_off[3];
   m->sh_sig3 = sh_sig;
   m->sh_tanh3 = sh_tab[3];
-  if (rec_init() != hipSuccess || in_gemm_init() != hipSuccess) return LSTM_INT_E_DEVICE;
+  if (rec_init() != hipSuccess || rec16_init() != hipSuccess || in_gemm_init() != hipSuccess) return LSTM_INT_E_DEVICE;
   return LSTM_INT_OK;
 }
 
@@ -498,6 +519,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
     bool use_p2 = m->path != 1 && !tr && d.p2 && (reinterpret_cast<uintptr_t>(y) & 3) == 0 &&
                   rec_supported(h.N, h.H, (int)h.flags, B, &p2_ks, &p2_rt, &p2_groups);
     RecArgs ra;
+    bool use16 = false;
     if (use_p2) {
       memset(&ra, 0, sizeof(ra));
       ra.T = T; ra.B = B; ra.N = h.N; ra.H = h.H; ra.Hpad = d.Hpad; ra.flags = (int)h.flags; ra.m_c = h.m_c;
@@ -553,6 +575,17 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
         ra.groups = p2_groups;
       }
       if (!ok || rec_lds_bytes(ra) > 160 * 1024) use_p2 = false;
+      // small batches: groups of 16 rows fill more compute units and halve a step's arithmetic
+      int k16 = 0, g16 = 0;
+      if (use_p2 && m->rows16 && d.p16 && rec16_supported(h.N, h.H, (int)h.flags, B, &k16, &g16)) {
+        RecArgs r16 = ra;
+        r16.R2h = d.R2h; r16.ks16 = d.ks16; r16.rows_pg = 16; r16.groups = g16;
+        if (rec16_lds_bytes(r16) <= 160 * 1024) {
+          ra = r16;
+          p2_groups = g16;
+          use16 = true;
+        }
+      }
     }
     if (use_p2) {
       // bytes of the synchronization region a launch over `groups` groups uses: all counters, and the
@@ -611,7 +644,8 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
             launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), sync_bytes(ra.groups) / 2, 0);
           }
           Timed t(m->prof, s, LSTM_INT_K_RECURRENT);
-          if (launch_rec(s, ra, m->cooperative != 0) != hipSuccess) return LSTM_INT_E_DEVICE;
+          if ((use16 ? launch_rec16(s, ra, m->cooperative != 0) : launch_rec(s, ra, m->cooperative != 0)) != hipSuccess)
+            return LSTM_INT_E_DEVICE;
         }
       }
       {
@@ -727,6 +761,11 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
   if (!strcmp(key, "cooperative_launch")) {
     if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
     m->cooperative = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "rows16")) {
+    if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
+    m->rows16 = (int)value;
     return LSTM_INT_OK;
   }
   if (!strcmp(key, "reverse")) {

@@ -55,6 +55,8 @@ struct RecArgs {
   int Ncp;        // GS * 64
   int Bp;         // B rounded up to 32
   const int4 *R2;      // [GS][4 waves][2 tiles][ks][64 lanes] 16 bytes each
+  const int4 *R2h;     // 16-row kernel: [GS][4 waves][4 tiles][ks16][64 lanes] 16 bytes each
+  int ks16;            // 16-row kernel: 64-wide k steps held in registers
   const int32_t *bh4;  // [4][Ncp]
   const int16_t *Lq4;  // [4][Ncp]
   const int32_t *qb4;  // [4][Ncp]
@@ -103,5 +105,13 @@ size_t rec_lds_bytes(const RecArgs &a);
 hipError_t launch_rec(hipStream_t s, const RecArgs &a, bool cooperative);
 // One-time per process: raises the kernels' dynamic LDS limits.
 hipError_t rec_init();
+
+// The same step for groups of 16 batch rows (rec16_kernel.inc.h): layer norm without CIFG and peephole
+// connections, batches of up to 16 * 8 * (32 / GS) rows in one launch.  mbuf is
+// [T][Bp / 16][npadp / 64][16 rows][64 cells] here.
+bool rec16_supported(int N, int H, int flags, int B, int *ks16, int *groups);
+size_t rec16_lds_bytes(const RecArgs &a);
+hipError_t launch_rec16(hipStream_t s, const RecArgs &a, bool cooperative);
+hipError_t rec16_init();
 
 }  // namespace lstm_int

@@ -17,6 +17,8 @@
 //                    cell update, hidden state, projection; groups synchronize
 //                    through a counter in global memory.  Batch rows never
 //                    interact, so groups run independently.
+//   rec16_kernel     the same step on groups of 16 rows (16x16x64 MFMA) for
+//                    small batches: rec16_kernel.inc.h, rec16_inst.hip.
 //
 // Exchange between the workgroups of a group goes through buffers that are
 // written once per step, in 128-byte cache lines that nothing has read before

@@ -1,0 +1,495 @@
+// Persistent recurrent kernel for small batches: groups of 16 batch rows on
+// the 16x16x64 int8 MFMA (rec_kernel.inc.h has the design; this is the same
+// step with half the rows per workgroup, so that 128 rows already fill the
+// chip and a workgroup's arithmetic per step is half as long).  Layer norm on,
+// no CIFG, no peephole; the projection is a runtime flag.
+//
+// Lane (r = lane % 16, q = lane / 16) of wave w owns batch row r of the group
+// and cells 16 w + 4 q + c, c = 0..3, of the workgroup's 64, all four gates:
+// weight tile j of the wave holds, in row 4 q' + gate, cell 16 w + 4 q' + j,
+// so that result value `gate` of tile j in that lane is (cell 4 q + j, gate).
+// The W x terms are read in the layout the input GEMM writes for the 32-row
+// kernel (two 16-byte loads per lane and step).
+#pragma once
+
+#include "rec_kernel.inc.h"
+
+namespace lstm_int {
+
+template <int KS16>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void rec16_kernel(RecArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const bool proj = a.flags & 8;
+  const int GS = a.GS;
+
+  // placement, as in rec_kernel
+  const int wg = blockIdx.x;
+  const int xcc = (int)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7);
+  const int slot = wg >> 3;
+  int xcd = wg & 7;
+  if (a.tickets) {
+    xcd = xcc;
+  } else if (xcc != xcd && GS > 1 && tid == 0) {
+    __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  auto placement_check = [&]() {
+    if (a.tickets && tid == 0) {
+      const int xcc_now = (int)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7);
+      const unsigned places = gridDim.x >> 3;  // at most 32
+      const u64 mine = ((u64)1 << 32) + ((u64)1 << (wg >> 3));
+      const u64 now =
+          __hip_atomic_fetch_add(&a.tickets[xcc_now * 32], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+      const unsigned count = (unsigned)(now >> 32);
+      const unsigned all = places >= 32 ? 0xFFFFFFFFu : (1u << places) - 1;
+      if (count > places || (count == places && (unsigned)now != all))
+        __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  };
+  const int group = xcd + 8 * (slot / GS), member = slot % GS;
+  if (group >= a.groups) {
+    placement_check();
+    return;
+  }
+  constexpr int items = 64;                    // (gate, row) layer-norm rows of the group
+  const int row0 = a.batch0 + group * 16;      // first batch row of the group
+  const int cellw = wave * 16 + 4 * q;         // + c, within the workgroup's 64 cells
+
+  // ---- LDS carve-up (rec16_lds_bytes mirrors it)
+  constexpr int LS = KS16 * 64 + 16;  // h tile row stride: LS / 4 = 4 * odd (mod 64), reads are conflict-free
+  constexpr int TILE_KB = (16 * LS + 1023) / 1024;
+  uint8_t *p = lds;
+  int8_t *hT = reinterpret_cast<int8_t *>(p);
+  int32_t *pred = reinterpret_cast<int32_t *>(p);  // projection partials reuse the h tile between steps
+  {
+    const size_t tile_bytes = (size_t)(TILE_KB + 1) * 1024;  // one spare chunk for the loads past the tile
+    const size_t pred_bytes = proj ? 4 * 2 * 4 * 64 * 4 : 0;
+    p += tile_bytes > pred_bytes ? tile_bytes : pred_bytes;
+  }
+  u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)4 * items * 8;
+  LnRow2 *lnrow = reinterpret_cast<LnRow2 *>(p);         p += (size_t)items * sizeof(LnRow2);
+  double *LdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;
+  double *bdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;
+  int32_t *bhL = reinterpret_cast<int32_t *>(p);         p += 4 * 64 * 4;
+  PrmLds *prm = reinterpret_cast<PrmLds *>(p);           p += sizeof(PrmLds);
+  int *flag = reinterpret_cast<int *>(p);                p += 16;
+  const bool share_tanh = a.tanhc_blob == a.tanh_blob;
+  const uint8_t *lutS = p;                               p += kLutBlobBytes;
+  const uint8_t *lutT = p;                               p += kLutBlobBytes;
+  const uint8_t *lutC = share_tanh ? lutT : p;           p += share_tanh ? 0 : kLutBlobBytes;
+  int8_t *WpL = reinterpret_cast<int8_t *>(p);
+  const int WLS = a.npadp + 16;  // W_proj tile row stride in LDS
+  const int my_ptiles = proj ? (a.ptiles > member ? (a.ptiles - member + GS - 1) / GS : 0) : 0;
+  const int sh_sig = a.sh_sig, sh_tanh = a.sh_tanh, sh_tanhc = a.sh_tanhc;
+
+  // ---- one-time loads: R slice -> registers, per-cell parameters, tables and W_proj tiles -> LDS
+  v4i Wf[4][KS16];
+  {
+    const int4 *src = a.R2h + ((size_t)(member * 4 + wave) * 4) * KS16 * 64 + lane;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int4 w[KS16];
+#pragma unroll
+      for (int ks = 0; ks < KS16; ++ks) w[ks] = src[(size_t)(j * KS16 + ks) * 64];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < KS16; ++ks) {
+        Wf[j][ks] = v4i{w[ks].x, w[ks].y, w[ks].z, w[ks].w};
+        asm volatile("" : "+a"(Wf[j][ks]));  // resident in accumulation registers for the whole launch
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  {
+    const int g = tid >> 6, n = tid & 63;  // 256 threads = 4 gates x 64 cells
+    const size_t idx = (size_t)g * a.Ncp + member * 64 + n;
+    LdL[tid] = ln_weight_scaled(a.Lq4[idx]);
+    bdL[tid] = ln_bias_scaled(a.qb4[idx]);
+    bhL[tid] = a.bh4[idx];
+  }
+  if (tid < 4) {
+    prm->h[tid] = rescale_hi_prepare(a.Mh[tid], a.rh[tid]);
+    prm->ln[tid] = rescale_hi_prepare(a.Mln[tid], a.rln[tid]);
+  }
+  if (tid == 0) {
+    prm->m = rescale_hi_prepare(a.Mm, a.rm);
+    prm->p = rescale_hi_prepare(proj ? a.Mp : 0, proj ? a.rp : 33);
+    prm->zp_m = a.zp_m; prm->zp_h = a.zp_h;
+    prm->m_c = a.m_c; prm->glo = -32767;
+  }
+  for (int i = tid; i < 16 * LS / 16; i += 256) reinterpret_cast<int4 *>(hT)[i] = int4{0, 0, 0, 0};
+  {
+    auto dma = [&](const void *src, const void *dst) {
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                       (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    };
+    for (int c = wave; c < kLutBlobBytes / 1024; c += 4) {
+      dma(a.sig_blob + c * 1024 + lane * 16, lutS + c * 1024);
+      dma(a.tanh_blob + c * 1024 + lane * 16, lutT + c * 1024);
+      if (!share_tanh) dma(a.tanhc_blob + c * 1024 + lane * 16, lutC + c * 1024);
+    }
+    const int wp_rows = my_ptiles * 32;
+    const int wp_chunks = (wp_rows * WLS + 1023) >> 10;
+    for (int c = wave; c < wp_chunks; c += 4) {
+      const int o = c * 1024 + lane * 16;
+      const int rr = o / WLS, col_b = o - rr * WLS;
+      const int8_t *src = a.Wp2;
+      if (rr < wp_rows && col_b < a.npadp) {
+        const int pt = rr >> 5;
+        src = a.Wp2 + ((size_t)(member + pt * GS) * 32 + (rr & 31)) * a.npadp + col_b;
+      }
+      dma(src, WpL + c * 1024);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+
+  // cell state of this lane's 4 cells of its row, kept in registers
+  const int row = row0 + r;
+  const int n0 = member * 64 + cellw;
+  int32_t creg[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+    creg[c] = (a.c_in && row < a.B && n0 + c < a.N) ? a.c_in[(size_t)row * a.N + n0 + c] : 0;
+
+  // h tile staging: wave instruction (wave + 4 j) fills bytes [1024 c, 1024 (c + 1)) of the tile
+  constexpr int NCH = (TILE_KB + 3) / 4;
+  int hsrc[NCH];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int o = (wave + 4 * j) * 1024 + lane * 16;
+    const int rr = o / LS, c = o - rr * LS;
+    int rw = row0 + rr;
+    rw = rw < a.B ? rw : a.B - 1;
+    hsrc[j] = (rr < 16 && c < a.Hpad) ? rw * a.Hpad + c : 0;
+  }
+
+  // projection: thread (ct = tid / 64 < 2, lane) finishes outputs 16 ct + 4 q + 0..3 of row r
+  int32_t bpr[4] = {0, 0, 0, 0};
+  if (my_ptiles > 0 && tid < 128) {
+    const int4 b4 = *reinterpret_cast<const int4 *>(a.bp2 + member * 32 + 16 * wave + 4 * q);
+    bpr[0] = b4.x; bpr[1] = b4.y; bpr[2] = b4.z; bpr[3] = b4.w;
+  }
+  if (tid == 0) {
+    flag[0] = 1;
+    flag[1] = 0;
+  }
+  __syncthreads();
+
+  unsigned epoch = 0;
+  unsigned *counter = a.counters + group * 64;
+  u64 *accS = a.acc + (size_t)group * 4 * 256;  // [S1|S2][item], item < 64 (the first round's words)
+  int64_t prevS[2] = {0, 0};
+  const double inv_n = 1.0 / (double)a.N;
+  const bool pre_ln = a.rln[0] < 33 || a.rln[1] < 33 || a.rln[2] < 33 || a.rln[3] < 33;
+  const bool pre_m = a.rm < 33;
+  constexpr u64 kValMask = ((u64)1 << 56) - 1;
+
+  for (int t = 0; t < a.T; ++t) {
+    // ---- h^{t-1} rows of the group -> LDS; W x terms of this step -> registers
+    {
+      const int8_t *hp = t == 0 ? a.h0 : a.out + (size_t)(t - 1) * a.B * a.Hpad;
+#pragma unroll
+      for (int j = 0; j < NCH; ++j)
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(hp + hsrc[j]),
+            (__attribute__((address_space(3))) void *)(lds + (wave + 4 * j < TILE_KB ? wave + 4 * j : TILE_KB) * 1024),
+            16, 0, 0);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();
+    int32_t txw[8];
+    {
+      size_t rb = ((size_t)t * a.Bp + row0) >> 5;
+      const size_t rbmax = ((size_t)a.T * a.Bp) >> 5;
+      rb = rb < rbmax ? rb : rbmax - 1;
+      // cell tile of 8: 2 w + q / 2; lane of the 32-row layout: row % 32 + 32 * (q % 2)
+      const int4 *src = a.tx2 + ((rb * (size_t)(GS * 8) + member * 8 + wave * 2 + (q >> 1)) * 2) * 64 +
+                        ((row0 + r) & 31) + 32 * (q & 1);
+      const v4i t0 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src));
+      const v4i t1 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src + 64));
+      txw[0] = t0.x; txw[1] = t0.y; txw[2] = t0.z; txw[3] = t0.w;
+      txw[4] = t1.x; txw[5] = t1.y; txw[6] = t1.z; txw[7] = t1.w;
+    }
+
+    // ---- R h on the MFMA: acc[j][gate] for cell 4 q + j; each tile's k loop runs to its end
+    // before the next tile starts (dependent 16x16x64 MFMAs issue back to back, rotating
+    // accumulators do not)
+    v4i acc[4];
+    {
+      v4i hf[KS16];
+      const int8_t *hbase = hT + (size_t)r * LS + (q << 4);
+#pragma unroll
+      for (int ks = 0; ks < KS16; ++ks) hf[ks] = *reinterpret_cast<const v4i *>(hbase + ks * 64);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) acc[j][g] = bhL[g * 64 + cellw + j];
+#pragma unroll
+        for (int ks = 0; ks < KS16; ++ks)
+          acc[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(Wf[j][ks], hf[ks], acc[j], 0, 0, 0);
+      }
+    }
+
+    // ---- gate sums (Sec. 3.2.5) and layer-norm partial statistics
+    int32_t gs[4][4];  // [gate][cell]
+    auto gate_sums = [&](auto pre_tag) {
+      constexpr int PRE = decltype(pre_tag)::value;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const RescaleHi pg = prm->h[g];
+        int32_t s1 = 0;
+        uint32_t s2 = 0;  // four squares of 16-bit values fit 32 bits
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int idx = g * 4 + c;
+          const int32_t th = rescale_sat16_pre<PRE>(acc[c][g], pg);
+          const int32_t w = txw[idx >> 1];
+          const int32_t tx = (idx & 1) ? (w >> 16) : (int32_t)(int16_t)(w & 0xFFFF);
+          const int32_t v = clamp_i32(tx + th, -32767, 32767);
+          gs[g][c] = v;
+          s1 += v;
+          s2 += (uint32_t)v * (uint32_t)v;
+        }
+        int64_t pk = ((int64_t)(u64)s2 << 24) + s1;
+        pk += __shfl_xor(pk, 16, 64);
+        pk += __shfl_xor(pk, 32, 64);
+        if (q == 0) red[(size_t)wave * items + g * 16 + r] = (u64)pk;
+      }
+    };
+    if (a.pre_h == 0)
+      gate_sums(std::integral_constant<int, 0>{});
+    else if (a.pre_h == 1)
+      gate_sums(std::integral_constant<int, 1>{});
+    else
+      gate_sums(std::integral_constant<int, 2>{});
+
+    // statistics over the group's workgroups: as in rec_kernel (words that are never reset, the top
+    // byte counts the adds)
+    __syncthreads();
+    if (tid < items) {
+      const int64_t pk = (int64_t)(red[tid] + red[items + tid] + red[2 * items + tid] + red[3 * items + tid]);
+      const int64_t v1 = ((pk + (1 << 23)) & 0xFFFFFF) - (1 << 23);
+      const int64_t v2 = (pk - v1) >> 24;
+      __hip_atomic_fetch_add(&accS[tid], ((u64)1 << 56) + (u64)(v1 + (1 << 22)), __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(&accS[256 + tid], ((u64)1 << 56) + (u64)v2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const u64 expect = (u64)(((unsigned)GS * (unsigned)(t + 1)) & 0xFFu);
+      u64 c1, c2;
+      int budget = a.spin_limit;
+      for (int i = 0; i < a.stats_first_sleep; ++i) __builtin_amdgcn_s_sleep(1);
+      for (;;) {
+        c1 = __hip_atomic_load(&accS[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        c2 = __hip_atomic_load(&accS[256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((c1 >> 56) == expect && (c2 >> 56) == expect) break;
+        if (--budget <= 0 || __hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+          __hip_atomic_store(a.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          *flag = 0;
+          break;
+        }
+        for (int i = 0; i < a.stats_sleep; ++i) __builtin_amdgcn_s_sleep(1);
+      }
+      c1 &= kValMask;
+      c2 &= kValMask;
+      const int64_t S1 = (int64_t)((c1 - (u64)prevS[0]) & kValMask) - (int64_t)GS * (1 << 22);
+      const int64_t S2 = (int64_t)((c2 - (u64)prevS[1]) & kValMask);
+      prevS[0] = (int64_t)c1;
+      prevS[1] = (int64_t)c2;
+      lnrow[tid] = ln_row2(ln_row(S1, S2, a.N, inv_n));
+    }
+    __syncthreads();
+    if (*flag == 0) return;
+
+    // ---- layer norm, sigma/tanh, cell update (Secs. 3.2.6, 3.2.1, 3.2.7); LDS reads in batches
+    int32_t xv[4][4], tv[4][4];
+    {
+      LnRow2 lr[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) lr[g] = lnrow[g * 16 + r];
+#pragma unroll
+      for (int gp = 0; gp < 4; gp += 2) {
+        double wL[2][4], wb[2][4];
+        RescaleHi pl[2];
+#pragma unroll
+        for (int g = gp; g < gp + 2; ++g) {
+          pl[g - gp] = prm->ln[g];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            wL[g - gp][c] = LdL[g * 64 + cellw + c];
+            wb[g - gp][c] = bdL[g * 64 + cellw + c];
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = gp; g < gp + 2; ++g)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            int32_t v = ln_second_stage(gs[g][c], lr[g], wL[g - gp][c], wb[g - gp][c]);
+            if (pre_ln) v = rescale_preshift(v, pl[g - gp]);
+            xv[g][c] = rescale_sat16_pre<0>(v, pl[g - gp]);
+          }
+      }
+    }
+    auto lookup = [&](int gmask, const int32_t (&x)[4][4], const uint8_t *const (&blob)[4], const int (&shf)[4],
+                      const uint16_t *const (&full)[4], int32_t (&out)[4][4]) {
+      int32_t mag[4][4];
+      uint32_t base[4][4], delta[4][4];
+      int over = 0;
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        if (gmask >> g & 1)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            mag[g][c] = abs_i32(x[g][c]);
+            over |= mag[g][c];
+            const int32_t ai = mag[g][c] < kLutDomain ? mag[g][c] : kLutDomain - 1;
+            base[g][c] = reinterpret_cast<const uint16_t *>(blob[g] + kLutDomain)[ai >> shf[g]];
+            delta[g][c] = blob[g][ai];
+          }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        if (gmask >> g & 1)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) out[g][c] = (int32_t)(base[g][c] + delta[g][c]);
+      if (__builtin_amdgcn_ballot_w64(over >= kLutDomain) != 0) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          if (gmask >> g & 1)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+              if (mag[g][c] >= kLutDomain) out[g][c] = full[g][mag[g][c]];
+      }
+    };
+    {
+      const uint8_t *const gate_blob[4] = {lutS, lutS, lutT, lutS};
+      const int gate_sh[4] = {sh_sig, sh_sig, sh_tanh, sh_sig};
+      const uint16_t *const gate_full[4] = {a.sig_tab, a.sig_tab, a.tanh_tab, a.sig_tab};
+      lookup(15, xv, gate_blob, gate_sh, gate_full, tv);
+    }
+    const int32_t m_c = prm->m_c;
+    int32_t xo[4];
+    int32_t cx[4][4];  // slot 0: the new cell state, for its tanh
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int32_t ig = mirror_sigmoid(xv[0][c], tv[0][c]);
+      const int32_t fg = mirror_sigmoid(xv[1][c], tv[1][c]);
+      const int32_t zg = mirror_tanh(xv[2][c], tv[2][c]);
+      xo[c] = mirror_sigmoid(xv[3][c], tv[3][c]);
+      creg[c] = cell_update32(ig, zg, fg, creg[c], m_c);
+      cx[0][c] = creg[c];
+    }
+
+    // ---- hidden state (Sec. 3.2.7)
+    int32_t tcv[4][4];
+    {
+      const uint8_t *const hid_blob[4] = {lutC, lutC, lutC, lutC};
+      const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_tanhc, sh_tanhc};
+      const uint16_t *const hid_full[4] = {a.tanhc_tab, a.tanhc_tab, a.tanhc_tab, a.tanhc_tab};
+      lookup(1, cx, hid_blob, hid_sh, hid_full, tcv);
+    }
+    {
+      const RescaleHi pm = prm->m;
+      const int32_t zp_m = prm->zp_m;
+      uint32_t pk = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        int32_t om = xo[c] * mirror_tanh(cx[0][c], tcv[0][c]);
+        if (pre_m) om = rescale_preshift(om, pm);
+        const int32_t mq = sat8(rescale_sat16_pre<0>(om, pm) + zp_m);
+        pk |= (uint32_t)(mq & 0xFF) << (8 * c);
+      }
+      if (row < a.B && n0 < a.N) {
+        if (proj) {
+          // exchange buffer [t][row / 16][k step of 64 cells = member][row % 16][64 cells]: a wave's
+          // load of one projection k step is one contiguous KB
+          int8_t *mdst = a.mbuf + (size_t)t * a.Bp * a.npadp +
+                         ((((size_t)(row >> 4) * (a.npadp >> 6) + member) * 16 + (row & 15)) << 6) + cellw;
+          *reinterpret_cast<uint32_t *>(mdst) = pk;
+        } else {
+          *reinterpret_cast<uint32_t *>(a.out + ((size_t)t * a.B + row) * a.Hpad + n0) = pk;
+          if (a.y) __builtin_nontemporal_store(pk, reinterpret_cast<uint32_t *>(a.y + ((size_t)t * a.B + row) * a.H + n0));
+        }
+      }
+    }
+    if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
+
+    // ---- projection (Sec. 3.2.8): tile pt of 32 outputs as two 16-wide halves, K = N split over the waves
+    if (proj) {
+      const int ksteps = a.npadp >> 6;
+      const int per_wave = (ksteps + 3) >> 2;
+      const RescaleHi pp = prm->p;
+      const int32_t zp_h = prm->zp_h;
+      for (int pt = 0; pt < my_ptiles; ++pt) {
+        const int ptile = member + pt * GS;
+        v4i pacc[2] = {v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}};
+        const int8_t *mbase = a.mbuf + (size_t)t * a.Bp * a.npadp + (((size_t)(row0 >> 4) * ksteps * 16 + r) << 6) + (q << 4);
+        const int8_t *wbase = WpL + ((size_t)pt * 32 + r) * WLS + (q << 4);
+        // all loads of the wave's k steps first (at most 8: N <= 2048); steps past the end re-read the
+        // last one against zero weights
+        int4 mv[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          int kk = wave * per_wave + (k < per_wave ? k : per_wave - 1);
+          kk = kk < ksteps ? kk : ksteps - 1;
+          mv[k] = *reinterpret_cast<const int4 *>(mbase + (size_t)kk * 1024);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          int kk = wave * per_wave + (k < per_wave ? k : per_wave - 1);
+          const bool real = k < per_wave && kk < ksteps;
+          kk = kk < ksteps ? kk : ksteps - 1;
+          const v4i mf = v4i{mv[k].x, mv[k].y, mv[k].z, mv[k].w};
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct) {
+            v4i wf = *reinterpret_cast<const v4i *>(wbase + (size_t)ct * 16 * WLS + kk * 64);
+            if (!real) wf = v4i{0, 0, 0, 0};
+            pacc[ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, mf, pacc[ct], 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) pred[((wave * 2 + ct) * 4 + v) * 64 + lane] = pacc[ct][v];
+        __syncthreads();
+        if (tid < 128) {
+          const int ct = wave;  // threads 0..127: waves 0 and 1
+          const int p0 = ptile * 32 + ct * 16 + 4 * q;
+          uint32_t pk = 0;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int32_t s = pred[((0 * 2 + ct) * 4 + v) * 64 + lane] + pred[((1 * 2 + ct) * 4 + v) * 64 + lane] +
+                              pred[((2 * 2 + ct) * 4 + v) * 64 + lane] + pred[((3 * 2 + ct) * 4 + v) * 64 + lane] +
+                              (pt == 0 ? bpr[v] : a.bp2[p0 + v]);
+            const int32_t hq = sat8(rescale_sat16_pre(s, pp) + zp_h);
+            pk |= (uint32_t)(hq & 0xFF) << (8 * v);
+          }
+          if (row < a.B && p0 < a.H) {
+            int8_t *od = a.out + ((size_t)t * a.B + row) * a.Hpad + p0;
+            if (p0 + 3 < a.H) {
+              *reinterpret_cast<uint32_t *>(od) = pk;
+            } else {
+              for (int c = 0; c < 4 && p0 + c < a.H; ++c) od[c] = (int8_t)(pk >> (8 * c));
+            }
+            if (a.y) {
+              int8_t *yd = a.y + ((size_t)t * a.B + row) * a.H + p0;
+              for (int c = 0; c < 4 && p0 + c < a.H; ++c) yd[c] = (int8_t)(pk >> (8 * c));
+            }
+          }
+        }
+        __syncthreads();
+      }
+      if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, my_ptiles == 0 ? a.idle_sleep : 0,
+                      my_ptiles == 0 ? a.idle_poll_sleep : a.poll_sleep, flag))
+        return;
+    }
+  }
+
+  placement_check();
+  if (a.c_out && row < a.B && n0 < a.N) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) a.c_out[(size_t)row * a.N + n0 + c] = (int16_t)creg[c];
+  }
+}
+
+}  // namespace lstm_int

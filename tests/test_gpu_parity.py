@@ -316,3 +316,40 @@ def test_maximum_sizes(orc):
     run_and_compare(orc, layers, x, "ln4096", trace=True)
     layers, x = wl.make_custom([32768], 16, 16, 0, 3, 2, seed=9, weight_param=0.01)
     run_and_compare(orc, layers, x, "depth32768", trace=True)
+
+
+@pytest.mark.parametrize("case", [
+    # (inputs, N, H, flags, B, T, rows)
+    ([72, 200], 200, 200, wl.LAYER_NORM, 37, 6, None),                      # 4 workgroups x 3 groups, ragged rows
+    ([72, 136], 200, 136, wl.LAYER_NORM | wl.PROJECTION, 70, 5, None),      # 5 projection tiles over 4 workgroups
+    ([40], 64, 64, wl.LAYER_NORM, 1, 7, None),                              # one workgroup, one row
+    ([64], 520, 520, wl.LAYER_NORM, 128, 3, [0, 15, 16, 100, 127]),         # k depth 10 without a projection
+    ([64], 1024, 1024, wl.LAYER_NORM, 48, 3, [0, 17, 47]),                  # k depth 16
+    ([640, 640], 2048, 640, wl.LAYER_NORM | wl.PROJECTION, 120, 4, [0, 17, 50, 119]),  # the C4 layer, 8 groups of 32
+])
+def test_rows16_kernel(orc, case):
+    """Option "rows16" (on by default): batches of up to 16 * 8 * (32 / workgroups
+    per group) rows take the recurrent kernel that works on groups of 16 rows."""
+    _rows16(orc, case, 1)
+
+
+@pytest.mark.parametrize("case", [
+    ([72, 200], 200, 200, wl.LAYER_NORM, 37, 6, None),
+    ([72, 136], 200, 136, wl.LAYER_NORM | wl.PROJECTION, 70, 5, None),
+])
+def test_rows16_off(orc, case):
+    """The same small batches on the kernel with groups of 32 rows."""
+    _rows16(orc, case, 0)
+
+
+def _rows16(orc, case, rows16):
+    import torch
+
+    inputs, N, H, flags, B, T, rows = case
+    print(f"rows16={rows16} N={N} H={H} flags={flags} B={B} T={T}", flush=True)
+    layers, x = wl.make_custom(inputs, N, H, flags, B, T, seed=N + B, weight_param=0.05 if N < 1024 else 0.03)
+    lib_model, y = run_and_compare(orc, layers, x, f"rows16_{N}_{B}", trace=False, rows=rows, options={"rows16": rows16})
+    lib_model.profile_begin()
+    lib_model.forward(torch.zeros((T, B, inputs[0]), dtype=torch.int8, device="cuda"))
+    prof = lib_model.profile_end()
+    assert prof["recurrent"]["launches"] == len(inputs) and prof["cell"]["launches"] == 0, prof
