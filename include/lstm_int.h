@@ -206,9 +206,8 @@ int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
  *               otherwise one launch per operation and step;
  *           1 = always one launch per operation and step;
  *           2 = same as 0.
- *   "rows16": 1 (default) = layers with layer norm and neither CIFG nor
- *           peephole connections run batches of up to 16 * 8 * (32 / ceil(N / 64))
- *           rows in a variant of the persistent kernel that works on groups of
+ *   "rows16": 1 (default) = batches of up to 16 * 8 * (32 / ceil(N / 64)) rows
+ *           run in a variant of the persistent kernel that works on groups of
  *           16 rows (more compute units busy, half the arithmetic per
  *           workgroup and step); 0 = always groups of 32 or 64 rows.
  *   "cooperative_launch": the persistent kernel needs all its workgroups (one

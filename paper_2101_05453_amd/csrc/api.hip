@@ -644,8 +644,8 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
             launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), sync_bytes(ra.groups) / 2, 0);
           }
           Timed t(m->prof, s, LSTM_INT_K_RECURRENT);
-          if ((use16 ? launch_rec16(s, ra, m->cooperative != 0) : launch_rec(s, ra, m->cooperative != 0)) != hipSuccess)
-            return LSTM_INT_E_DEVICE;
+          const bool coop = m->cooperative != 0;
+          if ((use16 ? launch_rec16(s, ra, coop) : launch_rec(s, ra, coop)) != hipSuccess) return LSTM_INT_E_DEVICE;
         }
       }
       {

@@ -106,8 +106,8 @@ hipError_t launch_rec(hipStream_t s, const RecArgs &a, bool cooperative);
 // One-time per process: raises the kernels' dynamic LDS limits.
 hipError_t rec_init();
 
-// The same step for groups of 16 batch rows (rec16_kernel.inc.h): layer norm without CIFG and peephole
-// connections, batches of up to 16 * 8 * (32 / GS) rows in one launch.  mbuf is
+// The same step for groups of 16 batch rows (rec16_kernel.inc.h): batches of up to 16 * 8 * (32 / GS) rows in
+// one launch.  mbuf is
 // [T][Bp / 16][npadp / 64][16 rows][64 cells] here.
 bool rec16_supported(int N, int H, int flags, int B, int *ks16, int *groups);
 size_t rec16_lds_bytes(const RecArgs &a);

@@ -1,20 +1,24 @@
-// The 16-row recurrent kernel: instantiations for h rows up to 256, 640 and 1024 bytes, and its launch.
-#include "rec16_kernel.inc.h"
+// The 16-row recurrent kernel: host side (the instantiations are in rec16_inst_4/10/16.hip).
+#include "persistent.h"
+
+#include "lstm_int_math.h"
 
 namespace lstm_int {
 
 static const int kKS16[] = {4, 10, 16};
 
-static rec_fn pick16(int ks16) {
-  if (ks16 == 4) return rec16_kernel<4>;
-  if (ks16 == 10) return rec16_kernel<10>;
-  if (ks16 == 16) return rec16_kernel<16>;
+typedef void (*rec_fn)(RecArgs);
+rec_fn rec16_pick_4(int fl);   // rec16_inst_4.hip
+rec_fn rec16_pick_10(int fl);  // rec16_inst_10.hip
+rec_fn rec16_pick_16(int fl);  // rec16_inst_16.hip
+static rec_fn pick16(int ks16, int fl) {
+  if (ks16 == 4) return rec16_pick_4(fl);
+  if (ks16 == 10) return rec16_pick_10(fl);
+  if (ks16 == 16) return rec16_pick_16(fl);
   return nullptr;
 }
 
 bool rec16_supported(int N, int H, int flags, int B, int *ks16, int *groups) {
-  // layer norm without CIFG and peephole connections; the projection is optional
-  if ((flags & 7) != 4) return false;
   if (N % 8 != 0 || N > 2048 || B < 1) return false;
   if (!(flags & 8) && H != N) return false;
   const int GS = (N + 63) / 64;
@@ -36,8 +40,8 @@ size_t rec16_lds_bytes(const RecArgs &a) {
   const bool proj = a.flags & 8;
   size_t tile = (((size_t)16 * (a.ks16 * 64 + 16) + 1023) / 1024 + 1) * 1024;
   if (proj && tile < 4 * 2 * 4 * 64 * 4) tile = 4 * 2 * 4 * 64 * 4;
-  size_t n = tile + (size_t)4 * items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 4 +
-             sizeof(PrmLds) + 16;
+  size_t n = tile + (size_t)4 * items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 4 + 4 * 64 * 2 +
+             256 /* PrmLds */ + 16;
   n += (a.tanhc_blob != a.tanh_blob ? 3 : 2) * (size_t)kLutBlobBytes;
   if (proj) {
     const int per_cu = (a.ptiles + a.GS - 1) / a.GS;
@@ -47,17 +51,18 @@ size_t rec16_lds_bytes(const RecArgs &a) {
 }
 
 hipError_t rec16_init() {
-  for (int ks : kKS16) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick16(ks)),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-  }
+  for (int ks : kKS16)
+    for (int fl = 0; fl < 8; ++fl) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick16(ks, fl)),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) return e;
+    }
   return hipSuccess;
 }
 
 hipError_t launch_rec16(hipStream_t s, const RecArgs &a, bool cooperative) {
-  rec_fn fn = pick16(a.ks16);
-  if (!fn || (a.flags & 7) != 4 || !a.R2h) return hipErrorInvalidValue;
+  rec_fn fn = pick16(a.ks16, a.flags & 7);
+  if (!fn || !a.R2h) return hipErrorInvalidValue;
   const int slots = a.GS * ((a.groups + 7) / 8);
   RecArgs args = a;
   void *params[] = {&args};

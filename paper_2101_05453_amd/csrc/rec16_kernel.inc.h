@@ -1,8 +1,8 @@
 // Persistent recurrent kernel for small batches: groups of 16 batch rows on
 // the 16x16x64 int8 MFMA (rec_kernel.inc.h has the design; this is the same
 // step with half the rows per workgroup, so that 128 rows already fill the
-// chip and a workgroup's arithmetic per step is half as long).  Layer norm on,
-// no CIFG, no peephole; the projection is a runtime flag.
+// chip and a workgroup's arithmetic per step is half as long).  FL: bit 0 CIFG,
+// bit 1 peephole, bit 2 layer norm; the projection is a runtime flag.
 //
 // Lane (r = lane % 16, q = lane / 16) of wave w owns batch row r of the group
 // and cells 16 w + 4 q + c, c = 0..3, of the workgroup's 64, all four gates:
@@ -16,12 +16,14 @@
 
 namespace lstm_int {
 
-template <int KS16>
+template <int KS16, int FL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void rec16_kernel(RecArgs a) {
+  constexpr bool cifg = FL & 1, ph = FL & 2, ln = FL & 4;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, q = lane >> 4;
   const bool proj = a.flags & 8;
+  constexpr int g_first = cifg ? 1 : 0;
   const int GS = a.GS;
 
   // placement, as in rec_kernel
@@ -72,6 +74,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   double *LdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;
   double *bdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;
   int32_t *bhL = reinterpret_cast<int32_t *>(p);         p += 4 * 64 * 4;
+  int16_t *PqL = reinterpret_cast<int16_t *>(p);         p += 4 * 64 * 2;  // 3 used
   PrmLds *prm = reinterpret_cast<PrmLds *>(p);           p += sizeof(PrmLds);
   int *flag = reinterpret_cast<int *>(p);                p += 16;
   const bool share_tanh = a.tanhc_blob == a.tanh_blob;
@@ -107,9 +110,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     LdL[tid] = ln_weight_scaled(a.Lq4[idx]);
     bdL[tid] = ln_bias_scaled(a.qb4[idx]);
     bhL[tid] = a.bh4[idx];
+    PqL[tid] = (ph && g < 3) ? a.Pq3[idx] : 0;
   }
   if (tid < 4) {
     prm->h[tid] = rescale_hi_prepare(a.Mh[tid], a.rh[tid]);
+    prm->c[tid] = rescale_hi_prepare(tid < 3 && ph ? a.Mc[tid] : 0, tid < 3 && ph ? a.rc[tid] : 33);
     prm->ln[tid] = rescale_hi_prepare(a.Mln[tid], a.rln[tid]);
   }
   if (tid == 0) {
@@ -178,8 +183,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   unsigned epoch = 0;
   unsigned *counter = a.counters + group * 64;
-  u64 *accS = a.acc + (size_t)group * 4 * 256;  // [S1|S2][item], item < 64 (the first round's words)
-  int64_t prevS[2] = {0, 0};
+  u64 *accS = a.acc + (size_t)group * 4 * 256;  // [round][S1|S2][item], item < 64
+  int64_t prevS[2][2] = {{0, 0}, {0, 0}};       // this thread's item, per round: S1, S2
   const double inv_n = 1.0 / (double)a.N;
   const bool pre_ln = a.rln[0] < 33 || a.rln[1] < 33 || a.rln[2] < 33 || a.rln[3] < 33;
   const bool pre_m = a.rm < 33;
@@ -231,7 +236,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     }
 
-    // ---- gate sums (Sec. 3.2.5) and layer-norm partial statistics
+    // ---- gate sums (Secs. 3.2.4/3.2.5) and layer-norm partial statistics.
+    // With a peephole the o gate keeps tx + th here and is finished after c^t.
+    constexpr int32_t glo = ln ? -32767 : -32768;  // layer norm takes symmetric gate sums
     int32_t gs[4][4];  // [gate][cell]
     auto gate_sums = [&](auto pre_tag) {
       constexpr int PRE = decltype(pre_tag)::value;
@@ -246,15 +253,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           const int32_t th = rescale_sat16_pre<PRE>(acc[c][g], pg);
           const int32_t w = txw[idx >> 1];
           const int32_t tx = (idx & 1) ? (w >> 16) : (int32_t)(int16_t)(w & 0xFFFF);
-          const int32_t v = clamp_i32(tx + th, -32767, 32767);
+          int32_t v = tx + th;
+          if (ph && g < 2) v += rescale_sat16_pre((int32_t)PqL[g * 64 + cellw + c] * creg[c], prm->c[g]);
+          if (!(ph && g == 3)) v = clamp_i32(v, glo, 32767);
           gs[g][c] = v;
           s1 += v;
           s2 += (uint32_t)v * (uint32_t)v;
         }
-        int64_t pk = ((int64_t)(u64)s2 << 24) + s1;
-        pk += __shfl_xor(pk, 16, 64);
-        pk += __shfl_xor(pk, 32, 64);
-        if (q == 0) red[(size_t)wave * items + g * 16 + r] = (u64)pk;
+        if (ln && !(ph && g == 3)) {
+          int64_t pk = ((int64_t)(u64)s2 << 24) + s1;
+          pk += __shfl_xor(pk, 16, 64);
+          pk += __shfl_xor(pk, 32, 64);
+          if (q == 0) red[(size_t)wave * items + g * 16 + r] = (u64)pk;
+        }
       }
     };
     if (a.pre_h == 0)
@@ -265,71 +276,101 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       gate_sums(std::integral_constant<int, 2>{});
 
     // statistics over the group's workgroups: as in rec_kernel (words that are never reset, the top
-    // byte counts the adds)
-    __syncthreads();
-    if (tid < items) {
-      const int64_t pk = (int64_t)(red[tid] + red[items + tid] + red[2 * items + tid] + red[3 * items + tid]);
-      const int64_t v1 = ((pk + (1 << 23)) & 0xFFFFFF) - (1 << 23);
-      const int64_t v2 = (pk - v1) >> 24;
-      __hip_atomic_fetch_add(&accS[tid], ((u64)1 << 56) + (u64)(v1 + (1 << 22)), __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_fetch_add(&accS[256 + tid], ((u64)1 << 56) + (u64)v2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const u64 expect = (u64)(((unsigned)GS * (unsigned)(t + 1)) & 0xFFu);
-      u64 c1, c2;
-      int budget = a.spin_limit;
-      for (int i = 0; i < a.stats_first_sleep; ++i) __builtin_amdgcn_s_sleep(1);
-      for (;;) {
-        c1 = __hip_atomic_load(&accS[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        c2 = __hip_atomic_load(&accS[256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((c1 >> 56) == expect && (c2 >> 56) == expect) break;
-        if (--budget <= 0 || __hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-          __hip_atomic_store(a.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          *flag = 0;
-          break;
+    // byte counts the adds); item = 16 gate + row
+    auto publish_stats = [&](int round, int g_lo, int g_hi) {
+      __syncthreads();
+      if (tid < items) {
+        const int g = tid >> 4;
+        if (g >= g_lo && g <= g_hi) {
+          const int64_t pk = (int64_t)(red[tid] + red[items + tid] + red[2 * items + tid] + red[3 * items + tid]);
+          const int64_t v1 = ((pk + (1 << 23)) & 0xFFFFFF) - (1 << 23);
+          const int64_t v2 = (pk - v1) >> 24;
+          __hip_atomic_fetch_add(&accS[(round * 2 + 0) * 256 + tid], ((u64)1 << 56) + (u64)(v1 + (1 << 22)),
+                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(&accS[(round * 2 + 1) * 256 + tid], ((u64)1 << 56) + (u64)v2, __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
         }
-        for (int i = 0; i < a.stats_sleep; ++i) __builtin_amdgcn_s_sleep(1);
       }
-      c1 &= kValMask;
-      c2 &= kValMask;
-      const int64_t S1 = (int64_t)((c1 - (u64)prevS[0]) & kValMask) - (int64_t)GS * (1 << 22);
-      const int64_t S2 = (int64_t)((c2 - (u64)prevS[1]) & kValMask);
-      prevS[0] = (int64_t)c1;
-      prevS[1] = (int64_t)c2;
-      lnrow[tid] = ln_row2(ln_row(S1, S2, a.N, inv_n));
+    };
+    // false: a wait gave up (status word raised), every thread leaves the kernel
+    auto collect_stats = [&](int round, int g_lo, int g_hi) -> bool {
+      if (tid < items) {
+        const int g = tid >> 4;
+        if (g >= g_lo && g <= g_hi) {
+          const u64 expect = (u64)(((unsigned)GS * (unsigned)(t + 1)) & 0xFFu);
+          u64 c1, c2;
+          int budget = a.spin_limit;
+          for (int i = 0; i < a.stats_first_sleep; ++i) __builtin_amdgcn_s_sleep(1);
+          for (;;) {
+            c1 = __hip_atomic_load(&accS[(round * 2 + 0) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c2 = __hip_atomic_load(&accS[(round * 2 + 1) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((c1 >> 56) == expect && (c2 >> 56) == expect) break;
+            if (--budget <= 0 || __hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+              __hip_atomic_store(a.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              *flag = 0;
+              break;
+            }
+            for (int i = 0; i < a.stats_sleep; ++i) __builtin_amdgcn_s_sleep(1);
+          }
+          c1 &= kValMask;
+          c2 &= kValMask;
+          const int64_t S1 = (int64_t)((c1 - (u64)prevS[round][0]) & kValMask) - (int64_t)GS * (1 << 22);
+          const int64_t S2 = (int64_t)((c2 - (u64)prevS[round][1]) & kValMask);
+          prevS[round][0] = (int64_t)c1;
+          prevS[round][1] = (int64_t)c2;
+          lnrow[tid] = ln_row2(ln_row(S1, S2, a.N, inv_n));
+        }
+      }
+      __syncthreads();
+      return *flag != 0;
+    };
+    if (ln) {
+      publish_stats(0, g_first, ph ? 2 : 3);
+      if (!collect_stats(0, g_first, ph ? 2 : 3)) return;
     }
-    __syncthreads();
-    if (*flag == 0) return;
 
-    // ---- layer norm, sigma/tanh, cell update (Secs. 3.2.6, 3.2.1, 3.2.7); LDS reads in batches
-    int32_t xv[4][4], tv[4][4];
-    {
-      LnRow2 lr[4];
+    // ---- layer norm, sigma/tanh, cell update (Secs. 3.2.6, 3.2.1, 3.2.9, 3.2.7); LDS reads in batches
+    // gates of `gmask` (bit g): gate sums -> layer norm -> xv[g][c]
+    auto normalize = [&](int gmask, int32_t (&xv)[4][4]) {
+      if (ln) {
+        LnRow2 lr[4];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) lr[g] = lnrow[g * 16 + r];
+        for (int g = 0; g < 4; ++g)
+          if (gmask >> g & 1) lr[g] = lnrow[g * 16 + r];
 #pragma unroll
-      for (int gp = 0; gp < 4; gp += 2) {
-        double wL[2][4], wb[2][4];
-        RescaleHi pl[2];
+        for (int gp = 0; gp < 4; gp += 2) {
+          if (!(gmask >> gp & 3)) continue;
+          double wL[2][4], wb[2][4];
+          RescaleHi pl[2];
 #pragma unroll
-        for (int g = gp; g < gp + 2; ++g) {
-          pl[g - gp] = prm->ln[g];
+          for (int g = gp; g < gp + 2; ++g)
+            if (gmask >> g & 1) {
+              pl[g - gp] = prm->ln[g];
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            wL[g - gp][c] = LdL[g * 64 + cellw + c];
-            wb[g - gp][c] = bdL[g * 64 + cellw + c];
-          }
+              for (int c = 0; c < 4; ++c) {
+                wL[g - gp][c] = LdL[g * 64 + cellw + c];
+                wb[g - gp][c] = bdL[g * 64 + cellw + c];
+              }
+            }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int g = gp; g < gp + 2; ++g)
+            if (gmask >> g & 1)
+#pragma unroll
+              for (int c = 0; c < 4; ++c) {
+                int32_t v = ln_second_stage(gs[g][c], lr[g], wL[g - gp][c], wb[g - gp][c]);
+                if (pre_ln) v = rescale_preshift(v, pl[g - gp]);
+                xv[g][c] = rescale_sat16_pre<0>(v, pl[g - gp]);
+              }
         }
-        __builtin_amdgcn_sched_barrier(0);
+      } else {
 #pragma unroll
-        for (int g = gp; g < gp + 2; ++g)
+        for (int g = 0; g < 4; ++g)
+          if (gmask >> g & 1)
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            int32_t v = ln_second_stage(gs[g][c], lr[g], wL[g - gp][c], wb[g - gp][c]);
-            if (pre_ln) v = rescale_preshift(v, pl[g - gp]);
-            xv[g][c] = rescale_sat16_pre<0>(v, pl[g - gp]);
-          }
+            for (int c = 0; c < 4; ++c) xv[g][c] = gs[g][c];
       }
-    }
+    };
     auto lookup = [&](int gmask, const int32_t (&x)[4][4], const uint8_t *const (&blob)[4], const int (&shf)[4],
                       const uint16_t *const (&full)[4], int32_t (&out)[4][4]) {
       int32_t mag[4][4];
@@ -361,32 +402,67 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
               if (mag[g][c] >= kLutDomain) out[g][c] = full[g][mag[g][c]];
       }
     };
+    constexpr int gates_now = (cifg ? 0 : 1) | 2 | 4 | (ph ? 0 : 8);  // with a peephole the o gate waits for c^t
+    int32_t xv[4][4], tv[4][4];
+    normalize(gates_now, xv);
     {
       const uint8_t *const gate_blob[4] = {lutS, lutS, lutT, lutS};
       const int gate_sh[4] = {sh_sig, sh_sig, sh_tanh, sh_sig};
       const uint16_t *const gate_full[4] = {a.sig_tab, a.sig_tab, a.tanh_tab, a.sig_tab};
-      lookup(15, xv, gate_blob, gate_sh, gate_full, tv);
+      lookup(gates_now, xv, gate_blob, gate_sh, gate_full, tv);
     }
     const int32_t m_c = prm->m_c;
     int32_t xo[4];
-    int32_t cx[4][4];  // slot 0: the new cell state, for its tanh
+    int32_t cx[4][4];  // slot 0: the new cell state, for its tanh; slot 3: the o gate with a peephole
+    {
+      int32_t s1 = 0;
+      uint32_t s2 = 0;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int32_t ig = mirror_sigmoid(xv[0][c], tv[0][c]);
-      const int32_t fg = mirror_sigmoid(xv[1][c], tv[1][c]);
-      const int32_t zg = mirror_tanh(xv[2][c], tv[2][c]);
-      xo[c] = mirror_sigmoid(xv[3][c], tv[3][c]);
-      creg[c] = cell_update32(ig, zg, fg, creg[c], m_c);
-      cx[0][c] = creg[c];
+      for (int c = 0; c < 4; ++c) {
+        const int32_t fg = mirror_sigmoid(xv[1][c], tv[1][c]);
+        const int32_t ig = cifg ? cifg_input_gate(fg) : mirror_sigmoid(xv[0][c], tv[0][c]);
+        const int32_t zg = mirror_tanh(xv[2][c], tv[2][c]);
+        xo[c] = ph ? 0 : mirror_sigmoid(xv[3][c], tv[3][c]);
+        creg[c] = cell_update32(ig, zg, fg, creg[c], m_c);
+        cx[0][c] = creg[c];
+        if (ph) {  // finish the o gate sum with P_o . c^t (eq. 5)
+          int32_t v = gs[3][c] + rescale_sat16_pre((int32_t)PqL[2 * 64 + cellw + c] * creg[c], prm->c[2]);
+          v = clamp_i32(v, glo, 32767);
+          gs[3][c] = v;
+          s1 += v;
+          s2 += (uint32_t)v * (uint32_t)v;
+        }
+      }
+      if (ph && ln) {
+        int64_t pk = ((int64_t)(u64)s2 << 24) + s1;
+        pk += __shfl_xor(pk, 16, 64);
+        pk += __shfl_xor(pk, 32, 64);
+        if (q == 0) red[(size_t)wave * items + 3 * 16 + r] = (u64)pk;
+      }
+    }
+    if (ph && ln) {
+      publish_stats(1, 3, 3);
+      if (!collect_stats(1, 3, 3)) return;
     }
 
-    // ---- hidden state (Sec. 3.2.7)
+    // ---- hidden state (Sec. 3.2.7): tanh of the new cell state in its own format (Sec. 3.2.2), and
+    // with a peephole the layer norm and sigma of the o gate
     int32_t tcv[4][4];
     {
-      const uint8_t *const hid_blob[4] = {lutC, lutC, lutC, lutC};
-      const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_tanhc, sh_tanhc};
-      const uint16_t *const hid_full[4] = {a.tanhc_tab, a.tanhc_tab, a.tanhc_tab, a.tanhc_tab};
-      lookup(1, cx, hid_blob, hid_sh, hid_full, tcv);
+      if (ph) {
+        int32_t ov[4][4];
+        normalize(8, ov);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) cx[3][c] = ov[3][c];
+      }
+      const uint8_t *const hid_blob[4] = {lutC, lutC, lutC, lutS};
+      const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_tanhc, sh_sig};
+      const uint16_t *const hid_full[4] = {a.tanhc_tab, a.tanhc_tab, a.tanhc_tab, a.sig_tab};
+      lookup(ph ? 9 : 1, cx, hid_blob, hid_sh, hid_full, tcv);
+      if (ph) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) xo[c] = mirror_sigmoid(cx[3][c], tcv[3][c]);
+      }
     }
     {
       const RescaleHi pm = prm->m;
@@ -489,6 +565,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   if (a.c_out && row < a.B && n0 < a.N) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) a.c_out[(size_t)row * a.N + n0 + c] = (int16_t)creg[c];
+  }
+}
+
+// kernel for (flags & 7) at k depth KS16
+template <int KS16>
+rec_fn rec16_pick_ks(int fl) {
+  switch (fl & 7) {
+    case 0: return rec16_kernel<KS16, 0>;
+    case 1: return rec16_kernel<KS16, 1>;
+    case 2: return rec16_kernel<KS16, 2>;
+    case 3: return rec16_kernel<KS16, 3>;
+    case 4: return rec16_kernel<KS16, 4>;
+    case 5: return rec16_kernel<KS16, 5>;
+    case 6: return rec16_kernel<KS16, 6>;
+    default: return rec16_kernel<KS16, 7>;
   }
 }
 

@@ -333,13 +333,21 @@ def test_rows16_kernel(orc, case):
     _rows16(orc, case, 1)
 
 
-@pytest.mark.parametrize("case", [
-    ([72, 200], 200, 200, wl.LAYER_NORM, 37, 6, None),
-    ([72, 136], 200, 136, wl.LAYER_NORM | wl.PROJECTION, 70, 5, None),
-])
-def test_rows16_off(orc, case):
-    """The same small batches on the kernel with groups of 32 rows."""
-    _rows16(orc, case, 0)
+@pytest.mark.parametrize("rows16", [1, 0])
+@pytest.mark.parametrize("flags", VARIANTS)
+def test_rows16_variants(orc, flags, rows16):
+    """Every variant on the persistent path at a small ragged batch, two layers:
+    on the 16-row kernel (default) and, with the option off, on the kernel
+    with groups of 32 rows."""
+    H = 136 if flags & wl.PROJECTION else 200
+    _rows16(orc, ([72, H], 200, H, flags, 37, 5, None), rows16)
+
+
+def test_rows16_c3_layer(orc):
+    """The C3 layer (peephole, layer norm, projection: two statistics rounds per
+    step) at B = 100 on the 16-row kernel."""
+    flags = wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION
+    _rows16(orc, ([640], 2048, 640, flags, 100, 4, [0, 15, 16, 63, 99]), 1)
 
 
 def _rows16(orc, case, rows16):
