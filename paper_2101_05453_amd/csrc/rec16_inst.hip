@@ -41,7 +41,7 @@ size_t rec16_lds_bytes(const RecArgs &a) {
   size_t tile = (((size_t)16 * (a.ks16 * 64 + 16) + 1023) / 1024 + 1) * 1024;
   if (proj && tile < 4 * 2 * 4 * 64 * 4) tile = 4 * 2 * 4 * 64 * 4;
   size_t n = tile + (size_t)4 * items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 4 + 4 * 64 * 2 +
-             256 /* PrmLds */ + 16;
+             256 /* PrmLds */ + 16 + 16 * 8;
   n += (a.tanhc_blob != a.tanh_blob ? 3 : 2) * (size_t)kLutBlobBytes;
   if (proj) {
     const int per_cu = (a.ptiles + a.GS - 1) / a.GS;

@@ -16,9 +16,22 @@
 
 namespace lstm_int {
 
+// 100 MHz wall clock ticks per phase, summed in LDS by thread 0 of workgroup 0
+#define TICK(i)                                                                           \
+  do {                                                                                    \
+    if (timing) {                                                                         \
+      asm volatile("" ::: "memory");                                                      \
+      const long long now = (long long)wall_clock64();                                    \
+      __hip_atomic_fetch_add(&tickL[i], (u64)(now - tick_last), __ATOMIC_RELAXED,         \
+                             __HIP_MEMORY_SCOPE_WORKGROUP);                               \
+      tick_last = now;                                                                    \
+    }                                                                                     \
+  } while (0)
+
 template <int KS16, int FL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void rec16_kernel(RecArgs a) {
   constexpr bool cifg = FL & 1, ph = FL & 2, ln = FL & 4;
+  const long long t_start = (long long)wall_clock64();
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, q = lane >> 4;
@@ -69,7 +82,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const size_t pred_bytes = proj ? 4 * 2 * 4 * 64 * 4 : 0;
     p += tile_bytes > pred_bytes ? tile_bytes : pred_bytes;
   }
-  u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)4 * items * 8;
+  u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)4 * items * 8;  // [item] sums (first 64 words)
   LnRow2 *lnrow = reinterpret_cast<LnRow2 *>(p);         p += (size_t)items * sizeof(LnRow2);
   double *LdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;
   double *bdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;
@@ -77,6 +90,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   int16_t *PqL = reinterpret_cast<int16_t *>(p);         p += 4 * 64 * 2;  // 3 used
   PrmLds *prm = reinterpret_cast<PrmLds *>(p);           p += sizeof(PrmLds);
   int *flag = reinterpret_cast<int *>(p);                p += 16;
+  u64 *tickL = reinterpret_cast<u64 *>(p);               p += 16 * 8;  // phase timers
   const bool share_tanh = a.tanhc_blob == a.tanh_blob;
   const uint8_t *lutS = p;                               p += kLutBlobBytes;
   const uint8_t *lutT = p;                               p += kLutBlobBytes;
@@ -179,6 +193,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     flag[0] = 1;
     flag[1] = 0;
   }
+  if (tid < 16) tickL[tid] = 0;
+  if (tid < items) red[tid] = 0;
   __syncthreads();
 
   unsigned epoch = 0;
@@ -190,8 +206,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const bool pre_m = a.rm < 33;
   constexpr u64 kValMask = ((u64)1 << 56) - 1;
 
+  // optional phase timing of workgroup 0 (diagnostics), phases numbered as in rec_kernel
+  long long tick_last = 0;
+  const bool timing = a.ticks && wg == 0 && tid == 0;
+  if (timing) {
+    tick_last = t_start;
+    __hip_atomic_store(&a.ticks[15], t_start, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  TICK(10);  // everything before the first step
+
+  // the two 16-byte W x pieces of this lane for step t, read in the layout of the 32-row kernel:
+  // cell tile of 8 = 2 wave + q / 2, lane there = row % 32 + 32 * (q % 2)
+  v4i txn0, txn1;
+  auto tx_request = [&](int t) {
+    size_t rb = ((size_t)t * a.Bp + row0) >> 5;
+    const size_t rbmax = ((size_t)a.T * a.Bp) >> 5;
+    rb = rb < rbmax ? rb : rbmax - 1;
+    const int4 *src = a.tx2 + ((rb * (size_t)(GS * 8) + member * 8 + wave * 2 + (q >> 1)) * 2) * 64 +
+                      ((row0 + r) & 31) + 32 * (q & 1);
+    // read once: streaming loads keep the W x terms from displacing the exchange buffers in L2
+    txn0 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src));
+    txn1 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src + 64));
+  };
+  tx_request(0);
+
   for (int t = 0; t < a.T; ++t) {
-    // ---- h^{t-1} rows of the group -> LDS; W x terms of this step -> registers
+    // ---- h^{t-1} rows of the group -> LDS
     {
       const int8_t *hp = t == 0 ? a.h0 : a.out + (size_t)(t - 1) * a.B * a.Hpad;
 #pragma unroll
@@ -203,19 +243,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __syncthreads();
-    int32_t txw[8];
-    {
-      size_t rb = ((size_t)t * a.Bp + row0) >> 5;
-      const size_t rbmax = ((size_t)a.T * a.Bp) >> 5;
-      rb = rb < rbmax ? rb : rbmax - 1;
-      // cell tile of 8: 2 w + q / 2; lane of the 32-row layout: row % 32 + 32 * (q % 2)
-      const int4 *src = a.tx2 + ((rb * (size_t)(GS * 8) + member * 8 + wave * 2 + (q >> 1)) * 2) * 64 +
-                        ((row0 + r) & 31) + 32 * (q & 1);
-      const v4i t0 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src));
-      const v4i t1 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src + 64));
-      txw[0] = t0.x; txw[1] = t0.y; txw[2] = t0.z; txw[3] = t0.w;
-      txw[4] = t1.x; txw[5] = t1.y; txw[6] = t1.z; txw[7] = t1.w;
-    }
+    // the W x terms of this step were requested one step ahead (they come from HBM)
+    const int32_t txw[8] = {txn0.x, txn0.y, txn0.z, txn0.w, txn1.x, txn1.y, txn1.z, txn1.w};
+    TICK(0);
 
     // ---- R h on the MFMA: acc[j][gate] for cell 4 q + j; each tile's k loop runs to its end
     // before the next tile starts (dependent 16x16x64 MFMAs issue back to back, rotating
@@ -235,6 +265,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           acc[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(Wf[j][ks], hf[ks], acc[j], 0, 0, 0);
       }
     }
+
+    TICK(1);
 
     // ---- gate sums (Secs. 3.2.4/3.2.5) and layer-norm partial statistics.
     // With a peephole the o gate keeps tx + th here and is finished after c^t.
@@ -261,10 +293,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           s2 += (uint32_t)v * (uint32_t)v;
         }
         if (ln && !(ph && g == 3)) {
-          int64_t pk = ((int64_t)(u64)s2 << 24) + s1;
-          pk += __shfl_xor(pk, 16, 64);
-          pk += __shfl_xor(pk, 32, 64);
-          if (q == 0) red[(size_t)wave * items + g * 16 + r] = (u64)pk;
+          // the 16 lanes of a row (4 per wave) add into one LDS word: no cross-lane traffic, no wait
+          const int64_t pk = ((int64_t)(u64)s2 << 24) + s1;
+          __hip_atomic_fetch_add(&red[g * 16 + r], (u64)pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
       }
     };
@@ -274,6 +305,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       gate_sums(std::integral_constant<int, 1>{});
     else
       gate_sums(std::integral_constant<int, 2>{});
+    tx_request(t + 1);  // past the last step: the last block again, unused
 
     // statistics over the group's workgroups: as in rec_kernel (words that are never reset, the top
     // byte counts the adds); item = 16 gate + row
@@ -282,7 +314,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       if (tid < items) {
         const int g = tid >> 4;
         if (g >= g_lo && g <= g_hi) {
-          const int64_t pk = (int64_t)(red[tid] + red[items + tid] + red[2 * items + tid] + red[3 * items + tid]);
+          const int64_t pk = (int64_t)red[tid];
+          red[tid] = 0;  // the next adds to this word come after the next barrier
           const int64_t v1 = ((pk + (1 << 23)) & 0xFFFFFF) - (1 << 23);
           const int64_t v2 = (pk - v1) >> 24;
           __hip_atomic_fetch_add(&accS[(round * 2 + 0) * 256 + tid], ((u64)1 << 56) + (u64)(v1 + (1 << 22)),
@@ -324,9 +357,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       __syncthreads();
       return *flag != 0;
     };
+    TICK(2);
     if (ln) {
       publish_stats(0, g_first, ph ? 2 : 3);
+      TICK(3);
       if (!collect_stats(0, g_first, ph ? 2 : 3)) return;
+      TICK(4);
     }
 
     // ---- layer norm, sigma/tanh, cell update (Secs. 3.2.6, 3.2.1, 3.2.9, 3.2.7); LDS reads in batches
@@ -434,12 +470,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
       }
       if (ph && ln) {
-        int64_t pk = ((int64_t)(u64)s2 << 24) + s1;
-        pk += __shfl_xor(pk, 16, 64);
-        pk += __shfl_xor(pk, 32, 64);
-        if (q == 0) red[(size_t)wave * items + 3 * 16 + r] = (u64)pk;
+        const int64_t pk = ((int64_t)(u64)s2 << 24) + s1;
+        __hip_atomic_fetch_add(&red[3 * 16 + r], (u64)pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
     }
+    TICK(5);
     if (ph && ln) {
       publish_stats(1, 3, 3);
       if (!collect_stats(1, 3, 3)) return;
@@ -488,7 +523,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
       }
     }
+    TICK(6);
     if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
+    TICK(7);
 
     // ---- projection (Sec. 3.2.8): tile pt of 32 outputs as two 16-wide halves, K = N split over the waves
     if (proj) {
@@ -555,10 +592,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
         __syncthreads();
       }
+      TICK(8);
       if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, my_ptiles == 0 ? a.idle_sleep : 0,
                       my_ptiles == 0 ? a.idle_poll_sleep : a.poll_sleep, flag))
         return;
+      TICK(9);
     }
+  }
+  if (timing)
+    for (int i = 0; i < 11; ++i) a.ticks[i] += (long long)tickL[i];
+  if (a.ticks && tid == 0) {
+    // spread of the workgroups' lifetimes against workgroup 0's start (maxima over all launches)
+    const long long t0 = __hip_atomic_load(&a.ticks[15], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const long long t_end = (long long)wall_clock64();
+    if (wg == 0) a.ticks[11] += t_end - t_start;
+    __hip_atomic_fetch_max(&a.ticks[12], t_start - t0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_max(&a.ticks[13], t_end - t0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_max(&a.ticks[14], t0 - t_start, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
   placement_check();
@@ -567,6 +617,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int c = 0; c < 4; ++c) a.c_out[(size_t)row * a.N + n0 + c] = (int16_t)creg[c];
   }
 }
+
+#undef TICK
 
 // kernel for (flags & 7) at k depth KS16
 template <int KS16>
