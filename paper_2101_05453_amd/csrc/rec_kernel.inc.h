@@ -276,6 +276,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
 
   if (tid < 16) tickL[tid] = 0;
+  if (tid < items) red[tid] = 0;
   if (tid == 0) {
     flag[0] = 1;
     flag[1] = 0;
@@ -420,11 +421,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
         if (ln) {
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            // 16 cells of this wave: the two lanes of a row (lane, lane ^ 32)
-            int64_t pk = ((int64_t)((u64)s2[g][0] + (u64)s2[g][1]) << 24) + s1[g];
-            pk += __shfl_xor(pk, 32, 64);
-            if (b2 == 0) red[(size_t)wave * items + (rt * 4 + g) * 32 + col] = (u64)pk;
+          for (int g = 0; g < (ph ? 3 : 4); ++g) {  // with a peephole the o gate follows after c^t
+            // the 8 lanes of a row (2 per wave) add into one LDS word: no cross-lane traffic, no wait
+            const int64_t pk = ((int64_t)((u64)s2[g][0] + (u64)s2[g][1]) << 24) + s1[g];
+            __hip_atomic_fetch_add(&red[(rt * 4 + g) * 32 + col], (u64)pk, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_WORKGROUP);
           }
         }
       }
@@ -449,7 +450,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       if (tid < items) {
         const int g = (tid >> 5) & 3;
         if (g >= g_lo && g <= g_hi) {
-          const int64_t pk = (int64_t)(red[tid] + red[items + tid] + red[2 * items + tid] + red[3 * items + tid]);
+          const int64_t pk = (int64_t)red[tid];
+          red[tid] = 0;  // the next adds to this word come after the next barrier
           const int64_t v1 = ((pk + (1 << 23)) & 0xFFFFFF) - (1 << 23);  // signed low 24 bits
           const int64_t v2 = (pk - v1) >> 24;
           __hip_atomic_fetch_add(&accS[(round * 2 + 0) * 256 + tid], ((u64)1 << 56) + (u64)(v1 + (1 << 22)),
@@ -641,9 +643,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           }
         }
       if (ph && ln) {
-        int64_t pk = (s2 << 24) + s1;
-        pk += __shfl_xor(pk, 32, 64);
-        if (b2 == 0) red[(size_t)wave * items + (rt * 4 + 3) * 32 + col] = (u64)pk;
+        const int64_t pk = (s2 << 24) + s1;
+        __hip_atomic_fetch_add(&red[(rt * 4 + 3) * 32 + col], (u64)pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
     }
     TICK(5);
