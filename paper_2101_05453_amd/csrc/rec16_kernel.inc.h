@@ -251,6 +251,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // before the next tile starts (dependent 16x16x64 MFMAs issue back to back, rotating
     // accumulators do not)
     v4i acc[4];
+    RescaleHi ph4[4];  // the R h rescale constants, read here so that the MFMAs cover the LDS round trip
+#pragma unroll
+    for (int g = 0; g < 4; ++g) ph4[g] = prm->h[g];
     {
       v4i hf[KS16];
       const int8_t *hbase = hT + (size_t)r * LS + (q << 4);
@@ -276,7 +279,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       constexpr int PRE = decltype(pre_tag)::value;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const RescaleHi pg = prm->h[g];
+        const RescaleHi pg = ph4[g];
         int32_t s1 = 0;
         uint32_t s2 = 0;  // four squares of 16-bit values fit 32 bits
 #pragma unroll
