@@ -182,7 +182,10 @@ size_t lstm_int_workspace_bytes(const lstm_int_model *model, int32_t T, int32_t 
  *   hip_stream a hipStream_t (NULL = the default stream)
  *   trace    NULL, or dumps of one layer
  * Allocates nothing, never synchronizes the host: all work is enqueued on
- * hip_stream and touches only y, the state buffers, workspace and trace.
+ * hip_stream and touches only y, the state buffers, workspace and trace; it
+ * launches kernels only (no memset or copy nodes), so a caller may capture it
+ * in a HIP graph once one call has run outside a capture (and while no
+ * profile is being recorded).
  * T = 0 or B = 0 is a no-op.  Calls sharing a model must not overlap in time
  * unless they use different workspaces and the same stream order.
  */

@@ -361,3 +361,49 @@ def _rows16(orc, case, rows16):
     lib_model.forward(torch.zeros((T, B, inputs[0]), dtype=torch.int8, device="cuda"))
     prof = lib_model.profile_end()
     assert prof["recurrent"]["launches"] == len(inputs) and prof["cell"]["launches"] == 0, prof
+
+
+def test_forward_captured_in_a_hip_graph(orc):
+    """forward allocates nothing, never synchronizes and launches only kernels, so
+    a caller can capture it in a HIP graph: one-step calls with carried state,
+    replayed with the program's own synchronization between the replays, give
+    what the same calls give when made directly (and what the oracle gives for
+    the whole sequence)."""
+    import torch
+
+    print("graph capture", flush=True)
+    flags = wl.LAYER_NORM | wl.PROJECTION
+    layers, x = wl.make_custom([72, 136], 200, 136, flags, 20, 6, seed=77, weight_param=0.08)
+    lib_model, orc_model, xq = prepare_both(orc, layers, x)
+    T, B, _ = xq.shape
+    dims = lib_model.dims()
+    want = orc.forward(orc_model, xq)
+
+    def fresh_state():
+        hs = torch.cat([torch.full((B * d[2],), lib_model.get_quant(l)["zp_h"], dtype=torch.int8)
+                        for l, d in enumerate(dims)]).cuda()
+        return hs, torch.zeros(sum(B * d[1] for d in dims), dtype=torch.int16).cuda()
+
+    ws = torch.empty(lib_model.workspace_bytes(1, B), dtype=torch.uint8, device="cuda")
+    xin = torch.from_numpy(np.ascontiguousarray(xq[:1])).cuda()
+    y = torch.empty((1, B, dims[-1][2]), dtype=torch.int8, device="cuda")
+    hs, cs = fresh_state()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # first call outside the capture (one-time initialisation of the library)
+        lib_model.forward(xin, y=y, workspace=ws, h_state=hs, c_state=cs)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lib_model.forward(xin, y=y, workspace=ws, h_state=hs, c_state=cs)
+    for rep in range(2):  # the whole sequence twice, from fresh state
+        h0, c0 = fresh_state()
+        hs.copy_(h0)
+        cs.copy_(c0)
+        for t in range(T):
+            xin.copy_(torch.from_numpy(np.ascontiguousarray(xq[t:t + 1])))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert_equal(f"graph.rep{rep}.y[{t}]", y.cpu().numpy()[0], want[t])
+    assert lib_model.device_status() == 0
