@@ -101,20 +101,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int sh_sig = a.sh_sig, sh_tanh = a.sh_tanh, sh_tanhc = a.sh_tanhc;
 
   // ---- one-time loads: R slice -> registers, per-cell parameters, tables and W_proj tiles -> LDS
+  // the loads into LDS go first: they need no registers and are in flight while the R slice arrives
+  {
+    auto dma = [&](const void *src, const void *dst) {
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                       (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    };
+    for (int c = wave; c < kLutBlobBytes / 1024; c += 4) {
+      dma(a.sig_blob + c * 1024 + lane * 16, lutS + c * 1024);
+      dma(a.tanh_blob + c * 1024 + lane * 16, lutT + c * 1024);
+      if (!share_tanh) dma(a.tanhc_blob + c * 1024 + lane * 16, lutC + c * 1024);
+    }
+    const int wp_rows = my_ptiles * 32;
+    const int wp_chunks = (wp_rows * WLS + 1023) >> 10;
+    for (int c = wave; c < wp_chunks; c += 4) {
+      const int o = c * 1024 + lane * 16;
+      const int rr = o / WLS, col_b = o - rr * WLS;
+      const int8_t *src = a.Wp2;
+      if (rr < wp_rows && col_b < a.npadp) {
+        const int pt = rr >> 5;
+        src = a.Wp2 + ((size_t)(member + pt * GS) * 32 + (rr & 31)) * a.npadp + col_b;
+      }
+      dma(src, WpL + c * 1024);
+    }
+  }
   v4i Wf[4][KS16];
   {
     const int4 *src = a.R2h + ((size_t)(member * 4 + wave) * 4) * KS16 * 64 + lane;
+    // all loads of the slice are issued before the first value is pinned (a pin waits for its load);
+    // at the deepest k the staging registers do not hold four tiles, so two at a time
+    constexpr int TB = KS16 <= 10 ? 4 : 2;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int4 w[KS16];
+    for (int j0 = 0; j0 < 4; j0 += TB) {
+      int4 w[TB][KS16];
 #pragma unroll
-      for (int ks = 0; ks < KS16; ++ks) w[ks] = src[(size_t)(j * KS16 + ks) * 64];
+      for (int j = 0; j < TB; ++j)
+#pragma unroll
+        for (int ks = 0; ks < KS16; ++ks) w[j][ks] = src[(size_t)((j0 + j) * KS16 + ks) * 64];
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int ks = 0; ks < KS16; ++ks) {
-        Wf[j][ks] = v4i{w[ks].x, w[ks].y, w[ks].z, w[ks].w};
-        asm volatile("" : "+a"(Wf[j][ks]));  // resident in accumulation registers for the whole launch
-      }
+      for (int j = 0; j < TB; ++j)
+#pragma unroll
+        for (int ks = 0; ks < KS16; ++ks) {
+          Wf[j0 + j][ks] = v4i{w[j][ks].x, w[j][ks].y, w[j][ks].z, w[j][ks].w};
+          asm volatile("" : "+a"(Wf[j0 + j][ks]));  // resident in accumulation registers for the whole launch
+        }
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -138,30 +169,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     prm->m_c = a.m_c; prm->glo = -32767;
   }
   for (int i = tid; i < 16 * LS / 16; i += 256) reinterpret_cast<int4 *>(hT)[i] = int4{0, 0, 0, 0};
-  {
-    auto dma = [&](const void *src, const void *dst) {
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                       (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-    };
-    for (int c = wave; c < kLutBlobBytes / 1024; c += 4) {
-      dma(a.sig_blob + c * 1024 + lane * 16, lutS + c * 1024);
-      dma(a.tanh_blob + c * 1024 + lane * 16, lutT + c * 1024);
-      if (!share_tanh) dma(a.tanhc_blob + c * 1024 + lane * 16, lutC + c * 1024);
-    }
-    const int wp_rows = my_ptiles * 32;
-    const int wp_chunks = (wp_rows * WLS + 1023) >> 10;
-    for (int c = wave; c < wp_chunks; c += 4) {
-      const int o = c * 1024 + lane * 16;
-      const int rr = o / WLS, col_b = o - rr * WLS;
-      const int8_t *src = a.Wp2;
-      if (rr < wp_rows && col_b < a.npadp) {
-        const int pt = rr >> 5;
-        src = a.Wp2 + ((size_t)(member + pt * GS) * 32 + (rr & 31)) * a.npadp + col_b;
-      }
-      dma(src, WpL + c * 1024);
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  }
 
   // cell state of this lane's 4 cells of its row, kept in registers
   const int row = row0 + r;
@@ -195,6 +202,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   if (tid < 16) tickL[tid] = 0;
   if (tid < items) red[tid] = 0;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // tables and W_proj tiles are in LDS
   __syncthreads();
 
   unsigned epoch = 0;
