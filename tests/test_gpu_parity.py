@@ -296,17 +296,20 @@ def test_empty_and_error_paths(orc):
     assert_equal("unaligned", y.cpu().numpy(), orc.forward(orc_model, xq))
 
 
-@pytest.mark.parametrize("T,flags,with_state", [(1 << 14, wl.LAYER_NORM, True), ((1 << 14) + 1, wl.LAYER_NORM, True),
-                                                ((1 << 14) + 1, wl.LAYER_NORM | wl.PROJECTION, False)])
-def test_longest_sequences(orc, T, flags, with_state):
+@pytest.mark.parametrize("T,flags,with_state,rows16", [
+    (1 << 14, wl.LAYER_NORM, True, 1), ((1 << 14) + 1, wl.LAYER_NORM, True, 1),
+    ((1 << 14) + 1, wl.LAYER_NORM | wl.PROJECTION, False, 1),
+    (1 << 14, wl.LAYER_NORM, True, 0), ((1 << 14) + 1, wl.LAYER_NORM | wl.PROJECTION, False, 0)])
+def test_longest_sequences(orc, T, flags, with_state, rows16):
     """2^14 steps is the most one launch of the persistent kernel takes (its
     layer-norm statistics words count up over the launch); one step more and
     the layer runs in two pieces, h and c carried from one to the next (c through
     the caller's state buffer, or through the workspace when there is none).  Two
-    workgroups per group, so the words are in use."""
-    print(f"T {T}", flush=True)
+    workgroups per group, so the words are in use.  On the 16-row kernel and,
+    with option "rows16" off, on the kernel with groups of 32 rows."""
+    print(f"T {T} rows16 {rows16}", flush=True)
     layers, x = wl.make_custom([16], 128, 64, flags, 3, T, seed=21)
-    run_and_compare(orc, layers, x, f"long{T}", trace=False, with_state=with_state)
+    run_and_compare(orc, layers, x, f"long{T}", trace=False, with_state=with_state, options={"rows16": rows16})
 
 
 def test_maximum_sizes(orc):
