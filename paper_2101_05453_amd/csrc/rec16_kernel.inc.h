@@ -486,29 +486,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     }
     TICK(5);
+    // ---- hidden state (Sec. 3.2.7): tanh of the new cell state in its own format (Sec. 3.2.2), and
+    // with a peephole the layer norm and sigma of the o gate; the tanh does not wait for the o gate's
+    // statistics, so it runs while they travel
+    int32_t tcv[4][4];
+    const uint8_t *const hid_blob[4] = {lutC, lutC, lutC, lutS};
+    const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_tanhc, sh_sig};
+    const uint16_t *const hid_full[4] = {a.tanhc_tab, a.tanhc_tab, a.tanhc_tab, a.sig_tab};
     if (ph && ln) {
       publish_stats(1, 3, 3);
+      lookup(1, cx, hid_blob, hid_sh, hid_full, tcv);
       if (!collect_stats(1, 3, 3)) return;
+    } else {
+      lookup(1, cx, hid_blob, hid_sh, hid_full, tcv);
     }
-
-    // ---- hidden state (Sec. 3.2.7): tanh of the new cell state in its own format (Sec. 3.2.2), and
-    // with a peephole the layer norm and sigma of the o gate
-    int32_t tcv[4][4];
-    {
-      if (ph) {
-        int32_t ov[4][4];
-        normalize(8, ov);
+    if (ph) {
+      int32_t ov[4][4];
+      normalize(8, ov);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) cx[3][c] = ov[3][c];
-      }
-      const uint8_t *const hid_blob[4] = {lutC, lutC, lutC, lutS};
-      const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_tanhc, sh_sig};
-      const uint16_t *const hid_full[4] = {a.tanhc_tab, a.tanhc_tab, a.tanhc_tab, a.sig_tab};
-      lookup(ph ? 9 : 1, cx, hid_blob, hid_sh, hid_full, tcv);
-      if (ph) {
+      for (int c = 0; c < 4; ++c) cx[3][c] = ov[3][c];
+      lookup(8, cx, hid_blob, hid_sh, hid_full, tcv);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) xo[c] = mirror_sigmoid(cx[3][c], tcv[3][c]);
-      }
+      for (int c = 0; c < 4; ++c) xo[c] = mirror_sigmoid(cx[3][c], tcv[3][c]);
     }
     {
       const RescaleHi pm = prm->m;
