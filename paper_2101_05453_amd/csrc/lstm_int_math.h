@@ -105,12 +105,20 @@ struct LnRow {
 // S2 * 2^20 can reach 2^62, too wide for the reciprocal division; with
 // S2 = a n + r (0 <= r < n) the quotient is a 2^20 + floor((r 2^20 + n/2)/n),
 // and both divisions have numerators below 2^44.
+// For n a power of two both floors are arithmetic right shifts (S2 * 2^20 < 2^62 for n <= 4096).
 LSTM_HD LnRow ln_row(int64_t S1, int64_t S2, int32_t n, double inv_n) {
   LnRow r;
-  const int64_t mean = floor_div_recip(S1 * 1024 + (n >> 1), n, inv_n);
-  const int64_t a = floor_div_recip(S2, n, inv_n);
-  const int64_t low = floor_div_recip(((S2 - a * n) << 20) + (n >> 1), n, inv_n);
-  int64_t var = (a << 20) + low - mean * mean;
+  int64_t mean, var;
+  if ((n & (n - 1)) == 0) {
+    const int sh = __builtin_ctz((unsigned)n);
+    mean = (S1 * 1024 + (n >> 1)) >> sh;
+    var = (((S2 << 20) + (n >> 1)) >> sh) - mean * mean;
+  } else {
+    mean = floor_div_recip(S1 * 1024 + (n >> 1), n, inv_n);
+    const int64_t a = floor_div_recip(S2, n, inv_n);
+    const int64_t low = floor_div_recip(((S2 - a * n) << 20) + (n >> 1), n, inv_n);
+    var = (a << 20) + low - mean * mean;
+  }
   if (var < 0) var = 0;
   r.mean = (int32_t)mean;
   r.sigma = (int32_t)isqrt_u52(var);
