@@ -81,12 +81,19 @@ LSTM_HD int64_t floor_div_recip(int64_t num, int32_t d, double inv_d) {
 
 // floor(sqrt(v)), 0 <= v < 2^52: the double root is within one of the
 // answer; the comparisons settle it exactly.
+// (r < 2^26, so r * r and v - r * r are exact in double: one fused
+// multiply-add gives the remainder, and (r + 1)^2 <= v iff v - r^2 >= 2 r + 1.)
 LSTM_HD int64_t isqrt_u52(int64_t v) {
   if (v <= 0) return 0;
-  int64_t r = (int64_t)sqrt((double)v);
-  while (r * r > v) --r;
-  while ((r + 1) * (r + 1) <= v) ++r;
-  return r;
+  const double dv = (double)v;
+  double r = floor(sqrt(dv));
+  const double rem = fma(-r, r, dv);
+  if (rem < 0.0) {
+    r -= 1.0;
+  } else if (rem >= 2.0 * r + 1.0) {
+    r += 1.0;
+  }
+  return (int64_t)r;
 }
 
 // ---------------------------------------------------------------------------

@@ -93,6 +93,8 @@ def test_isqrt(orc, hm):
     rnd = random.Random(1)
     vals = list(range(0, 5000)) + [rnd.randrange(0, 2**50) for _ in range(20000)]
     vals += [r * r + d for r in (2**24, 2**25 - 1, 33554431) for d in (-1, 0, 1)]
+    vals += [r * r + d for r in [rnd.randrange(1, 2**26) for _ in range(5000)] + [2**26 - 1] for d in (-1, 0, 1, 2)
+             if r * r + d < 2**52]
     for v in vals:
         assert hm.hm_isqrt(v) == orc.isqrt(v), v
 
