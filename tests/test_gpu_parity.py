@@ -410,3 +410,19 @@ def test_forward_captured_in_a_hip_graph(orc):
             torch.cuda.synchronize()
             assert_equal(f"graph.rep{rep}.y[{t}]", y.cpu().numpy()[0], want[t])
     assert lib_model.device_status() == 0
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes(orc, seed):
+    """Seeded random layer shapes, variants, batches and lengths on the persistent
+    path (whichever recurrent kernel the batch selects), two layers each."""
+    rng = np.random.default_rng(1000 + seed)
+    flags = int(rng.integers(0, 16))
+    N = 8 * int(rng.integers(1, 60))
+    H = int(rng.integers(8, N + 1)) if flags & wl.PROJECTION else N
+    I = int(rng.integers(1, 200))
+    B = int(rng.choice([1, 2, 15, 16, 17, 31, 33, 63, 100]))
+    T = int(rng.integers(1, 6))
+    print(f"random seed={seed} flags={flags} I={I} N={N} H={H} B={B} T={T}", flush=True)
+    layers, x = wl.make_custom([I, H], N, H, flags, B, T, seed=seed + 500, weight_param=0.08)
+    run_and_compare(orc, layers, x, f"random{seed}", trace=False, options={"rows16": seed % 3 != 2})
