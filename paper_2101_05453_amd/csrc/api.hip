@@ -593,15 +593,6 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       auto sync_bytes = [](int groups) { return (int64_t)256 * 64 * 4 + (int64_t)groups * 4 * 256 * 8; };
       const int launch_rows = p2_groups * ra.rows_pg;
       {
-        // initial h (given, or real 0 = zp_h) and the cleared words of the first launch, in one kernel
-        Timed t(m->prof, s, LSTM_INT_K_OTHER);
-        const int g0 = std::min(p2_groups, (B + ra.rows_pg - 1) / ra.rows_pg);
-        launch_init_layer(s, h_state ? h_state + h_off : nullptr, h.H, h0, d.Hpad, B, h.H, h.zp_h, wsb + ws.sync,
-                          sync_bytes(g0), pend.src, pend.ld, pend.dst, pend.cols);
-        pend.dst = nullptr;
-      }
-      {
-        Timed t(m->prof, s, LSTM_INT_K_INPUT_GEMM);
         InGemmArgs ga;
         memset(&ga, 0, sizeof(ga));
         ga.A = in; ga.lda = ld_in; ga.T = T; ga.B = B; ga.Bp = ra.Bp;
@@ -616,7 +607,25 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
           ga.pre = std::max(ga.pre, preshift_mode(ga.r[g], d.amax_x[sg]));
         }
         ga.tx2 = reinterpret_cast<int4 *>(tx);
-        if (in_gemm_ws_supported(ga))
+        // initial h (given, or real 0 = zp_h), the cleared words of the first launch and the previous layer's
+        // final h on its way to the state buffer: done by the input GEMM's workgroups ahead of their own
+        // work, or by a kernel of their own where the general input GEMM runs
+        const int g0 = std::min(p2_groups, (B + ra.rows_pg - 1) / ra.rows_pg);
+        const bool ws_gemm = in_gemm_ws_supported(ga);
+        if (ws_gemm) {
+          ga.has_init = 1;
+          ga.init.h_src = h_state ? h_state + h_off : nullptr; ga.init.ld_src = h.H;
+          ga.init.h0 = h0; ga.init.ld_h0 = d.Hpad; ga.init.rows = B; ga.init.cols = h.H; ga.init.zp = h.zp_h;
+          ga.init.sync = reinterpret_cast<int4 *>(wsb + ws.sync); ga.init.sync_vec = sync_bytes(g0) / 16;
+          ga.init.c_src = pend.src; ga.init.c_ld_src = pend.ld; ga.init.c_dst = pend.dst; ga.init.c_cols = pend.cols;
+        } else {
+          Timed t(m->prof, s, LSTM_INT_K_OTHER);
+          launch_init_layer(s, h_state ? h_state + h_off : nullptr, h.H, h0, d.Hpad, B, h.H, h.zp_h, wsb + ws.sync,
+                            sync_bytes(g0), pend.src, pend.ld, pend.dst, pend.cols);
+        }
+        pend.dst = nullptr;
+        Timed t(m->prof, s, LSTM_INT_K_INPUT_GEMM);
+        if (ws_gemm)
           launch_in_gemm_ws(s, ga, m->num_cus);
         else
           launch_in_gemm(s, ga);

@@ -59,6 +59,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   constexpr int BUF = NCH * 4096;                       // one stage; bytes beyond the block are padding
   constexpr int NST = 4;                                // stages: loads run three blocks ahead
   const int tid = threadIdx.x, lane = tid & 63;
+  // the chores ahead of the layer's recurrent kernel ride along (one launch less per layer)
+  if (a.has_init) layer_init_device(a.init, (long long)blockIdx.x * 256 + tid, (long long)gridDim.x * 256);
   // the wave index as a scalar: tile numbers, LDS stage addresses and store bases stay out of the vector unit
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, b2 = lane >> 5;

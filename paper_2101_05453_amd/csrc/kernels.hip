@@ -10,6 +10,10 @@
 //                   wavefront reductions).
 #include "kernels.h"
 
+#include <algorithm>
+
+#include "persistent.h"
+
 #include "lstm_int_math.h"
 
 namespace lstm_int {
@@ -397,42 +401,19 @@ void launch_fill_rows_i8(hipStream_t s, int8_t *dst, int ld_dst, int rows, int c
 // synchronization words, and -- to save a launch -- a pending copy of rows
 // (the previous layer's final h on its way to the caller's state buffer).
 // Workgroups [0, zero_blocks) clear, the next h_blocks write h, the rest copy.
-__global__ void init_layer_kernel(const int8_t *h_src, int ld_src, int8_t *h0, int ld_h0, int rows, int cols,
-                                  int zp, int4 *sync, int64_t sync_vec, int zero_blocks, int h_blocks,
-                                  const int8_t *c_src, int c_ld_src, int8_t *c_dst, int c_cols) {
-  if ((int)blockIdx.x < zero_blocks) {
-    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < sync_vec; i += (int64_t)zero_blocks * blockDim.x)
-      sync[i] = int4{0, 0, 0, 0};
-    return;
-  }
-  if ((int)blockIdx.x < zero_blocks + h_blocks) {
-    const int64_t total = (int64_t)rows * ld_h0;
-    for (int64_t i = (blockIdx.x - zero_blocks) * (int64_t)blockDim.x + threadIdx.x; i < total;
-         i += (int64_t)h_blocks * blockDim.x) {
-      const int64_t r = i / ld_h0;
-      const int col = (int)(i - r * ld_h0);
-      h0[i] = col < cols ? (h_src ? h_src[r * ld_src + col] : (int8_t)zp) : (int8_t)0;
-    }
-    return;
-  }
-  const int64_t nb = gridDim.x - zero_blocks - h_blocks;
-  const int64_t total = (int64_t)rows * c_cols;  // the copy has the same number of rows (the batch)
-  for (int64_t i = (blockIdx.x - zero_blocks - h_blocks) * (int64_t)blockDim.x + threadIdx.x; i < total;
-       i += nb * blockDim.x) {
-    const int64_t r = i / c_cols;
-    const int col = (int)(i - r * c_cols);
-    c_dst[i] = c_src[r * c_ld_src + col];
-  }
+__global__ void init_layer_kernel(LayerInit w) {
+  layer_init_device(w, blockIdx.x * (long long)blockDim.x + threadIdx.x, (long long)gridDim.x * blockDim.x);
 }
 
 void launch_init_layer(hipStream_t s, const int8_t *h_src, int ld_src, int8_t *h0, int ld_h0, int rows, int cols,
                        int zp, void *sync, int64_t sync_bytes, const int8_t *c_src, int c_ld_src, int8_t *c_dst,
                        int c_cols) {
-  const int64_t vec = sync_bytes / 16;  // the region is a multiple of 16 bytes, 16-byte aligned
-  const int zb = grid_for(vec), hb = grid_for((int64_t)rows * ld_h0);
-  const int cb = c_dst ? grid_for((int64_t)rows * c_cols) : 0;
-  hipLaunchKernelGGL(init_layer_kernel, dim3(zb + hb + cb), dim3(256), 0, s, h_src, ld_src, h0, ld_h0, rows, cols, zp,
-                     static_cast<int4 *>(sync), vec, zb, hb, c_src, c_ld_src, c_dst, c_cols);
+  LayerInit w;
+  w.h_src = h_src; w.ld_src = ld_src; w.h0 = h0; w.ld_h0 = ld_h0; w.rows = rows; w.cols = cols; w.zp = zp;
+  w.sync = static_cast<int4 *>(sync); w.sync_vec = sync_bytes / 16;  // a multiple of 16 bytes, 16-byte aligned
+  w.c_src = c_src; w.c_ld_src = c_ld_src; w.c_dst = c_dst; w.c_cols = c_cols;
+  const int64_t most = std::max<int64_t>(std::max<int64_t>(w.sync_vec, (int64_t)rows * ld_h0), c_dst ? (int64_t)rows * c_cols : 0);
+  hipLaunchKernelGGL(init_layer_kernel, dim3(grid_for(most)), dim3(256), 0, s, w);
 }
 
 __global__ void copy_i16_kernel(const int16_t *src, int16_t *dst, int64_t n, int value) {

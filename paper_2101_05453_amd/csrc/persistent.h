@@ -18,6 +18,40 @@ namespace lstm_int {
 //   tx2[(t*Bp + b) / 32][cell tile][half][lane][8]
 // with lane = b % 32 + 32 * ((cell % 8) / 4), half 0 = gates i,f, half 1 =
 // gates z,o, and the 8 values = [gate in half][cell % 4].
+// What has to be in place before a layer's recurrent kernel starts: the initial h (given, or the zero
+// point), cleared synchronization words, and -- to save a launch -- a pending copy of rows (the previous
+// layer's final h on its way to the caller's state buffer).  Done by its own small kernel, or by the
+// workgroups of the input GEMM ahead of their own work (grid-stride over all threads of the launch).
+struct LayerInit {
+  const int8_t *h_src;  // [rows, ld_src] or NULL (zero point)
+  int ld_src;
+  int8_t *h0;           // [rows, ld_h0], columns >= cols zeroed
+  int ld_h0, rows, cols, zp;
+  int4 *sync;           // sync_vec 16-byte words to clear
+  long long sync_vec;
+  const int8_t *c_src;  // pending copy [rows, c_cols] from rows of stride c_ld_src, or c_dst == NULL
+  int c_ld_src;
+  int8_t *c_dst;
+  int c_cols;
+};
+__device__ __forceinline__ void layer_init_device(const LayerInit &w, long long gtid, long long gthreads) {
+  for (long long i = gtid; i < w.sync_vec; i += gthreads) w.sync[i] = int4{0, 0, 0, 0};
+  const long long total = (long long)w.rows * w.ld_h0;
+  for (long long i = gtid; i < total; i += gthreads) {
+    const long long r = i / w.ld_h0;
+    const int col = (int)(i - r * w.ld_h0);
+    w.h0[i] = col < w.cols ? (w.h_src ? w.h_src[r * w.ld_src + col] : (int8_t)w.zp) : (int8_t)0;
+  }
+  if (w.c_dst) {
+    const long long ctotal = (long long)w.rows * w.c_cols;
+    for (long long i = gtid; i < ctotal; i += gthreads) {
+      const long long r = i / w.c_cols;
+      const int col = (int)(i - r * w.c_cols);
+      w.c_dst[i] = w.c_src[r * w.c_ld_src + col];
+    }
+  }
+}
+
 struct InGemmArgs {
   const int8_t *A;  // activations [T*B, lda]
   int a_slack;       // the buffer is readable for 31 more rows behind row T*B - 1 (launch_in_gemm_ws needs it
@@ -36,6 +70,8 @@ struct InGemmArgs {
   int gp;             // part groups over the 8 XCDs (1, 2, 4 or 8; 0 on entry = chosen by the launch; 0 in the
                       // kernel = workgroup id -> (id % parts, id / parts))
   RescaleHi rs[4];    // per gate, prepared from (M, r)
+  int has_init;       // launch_in_gemm_ws only: the workgroups do `init` before their own work
+  LayerInit init;
 };
 // one workgroup per 128 rows x 4 tiles, operands staged per 64-byte k tile
 // (any k depth, any shifts)
