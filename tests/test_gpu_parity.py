@@ -326,6 +326,7 @@ def test_maximum_sizes(orc):
     ([72, 200], 200, 200, wl.LAYER_NORM, 37, 6, None),                      # 4 workgroups x 3 groups, ragged rows
     ([72, 136], 200, 136, wl.LAYER_NORM | wl.PROJECTION, 70, 5, None),      # 5 projection tiles over 4 workgroups
     ([40], 64, 64, wl.LAYER_NORM, 1, 7, None),                              # one workgroup, one row
+    ([64], 456, 456, wl.LAYER_NORM, 40, 3, [0, 15, 16, 39]),                # h rows of 512 bytes (k depth class 10)
     ([64], 520, 520, wl.LAYER_NORM, 128, 3, [0, 15, 16, 100, 127]),         # k depth 10 without a projection
     ([64], 1024, 1024, wl.LAYER_NORM, 48, 3, [0, 17, 47]),                  # k depth 16
     ([640, 640], 2048, 640, wl.LAYER_NORM | wl.PROJECTION, 120, 4, [0, 17, 50, 119]),  # the C4 layer, 8 groups of 32
