@@ -36,9 +36,12 @@ def algorithmic_work(q, B, T, persistent):
     if persistent:
         # one launch runs all T steps; per step: weights once, W x terms, cell
         # state in and out, h in, h out
-        step = G * N * H + (Hout * N if proj else 0) + 2.0 * B * G * N + 4.0 * B * N + B * H + B * Hout
+        weights = G * N * H + (Hout * N if proj else 0)
+        step = weights + 2.0 * B * G * N + 4.0 * B * N + B * H + B * Hout
         ops = 2.0 * B * (G * N * H + (Hout * N if proj else 0))
-        w["recurrent"] = {"ops": ops * T, "bytes": step * T, "launches": 1}
+        # bytes_resident: the same step with the weights kept on chip (read from HBM once per launch)
+        w["recurrent"] = {"ops": ops * T, "bytes": step * T, "bytes_resident": (step - weights) * T + weights,
+                          "launches": 1}
     else:
         w["recurrent"] = {"ops": 2.0 * B * G * N * H * T, "bytes": (G * N * H + B * H + 2.0 * B * G * N) * T,
                           "launches": T}
@@ -67,7 +70,7 @@ def main():
     import torch
 
     import lstm_workloads as wl
-    from paper_2101_05453_amd import binding, calibration
+    from paper_2101_05453_amd import binding
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     if args.copy_calibration:
@@ -83,14 +86,15 @@ def main():
     binding.lib()
     cfg = wl.CONFIGS[args.config]
     layers, x = wl.make_workload(args.config)
-    calibration.collect_statistics(layers, x)  # statistics from the first 16 rows (Sec. 4)
+    xf = torch.from_numpy(x).cuda()
+    binding.calibrate(layers, xf, device=0, max_rows=16)  # statistics of the float run on the first 16 rows (Sec. 4)
     model = binding.prepare(layers, device=0)
     model.set_option("path", args.path)
     L = model.num_layers
     quants = [model.get_quant(l) for l in range(L)]
-    xq = calibration.quantize_input(x, quants[0]["s_x"], quants[0]["zp_x"])
-    T, B, _ = xq.shape
-    xd = torch.from_numpy(xq).cuda()
+    xd = model.quantize_input(xf)  # features -> int8 codes, resident in HBM before the timed region
+    del xf
+    T, B, _ = xd.shape
     y = torch.empty((T, B, quants[-1]["H"]), dtype=torch.int8, device="cuda")
     ws = torch.empty(model.workspace_bytes(T, B), dtype=torch.uint8, device="cuda")
 
@@ -105,6 +109,8 @@ def main():
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    if model.device_status() != 0:  # a bounded wait gave up or a group was misplaced: the kernels left early
+        sys.exit(f"bench.py: device status {model.device_status()} after the timed loop; the timing is void")
     ms_per_step = dt / args.steps * 1e3
     cell_steps = B * T * L
     value = cell_steps * args.steps / dt
@@ -114,13 +120,15 @@ def main():
     for _ in range(args.steps):
         step()
     prof = model.profile_end()
+    if model.device_status() != 0:
+        sys.exit(f"bench.py: device status {model.device_status()} after the profiled loop; the timing is void")
     persistent = prof["cell"]["launches"] == 0  # the per-step path launches a cell kernel per step
     work = {}
     for q in quants:
         for k, v in algorithmic_work(q, B, T, persistent).items():
-            e = work.setdefault(k, {"ops": 0.0, "bytes": 0.0, "launches": 0})
+            e = work.setdefault(k, {"ops": 0.0, "bytes": 0.0, "bytes_resident": 0.0, "launches": 0})
             for f in e:
-                e[f] += v[f]
+                e[f] += v.get(f, v["bytes"] if f == "bytes_resident" else 0)
     kernels = {}
     for k, w in work.items():
         p = prof[k]
@@ -131,6 +139,16 @@ def main():
                       "ms_per_step": per_step_ms,
                       "gbps": w["bytes"] / (per_step_ms * 1e-3) / 1e9,
                       "tops": w["ops"] / (per_step_ms * 1e-3) / 1e12}
+        if k == "recurrent" and persistent:
+            # the same launches against the bytes of the variant that keeps the weights on chip
+            kernels[k]["gbps_weights_resident"] = w["bytes_resident"] / (per_step_ms * 1e-3) / 1e9
+            kernels[k]["frac_hbm_weights_resident"] = kernels[k]["gbps_weights_resident"] / PEAK_HBM_GBS
+        if k == "input_gemm":
+            # the shape sits near the machine balance (peak ops / peak bytes): both bounds are reported
+            kernels[k]["frac_mfma"] = kernels[k]["tops"] / PEAK_INT8_TOPS
+            kernels[k]["frac_hbm"] = kernels[k]["gbps"] / PEAK_HBM_GBS
+            kernels[k]["ops_per_byte"] = w["ops"] / w["bytes"]
+            kernels[k]["machine_balance_ops_per_byte"] = PEAK_INT8_TOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     d = kernels[dominant]
     if dominant == "input_gemm":
@@ -158,11 +176,14 @@ def main():
         "roofline": roof,
     }
 
+    ok = True
     if not args.no_cpu_baseline:
-        # the oracle as it stands, on a bounded sample: one batch row per host
-        # thread, the first steps of the same workload, all layers
+        # the oracle as it stands, on a bounded sample of the same workload: batch rows spread evenly
+        # over the batch (so every group of rows of the recurrent kernel is sampled), the first steps,
+        # all layers; one row per host thread at a time.  Its output also checks the GPU's.
         import oracle
 
+        xq = xd.cpu().numpy()
         cores = min(oracle.max_threads(), 16, B)
         om = oracle.prepare(layers)
         probe_T = min(T, 4)
@@ -172,19 +193,27 @@ def main():
         # about 15 s of work: whole sequences of as many rows as that allows (multiples of the thread count)
         rows = int(max(cores, min(B, (15.0 * rate / (T * L)) // cores * cores)))
         Ts = T if rows * T * L <= 30.0 * rate else max(1, int(15.0 * rate / (rows * L)))
-        xs = np.ascontiguousarray(xq[:Ts, :rows])
+        sel = [(i * B) // rows for i in range(rows)]
+        xs = np.ascontiguousarray(xq[:Ts, sel])
         t0 = time.perf_counter()
-        oracle.forward(om, xs, threads=cores)
+        yo = oracle.forward(om, xs, threads=cores)
         dto = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": rows * Ts * L / dto, "unit": "cell-steps/s", "cores": cores,
                                "kind": "oracle",
-                               "sample": f"first {rows} batch rows x first {Ts} steps x {L} layers of "
-                                         f"{args.config}, {dto:.1f} s"}
+                               "sample": f"{rows} batch rows spread evenly over the batch x first {Ts} steps x "
+                                         f"{L} layers of {args.config}, {dto:.1f} s"}
+        # the output of the last timed call against the oracle's, element by element
+        got = y[:Ts].cpu().numpy()[:, sel]
+        ok = bool(got.shape == yo.shape and (got == yo).all())
+        out["parity"] = {"rows": rows, "steps": Ts, "layers": L, "equal": ok,
+                         "mismatches": int((got != yo).sum()) if got.shape == yo.shape else -1}
     print(json.dumps(out), flush=True)
     # release device objects in order before the interpreter tears down
     del xd, y, ws
     model.destroy()
     torch.cuda.synchronize()
+    if not ok:
+        sys.exit("bench.py: the GPU output differs from the oracle on the sampled rows")
 
 
 if __name__ == "__main__":

@@ -167,6 +167,17 @@ int lstm_int_calibrate(const lstm_int_layer_params *layers, int32_t num_layers,
 int lstm_int_get_quant(const lstm_int_model *model, int32_t layer,
                        lstm_int_layer_quant *out);
 
+/*
+ * The feature quantizer upstream of the first layer (Sec. 3.2.4: asymmetric
+ * int8 activations with a nudged zero point): for n float32 values x (DEVICE)
+ *   xq[i] = clamp(floor(x[i] / s_x + 1/2) + zp_x, -128, 127)
+ * with layer 0's (s_x, zp_x), evaluated in double precision; xq is DEVICE
+ * int8 [n], caller-owned.  Asynchronous on hip_stream, allocates nothing.
+ * A NaN input gives code 0.
+ */
+int lstm_int_quantize_input(const lstm_int_model *model, const float *x, int64_t n,
+                            int8_t *xq, void *hip_stream);
+
 /* Device bytes lstm_int_forward needs for T steps of B rows (0 on error). */
 size_t lstm_int_workspace_bytes(const lstm_int_model *model, int32_t T, int32_t B);
 
@@ -267,10 +278,11 @@ int lstm_int_phase_ticks(const lstm_int_model *model, int64_t ticks[16]);
 /*
  * Per-kernel device time of the forward calls made while profiling is on,
  * measured with HIP events on the stream the kernels run on.
- * lstm_int_profile_begin resets the counters and makes forward record events;
- * lstm_int_profile_end synchronizes that stream and fills, per kernel class k
- * (LSTM_INT_K_*), launches[k] and total_ms[k].  Profiling adds host work to
- * forward; throughput is measured with it off.
+ * lstm_int_profile_begin resets the counters and makes forward record events
+ * (created as the launches need them, any number per call);
+ * lstm_int_profile_end synchronizes that stream, fills, per kernel class k
+ * (LSTM_INT_K_*), launches[k] and total_ms[k], and destroys the events.
+ * Profiling adds host work to forward; throughput is measured with it off.
  */
 #define LSTM_INT_K_INPUT_GEMM 0 /* hoisted W x over all T, + rescale        */
 #define LSTM_INT_K_RECURRENT 1  /* R h per step (+ fused epilogue if any)   */

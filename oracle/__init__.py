@@ -10,7 +10,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "liblstm_int_oracle.so")
+# LSTM_INT_ORACLE_LIB selects another build of the same source (the sanitized one of oracle/build.py)
+_LIB_PATH = os.environ.get("LSTM_INT_ORACLE_LIB") or os.path.join(_HERE, "liblstm_int_oracle.so")
 
 CIFG, PEEPHOLE, LAYER_NORM, PROJECTION = 1, 2, 4, 8
 OK, INVALID_ARG, UNSUPPORTED, BAD_RANGE, NOMEM = 0, -1, -2, -3, -4

@@ -7,6 +7,20 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "liblstm_int_oracle.so")
+SAN_LIB = os.path.join(HERE, "liblstm_int_oracle_san.so")
+
+
+def build_sanitized():
+    """The same source under AddressSanitizer and UndefinedBehaviorSanitizer, errors
+    fatal: the oracle's claims of 64-bit headroom (Sec. 3.1.1 overflow model) and
+    its indexing are then checked by the machine.  Loaded by a process that has
+    the sanitizer runtime preloaded (tests/test_sanitizers.py)."""
+    src = os.path.join(HERE, "lstm_int_oracle.c")
+    cmd = ["gcc", "-std=c11", "-O1", "-g", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+           "-Wall", "-Wextra", "-o", SAN_LIB, src, "-lm"]
+    subprocess.run(cmd, check=True)
+    return SAN_LIB
 
 
 def build(force=True):

@@ -93,6 +93,8 @@ def lib():
                                        C.POINTER(C.c_void_p)]
         L.lstm_int_get_quant.restype = C.c_int
         L.lstm_int_get_quant.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerQuant)]
+        L.lstm_int_quantize_input.restype = C.c_int
+        L.lstm_int_quantize_input.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.lstm_int_workspace_bytes.restype = C.c_size_t
         L.lstm_int_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         L.lstm_int_forward.restype = C.c_int
@@ -208,6 +210,22 @@ class Model:
         self._dims = out
         return out
 
+    # lstm_int_quantize_input on a torch device tensor
+    def quantize_input(self, x, out=None):
+        """x: float32 CUDA tensor of features (any shape) -> int8 CUDA tensor of
+        the same shape, the codes layer 0 reads.  Asynchronous on torch's current
+        stream."""
+        import torch
+
+        assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+        if out is None:
+            out = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+        assert out.is_cuda and out.dtype == torch.int8 and out.is_contiguous() and out.numel() == x.numel()
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+        _check(lib().lstm_int_quantize_input(self._h, x.data_ptr(), x.numel(), out.data_ptr(), stream),
+               "lstm_int_quantize_input")
+        return out
+
     # lstm_int_workspace_bytes
     def workspace_bytes(self, T, B):
         return lib().lstm_int_workspace_bytes(self._h, T, B)
@@ -291,13 +309,15 @@ def prepare(layers, device=0):
 
 
 # lstm_int_calibrate
-def calibrate(layers, x, device=0, want_output=False, apply=True):
+def calibrate(layers, x, device=0, want_output=False, apply=True, max_rows=None):
     """Statistics of a float run on the GPU.  x: float32 CUDA tensor [T,B,I0]
-    (the calibration rows).  Returns the per-layer statistics as dicts (and the
+    (the calibration rows; max_rows keeps only the first rows of the batch).  Returns the per-layer statistics as dicts (and the
     float output of the last layer, a float64 CUDA tensor, with want_output);
     with apply they are also written into the layer specs, ready for prepare."""
     import torch
 
+    if max_rows is not None and x.shape[1] > max_rows:
+        x = x[:, :max_rows].contiguous()
     assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
     T, B, _ = x.shape
     arr, keep = marshal_layers(layers)

@@ -8,6 +8,8 @@ LIB = os.path.join(HERE, "liblstm_int.so")
 SOURCES = ["prepare.cpp", "kernels.hip", "persistent.hip", "in_gemm.hip", "rec_inst_8.hip", "rec_inst_20.hip",
            "rec_inst_32.hip", "rec16_inst.hip", "rec16_inst_4.hip", "rec16_inst_10.hip", "rec16_inst_16.hip", "calibrate.hip", "api.hip"]
 HOSTMATH_LIB = os.path.join(HERE, "liblstm_int_hostmath.so")
+HOSTMATH_SAN_LIB = os.path.join(HERE, "liblstm_int_hostmath_san.so")
+SANITIZE_FLAGS = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g"]
 
 # packed-fp32 instructions are disabled for all device code
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -42,12 +44,16 @@ def build(verbose=False):
     return LIB
 
 
-def build_hostmath():
-    """Host-only build of the device math header, for CPU checks of it."""
-    cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-ffp-contract=off", "-o", HOSTMATH_LIB,
-           os.path.join(CSRC, "hostmath_shim.cpp"), os.path.join(CSRC, "prepare.cpp")]
+def build_hostmath(sanitize=False):
+    """Host-only build of the device math header and of the offline phase, for CPU
+    checks of them; sanitize=True builds a second copy under AddressSanitizer and
+    UndefinedBehaviorSanitizer (signed overflow, shifts, bounds: the 64-bit
+    headroom claims of the integer arithmetic trap instead of wrapping)."""
+    out = HOSTMATH_SAN_LIB if sanitize else HOSTMATH_LIB
+    cmd = ["g++", "-std=c++17", "-O1" if sanitize else "-O2", "-fPIC", "-shared", "-ffp-contract=off", "-o", out,
+           os.path.join(CSRC, "hostmath_shim.cpp"), os.path.join(CSRC, "prepare.cpp")] + (SANITIZE_FLAGS if sanitize else [])
     subprocess.run(cmd, check=True)
-    return HOSTMATH_LIB
+    return out
 
 
 def _filter(text):

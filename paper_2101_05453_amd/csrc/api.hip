@@ -60,6 +60,14 @@ struct Profile {
   std::vector<hipEvent_t> ev;  // pairs (start, stop)
   std::vector<int> cls;
   size_t used = 0;  // pairs in use
+  bool failed = false;  // an event could not be created: the times would be incomplete
+  void release() {
+    for (auto &e : ev)
+      if (e) (void)hipEventDestroy(e);
+    ev.clear();
+    cls.clear();
+    used = 0;
+  }
 };
 
 }  // namespace
@@ -91,6 +99,7 @@ namespace {
 
 struct Workspace {
   size_t tx, out[2], xpad, th, mbuf, c, h0, sync, m2, total;
+  size_t tx_bytes, out_bytes, m2_bytes;  // extents of the regions the persistent kernels index
 };
 constexpr size_t kSyncBytes = 256 * 64 * 4 + 256 * 4 * 256 * 8;  // counters + statistics accumulators
 
@@ -115,7 +124,10 @@ Workspace plan_workspace(const lstm_int_model *m, int64_t T, int64_t B) {
     off += align256(bytes);
     return o;
   };
-  w.tx = take((size_t)T * ((B + 31) / 32 * 32) * maxGN * 2);
+  w.tx_bytes = (size_t)T * ((B + 31) / 32 * 32) * maxGN * 2;
+  w.out_bytes = ((size_t)T * B + 32) * maxHpad;
+  w.m2_bytes = (size_t)T * round_up(B, 32) * maxNpadp;
+  w.tx = take(w.tx_bytes);
   // 32 rows of slack behind the activation buffers: the input GEMM reads whole blocks of 32 rows
   w.out[0] = take(((size_t)T * B + 32) * maxHpad);
   w.out[1] = take(((size_t)T * B + 32) * maxHpad);
@@ -145,18 +157,50 @@ Requant make_requant(const int32_t *M, const int32_t *e, int first, int count, i
   return r;
 }
 
+// Whether everything a launch of a persistent recurrent kernel indexes with these arguments lies inside
+// the workspace regions it was given (checked on the host before every launch: an access out of bounds
+// on the device can take the whole GPU down).  T_all = steps of the whole call, t0 = first step of this launch.
+bool rec_extents_ok(const RecArgs &ra, const Workspace &ws, int T_all, int t0, bool has_proj) {
+  const size_t Bp = (size_t)ra.Bp;
+  if (ra.Bp % 32 || ra.Bp < ra.B || ra.B < 1 || ra.T < 1 || t0 < 0 || t0 + ra.T > T_all) return false;
+  if (ra.groups < 1 || ra.groups > 256 || ra.batch0 < 0 || ra.batch0 >= ra.B) return false;
+  // the first row of every group is a real row: later row tiles of a group are skipped or clamped by the kernels
+  if ((int64_t)ra.batch0 + (int64_t)(ra.groups - 1) * ra.rows_pg >= ra.B) return false;
+  // W x terms: [T_all * Bp / 32][GS * 8 tiles][2][64 lanes] 16-byte pieces
+  if ((size_t)T_all * Bp / 32 * (size_t)(ra.GS * 8) * 2 * 64 * 16 > ws.tx_bytes) return false;
+  // layer output [T_all, B, Hpad]
+  if ((size_t)T_all * ra.B * ra.Hpad > ws.out_bytes) return false;
+  // m exchange buffer [T][Bp][npadp] in tiles
+  if (has_proj && (size_t)ra.T * Bp * ra.npadp > ws.m2_bytes) return false;
+  // counters [groups][64] words and statistics accumulators [groups][4][256] 64-bit words
+  if ((size_t)ra.groups * 64 * 4 > (size_t)256 * 64 * 4 || (size_t)ra.groups * 4 * 256 * 8 > (size_t)256 * 4 * 256 * 8)
+    return false;
+  return true;
+}
+
 // Times each launch with a pair of events when profiling is on.
 struct Timed {
   Profile &p;
   hipStream_t s;
   bool active;
   Timed(Profile &prof, hipStream_t stream, int cls) : p(prof), s(stream), active(false) {
-    if (p.on && (p.used + 1) * 2 <= p.ev.size()) {
-      active = true;
-      p.cls[p.used] = cls;
-      p.stream = s;
-      (void)hipEventRecord(p.ev[2 * p.used], s);
+    if (!p.on) return;
+    // events are created as launches need them (any number of launches per call) and freed by profile_end
+    if ((p.used + 1) * 2 > p.ev.size()) {
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        p.failed = true;
+        return;
+      }
+      p.ev.push_back(e0);
+      p.ev.push_back(e1);
+      p.cls.push_back(0);
     }
+    active = true;
+    p.cls[p.used] = cls;
+    p.stream = s;
+    (void)hipEventRecord(p.ev[2 * p.used], s);
   }
   ~Timed() {
     if (active) {
@@ -445,6 +489,16 @@ int lstm_int_get_quant(const lstm_int_model *m, int32_t layer, lstm_int_layer_qu
   return LSTM_INT_OK;
 }
 
+int lstm_int_quantize_input(const lstm_int_model *m, const float *x, int64_t n, int8_t *xq, void *hip_stream) {
+  if (!m || n < 0 || m->host.empty()) return LSTM_INT_E_INVALID_ARG;
+  if (m->device < 0) return LSTM_INT_E_DEVICE;
+  if (n == 0) return LSTM_INT_OK;
+  if (!x || !xq) return LSTM_INT_E_INVALID_ARG;
+  if (hipSetDevice(m->device) != hipSuccess) return LSTM_INT_E_DEVICE;
+  launch_quantize_input(static_cast<hipStream_t>(hip_stream), x, xq, n, m->host[0].s_x, m->host[0].zp_x);
+  return hipGetLastError() == hipSuccess ? LSTM_INT_OK : LSTM_INT_E_DEVICE;
+}
+
 size_t lstm_int_workspace_bytes(const lstm_int_model *m, int32_t T, int32_t B) {
   if (!m || T < 0 || B < 0 || m->host.empty()) return 0;
   if (T == 0 || B == 0) return 256;
@@ -652,6 +706,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
             Timed t(m->prof, s, LSTM_INT_K_OTHER);
             launch_fill_i16(s, reinterpret_cast<int16_t *>(wsb + ws.sync), sync_bytes(ra.groups) / 2, 0);
           }
+          if (!rec_extents_ok(ra, ws, T, t0, proj)) return LSTM_INT_E_WORKSPACE;
           Timed t(m->prof, s, LSTM_INT_K_RECURRENT);
           const bool coop = m->cooperative != 0;
           if ((use16 ? launch_rec16(s, ra, coop) : launch_rec(s, ra, coop)) != hipSuccess) return LSTM_INT_E_DEVICE;
@@ -838,14 +893,8 @@ int lstm_int_profile_begin(lstm_int_model *m) {
   if (m->device < 0) return LSTM_INT_E_DEVICE;
   if (hipSetDevice(m->device) != hipSuccess) return LSTM_INT_E_DEVICE;
   Profile &p = m->prof;
-  const size_t pairs = 1 << 14;
-  if (p.ev.empty()) {
-    p.ev.resize(2 * pairs);
-    p.cls.resize(pairs);
-    for (auto &e : p.ev)
-      if (hipEventCreate(&e) != hipSuccess) return LSTM_INT_E_DEVICE;
-  }
-  p.used = 0;
+  p.release();
+  p.failed = false;
   p.on = true;
   return LSTM_INT_OK;
 }
@@ -860,23 +909,25 @@ int lstm_int_profile_end(lstm_int_model *m, int64_t launches[LSTM_INT_K_COUNT],
     launches[k] = 0;
     total_ms[k] = 0.0;
   }
-  if (hipStreamSynchronize(p.stream) != hipSuccess) return LSTM_INT_E_DEVICE;
-  for (size_t i = 0; i < p.used; ++i) {
+  int rc = hipStreamSynchronize(p.stream) == hipSuccess && !p.failed ? LSTM_INT_OK : LSTM_INT_E_DEVICE;
+  for (size_t i = 0; i < p.used && rc == LSTM_INT_OK; ++i) {
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, p.ev[2 * i], p.ev[2 * i + 1]) != hipSuccess)
-      return LSTM_INT_E_DEVICE;
+    if (hipEventElapsedTime(&ms, p.ev[2 * i], p.ev[2 * i + 1]) != hipSuccess) {
+      rc = LSTM_INT_E_DEVICE;
+      break;
+    }
     launches[p.cls[i]] += 1;
     total_ms[p.cls[i]] += ms;
   }
-  return LSTM_INT_OK;
+  p.release();  // no event outlives the measurement
+  return rc;
 }
 
 void lstm_int_destroy(lstm_int_model *m) {
   if (!m) return;
   if (m->device >= 0) {
     (void)hipSetDevice(m->device);
-    for (auto &e : m->prof.ev)
-      if (e) (void)hipEventDestroy(e);
+    m->prof.release();
     if (m->arena) (void)hipFree(m->arena);
   }
   delete m;

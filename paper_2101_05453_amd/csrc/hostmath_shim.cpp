@@ -65,4 +65,28 @@ int32_t hm_cell_update(int32_t i, int32_t z, int32_t f, int32_t c, int32_t m_c) 
 int32_t hm_hidden(int32_t o, int32_t tc, int32_t M, int32_t r, int32_t zp) {
   return hidden_state(o, tc, M, r, zp);
 }
+
+// The library's offline phase on the host (what lstm_int_prepare runs before the upload); *checksum
+// receives the sum of every quantized weight, bias and multiplier of every layer, for a cross-check.
+int hm_prepare(const lstm_int_layer_params *layers, int32_t num_layers, int64_t *checksum) {
+  std::vector<LayerHost> out;
+  const int rc = prepare_host(layers, num_layers, out);
+  int64_t s = 0;
+  for (const LayerHost &h : out) {
+    for (int8_t v : h.Wq) s += v;
+    for (int8_t v : h.Rq) s += v;
+    for (int8_t v : h.Wpq) s += v;
+    for (int32_t v : h.qb) s += v;
+    for (int32_t v : h.qbp) s += v;
+    for (int32_t v : h.bx_fold) s += v;
+    for (int32_t v : h.bh_fold) s += v;
+    for (int32_t v : h.bp_fold) s += v;
+    for (int16_t v : h.Pq) s += v;
+    for (int16_t v : h.Lq) s += v;
+    for (int g = 0; g < 4; ++g) s += (int64_t)h.Mx[g] + h.ex[g] + h.Mh[g] + h.eh[g] + h.Mln[g] + h.eln[g];
+    s += (int64_t)h.Mm + h.em + h.Mp + h.ep + h.zp_x + h.zp_h + h.zp_m + h.m_c;
+  }
+  if (checksum) *checksum = s;
+  return rc;
+}
 }

@@ -72,6 +72,8 @@ void launch_init_layer(hipStream_t s, const int8_t *h_src, int ld_src, int8_t *h
                        int c_cols);
 void launch_copy_i16(hipStream_t s, const int16_t *src, int16_t *dst, int64_t n);
 void launch_fill_i16(hipStream_t s, int16_t *dst, int64_t n, int value);
+// q[i] = clamp(floor(x[i] / scale + 1/2) + zp, -128, 127), computed in double (Sec. 3.2.4)
+void launch_quantize_input(hipStream_t s, const float *x, int8_t *q, int64_t n, double scale, int zp);
 // dump [rows, G*N] (present gates) into [rows, 4, N] gate slots first..3
 void launch_scatter_gates(hipStream_t s, const int16_t *src, int16_t *dst, int rows, int G, int N);
 

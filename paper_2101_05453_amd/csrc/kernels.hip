@@ -433,6 +433,20 @@ void launch_fill_i16(hipStream_t s, int16_t *dst, int64_t n, int value) {
                      dst, n, value);
 }
 
+// Affine quantization of float features to int8 codes (Sec. 3.2.4): q = clamp(floor(v / s + 1/2) + zp),
+// in double precision (division and addition are correctly rounded, no contraction).
+__global__ void quantize_input_kernel(const float *x, int8_t *q, int64_t n, double s, int zp) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const double v = floor((double)x[i] / s + 0.5) + (double)zp;
+    q[i] = v != v ? (int8_t)0 : (int8_t)(v < -128.0 ? -128.0 : (v > 127.0 ? 127.0 : v));
+  }
+}
+
+void launch_quantize_input(hipStream_t s, const float *x, int8_t *q, int64_t n, double scale, int zp) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(quantize_input_kernel, dim3(grid_for(n)), dim3(256), 0, s, x, q, n, scale, zp);
+}
+
 __global__ void scatter_gates_kernel(const int16_t *src, int16_t *dst, int rows, int G, int N) {
   const int64_t per_row = (int64_t)G * N, total = rows * per_row;
   const int first = 4 - G;

@@ -218,14 +218,14 @@ LSTM_HD int32_t rescale_preshift(int32_t a, const RescaleHi &p) {
   const int32_t lim = (int32_t)(0x7FFFFFFFu >> p.k);
   a = a < lim ? a : lim;
   a = a > -lim - 1 ? a : -lim - 1;
-  return a << p.k;
+  return (int32_t)((uint32_t)a << p.k);  // two's-complement shift, defined for negative a as well
 }
 // PRE: 2 = clamp and shift the operand (any operand), 1 = shift only (the caller
 // knows that the shifted operand fits 32 bits), 0 = neither (p.k == 0, or done already)
 template <int PRE = 2>
 LSTM_HD int32_t rescale_sat16_pre(int32_t a, const RescaleHi &p) {
   if (PRE == 2) a = rescale_preshift(a, p);
-  if (PRE == 1) a <<= p.k;
+  if (PRE == 1) a = (int32_t)((uint32_t)a << p.k);
 #if defined(__HIP_DEVICE_COMPILE__)
   const int32_t hi = __mulhi(a, p.M);
 #else

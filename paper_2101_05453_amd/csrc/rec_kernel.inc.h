@@ -736,6 +736,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const int ptile = member + pt * GS;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
+          // a row tile that starts beyond the batch (second tile of a ragged last group) has no rows in the
+          // exchange buffer at all; the test is uniform over the workgroup, so the barriers below stay matched
+          if (rt > 0 && row0 + rt * 32 >= a.B) continue;
           // rows of the tile beyond the batch were never written; their results are not stored either
           const int8_t *mrow = a.mbuf + (size_t)t * a.Bp * a.npadp +
                                ((((size_t)((row0 >> 5) + rt) * (a.npadp >> 5) + wave * per_wave) * 32 + col) << 5) +

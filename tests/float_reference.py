@@ -1,11 +1,11 @@
-"""Harness-side statistics collection (Sec. 4 of arXiv 2101.05453,
-post-training): runs the float LSTM of Sec. 2 (eqs. 1-7) over representative
-inputs and records, at the paper's "log" nodes, the ranges that
-lstm_int_prepare needs: min/max of x, h and m, max |c|, and max |gate sum|
-per gate when layer norm is on.
+"""TEST INFRASTRUCTURE: a second float LSTM, independent of the library and of the
+oracle, used by the CPU tests to fill in calibration statistics and to pin the
+oracle's own float LSTM (which in turn checks lstm_int_calibrate on the GPU).
 
-Offline tooling in plain PyTorch float64 on the CPU; it is not on the integer
-path and nothing in liblstm_int depends on it.
+Runs the float LSTM of Sec. 2 (eqs. 1-7) of arXiv 2101.05453 in plain PyTorch
+float64 on the CPU over representative inputs and records, at the paper's
+"log" nodes (Sec. 4, post-training), min/max of x, h and m, max |c|, and
+max |gate sum| per gate when layer norm is on.
 """
 import numpy as np
 import torch
@@ -84,11 +84,3 @@ def collect_statistics(layers, x, max_rows=16):
         all_stats.append(st)
         inp = out
     return all_stats
-
-
-def quantize_input(x, s_x, zp_x):
-    """Float features -> int8 codes with layer 0's (s_x, zp_x), the affine map
-    of Sec. 3.2.4: q = clamp(floor(v / s + 1/2) + zp, -128, 127).  Quantizing
-    the features is a separate operation upstream of the LSTM."""
-    v = np.floor(np.asarray(x, dtype=np.float64) / s_x + 0.5) + zp_x
-    return np.clip(v, -128, 127).astype(np.int8)

@@ -1,19 +1,36 @@
-"""Shared plumbing of the GPU parity tests: calibrate, prepare both sides from
-the same float parameters, run the HIP library and the CPU oracle on the same
-int8 input, and compare integer tensors element by element."""
+"""Shared plumbing of the GPU parity tests: collect statistics with the library's
+float run on the GPU (lstm_int_calibrate), prepare both sides from the same float
+parameters and statistics, quantize the features with the library (checked against
+the oracle's quantizer), run the HIP library and the CPU oracle on the same int8
+input, and compare integer tensors element by element."""
 import numpy as np
 
-from paper_2101_05453_amd import binding, calibration
+from paper_2101_05453_amd import binding
 
 TRACE_FIELDS = ("tx", "th", "g", "ln", "act", "c", "m", "h")
 
 
-def prepare_both(orc, layers, x, device=0):
-    calibration.collect_statistics(layers, x)
+def calibrate_on_gpu(layers, x, device=0):
+    """Fills the statistics of the layer specs from the library's float run over the
+    first 16 batch rows of x (Sec. 4); returns x as a float32 device tensor."""
+    import torch
+
+    xd = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda(device)
+    binding.calibrate(layers, xd, device=device, max_rows=16)
+    return xd
+
+
+def prepare_both(orc, layers, x, device=0, scale_x=1.0):
+    """scale_x: the features fed to the quantizer are x * scale_x (to drive them out of
+    the calibrated range)."""
+    xd = calibrate_on_gpu(layers, x, device)
     lib_model = binding.prepare(layers, device=device)
     orc_model = orc.prepare(layers)
-    q0 = lib_model.get_quant(0)
-    xq = calibration.quantize_input(x, q0["s_x"], q0["zp_x"])
+    if scale_x != 1.0:
+        xd = (xd * np.float32(scale_x)).contiguous()
+    xq = lib_model.quantize_input(xd).cpu().numpy()
+    q0 = orc_model.layer(0)
+    assert_equal("quantize_input", xq, orc.quantize_input(xd.cpu().numpy(), q0["s_x"], q0["zp_x"]))
     return lib_model, orc_model, xq
 
 

@@ -9,7 +9,8 @@ import numpy as np
 import pytest
 
 import lstm_workloads as wl
-from paper_2101_05453_amd import binding, calibration
+import float_reference
+from paper_2101_05453_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -58,7 +59,7 @@ def test_strerror_and_error_codes():
 
 def _calibrated(flags=0, **kw):
     layers, x = wl.make_custom([24], 40, 16, flags, 3, 6, seed=1, **kw)
-    calibration.collect_statistics(layers, x)
+    float_reference.collect_statistics(layers, x)
     return layers, x
 
 

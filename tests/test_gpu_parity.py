@@ -68,15 +68,96 @@ def test_c2_full(orc):
     run_and_compare(orc, layers, x, "C2", trace=True)
 
 
-@pytest.mark.parametrize("name,rows", [
-    ("C3", [0, 63, 64, 127]),
-    ("C4", [0, 100, 255]),
-    ("C5", [0, 511, 640, 1023]),
-])
-def test_benchmark_configs_full_size_sampled_rows(orc, name, rows):
-    print(f"{name} full size, oracle on rows {rows}", flush=True)
+def group_edge_rows(B, rows_pg):
+    """First and last batch row of every group of rows_pg rows."""
+    rows = set()
+    for r0 in range(0, B, rows_pg):
+        rows.update((r0, min(B, r0 + rows_pg) - 1))
+    return sorted(rows)
+
+
+@pytest.mark.parametrize("name,rows_pg", [("C3", 16), ("C4", 32), ("C5", 32)])
+def test_benchmark_configs_full_size_sampled_rows(orc, name, rows_pg):
+    """The benchmark configurations at full size in the launch configuration bench.py
+    times, compared on the first and the last batch row of every group of rows of the
+    recurrent kernel that runs them (C3: 8 groups of 16 rows; C4: 8 groups of 32, one
+    per XCD; C5: two launches of 16 groups of 32) -- every group, hence every XCD and
+    every launch, has rows under comparison."""
     layers, x = wl.make_workload(name)
+    rows = group_edge_rows(x.shape[1], rows_pg)
+    print(f"{name} full size, oracle on {len(rows)} rows {rows}", flush=True)
     run_and_compare(orc, layers, x, name, trace=False, rows=rows)
+
+
+def test_c3_layer_at_256_rows_on_the_32_row_kernel(orc):
+    """The peephole + layer norm + projection layer of C3 at B = 256 with option
+    "rows16" off: eight groups of 32 rows, one per XCD, two statistics rounds per
+    step; first and last row of every group compared."""
+    flags = wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION
+    print("C3 layer, B=256, rows16=0", flush=True)
+    layers, x = wl.make_custom([640], 2048, 640, flags, 256, 4, seed=91, weight_param=0.03)
+    run_and_compare(orc, layers, x, "c3layer256", trace=False, rows=group_edge_rows(256, 32), options={"rows16": 0})
+
+
+@pytest.mark.parametrize("case", [
+    # (inputs, N, H, flags, B, T): batches beyond 32 rows x the groups of one launch at a k depth below 32
+    # take two row tiles (64 rows) per group; the last group is ragged, its second tile empty
+    ([64], 1024, 512, wl.LAYER_NORM | wl.PROJECTION, 520, 3),
+    ([64], 512, 512, 0, 1100, 3),
+    ([64], 512, 512, wl.LAYER_NORM | wl.PEEPHOLE, 1090, 3),
+])
+def test_two_row_tiles_per_group(orc, case):
+    import torch
+
+    inputs, N, H, flags, B, T = case
+    print(f"two row tiles: N={N} H={H} flags={flags} B={B}", flush=True)
+    layers, x = wl.make_custom(inputs, N, H, flags, B, T, seed=N + B, weight_param=0.04)
+    last0 = (B - 1) // 64 * 64  # first row of the last group
+    rows = sorted({0, 31, 32, 63, 64, 95, 96, 127, last0 - 64, last0 - 33, last0 - 32, last0 - 1, last0, B - 1})
+    lib_model, y = run_and_compare(orc, layers, x, f"rt2_{N}_{B}", trace=False, rows=rows, options={"rows16": 0})
+    lib_model.profile_begin()
+    lib_model.forward(torch.zeros((T, B, inputs[0]), dtype=torch.int8, device="cuda"))
+    prof = lib_model.profile_end()
+    assert prof["recurrent"]["launches"] == 1 and prof["cell"]["launches"] == 0, prof  # one launch: 64 rows per group
+
+
+@pytest.mark.parametrize("rows16", [1, 0])
+@pytest.mark.parametrize("flags", [wl.LAYER_NORM | wl.PROJECTION, wl.CIFG | wl.LAYER_NORM | wl.PEEPHOLE,
+                                   wl.PEEPHOLE | wl.PROJECTION])
+def test_persistent_path_every_step_and_layer(orc, flags, rows16):
+    """The persistent kernels dump no intermediate tensors, so their state is
+    checked step by step instead: the sequence runs as one-step calls with h and c
+    carried in the state buffers, and after every call the h and c of EVERY layer
+    are compared with the oracle's traces of that layer at that step."""
+    import torch
+
+    print(f"every step and layer: flags={flags} rows16={rows16}", flush=True)
+    H = 136 if flags & wl.PROJECTION else 200
+    layers, x = wl.make_custom([72, H, H], 200, H, flags, 37, 6, seed=flags + 71, weight_param=0.08)
+    lib_model, orc_model, xq = prepare_both(orc, layers, x)
+    lib_model.set_option("rows16", rows16)
+    T, B, _ = xq.shape
+    dims = lib_model.dims()
+    traces = [orc.forward(orc_model, xq, trace_layer=l)[1] for l in range(len(layers))]
+    want_y = orc.forward(orc_model, xq)
+    hs = torch.cat([torch.full((B * d[2],), lib_model.get_quant(l)["zp_h"], dtype=torch.int8)
+                    for l, d in enumerate(dims)]).cuda()
+    cs = torch.zeros(sum(B * d[1] for d in dims), dtype=torch.int16).cuda()
+    xd = torch.from_numpy(xq).cuda()
+    lib_model.profile_begin()
+    for t in range(T):
+        y = lib_model.forward(xd[t:t + 1].contiguous(), h_state=hs, c_state=cs)
+        torch.cuda.synchronize()
+        assert_equal(f"y[{t}]", y.cpu().numpy()[0], want_y[t])
+        h_np, c_np = hs.cpu().numpy(), cs.cpu().numpy()
+        ho = co = 0
+        for l, (I, N, Hl) in enumerate(dims):
+            assert_equal(f"h[{t}] layer {l}", h_np[ho:ho + B * Hl].reshape(B, Hl), traces[l]["h"][t])
+            assert_equal(f"c[{t}] layer {l}", c_np[co:co + B * N].reshape(B, N), traces[l]["c"][t])
+            ho, co = ho + B * Hl, co + B * N
+    prof = lib_model.profile_end()
+    assert prof["cell"]["launches"] == 0 and prof["recurrent"]["launches"] == T * len(layers), prof
+    assert lib_model.device_status() == 0
 
 
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
@@ -85,13 +166,13 @@ def test_benchmark_configs_take_the_persistent_path(name):
     budget at C4 is within a KB of the limit): no per-step cell kernel may run."""
     import torch
 
-    from paper_2101_05453_amd import binding, calibration
+    from paper_2101_05453_amd import binding
+    from parity_util import calibrate_on_gpu
 
     layers, x = wl.make_workload(name, batch=None, steps=2, num_layers=2 if name == "C4" else None)
-    calibration.collect_statistics(layers, x)
+    xf = calibrate_on_gpu(layers, x)
     model = binding.prepare(layers, device=0)
-    q0 = model.get_quant(0)
-    xd = torch.from_numpy(calibration.quantize_input(x, q0["s_x"], q0["zp_x"])).cuda()
+    xd = model.quantize_input(xf)
     model.profile_begin()
     model.forward(xd)
     prof = model.profile_end()
@@ -238,10 +319,11 @@ def test_small_shifts(orc):
     above, i.e. rescale shifts below 33, where the one-product form of rescale
     pre-shifts (and clamps) its operand."""
     print("small shifts", flush=True)
-    from paper_2101_05453_amd import binding, calibration
+    from paper_2101_05453_amd import binding
+    from parity_util import calibrate_on_gpu
 
     layers, x = wl.make_custom([48], 128, 128, wl.PEEPHOLE, 40, 6, seed=77, weight_param=0.6)
-    calibration.collect_statistics(layers, x)
+    calibrate_on_gpu(layers, x)
     q = binding.prepare(layers, device=0).get_quant(0)
     shifts = [31 - e for e in q["ex"] + q["eh"]]
     assert min(shifts) < 33, shifts
@@ -254,16 +336,19 @@ def test_saturating_ranges(orc):
 
     layers, x = wl.make_custom([64], 128, 64, wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION, 8, 6, seed=5,
                                weight_param=0.3)
-    from paper_2101_05453_amd import binding, calibration
+    from paper_2101_05453_amd import binding
+    from parity_util import calibrate_on_gpu
 
-    calibration.collect_statistics(layers, x)
+    xf = calibrate_on_gpu(layers, x)
     s = layers[0]
     s.g_absmax = [v * 0.05 for v in s.g_absmax]
     s.m_min, s.m_max, s.h_min, s.h_max, s.c_absmax = -0.02, 0.03, -0.05, 0.02, 0.4
     lib_model = binding.prepare(layers, device=0)
     orc_model = orc.prepare(layers)
-    q0 = lib_model.get_quant(0)
-    xq = calibration.quantize_input(x * 4, q0["s_x"], q0["zp_x"])
+    q0 = orc_model.layer(0)
+    xq = lib_model.quantize_input((xf * 4).contiguous()).cpu().numpy()  # features beyond the calibrated range
+    assert xq.min() == -128 and xq.max() == 127
+    assert_equal("sat.xq", xq, orc.quantize_input(x * np.float32(4), q0["s_x"], q0["zp_x"]))
     y, gtr = lib_model.forward(torch.from_numpy(xq).cuda(), trace_layer=0)
     torch.cuda.synchronize()
     yo, otr = orc.forward(orc_model, xq, trace_layer=0)

@@ -442,10 +442,10 @@ def test_reverse_direction_runs_backward_in_time(orc):
     changing x[0] leaves y[1:] alone, changing x[T-1] reaches y[0]; and with one
     step the two directions coincide."""
     import lstm_workloads as wl
-    from paper_2101_05453_amd import calibration
+    import float_reference
 
     layers, x = wl.make_custom([12], 16, 16, wl.LAYER_NORM, 3, 6, seed=4)
-    calibration.collect_statistics(layers, x)
+    float_reference.collect_statistics(layers, x)
     model = orc.prepare(layers)
     q = model.layer(0)
     xq = orc.quantize_input(x, q["s_x"], q["zp_x"])

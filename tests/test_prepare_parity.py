@@ -5,7 +5,8 @@ import numpy as np
 import pytest
 
 import lstm_workloads as wl
-from paper_2101_05453_amd import binding, calibration
+import float_reference
+from paper_2101_05453_amd import binding
 
 VARIANTS = [0, wl.LAYER_NORM, wl.PEEPHOLE, wl.PROJECTION, wl.CIFG,
             wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION, wl.CIFG | wl.LAYER_NORM,
@@ -26,7 +27,7 @@ def assert_same_quant(a, b):
 def test_prepare_matches_oracle_on_variants(orc, flags):
     H = 24 if flags & wl.PROJECTION else 56
     layers, x = wl.make_custom([36, H], 56, H, flags, 4, 12, seed=flags + 3, weight_param=0.2)
-    calibration.collect_statistics(layers, x)
+    float_reference.collect_statistics(layers, x)
     lib_model = binding.prepare(layers, device=-1)
     orc_model = orc.prepare(layers)
     for l in range(2):
@@ -37,27 +38,41 @@ def test_prepare_matches_oracle_on_variants(orc, flags):
 def test_prepare_matches_oracle_on_benchmark_configs(orc, name):
     T = {"C1": 20, "C2": 20, "C3": 6, "C4": 4, "C5": 4}[name]
     layers, x = wl.make_workload(name, batch=2 if name != "C1" else 1, steps=T)
-    calibration.collect_statistics(layers, x)
+    float_reference.collect_statistics(layers, x)
     lib_model = binding.prepare(layers, device=-1)
     orc_model = orc.prepare(layers)
     for l in range(len(layers)):
         assert_same_quant(lib_model.get_quant(l), orc_model.layer(l))
 
 
-def test_calibration_harness_matches_oracle_float_lstm(orc):
-    """The harness's statistics run and the oracle's double LSTM see the same
+def test_float_reference_matches_oracle_float_lstm(orc):
+    """The PyTorch statistics run and the oracle's double LSTM see the same
     ranges (different summation orders: equal to rounding)."""
     for flags in (0, wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION, wl.CIFG | wl.LAYER_NORM | wl.PEEPHOLE):
         layers, x = wl.make_custom([20, 12 if flags & wl.PROJECTION else 32], 32, 12, flags, 3, 15,
                                    seed=flags, weight_param=0.3)
-        st = calibration.collect_statistics(layers, x)
+        st = float_reference.collect_statistics(layers, x)
         _, so = orc.float_forward(layers, x)
         for a, b in zip(st, so):
             for k in a:
                 assert np.allclose(a[k], b[k], rtol=1e-9, atol=1e-12), (flags, k, a[k], b[k])
 
 
-def test_input_quantization_matches_oracle(orc):
-    x = np.random.default_rng(0).normal(0, 2, size=(5, 3, 7)).astype(np.float32)
-    for s, zp in ((0.031, -3), (0.5, 100), (0.0011, -128)):
-        assert (calibration.quantize_input(x, s, zp) == orc.quantize_input(x, s, zp)).all()
+def test_oracle_input_quantization_hand_computed(orc):
+    """oracle.quantize_input against codes worked out by hand from the affine map of
+    Sec. 3.2.4, q = clamp(floor(v / s + 1/2) + zp, -128, 127): real 0 maps to the zero
+    point, ties go toward +infinity on both sides of zero, both clamps are reached."""
+    s, zp = 0.5, 3
+    #            v:  0.0  0.25  -0.25  -0.75  0.74  0.76  100.0  -100.0  62.0  62.25  -65.5  -65.75
+    v = np.array([0.0, 0.25, -0.25, -0.75, 0.74, 0.76, 100.0, -100.0, 62.0, 62.25, -65.5, -65.75], np.float32)
+    # v/s + 1/2:     0.5  1.0    0.0   -1.0   1.98  2.02  200.5  -199.5  124.5 125.0  -130.5 -131.0
+    # floor + zp:    3    4      3      2     4     5     203    -197    127   128    -128   -128
+    want = np.array([3, 4, 3, 2, 4, 5, 127, -128, 127, 127, -128, -128], np.int8)
+    got = orc.quantize_input(v, s, zp)
+    assert got.dtype == np.int8 and (got == want).all(), (got, want)
+    # zero point at the lower clamp
+    s, zp = 0.25, -128
+    v = np.array([0.0, 0.125, 0.1249, 63.75, 63.9, -0.126], np.float32)
+    # v/s + 1/2:  0.5  1.0  0.9996  255.5  256.1  -0.004
+    want = np.array([-128, -127, -128, 127, 127, -128], np.int8)
+    assert (orc.quantize_input(v, s, zp) == want).all()
