@@ -206,6 +206,29 @@ int lstm_int_forward(const lstm_int_model *model, const int8_t *x, int32_t T,
                      const lstm_int_trace *trace);
 
 /*
+ * lstm_int_forward for callers that cannot allocate device memory and have no
+ * workspace to pass: code under HIP graph capture, tight serving loops with
+ * small T and B (one step per call, state carried), harnesses that forbid
+ * hipMalloc.  Same arguments, results and rules as lstm_int_forward without a
+ * trace, but the workspace is a fixed array of
+ * LSTM_INT_STATIC_WORKSPACE_BYTES inside the library's device image (one copy
+ * per GPU, held until the process ends; its address on the model's device is
+ * looked up when the model is prepared).  The call itself allocates and frees
+ * nothing on host or device.
+ * LSTM_INT_E_WORKSPACE: lstm_int_workspace_bytes(model, T, B) exceeds
+ * LSTM_INT_STATIC_WORKSPACE_BYTES (nothing is enqueued).
+ * LSTM_INT_E_INVALID_ARG also while a profile is being recorded.
+ * Every call on a GPU, from any model, shares that GPU's array: the call
+ * clears what it needs cleared itself and depends on nothing an earlier call
+ * left there, but calls that overlap in time on one GPU (different streams or
+ * threads) race on it and must be serialized by the caller.
+ */
+#define LSTM_INT_STATIC_WORKSPACE_BYTES (32u << 20)
+int lstm_int_forward_static(const lstm_int_model *model, const int8_t *x, int32_t T,
+                            int32_t B, int8_t *y, int8_t *h_state, int16_t *c_state,
+                            void *hip_stream);
+
+/*
  * Options of the online phase.  One selects what is computed:
  *   "reverse": 1 = every layer runs its recursion (eqs. 1-7) from time T - 1
  *           down to 0, i.e. the stack applied to the time-reversed sequence,

@@ -17,6 +17,7 @@ OK = 0
 E_INVALID_ARG, E_UNSUPPORTED, E_BAD_RANGE, E_OUT_OF_MEMORY, E_DEVICE, E_WORKSPACE = -1, -2, -3, -4, -5, -6
 K_INPUT_GEMM, K_RECURRENT, K_CELL, K_PROJECTION, K_OTHER, K_COUNT = 0, 1, 2, 3, 4, 5
 KERNEL_CLASSES = ("input_gemm", "recurrent", "cell", "projection", "other")
+STATIC_WORKSPACE_BYTES = 32 << 20  # LSTM_INT_STATIC_WORKSPACE_BYTES
 
 _fp = C.POINTER(C.c_float)
 
@@ -101,6 +102,9 @@ def lib():
         L.lstm_int_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
                                        C.POINTER(Trace)]
+        L.lstm_int_forward_static.restype = C.c_int
+        L.lstm_int_forward_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p]
         L.lstm_int_set_option.restype = C.c_int
         L.lstm_int_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
         L.lstm_int_device_status.restype = C.c_int
@@ -262,6 +266,21 @@ class Model:
         _check(lib().lstm_int_forward(self._h, x_ptr, T, B, y_ptr, h_ptr, c_ptr, ws_ptr, ws_bytes,
                                       stream_ptr, C.byref(trace) if trace is not None else None),
                "lstm_int_forward")
+
+    # lstm_int_forward_static on torch device tensors (y must be given: the call allocates nothing)
+    def forward_static(self, x, y, h_state=None, c_state=None):
+        import torch
+
+        assert x.is_cuda and x.dtype == torch.int8 and x.is_contiguous()
+        assert y.is_cuda and y.dtype == torch.int8 and y.is_contiguous()
+        T, B, _ = x.shape
+        assert tuple(y.shape) == (T, B, self.dims()[-1][2])
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+        _check(lib().lstm_int_forward_static(self._h, x.data_ptr(), T, B, y.data_ptr(),
+                                             h_state.data_ptr() if h_state is not None else None,
+                                             c_state.data_ptr() if c_state is not None else None, stream),
+               "lstm_int_forward_static")
+        return y
 
     # lstm_int_forward on torch device tensors
     def forward(self, x, y=None, h_state=None, c_state=None, workspace=None, trace_layer=None):

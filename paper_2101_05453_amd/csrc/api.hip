@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -15,7 +16,27 @@
 
 using namespace lstm_int;
 
+// Workspace of lstm_int_forward_static: lives in the library's device image, one copy per GPU from the
+// moment the image is loaded there until the process ends.  Host code never uses this name as an address
+// (on the host it is only a handle for hipGetSymbolAddress); kernels get the per-device pointer below.
+static __device__ __align__(256) unsigned char scratch[LSTM_INT_STATIC_WORKSPACE_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, looked up once per device
+
+// Looks up (once per device, with that device current) where `scratch` lives on `device`.
+int scratch_lookup(int device) {
+  if (device < 0 || device >= kMaxDevices) return LSTM_INT_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device]) return LSTM_INT_OK;
+  void *ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LSTM_INT_E_DEVICE;
+  g_scratch_ptr[device] = ptr;
+  return LSTM_INT_OK;
+}
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -432,7 +453,7 @@ int upload(lstm_int_model *m) {
   m->sh_sig3 = sh_sig;
   m->sh_tanh3 = sh_tab[3];
   if (rec_init() != hipSuccess || rec16_init() != hipSuccess || in_gemm_init() != hipSuccess) return LSTM_INT_E_DEVICE;
-  return LSTM_INT_OK;
+  return scratch_lookup(m->device);  // the device is current here
 }
 
 }  // namespace
@@ -813,6 +834,19 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
   }
   flush_pending();
   return hipGetLastError() == hipSuccess ? LSTM_INT_OK : LSTM_INT_E_DEVICE;
+}
+
+int lstm_int_forward_static(const lstm_int_model *m, const int8_t *x, int32_t T, int32_t B, int8_t *y,
+                            int8_t *h_state, int16_t *c_state, void *hip_stream) {
+  if (!m || T < 0 || B < 0) return LSTM_INT_E_INVALID_ARG;
+  if (m->device < 0 || m->device >= kMaxDevices) return LSTM_INT_E_DEVICE;
+  if (m->prof.on) return LSTM_INT_E_INVALID_ARG;  // per-kernel timing creates events
+  if (T == 0 || B == 0) return LSTM_INT_OK;
+  if ((int64_t)T * B > (int64_t)1 << 30) return LSTM_INT_E_UNSUPPORTED;
+  if (plan_workspace(m, T, B).total > (size_t)LSTM_INT_STATIC_WORKSPACE_BYTES) return LSTM_INT_E_WORKSPACE;
+  void *ws = g_scratch_ptr[m->device];  // set when the model was prepared on this device
+  if (!ws) return LSTM_INT_E_DEVICE;
+  return lstm_int_forward(m, x, T, B, y, h_state, c_state, ws, LSTM_INT_STATIC_WORKSPACE_BYTES, hip_stream, nullptr);
 }
 
 int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
