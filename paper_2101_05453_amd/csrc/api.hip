@@ -106,6 +106,12 @@ struct lstm_int_model {
   int reverse = 0;  // 1: the recursion runs from time T - 1 down to 0
   int cooperative = 0;  // 1: the persistent kernel is launched cooperatively
   int rows16 = 1;       // 1: batches that fit one launch of the 16-row kernel take it
+  int stack = 1;        // stacked launch (one layer per XCD): 0 never, 1 where it is expected to be faster, 2 wherever it can run
+  int flag_sleep = 2;   // stacked launch: pause between two polls of the layer below's flag, x 64 clocks
+  double stack_step_us = 16.0;  // expected time of one (step, row tile) item of the stacked launch
+  bool stackable = false;            // every layer equal (and eligible): the stacked kernel can run the model
+  int stack_ks = 0;
+  const StackLayer *stack_layers = nullptr;  // [L] in the arena
   int spin_limit = 1 << 21;
   int poll_sleep = 0, stats_sleep = 0;  // pauses between polls, in units of 64 clocks
   int idle_sleep = 64, idle_poll_sleep = 12;
@@ -161,6 +167,52 @@ Workspace plan_workspace(const lstm_int_model *m, int64_t T, int64_t B) {
   w.m2 = take((size_t)T * round_up(B, 32) * maxNpadp);
   w.total = off;
   return w;
+}
+
+// Workspace of a stacked launch: the sequential regions are not needed then, so the two layouts overlay.
+struct StackPlan {
+  size_t out, h0, mbuf, c, xpad, sync, total;
+  size_t out_stride, mbuf_stride;
+};
+StackPlan plan_stack(const lstm_int_model *m, int64_t T, int64_t B) {
+  const LayerHost &h = m->host[0];
+  const int64_t L = (int64_t)m->host.size(), Hpad = round_up(h.H, 128), Bp = round_up((int)B, 32);
+  StackPlan w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += align256(bytes);
+    return o;
+  };
+  w.out_stride = align256(((size_t)T * B + 32) * Hpad);
+  w.out = take(w.out_stride * L);
+  w.h0 = take((size_t)L * B * Hpad);
+  w.mbuf_stride = h.projection() ? align256((size_t)T * Bp * round_up(h.N, 128)) : 0;
+  w.mbuf = take(w.mbuf_stride * L);
+  w.c = take((size_t)L * B * h.N * 2);
+  w.xpad = take(((size_t)T * B + 32) * round_up(h.I, 64));
+  w.sync = take(kSyncBytes);
+  w.total = off;
+  return w;
+}
+
+// Whether forward runs T steps of B rows as one stacked launch (a function of the model, its options, T
+// and B only: lstm_int_workspace_bytes and lstm_int_forward must agree).
+bool stack_chosen(const lstm_int_model *m, int64_t T, int64_t B) {
+  if (!m->stackable || m->stack == 0 || m->path == 1 || m->reverse) return false;
+  int ks = 0;
+  const LayerHost &h = m->host[0];
+  const int L = (int)m->host.size();
+  if (!stack_supported(h.N, h.H, (int)h.flags, m->dev[0].Ipad, L, (int)T, (int)B, &ks) || ks != m->stack_ks) return false;
+  if (131072 + (size_t)L * ((B + 31) / 32) * 128 > kSyncBytes) return false;  // flags behind the statistics words
+  if (m->stack == 2) return true;
+  // Expected time of the two ways, in microseconds (measured step times of the C4 layer shape; the launches
+  // one after the other pay about 30 us per layer for the input GEMM launch and the weight prologue, the
+  // stacked launch walks the row tiles of a step one after the other).
+  const double tiles = (double)((B + 31) / 32);
+  const double seq = L * (30.0 + T * (B <= 128 ? 9.0 : 11.0 * ((B + 255) / 256)));
+  const double stk = 20.0 + (T + L - 1) * tiles * m->stack_step_us;
+  return stk < seq;
 }
 
 Requant make_requant(const int32_t *M, const int32_t *e, int first, int count, int cols_per_gate,
@@ -435,6 +487,39 @@ int upload(lstm_int_model *m) {
       d.rq_h = make_requant(h.Mh, h.eh, first, h.G, h.N, 0);
       if (h.projection()) d.rq_p = make_requant(&h.Mp, &h.ep, 0, 1, 1 << 28, h.zp_h);
     }
+    {  // constants of the stacked kernel, one record per layer (filled when every layer has its tile-ordered copies)
+      const size_t oStack = take(L * sizeof(StackLayer));
+      if (pass) {
+        bool all = true;
+        for (size_t l = 0; l < L; ++l) all = all && m->dev[l].p2 && m->dev[l].W2f;
+        if (all) {
+          StackLayer *recs = reinterpret_cast<StackLayer *>(image.data() + oStack);
+          for (size_t l = 0; l < L; ++l) {
+            const LayerHost &h = m->host[l];
+            const LayerDev &d = m->dev[l];
+            StackLayer &r = recs[l];
+            memset(&r, 0, sizeof(r));
+            r.R2 = d.R2; r.W2f = d.W2f; r.bx2 = d.bx2; r.bh4 = d.bh4; r.Lq4 = d.Lq4; r.qb4 = d.qb4; r.Pq3 = d.Pq3;
+            r.Wp2 = d.Wp2; r.bp2 = d.bp2;
+            r.tanhc_tab = d.tanhc; r.tanhc_blob = d.tanhc_blob; r.sh_tanhc = d.sh_tanhc;
+            r.kx = d.Ipad / 32;
+            r.pre_x = r.pre_h = 0;
+            for (int g = 0; g < 4; ++g) {
+              const int sg = g < 4 - h.G ? 4 - h.G : g;  // an absent gate borrows valid numbers; its rows are zero
+              r.Mx[g] = h.Mx[sg]; r.rx[g] = 31 - h.ex[sg];
+              r.Mh[g] = h.Mh[sg]; r.rh[g] = 31 - h.eh[sg];
+              r.Mln[g] = h.Mln[sg]; r.rln[g] = 31 - h.eln[sg];
+              r.pre_x = std::max(r.pre_x, preshift_mode(r.rx[g], d.amax_x[sg]));
+              r.pre_h = std::max(r.pre_h, preshift_mode(r.rh[g], d.amax_h[sg]));
+            }
+            for (int j = 0; j < 3; ++j) { r.Mc[j] = h.Mc[j]; r.rc[j] = 31 - h.ec[j]; }
+            r.Mm = h.Mm; r.rm = 31 - h.em; r.zp_m = h.zp_m;
+            r.Mp = h.Mp; r.rp = 31 - h.ep; r.zp_h = h.zp_h; r.m_c = h.m_c;
+          }
+          m->stack_layers = reinterpret_cast<const StackLayer *>(static_cast<uint8_t *>(m->arena) + oStack);
+        }
+      }
+    }
     if (!pass) {
       image.assign(off, 0);
       if (hipMalloc(&m->arena, off) != hipSuccess) {
@@ -452,7 +537,28 @@ int upload(lstm_int_model *m) {
   m->tanh3_blob = dbase + blob_off[3];
   m->sh_sig3 = sh_sig;
   m->sh_tanh3 = sh_tab[3];
-  if (rec_init() != hipSuccess || rec16_init() != hipSuccess || in_gemm_init() != hipSuccess) return LSTM_INT_E_DEVICE;
+  if (rec_init() != hipSuccess || rec16_init() != hipSuccess || in_gemm_init() != hipSuccess || stack_init() != hipSuccess)
+    return LSTM_INT_E_DEVICE;
+  // The stacked kernel runs models whose layers are all alike (same cells, width and variant; every layer
+  // above the first reads the layer below), up to 8 of them, within the shift and table limits of the
+  // persistent kernels.
+  m->stackable = false;
+  if (m->stack_layers && L >= 2 && L <= 8) {
+    const LayerHost &h0 = m->host[0];
+    bool ok = stack_supported(h0.N, h0.H, (int)h0.flags, m->dev[0].Ipad, (int)L, 1, 1, &m->stack_ks);
+    auto shift_ok = [](int r) { return r >= 3 && r <= 62; };
+    for (size_t l = 0; l < L && ok; ++l) {
+      const LayerHost &h = m->host[l];
+      const LayerDev &d = m->dev[l];
+      ok = h.N == h0.N && h.H == h0.H && h.flags == h0.flags && (l == 0 || h.I == h0.H) && d.ks == m->stack_ks &&
+           shift_ok(31 - h.em) && (!h.projection() || shift_ok(31 - h.ep)) && sh_sig >= 0 && sh_tab[3] >= 0 &&
+           d.sh_tanhc >= 0;
+      for (int g = 4 - h.G; g < 4 && ok; ++g)
+        ok = shift_ok(31 - h.ex[g]) && shift_ok(31 - h.eh[g]) && (!h.layer_norm() || shift_ok(31 - h.eln[g]));
+      for (int j = 4 - h.G; j < 3 && ok; ++j) ok = !h.peephole() || shift_ok(31 - h.ec[j]);
+    }
+    m->stackable = ok;
+  }
   return scratch_lookup(m->device);  // the device is current here
 }
 
@@ -523,8 +629,90 @@ int lstm_int_quantize_input(const lstm_int_model *m, const float *x, int64_t n, 
 size_t lstm_int_workspace_bytes(const lstm_int_model *m, int32_t T, int32_t B) {
   if (!m || T < 0 || B < 0 || m->host.empty()) return 0;
   if (T == 0 || B == 0) return 256;
-  return plan_workspace(m, T, B).total;
+  // a call with a trace runs the layers one after the other, so that layout always has to fit
+  const size_t seq = plan_workspace(m, T, B).total;
+  return m->device >= 0 && stack_chosen(m, T, B) ? std::max(seq, plan_stack(m, T, B).total) : seq;
 }
+
+}  // extern "C"
+
+namespace {
+
+// All layers in one launch (stack_kernel.inc.h).  The caller has checked stack_chosen and the workspace size.
+int forward_stack(lstm_int_model *m, const int8_t *x, int32_t T, int32_t B, int8_t *y, int8_t *h_state,
+                  int16_t *c_state, uint8_t *wsb, hipStream_t s) {
+  const StackPlan sp = plan_stack(m, T, B);
+  const LayerHost &h = m->host[0];
+  const LayerDev &d = m->dev[0];
+  const int L = (int)m->host.size();
+  const int TB = T * B;
+  // the first layer reads x in place when its rows are 64-byte multiples and 16-byte aligned
+  const int8_t *in = x;
+  int ld_in = h.I;
+  if ((h.I & 63) || (reinterpret_cast<uintptr_t>(x) & 15)) {
+    Timed t(m->prof, s, LSTM_INT_K_OTHER);
+    int8_t *xp = reinterpret_cast<int8_t *>(wsb + sp.xpad);
+    launch_copy_rows_i8(s, x, h.I, xp, d.Ipad, TB, h.I, 0);
+    in = xp;
+    ld_in = d.Ipad;
+  }
+  StackArgs sa;
+  memset(&sa, 0, sizeof(sa));
+  RecArgs &ra = sa.c;
+  ra.T = T; ra.B = B; ra.N = h.N; ra.H = h.H; ra.Hpad = d.Hpad; ra.flags = (int)h.flags; ra.m_c = h.m_c;
+  ra.GS = d.GS; ra.groups = L; ra.rows_pg = 32; ra.ks = d.ks; ra.Ncp = d.Ncp; ra.Bp = round_up(B, 32);
+  ra.sig_tab = m->sig3; ra.tanh_tab = m->tanh3; ra.sig_blob = m->sig3_blob; ra.tanh_blob = m->tanh3_blob;
+  ra.sh_sig = m->sh_sig3; ra.sh_tanh = m->sh_tanh3;
+  // LDS budget: the cell-format tanh table of every layer shares the gate table's place or has its own
+  ra.tanhc_blob = m->tanh3_blob;
+  for (int l = 0; l < L; ++l)
+    if (m->dev[l].tanhc_blob != m->tanh3_blob) ra.tanhc_blob = m->dev[l].tanhc_blob;
+  ra.ptiles = d.ptiles; ra.npadp = d.npadp;
+  ra.y = y;
+  ra.counters = reinterpret_cast<unsigned *>(wsb + sp.sync);
+  ra.tickets = m->cooperative ? nullptr : reinterpret_cast<unsigned long long *>(ra.counters + 2);
+  ra.acc = reinterpret_cast<unsigned long long *>(wsb + sp.sync + 256 * 64 * 4);
+  ra.status = m->status;
+  ra.spin_limit = m->spin_limit;
+  ra.poll_sleep = m->poll_sleep; ra.stats_sleep = m->stats_sleep; ra.idle_sleep = m->idle_sleep;
+  ra.stats_first_sleep = m->stats_first_sleep;
+  ra.sync_sleep = m->sync_sleep >= 0 ? m->sync_sleep : (d.GS >= 16 ? 16 : 4);
+  ra.idle_poll_sleep = m->idle_poll_sleep;
+  sa.layers = m->stack_layers;
+  sa.L = L;
+  sa.row_tiles = (B + 31) / 32;
+  sa.x = in; sa.ldx = ld_in; sa.x_shared = 1;
+  sa.out_base = reinterpret_cast<int8_t *>(wsb + sp.out); sa.out_stride = sp.out_stride;
+  sa.h0_base = reinterpret_cast<const int8_t *>(wsb + sp.h0);
+  sa.mbuf_base = reinterpret_cast<int8_t *>(wsb + sp.mbuf); sa.mbuf_stride = sp.mbuf_stride;
+  sa.c_base = c_state ? c_state : reinterpret_cast<int16_t *>(wsb + sp.c);
+  sa.c_given = c_state != nullptr;
+  sa.h_final = h_state;
+  const size_t flags_off = 131072;  // behind the counters and the statistics words of 8 groups
+  sa.flags = reinterpret_cast<unsigned *>(wsb + sp.sync + flags_off);
+  sa.flag_sleep = m->flag_sleep;
+  if (stack_lds_bytes(sa) > 160 * 1024) return LSTM_INT_E_UNSUPPORTED;
+  {
+    Timed t(m->prof, s, LSTM_INT_K_OTHER);
+    StackInit si;
+    memset(&si, 0, sizeof(si));
+    si.h_src = h_state; si.h0 = reinterpret_cast<int8_t *>(wsb + sp.h0); si.ld_h0 = d.Hpad; si.rows = B; si.cols = h.H;
+    si.L = L;
+    for (int l = 0; l < L; ++l) si.zp[l] = m->host[l].zp_h;
+    si.sync = reinterpret_cast<int4 *>(wsb + sp.sync);
+    si.sync_vec = (long long)((flags_off + (size_t)L * sa.row_tiles * 128 + 15) / 16);
+    launch_stack_init(s, si);
+  }
+  {
+    Timed t(m->prof, s, LSTM_INT_K_RECURRENT);
+    if (launch_stack(s, sa, m->cooperative != 0) != hipSuccess) return LSTM_INT_E_DEVICE;
+  }
+  return hipGetLastError() == hipSuccess ? LSTM_INT_OK : LSTM_INT_E_DEVICE;
+}
+
+}  // namespace
+
+extern "C" {
 
 int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32_t B, int8_t *y,
                      int8_t *h_state, int16_t *c_state, void *workspace, size_t workspace_bytes,
@@ -538,11 +726,17 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
   if (trace && (trace->layer < 0 || trace->layer >= L)) return LSTM_INT_E_INVALID_ARG;
   if ((int64_t)T * B > (int64_t)1 << 30) return LSTM_INT_E_UNSUPPORTED;
   const Workspace ws = plan_workspace(m, T, B);
-  if (workspace_bytes < ws.total || (reinterpret_cast<uintptr_t>(workspace) & 255))
+  if (workspace_bytes < lstm_int_workspace_bytes(m, T, B) || (reinterpret_cast<uintptr_t>(workspace) & 255))
     return LSTM_INT_E_WORKSPACE;
   if (hipSetDevice(m->device) != hipSuccess) return LSTM_INT_E_DEVICE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   uint8_t *wsb = static_cast<uint8_t *>(workspace);
+  // every layer alike, no dump asked for: all layers in one launch, one layer per XCD, where that is faster
+  if (!trace && stack_chosen(m, T, B) && (reinterpret_cast<uintptr_t>(y) & 3) == 0 &&
+      (reinterpret_cast<uintptr_t>(h_state) & 3) == 0 && (reinterpret_cast<uintptr_t>(c_state) & 1) == 0) {
+    const int rc = forward_stack(m, x, T, B, y, h_state, c_state, wsb, s);
+    if (rc != LSTM_INT_E_UNSUPPORTED) return rc;  // the LDS budget did not fit: the layers run one after the other
+  }
   int16_t *tx = reinterpret_cast<int16_t *>(wsb + ws.tx);
   int16_t *th = reinterpret_cast<int16_t *>(wsb + ws.th);
   int8_t *mbuf = reinterpret_cast<int8_t *>(wsb + ws.mbuf);
@@ -864,6 +1058,21 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
   if (!strcmp(key, "rows16")) {
     if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
     m->rows16 = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "stack")) {
+    if (value < 0 || value > 2) return LSTM_INT_E_INVALID_ARG;
+    m->stack = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "flag_sleep")) {
+    if (value < 0 || value > 1024) return LSTM_INT_E_INVALID_ARG;
+    m->flag_sleep = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "stack_step_ns")) {  // expected time of one item of the stacked launch, for the choice between the two ways
+    if (value < 1 || value > 1000000) return LSTM_INT_E_INVALID_ARG;
+    m->stack_step_us = (double)value * 1e-3;
     return LSTM_INT_OK;
   }
   if (!strcmp(key, "reverse")) {

@@ -150,4 +150,73 @@ size_t rec16_lds_bytes(const RecArgs &a);
 hipError_t launch_rec16(hipStream_t s, const RecArgs &a, bool cooperative);
 hipError_t rec16_init();
 
+// ---------------------------------------------------------------------------
+// Stacked layers in one launch (stack_kernel.inc.h): layer l of a stack of up to 8 equal layers runs on
+// XCD l, all at once, each on its own step -- while layer l works on step t, layer l + 1 works on step
+// t - 1 (the layers of Sec. 7's stack are loops over the same cell, and step t of layer l + 1 needs only
+// step t of layer l).  The batch is walked in row tiles of 32, one (step, tile) item after the other.
+// Nothing is hoisted: the W x term of an item is computed when the layer's input for it arrives, with the
+// weights W streamed from memory as MFMA operands (R stays resident in registers as in rec_kernel).
+// A layer's h rows reach the next XCD through stores that write through the L2 and a flag per
+// (layer, row tile) that counts the finished steps.
+struct StackLayer {  // constants of one layer, in device memory (uploaded when the model is prepared)
+  const int4 *R2;       // as RecArgs
+  const int8_t *W2f;    // input weights in MFMA operand order [GS * 8 tiles][kx][64 lanes][16]
+  const int32_t *bx2;   // [GS * 8 tiles][32] folded input bias, tile row order
+  const int32_t *bh4;
+  const int16_t *Lq4;
+  const int32_t *qb4;
+  const int16_t *Pq3;
+  const int8_t *Wp2;
+  const int32_t *bp2;
+  const uint16_t *tanhc_tab;
+  const uint8_t *tanhc_blob;
+  int32_t sh_tanhc;
+  int32_t kx;           // 32-byte k steps of W x (padded input width / 32), at most the kernel's KS
+  int32_t Mx[4], rx[4], pre_x;
+  int32_t Mh[4], rh[4], pre_h;
+  int32_t Mc[3], rc[3];
+  int32_t Mln[4], rln[4];
+  int32_t Mm, rm, zp_m, Mp, rp, zp_h, m_c;
+  int32_t pad_;
+};
+
+struct StackArgs {
+  RecArgs c;                 // shape, options and tables common to the layers (per-layer fields unused)
+  const StackLayer *layers;  // [L]
+  int L;                     // layers in this launch, at most 8
+  int row_tiles;             // ceil(B / 32)
+  const int8_t *x;           // input of the first layer [T * B, ldx]
+  int ldx;
+  int x_shared;              // 1: x was written by an earlier launch (plain loads); layers > 0 always read
+                             // the previous layer's rows with loads that bypass the L2
+  int8_t *out_base;          // layer l writes [T, B, Hpad] at out_base + l * out_stride
+  size_t out_stride;
+  const int8_t *h0_base;     // initial h of layer l, [B, Hpad], at h0_base + l * B * Hpad
+  int8_t *mbuf_base;         // m exchange buffer of layer l at + l * mbuf_stride (projection only)
+  size_t mbuf_stride;
+  int16_t *c_base;           // running cell state of layer l, [B, N], at + l * B * N (the caller's state
+                             // buffer, or workspace)
+  int c_given;               // 0: the cell state starts from zero, 1: from c_base
+  int8_t *h_final;           // NULL, or the caller's h state: layer l's last h, [B, H], at + l * B * H
+  unsigned *flags;           // [L][row_tiles] words 128 bytes apart, zeroed: steps finished
+  int flag_sleep;            // pause between two polls of a flag, x 64 clocks
+};
+
+struct StackInit {
+  const int8_t *h_src;  // NULL, or the caller's h state: layer l is [rows, cols] at + l * rows * cols
+  int8_t *h0;           // [L][rows, ld_h0]
+  int ld_h0, rows, cols, L;
+  int zp[8];            // code of real 0 per layer (h_src == NULL)
+  int4 *sync;           // sync_vec 16-byte words to clear
+  long long sync_vec;
+};
+void launch_stack_init(hipStream_t s, const StackInit &w);
+
+// Whether `L` equal layers of this shape can run as a stack launch; ks = the kernel's k depth.
+bool stack_supported(int N, int H, int flags, int ipad0, int L, int T, int B, int *ks);
+size_t stack_lds_bytes(const StackArgs &a);
+hipError_t launch_stack(hipStream_t s, const StackArgs &a, bool cooperative);
+hipError_t stack_init();
+
 }  // namespace lstm_int
