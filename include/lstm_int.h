@@ -243,6 +243,19 @@ int lstm_int_forward_static(const lstm_int_model *model, const int8_t *x, int32_
  *               otherwise one launch per operation and step;
  *           1 = always one launch per operation and step;
  *           2 = same as 0.
+ *   "stack": models whose layers are all alike (same N, H and variant, each
+ *           layer reading the one below; 2 to 8 layers) can run in ONE launch,
+ *           layer l on XCD l, each layer one item (step, tile of 32 rows)
+ *           behind the layer below -- the stack of Sec. 7 as a wavefront over
+ *           layers and time.  Nothing is hoisted then: W x is computed per
+ *           item.  0 = never; 1 (default) = where it is expected to be faster
+ *           than one layer after the other (small batches: one-step calls,
+ *           sequences at up to about 64 rows); 2 = wherever it can run.
+ *           Calls with a trace or with "reverse" run layer after layer.
+ *   "stack_step_ns", "stack_prefetch_kb", "flag_sleep": knobs of the stacked
+ *           launch: expected time of one item (for the choice above), KB of a
+ *           layer's W requested ahead of each item, pause between polls of the
+ *           layer below's progress flag in units of 64 clocks.
  *   "rows16": 1 (default) = batches of up to 16 * 8 * (32 / ceil(N / 64)) rows
  *           run in a variant of the persistent kernel that works on groups of
  *           16 rows (more compute units busy, half the arithmetic per
@@ -275,7 +288,8 @@ int lstm_int_forward_static(const lstm_int_model *model, const int8_t *x, int32_
  *           after a wait gave up; synchronizes the device.
  *   "phase_timing": nonzero makes workgroup 0 of the persistent kernel add the
  *           time it spends in each of its phases to 16 device counters
- *           (diagnostics; read them with lstm_int_phase_ticks).
+ *           (diagnostics; read them with lstm_int_phase_ticks).  In a stacked
+ *           launch the value is 1 + the layer whose workgroup 0 is timed.
  * Unknown keys or values give LSTM_INT_E_INVALID_ARG.
  */
 int lstm_int_set_option(lstm_int_model *model, const char *key, int64_t value);

@@ -108,7 +108,8 @@ struct lstm_int_model {
   int rows16 = 1;       // 1: batches that fit one launch of the 16-row kernel take it
   int stack = 1;        // stacked launch (one layer per XCD): 0 never, 1 where it is expected to be faster, 2 wherever it can run
   int flag_sleep = 2;   // stacked launch: pause between two polls of the layer below's flag, x 64 clocks
-  double stack_step_us = 16.0;  // expected time of one (step, row tile) item of the stacked launch
+  double stack_step_us = 20.5;
+  int stack_prefetch_kb = 2048;  // stacked launch: KB of a layer's W asked for ahead of each W x  // expected time of one (step, row tile) item of the stacked launch
   bool stackable = false;            // every layer equal (and eligible): the stacked kernel can run the model
   int stack_ks = 0;
   const StackLayer *stack_layers = nullptr;  // [L] in the arena
@@ -206,12 +207,14 @@ bool stack_chosen(const lstm_int_model *m, int64_t T, int64_t B) {
   if (!stack_supported(h.N, h.H, (int)h.flags, m->dev[0].Ipad, L, (int)T, (int)B, &ks) || ks != m->stack_ks) return false;
   if (131072 + (size_t)L * ((B + 31) / 32) * 128 > kSyncBytes) return false;  // flags behind the statistics words
   if (m->stack == 2) return true;
-  // Expected time of the two ways, in microseconds (measured step times of the C4 layer shape; the launches
-  // one after the other pay about 30 us per layer for the input GEMM launch and the weight prologue, the
-  // stacked launch walks the row tiles of a step one after the other).
+  // Expected time of the two ways, in microseconds, from the times measured on the 8-layer benchmark stack
+  // (N = 2048, H = 640).  One after the other: about 30 us per layer for the input GEMM launch and the weight
+  // prologue, and 8.1 us per step up to 128 rows, 11 us per 256 rows beyond.  Stacked: every layer walks its
+  // T * tiles items (step, tile of 32 rows) one after the other at about 20.5 us each, one item behind the
+  // layer below.
   const double tiles = (double)((B + 31) / 32);
-  const double seq = L * (30.0 + T * (B <= 128 ? 9.0 : 11.0 * ((B + 255) / 256)));
-  const double stk = 20.0 + (T + L - 1) * tiles * m->stack_step_us;
+  const double seq = L * (30.0 + T * (B <= 128 ? 8.1 : 11.0 * ((B + 255) / 256)));
+  const double stk = 25.0 + (T * tiles + L - 1) * m->stack_step_us;
   return stk < seq;
 }
 
@@ -678,6 +681,7 @@ int forward_stack(lstm_int_model *m, const int8_t *x, int32_t T, int32_t B, int8
   ra.stats_first_sleep = m->stats_first_sleep;
   ra.sync_sleep = m->sync_sleep >= 0 ? m->sync_sleep : (d.GS >= 16 ? 16 : 4);
   ra.idle_poll_sleep = m->idle_poll_sleep;
+  ra.ticks = m->phase_timing ? reinterpret_cast<long long *>(m->status + 16) : nullptr;
   sa.layers = m->stack_layers;
   sa.L = L;
   sa.row_tiles = (B + 31) / 32;
@@ -691,6 +695,13 @@ int forward_stack(lstm_int_model *m, const int8_t *x, int32_t T, int32_t B, int8
   const size_t flags_off = 131072;  // behind the counters and the statistics words of 8 groups
   sa.flags = reinterpret_cast<unsigned *>(wsb + sp.sync + flags_off);
   sa.flag_sleep = m->flag_sleep;
+  sa.tick_layer = std::min(L - 1, std::max(0, m->phase_timing - 1));
+  {
+    // W of a layer is 4 N Ipad bytes, read by the GS workgroups of one XCD through its 4 MB L2: ask ahead for
+    // at most stack_prefetch_kb KB of it per XCD (default 2 MB), spread evenly over the waves
+    const int64_t per_wave = (int64_t)m->stack_prefetch_kb * 8 / ((int64_t)d.GS * 4);
+    sa.prefetch_lines = (int)std::min<int64_t>(per_wave, 16 * (int64_t)(m->dev[L - 1].Ipad / 32));
+  }
   if (stack_lds_bytes(sa) > 160 * 1024) return LSTM_INT_E_UNSUPPORTED;
   {
     Timed t(m->prof, s, LSTM_INT_K_OTHER);
@@ -1065,6 +1076,11 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
     m->stack = (int)value;
     return LSTM_INT_OK;
   }
+  if (!strcmp(key, "stack_prefetch_kb")) {
+    if (value < 0 || value > (1 << 20)) return LSTM_INT_E_INVALID_ARG;
+    m->stack_prefetch_kb = (int)value;
+    return LSTM_INT_OK;
+  }
   if (!strcmp(key, "flag_sleep")) {
     if (value < 0 || value > 1024) return LSTM_INT_E_INVALID_ARG;
     m->flag_sleep = (int)value;
@@ -1089,7 +1105,7 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
     return LSTM_INT_OK;
   }
   if (!strcmp(key, "phase_timing")) {
-    m->phase_timing = value != 0;
+    m->phase_timing = (int)std::min<int64_t>(std::max<int64_t>(value, 0), 64);  // stacked launch: 1 + the layer timed (at most the top one)
     if (m->device >= 0 && hipMemset(m->status + 16, 0, 16 * sizeof(long long)) != hipSuccess)
       return LSTM_INT_E_DEVICE;
     return LSTM_INT_OK;

@@ -201,6 +201,8 @@ struct StackArgs {
   int8_t *h_final;           // NULL, or the caller's h state: layer l's last h, [B, H], at + l * B * H
   unsigned *flags;           // [L][row_tiles] words 128 bytes apart, zeroed: steps finished
   int flag_sleep;            // pause between two polls of a flag, x 64 clocks
+  int tick_layer;            // the layer whose workgroup 0 fills the phase timers (diagnostics)
+  int prefetch_lines;        // 128-byte lines of a wave's slice of W asked for ahead of W x (at most 16 * kx)
 };
 
 struct StackInit {

@@ -46,7 +46,7 @@ size_t stack_lds_bytes(const StackArgs &sa) {
   size_t tile = (((size_t)32 * (a.ks * 32 + 16) + 1023) / 1024 + 1) * 1024;
   if (proj && tile < 4 * 16 * 64 * 4) tile = 4 * 16 * 64 * 4;
   size_t n = tile + (size_t)4 * items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 2 + 4 * 64 * 4 +
-             8 * 32 * 4 + 320 /* StkPrm */ + 16;
+             8 * 32 * 4 + 320 /* StkPrm */ + 16 + 12 * 8;
   n += (a.tanhc_blob != a.tanh_blob ? 3 : 2) * (size_t)kLutBlobBytes;
   if (proj) {
     const int per_cu = (a.ptiles + a.GS - 1) / a.GS;

@@ -117,6 +117,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   int32_t *bxL = reinterpret_cast<int32_t *>(p);         p += 8 * 32 * 4;  // folded input bias, tile row order
   StkPrm *prm = reinterpret_cast<StkPrm *>(p);           p += sizeof(StkPrm);
   int *flag = reinterpret_cast<int *>(p);                p += 16;
+  u64 *tickL = reinterpret_cast<u64 *>(p);               p += 12 * 8;  // phase timers
   const bool share_tanh = sl.tanhc_blob == a.tanh_blob;
   const uint8_t *lutS = p;                               p += kLutBlobBytes;
   const uint8_t *lutT = p;                               p += kLutBlobBytes;
@@ -201,15 +202,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     bpr[0] = b4.x; bpr[1] = b4.y; bpr[2] = b4.z; bpr[3] = b4.w;
   }
   if (tid < items) red[tid] = 0;
+  if (tid < 12) tickL[tid] = 0;
   if (tid == 0) {
     flag[0] = 1;
     flag[1] = 0;
   }
   __syncthreads();
 
+  // optional phase timing (diagnostics): workgroup 0 of one layer, 100 MHz wall clock ticks per phase
+  long long tick_last = 0;
+  const bool timing = a.ticks && layer == sa.tick_layer && member == 0 && tid == 0;
+#define TICK(i)                                                                           \
+  do {                                                                                    \
+    if (timing) {                                                                         \
+      asm volatile("" ::: "memory");                                                      \
+      const long long now = (long long)wall_clock64();                                    \
+      __hip_atomic_fetch_add(&tickL[i], (u64)(now - tick_last), __ATOMIC_RELAXED,         \
+                             __HIP_MEMORY_SCOPE_WORKGROUP);                               \
+      tick_last = now;                                                                    \
+    }                                                                                     \
+  } while (0)
+  if (timing) tick_last = (long long)wall_clock64();
+
   unsigned epoch = 0;
   unsigned *counter = a.counters + layer * 64;
   u64 *accS = a.acc + (size_t)layer * 4 * 256;
+  // The layer's counter and statistics words were cleared by another kernel: a first access would fetch
+  // them from memory in the middle of the first step.  Adding zero brings them into this XCD's L2 now,
+  // while the layers below are still at work.
+  if (tid < items) {
+    __hip_atomic_fetch_add(&accS[0 * 256 + tid], (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_add(&accS[1 * 256 + tid], (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (ph) {
+      __hip_atomic_fetch_add(&accS[2 * 256 + tid], (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(&accS[3 * 256 + tid], (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+  if (tid == 0) __hip_atomic_fetch_add(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   int64_t prevS[2][2] = {{0, 0}, {0, 0}};
   const double inv_n = 1.0 / (double)a.N;
   const int g_first = cifg ? 1 : 0;
@@ -239,19 +268,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
   };
 
+  int32_t creg[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
   for (int it = 0; it < n_items; ++it) {
     const int t = it / RTILES, rtile = it - t * RTILES;
     const int row0 = rtile * 32;
     const int row = row0 + col;
 
-    // ---- cell state of this lane's 8 cells (memory between the items of a row tile)
-    int32_t creg[2][4];
+    // ---- cell state of this lane's 8 cells: in registers from step to step when the batch is one row
+    // tile, in memory between the items of a row tile otherwise
+    if (t == 0 || RTILES > 1) {
 #pragma unroll
-    for (int tl = 0; tl < 2; ++tl) {
-      const int n0 = member * 64 + cell_w + tl * 8;
+      for (int tl = 0; tl < 2; ++tl) {
+        const int n0 = member * 64 + cell_w + tl * 8;
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
-        creg[tl][c] = ((t > 0 || sa.c_given) && row < a.B && n0 + c < a.N) ? cbuf[(size_t)row * a.N + n0 + c] : 0;
+        for (int c = 0; c < 4; ++c)
+          creg[tl][c] = ((t > 0 || sa.c_given) && row < a.B && n0 + c < a.N) ? cbuf[(size_t)row * a.N + n0 + c] : 0;
+      }
     }
 
     // ---- h^{t-1} rows of the tile -> LDS; R h on the MFMA; kept as packed int16 terms
@@ -261,6 +293,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __syncthreads();
+    TICK(0);
+    // The first part of this wave's slice of W (two tiles of kx fragments of 1 KB, contiguous) is asked for
+    // ahead of its use, one word per 128-byte line, so that it is on its way into the L2 while R h runs and
+    // the input is waited for.  Not all of it: a layer's W can be larger than the XCD's L2, and the last
+    // lines would push the first out again before they are used (measured on the 8-layer benchmark stack:
+    // about half of W ahead is best, all of it is as slow as none).
+    constexpr int NPF = (KS * 16 + 63) / 64;
+    unsigned pf[NPF];
+    {
+      const int8_t *w0 = sl.W2f + ((size_t)(member * 8 + wave * 2) * kx) * 1024;
+#pragma unroll
+      for (int i = 0; i < NPF; ++i) {
+        const int line = lane + 64 * i;
+        pf[i] = line < sa.prefetch_lines ? *reinterpret_cast<const unsigned *>(w0 + (size_t)line * 128) : 0u;
+      }
+    }
     int32_t thp[2][8];  // [tile][(4 gate + c) / 2]: low half = even index
     {
       v16i acc[2];
@@ -297,6 +345,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       else
         pack(std::integral_constant<int, 2>{});
     }
+    TICK(1);
 
     // ---- W x^t: weights streamed from memory as MFMA operands, DW k steps ahead per tile
     constexpr int DW = 6;
@@ -330,6 +379,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
     __syncthreads();  // also: every wave has read its h fragments, the tile can be overwritten
     if (flag[0] == 0) return;
+    TICK(2);
     {
       const int8_t *xp = xin + (size_t)t * a.B * ldx;
       if (x_bypass)
@@ -338,8 +388,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         tile_to_lds(xp, ldx, kx * 32, row0, std::false_type{});
       // the x chunks are the youngest NCH loads of this wave; the weight loads ahead of them are done then too
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int i = 0; i < NPF; ++i) asm volatile("" ::"v"(pf[i]));  // the prefetched words themselves are not used
     }
     __syncthreads();
+    TICK(3);
     v16i acc[2];
 #pragma unroll
     for (int tl = 0; tl < 2; ++tl)
@@ -368,6 +421,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     }
 
+    TICK(4);
     // ---- gate sums (Secs. 3.2.4/3.2.5) and layer-norm partial statistics
     auto gate_sums = [&](auto pre_tag) {
       constexpr int PRE = decltype(pre_tag)::value;
@@ -461,10 +515,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       __syncthreads();
       return *flag != 0;
     };
+    TICK(5);
     if (ln) {
       publish_stats(0, g_first, ph ? 2 : 3);
       if (!collect_stats(0, g_first, ph ? 2 : 3)) return;
     }
+    TICK(6);
 
     // ---- layer norm, sigma/tanh, cell update (Secs. 3.2.6, 3.2.1, 3.2.9, 3.2.7)
     constexpr int LNB = KS >= 32 ? 1 : 2;
@@ -600,14 +656,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         __hip_atomic_fetch_add(&red[3 * 32 + col], (u64)pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
     }
-    // the new cell state goes back to memory (read again by this thread at the tile's next step)
+    // the new cell state goes back to memory: read again by this thread at the tile's next step, or, after
+    // the last step, the state the caller gets back
+    if (RTILES > 1 || t == a.T - 1) {
 #pragma unroll
-    for (int tl = 0; tl < 2; ++tl) {
-      const int n0 = member * 64 + cell_w + tl * 8;
-      if (row < a.B && n0 < a.N)
+      for (int tl = 0; tl < 2; ++tl) {
+        const int n0 = member * 64 + cell_w + tl * 8;
+        if (row < a.B && n0 < a.N)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) cbuf[(size_t)row * a.N + n0 + c] = (int16_t)creg[tl][c];
+          for (int c = 0; c < 4; ++c) cbuf[(size_t)row * a.N + n0 + c] = (int16_t)creg[tl][c];
+      }
     }
+    TICK(7);
     if (ph && ln) {
       publish_stats(1, 3, 3);
       if (!collect_stats(1, 3, 3)) return;
@@ -671,7 +731,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
       }
     }
+    TICK(8);
     if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
+    TICK(9);
 
     // ---- projection (Sec. 3.2.8)
     if (proj) {
@@ -736,9 +798,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
         __syncthreads();
       }
+      TICK(10);
       if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, my_ptiles == 0 ? a.idle_sleep : 0,
                       my_ptiles == 0 ? a.idle_poll_sleep : a.poll_sleep, flag))
         return;
+      TICK(11);
     }
     // every workgroup of the layer is past its stores of step t (and they are acknowledged): tell the
     // layer above
@@ -746,6 +810,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       __hip_atomic_store(sa.flags + ((size_t)layer * RTILES + rtile) * 32, (unsigned)(t + 1), __ATOMIC_RELAXED,
                          __HIP_MEMORY_SCOPE_AGENT);
   }
+#undef TICK
+  if (timing)
+    for (int i = 0; i < 12; ++i) a.ticks[i] += (long long)tickL[i];
   placement_check();
 }
 

@@ -136,6 +136,7 @@ def test_persistent_path_every_step_and_layer(orc, flags, rows16):
     layers, x = wl.make_custom([72, H, H], 200, H, flags, 37, 6, seed=flags + 71, weight_param=0.08)
     lib_model, orc_model, xq = prepare_both(orc, layers, x)
     lib_model.set_option("rows16", rows16)
+    lib_model.set_option("stack", 0)  # one layer after the other (the stacked launch has its own test)
     T, B, _ = xq.shape
     dims = lib_model.dims()
     traces = [orc.forward(orc_model, xq, trace_layer=l)[1] for l in range(len(layers))]
@@ -445,14 +446,16 @@ def _rows16(orc, case, rows16):
     inputs, N, H, flags, B, T, rows = case
     print(f"rows16={rows16} N={N} H={H} flags={flags} B={B} T={T}", flush=True)
     layers, x = wl.make_custom(inputs, N, H, flags, B, T, seed=N + B, weight_param=0.05 if N < 1024 else 0.03)
-    lib_model, y = run_and_compare(orc, layers, x, f"rows16_{N}_{B}", trace=False, rows=rows, options={"rows16": rows16})
+    lib_model, y = run_and_compare(orc, layers, x, f"rows16_{N}_{B}", trace=False, rows=rows,
+                                   options={"rows16": rows16, "stack": 0})
     lib_model.profile_begin()
     lib_model.forward(torch.zeros((T, B, inputs[0]), dtype=torch.int8, device="cuda"))
     prof = lib_model.profile_end()
     assert prof["recurrent"]["launches"] == len(inputs) and prof["cell"]["launches"] == 0, prof
 
 
-def test_forward_captured_in_a_hip_graph(orc):
+@pytest.mark.parametrize("stack", [0, 2])
+def test_forward_captured_in_a_hip_graph(orc, stack):
     """forward allocates nothing, never synchronizes and launches only kernels, so
     a caller can capture it in a HIP graph: one-step calls with carried state,
     replayed with the program's own synchronization between the replays, give
@@ -460,10 +463,11 @@ def test_forward_captured_in_a_hip_graph(orc):
     the whole sequence)."""
     import torch
 
-    print("graph capture", flush=True)
+    print(f"graph capture stack={stack}", flush=True)
     flags = wl.LAYER_NORM | wl.PROJECTION
     layers, x = wl.make_custom([72, 136], 200, 136, flags, 20, 6, seed=77, weight_param=0.08)
     lib_model, orc_model, xq = prepare_both(orc, layers, x)
+    lib_model.set_option("stack", stack)  # layer after layer, and all layers in one launch
     T, B, _ = xq.shape
     dims = lib_model.dims()
     want = orc.forward(orc_model, xq)
