@@ -7,16 +7,17 @@
 namespace lstm_int {
 
 typedef void (*stack_fn)(StackArgs);
-stack_fn stack_pick_8(int fl);   // stack_inst_8.hip
-stack_fn stack_pick_20(int fl);  // stack_inst_20.hip
-stack_fn stack_pick_32(int fl);  // stack_inst_32.hip
+stack_fn stack_pick_8(int fl, bool one);   // stack_inst_8.hip
+stack_fn stack_pick_20(int fl, bool one);  // stack_inst_20.hip
+stack_fn stack_pick_32(int fl, bool one);  // stack_inst_32.hip
 
 static const int kStackKS[] = {8, 20, 32};
 
-static stack_fn pick(int ks, int fl) {
-  if (ks == 8) return stack_pick_8(fl);
-  if (ks == 20) return stack_pick_20(fl);
-  if (ks == 32) return stack_pick_32(fl);
+// one = the variant for launches of one item per layer (one step, one row tile)
+static stack_fn pick(int ks, int fl, bool one) {
+  if (ks == 8) return stack_pick_8(fl, one);
+  if (ks == 20) return stack_pick_20(fl, one);
+  if (ks == 32) return stack_pick_32(fl, one);
   return nullptr;
 }
 
@@ -57,8 +58,8 @@ size_t stack_lds_bytes(const StackArgs &sa) {
 
 hipError_t stack_init() {
   for (int ks : kStackKS)
-    for (int fl = 0; fl < 16; ++fl) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick(ks, fl)),
+    for (int fl = 0; fl < 32; ++fl) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick(ks, fl & 15, fl >= 16)),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (e != hipSuccess) return e;
     }
@@ -90,7 +91,7 @@ void launch_stack_init(hipStream_t s, const StackInit &w) {
 
 hipError_t launch_stack(hipStream_t s, const StackArgs &sa, bool cooperative) {
   const RecArgs &a = sa.c;
-  stack_fn fn = pick(a.ks, (a.flags & 7) | ((a.flags & 8) ? 0 : 8));
+  stack_fn fn = pick(a.ks, (a.flags & 7) | ((a.flags & 8) ? 0 : 8), a.T == 1 && sa.row_tiles == 1);
   if (!fn || sa.L < 1 || sa.L > 8) return hipErrorInvalidValue;
   StackArgs args = sa;
   void *params[] = {&args};

@@ -2,9 +2,9 @@
 #include "stack_kernel.inc.h"
 
 namespace lstm_int {
-stack_fn stack_pick_32(int fl) {
+stack_fn stack_pick_32(int fl, bool one) {
   switch (fl) {
-#define LSTM_STACK_CASE(F) case F: return stack_kernel<32, F>;
+#define LSTM_STACK_CASE(F) case F: return one ? stack_kernel<32, F, true> : stack_kernel<32, F, false>;
     LSTM_STACK_CASE(0) LSTM_STACK_CASE(1) LSTM_STACK_CASE(2) LSTM_STACK_CASE(3)
     LSTM_STACK_CASE(4) LSTM_STACK_CASE(5) LSTM_STACK_CASE(6) LSTM_STACK_CASE(7)
     LSTM_STACK_CASE(8) LSTM_STACK_CASE(9) LSTM_STACK_CASE(10) LSTM_STACK_CASE(11)

@@ -42,8 +42,9 @@ __device__ __forceinline__ int32_t stk_requant2(int32_t s0, int32_t s1, const Re
   return (v0 & 0xFFFF) | (v1 << 16);
 }
 
-// FL as in rec_kernel: bit 0 CIFG, bit 1 peephole, bit 2 layer norm, bit 3 "no projection"
-template <int KS, int FL>
+// FL as in rec_kernel: bit 0 CIFG, bit 1 peephole, bit 2 layer norm, bit 3 "no projection".
+// ONE: the launch has one item per layer (one step, one row tile).
+template <int KS, int FL, bool ONE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void stack_kernel(StackArgs sa) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const RecArgs &a = sa.c;
@@ -306,7 +307,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
       for (int i = 0; i < NPF; ++i) {
         const int line = lane + 64 * i;
-        pf[i] = line < sa.prefetch_lines ? *reinterpret_cast<const unsigned *>(w0 + (size_t)line * 128) : 0u;
+        pf[i] = (line < sa.prefetch_lines && !ONE) ? *reinterpret_cast<const unsigned *>(w0 + (size_t)line * 128) : 0u;
       }
     }
     int32_t thp[2][8];  // [tile][(4 gate + c) / 2]: low half = even index
@@ -345,6 +346,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       else
         pack(std::integral_constant<int, 2>{});
     }
+    // A launch of one item per layer (one step, one row tile -- the streaming call) has no further use for
+    // R: W takes its place in the registers while the layers below are still at work, and W x below runs
+    // from registers instead of waiting for memory.
+    constexpr bool w_resident = ONE;
+    if (w_resident) {
+      const int8_t *wsrc = sl.W2f + ((size_t)(member * 8 + wave * 2) * kx) * 1024 + (lane << 4);
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl) {
+        int4 w[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          w[ks] = *reinterpret_cast<const int4 *>(wsrc + ((size_t)tl * kx + (ks < kx ? ks : 0)) * 1024);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          Wf[tl][ks] = v4i{w[ks].x, w[ks].y, w[ks].z, w[ks].w};
+          asm volatile("" : "+a"(Wf[tl][ks]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
     TICK(1);
 
     // ---- W x^t: weights streamed from memory as MFMA operands, DW k steps ahead per tile
@@ -356,7 +378,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     };
 #pragma unroll
     for (int ks = 0; ks < DW && ks < KS; ++ks)
-      if (ks < kx) {
+      if (ks < kx && !w_resident) {
         wq[0][ks] = wload(0, ks);
         wq[1][ks] = wload(1, ks);
       }
@@ -405,19 +427,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
       for (int ks = 0; ks < DEPTH && ks < KS; ++ks) xf[ks] = *reinterpret_cast<const v4i *>(xbase + ks * 32);
       __builtin_amdgcn_sched_barrier(0);
+      if (w_resident) {
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        if (ks < kx) {  // uniform
+        for (int ks = 0; ks < KS; ++ks) {
+          if (ks < kx) {  // uniform
 #pragma unroll
-          for (int tl = 0; tl < 2; ++tl)
-            acc[tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wq[tl][ks % DW], xf[ks % DEPTH], acc[tl], 0, 0, 0);
-          if (ks + DW < KS && ks + DW < kx) {
-            wq[0][ks % DW] = wload(0, ks + DW);
-            wq[1][ks % DW] = wload(1, ks + DW);
+            for (int tl = 0; tl < 2; ++tl)
+              acc[tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Wf[tl][ks], xf[ks % DEPTH], acc[tl], 0, 0, 0);
+            if (ks + DEPTH < KS) xf[ks % DEPTH] = *reinterpret_cast<const v4i *>(xbase + (ks + DEPTH) * 32);
           }
-          if (ks + DEPTH < KS) xf[ks % DEPTH] = *reinterpret_cast<const v4i *>(xbase + (ks + DEPTH) * 32);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          if (ks < kx) {  // uniform
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl)
+              acc[tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wq[tl][ks % DW], xf[ks % DEPTH], acc[tl], 0, 0, 0);
+            if (ks + DW < KS && ks + DW < kx) {
+              wq[0][ks % DW] = wload(0, ks + DW);
+              wq[1][ks % DW] = wload(1, ks + DW);
+            }
+            if (ks + DEPTH < KS) xf[ks % DEPTH] = *reinterpret_cast<const v4i *>(xbase + (ks + DEPTH) * 32);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
 
