@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 one launch per operation and step")
+    ap.add_argument("--mfma-store-ceiling", action="store_true",
+                    help="only measure what the chip sustains for the input GEMM's mix of int8 MFMAs and streaming stores")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB MiB (a known-size reference for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -84,6 +86,11 @@ def main():
         print(json.dumps({"copy_bytes": n, "copies": 3}))
         return
     binding.lib()
+    if args.mfma_store_ceiling:
+        rows = [binding.mfma_store_ceiling(s) for s in (0, 1, 2, 4, 8)]
+        print(json.dumps({"mfma_store_ceiling": rows, "note": "40 int8 MFMAs (32x32x32) per wave and round on every CU, "
+                          "plus stores_per_block KB of streaming stores per wave and round; 4 = the C4 input GEMM's mix"}))
+        return
     cfg = wl.CONFIGS[args.config]
     layers, x = wl.make_workload(args.config)
     xf = torch.from_numpy(x).cuda()

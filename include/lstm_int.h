@@ -331,6 +331,18 @@ int lstm_int_profile_begin(lstm_int_model *model);
 int lstm_int_profile_end(lstm_int_model *model, int64_t launches[LSTM_INT_K_COUNT],
                          double total_ms[LSTM_INT_K_COUNT]);
 
+/*
+ * Measurement aid for the roofline of the hoisted input GEMM (Sec. 6: the
+ * folded-bias matmul W x): runs, on every compute unit, `blocks` rounds of 40
+ * int8 MFMAs (32x32x32, operands in registers) followed by stores_per_block
+ * (0..8) streaming stores of 1 KB per wave -- 4 is the benchmark layer's mix of
+ * matrix work and int16 output -- and reports the sustained TOP/s, the store
+ * rate in GB/s and the shader clock in GHz the chip held.  Allocates and frees
+ * 256 MiB of device memory; synchronizes.
+ */
+int lstm_int_mfma_store_ceiling(int32_t device, int32_t stores_per_block, int32_t blocks,
+                                double *tops, double *store_gbs, double *clock_ghz);
+
 void lstm_int_destroy(lstm_int_model *model);
 
 const char *lstm_int_strerror(int code);

@@ -118,6 +118,9 @@ def lib():
         L.lstm_int_calibrate.restype = C.c_int
         L.lstm_int_calibrate.argtypes = [C.POINTER(LayerParams), C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
                                          C.c_int32, C.c_void_p, C.POINTER(LayerStats), C.c_void_p]
+        L.lstm_int_mfma_store_ceiling.restype = C.c_int
+        L.lstm_int_mfma_store_ceiling.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double),
+                                                  C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.lstm_int_destroy.restype = None
         L.lstm_int_destroy.argtypes = [C.c_void_p]
         L.lstm_int_strerror.restype = C.c_char_p
@@ -357,6 +360,15 @@ def calibrate(layers, x, device=0, want_output=False, apply=True, max_rows=None)
             spec.m_min, spec.m_max, spec.c_absmax = d["m_min"], d["m_max"], d["c_absmax"]
             spec.g_absmax = list(d["g_absmax"])
     return (stats, y) if want_output else stats
+
+
+# lstm_int_mfma_store_ceiling
+def mfma_store_ceiling(stores_per_block, blocks=4096, device=0):
+    """Sustained int8 MFMA rate with `stores_per_block` KB of streaming stores per 40 MFMAs and wave."""
+    t, g, c = C.c_double(), C.c_double(), C.c_double()
+    _check(lib().lstm_int_mfma_store_ceiling(device, stores_per_block, blocks, C.byref(t), C.byref(g), C.byref(c)),
+           "lstm_int_mfma_store_ceiling")
+    return {"stores_per_block": stores_per_block, "tops": t.value, "store_gbs": g.value, "clock_ghz": c.value}
 
 
 def strerror(code):
