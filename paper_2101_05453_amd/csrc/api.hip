@@ -41,6 +41,31 @@ int scratch_lookup(int device) {
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// A table in the wide compressed form (lstm_int_math.h) and what prepare found out about it.
+struct WideTable {
+  const uint8_t *blob = nullptr;  // device, [kLutWideBytes]
+  int sh = -1;                    // block shift, -1 = does not compress
+  int has_tail = 0;               // the tail part (entries 16384..) is filled
+  int flat_from = 32768;          // every entry from here on is equal
+  // shortest prefix a kernel may keep in LDS (0 = none: the table cannot be used from LDS alone) and whether
+  // the tail part has to come with it
+  void shortest(int *dom, int *tail) const {
+    *dom = 0;
+    *tail = 0;
+    if (sh < 0) return;
+    const int flat_dom = flat_from + 1 <= 32768 ? (flat_from + 1 + 1023) / 1024 * 1024 : 0;  // flat from dom - 1 on
+    const int tail_dom = has_tail ? 16384 : 0;
+    const int flat_bytes = flat_dom ? lstm_int::lut_wide_lds_bytes(flat_dom, sh, false) : 0;
+    const int tail_bytes = tail_dom ? lstm_int::lut_wide_lds_bytes(tail_dom, sh, true) : 0;
+    if (flat_dom && (!tail_dom || flat_bytes <= tail_bytes)) {
+      *dom = flat_dom;
+    } else if (tail_dom) {
+      *dom = tail_dom;
+      *tail = 1;
+    }
+  }
+};
+
 // Device-side tensors of one layer, all inside the model's single allocation.
 struct LayerDev {
   // K extents padded to 64.  Hpad is padded to 128 so that the rows of a step's
@@ -56,6 +81,8 @@ struct LayerDev {
   const uint16_t *tanhc = nullptr;  // tanh table of the cell format Q(m_c).(15-m_c)
   const uint8_t *tanhc_blob = nullptr;  // its compressed copy, and block shift (-1: none)
   int sh_tanhc = -1;
+  int tm_tanhc = 0;  // tail mode of its LDS copy (kLutTail*)
+  WideTable wtanhc;  // the same table in the wide form (rec_kernel)
   Requant rq_x, rq_h, rq_p;
   // persistent path (persistent.h): tile-ordered copies; p2 = shape is eligible
   bool p2 = false;
@@ -101,6 +128,8 @@ struct lstm_int_model {
   const uint16_t *sig3 = nullptr, *tanh3 = nullptr;
   const uint8_t *sig3_blob = nullptr, *tanh3_blob = nullptr;
   int sh_sig3 = -1, sh_tanh3 = -1;
+  int tm_sig3 = 0, tm_tanh3 = 0;  // tail modes of the two gate tables' LDS copies (kLutTail*)
+  WideTable wsig3, wtanh3;        // the gate tables in the wide form (rec_kernel)
   int *status = nullptr;  // device word raised by the persistent kernel when a wait gives up
   int path = 0;
   int reverse = 0;  // 1: the recursion runs from time T - 1 down to 0
@@ -310,6 +339,9 @@ int upload(lstm_int_model *m) {
   need_tanh[3] = true;
   size_t tab_off[9], blob_off[9], sig_off = 0, sig_blob_off = 0;
   int sh_tab[9] = {-1, -1, -1, -1, -1, -1, -1, -1, -1}, sh_sig = -1;
+  int tm_tab[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0}, tm_sig = 0;
+  size_t wide_off[9], wide_sig_off = 0;
+  WideTable wide_tab[9], wide_sig;
   for (int pass = 0; pass < 2; ++pass) {
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -319,21 +351,33 @@ int upload(lstm_int_model *m) {
     };
     sig_off = take(32769 * 2);
     sig_blob_off = take(kLutBlobBytes);
+    wide_sig_off = take(kLutWideBytes);
     const size_t status_off = take(256);
     if (pass) {
       fill_sigmoid_table(3, reinterpret_cast<uint16_t *>(image.data() + sig_off));
       sh_sig = compress_table(reinterpret_cast<const uint16_t *>(image.data() + sig_off),
                               image.data() + sig_blob_off);
+      tm_sig = lut_tail_prepare(reinterpret_cast<const uint16_t *>(image.data() + sig_off), image.data() + sig_blob_off,
+                                sh_sig);
+      wide_sig.sh = compress_table_wide(reinterpret_cast<const uint16_t *>(image.data() + sig_off),
+                                        image.data() + wide_sig_off, &wide_sig.has_tail, &wide_sig.flat_from);
+      wide_sig.blob = static_cast<const uint8_t *>(m->arena) + wide_sig_off;
       m->status = reinterpret_cast<int *>(static_cast<uint8_t *>(m->arena) + status_off);
     }
     for (int mc = 0; mc <= 8; ++mc) {
       if (!need_tanh[mc]) continue;
       tab_off[mc] = take(32769 * 2);
       blob_off[mc] = take(kLutBlobBytes);
+      wide_off[mc] = take(kLutWideBytes);
       if (pass) {
         fill_tanh_table(mc, reinterpret_cast<uint16_t *>(image.data() + tab_off[mc]));
         sh_tab[mc] = compress_table(reinterpret_cast<const uint16_t *>(image.data() + tab_off[mc]),
                                     image.data() + blob_off[mc]);
+        tm_tab[mc] = lut_tail_prepare(reinterpret_cast<const uint16_t *>(image.data() + tab_off[mc]),
+                                      image.data() + blob_off[mc], sh_tab[mc]);
+        wide_tab[mc].sh = compress_table_wide(reinterpret_cast<const uint16_t *>(image.data() + tab_off[mc]),
+                                              image.data() + wide_off[mc], &wide_tab[mc].has_tail, &wide_tab[mc].flat_from);
+        wide_tab[mc].blob = static_cast<const uint8_t *>(m->arena) + wide_off[mc];
       }
     }
     for (size_t l = 0; l < L; ++l) {
@@ -486,6 +530,8 @@ int upload(lstm_int_model *m) {
       d.tanhc = reinterpret_cast<const uint16_t *>(dbase + tab_off[h.m_c]);
       d.tanhc_blob = dbase + blob_off[h.m_c];
       d.sh_tanhc = sh_tab[h.m_c];
+      d.tm_tanhc = tm_tab[h.m_c];
+      d.wtanhc = wide_tab[h.m_c];
       d.rq_x = make_requant(h.Mx, h.ex, first, h.G, h.N, 0);
       d.rq_h = make_requant(h.Mh, h.eh, first, h.G, h.N, 0);
       if (h.projection()) d.rq_p = make_requant(&h.Mp, &h.ep, 0, 1, 1 << 28, h.zp_h);
@@ -504,7 +550,7 @@ int upload(lstm_int_model *m) {
             memset(&r, 0, sizeof(r));
             r.R2 = d.R2; r.W2f = d.W2f; r.bx2 = d.bx2; r.bh4 = d.bh4; r.Lq4 = d.Lq4; r.qb4 = d.qb4; r.Pq3 = d.Pq3;
             r.Wp2 = d.Wp2; r.bp2 = d.bp2;
-            r.tanhc_tab = d.tanhc; r.tanhc_blob = d.tanhc_blob; r.sh_tanhc = d.sh_tanhc;
+            r.tanhc_tab = d.tanhc; r.tanhc_blob = d.tanhc_blob; r.sh_tanhc = d.sh_tanhc; r.tm_tanhc = d.tm_tanhc;
             r.kx = d.Ipad / 32;
             r.pre_x = r.pre_h = 0;
             for (int g = 0; g < 4; ++g) {
@@ -540,6 +586,10 @@ int upload(lstm_int_model *m) {
   m->tanh3_blob = dbase + blob_off[3];
   m->sh_sig3 = sh_sig;
   m->sh_tanh3 = sh_tab[3];
+  m->tm_sig3 = tm_sig;
+  m->tm_tanh3 = tm_tab[3];
+  m->wsig3 = wide_sig;
+  m->wtanh3 = wide_tab[3];
   if (rec_init() != hipSuccess || rec16_init() != hipSuccess || in_gemm_init() != hipSuccess || stack_init() != hipSuccess)
     return LSTM_INT_E_DEVICE;
   // The stacked kernel runs models whose layers are all alike (same cells, width and variant; every layer
@@ -555,7 +605,7 @@ int upload(lstm_int_model *m) {
       const LayerDev &d = m->dev[l];
       ok = h.N == h0.N && h.H == h0.H && h.flags == h0.flags && (l == 0 || h.I == h0.H) && d.ks == m->stack_ks &&
            shift_ok(31 - h.em) && (!h.projection() || shift_ok(31 - h.ep)) && sh_sig >= 0 && sh_tab[3] >= 0 &&
-           d.sh_tanhc >= 0;
+           d.sh_tanhc >= 0 && tm_sig != kLutTailGlobal && tm_tab[3] != kLutTailGlobal && d.tm_tanhc != kLutTailGlobal;
       for (int g = 4 - h.G; g < 4 && ok; ++g)
         ok = shift_ok(31 - h.ex[g]) && shift_ok(31 - h.eh[g]) && (!h.layer_norm() || shift_ok(31 - h.eln[g]));
       for (int j = 4 - h.G; j < 3 && ok; ++j) ok = !h.peephole() || shift_ok(31 - h.ec[j]);
@@ -666,6 +716,7 @@ int forward_stack(lstm_int_model *m, const int8_t *x, int32_t T, int32_t B, int8
   ra.GS = d.GS; ra.groups = L; ra.rows_pg = 32; ra.ks = d.ks; ra.Ncp = d.Ncp; ra.Bp = round_up(B, 32);
   ra.sig_tab = m->sig3; ra.tanh_tab = m->tanh3; ra.sig_blob = m->sig3_blob; ra.tanh_blob = m->tanh3_blob;
   ra.sh_sig = m->sh_sig3; ra.sh_tanh = m->sh_tanh3;
+  ra.tm_sig = m->tm_sig3; ra.tm_tanh = m->tm_tanh3;
   // LDS budget: the cell-format tanh table of every layer shares the gate table's place or has its own
   ra.tanhc_blob = m->tanh3_blob;
   for (int l = 0; l < L; ++l)
@@ -818,6 +869,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.sig_tab = m->sig3; ra.tanh_tab = m->tanh3; ra.tanhc_tab = d.tanhc;
       ra.sig_blob = m->sig3_blob; ra.tanh_blob = m->tanh3_blob; ra.tanhc_blob = d.tanhc_blob;
       ra.sh_sig = m->sh_sig3; ra.sh_tanh = m->sh_tanh3; ra.sh_tanhc = d.sh_tanhc;
+      ra.tm_sig = m->tm_sig3; ra.tm_tanh = m->tm_tanh3; ra.tm_tanhc = d.tm_tanhc;
       ra.Wp2 = d.Wp2; ra.bp2 = d.bp2; ra.ptiles = d.ptiles; ra.npadp = d.npadp;
       ra.Mp = h.Mp; ra.rp = 31 - h.ep; ra.zp_h = h.zp_h;
       ra.tx2 = reinterpret_cast<const int4 *>(tx);
@@ -842,19 +894,29 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.ticks = m->phase_timing ? reinterpret_cast<long long *>(m->status + 16) : nullptr;
       // the kernel's one-product form of rescale needs shifts in [3, 62], its tables must compress
       auto shift_ok = [](int r) { return r >= 3 && r <= 62; };
-      bool ok = shift_ok(ra.rm) && (!proj || shift_ok(ra.rp)) && ra.sh_sig >= 0 && ra.sh_tanh >= 0 && ra.sh_tanhc >= 0;
+      // ... and with their tails (the kernels never read the full tables)
+      bool ok = shift_ok(ra.rm) && (!proj || shift_ok(ra.rp)) && ra.sh_sig >= 0 && ra.sh_tanh >= 0 && ra.sh_tanhc >= 0 &&
+                ra.tm_sig != kLutTailGlobal && ra.tm_tanh != kLutTailGlobal && ra.tm_tanhc != kLutTailGlobal;
       for (int g = 4 - h.G; g < 4; ++g)
         if (!shift_ok(ra.rh[g]) || (h.layer_norm() && !shift_ok(ra.rln[g]))) ok = false;
       for (int j = 4 - h.G; j < 3; ++j)
         if (h.peephole() && !shift_ok(ra.rc[j])) ok = false;
-      if (ok && ra.rows_pg == 64 && rec_lds_bytes(ra) > 160 * 1024) {
+      // rec_kernel's tables: the shortest prefixes first (the budget test below uses them)
+      auto set_lut = [&](int i, const WideTable &w) {
+        int dom = 0, tail = 0;
+        w.shortest(&dom, &tail);
+        ra.lut[i].blob = w.blob; ra.lut[i].sh = w.sh; ra.lut[i].dom = dom; ra.lut[i].tail = tail;
+        return dom > 0;
+      };
+      const bool lut_ok = set_lut(0, m->wsig3) & set_lut(1, m->wtanh3) & set_lut(2, d.wtanhc);
+      if (ok && ra.rows_pg == 64 && lut_ok && rec_lds_bytes(ra) > 160 * 1024) {
         // two row tiles per group do not fit the LDS: one tile per group, more launches over the batch
         p2_rt = 1;
         ra.rows_pg = 32;
         p2_groups = std::min(8 * (32 / d.GS), (B + 31) / 32);
         ra.groups = p2_groups;
       }
-      if (!ok || rec_lds_bytes(ra) > 160 * 1024) use_p2 = false;
+      if (!ok || !lut_ok || rec_lds_bytes(ra) > 160 * 1024) use_p2 = false;
       // small batches: groups of 16 rows fill more compute units and halve a step's arithmetic
       int k16 = 0, g16 = 0;
       if (use_p2 && m->rows16 && d.p16 && rec16_supported(h.N, h.H, (int)h.flags, B, &k16, &g16)) {
@@ -864,6 +926,31 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
           ra = r16;
           p2_groups = g16;
           use16 = true;
+        }
+      }
+    }
+    if (use_p2 && !use16) {
+      // What LDS is left goes to longer prefixes of the two gate tables, 1 KB at a time in turn: a value
+      // beyond the prefix costs the whole group a detour (rec_kernel.inc.h, lookup), and with 24576 entries
+      // (|x| < 6 in Q3.12) there is about one per million layer-norm outputs instead of one per thousand.
+      // A prefix that reaches the table's flat end needs no tail part any more.
+      bool grew = true;
+      while (grew) {
+        grew = false;
+        for (int i = 0; i < 2; ++i) {
+          const WideTable &w = i == 0 ? m->wsig3 : m->wtanh3;
+          LutWide keep = ra.lut[i];
+          if (keep.dom >= 32768 || (!keep.tail && keep.dom - 1 >= w.flat_from)) continue;  // nothing left to gain
+          ra.lut[i].dom = keep.dom + 1024;
+          ra.lut[i].tail = (ra.lut[i].dom - 1 < w.flat_from) ? 1 : 0;
+          if (ra.lut[i].tail && !w.has_tail) { ra.lut[i] = keep; continue; }
+          if (i == 1 && ra.lut[2].blob == keep.blob) ra.lut[2] = ra.lut[1];  // one copy serves the cell tanh too
+          if (rec_lds_bytes(ra) > 160 * 1024) {
+            ra.lut[i] = keep;
+            if (i == 1 && ra.lut[2].blob == keep.blob) ra.lut[2] = keep;
+          } else {
+            grew = true;
+          }
         }
       }
     }

@@ -49,13 +49,21 @@ void hm_tanh_table(int m, uint16_t *tab) { fill_tanh_table(m, tab); }
 int32_t hm_sigmoid(const uint16_t *tab, int32_t x) { return sigmoid_from_table(tab, x); }
 int32_t hm_tanh(const uint16_t *tab, int32_t x) { return tanh_from_table(tab, x); }
 int hm_compress(const uint16_t *tab, uint8_t *blob) { return compress_table(tab, blob); }
-int32_t hm_sigmoid_lut(const uint16_t *tab, const uint8_t *blob, int sh, int32_t x) {
-  Lut t{blob, reinterpret_cast<const uint16_t *>(blob + kLutDomain), tab, sh < 0 ? 0 : sh, sh < 0 ? 0 : kLutDomain};
+int hm_tail_prepare(const uint16_t *tab, uint8_t *blob, int sh) { return lut_tail_prepare(tab, blob, sh); }
+// full == NULL: the lookup must not leave the blob (a tail in clamp or mask mode)
+int32_t hm_sigmoid_lut(const uint16_t *tab, const uint8_t *blob, int sh, int tail, int32_t x) {
+  Lut t{blob, reinterpret_cast<const uint16_t *>(blob + kLutDomain), tab, sh < 0 ? 0 : sh, sh < 0 ? 0 : kLutDomain, tail};
   return sigmoid_from_lut(t, x);
 }
-int32_t hm_tanh_lut(const uint16_t *tab, const uint8_t *blob, int sh, int32_t x) {
-  Lut t{blob, reinterpret_cast<const uint16_t *>(blob + kLutDomain), tab, sh < 0 ? 0 : sh, sh < 0 ? 0 : kLutDomain};
+int32_t hm_tanh_lut(const uint16_t *tab, const uint8_t *blob, int sh, int tail, int32_t x) {
+  Lut t{blob, reinterpret_cast<const uint16_t *>(blob + kLutDomain), tab, sh < 0 ? 0 : sh, sh < 0 ? 0 : kLutDomain, tail};
   return tanh_from_lut(t, x);
+}
+int hm_compress_wide(const uint16_t *tab, uint8_t *blob, int *has_tail, int *flat_from) {
+  return compress_table_wide(tab, blob, has_tail, flat_from);
+}
+int32_t hm_lut_wide_mag(const uint8_t *blob, int sh, int dom, int with_tail, int32_t a) {
+  return lut_wide_mag(blob, sh, dom, with_tail != 0, a);
 }
 int32_t hm_rescale_ge32(int32_t a, int32_t M, int32_t r) { return rescale_ge32(a, M, r); }
 int32_t hm_cifg(int32_t f) { return cifg_input_gate(f); }

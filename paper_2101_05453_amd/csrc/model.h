@@ -49,6 +49,13 @@ void fill_tanh_table(int m, uint16_t *tab /*[32769]*/);
 // the bases); returns the block shift (3..6), or -1 if no shift >= 3 keeps the
 // deltas within 8 bits.
 int compress_table(const uint16_t *tab, uint8_t *blob /*[kLutBlobBytes]*/);
+// Adds the compressed form of the table's tail (entries kLutDomain..32768) to a blob that compress_table
+// filled with block shift sh, where one exists; returns the tail mode (kLutTail* in lstm_int_math.h).
+int lut_tail_prepare(const uint16_t *tab, uint8_t *blob, int sh);
+// The wide form (lstm_int_math.h) of a table: returns the block shift (3..6; -1 if none keeps the deltas
+// within 8 bits); *has_tail = the tail part is filled (the table rises by at most one per entry from 16384
+// on); *flat_from = first index from which on every entry is equal.
+int compress_table_wide(const uint16_t *tab, uint8_t *blob /*[kLutWideBytes]*/, int *has_tail, int *flat_from);
 // exp(-y / 2^15) in Q0.31, y >= 0 (exposed for host-side checks)
 int64_t exp_neg_q31(int64_t y);
 

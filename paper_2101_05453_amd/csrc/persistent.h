@@ -81,6 +81,16 @@ hipError_t in_gemm_init();
 bool in_gemm_ws_supported(const InGemmArgs &a);
 void launch_in_gemm_ws(hipStream_t s, const InGemmArgs &a, int num_cus);
 
+// One activation table as rec_kernel keeps it in LDS: a prefix of `dom` entries of the table's wide form
+// (lstm_int_math.h), and the tail part if lookups at and beyond dom can differ from entry dom - 1.
+struct LutWide {
+  const uint8_t *blob;  // [kLutWideBytes], global memory
+  int32_t sh;           // block shift of the encoding
+  int32_t dom;          // entries kept, a multiple of 1024 (the launch chooses it from its LDS budget)
+  int32_t tail;         // 1: the tail part is kept (needs dom >= 16384); 0: the table is flat from dom - 1 on
+  int32_t pad_;
+};
+
 struct RecArgs {
   int T, B, N, H, Hpad, flags, m_c;
   int GS;         // workgroups (compute units) per group = cells / 64
@@ -105,6 +115,9 @@ struct RecArgs {
   const uint16_t *sig_tab, *tanh_tab, *tanhc_tab;  // full tables [32769]
   const uint8_t *sig_blob, *tanh_blob, *tanhc_blob;  // compressed copies for LDS (lstm_int_math.h)
   int sh_sig, sh_tanh, sh_tanhc;                    // block shifts, -1 = not compressed
+  int tm_sig, tm_tanh, tm_tanhc;                    // how the LDS copies hold the entries beyond kLutDomain (kLutTail*)
+  LutWide lut[3];  // rec_kernel: sigma and tanh of the gate format Q3.12, tanh of the cell format (the same
+                   // blob as the gate tanh when the formats agree: one copy serves both)
   // projection
   const int8_t *Wp2;   // [ptiles][32][npadp]
   const int32_t *bp2;  // [ptiles][32]
@@ -178,7 +191,7 @@ struct StackLayer {  // constants of one layer, in device memory (uploaded when 
   int32_t Mc[3], rc[3];
   int32_t Mln[4], rln[4];
   int32_t Mm, rm, zp_m, Mp, rp, zp_h, m_c;
-  int32_t pad_;
+  int32_t tm_tanhc;     // tail mode of the cell-format tanh table's LDS copy (kLutTail*)
 };
 
 struct StackArgs {

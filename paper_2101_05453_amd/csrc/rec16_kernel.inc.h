@@ -419,7 +419,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     };
     auto lookup = [&](int gmask, const int32_t (&x)[4][4], const uint8_t *const (&blob)[4], const int (&shf)[4],
-                      const uint16_t *const (&full)[4], int32_t (&out)[4][4]) {
+                      const int (&tmode)[4], const uint16_t *const (&full)[4], int32_t (&out)[4][4]) {
       int32_t mag[4][4];
       uint32_t base[4][4], delta[4][4];
       int over = 0;
@@ -440,13 +440,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         if (gmask >> g & 1)
 #pragma unroll
           for (int c = 0; c < 4; ++c) out[g][c] = (int32_t)(base[g][c] + delta[g][c]);
+      // values beyond the compressed domain: from the tail's own compressed form in LDS; the tests narrow
+      // down from the batch to the gate to the cell
       if (__builtin_amdgcn_ballot_w64(over >= kLutDomain) != 0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          if (gmask >> g & 1)
+          if ((gmask >> g & 1) && tmode[g] == kLutTailMask) {  // clamped tails: the clamped index was the lookup
+            const int og = mag[g][0] | mag[g][1] | mag[g][2] | mag[g][3];
+            if (__builtin_amdgcn_ballot_w64(og >= kLutDomain) != 0) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-              if (mag[g][c] >= kLutDomain) out[g][c] = full[g][mag[g][c]];
+              for (int c = 0; c < 4; ++c)
+                if (mag[g][c] >= kLutDomain)
+                  out[g][c] = lut_tail_mask(blob[g], mag[g][c]);
+            }
+          }
       }
     };
     constexpr int gates_now = (cifg ? 0 : 1) | 2 | 4 | (ph ? 0 : 8);  // with a peephole the o gate waits for c^t
@@ -455,8 +462,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     {
       const uint8_t *const gate_blob[4] = {lutS, lutS, lutT, lutS};
       const int gate_sh[4] = {sh_sig, sh_sig, sh_tanh, sh_sig};
+      const int gate_tm[4] = {a.tm_sig, a.tm_sig, a.tm_tanh, a.tm_sig};
       const uint16_t *const gate_full[4] = {a.sig_tab, a.sig_tab, a.tanh_tab, a.sig_tab};
-      lookup(gates_now, xv, gate_blob, gate_sh, gate_full, tv);
+      lookup(gates_now, xv, gate_blob, gate_sh, gate_tm, gate_full, tv);
     }
     const int32_t m_c = prm->m_c;
     int32_t xo[4];
@@ -492,20 +500,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     int32_t tcv[4][4];
     const uint8_t *const hid_blob[4] = {lutC, lutC, lutC, lutS};
     const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_tanhc, sh_sig};
+    const int hid_tm[4] = {a.tm_tanhc, a.tm_tanhc, a.tm_tanhc, a.tm_sig};
     const uint16_t *const hid_full[4] = {a.tanhc_tab, a.tanhc_tab, a.tanhc_tab, a.sig_tab};
     if (ph && ln) {
       publish_stats(1, 3, 3);
-      lookup(1, cx, hid_blob, hid_sh, hid_full, tcv);
+      lookup(1, cx, hid_blob, hid_sh, hid_tm, hid_full, tcv);
       if (!collect_stats(1, 3, 3)) return;
     } else {
-      lookup(1, cx, hid_blob, hid_sh, hid_full, tcv);
+      lookup(1, cx, hid_blob, hid_sh, hid_tm, hid_full, tcv);
     }
     if (ph) {
       int32_t ov[4][4];
       normalize(8, ov);
 #pragma unroll
       for (int c = 0; c < 4; ++c) cx[3][c] = ov[3][c];
-      lookup(8, cx, hid_blob, hid_sh, hid_full, tcv);
+      lookup(8, cx, hid_blob, hid_sh, hid_tm, hid_full, tcv);
 #pragma unroll
       for (int c = 0; c < 4; ++c) xo[c] = mirror_sigmoid(cx[3][c], tcv[3][c]);
     }

@@ -64,6 +64,13 @@ struct PrmLds {  // 256 bytes (kPrmLdsBytes in persistent.hip)
 
 static_assert(sizeof(PrmLds) == 256, "rec_lds_bytes assumes 256 bytes");
 
+// Where rec_kernel keeps a table in LDS (byte offsets from the start of the dynamic LDS), for the same
+// reason in LDS itself: offD = deltas, offB = bases, offT = tail part (0 = none kept).
+struct LutLds {
+  int32_t dom, sh, offD, offB, offT, pad[3];
+};
+static_assert(sizeof(LutLds) == 32, "rec_lds_bytes assumes 3 x 32 bytes");
+
 // |x| -> table value from the compressed copy in LDS; `a` must be below kLutDomain
 __device__ __forceinline__ int32_t lut_lds(const uint8_t *blob, int sh, int32_t a) {
   return (int32_t)reinterpret_cast<const uint16_t *>(blob + kLutDomain)[a >> sh] + (int32_t)blob[a];
@@ -149,7 +156,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const size_t pred_bytes = proj ? 4 * 16 * 64 * 4 : 0;
     p += tile_bytes > pred_bytes ? tile_bytes : pred_bytes;
   }
-  u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)4 * items * 8;
+  u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)items * 8;
   LnRow2 *lnrow = reinterpret_cast<LnRow2 *>(p);         p += (size_t)items * sizeof(LnRow2);
   double *LdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;  // layer-norm weights / 2^10 as doubles
   double *bdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;  // layer-norm biases / 2^10 + 2^-11 as doubles
@@ -158,15 +165,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   PrmLds *prm = reinterpret_cast<PrmLds *>(p);           p += sizeof(PrmLds);
   int *flag = reinterpret_cast<int *>(p);                p += 16;
   u64 *tickL = reinterpret_cast<u64 *>(p);               p += 16 * 8;  // phase timers
-  // compressed sigma / tanh tables (lstm_int_math.h); the cell-format tanh shares the gate one if equal
-  const bool share_tanh = a.tanhc_blob == a.tanh_blob;
-  const uint8_t *lutS = p;                               p += kLutBlobBytes;
-  const uint8_t *lutT = p;                               p += kLutBlobBytes;
-  const uint8_t *lutC = share_tanh ? lutT : p;           p += share_tanh ? 0 : kLutBlobBytes;
+  LutLds *lutP = reinterpret_cast<LutLds *>(p);          p += 3 * sizeof(LutLds);
+  // compressed sigma / tanh tables (wide form, lstm_int_math.h): deltas of the first dom entries, their
+  // bases, and the tail part where one is kept; the cell-format tanh shares the gate one if equal
+  const bool share_tanh = a.lut[2].blob == a.lut[1].blob;
+  const uint8_t *lutD[3];   // deltas
+  const uint16_t *lutB[3];  // bases
+  const uint8_t *lutTl[3];  // tail part, or NULL
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    if (i == 2 && share_tanh) {
+      lutD[2] = lutD[1]; lutB[2] = lutB[1]; lutTl[2] = lutTl[1];
+    } else {
+      const int nb = ((((a.lut[i].dom >> a.lut[i].sh) * 2) + 1023) >> 10) << 10;
+      lutD[i] = p;                                        p += a.lut[i].dom;
+      lutB[i] = reinterpret_cast<const uint16_t *>(p);    p += nb;
+      lutTl[i] = a.lut[i].tail ? p : nullptr;             p += a.lut[i].tail ? 3072 : 0;
+    }
+  }
   int8_t *WpL = reinterpret_cast<int8_t *>(p);
   const int WLS = a.npadp + 16;  // W_proj tile row stride in LDS
   const int my_ptiles = proj ? (a.ptiles > member ? (a.ptiles - member + GS - 1) / GS : 0) : 0;
-  const int sh_sig = a.sh_sig, sh_tanh = a.sh_tanh, sh_tanhc = a.sh_tanhc;
 
   // ---- one-time loads: R slice and its biases -> registers, other per-cell
   // parameters, the tables and the W_proj tiles -> LDS
@@ -202,6 +221,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     prm->c[tid] = rescale_hi_prepare(tid < 3 && ph ? a.Mc[tid] : 0, tid < 3 && ph ? a.rc[tid] : 33);
     prm->ln[tid] = rescale_hi_prepare(a.Mln[tid], ln ? a.rln[tid] : 33);
   }
+  if (tid < 3) {
+    LutLds d;
+    d.dom = a.lut[tid].dom; d.sh = a.lut[tid].sh;
+    d.offD = (int32_t)(lutD[tid] - lds);
+    d.offB = (int32_t)(reinterpret_cast<const uint8_t *>(lutB[tid]) - lds);
+    d.offT = lutTl[tid] ? (int32_t)(lutTl[tid] - lds) : 0;
+    d.pad[0] = d.pad[1] = d.pad[2] = 0;
+    lutP[tid] = d;
+  }
   if (tid == 0) {
     prm->m = rescale_hi_prepare(a.Mm, a.rm);
     prm->p = rescale_hi_prepare(proj ? a.Mp : 0, proj ? a.rp : 33);
@@ -215,11 +243,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                        (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     };
-    static_assert(kLutBlobBytes % 1024 == 0, "whole 1 KB chunks");
-    for (int c = wave; c < kLutBlobBytes / 1024; c += 4) {
-      dma(a.sig_blob + c * 1024 + lane * 16, lutS + c * 1024);
-      dma(a.tanh_blob + c * 1024 + lane * 16, lutT + c * 1024);
-      if (!share_tanh) dma(a.tanhc_blob + c * 1024 + lane * 16, lutC + c * 1024);
+    // per table: dom / 1024 chunks of deltas, then the chunks of bases, then the 3 chunks of the tail part,
+    // which sit in this order in LDS and at fixed offsets in the wide blob
+    for (int i = 0; i < (share_tanh ? 2 : 3); ++i) {
+      const int nd = a.lut[i].dom >> 10;
+      const int nb = (((a.lut[i].dom >> a.lut[i].sh) * 2) + 1023) >> 10;
+      const int nt = a.lut[i].tail ? 3 : 0;
+      for (int c = wave; c < nd + nb + nt; c += 4) {
+        const int so = c < nd ? c * 1024 : (c < nd + nb ? kLutWideBaseOff + (c - nd) * 1024 : kLutWideTailOff + (c - nd - nb) * 1024);
+        dma(a.lut[i].blob + so + lane * 16, lutD[i] + c * 1024);
+      }
     }
     // the workgroup's tiles pt = 0.. are rows [32 pt, 32 pt + 32) of one [rows][WLS] block in LDS;
     // bytes of the row padding and past the last row read the start of the weights
@@ -555,42 +588,60 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             for (int c = 0; c < 4; ++c) xv[g][c] = acc[rt][tl][g * 4 + c];
       }
     };
-    // table values of |xv[g][c]| for the gates of gmask: blob/shift/full table per gate
-    auto lookup = [&](int gmask, const int32_t (&xv)[4][4], const uint8_t *const (&blob)[4], const int (&shf)[4],
-                      const uint16_t *const (&full)[4], int32_t (&tv)[4][4]) {
+    // table values of |xv[g][c]| for the gates of gmask; tb[g] = which table (0 sigma, 1 tanh, 2 cell tanh)
+    auto lookup = [&](int gmask, const int32_t (&xv)[4][4], const int (&tb)[4], int32_t (&tv)[4][4]) {
       int32_t mag[4][4];
       uint32_t base[4][4], delta[4][4];
-      int over = 0;
+      bool over = false;
+      // the tables' places and sizes come from LDS (the same words for every lane)
+      LutLds lp[3];
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+        bool used = false;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) used = used || ((gmask >> g & 1) && tb[g] == i);
+        if (used) lp[i] = lutP[i];
+      }
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        if (gmask >> g & 1)
+        if (gmask >> g & 1) {
+          const int dom = lp[tb[g]].dom, sh = lp[tb[g]].sh;
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            mag[g][c] = abs_i32(xv[g][c]);  // below 2^16
-            over |= mag[g][c];
-            const int32_t ai = mag[g][c] < kLutDomain ? mag[g][c] : kLutDomain - 1;
-            base[g][c] = reinterpret_cast<const uint16_t *>(blob[g] + kLutDomain)[ai >> shf[g]];
-            delta[g][c] = blob[g][ai];
+            mag[g][c] = abs_i32(xv[g][c]);  // at most 2^15
+            over |= mag[g][c] >= dom;
+            const int32_t ai = mag[g][c] < dom ? mag[g][c] : dom - 1;
+            base[g][c] = *reinterpret_cast<const uint16_t *>(lds + lp[tb[g]].offB + 2 * (ai >> sh));
+            delta[g][c] = lds[lp[tb[g]].offD + ai];
           }
+        }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int g = 0; g < 4; ++g)
         if (gmask >> g & 1)
 #pragma unroll
           for (int c = 0; c < 4; ++c) tv[g][c] = (int32_t)(base[g][c] + delta[g][c]);
-      // a value beyond the compressed domain (rare) sends the wave to the full tables
-      if (__builtin_amdgcn_ballot_w64(over >= kLutDomain) != 0) {
+      // A value at or beyond the prefix kept in LDS takes its table value from the tail part (a table kept
+      // without one is flat from there on, and the clamped index was the lookup).  How often that happens is
+      // the launch's choice of prefix: with 16384 entries (|x| < 4 in Q3.12) about one layer-norm output in a
+      // thousand, i.e. some lane of most batches -- and the step then waits for the slowest of the group's
+      // 128 waves; with 24576 entries it is one in a million.  The tests narrow down from the batch to the
+      // gate to the cell.
+      if (__builtin_amdgcn_ballot_w64(over) != 0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          if (gmask >> g & 1)
+          if ((gmask >> g & 1) && lp[tb[g]].offT) {
+            const int dom = lp[tb[g]].dom;
+            const bool og = mag[g][0] >= dom || mag[g][1] >= dom || mag[g][2] >= dom || mag[g][3] >= dom;
+            if (__builtin_amdgcn_ballot_w64(og) != 0) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-              if (mag[g][c] >= kLutDomain) tv[g][c] = full[g][mag[g][c]];
+              for (int c = 0; c < 4; ++c)
+                if (mag[g][c] >= dom) tv[g][c] = lut_wide_tail(lds + lp[tb[g]].offT, mag[g][c]);
+            }
+          }
       }
     };
-    const uint8_t *const gate_blob[4] = {lutS, lutS, lutT, lutS};
-    const int gate_sh[4] = {sh_sig, sh_sig, sh_tanh, sh_sig};
-    const uint16_t *const gate_full[4] = {a.sig_tab, a.sig_tab, a.tanh_tab, a.sig_tab};
+    const int gate_tb[4] = {0, 0, 1, 0};
     constexpr int gates_now = (cifg ? 0 : 1) | 2 | 4 | (ph ? 0 : 8);  // with a peephole the o gate waits for c^t
     int32_t xi[RT][2][4], xf[RT][2][4], xz[RT][2][4], xo[RT][2][4];
 #pragma unroll
@@ -605,10 +656,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         int32_t xv[4][4], tv[4][4];
         normalize(rt, tl, gates_now, lr, xv);
         if (KS >= 32) {  // the deepest register-resident R leaves room for two gates' reads at a time
-          lookup(gates_now & 3, xv, gate_blob, gate_sh, gate_full, tv);
-          lookup(gates_now & 12, xv, gate_blob, gate_sh, gate_full, tv);
+          lookup(gates_now & 3, xv, gate_tb, tv);
+          lookup(gates_now & 12, xv, gate_tb, tv);
         } else {
-          lookup(gates_now, xv, gate_blob, gate_sh, gate_full, tv);
+          lookup(gates_now, xv, gate_tb, tv);
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -659,9 +710,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // own format (Sec. 3.2.2), and with a peephole the layer norm and sigma of the o gate
     int32_t tc[RT][2][4];
     {
-      const uint8_t *const hid_blob[4] = {lutC, lutC, lutC, lutS};
-      const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_tanhc, sh_sig};
-      const uint16_t *const hid_full[4] = {a.tanhc_tab, a.tanhc_tab, a.tanhc_tab, a.sig_tab};
+      const int hid_tb[4] = {2, 2, 0, 0};  // c^t of the two weight tiles, then the o gate sums of the two
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         LnRow2 lr[4];
@@ -678,10 +727,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             for (int c = 0; c < 4; ++c) xv[2 + tl][c] = ov[tl][3][c];
           }
         }
-        const uint8_t *const blob2[4] = {hid_blob[0], hid_blob[0], hid_blob[3], hid_blob[3]};
-        const int sh2[4] = {hid_sh[0], hid_sh[0], hid_sh[3], hid_sh[3]};
-        const uint16_t *const full2[4] = {hid_full[0], hid_full[0], hid_full[3], hid_full[3]};
-        lookup(ph ? 15 : 3, xv, blob2, sh2, full2, tv);
+        lookup(ph ? 15 : 3, xv, hid_tb, tv);
 #pragma unroll
         for (int tl = 0; tl < 2; ++tl)
 #pragma unroll

@@ -605,7 +605,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     };
     auto lookup = [&](int gmask, const int32_t (&xv)[4][4], const uint8_t *const (&blob)[4], const int (&shf)[4],
-                      const uint16_t *const (&full)[4], int32_t (&tv)[4][4]) {
+                      const int (&tmode)[4], const uint16_t *const (&full)[4], int32_t (&tv)[4][4]) {
       int32_t mag[4][4];
       uint32_t base[4][4], delta[4][4];
       int over = 0;
@@ -626,17 +626,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         if (gmask >> g & 1)
 #pragma unroll
           for (int c = 0; c < 4; ++c) tv[g][c] = (int32_t)(base[g][c] + delta[g][c]);
+      // A value beyond the compressed domain -- about one in a thousand layer-norm outputs, i.e. in most
+      // batches some lane has one -- takes its table value from the tail's own compressed form in LDS (the
+      // host sends layers whose tables have none to the per-step kernels).  The tests narrow down from the
+      // batch to the gate to the cell, so that the common case costs a few scalar branches.
       if (__builtin_amdgcn_ballot_w64(over >= kLutDomain) != 0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          if (gmask >> g & 1)
+          if ((gmask >> g & 1) && tmode[g] == kLutTailMask) {  // clamped tails: the clamped index was the lookup
+            const int og = mag[g][0] | mag[g][1] | mag[g][2] | mag[g][3];
+            if (__builtin_amdgcn_ballot_w64(og >= kLutDomain) != 0) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-              if (mag[g][c] >= kLutDomain) tv[g][c] = full[g][mag[g][c]];
+              for (int c = 0; c < 4; ++c)
+                if (mag[g][c] >= kLutDomain)
+                  tv[g][c] = lut_tail_mask(blob[g], mag[g][c]);
+            }
+          }
       }
     };
     const uint8_t *const gate_blob[4] = {lutS, lutS, lutT, lutS};
     const int gate_sh[4] = {sh_sig, sh_sig, sh_tanh, sh_sig};
+    const int gate_tm[4] = {a.tm_sig, a.tm_sig, a.tm_tanh, a.tm_sig};
     const uint16_t *const gate_full[4] = {a.sig_tab, a.sig_tab, a.tanh_tab, a.sig_tab};
     constexpr int gates_now = (cifg ? 0 : 1) | 2 | 4 | (ph ? 0 : 8);
     int32_t xi[2][4], xf_[2][4], xz[2][4], xo[2][4];
@@ -651,10 +661,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         int32_t xv[4][4], tv[4][4];
         normalize(tl, gates_now, lr, xv);
         if (KS >= 32) {
-          lookup(gates_now & 3, xv, gate_blob, gate_sh, gate_full, tv);
-          lookup(gates_now & 12, xv, gate_blob, gate_sh, gate_full, tv);
+          lookup(gates_now & 3, xv, gate_blob, gate_sh, gate_tm, gate_full, tv);
+          lookup(gates_now & 12, xv, gate_blob, gate_sh, gate_tm, gate_full, tv);
         } else {
-          lookup(gates_now, xv, gate_blob, gate_sh, gate_full, tv);
+          lookup(gates_now, xv, gate_blob, gate_sh, gate_tm, gate_full, tv);
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -713,6 +723,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     {
       const uint8_t *const hid_blob[4] = {lutC, lutC, lutS, lutS};
       const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_sig, sh_sig};
+      const int hid_tm[4] = {sl.tm_tanhc, sl.tm_tanhc, a.tm_sig, a.tm_sig};
       const uint16_t *const hid_full[4] = {sl.tanhc_tab, sl.tanhc_tab, a.sig_tab, a.sig_tab};
       LnRow2 lr[4];
       if (ph && ln) lr[3] = lnrow[3 * 32 + col];
@@ -727,7 +738,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           for (int c = 0; c < 4; ++c) xv[2 + tl][c] = ov[tl][3][c];
         }
       }
-      lookup(ph ? 15 : 3, xv, hid_blob, hid_sh, hid_full, tv);
+      lookup(ph ? 15 : 3, xv, hid_blob, hid_sh, hid_tm, hid_full, tv);
 #pragma unroll
       for (int tl = 0; tl < 2; ++tl)
 #pragma unroll

@@ -32,8 +32,9 @@ def hm():
     L.hm_rescale_sat16_pre.argtypes = [C.c_int32] * 3
     L.hm_rescale_sat16_pre.restype = C.c_int32
     L.hm_compress.argtypes = [C.c_void_p, C.c_void_p]
-    L.hm_sigmoid_lut.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32]
-    L.hm_tanh_lut.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32]
+    L.hm_sigmoid_lut.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int32]
+    L.hm_tanh_lut.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int32]
+    L.hm_tail_prepare.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
     L.hm_rescale_ge32.restype = C.c_int32
     L.hm_rescale_ge32.argtypes = [C.c_int32] * 3
     L.hm_cell_update.argtypes = [C.c_int32] * 5
@@ -73,20 +74,64 @@ def test_rescale_ge32(orc, hm):
 
 @pytest.mark.parametrize("m", range(0, 9))
 def test_compressed_tables_exhaustive(orc, hm, m):
-    """The LDS form of the tables (8-bit deltas on block bases, full table
-    beyond the compressed domain) returns the oracle's value for every input."""
+    """The LDS form of the tables (8-bit deltas on block bases up to 16384; beyond, the
+    tail's own form -- a clamped index where the tail is flat, block starts and
+    step masks where it rises by at most one per entry -- or the full table where
+    there is none) returns the oracle's value for EVERY input.  The full table
+    handed to the lookup is poisoned wherever the blob must suffice."""
     for kind in ("sigmoid", "tanh"):
         tab = np.zeros(32769, np.uint16)
         getattr(hm, f"hm_{kind}_table")(m, tab.ctypes.data)
         blob = np.zeros(16384 + 2 * 2048, np.uint8)
         sh = hm.hm_compress(tab.ctypes.data, blob.ctypes.data)
         assert sh in (-1, 3, 4, 5, 6)
+        tail = hm.hm_tail_prepare(tab.ctypes.data, blob.ctypes.data, sh)
+        assert tail in (0, 1, 2)
         if m == 3:
-            assert sh >= 3  # the gate formats always compress
+            assert sh >= 5 and tail == 2  # the gate formats compress, tails included: no lookup leaves LDS
+        if kind == "tanh" and m <= 5:
+            assert sh >= 3 and tail != 0  # so do the cell formats of |c| up to 32
+        full = tab.copy()
+        if sh >= 0:
+            full[:16384] = 12345  # never read: the blob covers these
+            if tail != 0:
+                full[:] = 12345
         f = getattr(hm, f"hm_{kind}_lut")
         want = orc.int_sigmoid if kind == "sigmoid" else orc.int_tanh
-        for x in list(range(-32768, 32768, 3)) + [-16385, -16384, -16383, 16383, 16384, 16385, 32767]:
-            assert f(tab.ctypes.data, blob.ctypes.data, sh, x) == want(x, m), (kind, m, x)
+        xs = list(range(-32768, -16380)) + list(range(-16380, 16380, 3)) + list(range(16380, 32768))
+        for x in xs:
+            assert f(full.ctypes.data, blob.ctypes.data, sh, tail, x) == want(x, m), (kind, m, x, sh, tail)
+
+
+@pytest.mark.parametrize("m", range(0, 9))
+def test_wide_tables_every_prefix(orc, hm, m):
+    """The wide form of the tables (the same encoding over all 32768 entries, of which a
+    kernel keeps a prefix in LDS, plus the tail part): for every prefix length a kernel
+    may choose -- any multiple of 1024 beyond the point from which the choice is legal --
+    the lookup returns the table's value for EVERY |x| in 0..32768."""
+    hm.hm_compress_wide.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    hm.hm_lut_wide_mag.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int32]
+    for kind in ("sigmoid", "tanh"):
+        tab = np.zeros(32769, np.uint16)
+        getattr(hm, f"hm_{kind}_table")(m, tab.ctypes.data)
+        blob = np.zeros(32768 + 8192 + 3072, np.uint8)
+        has_tail, flat_from = C.c_int(), C.c_int()
+        sh = hm.hm_compress_wide(tab.ctypes.data, blob.ctypes.data, C.byref(has_tail), C.byref(flat_from))
+        F = flat_from.value
+        assert all(tab[a] == tab[32768] for a in range(F, 32769)) and (F == 0 or tab[F - 1] != tab[32768])
+        if sh < 0:
+            continue
+        if m == 3:
+            assert has_tail.value == 1 and sh >= 5
+        # legal prefixes: with the tail part any multiple of 1024 from 16384 on; without it the table must be
+        # flat from the last kept entry on
+        doms = [d for d in range(1024, 32769, 1024) if (has_tail.value and d >= 16384) or d - 1 >= F]
+        assert doms, (kind, m)  # every format that compresses has a legal prefix
+        probe = sorted(set(doms[:3] + doms[-2:] + doms[len(doms) // 2:len(doms) // 2 + 1]))
+        for dom in probe:
+            with_tail = int(bool(has_tail.value) and dom - 1 < F)
+            for a in range(0, 32769):
+                assert hm.hm_lut_wide_mag(blob.ctypes.data, sh, dom, with_tail, a) == int(tab[a]), (kind, m, dom, a)
 
 
 def test_isqrt(orc, hm):
