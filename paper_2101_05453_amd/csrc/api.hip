@@ -100,6 +100,12 @@ struct LayerDev {
   int16_t *Lq4 = nullptr, *Pq3 = nullptr;  // [4][Ncp], [3][Ncp]
   int8_t *Wp2 = nullptr;    // [ptiles][32][npadp]
   int32_t *bp2 = nullptr;   // [ptiles][32]
+  // the 32-row kernel's own tiling of W_proj: prow outputs per tile, so that every workgroup of a group has
+  // one (H = 640 over 32 workgroups: 20 rows each instead of 20 tiles of 32 over 32 workgroups) and keeps only
+  // those rows in LDS; prow = 32 and the arrays above when H needs more tiles than a group has workgroups
+  int prow = 32, ptiles3 = 0;
+  int8_t *Wp3 = nullptr;    // [ptiles3][32][npadp], rows >= prow of a tile zero
+  int32_t *bp3 = nullptr;   // [ptiles3][32]
 };
 
 struct Profile {
@@ -405,7 +411,7 @@ int upload(lstm_int_model *m) {
       size_t oW2f = 0, oR2h = 0;
       int ks16 = 0, grp16 = 0;
       d.p16 = d.p2 && rec16_supported(h.N, h.H, (int)h.flags, 16, &ks16, &grp16);
-      size_t oW2 = 0, obx2 = 0, oR2 = 0, obh4 = 0, oqb4 = 0, oLq4 = 0, oPq3 = 0, oWp2 = 0, obp2 = 0;
+      size_t oW2 = 0, obx2 = 0, oR2 = 0, obh4 = 0, oqb4 = 0, oLq4 = 0, oPq3 = 0, oWp2 = 0, obp2 = 0, oWp3 = 0, obp3 = 0;
       if (d.p2) {
         d.GS = (h.N + 63) / 64;
         d.ks = ks;
@@ -427,6 +433,14 @@ int upload(lstm_int_model *m) {
         if (h.projection()) {
           oWp2 = take((size_t)d.ptiles * 32 * d.npadp);
           obp2 = take((size_t)d.ptiles * 32 * 4);
+          d.prow = 32;
+          d.ptiles3 = d.ptiles;
+          if (d.ptiles <= d.GS) {  // at most one 32-row tile per workgroup: spread the outputs evenly instead
+            d.prow = round_up((h.H + d.GS - 1) / d.GS, 4);
+            d.ptiles3 = (h.H + d.prow - 1) / d.prow;
+            oWp3 = take((size_t)d.ptiles3 * 32 * d.npadp);
+            obp3 = take((size_t)d.ptiles3 * 32 * 4);
+          }
         }
       }
       if (!pass) continue;
@@ -480,6 +494,11 @@ int upload(lstm_int_model *m) {
           for (int pcol = 0; pcol < h.H; ++pcol) {
             memcpy(base + oWp2 + (size_t)pcol * d.npadp, h.Wpq.data() + (size_t)pcol * h.N, h.N);
             reinterpret_cast<int32_t *>(base + obp2)[pcol] = h.bp_fold[pcol];
+            if (d.prow != 32) {
+              const size_t row3 = (size_t)(pcol / d.prow) * 32 + pcol % d.prow;
+              memcpy(base + oWp3 + row3 * d.npadp, h.Wpq.data() + (size_t)pcol * h.N, h.N);
+              reinterpret_cast<int32_t *>(base + obp3)[row3] = h.bp_fold[pcol];
+            }
           }
         }
         uint8_t *db = static_cast<uint8_t *>(m->arena);
@@ -495,6 +514,8 @@ int upload(lstm_int_model *m) {
         if (h.projection()) {
           d.Wp2 = reinterpret_cast<int8_t *>(db + oWp2);
           d.bp2 = reinterpret_cast<int32_t *>(db + obp2);
+          d.Wp3 = d.prow != 32 ? reinterpret_cast<int8_t *>(db + oWp3) : d.Wp2;
+          d.bp3 = d.prow != 32 ? reinterpret_cast<int32_t *>(db + obp3) : d.bp2;
         }
       }
       for (int g = first; g < 4; ++g) {
@@ -721,7 +742,7 @@ int forward_stack(lstm_int_model *m, const int8_t *x, int32_t T, int32_t B, int8
   ra.tanhc_blob = m->tanh3_blob;
   for (int l = 0; l < L; ++l)
     if (m->dev[l].tanhc_blob != m->tanh3_blob) ra.tanhc_blob = m->dev[l].tanhc_blob;
-  ra.ptiles = d.ptiles; ra.npadp = d.npadp;
+  ra.ptiles = d.ptiles; ra.npadp = d.npadp; ra.prow = 32;
   ra.y = y;
   ra.counters = reinterpret_cast<unsigned *>(wsb + sp.sync);
   ra.tickets = m->cooperative ? nullptr : reinterpret_cast<unsigned long long *>(ra.counters + 2);
@@ -870,7 +891,8 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.sig_blob = m->sig3_blob; ra.tanh_blob = m->tanh3_blob; ra.tanhc_blob = d.tanhc_blob;
       ra.sh_sig = m->sh_sig3; ra.sh_tanh = m->sh_tanh3; ra.sh_tanhc = d.sh_tanhc;
       ra.tm_sig = m->tm_sig3; ra.tm_tanh = m->tm_tanh3; ra.tm_tanhc = d.tm_tanhc;
-      ra.Wp2 = d.Wp2; ra.bp2 = d.bp2; ra.ptiles = d.ptiles; ra.npadp = d.npadp;
+      // the 32-row kernel's tiling of W_proj (the 16-row kernel gets the 32-row tiles back below)
+      ra.Wp2 = d.Wp3; ra.bp2 = d.bp3; ra.ptiles = d.ptiles3; ra.prow = d.prow; ra.npadp = d.npadp;
       ra.Mp = h.Mp; ra.rp = 31 - h.ep; ra.zp_h = h.zp_h;
       ra.tx2 = reinterpret_cast<const int4 *>(tx);
       ra.h0 = h0; ra.out = out; ra.y = (last && !rev) ? y : nullptr;
@@ -922,6 +944,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       if (use_p2 && m->rows16 && d.p16 && rec16_supported(h.N, h.H, (int)h.flags, B, &k16, &g16)) {
         RecArgs r16 = ra;
         r16.R2h = d.R2h; r16.ks16 = d.ks16; r16.rows_pg = 16; r16.groups = g16;
+        r16.Wp2 = d.Wp2; r16.bp2 = d.bp2; r16.ptiles = d.ptiles; r16.prow = 32;
         if (rec16_lds_bytes(r16) <= 160 * 1024) {
           ra = r16;
           p2_groups = g16;

@@ -122,6 +122,8 @@ struct RecArgs {
   const int8_t *Wp2;   // [ptiles][32][npadp]
   const int32_t *bp2;  // [ptiles][32]
   int ptiles, npadp;
+  int prow;            // rec_kernel: output rows per projection tile (4..32, a multiple of 4): tile p holds the
+                       // outputs [p * prow, p * prow + prow) in its first prow rows; the other kernels use 32
   int32_t Mp, rp, zp_h;
   // data
   const int4 *tx2;

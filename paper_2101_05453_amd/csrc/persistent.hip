@@ -197,7 +197,7 @@ size_t rec_lds_bytes(const RecArgs &a) {
     if (i < 2 || a.lut[2].blob != a.lut[1].blob) n += (size_t)lut_wide_lds_bytes(a.lut[i].dom, a.lut[i].sh, a.lut[i].tail != 0);
   if (proj) {
     const int per_cu = (a.ptiles + a.GS - 1) / a.GS;
-    n += ((size_t)per_cu * 32 * (a.npadp + 16) + 1023) / 1024 * 1024;  // loaded in whole 1 KB chunks
+    n += ((size_t)per_cu * a.prow * (a.npadp + 16) + 1023) / 1024 * 1024;  // loaded in whole 1 KB chunks
   }
   return n;
 }

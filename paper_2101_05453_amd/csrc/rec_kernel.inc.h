@@ -254,17 +254,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         dma(a.lut[i].blob + so + lane * 16, lutD[i] + c * 1024);
       }
     }
-    // the workgroup's tiles pt = 0.. are rows [32 pt, 32 pt + 32) of one [rows][WLS] block in LDS;
-    // bytes of the row padding and past the last row read the start of the weights
-    const int wp_rows = my_ptiles * 32;
+    // the workgroup's tiles pt = 0.. are rows [prow pt, prow pt + prow) of one [rows][WLS] block in LDS (only
+    // the prow output rows a tile really has are kept); bytes of the row padding and past the last row read
+    // the start of the weights
+    const int prow = a.prow;
+    const int wp_rows = my_ptiles * prow;
     const int wp_chunks = (wp_rows * WLS + 1023) >> 10;
     for (int c = wave; c < wp_chunks; c += 4) {
       const int o = c * 1024 + lane * 16;
       const int r = o / WLS, col_b = o - r * WLS;
       const int8_t *src = a.Wp2;
       if (r < wp_rows && col_b < a.npadp) {
-        const int pt = r >> 5;
-        src = a.Wp2 + ((size_t)(member + pt * GS) * 32 + (r & 31)) * a.npadp + col_b;
+        const int pt = r / prow;
+        src = a.Wp2 + ((size_t)(member + pt * GS) * 32 + (r - pt * prow)) * a.npadp + col_b;
       }
       dma(src, WpL + c * 1024);
     }
@@ -789,7 +791,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           const int8_t *mrow = a.mbuf + (size_t)t * a.Bp * a.npadp +
                                ((((size_t)((row0 >> 5) + rt) * (a.npadp >> 5) + wave * per_wave) * 32 + col) << 5) +
                                (b2 << 4);
-          const int8_t *wrow = WpL + ((size_t)pt * 32 + col) * WLS + (b2 << 4) + wave * per_wave * 32;
+          // operand rows beyond the tile's prow outputs re-read row 0: their results are never stored
+          const int8_t *wrow = WpL + ((size_t)pt * a.prow + (col < a.prow ? col : 0)) * WLS + (b2 << 4) + wave * per_wave * 32;
           int4 mv[16];
 #pragma unroll
           for (int k = 0; k < 16; ++k) {
@@ -820,7 +823,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           {
             // thread (q = tid / 64, lane' = tid % 64): outputs 8q + 4*(lane'/32) + 0..3 of row lane' % 32
             const int q = tid >> 6, l2 = tid & 63;
-            const int p0 = ptile * 32 + 8 * q + 4 * (l2 >> 5);
+            const int pl = 8 * q + 4 * (l2 >> 5);  // row of the tile; prow is a multiple of 4
+            const int p0 = ptile * a.prow + pl;
             const int orow = row0 + rt * 32 + (l2 & 31);
             uint32_t pk = 0;
 #pragma unroll
@@ -828,11 +832,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
               const int v = 4 * q + c;
               const int32_t s = pred[(0 * 16 + v) * 64 + l2] + pred[(1 * 16 + v) * 64 + l2] +
                                 pred[(2 * 16 + v) * 64 + l2] + pred[(3 * 16 + v) * 64 + l2] +
-                                (pt == 0 ? bpr[c] : a.bp2[p0 + c]);
+                                (pt == 0 ? bpr[c] : a.bp2[ptile * 32 + pl + c]);
               const int32_t hq = sat8(rescale_sat16_pre(s, pp) + zp_h);
               pk |= (uint32_t)(hq & 0xFF) << (8 * c);
             }
-            if (orow < a.B && p0 < a.H) {
+            if (orow < a.B && p0 < a.H && pl < a.prow) {
               int8_t *od = a.out + ((size_t)t * a.B + orow) * a.Hpad + p0;
               if (p0 + 3 < a.H) {
                 *reinterpret_cast<uint32_t *>(od) = pk;

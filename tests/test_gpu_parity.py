@@ -207,16 +207,17 @@ def test_wait_gives_up_and_model_recovers(orc):
 
 
 def test_batch_beyond_one_launch(orc):
-    """N = 2048 with a projection: 8 groups of 32 rows per launch (two row tiles
-    per group would not fit the LDS), so B = 300 runs in two launches, the
-    second with a ragged last group; still on the persistent path."""
+    """N = 2048 with a projection: 8 groups of 64 rows per launch (two row tiles per
+    group), so B = 600 runs in two launches, the second with a ragged last group
+    whose second row tile is empty; still on the persistent path."""
     import torch
 
     print("batch beyond one launch", flush=True)
-    layers, x = wl.make_custom([64], 2048, 640, wl.LAYER_NORM | wl.PROJECTION, 300, 3, seed=21, weight_param=0.03)
-    lib_model, y = run_and_compare(orc, layers, x, "b300", trace=False, rows=[0, 31, 32, 255, 256, 257, 290, 299])
+    layers, x = wl.make_custom([64], 2048, 640, wl.LAYER_NORM | wl.PROJECTION, 600, 3, seed=21, weight_param=0.03)
+    lib_model, y = run_and_compare(orc, layers, x, "b600", trace=False,
+                                   rows=[0, 31, 32, 63, 64, 255, 256, 511, 512, 543, 544, 575, 576, 599])
     lib_model.profile_begin()
-    lib_model.forward(torch.zeros((3, 300, 64), dtype=torch.int8, device="cuda"))
+    lib_model.forward(torch.zeros((3, 600, 64), dtype=torch.int8, device="cuda"))
     prof = lib_model.profile_end()
     assert prof["recurrent"]["launches"] == 2 and prof["cell"]["launches"] == 0, prof
 
