@@ -952,7 +952,8 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
         }
       }
     }
-    if (use_p2 && !use16) {
+    if (use_p2) {
+      auto lds_need = [&]() { return use16 ? rec16_lds_bytes(ra) : rec_lds_bytes(ra); };
       // What LDS is left goes to longer prefixes of the two gate tables, 1 KB at a time in turn: a value
       // beyond the prefix costs the whole group a detour (rec_kernel.inc.h, lookup), and with 24576 entries
       // (|x| < 6 in Q3.12) there is about one per million layer-norm outputs instead of one per thousand.
@@ -968,7 +969,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
           ra.lut[i].tail = (ra.lut[i].dom - 1 < w.flat_from) ? 1 : 0;
           if (ra.lut[i].tail && !w.has_tail) { ra.lut[i] = keep; continue; }
           if (i == 1 && ra.lut[2].blob == keep.blob) ra.lut[2] = ra.lut[1];  // one copy serves the cell tanh too
-          if (rec_lds_bytes(ra) > 160 * 1024) {
+          if (lds_need() > 160 * 1024) {
             ra.lut[i] = keep;
             if (i == 1 && ra.lut[2].blob == keep.blob) ra.lut[2] = keep;
           } else {

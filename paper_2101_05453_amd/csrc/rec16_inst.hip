@@ -40,9 +40,10 @@ size_t rec16_lds_bytes(const RecArgs &a) {
   const bool proj = a.flags & 8;
   size_t tile = (((size_t)16 * (a.ks16 * 64 + 16) + 1023) / 1024 + 1) * 1024;
   if (proj && tile < 4 * 2 * 4 * 64 * 4) tile = 4 * 2 * 4 * 64 * 4;
-  size_t n = tile + (size_t)4 * items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 4 + 4 * 64 * 2 +
-             256 /* PrmLds */ + 16 + 16 * 8;
-  n += (a.tanhc_blob != a.tanh_blob ? 3 : 2) * (size_t)kLutBlobBytes;
+  size_t n = tile + (size_t)items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 4 + 4 * 64 * 2 +
+             256 /* PrmLds */ + 16 + 16 * 8 + 3 * 32 /* LutLds */;
+  for (int i = 0; i < 3; ++i)
+    if (i < 2 || a.lut[2].blob != a.lut[1].blob) n += (size_t)lut_wide_lds_bytes(a.lut[i].dom, a.lut[i].sh, a.lut[i].tail != 0);
   if (proj) {
     const int per_cu = (a.ptiles + a.GS - 1) / a.GS;
     n += ((size_t)per_cu * 32 * (a.npadp + 16) + 1023) / 1024 * 1024;  // loaded in whole 1 KB chunks

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const size_t pred_bytes = proj ? 4 * 2 * 4 * 64 * 4 : 0;
     p += tile_bytes > pred_bytes ? tile_bytes : pred_bytes;
   }
-  u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)4 * items * 8;  // [item] sums (first 64 words)
+  u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)items * 8;  // [item] sums
   LnRow2 *lnrow = reinterpret_cast<LnRow2 *>(p);         p += (size_t)items * sizeof(LnRow2);
   double *LdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;
   double *bdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;
@@ -91,14 +91,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   PrmLds *prm = reinterpret_cast<PrmLds *>(p);           p += sizeof(PrmLds);
   int *flag = reinterpret_cast<int *>(p);                p += 16;
   u64 *tickL = reinterpret_cast<u64 *>(p);               p += 16 * 8;  // phase timers
-  const bool share_tanh = a.tanhc_blob == a.tanh_blob;
-  const uint8_t *lutS = p;                               p += kLutBlobBytes;
-  const uint8_t *lutT = p;                               p += kLutBlobBytes;
-  const uint8_t *lutC = share_tanh ? lutT : p;           p += share_tanh ? 0 : kLutBlobBytes;
+  LutLds *lutP = reinterpret_cast<LutLds *>(p);          p += 3 * sizeof(LutLds);
+  // the activation tables as in rec_kernel: prefixes of the wide form, chosen by the launch
+  const bool share_tanh = a.lut[2].blob == a.lut[1].blob;
+  const uint8_t *lutD[3];
+  const uint8_t *lutB[3];
+  const uint8_t *lutTl[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    if (i == 2 && share_tanh) {
+      lutD[2] = lutD[1]; lutB[2] = lutB[1]; lutTl[2] = lutTl[1];
+    } else {
+      const int nb = ((((a.lut[i].dom >> a.lut[i].sh) * 2) + 1023) >> 10) << 10;
+      lutD[i] = p;                               p += a.lut[i].dom;
+      lutB[i] = p;                               p += nb;
+      lutTl[i] = a.lut[i].tail ? p : nullptr;    p += a.lut[i].tail ? 3072 : 0;
+    }
+  }
   int8_t *WpL = reinterpret_cast<int8_t *>(p);
   const int WLS = a.npadp + 16;  // W_proj tile row stride in LDS
   const int my_ptiles = proj ? (a.ptiles > member ? (a.ptiles - member + GS - 1) / GS : 0) : 0;
-  const int sh_sig = a.sh_sig, sh_tanh = a.sh_tanh, sh_tanhc = a.sh_tanhc;
 
   // ---- one-time loads: R slice -> registers, per-cell parameters, tables and W_proj tiles -> LDS
   // the loads into LDS go first: they need no registers and are in flight while the R slice arrives
@@ -107,10 +119,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                        (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     };
-    for (int c = wave; c < kLutBlobBytes / 1024; c += 4) {
-      dma(a.sig_blob + c * 1024 + lane * 16, lutS + c * 1024);
-      dma(a.tanh_blob + c * 1024 + lane * 16, lutT + c * 1024);
-      if (!share_tanh) dma(a.tanhc_blob + c * 1024 + lane * 16, lutC + c * 1024);
+    for (int i = 0; i < (share_tanh ? 2 : 3); ++i) {
+      const int nd = a.lut[i].dom >> 10;
+      const int nb = (((a.lut[i].dom >> a.lut[i].sh) * 2) + 1023) >> 10;
+      const int nt = a.lut[i].tail ? 3 : 0;
+      for (int c = wave; c < nd + nb + nt; c += 4) {
+        const int so = c < nd ? c * 1024 : (c < nd + nb ? kLutWideBaseOff + (c - nd) * 1024 : kLutWideTailOff + (c - nd - nb) * 1024);
+        dma(a.lut[i].blob + so + lane * 16, lutD[i] + c * 1024);
+      }
+    }
+    if (tid < 3) {
+      LutLds d;
+      d.dom = a.lut[tid].dom; d.sh = a.lut[tid].sh;
+      d.offD = (int32_t)(lutD[tid] - lds);
+      d.offB = (int32_t)(lutB[tid] - lds);
+      d.offT = lutTl[tid] ? (int32_t)(lutTl[tid] - lds) : 0;
+      d.pad[0] = d.pad[1] = d.pad[2] = 0;
+      lutP[tid] = d;
     }
     const int wp_rows = my_ptiles * 32;
     const int wp_chunks = (wp_rows * WLS + 1023) >> 10;
@@ -418,40 +443,49 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             for (int c = 0; c < 4; ++c) xv[g][c] = gs[g][c];
       }
     };
-    auto lookup = [&](int gmask, const int32_t (&x)[4][4], const uint8_t *const (&blob)[4], const int (&shf)[4],
-                      const int (&tmode)[4], const uint16_t *const (&full)[4], int32_t (&out)[4][4]) {
+    // table values of |x[g][c]| for the gates of gmask; tb[g] = which table (0 sigma, 1 tanh, 2 cell tanh);
+    // see rec_kernel's lookup
+    auto lookup = [&](int gmask, const int32_t (&x)[4][4], const int (&tb)[4], int32_t (&out)[4][4]) {
       int32_t mag[4][4];
       uint32_t base[4][4], delta[4][4];
-      int over = 0;
+      bool over = false;
+      LutLds lp[3];
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+        bool used = false;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) used = used || ((gmask >> g & 1) && tb[g] == i);
+        if (used) lp[i] = lutP[i];
+      }
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        if (gmask >> g & 1)
+        if (gmask >> g & 1) {
+          const int dom = lp[tb[g]].dom, sh = lp[tb[g]].sh;
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             mag[g][c] = abs_i32(x[g][c]);
-            over |= mag[g][c];
-            const int32_t ai = mag[g][c] < kLutDomain ? mag[g][c] : kLutDomain - 1;
-            base[g][c] = reinterpret_cast<const uint16_t *>(blob[g] + kLutDomain)[ai >> shf[g]];
-            delta[g][c] = blob[g][ai];
+            over |= mag[g][c] >= dom;
+            const int32_t ai = mag[g][c] < dom ? mag[g][c] : dom - 1;
+            base[g][c] = *reinterpret_cast<const uint16_t *>(lds + lp[tb[g]].offB + 2 * (ai >> sh));
+            delta[g][c] = lds[lp[tb[g]].offD + ai];
           }
+        }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int g = 0; g < 4; ++g)
         if (gmask >> g & 1)
 #pragma unroll
           for (int c = 0; c < 4; ++c) out[g][c] = (int32_t)(base[g][c] + delta[g][c]);
-      // values beyond the compressed domain: from the tail's own compressed form in LDS; the tests narrow
-      // down from the batch to the gate to the cell
-      if (__builtin_amdgcn_ballot_w64(over >= kLutDomain) != 0) {
+      if (__builtin_amdgcn_ballot_w64(over) != 0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          if ((gmask >> g & 1) && tmode[g] == kLutTailMask) {  // clamped tails: the clamped index was the lookup
-            const int og = mag[g][0] | mag[g][1] | mag[g][2] | mag[g][3];
-            if (__builtin_amdgcn_ballot_w64(og >= kLutDomain) != 0) {
+          if ((gmask >> g & 1) && lp[tb[g]].offT) {
+            const int dom = lp[tb[g]].dom;
+            const bool og = mag[g][0] >= dom || mag[g][1] >= dom || mag[g][2] >= dom || mag[g][3] >= dom;
+            if (__builtin_amdgcn_ballot_w64(og) != 0) {
 #pragma unroll
               for (int c = 0; c < 4; ++c)
-                if (mag[g][c] >= kLutDomain)
-                  out[g][c] = lut_tail_mask(blob[g], mag[g][c]);
+                if (mag[g][c] >= dom) out[g][c] = lut_wide_tail(lds + lp[tb[g]].offT, mag[g][c]);
             }
           }
       }
@@ -460,11 +494,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     int32_t xv[4][4], tv[4][4];
     normalize(gates_now, xv);
     {
-      const uint8_t *const gate_blob[4] = {lutS, lutS, lutT, lutS};
-      const int gate_sh[4] = {sh_sig, sh_sig, sh_tanh, sh_sig};
-      const int gate_tm[4] = {a.tm_sig, a.tm_sig, a.tm_tanh, a.tm_sig};
-      const uint16_t *const gate_full[4] = {a.sig_tab, a.sig_tab, a.tanh_tab, a.sig_tab};
-      lookup(gates_now, xv, gate_blob, gate_sh, gate_tm, gate_full, tv);
+      const int gate_tb[4] = {0, 0, 1, 0};
+      lookup(gates_now, xv, gate_tb, tv);
     }
     const int32_t m_c = prm->m_c;
     int32_t xo[4];
@@ -498,23 +529,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // with a peephole the layer norm and sigma of the o gate; the tanh does not wait for the o gate's
     // statistics, so it runs while they travel
     int32_t tcv[4][4];
-    const uint8_t *const hid_blob[4] = {lutC, lutC, lutC, lutS};
-    const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_tanhc, sh_sig};
-    const int hid_tm[4] = {a.tm_tanhc, a.tm_tanhc, a.tm_tanhc, a.tm_sig};
-    const uint16_t *const hid_full[4] = {a.tanhc_tab, a.tanhc_tab, a.tanhc_tab, a.sig_tab};
+    const int hid_tb[4] = {2, 2, 2, 0};
     if (ph && ln) {
       publish_stats(1, 3, 3);
-      lookup(1, cx, hid_blob, hid_sh, hid_tm, hid_full, tcv);
+      lookup(1, cx, hid_tb, tcv);
       if (!collect_stats(1, 3, 3)) return;
     } else {
-      lookup(1, cx, hid_blob, hid_sh, hid_tm, hid_full, tcv);
+      lookup(1, cx, hid_tb, tcv);
     }
     if (ph) {
       int32_t ov[4][4];
       normalize(8, ov);
 #pragma unroll
       for (int c = 0; c < 4; ++c) cx[3][c] = ov[3][c];
-      lookup(8, cx, hid_blob, hid_sh, hid_tm, hid_full, tcv);
+      lookup(8, cx, hid_tb, tcv);
 #pragma unroll
       for (int c = 0; c < 4; ++c) xo[c] = mirror_sigmoid(cx[3][c], tcv[3][c]);
     }
