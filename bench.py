@@ -5,7 +5,10 @@ T, then T recurrent steps, for every layer) over one synthetic batch that is
 already resident in HBM.  The metric is LSTM cell-steps/s = B*T*L / time.
 Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C4]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C4] [--batch B] [--seq-len T]
+
+--batch / --seq-len shrink the configuration (its first rows and steps): the streaming and
+small-batch regimes of the same stack, which take the stacked launch (one layer per XCD).
 """
 import argparse
 import json
@@ -57,6 +60,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--batch", type=int, default=0, help="fewer batch rows than the configuration has (its first rows)")
+    ap.add_argument("--seq-len", type=int, default=0, help="fewer steps than the configuration has (its first steps)")
+    ap.add_argument("--stack", type=int, default=-1, help="option 'stack' of the library (default: the library's own choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 one launch per operation and step")
     ap.add_argument("--mfma-store-ceiling", action="store_true",
@@ -92,11 +98,13 @@ def main():
                           "plus stores_per_block KB of streaming stores per wave and round; 4 = the C4 input GEMM's mix"}))
         return
     cfg = wl.CONFIGS[args.config]
-    layers, x = wl.make_workload(args.config)
+    layers, x = wl.make_workload(args.config, batch=args.batch or None, steps=args.seq_len or None)
     xf = torch.from_numpy(x).cuda()
     binding.calibrate(layers, xf, device=0, max_rows=16)  # statistics of the float run on the first 16 rows (Sec. 4)
     model = binding.prepare(layers, device=0)
     model.set_option("path", args.path)
+    if args.stack >= 0:
+        model.set_option("stack", args.stack)
     L = model.num_layers
     quants = [model.get_quant(l) for l in range(L)]
     xd = model.quantize_input(xf)  # features -> int8 codes, resident in HBM before the timed region
@@ -130,12 +138,21 @@ def main():
     if model.device_status() != 0:
         sys.exit(f"bench.py: device status {model.device_status()} after the profiled loop; the timing is void")
     persistent = prof["cell"]["launches"] == 0  # the per-step path launches a cell kernel per step
+    stacked = persistent and prof["input_gemm"]["launches"] == 0  # all layers in one launch, W x computed per step
     work = {}
     for q in quants:
         for k, v in algorithmic_work(q, B, T, persistent).items():
             e = work.setdefault(k, {"ops": 0.0, "bytes": 0.0, "bytes_resident": 0.0, "launches": 0})
             for f in e:
                 e[f] += v.get(f, v["bytes"] if f == "bytes_resident" else 0)
+    if stacked:
+        # the one kernel does the input GEMM's work too: its ops, its weights once per step, and x; no W x terms
+        # go through memory (the 2 B G N bytes per step that the recurrent figure counts for reading them stay in,
+        # as the price of comparing both ways against the same figure)
+        wi = work.pop("input_gemm")
+        work["recurrent"]["ops"] += wi["ops"]
+        work["recurrent"]["bytes"] += sum(q["G"] * q["N"] * q["I"] * T + T * B * q["I"] for q in quants)
+        work["recurrent"]["bytes_resident"] += sum(T * B * q["I"] for q in quants)
     kernels = {}
     for k, w in work.items():
         p = prof[k]
@@ -165,9 +182,9 @@ def main():
         roof = {"bound": "hbm", "achieved": d["gbps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": d["gbps"] / PEAK_HBM_GBS}
     roof.update({"kernel": dominant, "avg_launch_us": d["avg_us"], "traffic": None,
-                 "path": "persistent" if persistent else "per-step", "kernels": kernels})
+                 "path": "stacked" if stacked else ("persistent" if persistent else "per-step"), "kernels": kernels})
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):  # HBM bytes per launch from rocprofv3 --pmc runs (see profiles/)
+    if os.path.exists(tpath) and not (args.batch or args.seq_len or stacked):  # HBM bytes per launch from rocprofv3 --pmc runs (see profiles/)
         rec = json.load(open(tpath)).get(args.config, {}).get(dominant)
         if rec:
             roof["traffic"] = rec["bytes_per_launch"]
@@ -177,7 +194,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": wl.describe(args.config), "cell_steps_per_step": cell_steps,
+        "config": {"workload": wl.describe(args.config) + (f" shrunk to B={B} T={T}" if (args.batch or args.seq_len) else ""),
+                   "cell_steps_per_step": cell_steps,
                    "batch": B, "seq_len": T, "layers": L,
                    "options": "library defaults (plain launch of the recurrent kernel)"},
         "roofline": roof,
