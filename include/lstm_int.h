@@ -272,6 +272,10 @@ int lstm_int_forward_static(const lstm_int_model *model, const int8_t *x, int32_
  *   "spin_limit": polls after which a wait inside the persistent kernel gives
  *           up (every workgroup then leaves the kernel and the status word of
  *           lstm_int_device_status becomes nonzero).
+ *   "barrier_never_completes": 1 = test hook for that path: every barrier
+ *           among the workgroups of a group waits for one arrival more than
+ *           will come, so the waits give up after spin_limit polls (keep it
+ *           small) and the outputs of the call are not valid.  Default 0.
  *   "poll_sleep", "stats_sleep": pause between two polls of a group barrier /
  *           of the layer-norm statistics words inside the persistent kernel,
  *           in units of 64 clocks (0..1024; defaults 0 and 0).

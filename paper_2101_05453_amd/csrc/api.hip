@@ -79,9 +79,6 @@ struct LayerDev {
   int16_t *Pq = nullptr, *Lq = nullptr;
   int32_t *qb = nullptr;
   const uint16_t *tanhc = nullptr;  // tanh table of the cell format Q(m_c).(15-m_c)
-  const uint8_t *tanhc_blob = nullptr;  // its compressed copy, and block shift (-1: none)
-  int sh_tanhc = -1;
-  int tm_tanhc = 0;  // tail mode of its LDS copy (kLutTail*)
   WideTable wtanhc;  // the same table in the wide form (rec_kernel)
   Requant rq_x, rq_h, rq_p;
   // persistent path (persistent.h): tile-ordered copies; p2 = shape is eligible
@@ -132,9 +129,6 @@ struct lstm_int_model {
   std::vector<LayerDev> dev;
   void *arena = nullptr;
   const uint16_t *sig3 = nullptr, *tanh3 = nullptr;
-  const uint8_t *sig3_blob = nullptr, *tanh3_blob = nullptr;
-  int sh_sig3 = -1, sh_tanh3 = -1;
-  int tm_sig3 = 0, tm_tanh3 = 0;  // tail modes of the two gate tables' LDS copies (kLutTail*)
   WideTable wsig3, wtanh3;        // the gate tables in the wide form (rec_kernel)
   int *status = nullptr;  // device word raised by the persistent kernel when a wait gives up
   int path = 0;
@@ -154,6 +148,7 @@ struct lstm_int_model {
   int stats_first_sleep = 8;
   int sync_sleep = -1;  // pause before the first poll where all arrive together; -1 = by group size
   int phase_timing = 0;
+  int extra_arrivals = 0;  // test hook: group barriers wait for one arrival too many (see RecArgs)
   int num_cus = 256;
   Profile prof;
 };
@@ -343,9 +338,7 @@ int upload(lstm_int_model *m) {
   bool need_tanh[9] = {false, false, false, false, false, false, false, false, false};
   for (const LayerHost &h : m->host) need_tanh[h.m_c] = true;
   need_tanh[3] = true;
-  size_t tab_off[9], blob_off[9], sig_off = 0, sig_blob_off = 0;
-  int sh_tab[9] = {-1, -1, -1, -1, -1, -1, -1, -1, -1}, sh_sig = -1;
-  int tm_tab[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0}, tm_sig = 0;
+  size_t tab_off[9], sig_off = 0;
   size_t wide_off[9], wide_sig_off = 0;
   WideTable wide_tab[9], wide_sig;
   for (int pass = 0; pass < 2; ++pass) {
@@ -356,15 +349,10 @@ int upload(lstm_int_model *m) {
       return o;
     };
     sig_off = take(32769 * 2);
-    sig_blob_off = take(kLutBlobBytes);
     wide_sig_off = take(kLutWideBytes);
     const size_t status_off = take(256);
     if (pass) {
       fill_sigmoid_table(3, reinterpret_cast<uint16_t *>(image.data() + sig_off));
-      sh_sig = compress_table(reinterpret_cast<const uint16_t *>(image.data() + sig_off),
-                              image.data() + sig_blob_off);
-      tm_sig = lut_tail_prepare(reinterpret_cast<const uint16_t *>(image.data() + sig_off), image.data() + sig_blob_off,
-                                sh_sig);
       wide_sig.sh = compress_table_wide(reinterpret_cast<const uint16_t *>(image.data() + sig_off),
                                         image.data() + wide_sig_off, &wide_sig.has_tail, &wide_sig.flat_from);
       wide_sig.blob = static_cast<const uint8_t *>(m->arena) + wide_sig_off;
@@ -373,14 +361,9 @@ int upload(lstm_int_model *m) {
     for (int mc = 0; mc <= 8; ++mc) {
       if (!need_tanh[mc]) continue;
       tab_off[mc] = take(32769 * 2);
-      blob_off[mc] = take(kLutBlobBytes);
       wide_off[mc] = take(kLutWideBytes);
       if (pass) {
         fill_tanh_table(mc, reinterpret_cast<uint16_t *>(image.data() + tab_off[mc]));
-        sh_tab[mc] = compress_table(reinterpret_cast<const uint16_t *>(image.data() + tab_off[mc]),
-                                    image.data() + blob_off[mc]);
-        tm_tab[mc] = lut_tail_prepare(reinterpret_cast<const uint16_t *>(image.data() + tab_off[mc]),
-                                      image.data() + blob_off[mc], sh_tab[mc]);
         wide_tab[mc].sh = compress_table_wide(reinterpret_cast<const uint16_t *>(image.data() + tab_off[mc]),
                                               image.data() + wide_off[mc], &wide_tab[mc].has_tail, &wide_tab[mc].flat_from);
         wide_tab[mc].blob = static_cast<const uint8_t *>(m->arena) + wide_off[mc];
@@ -549,9 +532,6 @@ int upload(lstm_int_model *m) {
         d.bp = reinterpret_cast<int32_t *>(dbase + obp);
       }
       d.tanhc = reinterpret_cast<const uint16_t *>(dbase + tab_off[h.m_c]);
-      d.tanhc_blob = dbase + blob_off[h.m_c];
-      d.sh_tanhc = sh_tab[h.m_c];
-      d.tm_tanhc = tm_tab[h.m_c];
       d.wtanhc = wide_tab[h.m_c];
       d.rq_x = make_requant(h.Mx, h.ex, first, h.G, h.N, 0);
       d.rq_h = make_requant(h.Mh, h.eh, first, h.G, h.N, 0);
@@ -570,8 +550,12 @@ int upload(lstm_int_model *m) {
             StackLayer &r = recs[l];
             memset(&r, 0, sizeof(r));
             r.R2 = d.R2; r.W2f = d.W2f; r.bx2 = d.bx2; r.bh4 = d.bh4; r.Lq4 = d.Lq4; r.qb4 = d.qb4; r.Pq3 = d.Pq3;
-            r.Wp2 = d.Wp2; r.bp2 = d.bp2;
-            r.tanhc_tab = d.tanhc; r.tanhc_blob = d.tanhc_blob; r.sh_tanhc = d.sh_tanhc; r.tm_tanhc = d.tm_tanhc;
+            r.Wp2 = d.Wp3; r.bp2 = d.bp3;  // the tiling by rows per workgroup where there is one
+            {
+              int dom = 0, tail = 0;
+              d.wtanhc.shortest(&dom, &tail);
+              r.lutc.blob = d.wtanhc.blob; r.lutc.sh = d.wtanhc.sh; r.lutc.dom = dom; r.lutc.tail = tail;
+            }
             r.kx = d.Ipad / 32;
             r.pre_x = r.pre_h = 0;
             for (int g = 0; g < 4; ++g) {
@@ -603,12 +587,6 @@ int upload(lstm_int_model *m) {
   const uint8_t *dbase = static_cast<const uint8_t *>(m->arena);
   m->sig3 = reinterpret_cast<const uint16_t *>(dbase + sig_off);
   m->tanh3 = reinterpret_cast<const uint16_t *>(dbase + tab_off[3]);
-  m->sig3_blob = dbase + sig_blob_off;
-  m->tanh3_blob = dbase + blob_off[3];
-  m->sh_sig3 = sh_sig;
-  m->sh_tanh3 = sh_tab[3];
-  m->tm_sig3 = tm_sig;
-  m->tm_tanh3 = tm_tab[3];
   m->wsig3 = wide_sig;
   m->wtanh3 = wide_tab[3];
   if (rec_init() != hipSuccess || rec16_init() != hipSuccess || in_gemm_init() != hipSuccess || stack_init() != hipSuccess)
@@ -625,8 +603,8 @@ int upload(lstm_int_model *m) {
       const LayerHost &h = m->host[l];
       const LayerDev &d = m->dev[l];
       ok = h.N == h0.N && h.H == h0.H && h.flags == h0.flags && (l == 0 || h.I == h0.H) && d.ks == m->stack_ks &&
-           shift_ok(31 - h.em) && (!h.projection() || shift_ok(31 - h.ep)) && sh_sig >= 0 && sh_tab[3] >= 0 &&
-           d.sh_tanhc >= 0 && tm_sig != kLutTailGlobal && tm_tab[3] != kLutTailGlobal && d.tm_tanhc != kLutTailGlobal;
+           shift_ok(31 - h.em) && (!h.projection() || shift_ok(31 - h.ep)) && wide_sig.sh >= 0 && wide_tab[3].sh >= 0 &&
+           d.wtanhc.sh >= 0;
       for (int g = 4 - h.G; g < 4 && ok; ++g)
         ok = shift_ok(31 - h.ex[g]) && shift_ok(31 - h.eh[g]) && (!h.layer_norm() || shift_ok(31 - h.eln[g]));
       for (int j = 4 - h.G; j < 3 && ok; ++j) ok = !h.peephole() || shift_ok(31 - h.ec[j]);
@@ -735,14 +713,26 @@ int forward_stack(lstm_int_model *m, const int8_t *x, int32_t T, int32_t B, int8
   RecArgs &ra = sa.c;
   ra.T = T; ra.B = B; ra.N = h.N; ra.H = h.H; ra.Hpad = d.Hpad; ra.flags = (int)h.flags; ra.m_c = h.m_c;
   ra.GS = d.GS; ra.groups = L; ra.rows_pg = 32; ra.ks = d.ks; ra.Ncp = d.Ncp; ra.Bp = round_up(B, 32);
-  ra.sig_tab = m->sig3; ra.tanh_tab = m->tanh3; ra.sig_blob = m->sig3_blob; ra.tanh_blob = m->tanh3_blob;
-  ra.sh_sig = m->sh_sig3; ra.sh_tanh = m->sh_tanh3;
-  ra.tm_sig = m->tm_sig3; ra.tm_tanh = m->tm_tanh3;
-  // LDS budget: the cell-format tanh table of every layer shares the gate table's place or has its own
-  ra.tanhc_blob = m->tanh3_blob;
-  for (int l = 0; l < L; ++l)
-    if (m->dev[l].tanhc_blob != m->tanh3_blob) ra.tanhc_blob = m->dev[l].tanhc_blob;
-  ra.ptiles = d.ptiles; ra.npadp = d.npadp; ra.prow = 32;
+  ra.ptiles = d.ptiles3; ra.npadp = d.npadp; ra.prow = d.prow;
+  // the tables: the cell-format tanh of every layer at its shortest prefix (a layer whose format is the gates'
+  // shares the gate tanh's copy), the two gate tables as long as the LDS left allows
+  {
+    auto set_lut = [&](int i, const WideTable &w) {
+      int dom = 0, tail = 0;
+      w.shortest(&dom, &tail);
+      ra.lut[i].blob = w.blob; ra.lut[i].sh = w.sh; ra.lut[i].dom = dom; ra.lut[i].tail = tail;
+    };
+    set_lut(0, m->wsig3);
+    set_lut(1, m->wtanh3);
+    sa.lutc_lds_bytes = 0;
+    for (int l = 0; l < L; ++l) {
+      const WideTable &w = m->dev[l].wtanhc;
+      if (w.blob == m->wtanh3.blob) continue;
+      int dom = 0, tail = 0;
+      w.shortest(&dom, &tail);
+      sa.lutc_lds_bytes = std::max(sa.lutc_lds_bytes, lut_wide_lds_bytes(dom, w.sh, tail != 0));
+    }
+  }
   ra.y = y;
   ra.counters = reinterpret_cast<unsigned *>(wsb + sp.sync);
   ra.tickets = m->cooperative ? nullptr : reinterpret_cast<unsigned long long *>(ra.counters + 2);
@@ -754,6 +744,7 @@ int forward_stack(lstm_int_model *m, const int8_t *x, int32_t T, int32_t B, int8
   ra.sync_sleep = m->sync_sleep >= 0 ? m->sync_sleep : (d.GS >= 16 ? 16 : 4);
   ra.idle_poll_sleep = m->idle_poll_sleep;
   ra.ticks = m->phase_timing ? reinterpret_cast<long long *>(m->status + 16) : nullptr;
+  ra.extra_arrivals = m->extra_arrivals;
   sa.layers = m->stack_layers;
   sa.L = L;
   sa.row_tiles = (B + 31) / 32;
@@ -775,6 +766,28 @@ int forward_stack(lstm_int_model *m, const int8_t *x, int32_t T, int32_t B, int8
     sa.prefetch_lines = (int)std::min<int64_t>(per_wave, 16 * (int64_t)(m->dev[L - 1].Ipad / 32));
   }
   if (stack_lds_bytes(sa) > 160 * 1024) return LSTM_INT_E_UNSUPPORTED;
+  {
+    // longer prefixes of the gate tables into the LDS that is left, as for the kernels of one layer -- unless a
+    // layer shares the gate tanh's copy for its cell format: that copy then stays at the prefix its record names
+    bool shares = false;
+    for (int l = 0; l < L; ++l) shares = shares || m->dev[l].wtanhc.blob == m->wtanh3.blob;
+    bool grew = true;
+    while (grew) {
+      grew = false;
+      for (int i = 0; i < 2; ++i) {
+        if (i == 1 && shares) continue;
+        const WideTable &w = i == 0 ? m->wsig3 : m->wtanh3;
+        const LutWide keep = ra.lut[i];
+        if (keep.dom >= 32768 || (!keep.tail && keep.dom - 1 >= w.flat_from)) continue;
+        ra.lut[i].dom = keep.dom + 1024;
+        ra.lut[i].tail = (ra.lut[i].dom - 1 < w.flat_from) ? 1 : 0;
+        if ((ra.lut[i].tail && !w.has_tail) || stack_lds_bytes(sa) > 160 * 1024)
+          ra.lut[i] = keep;
+        else
+          grew = true;
+      }
+    }
+  }
   {
     Timed t(m->prof, s, LSTM_INT_K_OTHER);
     StackInit si;
@@ -887,10 +900,6 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       }
       for (int j = 0; j < 3; ++j) { ra.Mc[j] = h.Mc[j]; ra.rc[j] = 31 - h.ec[j]; }
       ra.Mm = h.Mm; ra.rm = 31 - h.em; ra.zp_m = h.zp_m;
-      ra.sig_tab = m->sig3; ra.tanh_tab = m->tanh3; ra.tanhc_tab = d.tanhc;
-      ra.sig_blob = m->sig3_blob; ra.tanh_blob = m->tanh3_blob; ra.tanhc_blob = d.tanhc_blob;
-      ra.sh_sig = m->sh_sig3; ra.sh_tanh = m->sh_tanh3; ra.sh_tanhc = d.sh_tanhc;
-      ra.tm_sig = m->tm_sig3; ra.tm_tanh = m->tm_tanh3; ra.tm_tanhc = d.tm_tanhc;
       // the 32-row kernel's tiling of W_proj (the 16-row kernel gets the 32-row tiles back below)
       ra.Wp2 = d.Wp3; ra.bp2 = d.bp3; ra.ptiles = d.ptiles3; ra.prow = d.prow; ra.npadp = d.npadp;
       ra.Mp = h.Mp; ra.rp = 31 - h.ep; ra.zp_h = h.zp_h;
@@ -914,11 +923,10 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
       ra.sync_sleep = m->sync_sleep >= 0 ? m->sync_sleep : (d.GS >= 16 ? 16 : 4);
       ra.idle_poll_sleep = m->idle_poll_sleep;
       ra.ticks = m->phase_timing ? reinterpret_cast<long long *>(m->status + 16) : nullptr;
-      // the kernel's one-product form of rescale needs shifts in [3, 62], its tables must compress
+      ra.extra_arrivals = m->extra_arrivals;
+      // the kernel's one-product form of rescale needs shifts in [3, 62]; its tables must compress (lut_ok below)
       auto shift_ok = [](int r) { return r >= 3 && r <= 62; };
-      // ... and with their tails (the kernels never read the full tables)
-      bool ok = shift_ok(ra.rm) && (!proj || shift_ok(ra.rp)) && ra.sh_sig >= 0 && ra.sh_tanh >= 0 && ra.sh_tanhc >= 0 &&
-                ra.tm_sig != kLutTailGlobal && ra.tm_tanh != kLutTailGlobal && ra.tm_tanhc != kLutTailGlobal;
+      bool ok = shift_ok(ra.rm) && (!proj || shift_ok(ra.rp));
       for (int g = 4 - h.G; g < 4; ++g)
         if (!shift_ok(ra.rh[g]) || (h.layer_norm() && !shift_ok(ra.rln[g]))) ok = false;
       for (int j = 4 - h.G; j < 3; ++j)
@@ -1229,6 +1237,11 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
                : !strcmp(key, "sync_sleep") ? m->sync_sleep
                : !strcmp(key, "stats_first_sleep") ? m->stats_first_sleep : m->idle_poll_sleep;
     dst = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "barrier_never_completes")) {
+    if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
+    m->extra_arrivals = (int)value;
     return LSTM_INT_OK;
   }
   if (!strcmp(key, "spin_limit")) {

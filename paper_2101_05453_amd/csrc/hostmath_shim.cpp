@@ -48,17 +48,6 @@ void hm_sigmoid_table(int m, uint16_t *tab) { fill_sigmoid_table(m, tab); }
 void hm_tanh_table(int m, uint16_t *tab) { fill_tanh_table(m, tab); }
 int32_t hm_sigmoid(const uint16_t *tab, int32_t x) { return sigmoid_from_table(tab, x); }
 int32_t hm_tanh(const uint16_t *tab, int32_t x) { return tanh_from_table(tab, x); }
-int hm_compress(const uint16_t *tab, uint8_t *blob) { return compress_table(tab, blob); }
-int hm_tail_prepare(const uint16_t *tab, uint8_t *blob, int sh) { return lut_tail_prepare(tab, blob, sh); }
-// full == NULL: the lookup must not leave the blob (a tail in clamp or mask mode)
-int32_t hm_sigmoid_lut(const uint16_t *tab, const uint8_t *blob, int sh, int tail, int32_t x) {
-  Lut t{blob, reinterpret_cast<const uint16_t *>(blob + kLutDomain), tab, sh < 0 ? 0 : sh, sh < 0 ? 0 : kLutDomain, tail};
-  return sigmoid_from_lut(t, x);
-}
-int32_t hm_tanh_lut(const uint16_t *tab, const uint8_t *blob, int sh, int tail, int32_t x) {
-  Lut t{blob, reinterpret_cast<const uint16_t *>(blob + kLutDomain), tab, sh < 0 ? 0 : sh, sh < 0 ? 0 : kLutDomain, tail};
-  return tanh_from_lut(t, x);
-}
 int hm_compress_wide(const uint16_t *tab, uint8_t *blob, int *has_tail, int *flat_from) {
   return compress_table_wide(tab, blob, has_tail, flat_from);
 }

@@ -278,23 +278,9 @@ LSTM_HD int32_t tanh_from_table(const uint16_t *tab, int32_t x) {
   return x < 0 ? -v : (v > 32767 ? 32767 : v);
 }
 
-// Compressed copy of the first kLutDomain entries of such a table, small
-// enough for LDS: tab[a] = base[a >> sh] + delta[a] with 8-bit deltas (the
-// tables are monotone, so a block of 2^sh entries that rises by at most 255
-// compresses exactly).  Entries at or beyond `lim` come from the full table.
-constexpr int kLutDomain = 16384;
-constexpr int kLutBlobBytes = kLutDomain + 2 * (kLutDomain >> 3);  // deltas, then bases (sh >= 3)
-// The entries at and beyond kLutDomain (the flat tails) have a compressed form of their own, so that a
-// lookup never has to leave LDS.  Tail modes (lut_tail_prepare in prepare.cpp decides):
-//   kLutTailGlobal  no compressed form: such entries come from the full table in global memory;
-//   kLutTailClamp   every entry from kLutDomain - 1 on is equal: clamping the index is the lookup;
-//   kLutTailMask    the tail rises by at most one per entry: blocks of 32 entries hold the value at the
-//                   block's start (uint16) and a 32-bit mask of the steps inside the block
-//                   (lut_tail_value).  The 512 starts sit at byte kLutTailBaseOff of the blob and the 512
-//                   masks at kLutTailMaskOff, in the part of the base array that block shifts >= 5 leave
-//                   unused.
-constexpr int kLutTailGlobal = 0, kLutTailClamp = 1, kLutTailMask = 2;
-constexpr int kLutTailBaseOff = kLutDomain + 1024, kLutTailMaskOff = kLutDomain + 2048;
+// Compressed forms of such a table for LDS: tab[a] = base[a >> sh] + delta[a] with 8-bit deltas (the tables
+// are monotone, so a block of 2^sh entries that rises by at most 255 compresses exactly), and for the flat
+// tail a form of its own:
 // Entry a of a tail, 16384 <= a <= 32768, from 512 block starts (uint16) and 512 masks (uint32): bit i > 0 of
 // a block's mask says that entry i of the block is one above entry i - 1; bit 0 of the LAST block's mask says
 // the same of entry 32768 against entry 32767 (|x| = 32768 occurs for x = -32768 only); bit 0 of the other
@@ -313,15 +299,11 @@ LSTM_HD int32_t lut_tail_value(const uint16_t *starts, const uint32_t *masks, in
 #endif
   return (int32_t)(start + steps + (beyond ? (mask & 1u) : 0u));
 }
-LSTM_HD int32_t lut_tail_mask(const uint8_t *blob, int32_t a) {
-  return lut_tail_value(reinterpret_cast<const uint16_t *>(blob + kLutTailBaseOff),
-                        reinterpret_cast<const uint32_t *>(blob + kLutTailMaskOff), a);
-}
 // Wide form of a compressed table (global memory): the same encoding over ALL 32768 entries, from which a
 // kernel copies into LDS as long a prefix (`dom` entries, a multiple of 1024) as its LDS budget allows --
 // the longer, the rarer a lookup has to go to the tail.  Layout: 32768 deltas; the bases (32768 >> sh
 // uint16, at most 8 KB); 512 tail starts (1 KB) and 512 tail masks (2 KB) for the entries 16384..32767
-// (kLutTailMask form incl. the step to entry 32768, present if the table rises by at most one per entry there).
+// (lut_tail_value's form incl. the step to entry 32768, present if the table rises by at most one per entry there).
 constexpr int kLutWideBaseOff = 32768, kLutWideTailOff = 32768 + 8192, kLutWideBytes = kLutWideTailOff + 3072;
 // bytes of the LDS copy for a prefix of dom entries
 LSTM_HD int32_t lut_wide_lds_bytes(int32_t dom, int32_t sh, bool with_tail) {
@@ -337,28 +319,6 @@ LSTM_HD int32_t lut_wide_mag(const uint8_t *blob, int32_t sh, int32_t dom, bool 
   if (a >= dom && with_tail) return lut_wide_tail(blob + kLutWideTailOff, a);
   const int32_t ai = a < dom ? a : dom - 1;  // without a tail the table is flat from dom - 1 on
   return (int32_t)reinterpret_cast<const uint16_t *>(blob + kLutWideBaseOff)[ai >> sh] + (int32_t)blob[ai];
-}
-
-struct Lut {
-  const uint8_t *delta;   // [kLutDomain] (the blob)
-  const uint16_t *base;   // [kLutDomain >> sh]
-  const uint16_t *full;   // [32769]
-  int32_t sh, lim;        // lim = kLutDomain, or 0 when the table does not compress
-  int32_t tail;           // kLutTail*
-};
-LSTM_HD int32_t lut_mag(const Lut &t, int32_t a) {
-  if (a < t.lim) return (int32_t)t.base[a >> t.sh] + (int32_t)t.delta[a];
-  if (t.lim && t.tail == kLutTailClamp) return (int32_t)t.base[(kLutDomain - 1) >> t.sh] + (int32_t)t.delta[kLutDomain - 1];
-  if (t.lim && t.tail == kLutTailMask) return lut_tail_mask(t.delta, a);
-  return t.full[a];
-}
-LSTM_HD int32_t sigmoid_from_lut(const Lut &t, int32_t x) {
-  const int32_t v = lut_mag(t, x < 0 ? -x : x);
-  return x < 0 ? 32768 - v : (v > 32767 ? 32767 : v);
-}
-LSTM_HD int32_t tanh_from_lut(const Lut &t, int32_t x) {
-  const int32_t v = lut_mag(t, x < 0 ? -x : x);
-  return x < 0 ? -v : (v > 32767 ? 32767 : v);
 }
 
 // CIFG coupling, Sec. 3.2.9 (the value must fit int16, so the smaller of the

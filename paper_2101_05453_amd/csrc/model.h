@@ -45,13 +45,6 @@ int quantize_multiplier(double s, int32_t *M, int32_t *e);
 // 0..32768, for inputs in Q(m).(15-m) (Sec. 3.2.1).  Values lie in 0..32768.
 void fill_sigmoid_table(int m, uint16_t *tab /*[32769]*/);
 void fill_tanh_table(int m, uint16_t *tab /*[32769]*/);
-// Compresses the first 16384 entries of a table into `blob` (16384 deltas, then
-// the bases); returns the block shift (3..6), or -1 if no shift >= 3 keeps the
-// deltas within 8 bits.
-int compress_table(const uint16_t *tab, uint8_t *blob /*[kLutBlobBytes]*/);
-// Adds the compressed form of the table's tail (entries kLutDomain..32768) to a blob that compress_table
-// filled with block shift sh, where one exists; returns the tail mode (kLutTail* in lstm_int_math.h).
-int lut_tail_prepare(const uint16_t *tab, uint8_t *blob, int sh);
 // The wide form (lstm_int_math.h) of a table: returns the block shift (3..6; -1 if none keeps the deltas
 // within 8 bits); *has_tail = the tail part is filled (the table rises by at most one per entry from 16384
 // on); *flat_from = first index from which on every entry is equal.

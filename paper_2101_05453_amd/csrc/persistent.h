@@ -81,7 +81,7 @@ hipError_t in_gemm_init();
 bool in_gemm_ws_supported(const InGemmArgs &a);
 void launch_in_gemm_ws(hipStream_t s, const InGemmArgs &a, int num_cus);
 
-// One activation table as rec_kernel keeps it in LDS: a prefix of `dom` entries of the table's wide form
+// One activation table as the persistent kernels keep it in LDS: a prefix of `dom` entries of the table's wide form
 // (lstm_int_math.h), and the tail part if lookups at and beyond dom can differ from entry dom - 1.
 struct LutWide {
   const uint8_t *blob;  // [kLutWideBytes], global memory
@@ -112,12 +112,9 @@ struct RecArgs {
   int32_t Mc[3], rc[3];
   int32_t Mln[4], rln[4];
   int32_t Mm, rm, zp_m;
-  const uint16_t *sig_tab, *tanh_tab, *tanhc_tab;  // full tables [32769]
-  const uint8_t *sig_blob, *tanh_blob, *tanhc_blob;  // compressed copies for LDS (lstm_int_math.h)
-  int sh_sig, sh_tanh, sh_tanhc;                    // block shifts, -1 = not compressed
-  int tm_sig, tm_tanh, tm_tanhc;                    // how the LDS copies hold the entries beyond kLutDomain (kLutTail*)
-  LutWide lut[3];  // rec_kernel: sigma and tanh of the gate format Q3.12, tanh of the cell format (the same
-                   // blob as the gate tanh when the formats agree: one copy serves both)
+  LutWide lut[3];  // sigma and tanh of the gate format Q3.12, tanh of the cell format (the same blob as the
+                   // gate tanh when the formats agree: one copy serves both; the stacked kernel takes the third
+                   // from its layer record)
   // projection
   const int8_t *Wp2;   // [ptiles][32][npadp]
   const int32_t *bp2;  // [ptiles][32]
@@ -146,6 +143,8 @@ struct RecArgs {
   int idle_sleep, idle_poll_sleep;  // workgroups without a projection tile, at the barrier after the projection:
                                     // pause before the first poll, and between polls
   long long *ticks;  // NULL, or [16] phase timers of workgroup 0 (diagnostics)
+  int extra_arrivals;  // 0; tests set 1: every group barrier then waits for an arrival that never comes, so that
+                       // the bounded waits give up (and every workgroup leaves the kernel) on demand
 };
 
 // Whether a layer shape can take the persistent path; fills ks and rt.
@@ -184,16 +183,15 @@ struct StackLayer {  // constants of one layer, in device memory (uploaded when 
   const int16_t *Pq3;
   const int8_t *Wp2;
   const int32_t *bp2;
-  const uint16_t *tanhc_tab;
-  const uint8_t *tanhc_blob;
-  int32_t sh_tanhc;
+  LutWide lutc;         // tanh of the layer's cell format: wide blob and the prefix its LDS copy keeps
   int32_t kx;           // 32-byte k steps of W x (padded input width / 32), at most the kernel's KS
+  int32_t pad0_;
   int32_t Mx[4], rx[4], pre_x;
   int32_t Mh[4], rh[4], pre_h;
   int32_t Mc[3], rc[3];
   int32_t Mln[4], rln[4];
   int32_t Mm, rm, zp_m, Mp, rp, zp_h, m_c;
-  int32_t tm_tanhc;     // tail mode of the cell-format tanh table's LDS copy (kLutTail*)
+  int32_t pad1_;
 };
 
 struct StackArgs {
@@ -215,6 +213,8 @@ struct StackArgs {
   int c_given;               // 0: the cell state starts from zero, 1: from c_base
   int8_t *h_final;           // NULL, or the caller's h state: layer l's last h, [B, H], at + l * B * H
   unsigned *flags;           // [L][row_tiles] words 128 bytes apart, zeroed: steps finished
+  int lutc_lds_bytes;        // LDS bytes of the largest cell-format tanh copy among the layers (0: all share the
+                             // gate tanh table's copy); host side of the LDS budget
   int flag_sleep;            // pause between two polls of a flag, x 64 clocks
   int tick_layer;            // the layer whose workgroup 0 fills the phase timers (diagnostics)
   int prefetch_lines;        // 128-byte lines of a wave's slice of W asked for ahead of W x (at most 16 * kx)

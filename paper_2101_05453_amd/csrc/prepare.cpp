@@ -262,50 +262,6 @@ int64_t exp_neg_q31(int64_t y) {
   return (int64_t)acc;
 }
 
-int compress_table(const uint16_t *tab, uint8_t *blob) {
-  for (int sh = 6; sh >= 3; --sh) {
-    bool ok = true;
-    for (int a = 0; a < kLutDomain && ok; ++a) {
-      const int d = (int)tab[a] - (int)tab[(a >> sh) << sh];
-      ok = d >= 0 && d <= 255;
-    }
-    if (!ok) continue;
-    memset(blob, 0, kLutBlobBytes);
-    uint16_t *base = reinterpret_cast<uint16_t *>(blob + kLutDomain);
-    for (int a = 0; a < kLutDomain; ++a) {
-      blob[a] = (uint8_t)(tab[a] - tab[(a >> sh) << sh]);
-      if ((a & ((1 << sh) - 1)) == 0) base[a >> sh] = tab[a];
-    }
-    return sh;
-  }
-  return -1;
-}
-
-int lut_tail_prepare(const uint16_t *tab, uint8_t *blob, int sh) {
-  if (sh < 0) return kLutTailGlobal;
-  bool flat = true, gentle = true;
-  for (int a = kLutDomain; a <= 32768; ++a) {
-    flat = flat && tab[a] == tab[kLutDomain - 1];
-    const int step = (int)tab[a] - (int)tab[a - 1];
-    gentle = gentle && (a == kLutDomain || (step >= 0 && step <= 1));
-  }
-  if (flat) return kLutTailClamp;
-  // the starts and masks need the 3 KB behind the first 1 KB of the base array
-  if (!gentle || (kLutDomain >> sh) * 2 > 1024) return kLutTailGlobal;
-  uint16_t *start = reinterpret_cast<uint16_t *>(blob + kLutTailBaseOff);
-  uint32_t *mask = reinterpret_cast<uint32_t *>(blob + kLutTailMaskOff);
-  for (int b = 0; b < 512; ++b) {
-    const int a0 = kLutDomain + 32 * b;
-    start[b] = tab[a0];
-    uint32_t mk = 0;
-    for (int i = 1; i < 32; ++i)
-      if (tab[a0 + i] != tab[a0 + i - 1]) mk |= 1u << i;
-    mask[b] = mk;
-  }
-  if (tab[32768] != tab[32767]) mask[511] |= 1u;  // the step to the one entry beyond the last block
-  return kLutTailMask;
-}
-
 int compress_table_wide(const uint16_t *tab, uint8_t *blob, int *has_tail, int *flat_from) {
   int F = 32768;
   while (F > 0 && tab[F - 1] == tab[32768]) --F;

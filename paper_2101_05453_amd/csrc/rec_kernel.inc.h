@@ -71,11 +71,6 @@ struct LutLds {
 };
 static_assert(sizeof(LutLds) == 32, "rec_lds_bytes assumes 3 x 32 bytes");
 
-// |x| -> table value from the compressed copy in LDS; `a` must be below kLutDomain
-__device__ __forceinline__ int32_t lut_lds(const uint8_t *blob, int sh, int32_t a) {
-  return (int32_t)reinterpret_cast<const uint16_t *>(blob + kLutDomain)[a >> sh] + (int32_t)blob[a];
-}
-
 __device__ __forceinline__ int32_t abs_i32(int32_t v) { return v < 0 ? -v : v; }
 // table value t = tab[|x|] -> sigma(x), tanh(x) (Sec. 3.2.1 output clamp)
 __device__ __forceinline__ int32_t mirror_sigmoid(int32_t x, int32_t t) {
@@ -772,7 +767,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     }
     TICK(6);
-    if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
+    if (!group_sync(counter, epoch, GS + a.extra_arrivals, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
     TICK(7);
 
     // ---- projection (Sec. 3.2.8): tile pt of 32 outputs, K = N split over the four waves
@@ -853,7 +848,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
       }
       TICK(8);
-      if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, my_ptiles == 0 ? a.idle_sleep : 0,
+      if (!group_sync(counter, epoch, GS + a.extra_arrivals, a.status, a.spin_limit, my_ptiles == 0 ? a.idle_sleep : 0,
                       my_ptiles == 0 ? a.idle_poll_sleep : a.poll_sleep, flag))
         return;
       TICK(9);

@@ -46,12 +46,13 @@ size_t stack_lds_bytes(const StackArgs &sa) {
   const bool proj = a.flags & 8;
   size_t tile = (((size_t)32 * (a.ks * 32 + 16) + 1023) / 1024 + 1) * 1024;
   if (proj && tile < 4 * 16 * 64 * 4) tile = 4 * 16 * 64 * 4;
-  size_t n = tile + (size_t)4 * items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 2 + 4 * 64 * 4 +
-             8 * 32 * 4 + 320 /* StkPrm */ + 16 + 12 * 8;
-  n += (a.tanhc_blob != a.tanh_blob ? 3 : 2) * (size_t)kLutBlobBytes;
+  size_t n = tile + (size_t)items * 8 + (size_t)items * sizeof(LnRow2) + 2 * 4 * 64 * 8 + 4 * 64 * 2 + 4 * 64 * 4 +
+             8 * 32 * 4 + 320 /* StkPrm */ + 16 + 12 * 8 + 3 * 32 /* LutLds */;
+  for (int i = 0; i < 2; ++i) n += (size_t)lut_wide_lds_bytes(a.lut[i].dom, a.lut[i].sh, a.lut[i].tail != 0);
+  n += (size_t)sa.lutc_lds_bytes;  // the largest cell-format copy among the layers
   if (proj) {
     const int per_cu = (a.ptiles + a.GS - 1) / a.GS;
-    n += ((size_t)per_cu * 32 * (a.npadp + 16) + 1023) / 1024 * 1024;
+    n += ((size_t)per_cu * a.prow * (a.npadp + 16) + 1023) / 1024 * 1024;
   }
   return n;
 }

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const size_t pred_bytes = proj ? 4 * 16 * 64 * 4 : 0;
     p += tile_bytes > pred_bytes ? tile_bytes : pred_bytes;
   }
-  u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)4 * items * 8;
+  u64 *red = reinterpret_cast<u64 *>(p);                 p += (size_t)items * 8;
   LnRow2 *lnrow = reinterpret_cast<LnRow2 *>(p);         p += (size_t)items * sizeof(LnRow2);
   double *LdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;
   double *bdL = reinterpret_cast<double *>(p);           p += 4 * 64 * 8;
@@ -119,14 +119,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   StkPrm *prm = reinterpret_cast<StkPrm *>(p);           p += sizeof(StkPrm);
   int *flag = reinterpret_cast<int *>(p);                p += 16;
   u64 *tickL = reinterpret_cast<u64 *>(p);               p += 12 * 8;  // phase timers
-  const bool share_tanh = sl.tanhc_blob == a.tanh_blob;
-  const uint8_t *lutS = p;                               p += kLutBlobBytes;
-  const uint8_t *lutT = p;                               p += kLutBlobBytes;
-  const uint8_t *lutC = share_tanh ? lutT : p;           p += share_tanh ? 0 : kLutBlobBytes;
+  LutLds *lutP = reinterpret_cast<LutLds *>(p);          p += 3 * sizeof(LutLds);
+  // the activation tables as in rec_kernel: prefixes of the wide form; the two gate tables are common to
+  // the layers, the cell-format tanh is the layer's own (or the gate tanh's copy when the formats agree)
+  const LutWide lw[3] = {a.lut[0], a.lut[1], sl.lutc};
+  const bool share_tanh = lw[2].blob == lw[1].blob;
+  const uint8_t *lutD[3];
+  const uint8_t *lutB[3];
+  const uint8_t *lutTl[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    if (i == 2 && share_tanh) {
+      lutD[2] = lutD[1]; lutB[2] = lutB[1]; lutTl[2] = lutTl[1];
+    } else {
+      const int nb = ((((lw[i].dom >> lw[i].sh) * 2) + 1023) >> 10) << 10;
+      lutD[i] = p;                            p += lw[i].dom;
+      lutB[i] = p;                            p += nb;
+      lutTl[i] = lw[i].tail ? p : nullptr;    p += lw[i].tail ? 3072 : 0;
+    }
+  }
   int8_t *WpL = reinterpret_cast<int8_t *>(p);
   const int WLS = a.npadp + 16;
   const int my_ptiles = proj ? (a.ptiles > member ? (a.ptiles - member + GS - 1) / GS : 0) : 0;
-  const int sh_sig = a.sh_sig, sh_tanh = a.sh_tanh, sh_tanhc = sl.sh_tanhc;
 
   // ---- one-time loads: R slice -> registers; per-cell parameters, tables, W_proj tiles -> LDS
   v4i Wf[2][KS];
@@ -162,6 +176,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     prm->c[tid] = rescale_hi_prepare(tid < 3 && ph ? sl.Mc[tid] : 0, tid < 3 && ph ? sl.rc[tid] : 33);
     prm->ln[tid] = rescale_hi_prepare(sl.Mln[tid], ln ? sl.rln[tid] : 33);
   }
+  if (tid < 3) {
+    LutLds d;
+    const LutWide &w = (tid == 2 && share_tanh) ? lw[1] : lw[tid];  // a shared copy has the gate table's prefix
+    d.dom = w.dom; d.sh = w.sh;
+    d.offD = (int32_t)(lutD[tid] - lds);
+    d.offB = (int32_t)(lutB[tid] - lds);
+    d.offT = lutTl[tid] ? (int32_t)(lutTl[tid] - lds) : 0;
+    d.pad[0] = d.pad[1] = d.pad[2] = 0;
+    lutP[tid] = d;
+  }
   if (tid == 0) {
     prm->m = rescale_hi_prepare(sl.Mm, sl.rm);
     prm->p = rescale_hi_prepare(proj ? sl.Mp : 0, proj ? sl.rp : 33);
@@ -174,20 +198,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                        (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     };
-    for (int c = wave; c < kLutBlobBytes / 1024; c += 4) {
-      dma(a.sig_blob + c * 1024 + lane * 16, lutS + c * 1024);
-      dma(a.tanh_blob + c * 1024 + lane * 16, lutT + c * 1024);
-      if (!share_tanh) dma(sl.tanhc_blob + c * 1024 + lane * 16, lutC + c * 1024);
+    for (int i = 0; i < (share_tanh ? 2 : 3); ++i) {
+      const int nd = lw[i].dom >> 10;
+      const int nb = (((lw[i].dom >> lw[i].sh) * 2) + 1023) >> 10;
+      const int nt = lw[i].tail ? 3 : 0;
+      for (int c = wave; c < nd + nb + nt; c += 4) {
+        const int so = c < nd ? c * 1024 : (c < nd + nb ? kLutWideBaseOff + (c - nd) * 1024 : kLutWideTailOff + (c - nd - nb) * 1024);
+        dma(lw[i].blob + so + lane * 16, lutD[i] + c * 1024);
+      }
     }
-    const int wp_rows = my_ptiles * 32;
+    const int prow = a.prow;
+    const int wp_rows = my_ptiles * prow;
     const int wp_chunks = (wp_rows * WLS + 1023) >> 10;
     for (int c = wave; c < wp_chunks; c += 4) {
       const int o = c * 1024 + lane * 16;
       const int r = o / WLS, col_b = o - r * WLS;
       const int8_t *src = sl.Wp2;
       if (r < wp_rows && col_b < a.npadp) {
-        const int pt = r >> 5;
-        src = sl.Wp2 + ((size_t)(member + pt * GS) * 32 + (r & 31)) * a.npadp + col_b;
+        const int pt = r / prow;
+        src = sl.Wp2 + ((size_t)(member + pt * GS) * 32 + (r - pt * prow)) * a.npadp + col_b;
       }
       dma(src, WpL + c * 1024);
     }
@@ -604,50 +633,54 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             for (int c = 0; c < 4; ++c) xv[g][c] = acc[tl][g * 4 + c];
       }
     };
-    auto lookup = [&](int gmask, const int32_t (&xv)[4][4], const uint8_t *const (&blob)[4], const int (&shf)[4],
-                      const int (&tmode)[4], const uint16_t *const (&full)[4], int32_t (&tv)[4][4]) {
+    // table values of |xv[g][c]| for the gates of gmask; tb[g] = which table (0 sigma, 1 tanh, 2 cell tanh);
+    // see rec_kernel's lookup
+    auto lookup = [&](int gmask, const int32_t (&xv)[4][4], const int (&tb)[4], int32_t (&tv)[4][4]) {
       int32_t mag[4][4];
       uint32_t base[4][4], delta[4][4];
-      int over = 0;
+      bool over = false;
+      LutLds lp[3];
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+        bool used = false;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) used = used || ((gmask >> g & 1) && tb[g] == i);
+        if (used) lp[i] = lutP[i];
+      }
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        if (gmask >> g & 1)
+        if (gmask >> g & 1) {
+          const int dom = lp[tb[g]].dom, sh = lp[tb[g]].sh;
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             mag[g][c] = abs_i32(xv[g][c]);
-            over |= mag[g][c];
-            const int32_t ai = mag[g][c] < kLutDomain ? mag[g][c] : kLutDomain - 1;
-            base[g][c] = reinterpret_cast<const uint16_t *>(blob[g] + kLutDomain)[ai >> shf[g]];
-            delta[g][c] = blob[g][ai];
+            over |= mag[g][c] >= dom;
+            const int32_t ai = mag[g][c] < dom ? mag[g][c] : dom - 1;
+            base[g][c] = *reinterpret_cast<const uint16_t *>(lds + lp[tb[g]].offB + 2 * (ai >> sh));
+            delta[g][c] = lds[lp[tb[g]].offD + ai];
           }
+        }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int g = 0; g < 4; ++g)
         if (gmask >> g & 1)
 #pragma unroll
           for (int c = 0; c < 4; ++c) tv[g][c] = (int32_t)(base[g][c] + delta[g][c]);
-      // A value beyond the compressed domain -- about one in a thousand layer-norm outputs, i.e. in most
-      // batches some lane has one -- takes its table value from the tail's own compressed form in LDS (the
-      // host sends layers whose tables have none to the per-step kernels).  The tests narrow down from the
-      // batch to the gate to the cell, so that the common case costs a few scalar branches.
-      if (__builtin_amdgcn_ballot_w64(over >= kLutDomain) != 0) {
+      if (__builtin_amdgcn_ballot_w64(over) != 0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          if ((gmask >> g & 1) && tmode[g] == kLutTailMask) {  // clamped tails: the clamped index was the lookup
-            const int og = mag[g][0] | mag[g][1] | mag[g][2] | mag[g][3];
-            if (__builtin_amdgcn_ballot_w64(og >= kLutDomain) != 0) {
+          if ((gmask >> g & 1) && lp[tb[g]].offT) {
+            const int dom = lp[tb[g]].dom;
+            const bool og = mag[g][0] >= dom || mag[g][1] >= dom || mag[g][2] >= dom || mag[g][3] >= dom;
+            if (__builtin_amdgcn_ballot_w64(og) != 0) {
 #pragma unroll
               for (int c = 0; c < 4; ++c)
-                if (mag[g][c] >= kLutDomain)
-                  tv[g][c] = lut_tail_mask(blob[g], mag[g][c]);
+                if (mag[g][c] >= dom) tv[g][c] = lut_wide_tail(lds + lp[tb[g]].offT, mag[g][c]);
             }
           }
       }
     };
-    const uint8_t *const gate_blob[4] = {lutS, lutS, lutT, lutS};
-    const int gate_sh[4] = {sh_sig, sh_sig, sh_tanh, sh_sig};
-    const int gate_tm[4] = {a.tm_sig, a.tm_sig, a.tm_tanh, a.tm_sig};
-    const uint16_t *const gate_full[4] = {a.sig_tab, a.sig_tab, a.tanh_tab, a.sig_tab};
+    const int gate_tb[4] = {0, 0, 1, 0};
     constexpr int gates_now = (cifg ? 0 : 1) | 2 | 4 | (ph ? 0 : 8);
     int32_t xi[2][4], xf_[2][4], xz[2][4], xo[2][4];
     {
@@ -661,10 +694,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         int32_t xv[4][4], tv[4][4];
         normalize(tl, gates_now, lr, xv);
         if (KS >= 32) {
-          lookup(gates_now & 3, xv, gate_blob, gate_sh, gate_tm, gate_full, tv);
-          lookup(gates_now & 12, xv, gate_blob, gate_sh, gate_tm, gate_full, tv);
+          lookup(gates_now & 3, xv, gate_tb, tv);
+          lookup(gates_now & 12, xv, gate_tb, tv);
         } else {
-          lookup(gates_now, xv, gate_blob, gate_sh, gate_tm, gate_full, tv);
+          lookup(gates_now, xv, gate_tb, tv);
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -721,10 +754,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // ---- hidden state (Sec. 3.2.7)
     int32_t tc[2][4];
     {
-      const uint8_t *const hid_blob[4] = {lutC, lutC, lutS, lutS};
-      const int hid_sh[4] = {sh_tanhc, sh_tanhc, sh_sig, sh_sig};
-      const int hid_tm[4] = {sl.tm_tanhc, sl.tm_tanhc, a.tm_sig, a.tm_sig};
-      const uint16_t *const hid_full[4] = {sl.tanhc_tab, sl.tanhc_tab, a.sig_tab, a.sig_tab};
+      const int hid_tb[4] = {2, 2, 0, 0};
       LnRow2 lr[4];
       if (ph && ln) lr[3] = lnrow[3 * 32 + col];
       int32_t xv[4][4], tv[4][4], ov[2][4][4];
@@ -738,7 +768,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           for (int c = 0; c < 4; ++c) xv[2 + tl][c] = ov[tl][3][c];
         }
       }
-      lookup(ph ? 15 : 3, xv, hid_blob, hid_sh, hid_tm, hid_full, tv);
+      lookup(ph ? 15 : 3, xv, hid_tb, tv);
 #pragma unroll
       for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
@@ -778,7 +808,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     }
     TICK(8);
-    if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
+    if (!group_sync(counter, epoch, GS + a.extra_arrivals, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
     TICK(9);
 
     // ---- projection (Sec. 3.2.8)
@@ -790,7 +820,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const int ptile = member + pt * GS;
         const int8_t *mrow = mbuf + (size_t)t * a.Bp * a.npadp +
                              ((((size_t)(row0 >> 5) * (a.npadp >> 5) + wave * per_wave) * 32 + col) << 5) + (b2 << 4);
-        const int8_t *wrow = WpL + ((size_t)pt * 32 + col) * WLS + (b2 << 4) + wave * per_wave * 32;
+        const int8_t *wrow = WpL + ((size_t)pt * a.prow + (col < a.prow ? col : 0)) * WLS + (b2 << 4) + wave * per_wave * 32;
         int4 mv[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
@@ -812,7 +842,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         __syncthreads();
         {
           const int q = tid >> 6, l2 = tid & 63;
-          const int p0 = ptile * 32 + 8 * q + 4 * (l2 >> 5);
+          const int pl = 8 * q + 4 * (l2 >> 5);  // row of the tile; prow is a multiple of 4
+          const int p0 = ptile * a.prow + pl;
           const int orow = row0 + (l2 & 31);
           uint32_t pk = 0;
 #pragma unroll
@@ -820,11 +851,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             const int v = 4 * q + c;
             const int32_t s = pred[(0 * 16 + v) * 64 + l2] + pred[(1 * 16 + v) * 64 + l2] +
                               pred[(2 * 16 + v) * 64 + l2] + pred[(3 * 16 + v) * 64 + l2] +
-                              (pt == 0 ? bpr[c] : sl.bp2[p0 + c]);
+                              (pt == 0 ? bpr[c] : sl.bp2[ptile * 32 + pl + c]);
             const int32_t hq = sat8(rescale_sat16_pre(s, pp) + zp_h);
             pk |= (uint32_t)(hq & 0xFF) << (8 * c);
           }
-          if (orow < a.B && p0 < a.H) {
+          if (orow < a.B && p0 < a.H && pl < a.prow) {
             int8_t *od = out + ((size_t)t * a.B + orow) * a.Hpad + p0;
             if (p0 + 3 < a.H) {
               __hip_atomic_store(reinterpret_cast<uint32_t *>(od), pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -845,7 +876,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         __syncthreads();
       }
       TICK(10);
-      if (!group_sync(counter, epoch, GS, a.status, a.spin_limit, my_ptiles == 0 ? a.idle_sleep : 0,
+      if (!group_sync(counter, epoch, GS + a.extra_arrivals, a.status, a.spin_limit, my_ptiles == 0 ? a.idle_sleep : 0,
                       my_ptiles == 0 ? a.idle_poll_sleep : a.poll_sleep, flag))
         return;
       TICK(11);

@@ -181,23 +181,27 @@ def test_benchmark_configs_take_the_persistent_path(name):
     assert model.device_status() == 0
 
 
-def test_wait_gives_up_and_model_recovers(orc):
-    """A spin limit of one poll makes the waits inside the persistent kernel give
-    up: every workgroup leaves the kernel (no hang), the status word says so,
-    and after a reset the same model computes the right answer again."""
+@pytest.mark.parametrize("rows16", [1, 0])
+def test_wait_gives_up_and_model_recovers(orc, rows16):
+    """A barrier that cannot complete (option "barrier_never_completes": it waits for
+    one arrival more than will come) and a small spin limit make the waits inside
+    the persistent kernel give up: every workgroup leaves the kernel (no hang),
+    the status word says so, and after a reset the same model computes the right
+    answer again.  On both kernels of the one-layer path."""
     import torch
 
     print("bounded waits", flush=True)
     layers, x = wl.make_custom([40], 512, 512, wl.LAYER_NORM, 40, 6, seed=31, weight_param=0.05)
     lib_model, orc_model, xq = prepare_both(orc, layers, x)
     xd = torch.from_numpy(xq).cuda()
-    lib_model.set_option("spin_limit", 1)
-    for name in ("sync_sleep", "stats_first_sleep"):
-        lib_model.set_option(name, 0)
+    lib_model.set_option("rows16", rows16)
+    lib_model.set_option("spin_limit", 64)
+    lib_model.set_option("barrier_never_completes", 1)
     lib_model.forward(xd)
     torch.cuda.synchronize()
     assert lib_model.device_status() == 1
     lib_model.set_option("spin_limit", 1 << 21)
+    lib_model.set_option("barrier_never_completes", 0)
     lib_model.set_option("reset_status", 1)
     assert lib_model.device_status() == 0
     y = lib_model.forward(xd)

@@ -106,6 +106,33 @@ def test_stack_c4_layers(orc, B, T):
     assert _ran_stacked(lib_model, T, B, 512, layers)
 
 
+def test_stack_wait_gives_up_and_model_recovers(orc):
+    """The bounded waits of the stacked launch: with a barrier that cannot complete
+    every workgroup of every layer leaves the kernel -- the layers above give up on
+    the flag of the layer below -- the status word says so, and after a reset the
+    model computes the right answer again."""
+    import torch
+
+    print("stack bounded waits", flush=True)
+    layers, x = wl.make_custom([40, 512, 512], 512, 512, wl.LAYER_NORM, 40, 4, seed=33, weight_param=0.05)
+    lib_model, orc_model, xq = prepare_both(orc, layers, x)
+    lib_model.set_option("stack", 2)
+    xd = torch.from_numpy(xq).cuda()
+    lib_model.set_option("spin_limit", 64)
+    lib_model.set_option("barrier_never_completes", 1)
+    lib_model.forward(xd)
+    torch.cuda.synchronize()
+    assert lib_model.device_status() == 1
+    lib_model.set_option("spin_limit", 1 << 21)
+    lib_model.set_option("barrier_never_completes", 0)
+    lib_model.set_option("reset_status", 1)
+    assert lib_model.device_status() == 0
+    y = lib_model.forward(xd)
+    torch.cuda.synchronize()
+    assert lib_model.device_status() == 0
+    assert_equal("recovered", y.cpu().numpy(), orc.forward(orc_model, xq))
+
+
 def test_stack_falls_back(orc):
     """Layers that differ (or a trace request) run one after the other as before, with
     the option on."""

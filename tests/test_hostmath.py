@@ -31,10 +31,6 @@ def hm():
     L.hm_cell_update32.argtypes = [C.c_int32] * 5
     L.hm_rescale_sat16_pre.argtypes = [C.c_int32] * 3
     L.hm_rescale_sat16_pre.restype = C.c_int32
-    L.hm_compress.argtypes = [C.c_void_p, C.c_void_p]
-    L.hm_sigmoid_lut.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int32]
-    L.hm_tanh_lut.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int32]
-    L.hm_tail_prepare.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
     L.hm_rescale_ge32.restype = C.c_int32
     L.hm_rescale_ge32.argtypes = [C.c_int32] * 3
     L.hm_cell_update.argtypes = [C.c_int32] * 5
@@ -70,37 +66,6 @@ def test_rescale_ge32(orc, hm):
     for a in list(range(-5, 6)) + [2**31 - 1, -2**31, 2**30, -2**30]:
         for M in (2**30, 2**31 - 1, 2**30 + 1):
             assert hm.hm_rescale_ge32(a, M, 32) == orc.rescale(a, M, -1)
-
-
-@pytest.mark.parametrize("m", range(0, 9))
-def test_compressed_tables_exhaustive(orc, hm, m):
-    """The LDS form of the tables (8-bit deltas on block bases up to 16384; beyond, the
-    tail's own form -- a clamped index where the tail is flat, block starts and
-    step masks where it rises by at most one per entry -- or the full table where
-    there is none) returns the oracle's value for EVERY input.  The full table
-    handed to the lookup is poisoned wherever the blob must suffice."""
-    for kind in ("sigmoid", "tanh"):
-        tab = np.zeros(32769, np.uint16)
-        getattr(hm, f"hm_{kind}_table")(m, tab.ctypes.data)
-        blob = np.zeros(16384 + 2 * 2048, np.uint8)
-        sh = hm.hm_compress(tab.ctypes.data, blob.ctypes.data)
-        assert sh in (-1, 3, 4, 5, 6)
-        tail = hm.hm_tail_prepare(tab.ctypes.data, blob.ctypes.data, sh)
-        assert tail in (0, 1, 2)
-        if m == 3:
-            assert sh >= 5 and tail == 2  # the gate formats compress, tails included: no lookup leaves LDS
-        if kind == "tanh" and m <= 5:
-            assert sh >= 3 and tail != 0  # so do the cell formats of |c| up to 32
-        full = tab.copy()
-        if sh >= 0:
-            full[:16384] = 12345  # never read: the blob covers these
-            if tail != 0:
-                full[:] = 12345
-        f = getattr(hm, f"hm_{kind}_lut")
-        want = orc.int_sigmoid if kind == "sigmoid" else orc.int_tanh
-        xs = list(range(-32768, -16380)) + list(range(-16380, 16380, 3)) + list(range(16380, 32768))
-        for x in xs:
-            assert f(full.ctypes.data, blob.ctypes.data, sh, tail, x) == want(x, m), (kind, m, x, sh, tail)
 
 
 @pytest.mark.parametrize("m", range(0, 9))
