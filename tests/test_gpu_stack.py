@@ -106,6 +106,43 @@ def test_stack_c4_layers(orc, B, T):
     assert _ran_stacked(lib_model, T, B, 512, layers)
 
 
+@pytest.mark.parametrize("B,T", [(32, 3000), (70, 700)])
+def test_stack_long_sequences_match_the_layer_by_layer_path(orc, B, T):
+    """Many hand-offs between XCDs: the 8-layer headline stack over thousands of
+    steps on the stacked path gives, bit for bit, what the same library gives layer
+    after layer (the path the oracle checks at full size), outputs and final
+    states; and the first steps are checked against the oracle directly."""
+    import torch
+
+    from paper_2101_05453_amd import binding
+    from parity_util import calibrate_on_gpu
+
+    print(f"stack long B={B} T={T}", flush=True)
+    layers, x64 = wl.make_workload("C4", batch=B)
+    calibrate_on_gpu(layers, x64)
+    model = binding.prepare(layers, device=0)
+    rng = np.random.Generator(np.random.PCG64(T))
+    xq = rng.integers(-128, 128, (T, B, 512), dtype=np.int8)
+    xd = torch.from_numpy(xq).cuda()
+    outs = {}
+    for stack in (0, 2):
+        model.set_option("stack", stack)
+        hs = torch.zeros(8 * B * 640, dtype=torch.int8, device="cuda")
+        cs = torch.zeros(8 * B * 2048, dtype=torch.int16, device="cuda")
+        y = model.forward(xd, h_state=hs, c_state=cs)
+        torch.cuda.synchronize()
+        assert model.device_status() == 0
+        outs[stack] = (y.cpu().numpy(), hs.cpu().numpy(), cs.cpu().numpy())
+    for name, a, b in zip(("y", "h_state", "c_state"), outs[2], outs[0]):
+        assert_equal(f"long.{name}", a, b)
+    om = orc.prepare(layers)
+    rows = [0, B - 1]
+    hs0 = np.zeros(8 * 2 * 640, np.int8)
+    cs0 = np.zeros(8 * 2 * 2048, np.int16)
+    want = orc.forward(om, np.ascontiguousarray(xq[:12, rows]), h_state=hs0, c_state=cs0)
+    assert_equal("long.y vs oracle", outs[2][0][:12, rows], want)
+
+
 def test_stack_wait_gives_up_and_model_recovers(orc):
     """The bounded waits of the stacked launch: with a barrier that cannot complete
     every workgroup of every layer leaves the kernel -- the layers above give up on
