@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="fewer batch rows than the configuration has (its first rows)")
     ap.add_argument("--seq-len", type=int, default=0, help="fewer steps than the configuration has (its first steps)")
     ap.add_argument("--stack", type=int, default=-1, help="option 'stack' of the library (default: the library's own choice)")
+    ap.add_argument("--sparse", action="store_true",
+                    help="prune the synthetic weights W, R, W_proj to two nonzeros per aligned group of four inputs "
+                         "(the structured stand-in for the 50 %% sparse models of Table 1): R h runs on the sparse MFMA")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 one launch per operation and step")
     ap.add_argument("--mfma-store-ceiling", action="store_true",
@@ -99,6 +102,8 @@ def main():
         return
     cfg = wl.CONFIGS[args.config]
     layers, x = wl.make_workload(args.config, batch=args.batch or None, steps=args.seq_len or None)
+    if args.sparse:
+        wl.prune_2of4(layers, ("W", "R", "Wproj"))
     xf = torch.from_numpy(x).cuda()
     binding.calibrate(layers, xf, device=0, max_rows=16)  # statistics of the float run on the first 16 rows (Sec. 4)
     model = binding.prepare(layers, device=0)
@@ -194,7 +199,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": wl.describe(args.config) + (f" shrunk to B={B} T={T}" if (args.batch or args.seq_len) else ""),
+        "config": {"workload": wl.describe(args.config) + (f" shrunk to B={B} T={T}" if (args.batch or args.seq_len) else "") +
+                               (f" weights pruned 2:4 ({model.sparse_layers()} of {L} layers on the sparse MFMA)" if args.sparse else ""),
                    "cell_steps_per_step": cell_steps,
                    "batch": B, "seq_len": T, "layers": L,
                    "options": "library defaults (plain launch of the recurrent kernel)"},

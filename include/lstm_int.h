@@ -288,6 +288,12 @@ int lstm_int_forward_static(const lstm_int_model *model, const int8_t *x, int32_
  *   "idle_sleep", "idle_poll_sleep": the same for the workgroups that have no
  *           projection tile, at the barrier that follows the projection: pause
  *           before their first poll and between polls (defaults 64 and 12).
+ *   "sparse": 1 (default) runs the recurrent product of a layer whose quantized
+ *           recurrent weights are 2:4 along the contraction (at most two nonzeros
+ *           in every aligned group of four h inputs; see lstm_int_sparse_layers)
+ *           on the sparse MFMA where the persistent kernel for groups of 32 rows
+ *           runs; 0 = always the dense product.  The results are the same
+ *           integers either way.
  *   "reset_status": clears the device status word (see lstm_int_device_status)
  *           after a wait gave up; synchronizes the device.
  *   "phase_timing": nonzero makes workgroup 0 of the persistent kernel add the
@@ -297,6 +303,17 @@ int lstm_int_forward_static(const lstm_int_model *model, const int8_t *x, int32_
  * Unknown keys or values give LSTM_INT_E_INVALID_ARG.
  */
 int lstm_int_set_option(lstm_int_model *model, const char *key, int64_t value);
+
+/*
+ * Pruned models (Table 1, the sparse LSTM and sparse CIFG rows): *count receives
+ * the number of layers whose quantized recurrent weights R are 2:4 structured
+ * -- every row has at most two nonzero weights in each aligned group of four
+ * consecutive inputs h[4j .. 4j+3] -- and for which prepare therefore also
+ * built the compressed operands of the sparse MFMA (option "sparse").  A zero
+ * weight is one whose int8 code is 0; symmetric weight quantization (Table 2)
+ * maps a pruned float weight to exactly that.  Host only; no device work.
+ */
+int lstm_int_sparse_layers(const lstm_int_model *model, int32_t *count);
 
 /*
  * Blocking read of the model's device status word: 0 = every persistent

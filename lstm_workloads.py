@@ -152,6 +152,37 @@ def make_workload(name, batch=None, steps=None, seed=None, num_layers=None):
     return layers, np.ascontiguousarray(x[:T, :B])
 
 
+def prune_2of4(layers, tensors=("R",)):
+    """Stand-in for the pruned models of the paper's Table 1 (50 % sparse LSTM and
+    CIFG) in structured form: in every aligned group of four consecutive inputs of
+    every row of the named weight tensors ("W", "R", "Wproj") the two entries of
+    smallest magnitude are set to 0.0 (ties: the lower index goes first).  In place;
+    returns layers.  Pure input structure: no arithmetic of the method."""
+    def prune(w):
+        rows, K = w.shape
+        full = (K // 4) * 4
+        if full:
+            g = w[:, :full].reshape(rows, full // 4, 4)
+            order = np.argsort(np.abs(g), axis=2, kind="stable")
+            np.put_along_axis(g, order[:, :, :2], np.float32(0.0), axis=2)
+            w[:, :full] = g.reshape(rows, full)
+        rest = K - full  # a last group of fewer than four inputs keeps at most two
+        if rest == 3:
+            k = full + np.argmin(np.abs(w[:, full:]), axis=1)
+            w[np.arange(rows), k] = 0.0
+
+    for spec in layers:
+        for name in tensors:
+            if name == "Wproj":
+                if spec.Wproj is not None:
+                    prune(spec.Wproj)
+            else:
+                for m in getattr(spec, name):
+                    if m is not None:
+                        prune(m)
+    return layers
+
+
 def describe(name):
     cfg = CONFIGS[name]
     v = [n for bit, n in ((CIFG, "cifg"), (PEEPHOLE, "peephole"), (LAYER_NORM, "layernorm"),

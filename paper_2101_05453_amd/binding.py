@@ -109,6 +109,8 @@ def lib():
         L.lstm_int_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
         L.lstm_int_device_status.restype = C.c_int
         L.lstm_int_device_status.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+        L.lstm_int_sparse_layers.restype = C.c_int
+        L.lstm_int_sparse_layers.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         L.lstm_int_phase_ticks.restype = C.c_int
         L.lstm_int_phase_ticks.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
         L.lstm_int_profile_begin.restype = C.c_int
@@ -240,6 +242,12 @@ class Model:
     # lstm_int_set_option
     def set_option(self, key, value):
         _check(lib().lstm_int_set_option(self._h, key.encode(), value), "lstm_int_set_option")
+
+    # lstm_int_sparse_layers
+    def sparse_layers(self):
+        v = C.c_int32(0)
+        _check(lib().lstm_int_sparse_layers(self._h, C.byref(v)), "lstm_int_sparse_layers")
+        return v.value
 
     # lstm_int_device_status
     def device_status(self):

@@ -90,6 +90,7 @@ struct LayerDev {
   int8_t *W2f = nullptr;    // the same in MFMA operand order [GS*8][Ipad/32][64 lanes][16] (Ipad <= 1024), else NULL
   int32_t *bx2 = nullptr;   // [GS*8][32]
   int4 *R2 = nullptr;       // [GS][4][2][ks][64]
+  int4 *R2s = nullptr;      // the same weights in the 2:4 compressed form (persistent.h), or NULL: R is not 2:4
   bool p16 = false;         // the 16-row kernel takes this layer (small batches)
   int ks16 = 0;
   int4 *R2h = nullptr;      // [GS][4][4][ks16][64]
@@ -135,6 +136,7 @@ struct lstm_int_model {
   int reverse = 0;  // 1: the recursion runs from time T - 1 down to 0
   int cooperative = 0;  // 1: the persistent kernel is launched cooperatively
   int rows16 = 1;       // 1: batches that fit one launch of the 16-row kernel take it
+  int sparse = 1;       // 1: layers whose recurrent weights are 2:4 run R h on the sparse MFMA (32-row kernel)
   int stack = 1;        // stacked launch (one layer per XCD): 0 never, 1 where it is expected to be faster, 2 wherever it can run
   int flag_sleep = 2;   // stacked launch: pause between two polls of the layer below's flag, x 64 clocks
   double stack_step_us = 20.5;
@@ -391,7 +393,8 @@ int upload(lstm_int_model *m) {
       // tile-ordered copies for the persistent path
       int ks = 0, rt = 0, grp = 0;
       d.p2 = rec_supported(h.N, h.H, (int)h.flags, 32, &ks, &rt, &grp);
-      size_t oW2f = 0, oR2h = 0;
+      size_t oW2f = 0, oR2h = 0, oR2s = 0;
+      bool r_sparse = false;
       int ks16 = 0, grp16 = 0;
       d.p16 = d.p2 && rec16_supported(h.N, h.H, (int)h.flags, 16, &ks16, &grp16);
       size_t oW2 = 0, obx2 = 0, oR2 = 0, obh4 = 0, oqb4 = 0, oLq4 = 0, oPq3 = 0, oWp2 = 0, obp2 = 0, oWp3 = 0, obp3 = 0;
@@ -405,6 +408,11 @@ int upload(lstm_int_model *m) {
         if (d.Ipad <= 1024) oW2f = take((size_t)d.GS * 8 * 32 * d.Ipad);
         obx2 = take((size_t)d.GS * 8 * 32 * 4);
         oR2 = take((size_t)d.GS * 4 * 2 * ks * 64 * 16);
+        r_sparse = true;
+        for (int g = first; g < 4 && r_sparse; ++g)
+          for (int n = 0; n < h.N && r_sparse; ++n)
+            r_sparse = sparse24_row_ok(h.Rq.data() + ((size_t)g * h.N + n) * h.H, h.H);
+        if (r_sparse) oR2s = take(rec_sparse_bytes(d.GS, ks));
         if (d.p16) {
           d.ks16 = ks16;
           oR2h = take((size_t)d.GS * 4 * 4 * ks16 * 64 * 16);
@@ -458,6 +466,17 @@ int upload(lstm_int_model *m) {
               const size_t o = ((((size_t)(member * 4 + wave) * 2 + tl) * ks + kstep) * 64 + lane) * 16 + byte;
               base[oR2 + o] = (uint8_t)h.Rq[src * h.H + k];
             }
+            if (r_sparse) {
+              const int kw = ks / 2;
+              uint8_t *vals = base + oR2s;
+              uint32_t *index = reinterpret_cast<uint32_t *>(vals + (size_t)d.GS * 4 * 2 * kw * 64 * 16);
+              for (int q = 0; q < kw; ++q)
+                for (int a2 = 0; a2 < 2; ++a2) {
+                  const size_t slot = (((size_t)(member * 4 + wave) * 2 + tl) * kw + q) * 64 + rho + 32 * a2;
+                  sparse24_pack_lane(h.Rq.data() + src * h.H, h.H, q, a2, reinterpret_cast<int8_t *>(vals + slot * 16),
+                                     index + slot);
+                }
+            }
             if (d.p16) {
               // 16-row kernel: [member][wave][tile j][ks16][lane][16]; tile j of a wave holds cell
               // 16 wave + 4 q + j of gate g in row 4 q + g, lane = row + 16 * (k / 16 % 4)
@@ -490,6 +509,7 @@ int upload(lstm_int_model *m) {
         d.bx2 = reinterpret_cast<int32_t *>(db + obx2);
         d.R2 = reinterpret_cast<int4 *>(db + oR2);
         d.R2h = d.p16 ? reinterpret_cast<int4 *>(db + oR2h) : nullptr;
+        d.R2s = r_sparse ? reinterpret_cast<int4 *>(db + oR2s) : nullptr;
         d.bh4 = reinterpret_cast<int32_t *>(db + obh4);
         d.qb4 = reinterpret_cast<int32_t *>(db + oqb4);
         d.Lq4 = reinterpret_cast<int16_t *>(db + oLq4);
@@ -959,6 +979,11 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
           use16 = true;
         }
       }
+      // 2:4 recurrent weights: the 32-row kernel with one row tile per group has a sparse-MFMA form
+      if (use_p2 && !use16 && m->sparse && d.R2s && ra.rows_pg == 32) {
+        ra.R2 = d.R2s;
+        ra.sparse = 1;
+      }
     }
     if (use_p2) {
       auto lds_need = [&]() { return use16 ? rec16_lds_bytes(ra) : rec_lds_bytes(ra); };
@@ -1185,6 +1210,11 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
     m->cooperative = (int)value;
     return LSTM_INT_OK;
   }
+  if (!strcmp(key, "sparse")) {
+    if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
+    m->sparse = (int)value;
+    return LSTM_INT_OK;
+  }
   if (!strcmp(key, "rows16")) {
     if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
     m->rows16 = (int)value;
@@ -1250,6 +1280,14 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
     return LSTM_INT_OK;
   }
   return LSTM_INT_E_INVALID_ARG;
+}
+
+int lstm_int_sparse_layers(const lstm_int_model *m, int32_t *count) {
+  if (!m || !count) return LSTM_INT_E_INVALID_ARG;
+  int32_t n = 0;
+  for (const LayerDev &d : m->dev) n += d.R2s != nullptr;
+  *count = n;
+  return LSTM_INT_OK;
 }
 
 int lstm_int_device_status(const lstm_int_model *m, int32_t *status) {

@@ -54,6 +54,10 @@ int hm_compress_wide(const uint16_t *tab, uint8_t *blob, int *has_tail, int *fla
 int32_t hm_lut_wide_mag(const uint8_t *blob, int sh, int dom, int with_tail, int32_t a) {
   return lut_wide_mag(blob, sh, dom, with_tail != 0, a);
 }
+int hm_sparse24_row_ok(const int8_t *row, int K) { return sparse24_row_ok(row, K) ? 1 : 0; }
+void hm_sparse24_pack_lane(const int8_t *row, int K, int q, int a, int8_t *vals, uint32_t *index) {
+  sparse24_pack_lane(row, K, q, a, vals, index);
+}
 int32_t hm_rescale_ge32(int32_t a, int32_t M, int32_t r) { return rescale_ge32(a, M, r); }
 int32_t hm_cifg(int32_t f) { return cifg_input_gate(f); }
 int32_t hm_cell_update(int32_t i, int32_t z, int32_t f, int32_t c, int32_t m_c) {

@@ -49,6 +49,14 @@ void fill_tanh_table(int m, uint16_t *tab /*[32769]*/);
 // within 8 bits); *has_tail = the tail part is filled (the table rises by at most one per entry from 16384
 // on); *flat_from = first index from which on every entry is equal.
 int compress_table_wide(const uint16_t *tab, uint8_t *blob /*[kLutWideBytes]*/, int *has_tail, int *flat_from);
+// 2:4 structure along k of a weight row (the pruned models of Table 1 in structured form): at most two nonzeros in
+// every aligned group of four.
+bool sparse24_row_ok(const int8_t *row, int K);
+// One lane's operand of the sparse MFMA for k step q (64 deep) of such a row (entries at k >= K count as zero): lane
+// half a holds the groups k = 64 q + (j < 4 ? 0 : 32) + 16 a + 4 (j % 4) + 0..3, j = 0..7, as values 2 j, 2 j + 1 (the
+// two kept weights in ascending position; zeros fill a group with fewer) and their positions in index bits
+// [4 j + 1 : 4 j] and [4 j + 3 : 4 j + 2].
+void sparse24_pack_lane(const int8_t *row, int K, int q, int a, int8_t vals[16], uint32_t *index);
 // exp(-y / 2^15) in Q0.31, y >= 0 (exposed for host-side checks)
 int64_t exp_neg_q31(int64_t y);
 

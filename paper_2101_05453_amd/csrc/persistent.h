@@ -100,7 +100,7 @@ struct RecArgs {
   int ks;         // 32-wide k steps held in registers (template KS)
   int Ncp;        // GS * 64
   int Bp;         // B rounded up to 32
-  const int4 *R2;      // [GS][4 waves][2 tiles][ks][64 lanes] 16 bytes each
+  const int4 *R2;      // [GS][4 waves][2 tiles][ks][64 lanes] 16 bytes each (sparse != 0: see rec_sparse_bytes)
   const int4 *R2h;     // 16-row kernel: [GS][4 waves][4 tiles][ks16][64 lanes] 16 bytes each
   int ks16;            // 16-row kernel: 64-wide k steps held in registers
   const int32_t *bh4;  // [4][Ncp]
@@ -145,7 +145,21 @@ struct RecArgs {
   long long *ticks;  // NULL, or [16] phase timers of workgroup 0 (diagnostics)
   int extra_arrivals;  // 0; tests set 1: every group barrier then waits for an arrival that never comes, so that
                        // the bounded waits give up (and every workgroup leaves the kernel) on demand
+  int sparse;  // rec_kernel, 32 rows per group: R2 holds the recurrent weights in the 2:4 compressed form below
 };
+
+// Recurrent weights with at most two nonzeros in every aligned group of four along k (the pruned models of
+// Table 1 in their structured form) as operands of the sparse MFMA v_smfmac_i32_32x32x64_i8, which takes a
+// 64-deep k step in the time the dense 32x32x32 instruction takes a 32-deep one:
+//   values  [GS][4 waves][2 tiles][ks / 2][64 lanes] 16 bytes,
+//   indices [GS][4 waves][2 tiles][ks / 2][64 lanes] 4 bytes, behind all the values.
+// Lane = rho + 32 * a (rho = the tile row, as in R2) holds, for k step q, the groups of four
+//   k = 64 q + (j < 4 ? 0 : 32) + 16 a + 4 (j % 4) + 0..3,   j = 0..7,
+// as value bytes 2 j and 2 j + 1 (the group's two kept weights; a group with fewer nonzeros is filled with
+// zeros at other positions) and index bits [4 j + 1 : 4 j], [4 j + 3 : 4 j + 2] (their positions in the group).
+// The other operand is dense: lane (row, b) holds k = 64 q + 32 b + 0..31 (layout checked on the device against
+// a host product).
+inline size_t rec_sparse_bytes(int GS, int ks) { return (size_t)GS * 4 * 2 * (ks / 2) * 64 * (16 + 4); }
 
 // Whether a layer shape can take the persistent path; fills ks and rt.
 bool rec_supported(int N, int H, int flags, int B, int *ks, int *rt, int *groups);

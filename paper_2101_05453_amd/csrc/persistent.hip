@@ -206,6 +206,15 @@ typedef void (*rec_fn)(RecArgs);
 rec_fn rec_pick_8(int rt, int fl);   // rec_inst_8.hip
 rec_fn rec_pick_20(int rt, int fl);  // rec_inst_20.hip
 rec_fn rec_pick_32(int rt, int fl);  // rec_inst_32.hip
+rec_fn rec_pick_sparse_8(int fl);   // rec_sparse_inst_8.hip
+rec_fn rec_pick_sparse_20(int fl);  // rec_sparse_inst_20.hip
+rec_fn rec_pick_sparse_32(int fl);  // rec_sparse_inst_32.hip
+static rec_fn pick_sparse(int ks, int fl) {
+  if (ks == 8) return rec_pick_sparse_8(fl);
+  if (ks == 20) return rec_pick_sparse_20(fl);
+  if (ks == 32) return rec_pick_sparse_32(fl);
+  return nullptr;
+}
 static rec_fn pick(int ks, int rt, int fl) {
   if (ks == 8) return rec_pick_8(rt, fl);
   if (ks == 20) return rec_pick_20(rt, fl);
@@ -223,11 +232,19 @@ hipError_t rec_init() {
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
       }
+  for (int ks : kKS)
+    for (int fl = 0; fl < 16; ++fl) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_sparse(ks, fl)),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) return e;
+    }
   return hipSuccess;
 }
 
 hipError_t launch_rec(hipStream_t s, const RecArgs &a, bool cooperative) {
-  rec_fn fn = pick(a.ks, a.rows_pg / 32, (a.flags & 7) | ((a.flags & 8) ? 0 : 8));  // bit 3: no projection
+  const int fl = (a.flags & 7) | ((a.flags & 8) ? 0 : 8);  // bit 3: no projection
+  if (a.sparse && a.rows_pg != 32) return hipErrorInvalidValue;
+  rec_fn fn = a.sparse ? pick_sparse(a.ks, fl) : pick(a.ks, a.rows_pg / 32, fl);
   if (!fn) return hipErrorInvalidValue;
   const int slots = a.GS * ((a.groups + 7) / 8);
   RecArgs args = a;

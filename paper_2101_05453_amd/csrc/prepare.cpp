@@ -262,6 +262,39 @@ int64_t exp_neg_q31(int64_t y) {
   return (int64_t)acc;
 }
 
+bool sparse24_row_ok(const int8_t *row, int K) {
+  for (int k0 = 0; k0 < K; k0 += 4) {
+    int nz = 0;
+    for (int k = k0; k < k0 + 4 && k < K; ++k) nz += row[k] != 0;
+    if (nz > 2) return false;
+  }
+  return true;
+}
+
+void sparse24_pack_lane(const int8_t *row, int K, int q, int a, int8_t vals[16], uint32_t *index) {
+  uint32_t idx = 0;
+  for (int j = 0; j < 8; ++j) {
+    const int kb = 64 * q + (j < 4 ? 0 : 32) + 16 * a + 4 * (j % 4);
+    int pos[2] = {0, 1}, n = 0;
+    for (int i = 0; i < 4; ++i)
+      if (kb + i < K && row[kb + i] != 0 && n < 2) pos[n++] = i;
+    if (n == 1) {  // the second slot takes a neighbouring position, which holds a zero
+      if (pos[0] < 3) {
+        pos[1] = pos[0] + 1;
+      } else {
+        pos[1] = 3;
+        pos[0] = 2;
+      }
+    }
+    for (int s = 0; s < 2; ++s) {
+      const int k = kb + pos[s];
+      vals[2 * j + s] = k < K ? row[k] : (int8_t)0;
+      idx |= (uint32_t)pos[s] << (4 * j + 2 * s);
+    }
+  }
+  *index = idx;
+}
+
 int compress_table_wide(const uint16_t *tab, uint8_t *blob, int *has_tail, int *flat_from) {
   int F = 32768;
   while (F > 0 && tab[F - 1] == tab[32768]) --F;

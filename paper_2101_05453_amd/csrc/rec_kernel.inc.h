@@ -11,6 +11,7 @@
 namespace lstm_int {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned long long u64;
 
@@ -26,9 +27,13 @@ typedef unsigned long long u64;
 // added made the barrier slower).  Gives up after spin_limit polls (or when
 // another workgroup gave up), raising the status word so that every workgroup
 // leaves the kernel; lds_flag[0] is then 0 for good.
+// PENDING: vector memory loads the caller issued after its last store and does
+// not need yet (the counter of outstanding operations drains in issue order, so
+// waiting until PENDING are left means every store before them is complete).
+template <int PENDING = 0>
 __device__ __forceinline__ bool group_sync(unsigned *counter, unsigned &epoch, int GS, int *status,
                                            int spin_limit, int first_sleep, int poll_sleep, int *lds_flag) {
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
   __syncthreads();
   if (GS == 1) return true;
   epoch += (unsigned)GS;
@@ -82,8 +87,9 @@ __device__ __forceinline__ int32_t mirror_tanh(int32_t x, int32_t t) {
 
 // FL: bit 0 CIFG, bit 1 peephole, bit 2 layer norm, bit 3 "no projection" (compile
 // time, so that the code carries no tests of them); with bit 3 clear the
-// projection is a runtime flag.
-template <int KS, int RT, int FL>
+// projection is a runtime flag.  SP: the recurrent weights are in the 2:4
+// compressed form (persistent.h) and R h runs on the sparse MFMA.
+template <int KS, int RT, int FL, bool SP = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void rec_kernel(RecArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const long long t_start = (long long)wall_clock64();
@@ -184,20 +190,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   // ---- one-time loads: R slice and its biases -> registers, other per-cell
   // parameters, the tables and the W_proj tiles -> LDS
-  v4i Wf[2][KS];
+  constexpr int KW = SP ? KS / 2 : KS;  // weight operands per tile: 64-deep k steps in the sparse form
+  static_assert(!SP || KS % 2 == 0, "the sparse form takes k in steps of 64");
+  v4i Wf[2][KW];
+  int Wi[2][SP ? KW : 1];  // sparse form: the index word of each operand
   {
-    const int4 *src = a.R2 + ((size_t)(member * 4 + wave) * 2) * KS * 64 + lane;
+    const int4 *src = a.R2 + ((size_t)(member * 4 + wave) * 2) * KW * 64 + lane;
+    const int *isrc = reinterpret_cast<const int *>(a.R2 + (size_t)GS * 4 * 2 * KW * 64) +
+                      ((size_t)(member * 4 + wave) * 2) * KW * 64 + lane;
     // all loads of a tile are in flight together before the first is moved to its place
 #pragma unroll
     for (int tl = 0; tl < 2; ++tl) {
-      int4 w[KS];
+      int4 w[KW];
+      int wi[KW];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) w[ks] = src[(size_t)(tl * KS + ks) * 64];
+      for (int ks = 0; ks < KW; ++ks) {
+        w[ks] = src[(size_t)(tl * KW + ks) * 64];
+        if (SP) wi[ks] = isrc[(size_t)(tl * KW + ks) * 64];
+      }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
+      for (int ks = 0; ks < KW; ++ks) {
         Wf[tl][ks] = v4i{w[ks].x, w[ks].y, w[ks].z, w[ks].w};
         asm volatile("" : "+a"(Wf[tl][ks]));  // resident in accumulation registers for the whole launch
+        if (SP) {
+          Wi[tl][ks] = wi[ks];
+          asm volatile("" : "+v"(Wi[tl][ks]));  // the index operand is read from an ordinary vector register
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -353,8 +372,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   };
 
 
+  // The W x terms of a step come from memory, not from a cache.  The dense kernel asks for them after the h tile
+  // is in LDS: the MFMA phase covers the latency.  The sparse kernel's MFMA phase is too short for that (measured:
+  // the gate sums, and then the whole group at the statistics, waited for the slowest workgroup's terms), so it
+  // asks for the terms of step t before the last barrier of step t - 1 (those of step 0 ahead of the loop).
+  // That is not free -- the polling wave's loads return in issue order, so its polls wait behind its own W x
+  // loads -- which is why the dense kernel does not do the same (measured: 1.2 % slower with it).
+  constexpr bool TX_AHEAD = SP;
+  int4 txv[RT][2][2];
+  auto load_tx = [&](int t) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl) {
+        const int4 *src = tx_ptr(t, rt, tl);  // clamped to the last row block: step T reads step T - 1's again
+        // read once: a streaming load keeps the W x terms from displacing the exchange buffers in L2
+        const v4i t0 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src));
+        const v4i t1 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src + 64));
+        txv[rt][tl][0] = int4{t0.x, t0.y, t0.z, t0.w};
+        txv[rt][tl][1] = int4{t1.x, t1.y, t1.z, t1.w};
+      }
+  };
+  constexpr int TXLOADS = TX_AHEAD ? RT * 4 : 0;  // vector loads in flight across the step's last barrier
+  if (TX_AHEAD && a.T > 0) load_tx(0);
+
   for (int t = 0; t < a.T; ++t) {
-    // ---- h^{t-1} rows of the group -> LDS; W x terms of this step -> registers
+    // ---- h^{t-1} rows of the group -> LDS
     {
       const int8_t *hp = t == 0 ? a.h0 : a.out + (size_t)(t - 1) * a.B * a.Hpad;
 #pragma unroll
@@ -366,18 +409,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __syncthreads();
-    int4 txv[RT][2][2];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-      for (int tl = 0; tl < 2; ++tl) {
-        const int4 *src = tx_ptr(t, rt, tl);
-        // read once: a streaming load keeps the W x terms from displacing the exchange buffers in L2
-        const v4i t0 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src));
-        const v4i t1 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(src + 64));
-        txv[rt][tl][0] = int4{t0.x, t0.y, t0.z, t0.w};
-        txv[rt][tl][1] = int4{t1.x, t1.y, t1.z, t1.w};
-      }
+    if (!TX_AHEAD) load_tx(t);
     TICK(0);
 
     // ---- R h on the MFMA: acc[rt][tile][4*gate + c]
@@ -388,7 +420,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[rt][tl][v] = bhL[(v >> 2) * 64 + cell_w + tl * 8 + (v & 3)];
-    {
+    if constexpr (SP) {
+      constexpr int DEPTH = 2;  // 64-deep h fragments in flight ahead of the MFMAs
+      v8i hf[RT][DEPTH];
+      const int8_t *hbase = hT + (size_t)col * LS + (b2 << 5);
+      auto frag = [&](int rt, int kq) {
+        const v4i lo = *reinterpret_cast<const v4i *>(hbase + (size_t)rt * 32 * LS + kq * 64);
+        const v4i hi = *reinterpret_cast<const v4i *>(hbase + (size_t)rt * 32 * LS + kq * 64 + 16);
+        return v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      };
+#pragma unroll
+      for (int kq = 0; kq < DEPTH && kq < KW; ++kq)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) hf[rt][kq] = frag(rt, kq);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kq = 0; kq < KW; ++kq) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+          for (int tl = 0; tl < 2; ++tl)
+            acc[rt][tl] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(Wf[tl][kq], hf[rt][kq % DEPTH], acc[rt][tl], Wi[tl][kq], 0, 0);
+          if (kq + DEPTH < KW) hf[rt][kq % DEPTH] = frag(rt, kq + DEPTH);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
       constexpr int DEPTH = 4;  // h fragments in flight ahead of the MFMAs
       v4i hf[RT][DEPTH];
       const int8_t *hbase = hT + (size_t)col * LS + (b2 << 4);
@@ -767,11 +824,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
     }
     TICK(6);
-    if (!group_sync(counter, epoch, GS + a.extra_arrivals, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
+    if (proj) {
+      if (!group_sync(counter, epoch, GS + a.extra_arrivals, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
+    } else {
+      if (TX_AHEAD) load_tx(t + 1);
+      if (!group_sync<TXLOADS>(counter, epoch, GS + a.extra_arrivals, a.status, a.spin_limit, a.sync_sleep, a.poll_sleep, flag)) return;
+    }
     TICK(7);
 
     // ---- projection (Sec. 3.2.8): tile pt of 32 outputs, K = N split over the four waves
     if (proj) {
+
       const int per_wave = a.npadp >> 7;  // 32-wide k steps per wave, at most 16 (N <= 2048)
       const RescaleHi pp = prm->p;
       const int32_t zp_h = prm->zp_h;
@@ -848,7 +911,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
       }
       TICK(8);
-      if (!group_sync(counter, epoch, GS + a.extra_arrivals, a.status, a.spin_limit, my_ptiles == 0 ? a.idle_sleep : 0,
+      if (TX_AHEAD) load_tx(t + 1);
+      if (!group_sync<TXLOADS>(counter, epoch, GS + a.extra_arrivals, a.status, a.spin_limit, my_ptiles == 0 ? a.idle_sleep : 0,
                       my_ptiles == 0 ? a.idle_poll_sleep : a.poll_sleep, flag))
         return;
       TICK(9);
@@ -884,6 +948,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
 
 typedef void (*rec_fn)(RecArgs);
+
+// sparse-weight kernel for the flags at k depth KS (one row tile per group)
+template <int KS>
+rec_fn rec_pick_sparse_ks(int fl) {
+#define LSTM_REC_CASE(F) \
+  if (fl == F) return rec_kernel<KS, 1, F, true>;
+  LSTM_REC_CASE(0) LSTM_REC_CASE(1) LSTM_REC_CASE(2) LSTM_REC_CASE(3)
+  LSTM_REC_CASE(4) LSTM_REC_CASE(5) LSTM_REC_CASE(6) LSTM_REC_CASE(7)
+  LSTM_REC_CASE(8) LSTM_REC_CASE(9) LSTM_REC_CASE(10) LSTM_REC_CASE(11)
+  LSTM_REC_CASE(12) LSTM_REC_CASE(13) LSTM_REC_CASE(14) LSTM_REC_CASE(15)
+#undef LSTM_REC_CASE
+  return nullptr;
+}
 
 // kernel for (rt, flags & 7) at k depth KS
 template <int KS>

@@ -1,0 +1,6 @@
+// Instantiations of the persistent recurrent kernel with 2:4 sparse recurrent weights, k depth 20.
+#include "rec_kernel.inc.h"
+
+namespace lstm_int {
+rec_fn rec_pick_sparse_20(int fl) { return rec_pick_sparse_ks<20>(fl); }
+}  // namespace lstm_int

@@ -1,0 +1,6 @@
+// Instantiations of the persistent recurrent kernel with 2:4 sparse recurrent weights, k depth 8.
+#include "rec_kernel.inc.h"
+
+namespace lstm_int {
+rec_fn rec_pick_sparse_8(int fl) { return rec_pick_sparse_ks<8>(fl); }
+}  // namespace lstm_int

@@ -198,3 +198,51 @@ def test_cell_update_and_hidden(orc, hm):
         assert hm.hm_hidden(o, tc, M, 31 - e, zp) == want
     for f in (0, 1, 16384, 32767):
         assert hm.hm_cifg(f) == min(32768 - f, 32767)
+
+
+def test_sparse_operand_packing(hm):
+    """The 2:4 compressed form of recurrent weight rows (sparse MFMA operands): unpacking every lane's
+    values through its index bits, at the k positions the layout states, gives the row back; and the
+    sparse dot product over that form equals the dense one."""
+    rng = np.random.default_rng(11)
+    hm.hm_sparse24_row_ok.argtypes = [C.c_void_p, C.c_int]
+    hm.hm_sparse24_pack_lane.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    for K in (4, 7, 62, 64, 100, 128, 640, 1023):
+        for kind in ("two", "mixed", "empty"):
+            row = np.zeros(K, np.int8)
+            for k0 in range(0, K, 4):
+                width = min(4, K - k0)
+                n = {"two": 2, "mixed": int(rng.integers(0, 3)), "empty": 0}[kind]
+                pos = rng.choice(width, size=min(n, width, 2), replace=False)
+                vals = rng.integers(-128, 128, size=len(pos))
+                vals[vals == 0] = 5
+                row[k0 + pos] = vals
+            assert hm.hm_sparse24_row_ok(row.ctypes.data, K) == 1
+            steps = (K + 63) // 64
+            back = np.zeros(steps * 64, np.int8)
+            hvec = rng.integers(-128, 128, size=steps * 64).astype(np.int64)
+            dot = 0
+            for q in range(steps):
+                for a in range(2):
+                    vals = np.zeros(16, np.int8)
+                    idx = C.c_uint32(0)
+                    hm.hm_sparse24_pack_lane(row.ctypes.data, K, q, a, vals.ctypes.data, C.byref(idx))
+                    for j in range(8):
+                        kb = 64 * q + (0 if j < 4 else 32) + 16 * a + 4 * (j % 4)
+                        p0 = (idx.value >> (4 * j)) & 3
+                        p1 = (idx.value >> (4 * j + 2)) & 3
+                        assert p0 < p1, (K, q, a, j, idx.value)
+                        for s, pp in ((0, p0), (1, p1)):
+                            v = int(vals[2 * j + s])
+                            assert back[kb + pp] == 0
+                            back[kb + pp] = v
+                            dot += v * int(hvec[kb + pp])
+            assert (back[:K] == row).all() and not back[K:].any(), (K, kind)
+            assert dot == int((row.astype(np.int64) * hvec[:K]).sum())
+    # three nonzeros in one aligned group: not 2:4
+    bad = np.zeros(64, np.int8)
+    bad[[8, 9, 11]] = 1
+    assert hm.hm_sparse24_row_ok(bad.ctypes.data, 64) == 0
+    ok = np.zeros(64, np.int8)
+    ok[[7, 8, 9, 12]] = 1  # spans two groups
+    assert hm.hm_sparse24_row_ok(ok.ctypes.data, 64) == 1
