@@ -35,7 +35,18 @@ void hm_layernorm2(const int16_t *q, int32_t n, const int16_t *qL, const int32_t
   const LnRow2 row = ln_row2(ln_row(s1, s2, n, 1.0 / (double)n));
   const RescaleHi p = rescale_hi_prepare(M, r);
   for (int i = 0; i < n; ++i)
-    out[i] = (int16_t)ln_apply2(q[i], row, ln_weight_scaled(qL[i]), ln_bias_scaled(qb[i]), p);
+    out[i] = ln_row_is_narrow(row)
+                 ? (int16_t)rescale_sat16_pre(ln_second_stage_narrow(q[i], row, ln_weight_scaled(qL[i]), ln_bias_scaled(qb[i])), p)
+                 : (int16_t)ln_apply2(q[i], row, ln_weight_scaled(qL[i]), ln_bias_scaled(qb[i]), p);
+}
+// 1 if a row with these statistics takes the second stage without the int32 clamp
+int hm_ln_row_is_narrow(const int16_t *q, int32_t n) {
+  int64_t s1 = 0, s2 = 0;
+  for (int i = 0; i < n; ++i) {
+    s1 += q[i];
+    s2 += (int64_t)q[i] * q[i];
+  }
+  return ln_row_is_narrow(ln_row2(ln_row(s1, s2, n, 1.0 / (double)n))) ? 1 : 0;
 }
 int32_t hm_rescale_sat16_pre(int32_t a, int32_t M, int32_t r) {
   return rescale_sat16_pre(a, rescale_hi_prepare(M, r));

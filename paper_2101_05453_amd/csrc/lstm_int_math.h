@@ -249,6 +249,15 @@ LSTM_HD int32_t ln_second_stage(int32_t q, const LnRow2 &row, double qLs, double
   v = fmin(fmax(v, -2147483648.0), 2147483647.0);
   return f64_low_word(v + 6755399441055744.0);
 }
+// The same without the clamp, for rows with sigma >= 2^12 (or sigma = 0), which ln_row_is_narrow tells from
+// a = 2^20 / sigma <= 2^8: the numerator 2^20 q + c0 is below 2^36 + 2^25 in magnitude (|2^10 q - mean| <= 2^26,
+// sigma < 2^25), so |q'| <= 2^24 + 2^13, |q' qL| <= 2^39 + 2^28, and with |qb| <= 2^31 the second-stage value
+// (q' qL + qb) / 2^10 stays below 2^30: sat32 never acts.  (sigma = 0: q' = 0 and the value is qb / 2^10.)
+LSTM_HD bool ln_row_is_narrow(const LnRow2 &row) { return row.a <= 256.0; }
+LSTM_HD int32_t ln_second_stage_narrow(int32_t q, const LnRow2 &row, double qLs, double qbs) {
+  const double qn = floor(fma((double)q, row.a, row.b));
+  return f64_low_word(fma(qn, qLs, qbs) + 6755399441055744.0);
+}
 LSTM_HD int32_t ln_apply2(int32_t q, const LnRow2 &row, double qLs, double qbs, const RescaleHi &p) {
   return rescale_sat16_pre(ln_second_stage(q, row, qLs, qbs), p);
 }

@@ -406,9 +406,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     auto normalize = [&](int gmask, int32_t (&xv)[4][4]) {
       if (ln) {
         LnRow2 lr[4];
+        bool wide = false;
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          if (gmask >> g & 1) lr[g] = lnrow[g * 16 + r];
+          if (gmask >> g & 1) {
+            lr[g] = lnrow[g * 16 + r];
+            wide |= !ln_row_is_narrow(lr[g]);
+          }
+        // uniform: every row of this wave has sigma >= 2^12, and the second stage needs no int32 clamp
+        const bool narrow = __builtin_amdgcn_ballot_w64(wide) == 0;
+        auto second_stage = [&](auto narrow_tag) {
 #pragma unroll
         for (int gp = 0; gp < 4; gp += 2) {
           if (!(gmask >> gp & 3)) continue;
@@ -430,11 +437,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             if (gmask >> g & 1)
 #pragma unroll
               for (int c = 0; c < 4; ++c) {
-                int32_t v = ln_second_stage(gs[g][c], lr[g], wL[g - gp][c], wb[g - gp][c]);
+                int32_t v = decltype(narrow_tag)::value ? ln_second_stage_narrow(gs[g][c], lr[g], wL[g - gp][c], wb[g - gp][c])
+                                                        : ln_second_stage(gs[g][c], lr[g], wL[g - gp][c], wb[g - gp][c]);
                 if (pre_ln) v = rescale_preshift(v, pl[g - gp]);
                 xv[g][c] = rescale_sat16_pre<0>(v, pl[g - gp]);
               }
         }
+        };
+        if (narrow)
+          second_stage(std::true_type{});
+        else
+          second_stage(std::false_type{});
       } else {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
@@ -448,7 +461,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     auto lookup = [&](int gmask, const int32_t (&x)[4][4], const int (&tb)[4], int32_t (&out)[4][4]) {
       int32_t mag[4][4];
       uint32_t base[4][4], delta[4][4];
-      bool over = false;
+      int32_t top[3] = {0, 0, 0};  // largest |x| looked up in each table
       LutLds lp[3];
 #pragma unroll
       for (int i = 0; i < 3; ++i) {
@@ -464,7 +477,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             mag[g][c] = abs_i32(x[g][c]);
-            over |= mag[g][c] >= dom;
+            top[tb[g]] = top[tb[g]] > mag[g][c] ? top[tb[g]] : mag[g][c];
             const int32_t ai = mag[g][c] < dom ? mag[g][c] : dom - 1;
             base[g][c] = *reinterpret_cast<const uint16_t *>(lds + lp[tb[g]].offB + 2 * (ai >> sh));
             delta[g][c] = lds[lp[tb[g]].offD + ai];
@@ -476,6 +489,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         if (gmask >> g & 1)
 #pragma unroll
           for (int c = 0; c < 4; ++c) out[g][c] = (int32_t)(base[g][c] + delta[g][c]);
+      bool over = false;
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+        bool used = false;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) used = used || ((gmask >> g & 1) && tb[g] == i);
+        if (used) over |= top[i] >= lp[i].dom;
+      }
       if (__builtin_amdgcn_ballot_w64(over) != 0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)

@@ -597,7 +597,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // half of this phase).
     // gates of `gmask` (bit g) of tile (rt, tl): gate sums -> layer norm -> xv[g][c]
     constexpr int LNB = KS >= 32 ? 1 : 2;  // the deepest register-resident R leaves room for less
-    auto normalize = [&](int rt, int tl, int gmask, const LnRow2 (&lr)[4], int32_t (&xv)[4][4]) {
+    auto normalize = [&](int rt, int tl, int gmask, const LnRow2 (&lr)[4], int32_t (&xv)[4][4], bool narrow) {
       if (ln) {
 #pragma unroll
         for (int gp = 0; gp < 4; gp += LNB) {  // LNB gates per batch of reads: 8 LNB doubles in flight
@@ -620,7 +620,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             if (gmask >> g & 1)
 #pragma unroll
               for (int c = 0; c < 4; ++c)
-                xv[g][c] = ln_second_stage(acc[rt][tl][g * 4 + c], lr[g], wL[g - gp][c], wb[g - gp][c]);
+                xv[g][c] = narrow ? ln_second_stage_narrow(acc[rt][tl][g * 4 + c], lr[g], wL[g - gp][c], wb[g - gp][c])
+                                  : ln_second_stage(acc[rt][tl][g * 4 + c], lr[g], wL[g - gp][c], wb[g - gp][c]);
           if (pre_ln) {  // some second-stage shift is below 33 (uniform; rare)
 #pragma unroll
             for (int g = gp; g < gp + LNB; ++g)
@@ -646,7 +647,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     auto lookup = [&](int gmask, const int32_t (&xv)[4][4], const int (&tb)[4], int32_t (&tv)[4][4]) {
       int32_t mag[4][4];
       uint32_t base[4][4], delta[4][4];
-      bool over = false;
+      int32_t top[3] = {0, 0, 0};  // largest |x| looked up in each table
       // the tables' places and sizes come from LDS (the same words for every lane)
       LutLds lp[3];
 #pragma unroll
@@ -663,7 +664,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             mag[g][c] = abs_i32(xv[g][c]);  // at most 2^15
-            over |= mag[g][c] >= dom;
+            top[tb[g]] = top[tb[g]] > mag[g][c] ? top[tb[g]] : mag[g][c];
             const int32_t ai = mag[g][c] < dom ? mag[g][c] : dom - 1;
             base[g][c] = *reinterpret_cast<const uint16_t *>(lds + lp[tb[g]].offB + 2 * (ai >> sh));
             delta[g][c] = lds[lp[tb[g]].offD + ai];
@@ -681,6 +682,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       // thousand, i.e. some lane of most batches -- and the step then waits for the slowest of the group's
       // 128 waves; with 24576 entries it is one in a million.  The tests narrow down from the batch to the
       // gate to the cell.
+      bool over = false;
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+        bool used = false;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) used = used || ((gmask >> g & 1) && tb[g] == i);
+        if (used) over |= top[i] >= lp[i].dom;
+      }
       if (__builtin_amdgcn_ballot_w64(over) != 0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
@@ -701,14 +710,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       LnRow2 lr[4];
+      bool narrow = false;  // uniform: every row of this wave has sigma >= 2^12, the second stage stays within int32
       if (ln) {
+        bool wide = false;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) lr[g] = lnrow[(rt * 4 + g) * 32 + col];
+        for (int g = 0; g < 4; ++g) {
+          lr[g] = lnrow[(rt * 4 + g) * 32 + col];
+          if (gates_now >> g & 1) wide |= !ln_row_is_narrow(lr[g]);
+        }
+        narrow = __builtin_amdgcn_ballot_w64(wide) == 0;
       }
 #pragma unroll
       for (int tl = 0; tl < 2; ++tl) {
         int32_t xv[4][4], tv[4][4];
-        normalize(rt, tl, gates_now, lr, xv);
+        if (narrow)
+          normalize(rt, tl, gates_now, lr, xv, true);
+        else
+          normalize(rt, tl, gates_now, lr, xv, false);
         if (KS >= 32) {  // the deepest register-resident R leaves room for two gates' reads at a time
           lookup(gates_now & 3, xv, gate_tb, tv);
           lookup(gates_now & 12, xv, gate_tb, tv);
@@ -776,7 +794,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
           for (int c = 0; c < 4; ++c) xv[tl][c] = creg[rt][tl][c];
           if (ph) {
-            normalize(rt, tl, 8, lr, ov[tl]);
+            normalize(rt, tl, 8, lr, ov[tl], false);
 #pragma unroll
             for (int c = 0; c < 4; ++c) xv[2 + tl][c] = ov[tl][3][c];
           }

@@ -588,7 +588,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
     // ---- layer norm, sigma/tanh, cell update (Secs. 3.2.6, 3.2.1, 3.2.9, 3.2.7)
     constexpr int LNB = KS >= 32 ? 1 : 2;
-    auto normalize = [&](int tl, int gmask, const LnRow2 (&lr)[4], int32_t (&xv)[4][4]) {
+    auto normalize = [&](int tl, int gmask, const LnRow2 (&lr)[4], int32_t (&xv)[4][4], bool narrow) {
       if (ln) {
 #pragma unroll
         for (int gp = 0; gp < 4; gp += LNB) {
@@ -611,7 +611,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             if (gmask >> g & 1)
 #pragma unroll
               for (int c = 0; c < 4; ++c)
-                xv[g][c] = ln_second_stage(acc[tl][g * 4 + c], lr[g], wL[g - gp][c], wb[g - gp][c]);
+                xv[g][c] = narrow ? ln_second_stage_narrow(acc[tl][g * 4 + c], lr[g], wL[g - gp][c], wb[g - gp][c])
+                                  : ln_second_stage(acc[tl][g * 4 + c], lr[g], wL[g - gp][c], wb[g - gp][c]);
           if (pre_ln) {
 #pragma unroll
             for (int g = gp; g < gp + LNB; ++g)
@@ -638,7 +639,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     auto lookup = [&](int gmask, const int32_t (&xv)[4][4], const int (&tb)[4], int32_t (&tv)[4][4]) {
       int32_t mag[4][4];
       uint32_t base[4][4], delta[4][4];
-      bool over = false;
+      int32_t top[3] = {0, 0, 0};  // largest |x| looked up in each table
       LutLds lp[3];
 #pragma unroll
       for (int i = 0; i < 3; ++i) {
@@ -654,7 +655,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             mag[g][c] = abs_i32(xv[g][c]);
-            over |= mag[g][c] >= dom;
+            top[tb[g]] = top[tb[g]] > mag[g][c] ? top[tb[g]] : mag[g][c];
             const int32_t ai = mag[g][c] < dom ? mag[g][c] : dom - 1;
             base[g][c] = *reinterpret_cast<const uint16_t *>(lds + lp[tb[g]].offB + 2 * (ai >> sh));
             delta[g][c] = lds[lp[tb[g]].offD + ai];
@@ -666,6 +667,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         if (gmask >> g & 1)
 #pragma unroll
           for (int c = 0; c < 4; ++c) tv[g][c] = (int32_t)(base[g][c] + delta[g][c]);
+      bool over = false;
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+        bool used = false;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) used = used || ((gmask >> g & 1) && tb[g] == i);
+        if (used) over |= top[i] >= lp[i].dom;
+      }
       if (__builtin_amdgcn_ballot_w64(over) != 0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
@@ -685,14 +694,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     int32_t xi[2][4], xf_[2][4], xz[2][4], xo[2][4];
     {
       LnRow2 lr[4];
+      bool narrow = false;  // uniform: every row of this wave has sigma >= 2^12 (see rec_kernel)
       if (ln) {
+        bool wide = false;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) lr[g] = lnrow[g * 32 + col];
+        for (int g = 0; g < 4; ++g) {
+          lr[g] = lnrow[g * 32 + col];
+          if (gates_now >> g & 1) wide |= !ln_row_is_narrow(lr[g]);
+        }
+        narrow = __builtin_amdgcn_ballot_w64(wide) == 0;
       }
 #pragma unroll
       for (int tl = 0; tl < 2; ++tl) {
         int32_t xv[4][4], tv[4][4];
-        normalize(tl, gates_now, lr, xv);
+        if (narrow)
+          normalize(tl, gates_now, lr, xv, true);
+        else
+          normalize(tl, gates_now, lr, xv, false);
         if (KS >= 32) {
           lookup(gates_now & 3, xv, gate_tb, tv);
           lookup(gates_now & 12, xv, gate_tb, tv);
@@ -763,7 +781,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
         for (int c = 0; c < 4; ++c) xv[tl][c] = creg[tl][c];
         if (ph) {
-          normalize(tl, 8, lr, ov[tl]);
+          normalize(tl, 8, lr, ov[tl], false);
 #pragma unroll
           for (int c = 0; c < 4; ++c) xv[2 + tl][c] = ov[tl][3][c];
         }

@@ -129,13 +129,15 @@ def _ln_case(rng, n, kind):
         q = np.full(n, rng.integers(-32767, 32767))
         q[rng.integers(0, n)] += rng.choice([-1, 1, 2, 500])
         q = np.clip(q, -32767, 32767)
+    elif kind == "threshold":  # sigma around 2^12, where the kernel switches between its two second-stage forms
+        q = np.clip(np.rint(rng.normal(rng.choice([-32000, -5, 31000]), rng.choice([3.6, 4.0, 4.4]), size=n)), -32767, 32767)
     elif kind == "near_constant":
         q = np.full(n, rng.integers(-32000, 32000)) + rng.integers(0, 2, size=n)
     else:
         q = np.full(n, rng.integers(-32767, 32767))
     qL = rng.integers(-32767, 32768, size=n)
     qb = rng.integers(-2**31 + 1, 2**31, size=n)
-    if kind == "extreme":
+    if kind in ("extreme", "threshold"):
         qL[:] = rng.choice([-32767, 32767], size=n)
         qb[:] = rng.choice([-2**31 + 1, 2**31 - 1], size=n)
     return q.astype(np.int16), qL.astype(np.int16), qb.astype(np.int32)
@@ -143,10 +145,13 @@ def _ln_case(rng, n, kind):
 
 def test_layernorm_matches_oracle(orc, hm):
     rng = np.random.default_rng(5)
-    for trial in range(400):
+    hm.hm_ln_row_is_narrow.argtypes = [C.c_void_p, C.c_int32]
+    forms = {0: 0, 1: 0}  # rows that took the second stage with / without the int32 clamp
+    for trial in range(480):
         n = int(rng.choice([1, 2, 3, 17, 64, 512, 1000, 2048, 4096]))
-        kind = ["normal", "extreme", "spike", "near_constant", "constant"][trial % 5]
+        kind = ["normal", "extreme", "spike", "near_constant", "constant", "threshold"][trial % 6]
         q, qL, qb = _ln_case(rng, n, kind)
+        forms[hm.hm_ln_row_is_narrow(q.ctypes.data, n)] += 1
         M, e = int(rng.integers(2**30, 2**31)), int(rng.integers(-24, 4))
         want = orc.int_layernorm(q, qL, qb, M, e)
         got = np.zeros(n, np.int16)
@@ -156,6 +161,7 @@ def test_layernorm_matches_oracle(orc, hm):
             got2 = np.zeros(n, np.int16)
             hm.hm_layernorm2(q.ctypes.data, n, qL.ctypes.data, qb.ctypes.data, M, 31 - e, got2.ctypes.data)
             assert (got2 == want).all(), (trial, n, kind)
+    assert forms[0] > 100 and forms[1] > 100, forms
 
 
 def test_rescale_sat16_from_high_word(orc, hm):
