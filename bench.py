@@ -66,6 +66,9 @@ def main():
     ap.add_argument("--sparse", action="store_true",
                     help="prune the synthetic weights W, R, W_proj to two nonzeros per aligned group of four inputs "
                          "(the structured stand-in for the 50 %% sparse models of Table 1): R h runs on the sparse MFMA")
+    ap.add_argument("--phase-timing", action="store_true",
+                    help="diagnostics instead of the benchmark: the recurrent kernel's phase timers (workgroup 0), "
+                         "microseconds per step and phase, as one JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 one launch per operation and step")
     ap.add_argument("--mfma-store-ceiling", action="store_true",
@@ -120,6 +123,26 @@ def main():
 
     def step():
         model.forward(xd, y=y, workspace=ws)
+
+    if args.phase_timing:
+        # phases of the kernel with groups of 32 rows: 0 h tile -> LDS (and W x terms), 1 R h (MFMA), 2 gate sums,
+        # 3 publish statistics, 4 wait for them and (mean, sigma), 5 layer norm, sigma/tanh, cell, 6 hidden state,
+        # 7 barrier, 8 projection, 9 barrier; 10 = everything before the first step, per launch
+        model.set_option("stack", 0)
+        step()
+        torch.cuda.synchronize()
+        model.set_option("phase_timing", 1)
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        ticks = model.phase_ticks()  # 100 MHz ticks summed over steps, layers and calls
+        n = args.steps * T * L
+        print(json.dumps({"phase_us_per_step": [round(t / 100.0 / n, 3) for t in ticks[:10]],
+                          "step_us": round(sum(ticks[:10]) / 100.0 / n, 3),
+                          "prologue_us_per_launch": round(ticks[10] / 100.0 / (args.steps * L), 2),
+                          "device_status": model.device_status(), "sparse_layers": model.sparse_layers(),
+                          "note": "timers of workgroup 0 only; they cost about 0.3 us per step themselves"}))
+        return
 
     for _ in range(args.warmup):
         step()
