@@ -11,12 +11,14 @@
 //                    64 cells and keeps its slice of R in registers as MFMA
 //                    operands for the whole sequence, and its slice of W_proj
 //                    in LDS.  Per step: R h on the MFMA, gate sums, layer-norm
-//                    statistics (wavefront reductions, then one 64-bit atomic
-//                    add per row and gate into words that also count their
-//                    contributions, so readers need no barrier), sigma/tanh,
+//                    statistics (summed per workgroup in LDS, then two 64-bit
+//                    atomic adds per row and gate into words that also count
+//                    their contributions, so readers need no barrier), sigma/tanh,
 //                    cell update, hidden state, projection; groups synchronize
 //                    through a counter in global memory.  Batch rows never
 //                    interact, so groups run independently.
+//                    A layer whose recurrent weights are 2:4 sparse has a form
+//                    that runs R h on the sparse MFMA (rec_sparse_inst_*.hip).
 //   rec16_kernel     the same step on groups of 16 rows (16x16x64 MFMA) for
 //                    small batches: rec16_kernel.inc.h, rec16_inst.hip.
 //
