@@ -292,8 +292,11 @@ int lstm_int_forward_static(const lstm_int_model *model, const int8_t *x, int32_
  *           recurrent weights are 2:4 along the contraction (at most two nonzeros
  *           in every aligned group of four h inputs; see lstm_int_sparse_layers)
  *           on the sparse MFMA where the persistent kernel for groups of 32 rows
- *           runs; 0 = always the dense product.  The results are the same
- *           integers either way.
+ *           runs; 0 = always the dense product; 2 = as 1, but a forward call in
+ *           which such a layer would run the dense product (batch too small or too
+ *           large for that kernel, stacked launch, a trace request) fails with
+ *           LSTM_INT_E_UNSUPPORTED instead.  The results are the same integers
+ *           either way.
  *   "reset_status": clears the device status word (see lstm_int_device_status)
  *           after a wait gave up; synchronizes the device.
  *   "phase_timing": nonzero makes workgroup 0 of the persistent kernel add the

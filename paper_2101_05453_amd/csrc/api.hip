@@ -985,6 +985,8 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
         ra.sparse = 1;
       }
     }
+    // option "sparse" = 2: a layer with 2:4 recurrent weights must run in the sparse form, or the call fails
+    if (m->sparse == 2 && d.R2s && !(use_p2 && ra.sparse)) return LSTM_INT_E_UNSUPPORTED;
     if (use_p2) {
       auto lds_need = [&]() { return use16 ? rec16_lds_bytes(ra) : rec_lds_bytes(ra); };
       // What LDS is left goes to longer prefixes of the two gate tables, 1 KB at a time in turn: a value
@@ -1211,7 +1213,7 @@ int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
     return LSTM_INT_OK;
   }
   if (!strcmp(key, "sparse")) {
-    if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
+    if (value < 0 || value > 2) return LSTM_INT_E_INVALID_ARG;
     m->sparse = (int)value;
     return LSTM_INT_OK;
   }

@@ -15,8 +15,9 @@ VARIANTS = [0, wl.LAYER_NORM, wl.PEEPHOLE, wl.PROJECTION, wl.CIFG,
             wl.CIFG | wl.PEEPHOLE | wl.PROJECTION,
             wl.CIFG | wl.LAYER_NORM | wl.PEEPHOLE | wl.PROJECTION]
 
-# the kernel with groups of 32 rows, one launch per layer (the sparse form belongs to it)
-OPTS = {"rows16": 0, "stack": 0}
+# the kernel with groups of 32 rows, one launch per layer (the sparse form belongs to it); sparse = 2: a call in
+# which a 2:4 layer would fall back to the dense product fails instead of passing unnoticed
+OPTS = {"rows16": 0, "stack": 0, "sparse": 2}
 
 
 def _dense_again(lib_model, x_shape, y_sparse, seed):
@@ -29,7 +30,7 @@ def _dense_again(lib_model, x_shape, y_sparse, seed):
     ys = lib_model.forward(xq).cpu().numpy()
     lib_model.set_option("sparse", 0)
     yd = lib_model.forward(xq).cpu().numpy()
-    lib_model.set_option("sparse", 1)
+    lib_model.set_option("sparse", 2)
     assert lib_model.device_status() == 0
     assert_equal("sparse against dense kernel", ys, yd)
 
@@ -80,6 +81,26 @@ def test_sparse_only_where_the_weights_allow(orc):
     R[17, 40:44] = [0.05, -0.05, 0.05, 0.0]
     lib_model, _ = run_and_compare(orc, layers, x, "sparse_not_quite", trace=False, options=OPTS)
     assert lib_model.sparse_layers() == 0
+
+
+def test_sparse_required_but_not_possible(orc):
+    """Option sparse = 2 where the sparse form does not run (the 16-row kernel takes this batch): the call fails
+    with a clean error, and works again with the option at 1."""
+    import torch
+    from paper_2101_05453_amd import binding
+
+    layers, x = wl.make_custom([72], 200, 200, wl.LAYER_NORM, 8, 3, seed=9, weight_param=0.08)
+    wl.prune_2of4(layers)
+    lib_model, _ = run_and_compare(orc, layers, x, "sparse_small_batch", trace=False, options={"stack": 0})
+    assert lib_model.sparse_layers() == 1
+    xq = torch.zeros((3, 8, 72), dtype=torch.int8, device="cuda")
+    lib_model.set_option("sparse", 2)
+    with pytest.raises(RuntimeError):
+        lib_model.forward(xq)
+    lib_model.set_option("sparse", 1)
+    lib_model.forward(xq)
+    torch.cuda.synchronize()
+    assert lib_model.device_status() == 0
 
 
 def test_sparse_with_state_over_calls(orc):
