@@ -161,7 +161,9 @@ struct Workspace {
   size_t tx, out[2], xpad, th, mbuf, c, h0, sync, m2, total;
   size_t tx_bytes, out_bytes, m2_bytes;  // extents of the regions the persistent kernels index
 };
-constexpr size_t kSyncBytes = 256 * 64 * 4 + 256 * 4 * 256 * 8;  // counters + statistics accumulators
+constexpr size_t kStatGroupBytes = (size_t)kStatGroupWords * 8;  // statistics words of one group of workgroups
+constexpr size_t kSyncBytes = 256 * 64 * 4 + 256 * kStatGroupBytes;  // counters + statistics accumulators
+constexpr size_t kStackFlagsOff = 256 * 64 * 4 + 8 * kStatGroupBytes;  // stacked launch: flags behind the counters and the statistics words of its 8 layers
 
 Workspace plan_workspace(const lstm_int_model *m, int64_t T, int64_t B) {
   int maxGN = 0, maxHpad = 0, maxNpad = 0, maxN = 0, maxNpadp = 0;
@@ -237,7 +239,7 @@ bool stack_chosen(const lstm_int_model *m, int64_t T, int64_t B) {
   const LayerHost &h = m->host[0];
   const int L = (int)m->host.size();
   if (!stack_supported(h.N, h.H, (int)h.flags, m->dev[0].Ipad, L, (int)T, (int)B, &ks) || ks != m->stack_ks) return false;
-  if (131072 + (size_t)L * ((B + 31) / 32) * 128 > kSyncBytes) return false;  // flags behind the statistics words
+  if (kStackFlagsOff + (size_t)L * ((B + 31) / 32) * 128 > kSyncBytes) return false;  // flags behind the statistics words
   if (m->stack == 2) return true;
   // Expected time of the two ways, in microseconds, from the times measured on the 8-layer benchmark stack
   // (N = 2048, H = 640).  One after the other: about 30 us per layer for the input GEMM launch and the weight
@@ -281,7 +283,7 @@ bool rec_extents_ok(const RecArgs &ra, const Workspace &ws, int T_all, int t0, b
   // m exchange buffer [T][Bp][npadp] in tiles
   if (has_proj && (size_t)ra.T * Bp * ra.npadp > ws.m2_bytes) return false;
   // counters [groups][64] words and statistics accumulators [groups][4][256] 64-bit words
-  if ((size_t)ra.groups * 64 * 4 > (size_t)256 * 64 * 4 || (size_t)ra.groups * 4 * 256 * 8 > (size_t)256 * 4 * 256 * 8)
+  if ((size_t)ra.groups * 64 * 4 > (size_t)256 * 64 * 4 || (size_t)ra.groups * kStatGroupBytes > (size_t)256 * kStatGroupBytes)
     return false;
   return true;
 }
@@ -775,7 +777,7 @@ int forward_stack(lstm_int_model *m, const int8_t *x, int32_t T, int32_t B, int8
   sa.c_base = c_state ? c_state : reinterpret_cast<int16_t *>(wsb + sp.c);
   sa.c_given = c_state != nullptr;
   sa.h_final = h_state;
-  const size_t flags_off = 131072;  // behind the counters and the statistics words of 8 groups
+  const size_t flags_off = kStackFlagsOff;
   sa.flags = reinterpret_cast<unsigned *>(wsb + sp.sync + flags_off);
   sa.flag_sleep = m->flag_sleep;
   sa.tick_layer = std::min(L - 1, std::max(0, m->phase_timing - 1));
@@ -1016,7 +1018,7 @@ int lstm_int_forward(const lstm_int_model *cm, const int8_t *x, int32_t T, int32
     if (use_p2) {
       // bytes of the synchronization region a launch over `groups` groups uses: all counters, and the
       // statistics words of its groups (they follow the counters)
-      auto sync_bytes = [](int groups) { return (int64_t)256 * 64 * 4 + (int64_t)groups * 4 * 256 * 8; };
+      auto sync_bytes = [](int groups) { return (int64_t)256 * 64 * 4 + (int64_t)groups * (int64_t)kStatGroupBytes; };
       const int launch_rows = p2_groups * ra.rows_pg;
       {
         InGemmArgs ga;

@@ -91,6 +91,16 @@ struct LutWide {
   int32_t pad_;
 };
 
+// Layer-norm statistics words of one group of workgroups: [set][round][sum q | sum q^2][item], 64 bits each.  In
+// rec_kernel and stack_kernel the group's workgroups add into two sets of words, even members into set 0 and odd
+// members into set 1, and every reader adds the two up: half as many atomic adds meet in each cache line (measured at
+// 32 workgroups per group: 0.19 us per step; four sets were no better than two, with twice the words to poll).
+// Groups of fewer than 16 workgroups keep to one set there (the second set's polls cost more than they save), and
+// so does rec16_kernel at any group size.
+constexpr int kStatSetWords = 2 * 2 * 256;
+constexpr int kStatGroupWords = 2 * kStatSetWords;
+__host__ __device__ inline bool stat_two_sets(int GS) { return GS >= 16; }
+
 struct RecArgs {
   int T, B, N, H, Hpad, flags, m_c;
   int GS;         // workgroups (compute units) per group = cells / 64
@@ -134,7 +144,7 @@ struct RecArgs {
   unsigned *counters;          // [groups][64]
   unsigned long long *tickets; // plain launch: [8 XCDs][32], word 0 of each (zeroed with the counters) sums up
                                // the workgroups that ran there (rec_kernel.inc.h); NULL = cooperative launch
-  unsigned long long *acc;     // [groups][2 rounds][2 (S1,S2)][rows_pg*4]
+  unsigned long long *acc;     // [groups][kStatGroupWords]
   int *status;                 // [0] != 0: a wait gave up or the placement check failed
   int spin_limit;
   int poll_sleep, stats_sleep;  // pauses between two polls of a barrier / of the statistics words, x 64 clocks

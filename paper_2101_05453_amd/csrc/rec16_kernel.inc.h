@@ -232,7 +232,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   unsigned epoch = 0;
   unsigned *counter = a.counters + group * 64;
-  u64 *accS = a.acc + (size_t)group * 4 * 256;  // [round][S1|S2][item], item < 64
+  // one set of words: two sets (as in rec_kernel) made this kernel 2-3 % slower, at 8 and at 32 workgroups per group
+  u64 *accS = a.acc + (size_t)group * kStatGroupWords;  // [round][S1|S2][item], item < 64
   int64_t prevS[2][2] = {{0, 0}, {0, 0}};       // this thread's item, per round: S1, S2
   const double inv_n = 1.0 / (double)a.N;
   const bool pre_ln = a.rln[0] < 33 || a.rln[1] < 33 || a.rln[2] < 33 || a.rln[3] < 33;

@@ -334,8 +334,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   unsigned epoch = 0;
   unsigned *counter = a.counters + group * 64;
-  u64 *accS = a.acc + (size_t)group * 4 * 256;  // [round][S1|S2][item], item < 256
-  int64_t prevS[2][2] = {{0, 0}, {0, 0}};       // this thread's item, per round: S1, S2
+  u64 *accS = a.acc + (size_t)group * kStatGroupWords;  // [set][round][S1|S2][item]
+  int64_t prevS[2][2][2] = {{{0, 0}, {0, 0}}, {{0, 0}, {0, 0}}};  // this thread's item, per round and set: S1, S2
   const double inv_n = 1.0 / (double)a.N;
   const int g_first = cifg ? 1 : 0;
   // uniform: some shift of the layer norm's second stage / of the hidden state's rescale is below 33
@@ -541,9 +541,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           red[tid] = 0;  // the next adds to this word come after the next barrier
           const int64_t v1 = ((pk + (1 << 23)) & 0xFFFFFF) - (1 << 23);  // signed low 24 bits
           const int64_t v2 = (pk - v1) >> 24;
-          __hip_atomic_fetch_add(&accS[(round * 2 + 0) * 256 + tid], ((u64)1 << 56) + (u64)(v1 + (1 << 22)),
+          u64 *mine = accS + (stat_two_sets(GS) ? (member & 1) : 0) * kStatSetWords;  // this workgroup's set of words
+          __hip_atomic_fetch_add(&mine[(round * 2 + 0) * 256 + tid], ((u64)1 << 56) + (u64)(v1 + (1 << 22)),
                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_fetch_add(&accS[(round * 2 + 1) * 256 + tid], ((u64)1 << 56) + (u64)v2, __ATOMIC_RELAXED,
+          __hip_atomic_fetch_add(&mine[(round * 2 + 1) * 256 + tid], ((u64)1 << 56) + (u64)v2, __ATOMIC_RELAXED,
                                  __HIP_MEMORY_SCOPE_AGENT);
         }
       }
@@ -553,15 +554,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       if (tid < items) {
         const int g = (tid >> 5) & 3;
         if (g >= g_lo && g <= g_hi) {
-          const u64 expect = (u64)(((unsigned)GS * (unsigned)(t + 1)) & 0xFFu);
-          u64 c1, c2;
+          // two sets: set 0 holds the adds of the even members, set 1 those of the odd ones
+          const bool two = stat_two_sets(GS);
+          const unsigned n0 = two ? ((unsigned)GS + 1) >> 1 : (unsigned)GS, n1 = two ? (unsigned)GS >> 1 : 0u;
+          const u64 expect0 = (u64)((n0 * (unsigned)(t + 1)) & 0xFFu), expect1 = (u64)((n1 * (unsigned)(t + 1)) & 0xFFu);
+          u64 c1[2], c2[2];
           int budget = a.spin_limit;
           // the adds of the other workgroups need this long to land; a poll before that only delays them
           for (int i = 0; i < a.stats_first_sleep; ++i) __builtin_amdgcn_s_sleep(1);
           for (;;) {
-            c1 = __hip_atomic_load(&accS[(round * 2 + 0) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            c2 = __hip_atomic_load(&accS[(round * 2 + 1) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((c1 >> 56) == expect && (c2 >> 56) == expect) break;
+            c1[0] = __hip_atomic_load(&accS[(round * 2 + 0) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c2[0] = __hip_atomic_load(&accS[(round * 2 + 1) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c1[1] = c2[1] = 0;  // one set: the second set's words are never added to, nor read
+            if (two) {
+              c1[1] = __hip_atomic_load(&accS[kStatSetWords + (round * 2 + 0) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              c2[1] = __hip_atomic_load(&accS[kStatSetWords + (round * 2 + 1) * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if ((c1[0] >> 56) == expect0 && (c2[0] >> 56) == expect0 && (c1[1] >> 56) == expect1 && (c2[1] >> 56) == expect1) break;
             if (--budget <= 0 || __hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
               __hip_atomic_store(a.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
               *flag = 0;
@@ -569,12 +578,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             }
             for (int i = 0; i < a.stats_sleep; ++i) __builtin_amdgcn_s_sleep(1);
           }
-          c1 &= kValMask;
-          c2 &= kValMask;
-          const int64_t S1 = (int64_t)((c1 - (u64)prevS[round][0]) & kValMask) - (int64_t)GS * (1 << 22);
-          const int64_t S2 = (int64_t)((c2 - (u64)prevS[round][1]) & kValMask);
-          prevS[round][0] = (int64_t)c1;
-          prevS[round][1] = (int64_t)c2;
+          int64_t S1 = -(int64_t)GS * (1 << 22), S2 = 0;
+#pragma unroll
+          for (int ss = 0; ss < 2; ++ss) {
+            c1[ss] &= kValMask;
+            c2[ss] &= kValMask;
+            S1 += (int64_t)((c1[ss] - (u64)prevS[round][ss][0]) & kValMask);
+            S2 += (int64_t)((c2[ss] - (u64)prevS[round][ss][1]) & kValMask);
+            prevS[round][ss][0] = (int64_t)c1[ss];
+            prevS[round][ss][1] = (int64_t)c2[ss];
+          }
           lnrow[tid] = ln_row2(ln_row(S1, S2, a.N, inv_n));
         }
       }
