@@ -183,6 +183,41 @@ def prune_2of4(layers, tensors=("R",)):
     return layers
 
 
+@dataclass
+class GruLayerSpec:
+    """Float parameters of one GRU layer (gate order r, u, n; reset gate applied to the recurrent
+    product) and the range of its input."""
+
+    input_size: int
+    num_cells: int
+    W: List[np.ndarray] = field(default_factory=list)   # 3 x [N, I]
+    R: List[np.ndarray] = field(default_factory=list)   # 3 x [N, N]
+    bx: List[np.ndarray] = field(default_factory=list)  # 3 x [N]
+    bh: List[np.ndarray] = field(default_factory=list)  # 3 x [N]
+    x_min: float = 0.0
+    x_max: float = 0.0
+
+
+def make_gru(layer_inputs, num_cells, batch, steps, seed=0, weight_dist="normal", weight_param=0.05,
+             input_dist="normal", input_param=1.0):
+    """Float GRU layers and the float input x [T, B, I0].  Layer l draws from PCG64(seed + l) in the
+    order W_r, W_u, W_n, R_r, R_u, R_n, bx_r..bx_n, bh_r..bh_n (biases U(-0.1, 0.1)); x from
+    PCG64(seed + 100003).  The input range of layer 0 is the range of x."""
+    layers = []
+    for l, I in enumerate(layer_inputs):
+        rng = np.random.Generator(np.random.PCG64(seed + l))
+        spec = GruLayerSpec(I, num_cells)
+        spec.W = [_draw(rng, weight_dist, weight_param, (num_cells, I)) for _ in range(3)]
+        spec.R = [_draw(rng, weight_dist, weight_param, (num_cells, num_cells)) for _ in range(3)]
+        spec.bx = [_draw(rng, "uniform", 0.1, (num_cells,)) for _ in range(3)]
+        spec.bh = [_draw(rng, "uniform", 0.1, (num_cells,)) for _ in range(3)]
+        layers.append(spec)
+    rng = np.random.Generator(np.random.PCG64(seed + 100003))
+    x = _draw(rng, input_dist, input_param, (steps, batch, layer_inputs[0]))
+    layers[0].x_min, layers[0].x_max = float(x.min()), float(x.max())
+    return layers, x
+
+
 def describe(name):
     cfg = CONFIGS[name]
     v = [n for bit, n in ((CIFG, "cifg"), (PEEPHOLE, "peephole"), (LAYER_NORM, "layernorm"),
