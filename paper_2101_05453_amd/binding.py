@@ -381,3 +381,152 @@ def mfma_store_ceiling(stores_per_block, blocks=4096, device=0):
 
 def strerror(code):
     return lib().lstm_int_strerror(code).decode()
+
+
+# ---------------------------------------------------------------------------
+# gru_int_* (include/gru_int.h): the integer GRU built from the same blocks
+# ---------------------------------------------------------------------------
+class GruLayerParams(C.Structure):
+    """gru_int_layer_params"""
+    _fields_ = [
+        ("input_size", C.c_int32), ("num_cells", C.c_int32),
+        ("W", _fp * 3), ("R", _fp * 3), ("bx", _fp * 3), ("bh", _fp * 3),
+        ("x_min", C.c_float), ("x_max", C.c_float),
+    ]
+
+
+class GruLayerQuant(C.Structure):
+    """gru_int_layer_quant"""
+    _fields_ = [
+        ("I", C.c_int32), ("N", C.c_int32), ("zp_x", C.c_int32),
+        ("s_x", C.c_double), ("s_W", C.c_double * 3), ("s_R", C.c_double * 3),
+        ("Mx", C.c_int32 * 3), ("ex", C.c_int32 * 3), ("Mh", C.c_int32 * 3), ("eh", C.c_int32 * 3),
+        ("Wq", C.POINTER(C.c_int8)), ("Rq", C.POINTER(C.c_int8)),
+        ("bxq", C.POINTER(C.c_int32)), ("bhq", C.POINTER(C.c_int32)), ("bx_fold", C.POINTER(C.c_int32)),
+    ]
+
+
+class GruTrace(C.Structure):
+    """gru_int_trace"""
+    _fields_ = [("layer", C.c_int32)] + [(n, C.c_void_p) for n in ("tx", "th", "act", "h16", "h8")]
+
+
+GRU_TRACE_FIELDS = ("tx", "th", "act", "h16", "h8")
+_gru_ready = False
+
+
+def gru_lib():
+    global _gru_ready
+    L = lib()
+    if not _gru_ready:
+        L.gru_int_prepare.restype = C.c_int
+        L.gru_int_prepare.argtypes = [C.POINTER(GruLayerParams), C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+        L.gru_int_get_quant.restype = C.c_int
+        L.gru_int_get_quant.argtypes = [C.c_void_p, C.c_int32, C.POINTER(GruLayerQuant)]
+        L.gru_int_workspace_bytes.restype = C.c_size_t
+        L.gru_int_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.gru_int_forward.restype = C.c_int
+        L.gru_int_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(GruTrace)]
+        L.gru_int_destroy.restype = None
+        L.gru_int_destroy.argtypes = [C.c_void_p]
+        _gru_ready = True
+    return L
+
+
+def marshal_gru_layers(layers):
+    arr = (GruLayerParams * len(layers))()
+    keep = []
+
+    def ptr(a):
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        keep.append(a)
+        return a.ctypes.data_as(_fp)
+
+    for p, s in zip(arr, layers):
+        p.input_size, p.num_cells = s.input_size, s.num_cells
+        for g in range(3):
+            p.W[g], p.R[g], p.bx[g], p.bh[g] = ptr(s.W[g]), ptr(s.R[g]), ptr(s.bx[g]), ptr(s.bh[g])
+        p.x_min, p.x_max = s.x_min, s.x_max
+    return arr, keep
+
+
+class GruModel:
+    """Owns one gru_int_model."""
+
+    def __init__(self, handle, num_layers, device):
+        self._h = handle
+        self.num_layers = num_layers
+        self.device = device
+
+    def __del__(self):
+        self.destroy()
+
+    # gru_int_destroy
+    def destroy(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.gru_int_destroy(self._h)
+        self._h = None
+
+    # gru_int_get_quant
+    def get_quant(self, layer):
+        q = GruLayerQuant()
+        _check(gru_lib().gru_int_get_quant(self._h, layer, C.byref(q)), "gru_int_get_quant")
+        N, I = q.N, q.I
+        d = {k: getattr(q, k) for k in ("I", "N", "zp_x", "s_x")}
+        for k in ("s_W", "s_R", "Mx", "ex", "Mh", "eh"):
+            d[k] = list(getattr(q, k))
+        d["Wq"] = _view(q.Wq, (3, N, I), np.int8)
+        d["Rq"] = _view(q.Rq, (3, N, N), np.int8)
+        for k in ("bxq", "bhq", "bx_fold"):
+            d[k] = _view(getattr(q, k), (3, N), np.int32)
+        return d
+
+    # gru_int_workspace_bytes
+    def workspace_bytes(self, T, B):
+        return gru_lib().gru_int_workspace_bytes(self._h, T, B)
+
+    # gru_int_forward on torch device tensors
+    def forward(self, x, y=None, h_state=None, workspace=None, trace_layer=None):
+        """x: int8 CUDA tensor [T,B,I0].  Returns y (int8 [T,B,N_last]); with trace_layer also a dict of
+        that layer's intermediate tensors.  Asynchronous on torch's current stream."""
+        import torch
+
+        assert x.is_cuda and x.dtype == torch.int8 and x.is_contiguous()
+        T, B, _ = x.shape
+        ql = GruLayerQuant()
+        _check(gru_lib().gru_int_get_quant(self._h, self.num_layers - 1, C.byref(ql)), "gru_int_get_quant")
+        if y is None:
+            y = torch.empty((T, B, ql.N), dtype=torch.int8, device=x.device)
+        if workspace is None:
+            workspace = torch.empty(max(self.workspace_bytes(T, B), 256), dtype=torch.uint8, device=x.device)
+        tr, bufs = None, {}
+        if trace_layer is not None:
+            qt = GruLayerQuant()
+            _check(gru_lib().gru_int_get_quant(self._h, trace_layer, C.byref(qt)), "gru_int_get_quant")
+            tr = GruTrace()
+            tr.layer = trace_layer
+            for f in GRU_TRACE_FIELDS:
+                shape = (T, B, qt.N) if f in ("h16", "h8") else (T, B, 3, qt.N)
+                bufs[f] = torch.zeros(shape, dtype=torch.int8 if f == "h8" else torch.int16, device=x.device)
+                setattr(tr, f, bufs[f].data_ptr())
+        if h_state is not None:
+            assert h_state.is_cuda and h_state.dtype == torch.int16 and h_state.is_contiguous()
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+        _check(gru_lib().gru_int_forward(self._h, x.data_ptr(), T, B, y.data_ptr(),
+                                         h_state.data_ptr() if h_state is not None else None,
+                                         workspace.data_ptr(), workspace.numel(), stream,
+                                         C.byref(tr) if tr is not None else None), "gru_int_forward")
+        return (y, bufs) if trace_layer is not None else y
+
+
+# gru_int_prepare
+def gru_prepare(layers, device=0):
+    """layers: GruLayerSpec-like objects (x_min / x_max of layer 0 filled in).  device = -1 builds a
+    host-only model."""
+    arr, keep = marshal_gru_layers(layers)
+    h = C.c_void_p()
+    rc = gru_lib().gru_int_prepare(arr, len(layers), device, C.byref(h))
+    del keep
+    _check(rc, "gru_int_prepare")
+    return GruModel(h, len(layers), device)

@@ -1,0 +1,132 @@
+"""GPU parity of the integer GRU (gru_int_forward through the C ABI) against the CPU oracle's
+(oracle/gru_int_oracle.c) on the same seeded inputs: every integer tensor of every layer and step,
+bit for bit.  The recipe itself is this build's (Sec. 7 of the paper names the GRU and gives none)."""
+import numpy as np
+import pytest
+
+import lstm_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gru(orc):
+    from oracle import gru as g
+
+    g.lib()
+    return g
+
+
+def both(gru, layers):
+    from paper_2101_05453_amd import binding
+
+    return binding.gru_prepare(layers, device=0), gru.GruModel(layers)
+
+
+def quantize_x(x, q):
+    return np.clip(np.floor(x.astype(np.float64) / q["s_x"] + 0.5) + q["zp_x"], -128, 127).astype(np.int8)
+
+
+def equal(name, got, want):
+    got, want = np.asarray(got), np.asarray(want)
+    assert got.shape == want.shape and got.dtype == want.dtype, (name, got.shape, want.shape, got.dtype, want.dtype)
+    if not (got == want).all():
+        bad = np.argwhere(got != want)
+        first = tuple(bad[0])
+        raise AssertionError(f"{name}: {len(bad)} of {got.size} differ; first at {first}: gpu={got[first]} oracle={want[first]}")
+
+
+def compare_all(gru, layers, x, name, rows=None):
+    """Every traced tensor of every layer, the output and the carried state."""
+    import torch
+
+    lib_m, orc_m = both(gru, layers)
+    xq = quantize_x(x, orc_m.get_quant(0))
+    T, B, _ = xq.shape
+    xd = torch.from_numpy(xq).cuda()
+    sel = np.arange(B) if rows is None else np.asarray(rows)
+    Ntot = sum(s.num_cells for s in layers)
+    for l in range(len(layers)):
+        hs = torch.zeros(B * Ntot, dtype=torch.int16, device="cuda")
+        y, tr = lib_m.forward(xd, h_state=hs, trace_layer=l)
+        torch.cuda.synchronize()
+        hs_o = np.zeros(len(sel) * Ntot, dtype=np.int16)
+        yo, tro = orc_m.forward(xq[:, sel], h_state=hs_o, trace_layer=l, threads=8)
+        for f in ("tx", "th", "act", "h16", "h8"):
+            equal(f"{name}.layer{l}.{f}", tr[f].cpu().numpy()[:, sel], tro[f])
+        equal(f"{name}.y", y.cpu().numpy()[:, sel], yo)
+        off_g = off_o = 0
+        for s in layers:
+            n = s.num_cells
+            equal(f"{name}.h_state", hs.cpu().numpy()[off_g:off_g + B * n].reshape(B, n)[sel],
+                  hs_o[off_o:off_o + len(sel) * n].reshape(len(sel), n))
+            off_g += B * n
+            off_o += len(sel) * n
+    y2 = lib_m.forward(xd)  # no state buffer, no trace: the same output from zeros
+    equal(f"{name}.y_nostate", y2.cpu().numpy()[:, sel], yo)
+
+
+@pytest.mark.parametrize("case", [
+    ([24], 40, 3, 6, 0.2),          # ragged: I, N no multiples of the tiles
+    ([64], 64, 16, 5, 0.2),         # exact tiles, x read in place
+    ([17, 37, 37], 37, 5, 7, 0.3),  # N not a multiple of 4, three layers
+    ([32, 128], 128, 33, 9, 0.1),   # three row tiles, the last with one row
+    ([100], 200, 1, 12, 0.15),      # a single row
+])
+def test_every_tensor_small_shapes(gru, case):
+    inputs, N, B, T, wp = case
+    layers, x = wl.make_gru(inputs, N, B, T, seed=21, weight_param=wp, input_param=1.5)
+    compare_all(gru, layers, x, f"gru{inputs}x{N}")
+
+
+def test_saturating_inputs_and_clipped_range(gru):
+    layers, x = wl.make_gru([48], 96, 6, 8, seed=5, weight_param=0.5, input_dist="uniform", input_param=3.0)
+    layers[0].x_min, layers[0].x_max = -1.0, 2.0  # inputs beyond the range saturate; zero point off centre
+    for s in layers:  # large biases drive gate sums into the Q3.12 clamps
+        s.bx[1] = s.bx[1] * 80
+        s.bh[2] = s.bh[2] * 60
+    compare_all(gru, layers, x, "gru_sat")
+
+
+def test_speech_encoder_shapes_sampled_rows(gru):
+    """Layers of the benchmark's width: N = 2048 at B = 256 (two layers, T = 6) on rows spread over the row
+    tiles, N = 1024 at B = 64 whole."""
+    layers, x = wl.make_gru([512, 2048], 2048, 256, 6, seed=3, weight_param=0.03)
+    compare_all(gru, layers, x, "gru2048", rows=[0, 15, 16, 100, 127, 128, 200, 255])
+    layers, x = wl.make_gru([256], 1024, 64, 10, seed=4, weight_param=0.04)
+    compare_all(gru, layers, x, "gru1024")
+
+
+def test_split_sequence_and_long_run(gru):
+    import torch
+
+    layers, x = wl.make_gru([32, 64], 64, 5, 300, seed=8, weight_param=0.12)
+    lib_m, orc_m = both(gru, layers)
+    xq = quantize_x(x, orc_m.get_quant(0))
+    xd = torch.from_numpy(xq).cuda()
+    hs = torch.zeros(2 * 5 * 64, dtype=torch.int16, device="cuda")
+    parts = [lib_m.forward(xd[a:b].contiguous(), h_state=hs).cpu().numpy() for a, b in ((0, 1), (1, 120), (120, 300))]
+    hs_o = np.zeros(2 * 5 * 64, dtype=np.int16)
+    yo, _ = orc_m.forward(xq, h_state=hs_o, threads=5)
+    equal("gru_split.y", np.concatenate(parts), yo)
+    equal("gru_split.h_state", hs.cpu().numpy(), hs_o)
+
+
+def test_empty_inputs_and_workspace_checks(gru):
+    import torch
+    from paper_2101_05453_amd import binding
+
+    layers, x = wl.make_gru([16], 32, 2, 3, seed=1)
+    m = binding.gru_prepare(layers, device=0)
+    xd = torch.zeros((0, 2, 16), dtype=torch.int8, device="cuda")
+    assert m.forward(xd).shape == (0, 2, 32)
+    xd = torch.zeros((3, 2, 16), dtype=torch.int8, device="cuda")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.LstmIntError) as e:
+        m.forward(xd, workspace=small)
+    assert e.value.code == binding.E_WORKSPACE
+    big = torch.empty(m.workspace_bytes(3, 2) + 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.LstmIntError) as e:
+        m.forward(xd, workspace=big[1:])  # misaligned
+    assert e.value.code == binding.E_WORKSPACE
+    torch.cuda.synchronize()
