@@ -54,6 +54,63 @@ def algorithmic_work(q, B, T, persistent):
     return w
 
 
+def bench_gru(args, np, torch, wl, binding):
+    """One step = one gru_int_forward call on a synthetic batch resident in HBM; checked against the oracle on a
+    few rows and steps in the same run.  Roofline of the step kernel: the bytes one step must move with the
+    weights re-streamed (3 N^2 int8 weights, int16 W x terms, int16 state in and out, int8 state in and three
+    int8 copies out) against its HIP-event time."""
+    L, I, N, B, T = (int(v) for v in args.gru.split(","))
+    layers, x = wl.make_gru([I] + [N] * (L - 1), N, B, T, seed=0, weight_param=0.03)
+    model = binding.gru_prepare(layers, device=0)
+    q0 = model.get_quant(0)
+    xq = np.clip(np.floor(x.astype(np.float64) / q0["s_x"] + 0.5) + q0["zp_x"], -128, 127).astype(np.int8)
+    xd = torch.from_numpy(xq).cuda()
+    ws = torch.empty(model.workspace_bytes(T, B), dtype=torch.uint8, device="cuda")
+    y = model.forward(xd, workspace=ws)
+    for _ in range(args.warmup):
+        model.forward(xd, y=y, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        model.forward(xd, y=y, workspace=ws)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    model.profile_begin()
+    for _ in range(args.steps):
+        model.forward(xd, y=y, workspace=ws)
+    prof = model.profile_end()
+    step_us = prof["step"]["total_ms"] / prof["step"]["launches"] * 1e3
+    gemm_us = prof["input_gemm"]["total_ms"] / prof["input_gemm"]["launches"] * 1e3
+    step_bytes = 3.0 * N * N + 2.0 * B * 3 * N + 4.0 * B * N + B * N + 3.0 * B * N
+    gemm_ops = sum(2.0 * T * B * 3 * N * (I if l == 0 else N) for l in range(L)) / L
+    out = {"metric": "gru_cell_steps_per_sec", "value": B * T * L / dt, "unit": "cell-steps/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+           "config": {"workload": f"integer GRU: L={L} I={I} N={N} B={B} T={T}", "cell_steps_per_step": B * T * L},
+           "roofline": {"bound": "hbm", "achieved": step_bytes / step_us * 1e-3, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": step_bytes / step_us * 1e-3 / PEAK_HBM_GBS, "kernel": "gru_step_kernel",
+                        "avg_launch_us": step_us, "traffic": None,
+                        "kernels": {"input_gemm": {"avg_us": gemm_us, "tops": gemm_ops / gemm_us * 1e-6,
+                                                   "frac_mfma": gemm_ops / gemm_us * 1e-6 / PEAK_INT8_TOPS}}}}
+    if not args.no_cpu_baseline:
+        from oracle import gru as ogru
+
+        rows = sorted(set(int(r) for r in np.linspace(0, B - 1, min(B, 8))))
+        Ts = min(T, 16)
+        om = ogru.GruModel(layers)
+        t0 = time.perf_counter()
+        yo, _ = om.forward(xq[:Ts, rows], threads=len(rows))
+        ot = time.perf_counter() - t0
+        eq = bool((y[:Ts].cpu().numpy()[:, rows] == yo).all())
+        out["cpu_baseline"] = {"value": len(rows) * Ts * L / ot, "unit": "cell-steps/s", "cores": len(rows), "kind": "oracle",
+                               "sample": f"{len(rows)} rows spread over the batch x first {Ts} steps x {L} layers, {ot:.1f} s"}
+        out["parity"] = {"rows": len(rows), "steps": Ts, "layers": L, "equal": eq}
+        if not eq:
+            print(json.dumps(out))
+            sys.exit("bench.py: the GRU output differs from the oracle's")
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +130,9 @@ def main():
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 one launch per operation and step")
     ap.add_argument("--mfma-store-ceiling", action="store_true",
                     help="only measure what the chip sustains for the input GEMM's mix of int8 MFMAs and streaming stores")
+    ap.add_argument("--gru", default="", metavar="L,I,N,B,T",
+                    help="benchmark the integer GRU instead (the cell Sec. 7 names; gru_int_forward): L layers of N cells, "
+                         "layer 0 input I, B rows, T steps, e.g. 2,512,2048,256,64; one JSON line")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB MiB (a known-size reference for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -98,6 +158,9 @@ def main():
         print(json.dumps({"copy_bytes": n, "copies": 3}))
         return
     binding.lib()
+    if args.gru:
+        bench_gru(args, np, torch, wl, binding)
+        return
     if args.mfma_store_ceiling:
         rows = [binding.mfma_store_ceiling(s) for s in (0, 1, 2, 4, 8)]
         print(json.dumps({"mfma_store_ceiling": rows, "note": "40 int8 MFMAs (32x32x32) per wave and round on every CU, "

@@ -124,6 +124,23 @@ int gru_int_forward(const gru_int_model *model, const int8_t *x, int32_t T, int3
                     int16_t *h_state, void *workspace, size_t workspace_bytes, void *hip_stream,
                     const gru_int_trace *trace);
 
+/*
+ * Device time of the forward calls made while profiling is on, measured with
+ * HIP events on the stream the kernels run on, per kernel class: the hoisted
+ * input matmul (one launch per layer and call) and the fused step kernel (T
+ * launches per layer and call, timed as one stretch, so the figure includes
+ * the gaps between consecutive launches).  gru_int_profile_begin resets the
+ * record; gru_int_profile_end waits for the recorded work, fills launches[k]
+ * and total_ms[k] and destroys the events.  Profiling adds host work to
+ * forward and is not meant for calls under graph capture.
+ */
+#define GRU_INT_K_INPUT_GEMM 0
+#define GRU_INT_K_STEP 1
+#define GRU_INT_K_COUNT 2
+int gru_int_profile_begin(gru_int_model *model);
+int gru_int_profile_end(gru_int_model *model, int64_t launches[GRU_INT_K_COUNT],
+                        double total_ms[GRU_INT_K_COUNT]);
+
 void gru_int_destroy(gru_int_model *model);
 
 #ifdef __cplusplus

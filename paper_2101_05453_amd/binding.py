@@ -428,6 +428,10 @@ def gru_lib():
         L.gru_int_forward.restype = C.c_int
         L.gru_int_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(GruTrace)]
+        L.gru_int_profile_begin.restype = C.c_int
+        L.gru_int_profile_begin.argtypes = [C.c_void_p]
+        L.gru_int_profile_end.restype = C.c_int
+        L.gru_int_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
         L.gru_int_destroy.restype = None
         L.gru_int_destroy.argtypes = [C.c_void_p]
         _gru_ready = True
@@ -485,6 +489,16 @@ class GruModel:
     # gru_int_workspace_bytes
     def workspace_bytes(self, T, B):
         return gru_lib().gru_int_workspace_bytes(self._h, T, B)
+
+    # gru_int_profile_begin / gru_int_profile_end
+    def profile_begin(self):
+        _check(gru_lib().gru_int_profile_begin(self._h), "gru_int_profile_begin")
+
+    def profile_end(self):
+        n = (C.c_int64 * 2)()
+        ms = (C.c_double * 2)()
+        _check(gru_lib().gru_int_profile_end(self._h, n, ms), "gru_int_profile_end")
+        return {k: {"launches": int(n[i]), "total_ms": float(ms[i])} for i, k in enumerate(("input_gemm", "step"))}
 
     # gru_int_forward on torch device tensors
     def forward(self, x, y=None, h_state=None, workspace=None, trace_layer=None):

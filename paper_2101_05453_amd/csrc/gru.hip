@@ -7,16 +7,17 @@
 //   1. tx = sat16(rescale(W x + bx')) for all T*B rows: the library's int8
 //      MFMA matmul (kernels.hip), gate-major columns [3N].
 //   2. per step ONE kernel, gru_step_kernel: R h8 + bh for the three gates on
-//      the 16x16x64 int8 MFMA, each wave a tile of 16 batch rows x 16 cells
-//      over the whole depth, with the weights read in operand order (one
-//      contiguous KB per wave load).  The MFMA leaves every lane with the
-//      three gate accumulators of four cells of one batch row, so the whole
-//      elementwise cell (rescale, sigma/tanh tables, reset product, coupled
-//      update, the int8 form of the new state) runs in that lane with no
-//      exchange of any kind.
+//      the 32x32x32 int8 MFMA, a workgroup per tile of 32 cells x 32 or 64
+//      batch rows, depth split over its four waves, weights and state read in
+//      operand order (one contiguous KB per wave load, every byte once per
+//      workgroup).  The MFMA leaves a lane with the three gate accumulators of
+//      the same cells of one batch row, so the whole elementwise cell
+//      (rescale, sigma/tanh tables, reset product, coupled update, the int8
+//      form of the new state) follows in the same kernel with one LDS
+//      reduction and no exchange between workgroups.
 // The state is read and written in place (each (row, cell) belongs to one
-// lane); the int8 form of step t is read by step t + 1 from the layer's output
-// buffer.
+// thread); its int8 form is written three times: in operand order for the
+// next step, row-major for the next layer's matmul, dense for the caller.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -48,16 +49,18 @@ struct GruLayerHost {
 
 // padded extents of one layer on the device
 struct GruDims {
-  int Ip, Kp, Ncp, cols_pad;  // input depth / state depth (multiples of 64), cells (multiple of 16), 3N to 128
+  int Ip, Kp, Ncp, cols_pad;  // input depth / state depth (multiples of 64), cells (multiple of 32), 3N to 128
 };
 GruDims gru_dims(int I, int N) {
-  return GruDims{(I + 63) / 64 * 64, (N + 63) / 64 * 64, (N + 15) / 16 * 16, (3 * N + 127) / 128 * 128};
+  return GruDims{(I + 63) / 64 * 64, (N + 63) / 64 * 64, (N + 31) / 32 * 32, (3 * N + 127) / 128 * 128};
 }
+// bytes of the operand-ordered copy of the int8 state for B rows: whole blocks of 32 rows, an even number of them
+size_t hop_bytes(int B, int Kp) { return (size_t)((B + 63) / 64 * 2) * (Kp / 32) * 1024; }
 
 struct GruLayerDev {
   const int8_t *W = nullptr;      // [cols_pad][Ip] gate-major rows, zero beyond the real extents
   const int32_t *bx = nullptr;    // [cols_pad] folded input bias
-  const int8_t *Rop = nullptr;    // [Ncp/16][3][Kp/64][64 lanes][16 B]: operand order of the 16x16x64 MFMA
+  const int8_t *Rop = nullptr;    // [Ncp/32][3][Kp/32][64 lanes][16 B]: operand order of the 32x32x32 MFMA
   const int32_t *bh = nullptr;    // [3][Ncp]
 };
 
@@ -148,12 +151,21 @@ int prepare_gru_layer(const gru_int_layer_params &p, bool has_prev, GruLayerHost
 // kernels
 // ---------------------------------------------------------------------------
 
+typedef int v16i __attribute__((ext_vector_type(16)));
+
 // the int8 form of a state value: sat8(floor((h16 + 128) / 256))
 __device__ __forceinline__ int32_t state_i8(int32_t h16) { return sat8((h16 + 128) >> 8); }
 
+// Byte offset of state value (row, k) in the operand-ordered copy of h8 that the step kernel reads:
+// [row / 32][k / 32][64 lanes][16 B], lane = 32 ((k / 16) % 2) + row % 32 -- the second operand of the
+// 32x32x32 int8 MFMA for 32 rows and one 32-deep k step is one contiguous KB.
+__host__ __device__ __forceinline__ size_t hop_offset(int row, int k, int KS32) {
+  return ((((size_t)(row >> 5) * KS32 + (k >> 5)) * 64 + (((k >> 4) & 1) << 5) + (row & 31)) << 4) + (k & 15);
+}
+
 // Start of a layer: the working state (caller's h_state slice or zeros) is used in place; its int8 form
-// goes to h8_0 [B][Kp] (pad bytes zero).
-__global__ void gru_init_kernel(int16_t *h16, int B, int N, int Kp, int8_t *h8_0, int zero_state) {
+// goes to the operand-ordered buffer hop0 (columns N..Kp-1 zero).
+__global__ void gru_init_kernel(int16_t *h16, int B, int N, int Kp, int8_t *hop0, int zero_state) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)B * Kp) return;
   const int b = (int)(i / Kp), k = (int)(i - (int64_t)b * Kp);
@@ -164,17 +176,19 @@ __global__ void gru_init_kernel(int16_t *h16, int B, int N, int Kp, int8_t *h8_0
     else
       v = state_i8(h16[(size_t)b * N + k]);
   }
-  h8_0[i] = (int8_t)v;
+  hop0[hop_offset(b, k, Kp >> 5)] = (int8_t)v;
 }
 
 struct GruStepArgs {
-  int32_t B, N, Ncp, Kp, KS;  // KS = Kp / 64
-  const int8_t *h8_prev;      // [B][Kp]
-  const int8_t *Rop;
-  const int32_t *bh;          // [3][Ncp]
+  int32_t B, N, Kp, KS32;     // KS32 = Kp / 32
+  int32_t ctiles, rtn;        // tiles of 32 cells; tiles of 32 RB rows
+  const int8_t *hop_prev;     // state before the step, operand order
+  const int8_t *Rop;          // [ctiles][3][KS32][64 lanes][16 B]
+  const int32_t *bh;          // [3][32 ctiles]
   const int16_t *tx;          // [B][3N] of this step
   int16_t *h16;               // [B][N] in/out
-  int8_t *h8_out;             // [B][Kp]
+  int8_t *hop_out;            // state after the step, operand order
+  int8_t *h8_out;             // [B][Kp] row-major (the next layer's matmul input)
   int8_t *y;                  // [B][N] or NULL
   int32_t Mh[3], rh[3];
   const uint16_t *sig_tab, *tanh_tab;  // [32769] each, Q3.12 inputs
@@ -182,79 +196,179 @@ struct GruStepArgs {
   int8_t *tr_h8;
 };
 
-__global__ __launch_bounds__(256) void gru_step_kernel(GruStepArgs a) {
-  const int lane = threadIdx.x & 63;
-  const int wave_id = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int ctiles = a.Ncp >> 4;
-  const int rt = wave_id / ctiles, ct = wave_id - rt * ctiles;
-  if (rt * 16 >= a.B) return;  // uniform per wave; the kernel has no barrier
-  const int rowl = lane & 15, q4 = lane >> 4;
-  int brow = rt * 16 + rowl;
-  const bool row_ok = brow < a.B;
-  brow = row_ok ? brow : a.B - 1;  // rows past the batch repeat the last one; never stored
+// One step of one layer.  A workgroup owns 32 cells (their r, u, n rows of R: 96 x Kp bytes) and 32 RB batch
+// rows; its four waves split the depth, each running its quarter of the k steps for all RB x 3 tiles of the
+// 32x32x32 int8 MFMA with both operands loaded straight into registers in operand order (every byte of the
+// weight slice and of the state tile is loaded once per workgroup, a contiguous KB per wave load), and the four
+// partial sums meet in LDS.  The MFMA leaves a lane with 16 cells of one batch row, the same cells in each of
+// the three gate tiles, so the elementwise cell needs no further exchange.
+// Workgroup w takes cell tile (w % 8) + 8 (w / 8 / rtn): the hardware deals consecutive workgroups out to the
+// eight XCDs in turn, and every launch here is a multiple of eight workgroups, so an XCD meets the same eighth
+// of R at every step of a sequence and keeps it in its L2 (N = 2048: 1.5 MB of 4 MB).  The mapping only places
+// the work; results do not depend on where a workgroup runs.
+constexpr int kPartTile = 32 * 33;  // one 32 x 32 tile of partial sums in LDS, row stride 33
 
-  // R h8 for the three gates: acc[g][v] = sum_k R_g[16 ct + 4 q4 + v][k] h8[brow][k]
-  v4i acc[3] = {v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}};
-  const int8_t *hp = a.h8_prev + (size_t)brow * a.Kp + (q4 << 4);
-  const v4i *wp = reinterpret_cast<const v4i *>(a.Rop) + ((size_t)ct * 3 * a.KS) * 64 + lane;
-  const int KS = a.KS;
-  constexpr int U = 4;  // k steps whose loads are issued together
-  int ks = 0;
-  for (; ks + U <= KS; ks += U) {
-    v4i hf[U], wf[U][3];
+template <int RB>
+__global__ __launch_bounds__(256) void gru_step_kernel(GruStepArgs a) {
+  extern __shared__ __attribute__((aligned(16))) int32_t part[];  // [4 waves][RB][3][kPartTile]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, b2 = lane >> 5;
+  const int w = blockIdx.x, j = w >> 3;
+  const int ct = (w & 7) + 8 * (j / a.rtn), rt = j % a.rtn;
+  if (ct >= a.ctiles) return;  // uniform over the workgroup, ahead of every barrier
+  const int KS = a.KS32;
+  const int rblocks = (a.B + 31) >> 5;  // row blocks that exist in the operand-ordered buffers
+
+  // this thread's share of the elementwise cell, and its W x terms and old state requested now: they come from
+  // memory and are not needed before the matmul is done
+  const int rsub = threadIdx.x >> 3, cg = threadIdx.x & 7;
+  const int N = a.N;
+  const int n0 = ct * 32 + 4 * cg;
+  const bool vec = (N & 3) == 0;  // runs of four cells are aligned 8-byte pieces of tx and h16
+  int rowe[RB];
+  int32_t txe[RB][3][4], h16e[RB][4];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    rowe[rb] = (rt * RB + rb) * 32 + rsub;
+    const int row = rowe[rb] < a.B ? rowe[rb] : a.B - 1;
+    const int16_t *txp = a.tx + (size_t)row * 3 * N + n0;
+    const int16_t *hq = a.h16 + (size_t)row * N + n0;
+    if (vec && n0 < N) {
+#pragma unroll
+      for (int g = 0; g < 3; ++g) {
+        const short4 t4 = *reinterpret_cast<const short4 *>(txp + (size_t)g * N);
+        txe[rb][g][0] = t4.x; txe[rb][g][1] = t4.y; txe[rb][g][2] = t4.z; txe[rb][g][3] = t4.w;
+      }
+      const short4 h4 = *reinterpret_cast<const short4 *>(hq);
+      h16e[rb][0] = h4.x; h16e[rb][1] = h4.y; h16e[rb][2] = h4.z; h16e[rb][3] = h4.w;
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool in = n0 + c < N;
+#pragma unroll
+        for (int g = 0; g < 3; ++g) txe[rb][g][c] = in ? txp[(size_t)g * N + c] : 0;
+        h16e[rb][c] = in ? hq[c] : 0;
+      }
+    }
+  }
+
+  v16i acc[RB][3];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int g = 0; g < 3; ++g)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[rb][g][v] = 0;
+  const v4i *wp = reinterpret_cast<const v4i *>(a.Rop) + (size_t)ct * 3 * KS * 64 + lane;
+  const v4i *hp[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    int blk = rt * RB + rb;
+    blk = blk < rblocks ? blk : rblocks - 1;  // a row block past the batch repeats the last one; never stored
+    hp[rb] = reinterpret_cast<const v4i *>(a.hop_prev) + (size_t)blk * KS * 64 + lane;
+  }
+  const int per = (KS + 3) >> 2;
+  const int k0 = wave * per, k1 = k0 + per < KS ? k0 + per : KS;
+  // U k steps per batch, all their loads in flight together (one wave per SIMD: nothing else hides the
+  // latency); steps past the wave's share re-read its last step against zero weights
+  constexpr int U = 8;
+  for (int ks = k0; ks < k1; ks += U) {
+    v4i hf[U][RB], wf[U][3];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      hf[u] = *reinterpret_cast<const v4i *>(hp + (size_t)(ks + u) * 64);
+      const int kk = ks + u < k1 ? ks + u : k1 - 1;
 #pragma unroll
-      for (int g = 0; g < 3; ++g) wf[u][g] = wp[((size_t)g * KS + ks + u) * 64];
+      for (int g = 0; g < 3; ++g) wf[u][g] = wp[((size_t)g * KS + kk) * 64];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) hf[u][rb] = hp[rb][(size_t)kk * 64];
     }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int u = 0; u < U; ++u) {
+      const bool live = ks + u < k1;
 #pragma unroll
-      for (int g = 0; g < 3; ++g) acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[u][g], hf[u], acc[g], 0, 0, 0);
+      for (int g = 0; g < 3; ++g) {
+        const v4i wv = live ? wf[u][g] : v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+          acc[rb][g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, hf[u][rb], acc[rb][g], 0, 0, 0);
+      }
+    }
   }
-  for (; ks < KS; ++ks) {
-    const v4i hf = *reinterpret_cast<const v4i *>(hp + (size_t)ks * 64);
+  // partial sums -> LDS as [wave][rb][gate][2 v + b2][33]: result value v of lane (col, b2) is cell
+  // 8 (v / 4) + 4 b2 + v % 4 of the tile for batch row col; the odd stride keeps the transposed reads below
+  // at two lanes per bank
 #pragma unroll
-    for (int g = 0; g < 3; ++g) acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wp[((size_t)g * KS + ks) * 64], hf, acc[g], 0, 0, 0);
-  }
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int g = 0; g < 3; ++g)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) part[((wave * RB + rb) * 3 + g) * kPartTile + (2 * v + b2) * 33 + col] = acc[rb][g][v];
+  __syncthreads();
 
-  // the cell, four cells of one batch row per lane
-  const int n0 = ct * 16 + q4 * 4;
-  const int N = a.N;
-  const size_t row3 = (size_t)brow * 3 * N;
+  // The elementwise cell, with the threads laid out along the rows: thread (rsub, cg) takes cells 4 cg .. 4 cg + 3
+  // of row rsub in each row block, so that a wave's loads and stores cover runs of 32 consecutive cells of 8 rows
+  // (a lane's four cells share the result index v / 4 = cg / 2 and the lane half b2 = cg % 2).
 #pragma unroll
-  for (int v = 0; v < 4; ++v) {
-    const int n = n0 + v;
-    if (n >= N || !row_ok) continue;
-    int32_t tx[3], th[3];
+  for (int rb = 0; rb < RB; ++rb) {
+    const int row = rowe[rb];
+    const bool row_ok = row < a.B;
+    int32_t h84[4], hn4[4];
 #pragma unroll
-    for (int g = 0; g < 3; ++g) {
-      tx[g] = a.tx[row3 + (size_t)g * N + n];
-      th[g] = sat16(rescale(acc[g][v] + a.bh[g * a.Ncp + n], a.Mh[g], a.rh[g]));
+    for (int c = 0; c < 4; ++c) {
+      const int n = n0 + c;
+      int32_t th[3];
+#pragma unroll
+      for (int g = 0; g < 3; ++g) {
+        const int o = (rb * 3 + g) * kPartTile + (2 * (4 * (cg >> 1) + c) + (cg & 1)) * 33 + rsub;
+        const int32_t sum = part[o] + part[o + RB * 3 * kPartTile] + part[o + 2 * RB * 3 * kPartTile] + part[o + 3 * RB * 3 * kPartTile];
+        th[g] = sat16(rescale(sum + a.bh[g * 32 * a.ctiles + n], a.Mh[g], a.rh[g]));
+      }
+      const int32_t r = sigmoid_from_table(a.sig_tab, sat16(txe[rb][0][c] + th[0]));  // Sec. 3.2.1
+      const int32_t u = sigmoid_from_table(a.sig_tab, sat16(txe[rb][1][c] + th[1]));
+      const int32_t rn = (r * th[2] + 16384) >> 15;  // Q0.15 x Q3.12 -> Q3.12; |r th| < 2^30
+      const int32_t cand = tanh_from_table(a.tanh_tab, sat16(txe[rb][2][c] + rn));
+      const int32_t ubar = cifg_input_gate(u);  // 1 - u, Sec. 3.2.9
+      const int32_t hn = cell_update32(ubar, cand, u, h16e[rb][c], 0);  // Sec. 3.2.7, both products Q0.30 -> Q0.15
+      hn4[c] = hn;
+      h84[c] = state_i8(hn);
+      if (row_ok && n < N) {
+        const size_t row3 = (size_t)row * 3 * N;
+        if (a.tr_tx)
+          for (int g = 0; g < 3; ++g) a.tr_tx[row3 + (size_t)g * N + n] = (int16_t)txe[rb][g][c];
+        if (a.tr_th)
+          for (int g = 0; g < 3; ++g) a.tr_th[row3 + (size_t)g * N + n] = (int16_t)th[g];
+        if (a.tr_act) {
+          a.tr_act[row3 + n] = (int16_t)r;
+          a.tr_act[row3 + (size_t)N + n] = (int16_t)u;
+          a.tr_act[row3 + (size_t)2 * N + n] = (int16_t)cand;
+        }
+        if (a.tr_h16) a.tr_h16[(size_t)row * N + n] = (int16_t)hn;
+        if (a.tr_h8) a.tr_h8[(size_t)row * N + n] = (int8_t)h84[c];
+      }
     }
-    const int32_t r = sigmoid_from_table(a.sig_tab, sat16(tx[0] + th[0]));  // Sec. 3.2.1
-    const int32_t u = sigmoid_from_table(a.sig_tab, sat16(tx[1] + th[1]));
-    const int32_t rn = (r * th[2] + 16384) >> 15;  // Q0.15 x Q3.12 -> Q3.12; |r th| < 2^30
-    const int32_t c = tanh_from_table(a.tanh_tab, sat16(tx[2] + rn));
-    const int32_t ubar = cifg_input_gate(u);  // 1 - u, Sec. 3.2.9
-    const int32_t hold = a.h16[(size_t)brow * N + n];
-    const int32_t hn = cell_update32(ubar, c, u, hold, 0);  // Sec. 3.2.7 with both products Q0.30 -> Q0.15
-    const int32_t h8 = state_i8(hn);
-    a.h16[(size_t)brow * N + n] = (int16_t)hn;
-    a.h8_out[(size_t)brow * a.Kp + n] = (int8_t)h8;
-    if (a.y) a.y[(size_t)brow * N + n] = (int8_t)h8;
-    if (a.tr_tx)
-      for (int g = 0; g < 3; ++g) a.tr_tx[row3 + (size_t)g * N + n] = (int16_t)tx[g];
-    if (a.tr_th)
-      for (int g = 0; g < 3; ++g) a.tr_th[row3 + (size_t)g * N + n] = (int16_t)th[g];
-    if (a.tr_act) {
-      a.tr_act[row3 + n] = (int16_t)r;
-      a.tr_act[row3 + (size_t)N + n] = (int16_t)u;
-      a.tr_act[row3 + (size_t)2 * N + n] = (int16_t)c;
+    if (!row_ok || n0 >= N) continue;
+    int16_t *hd = a.h16 + (size_t)row * N + n0;
+    if (vec) {
+      short4 o4;
+      o4.x = (short)hn4[0]; o4.y = (short)hn4[1]; o4.z = (short)hn4[2]; o4.w = (short)hn4[3];
+      *reinterpret_cast<short4 *>(hd) = o4;
+    } else {
+      for (int c = 0; c < 4 && n0 + c < N; ++c) hd[c] = (int16_t)hn4[c];
     }
-    if (a.tr_h16) a.tr_h16[(size_t)brow * N + n] = (int16_t)hn;
-    if (a.tr_h8) a.tr_h8[(size_t)brow * N + n] = (int8_t)h8;
+    // the int8 form: operand order for the next step, row-major for the next layer, dense for the caller
+    uint32_t pk = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) pk |= (uint32_t)((n0 + c < N ? h84[c] : 0) & 0xFF) << (8 * c);
+    *reinterpret_cast<uint32_t *>(a.hop_out + hop_offset(row, n0, KS)) = pk;  // cells past N hold 0 and meet zero weights
+    *reinterpret_cast<uint32_t *>(a.h8_out + (size_t)row * a.Kp + n0) = pk;
+    if (a.y) {
+      int8_t *yd = a.y + (size_t)row * N + n0;
+      if (vec && !(reinterpret_cast<uintptr_t>(a.y) & 3))
+        *reinterpret_cast<uint32_t *>(yd) = pk;
+      else
+        for (int c = 0; c < 4 && n0 + c < N; ++c) yd[c] = (int8_t)h84[c];
+    }
   }
 }
 
@@ -266,8 +380,15 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 using namespace lstm_int;
 
+struct GruTimed {  // one timed stretch of launches of a forward call made while profiling
+  hipEvent_t start, stop;
+  int cls, launches;
+};
+
 struct gru_int_model {
   int device = -1;
+  bool profiling = false;
+  std::vector<GruTimed> timed;
   std::vector<GruLayerHost> host;
   std::vector<GruLayerDev> dev;
   uint8_t *arena = nullptr;
@@ -278,16 +399,16 @@ namespace {
 
 // carve-up of the workspace for (T, B)
 struct GruWs {
-  size_t xpad, tx, out[2], h8_0, h16, total;
+  size_t xpad, tx, out[2], hop[2], h16, total;
 };
 GruWs gru_workspace(const gru_int_model *m, int64_t T, int64_t B) {
   GruWs w{};
-  size_t off = 0, max_tx = 0, max_out = 0, max_h0 = 0, sum_h16 = 0;
+  size_t off = 0, max_tx = 0, max_out = 0, max_hop = 0, sum_h16 = 0;
   for (const GruLayerHost &q : m->host) {
     const GruDims d = gru_dims(q.I, q.N);
     max_tx = std::max(max_tx, (size_t)T * B * 3 * q.N * 2);
     max_out = std::max(max_out, (size_t)T * B * d.Kp);
-    max_h0 = std::max(max_h0, (size_t)B * d.Kp);
+    max_hop = std::max(max_hop, hop_bytes((int)B, d.Kp));
     sum_h16 = std::max(sum_h16, (size_t)B * q.N * 2);
   }
   const GruDims d0 = gru_dims(m->host[0].I, m->host[0].N);
@@ -295,7 +416,8 @@ GruWs gru_workspace(const gru_int_model *m, int64_t T, int64_t B) {
   w.tx = off; off += align256(max_tx);
   w.out[0] = off; off += align256(max_out);
   w.out[1] = off; off += align256(max_out);
-  w.h8_0 = off; off += align256(max_h0);
+  w.hop[0] = off; off += align256(max_hop);
+  w.hop[1] = off; off += align256(max_hop);
   w.h16 = off; off += align256(sum_h16);
   w.total = off;
   return w;
@@ -345,21 +467,21 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
       const GruLayerHost &q = m->host[l];
       const int I = q.I, N = q.N;
       const GruDims d = gru_dims(I, N);
-      const int KS = d.Kp / 64;
+      const int KS = d.Kp / 32;
       Off o;
       o.W = reserve((size_t)d.cols_pad * d.Ip);
       o.bx = reserve((size_t)d.cols_pad * 4);
-      o.R = reserve((size_t)(d.Ncp / 16) * 3 * KS * 1024);
+      o.R = reserve((size_t)(d.Ncp / 32) * 3 * KS * 1024);
       o.bh = reserve((size_t)3 * d.Ncp * 4);
       for (int r = 0; r < 3 * N; ++r) std::memcpy(img.data() + o.W + (size_t)r * d.Ip, q.Wq.data() + (size_t)r * I, I);
       std::memcpy(img.data() + o.bx, q.bx_fold.data(), (size_t)3 * N * 4);
-      // operand of lane (row = lane % 16, chunk = lane / 16) at k step ks: bytes 64 ks + 16 chunk .. + 15 of weight
-      // row 16 ct + row of gate g (zero beyond N in either direction)
-      for (int ct = 0; ct < d.Ncp / 16; ++ct)
+      // first operand of the 32x32x32 MFMA: lane (row = lane % 32, half = lane / 32) holds, for k step ks, bytes
+      // 32 ks + 16 half .. + 15 of weight row 32 ct + row of gate g (zero beyond N in either direction)
+      for (int ct = 0; ct < d.Ncp / 32; ++ct)
         for (int g = 0; g < 3; ++g)
           for (int ks = 0; ks < KS; ++ks)
             for (int lane = 0; lane < 64; ++lane) {
-              const int n = ct * 16 + (lane & 15), k0 = ks * 64 + (lane >> 4) * 16;
+              const int n = ct * 32 + (lane & 31), k0 = ks * 32 + (lane >> 5) * 16;
               uint8_t *dst = img.data() + o.R + ((((size_t)ct * 3 + g) * KS + ks) * 64 + lane) * 16;
               if (n < N)
                 for (int j = 0; j < 16 && k0 + j < N; ++j) dst[j] = (uint8_t)q.Rq[((size_t)g * N + n) * N + k0 + j];
@@ -368,7 +490,10 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
         std::memcpy(img.data() + o.bh + (size_t)g * d.Ncp * 4, q.bhq.data() + (size_t)g * N, (size_t)N * 4);
       offs[l] = o;
     }
-    if (hipSetDevice(device) != hipSuccess || hipMalloc(reinterpret_cast<void **>(&m->arena), img.size()) != hipSuccess) {
+    if (hipSetDevice(device) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void *>(gru_step_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            4 * 2 * 3 * kPartTile * 4) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&m->arena), img.size()) != hipSuccess) {
       m->arena = nullptr;
       delete m;
       return LSTM_INT_E_DEVICE;
@@ -451,7 +576,7 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
     const GruDims d = gru_dims(q.I, N);
     int16_t *tx = reinterpret_cast<int16_t *>(ws + w.tx);
     int8_t *out = reinterpret_cast<int8_t *>(ws + w.out[l & 1]);
-    int8_t *h8_0 = reinterpret_cast<int8_t *>(ws + w.h8_0);
+    int8_t *hop[2] = {reinterpret_cast<int8_t *>(ws + w.hop[0]), reinterpret_cast<int8_t *>(ws + w.hop[1])};
     int16_t *h16 = h_state ? h_state + h_off : reinterpret_cast<int16_t *>(ws + w.h16);
     const gru_int_trace *tr = (trace && trace->layer == l) ? trace : nullptr;
 
@@ -466,26 +591,45 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
     rq.r[3] = rq.r[2];
     rq.cols_per_gate = N;
     rq.zp = 0;
+    gru_int_model *mm = const_cast<gru_int_model *>(m);  // the profile is bookkeeping beside the model
+    auto timed_begin = [&](int cls, int launches) {
+      if (!m->profiling) return;
+      GruTimed e{nullptr, nullptr, cls, launches};
+      if (hipEventCreate(&e.start) != hipSuccess || hipEventCreate(&e.stop) != hipSuccess) return;
+      (void)hipEventRecord(e.start, s);
+      mm->timed.push_back(e);
+    };
+    auto timed_end = [&]() {
+      if (m->profiling && !mm->timed.empty()) (void)hipEventRecord(mm->timed.back().stop, s);
+    };
+    timed_begin(GRU_INT_K_INPUT_GEMM, 1);
     launch_gemm_i16(s, in, ld_in, (int)TB, dv.W, d.Ip, 3 * N, dv.bx, rq, tx, 3 * N);
+    timed_end();
 
     {
-      const int64_t n = (int64_t)B * d.Kp;
-      hipLaunchKernelGGL(gru_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, h16, B, N, d.Kp, h8_0,
+      const int64_t n = (int64_t)B * d.Kp;  // the state before step 0 goes where step "-1" would have put it
+      hipLaunchKernelGGL(gru_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, h16, B, N, d.Kp, hop[1],
                          h_state ? 0 : 1);
     }
     GruStepArgs a{};
-    a.B = B; a.N = N; a.Ncp = d.Ncp; a.Kp = d.Kp; a.KS = d.Kp / 64;
+    a.B = B; a.N = N; a.Kp = d.Kp; a.KS32 = d.Kp / 32;
+    a.ctiles = d.Ncp / 32;
     a.Rop = dv.Rop; a.bh = dv.bh; a.h16 = h16;
     for (int g = 0; g < 3; ++g) {
       a.Mh[g] = q.Mh[g];
       a.rh[g] = 31 - q.eh[g];
     }
     a.sig_tab = m->sig_tab; a.tanh_tab = m->tanh_tab;
-    const int waves = ((B + 15) / 16) * (d.Ncp / 16);
-    const dim3 grid((unsigned)((waves + 3) / 4));
+    // 64 rows per workgroup once that still leaves a workgroup for every compute unit, else 32
+    const int rb = ((B + 63) / 64) * a.ctiles >= 256 ? 2 : 1;
+    a.rtn = (B + 32 * rb - 1) / (32 * rb);
+    const dim3 grid((unsigned)(8 * a.rtn * ((a.ctiles + 7) / 8)));
+    const size_t lds = (size_t)4 * rb * 3 * kPartTile * 4;
+    timed_begin(GRU_INT_K_STEP, T);
     for (int t = 0; t < T; ++t) {
       const size_t tb = (size_t)t * B;
-      a.h8_prev = t == 0 ? h8_0 : out + (tb - B) * d.Kp;
+      a.hop_prev = hop[(t + 1) & 1];
+      a.hop_out = hop[t & 1];
       a.tx = tx + tb * 3 * N;
       a.h8_out = out + tb * d.Kp;
       a.y = l == L - 1 ? y + tb * N : nullptr;
@@ -494,8 +638,12 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
       a.tr_act = tr && tr->act ? tr->act + tb * 3 * N : nullptr;
       a.tr_h16 = tr && tr->h16 ? tr->h16 + tb * N : nullptr;
       a.tr_h8 = tr && tr->h8 ? tr->h8 + tb * N : nullptr;
-      hipLaunchKernelGGL(gru_step_kernel, grid, dim3(256), 0, s, a);
+      if (rb == 2)
+        hipLaunchKernelGGL(gru_step_kernel<2>, grid, dim3(256), lds, s, a);
+      else
+        hipLaunchKernelGGL(gru_step_kernel<1>, grid, dim3(256), lds, s, a);
     }
+    timed_end();
     in = out;
     ld_in = d.Kp;
     h_off += (size_t)B * N;
@@ -503,8 +651,49 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
   return hipGetLastError() == hipSuccess ? LSTM_INT_OK : LSTM_INT_E_DEVICE;
 }
 
+int gru_int_profile_begin(gru_int_model *m) {
+  if (!m) return LSTM_INT_E_INVALID_ARG;
+  if (m->device < 0) return LSTM_INT_E_DEVICE;
+  for (GruTimed &e : m->timed) {
+    (void)hipEventDestroy(e.start);
+    (void)hipEventDestroy(e.stop);
+  }
+  m->timed.clear();
+  m->profiling = true;
+  return LSTM_INT_OK;
+}
+
+int gru_int_profile_end(gru_int_model *m, int64_t launches[GRU_INT_K_COUNT], double total_ms[GRU_INT_K_COUNT]) {
+  if (!m || !launches || !total_ms) return LSTM_INT_E_INVALID_ARG;
+  if (m->device < 0) return LSTM_INT_E_DEVICE;
+  m->profiling = false;
+  for (int k = 0; k < GRU_INT_K_COUNT; ++k) {
+    launches[k] = 0;
+    total_ms[k] = 0.0;
+  }
+  int rc = LSTM_INT_OK;
+  if (hipSetDevice(m->device) != hipSuccess) rc = LSTM_INT_E_DEVICE;
+  for (GruTimed &e : m->timed) {
+    float ms = 0.f;
+    if (rc == LSTM_INT_OK && hipEventSynchronize(e.stop) == hipSuccess && hipEventElapsedTime(&ms, e.start, e.stop) == hipSuccess) {
+      launches[e.cls] += e.launches;
+      total_ms[e.cls] += ms;
+    } else {
+      rc = LSTM_INT_E_DEVICE;
+    }
+    (void)hipEventDestroy(e.start);
+    (void)hipEventDestroy(e.stop);
+  }
+  m->timed.clear();
+  return rc;
+}
+
 void gru_int_destroy(gru_int_model *m) {
   if (!m) return;
+  for (GruTimed &e : m->timed) {
+    (void)hipEventDestroy(e.start);
+    (void)hipEventDestroy(e.stop);
+  }
   if (m->arena) {
     (void)hipSetDevice(m->device);
     (void)hipFree(m->arena);
