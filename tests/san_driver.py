@@ -118,6 +118,27 @@ def main():
     for m_c in range(9):
         for i, z, f, c in ((32767, 32767, 32767, 32767), (32767, -32768, 32767, -32768), (0, 0, 0, 0)):
             hm.hm_cell_update32(i, z, f, c, m_c)
+    # 5. the GRU of the same oracle: ragged shapes, saturating inputs and gate sums, depth 2^15 at the weight bounds
+    from oracle import gru  # noqa: E402
+
+    layers, x = wl.make_gru([19, 37], 37, 3, 9, seed=6, weight_param=0.3, input_dist="uniform", input_param=3.0)
+    layers[0].x_min, layers[0].x_max = -1.0, 2.0
+    layers[0].bx[1] = layers[0].bx[1] * 80
+    gm = gru.GruModel(layers)
+    q0 = gm.get_quant(0)
+    xq = np.clip(np.floor(x.astype(np.float64) / q0["s_x"] + 0.5) + q0["zp_x"], -128, 127).astype(np.int8)
+    hs = np.full(2 * 3 * 37, -32768, np.int16)
+    for l in range(2):
+        gm.forward(xq, h_state=hs, trace_layer=l)
+    gm.forward(xq, unfolded=True)
+    gru.float_forward(layers, x)
+    layers, x = wl.make_gru([32768], 8, 1, 2, seed=2, weight_param=0.01)
+    for g in range(3):
+        layers[0].W[g] = np.where(layers[0].W[g] >= 0, 0.01, -0.01).astype(np.float32)
+    gm = gru.GruModel(layers)
+    xq = np.where(np.asarray(layers[0].W[0][0])[None, None, :] >= 0, -128, 127).astype(np.int8).repeat(2, 0)
+    gm.forward(np.ascontiguousarray(xq), trace_layer=0)
+    print("gru ok", flush=True)
     print("SAN DRIVER OK", flush=True)
 
 
