@@ -229,6 +229,31 @@ int lstm_int_forward_static(const lstm_int_model *model, const int8_t *x, int32_
                             void *hip_stream);
 
 /*
+ * A bidirectional layer (Sec. 7: the bidirectional LSTM is two loops over the
+ * same cell, one in each time direction): `fwd` runs from t = 0 up, `bwd` --
+ * a model of its own whose option "reverse" is 1 -- from t = T - 1 down, both
+ * over the same x, and y (DEVICE int8 [T,B,H_fwd + H_bwd]) receives at every
+ * (t, b) the forward stack's output in columns [0, H_fwd) and the backward
+ * stack's in [H_fwd, H_fwd + H_bwd), each in its own model's (s_h, zp_h): the
+ * concatenation needs no common scale (the paper gives no rule for any other
+ * way of joining the two).  Both models must be prepared on the same device
+ * with the same input width and input quantization (x_min, x_max of layer 0).
+ * State buffers as in lstm_int_forward, per direction, each may be NULL; the
+ * backward state enters at t = T - 1 and leaves after t = 0.
+ * workspace >= lstm_int_bidirectional_workspace_bytes(fwd, bwd, T, B).
+ * The two directions run one after the other on hip_stream.
+ * LSTM_INT_E_INVALID_ARG: widths or input quantization differ, fwd has
+ * "reverse" set or bwd has not.
+ */
+size_t lstm_int_bidirectional_workspace_bytes(const lstm_int_model *fwd, const lstm_int_model *bwd,
+                                              int32_t T, int32_t B);
+int lstm_int_forward_bidirectional(const lstm_int_model *fwd, const lstm_int_model *bwd,
+                                   const int8_t *x, int32_t T, int32_t B, int8_t *y,
+                                   int8_t *h_state_fwd, int16_t *c_state_fwd,
+                                   int8_t *h_state_bwd, int16_t *c_state_bwd,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Options of the online phase.  One selects what is computed:
  *   "reverse": 1 = every layer runs its recursion (eqs. 1-7) from time T - 1
  *           down to 0, i.e. the stack applied to the time-reversed sequence,

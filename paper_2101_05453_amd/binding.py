@@ -105,6 +105,12 @@ def lib():
         L.lstm_int_forward_static.restype = C.c_int
         L.lstm_int_forward_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                               C.c_void_p, C.c_void_p, C.c_void_p]
+        L.lstm_int_bidirectional_workspace_bytes.restype = C.c_size_t
+        L.lstm_int_bidirectional_workspace_bytes.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
+        L.lstm_int_forward_bidirectional.restype = C.c_int
+        L.lstm_int_forward_bidirectional.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                     C.c_void_p, C.c_size_t, C.c_void_p]
         L.lstm_int_set_option.restype = C.c_int
         L.lstm_int_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
         L.lstm_int_device_status.restype = C.c_int
@@ -336,6 +342,32 @@ def prepare(layers, device=0):
     del keep
     _check(rc, "lstm_int_prepare")
     return Model(h, len(layers), device)
+
+
+# lstm_int_bidirectional_workspace_bytes
+def bidirectional_workspace_bytes(fwd, bwd, T, B):
+    return lib().lstm_int_bidirectional_workspace_bytes(fwd._h, bwd._h, T, B)
+
+
+# lstm_int_forward_bidirectional on torch device tensors
+def forward_bidirectional(fwd, bwd, x, y=None, state_fwd=(None, None), state_bwd=(None, None), workspace=None):
+    """fwd, bwd: Models on the same device, bwd with option "reverse" = 1.  x: int8 CUDA tensor [T,B,I0].
+    Returns y int8 [T,B,H_fwd + H_bwd].  Asynchronous on torch's current stream."""
+    import torch
+
+    assert x.is_cuda and x.dtype == torch.int8 and x.is_contiguous()
+    T, B, _ = x.shape
+    Hf, Hb = fwd.dims()[-1][2], bwd.dims()[-1][2]
+    if y is None:
+        y = torch.empty((T, B, Hf + Hb), dtype=torch.int8, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(bidirectional_workspace_bytes(fwd, bwd, T, B), 256), dtype=torch.uint8, device=x.device)
+    p = lambda t: t.data_ptr() if t is not None else None
+    stream = torch.cuda.current_stream(x.device).cuda_stream
+    _check(lib().lstm_int_forward_bidirectional(fwd._h, bwd._h, x.data_ptr(), T, B, y.data_ptr(), p(state_fwd[0]),
+                                                p(state_fwd[1]), p(state_bwd[0]), p(state_bwd[1]), workspace.data_ptr(),
+                                                workspace.numel(), stream), "lstm_int_forward_bidirectional")
+    return y
 
 
 # lstm_int_calibrate

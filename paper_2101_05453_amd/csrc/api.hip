@@ -1202,6 +1202,47 @@ int lstm_int_forward_static(const lstm_int_model *m, const int8_t *x, int32_t T,
   return lstm_int_forward(m, x, T, B, y, h_state, c_state, ws, LSTM_INT_STATIC_WORKSPACE_BYTES, hip_stream, nullptr);
 }
 
+// Workspace of a bidirectional call: the larger of the two directions' own workspaces, then one dense
+// [T, B, max(H_fwd, H_bwd)] staging buffer from which each direction's output is placed into its columns of y.
+static size_t bidi_stage_offset(const lstm_int_model *f, const lstm_int_model *b, int32_t T, int32_t B) {
+  const size_t wf = lstm_int_workspace_bytes(f, T, B), wb = lstm_int_workspace_bytes(b, T, B);
+  return ((wf > wb ? wf : wb) + 255) & ~(size_t)255;
+}
+
+size_t lstm_int_bidirectional_workspace_bytes(const lstm_int_model *f, const lstm_int_model *b, int32_t T, int32_t B) {
+  if (!f || !b || T < 0 || B < 0 || f->host.empty() || b->host.empty()) return 0;
+  const int Hm = std::max(f->host.back().H, b->host.back().H);
+  return bidi_stage_offset(f, b, T, B) + (((size_t)T * B * Hm + 255) & ~(size_t)255);
+}
+
+int lstm_int_forward_bidirectional(const lstm_int_model *f, const lstm_int_model *b, const int8_t *x, int32_t T,
+                                   int32_t B, int8_t *y, int8_t *h_state_fwd, int16_t *c_state_fwd,
+                                   int8_t *h_state_bwd, int16_t *c_state_bwd, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream) {
+  if (!f || !b || T < 0 || B < 0 || f->host.empty() || b->host.empty()) return LSTM_INT_E_INVALID_ARG;
+  // the two stacks read the same features: same width, same input quantization
+  if (f->host[0].I != b->host[0].I || f->host[0].s_x != b->host[0].s_x || f->host[0].zp_x != b->host[0].zp_x)
+    return LSTM_INT_E_INVALID_ARG;
+  if (f->reverse != 0 || b->reverse != 1) return LSTM_INT_E_INVALID_ARG;
+  if (f->device < 0 || f->device != b->device) return LSTM_INT_E_DEVICE;
+  if (T == 0 || B == 0) return LSTM_INT_OK;
+  if (!x || !y) return LSTM_INT_E_INVALID_ARG;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) ||
+      workspace_bytes < lstm_int_bidirectional_workspace_bytes(f, b, T, B))
+    return LSTM_INT_E_WORKSPACE;
+  const int Hf = f->host.back().H, Hb = b->host.back().H;
+  const size_t so = bidi_stage_offset(f, b, T, B);
+  int8_t *stage = reinterpret_cast<int8_t *>(workspace) + so;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  int rc = lstm_int_forward(f, x, T, B, stage, h_state_fwd, c_state_fwd, workspace, so, hip_stream, nullptr);
+  if (rc != LSTM_INT_OK) return rc;
+  launch_place_cols_i8(s, stage, y, Hf + Hb, (int64_t)T * B, Hf);
+  rc = lstm_int_forward(b, x, T, B, stage, h_state_bwd, c_state_bwd, workspace, so, hip_stream, nullptr);
+  if (rc != LSTM_INT_OK) return rc;
+  launch_place_cols_i8(s, stage, y + Hf, Hf + Hb, (int64_t)T * B, Hb);
+  return hipGetLastError() == hipSuccess ? LSTM_INT_OK : LSTM_INT_E_DEVICE;
+}
+
 int lstm_int_set_option(lstm_int_model *m, const char *key, int64_t value) {
   if (!m || !key) return LSTM_INT_E_INVALID_ARG;
   if (!strcmp(key, "path")) {

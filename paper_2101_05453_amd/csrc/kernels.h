@@ -58,6 +58,8 @@ void launch_cell(hipStream_t s, const CellArgs &a);
 // bytes cols..ld_dst-1 of dst are set to `fill`.
 void launch_copy_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *dst, int ld_dst,
                          int rows, int cols, int fill);
+// dst [rows, ld_dst] columns [0, cols) <- src [rows, cols] (dense); other columns of dst are left alone
+void launch_place_cols_i8(hipStream_t s, const int8_t *src, int8_t *dst, int ld_dst, int64_t rows, int cols);
 // dst [T*B, ld_dst] row (t, b) <- src row (T - 1 - t, b), first cols bytes; `fill` for the rest
 void launch_flip_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *dst, int ld_dst, int T, int B,
                          int cols, int fill);

@@ -358,6 +358,15 @@ __global__ void copy_rows_i8_kernel(const int8_t *src, int ld_src, int8_t *dst, 
   }
 }
 
+// dst [rows, ld_dst] columns [0, cols) <- src [rows, cols]; the other columns of dst stay as they are
+__global__ void place_cols_i8_kernel(const int8_t *src, int8_t *dst, int ld_dst, int64_t rows, int cols) {
+  const int64_t total = rows * cols;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = i / cols;
+    dst[r * ld_dst + (i - r * cols)] = src[i];
+  }
+}
+
 // dst row (t, b) <- src row (T - 1 - t, b): the time flip at the two ends of a reverse run
 __global__ void flip_rows_i8_kernel(const int8_t *src, int ld_src, int8_t *dst, int ld_dst, int T, int B, int cols,
                                     int fill) {
@@ -380,6 +389,11 @@ void launch_copy_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *d
   if (rows <= 0) return;
   hipLaunchKernelGGL(copy_rows_i8_kernel, dim3(grid_for((int64_t)rows * ld_dst)), dim3(256), 0, s,
                      src, ld_src, dst, ld_dst, rows, cols, 0, fill);
+}
+
+void launch_place_cols_i8(hipStream_t s, const int8_t *src, int8_t *dst, int ld_dst, int64_t rows, int cols) {
+  if (rows <= 0 || cols <= 0) return;
+  hipLaunchKernelGGL(place_cols_i8_kernel, dim3(grid_for(rows * cols)), dim3(256), 0, s, src, dst, ld_dst, rows, cols);
 }
 
 void launch_flip_rows_i8(hipStream_t s, const int8_t *src, int ld_src, int8_t *dst, int ld_dst, int T, int B,
