@@ -42,8 +42,13 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(
   constexpr int XCH = BM * 4, WCH = BN * 4;  // 16-byte chunks per k-tile
   constexpr int XPT = (XCH + 255) / 256, WPT = (WCH + 255) / 256;
 
-  __shared__ __attribute__((aligned(16))) int8_t Xs[BM * kLdsRow];
-  __shared__ __attribute__((aligned(16))) int8_t Ws[BN * kLdsRow];
+  // operand tiles during the k loop; afterwards (int16 output) each wave's TM x TN results, staged so that
+  // the stores cover whole 16-byte pieces of consecutive columns
+  constexpr int kStageRow = TN + 8;  // int16 elements; the pad keeps the 8-byte writes off each other's banks
+  constexpr int kOperandBytes = (BM + BN) * kLdsRow;
+  constexpr int kStageBytes = OUT8 ? 0 : 4 * TM * kStageRow * 2;
+  __shared__ __attribute__((aligned(16))) int8_t lds_buf[kOperandBytes > kStageBytes ? kOperandBytes : kStageBytes];
+  int8_t *Xs = lds_buf, *Ws = lds_buf + BM * kLdsRow;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -117,6 +122,11 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(
 
   // epilogue: + bias, rescale, saturate, store
   const int cpg = rq.cols_per_gate;
+  // int16 output with rows of whole 16-byte pieces: through LDS, so that a wave instruction stores 128 consecutive
+  // bytes of each of 8 rows (straight from the MFMA layout it is 32 bytes of each of 16 rows, and the memory
+  // system wrote several times the output)
+  const bool staged = !OUT8 && (ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
+  int16_t *stage = reinterpret_cast<int16_t *>(lds_buf) + wave * TM * kStageRow;
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) {
     const int n0 = col_base + wn * TN + ni * 16 + ((lane >> 4) << 2);
@@ -152,6 +162,13 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(
             if (out2) out2[(size_t)m * ldc2 + n0 + j] = q;
           }
         }
+      } else if (staged) {
+        short4 pk;
+        pk.x = (short)sat16(v[0]);
+        pk.y = (short)sat16(v[1]);
+        pk.z = (short)sat16(v[2]);
+        pk.w = (short)sat16(v[3]);
+        *reinterpret_cast<short4 *>(stage + (mi * 16 + (lane & 15)) * kStageRow + ni * 16 + ((lane >> 4) << 2)) = pk;
       } else {
         int16_t *o = reinterpret_cast<int16_t *>(out) + (size_t)m * ldc;
         if (n0 + 3 < ncols && (ldc & 3) == 0) {
@@ -165,6 +182,29 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             if (n0 + j < ncols) o[n0 + j] = (int16_t)sat16(v[j]);
+        }
+      }
+    }
+  }
+  if (!OUT8 && staged) {
+    // a wave reads back only what it wrote itself; LDS serves a wave's requests in order
+    constexpr int PPR = TN / 8;  // 16-byte pieces per row
+#pragma unroll
+    for (int i = 0; i < TM * PPR / 64; ++i) {
+      const int idx = i * 64 + lane;
+      const int r = idx / PPR, pc = idx - r * PPR;
+      const int m = row_base + wm * TM + r;
+      const int n = col_base + wn * TN + pc * 8;
+      const int4 piece = *reinterpret_cast<const int4 *>(stage + r * kStageRow + pc * 8);
+      if (m < M) {
+        int16_t *o = reinterpret_cast<int16_t *>(out) + (size_t)m * ldc + n;
+        if (n + 7 < ncols) {
+          *reinterpret_cast<int4 *>(o) = piece;
+        } else {
+          const int16_t e[8] = {(int16_t)piece.x, (int16_t)(piece.x >> 16), (int16_t)piece.y, (int16_t)(piece.y >> 16),
+                                (int16_t)piece.z, (int16_t)(piece.z >> 16), (int16_t)piece.w, (int16_t)(piece.w >> 16)};
+          for (int j = 0; j < 8; ++j)
+            if (n + j < ncols) o[j] = e[j];
         }
       }
     }
