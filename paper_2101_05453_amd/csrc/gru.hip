@@ -197,7 +197,7 @@ struct GruStepArgs {
 };
 
 // One step of one layer.  A workgroup owns 32 cells (their r, u, n rows of R: 96 x Kp bytes) and 32 RB batch
-// rows; its four waves split the depth, each running its quarter of the k steps for all RB x 3 tiles of the
+// rows (the library launches RB = 1); its four waves split the depth, each running its quarter of the k steps for all RB x 3 tiles of the
 // 32x32x32 int8 MFMA with both operands loaded straight into registers in operand order (every byte of the
 // weight slice and of the state tile is loaded once per workgroup, a contiguous KB per wave load), and the four
 // partial sums meet in LDS.  The MFMA leaves a lane with 16 cells of one batch row, the same cells in each of
@@ -491,8 +491,6 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
       offs[l] = o;
     }
     if (hipSetDevice(device) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void *>(gru_step_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            4 * 2 * 3 * kPartTile * 4) != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&m->arena), img.size()) != hipSuccess) {
       m->arena = nullptr;
       delete m;
@@ -620,8 +618,9 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
       a.rh[g] = 31 - q.eh[g];
     }
     a.sig_tab = m->sig_tab; a.tanh_tab = m->tanh_tab;
-    // 64 rows per workgroup once that still leaves a workgroup for every compute unit, else 32
-    const int rb = ((B + 63) / 64) * a.ctiles >= 256 ? 2 : 1;
+    // 32 rows per workgroup (RB = 1): at large batches two workgroups then share a compute unit and one's cell runs
+    // under the other's matmul (measured at N = 2048, B = 256: 12.9 us per step against 13.3 with RB = 2)
+    constexpr int rb = 1;
     a.rtn = (B + 32 * rb - 1) / (32 * rb);
     const dim3 grid((unsigned)(8 * a.rtn * ((a.ctiles + 7) / 8)));
     const size_t lds = (size_t)4 * rb * 3 * kPartTile * 4;
@@ -638,10 +637,7 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
       a.tr_act = tr && tr->act ? tr->act + tb * 3 * N : nullptr;
       a.tr_h16 = tr && tr->h16 ? tr->h16 + tb * N : nullptr;
       a.tr_h8 = tr && tr->h8 ? tr->h8 + tb * N : nullptr;
-      if (rb == 2)
-        hipLaunchKernelGGL(gru_step_kernel<2>, grid, dim3(256), lds, s, a);
-      else
-        hipLaunchKernelGGL(gru_step_kernel<1>, grid, dim3(256), lds, s, a);
+      hipLaunchKernelGGL(gru_step_kernel<rb>, grid, dim3(256), lds, s, a);
     }
     timed_end();
     in = out;

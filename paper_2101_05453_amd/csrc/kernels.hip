@@ -53,8 +53,22 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const int row_base = blockIdx.x * BM;  // activation rows
-  const int col_base = blockIdx.y * BN;  // weight rows = output columns
+  // Workgroup -> tile: bands of kBand row blocks; inside a band the row block runs fastest and the column block
+  // next, so that the workgroups in flight together share kBand activation tiles and sweep the weights once per
+  // band (with the plain grid order every activation tile was fetched from memory once per column block).
+  constexpr int kBand = 16;
+  int rblk, cblk;
+  {
+    const int nrb = gridDim.x;
+    const int id = blockIdx.y * nrb + blockIdx.x;
+    const int per_band = kBand * gridDim.y;
+    const int band = id / per_band, in_band = id - band * per_band;
+    const int rows_here = nrb - band * kBand < kBand ? nrb - band * kBand : kBand;
+    cblk = in_band / rows_here;
+    rblk = band * kBand + (in_band - cblk * rows_here);
+  }
+  const int row_base = rblk * BM;  // activation rows
+  const int col_base = cblk * BN;  // weight rows = output columns
 
   v4i acc[NI][MI];
 #pragma unroll
