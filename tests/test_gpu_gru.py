@@ -130,3 +130,38 @@ def test_empty_inputs_and_workspace_checks(gru):
         m.forward(xd, workspace=big[1:])  # misaligned
     assert e.value.code == binding.E_WORKSPACE
     torch.cuda.synchronize()
+
+
+def test_forward_captured_in_a_hip_graph(gru):
+    """gru_int_forward allocates nothing, never synchronizes and launches only kernels: a caller can capture a
+    whole multi-step call (two layers x eight steps = 20 kernel nodes) in a HIP graph.  Replays with new inputs and
+    carried state, with the program's own eager work and synchronization in between, give what the oracle gives."""
+    import torch
+
+    layers, x = wl.make_gru([40, 96], 96, 12, 24, seed=17, weight_param=0.15)
+    lib_m, orc_m = both(gru, layers)
+    xq = quantize_x(x, orc_m.get_quant(0))
+    T, B = 8, 12
+    xin = torch.from_numpy(np.ascontiguousarray(xq[:T])).cuda()
+    y = torch.empty((T, B, 96), dtype=torch.int8, device="cuda")
+    hs = torch.zeros(2 * B * 96, dtype=torch.int16, device="cuda")
+    ws = torch.empty(lib_m.workspace_bytes(T, B), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # one call outside the capture first
+        lib_m.forward(xin, y=y, h_state=hs, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lib_m.forward(xin, y=y, h_state=hs, workspace=ws)
+    for rep in range(2):
+        hs.zero_()
+        hs_o = np.zeros(2 * B * 96, dtype=np.int16)
+        for part in range(3):  # the 24 steps as three replays of the captured 8-step call
+            xin.copy_(torch.from_numpy(np.ascontiguousarray(xq[part * T:(part + 1) * T])))
+            graph.replay()
+            torch.cuda.synchronize()
+            want, _ = orc_m.forward(xq[part * T:(part + 1) * T], h_state=hs_o)
+            equal(f"gru_graph.rep{rep}.part{part}.y", y.cpu().numpy(), want)
+            equal(f"gru_graph.rep{rep}.part{part}.h", hs.cpu().numpy(), hs_o)
