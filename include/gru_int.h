@@ -115,9 +115,17 @@ size_t gru_int_workspace_bytes(const gru_int_model *model, int32_t T, int32_t B)
  *   workspace DEVICE, >= gru_int_workspace_bytes(model,T,B), 256-byte aligned
  *   hip_stream a hipStream_t (NULL = the default stream)
  *   trace    NULL, or dumps of one layer
- * Per layer: W x + bx over all T*B rows as one int8 MFMA matmul, then per step
- * one kernel for R h8 + bh of the three gates fused with the whole elementwise
- * cell.  Allocates nothing, never synchronizes the host, launches kernels only.
+ * Per layer: W x + bx over all T*B rows as one int8 MFMA matmul, then R h8 + bh
+ * of the three gates fused with the whole elementwise cell -- as ONE persistent
+ * launch for all T steps where the layer fits (N <= 1024, batches of up to
+ * 256 * (32 / ceil(N / 32)) rows, no trace of that layer: the recurrent weights
+ * stay in registers and the workgroups that share 32 batch rows meet at one
+ * barrier per step inside one XCD), else as one launch per step.  Allocates
+ * nothing, never synchronizes the host, launches kernels only.
+ * The persistent launch needs all its workgroups on the device at once (one
+ * per compute unit): nothing else may occupy the device for long while it
+ * runs; if that does not hold its bounded waits give up, the call's outputs
+ * are not valid and gru_int_device_status reports it.
  * T = 0 or B = 0 is a no-op.
  */
 int gru_int_forward(const gru_int_model *model, const int8_t *x, int32_t T, int32_t B, int8_t *y,
@@ -125,11 +133,30 @@ int gru_int_forward(const gru_int_model *model, const int8_t *x, int32_t T, int3
                     const gru_int_trace *trace);
 
 /*
+ * Options: "persistent" 1 (default) / 0 = never the one-launch form;
+ * "spin_limit" = polls after which a wait inside the persistent kernel gives
+ * up; "sync_sleep" = pause before the first poll of a barrier, in units of 64
+ * clocks; "barrier_never_completes" 1 = test hook: every barrier waits for an
+ * arrival that never comes (keep spin_limit small); "reset_status" clears the
+ * status word (synchronizes the device).  Results never depend on the tuning
+ * options.  Unknown keys or values give LSTM_INT_E_INVALID_ARG.
+ */
+int gru_int_set_option(gru_int_model *model, const char *key, int64_t value);
+
+/*
+ * Blocking read of the model's device status word: 0 = every persistent launch
+ * so far ran to completion; 1 = a wait gave up; 2 = the workgroups of a group
+ * were not placed on one XCD; nonzero means the outputs of that call are not
+ * valid.  The word is sticky.  Synchronizes the device.
+ */
+int gru_int_device_status(const gru_int_model *model, int32_t *status);
+
+/*
  * Device time of the forward calls made while profiling is on, measured with
  * HIP events on the stream the kernels run on, per kernel class: the hoisted
- * input matmul (one launch per layer and call) and the fused step kernel (T
- * launches per layer and call, timed as one stretch, so the figure includes
- * the gaps between consecutive launches).  gru_int_profile_begin resets the
+ * input matmul (one launch per layer and call) and the recurrent part (the T
+ * steps of a layer timed as one stretch -- T launches with their gaps, or the
+ * one persistent launch -- and counted as T).  gru_int_profile_begin resets the
  * record; gru_int_profile_end waits for the recorded work, fills launches[k]
  * and total_ms[k] and destroys the events.  Profiling adds host work to
  * forward and is not meant for calls under graph capture.

@@ -460,6 +460,10 @@ def gru_lib():
         L.gru_int_forward.restype = C.c_int
         L.gru_int_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(GruTrace)]
+        L.gru_int_set_option.restype = C.c_int
+        L.gru_int_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
+        L.gru_int_device_status.restype = C.c_int
+        L.gru_int_device_status.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         L.gru_int_profile_begin.restype = C.c_int
         L.gru_int_profile_begin.argtypes = [C.c_void_p]
         L.gru_int_profile_end.restype = C.c_int
@@ -521,6 +525,16 @@ class GruModel:
     # gru_int_workspace_bytes
     def workspace_bytes(self, T, B):
         return gru_lib().gru_int_workspace_bytes(self._h, T, B)
+
+    # gru_int_set_option
+    def set_option(self, key, value):
+        _check(gru_lib().gru_int_set_option(self._h, key.encode(), value), "gru_int_set_option")
+
+    # gru_int_device_status
+    def device_status(self):
+        v = C.c_int32()
+        _check(gru_lib().gru_int_device_status(self._h, C.byref(v)), "gru_int_device_status")
+        return v.value
 
     # gru_int_profile_begin / gru_int_profile_end
     def profile_begin(self):

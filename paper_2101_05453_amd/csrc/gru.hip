@@ -164,9 +164,11 @@ __host__ __device__ __forceinline__ size_t hop_offset(int row, int k, int KS32) 
 }
 
 // Start of a layer: the working state (caller's h_state slice or zeros) is used in place; its int8 form
-// goes to the operand-ordered buffer hop0 (columns N..Kp-1 zero).
-__global__ void gru_init_kernel(int16_t *h16, int B, int N, int Kp, int8_t *hop0, int zero_state) {
+// goes to the operand-ordered buffer hop0 (columns N..Kp-1 zero); sync_vec 16-byte words at sync are cleared.
+__global__ void gru_init_kernel(int16_t *h16, int B, int N, int Kp, int8_t *hop0, int zero_state, int4 *sync,
+                                int sync_vec) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < sync_vec) sync[i] = int4{0, 0, 0, 0};  // counters and placement words of the persistent kernel
   if (i >= (int64_t)B * Kp) return;
   const int b = (int)(i / Kp), k = (int)(i - (int64_t)b * Kp);
   int32_t v = 0;
@@ -372,6 +374,217 @@ __global__ __launch_bounds__(256) void gru_step_kernel(GruStepArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Persistent form of the step kernel: one launch runs all T steps of a layer.
+// ---------------------------------------------------------------------------
+// Wait of one workgroup for the other members of its group (the workgroups that share 32 batch rows), at the end of
+// every step: every wave first waits for its own stores, thread 0 adds one to the group's counter and polls it
+// (relaxed agent-scope atomics; the members of a group run on one XCD and meet in its L2).  Gives up after
+// spin_limit polls or when another workgroup has: the status word becomes 1 and every workgroup leaves the kernel.
+__device__ __forceinline__ bool gru_group_sync(unsigned *counter, unsigned &epoch, int GS, int *status, int spin_limit,
+                                               int first_sleep, int *lds_flag) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (GS == 1) return true;
+  epoch += (unsigned)GS;
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int i = 0; i < first_sleep; ++i) __builtin_amdgcn_s_sleep(1);  // a poll before the arrivals have landed only delays them
+    int budget = spin_limit;
+    for (;;) {
+      const unsigned c = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((int)(c - epoch) >= 0) break;
+      --budget;
+      if ((budget & 15) == 0 &&
+          (budget <= 0 || __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+        __hip_atomic_store(status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lds_flag[0] = 0;
+        break;
+      }
+    }
+  }
+  __syncthreads();
+  return lds_flag[0] != 0;
+}
+
+struct GruSeqArgs {
+  int32_t B, N, Kp, KS32, T;
+  int32_t GS, groups;         // workgroups per group (= tiles of 32 cells); groups of 32 batch rows
+  const int8_t *hop0;         // state before step 0, operand order
+  int8_t *hop_seq;            // [T][row blocks][KS32][64 lanes][16 B]: the state after every step, operand order; the
+                              // exchange buffer of the launch, every line written once and never read before that
+  size_t hop_step;            // bytes of one step of hop_seq
+  const int8_t *Rop;          // [GS][3][KS32][64 lanes][16 B]
+  const int32_t *bh;          // [3][32 GS]
+  const int16_t *tx;          // [T][B][3N]
+  int16_t *h16;               // [B][N]: read before step 0, written after step T - 1
+  int8_t *h8_seq;             // [T][B][Kp] row-major
+  int8_t *y;                  // [T][B][N] or NULL
+  int32_t Mh[3], rh[3];
+  const uint16_t *sig_tab, *tanh_tab;
+  unsigned *counters;         // [groups][64], zero at launch
+  unsigned long long *tickets;  // [8][32], zero at launch: placement check
+  int *status;
+  int32_t spin_limit, sync_sleep;
+  int32_t extra_arrivals;     // test hook: every barrier waits for this many arrivals more than will come
+};
+
+constexpr int kSeqMaxPer = 8;  // k steps per wave: depth up to 4 x 8 x 32 = 1024
+
+// The step kernel's work with the weights kept in registers over the whole sequence: the workgroups that share 32
+// batch rows -- one per tile of 32 cells -- form a group on ONE XCD; each keeps its 96 x Kp bytes of R as MFMA
+// operands (wave w the k steps of its quarter of the depth: at most 96 registers), its threads' share of the state in
+// registers, and per step loads only the int8 state of the group (operand order, one KB per k step, the KB of k step j
+// written by member j), runs the matmul and the cell as gru_step_kernel does, publishes its 32 cells of the new state
+// and meets the group at one barrier.  A GRU step needs this one exchange (the LSTM with layer norm and projection
+// needs three).  Placement: the XCD is read from the XCC_ID register and the place there is w / 8 (the hardware deals
+// consecutive workgroups out to the XCDs in turn); every workgroup records its place when it is done and a place taken
+// twice or not at all raises the status word (2), as in the LSTM's recurrent kernel.  All workgroups must be resident
+// at once (one per compute unit, launched on an otherwise idle stream); if they are not, the bounded waits end the
+// kernel with status 1.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gru_seq_kernel(GruSeqArgs a) {
+  __shared__ __attribute__((aligned(16))) int32_t part[4 * 3 * kPartTile];
+  __shared__ int flag[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, b2 = lane >> 5;
+  const int wg = blockIdx.x;
+  const int xcc = (int)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7);  // XCC_ID, bits 3:0
+  const int slot = wg >> 3, GS = a.GS;
+  auto placement_check = [&]() {
+    if (tid == 0) {
+      const unsigned places = gridDim.x >> 3;  // at most 32
+      const unsigned long long mine = (1ull << 32) + (1ull << (wg >> 3));
+      const unsigned long long now =
+          __hip_atomic_fetch_add(&a.tickets[xcc * 32], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+      const unsigned count = (unsigned)(now >> 32);
+      const unsigned all = places >= 32 ? 0xFFFFFFFFu : (1u << places) - 1;
+      if (count > places || (count == places && (unsigned)now != all))
+        __hip_atomic_store(a.status, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  };
+  const int group = xcc + 8 * (slot / GS), ct = slot % GS;
+  if (group >= a.groups) {  // no rows for this workgroup
+    placement_check();
+    return;
+  }
+  const int KS = a.KS32;
+  const int per = (KS + 3) >> 2;
+  const int k0 = wave * per, k1 = k0 + per < KS ? k0 + per : KS;
+
+  // ---- once: the wave's share of the weights -> registers (k steps past its share hold zeros)
+  v4i Wr[3][kSeqMaxPer];
+  {
+    const v4i *wp = reinterpret_cast<const v4i *>(a.Rop) + (size_t)ct * 3 * KS * 64 + lane;
+#pragma unroll
+    for (int g = 0; g < 3; ++g)
+#pragma unroll
+      for (int u = 0; u < kSeqMaxPer; ++u) {
+        Wr[g][u] = k0 + u < k1 ? wp[((size_t)g * KS + k0 + u) * 64] : v4i{0, 0, 0, 0};
+      }
+  }
+  // this thread's share of the cell: row rsub of the group, cells 4 cg .. 4 cg + 3 of the tile
+  const int rsub = tid >> 3, cg = tid & 7;
+  const int N = a.N;
+  const int n0 = ct * 32 + 4 * cg;
+  const int row = group * 32 + rsub;
+  const bool row_ok = row < a.B;
+  const int rowc = row_ok ? row : a.B - 1;
+  const bool vec = (N & 3) == 0;
+  int32_t bhe[3][4], h16r[4];
+#pragma unroll
+  for (int g = 0; g < 3; ++g) {
+    const int4 b4 = *reinterpret_cast<const int4 *>(a.bh + g * 32 * GS + n0);
+    bhe[g][0] = b4.x; bhe[g][1] = b4.y; bhe[g][2] = b4.z; bhe[g][3] = b4.w;
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) h16r[c] = n0 + c < N ? a.h16[(size_t)rowc * N + n0 + c] : 0;
+  if (tid == 0) flag[0] = 1;
+  __syncthreads();
+
+  unsigned epoch = 0;
+  unsigned *counter = a.counters + group * 64;
+  const size_t hop_blk = (size_t)group * KS * 64;  // this group's row block, in 16-byte units
+  for (int t = 0; t < a.T; ++t) {
+    // W x terms of this thread's cells: from memory, not needed before the matmul is done
+    int32_t txe[3][4];
+    {
+      const int16_t *txp = a.tx + ((size_t)t * a.B + rowc) * 3 * N + n0;
+      if (vec && n0 < N) {
+#pragma unroll
+        for (int g = 0; g < 3; ++g) {
+          const short4 t4 = *reinterpret_cast<const short4 *>(txp + (size_t)g * N);
+          txe[g][0] = t4.x; txe[g][1] = t4.y; txe[g][2] = t4.z; txe[g][3] = t4.w;
+        }
+      } else {
+#pragma unroll
+        for (int g = 0; g < 3; ++g)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) txe[g][c] = n0 + c < N ? txp[(size_t)g * N + c] : 0;
+      }
+    }
+    // ---- R h8: the group's int8 state, the wave's k steps
+    const v4i *hp = reinterpret_cast<const v4i *>(t == 0 ? a.hop0 : a.hop_seq + (size_t)(t - 1) * a.hop_step) + hop_blk + lane;
+    v4i hf[kSeqMaxPer];
+#pragma unroll
+    for (int u = 0; u < kSeqMaxPer; ++u)  // k steps past the wave's share meet zero weights: re-read a step that exists
+      hf[u] = hp[(size_t)(k0 + u < k1 ? k0 + u : (k0 < KS ? k0 : 0)) * 64];
+    v16i acc[3];
+#pragma unroll
+    for (int g = 0; g < 3; ++g)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[g][v] = 0;
+#pragma unroll
+    for (int u = 0; u < kSeqMaxPer; ++u)
+#pragma unroll
+      for (int g = 0; g < 3; ++g) acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Wr[g][u], hf[u], acc[g], 0, 0, 0);
+#pragma unroll
+    for (int g = 0; g < 3; ++g)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) part[(wave * 3 + g) * kPartTile + (2 * v + b2) * 33 + col] = acc[g][v];
+    __syncthreads();
+
+    // ---- the cell (as in gru_step_kernel), state in registers
+    int32_t h84[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      int32_t th[3];
+#pragma unroll
+      for (int g = 0; g < 3; ++g) {
+        const int o = g * kPartTile + (2 * (4 * (cg >> 1) + c) + (cg & 1)) * 33 + rsub;
+        const int32_t sum = part[o] + part[o + 3 * kPartTile] + part[o + 6 * kPartTile] + part[o + 9 * kPartTile];
+        th[g] = sat16(rescale(sum + bhe[g][c], a.Mh[g], a.rh[g]));
+      }
+      const int32_t r = sigmoid_from_table(a.sig_tab, sat16(txe[0][c] + th[0]));
+      const int32_t u = sigmoid_from_table(a.sig_tab, sat16(txe[1][c] + th[1]));
+      const int32_t rn = (r * th[2] + 16384) >> 15;
+      const int32_t cand = tanh_from_table(a.tanh_tab, sat16(txe[2][c] + rn));
+      const int32_t hn = cell_update32(cifg_input_gate(u), cand, u, h16r[c], 0);
+      h16r[c] = n0 + c < N ? hn : 0;
+      h84[c] = n0 + c < N ? state_i8(hn) : 0;
+    }
+    if (row_ok && n0 < N) {
+      const uint32_t pk = (uint32_t)(h84[0] & 0xFF) | ((uint32_t)(h84[1] & 0xFF) << 8) | ((uint32_t)(h84[2] & 0xFF) << 16) |
+                          ((uint32_t)(h84[3] & 0xFF) << 24);
+      *reinterpret_cast<uint32_t *>(a.hop_seq + (size_t)t * a.hop_step + hop_offset(row, n0, KS)) = pk;
+      *reinterpret_cast<uint32_t *>(a.h8_seq + ((size_t)t * a.B + row) * a.Kp + n0) = pk;
+      if (a.y) {
+        int8_t *yd = a.y + ((size_t)t * a.B + row) * N + n0;
+        if (vec && !(reinterpret_cast<uintptr_t>(a.y) & 3))
+          *reinterpret_cast<uint32_t *>(yd) = pk;
+        else
+          for (int c = 0; c < 4 && n0 + c < N; ++c) yd[c] = (int8_t)h84[c];
+      }
+    }
+    // rows of the block past the batch are never written: their (garbage) state only ever feeds their own results
+    if (!gru_group_sync(counter, epoch, GS + a.extra_arrivals, a.status, a.spin_limit, a.sync_sleep, flag)) return;
+  }
+  if (row_ok)
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (n0 + c < N) a.h16[(size_t)row * N + n0 + c] = (int16_t)h16r[c];
+  placement_check();
+}
+
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 }  // namespace
@@ -389,6 +602,11 @@ struct gru_int_model {
   int device = -1;
   bool profiling = false;
   std::vector<GruTimed> timed;
+  int persistent = 1;   // layers that fit run all their steps in one launch of gru_seq_kernel
+  int spin_limit = 1 << 21, sync_sleep = 12;
+  int extra_arrivals = 0;  // test hook (option "barrier_never_completes")
+  int *status = nullptr;  // device word: nonzero once a wait inside gru_seq_kernel gave up (1) or placement failed (2)
+  int num_cus = 0;
   std::vector<GruLayerHost> host;
   std::vector<GruLayerDev> dev;
   uint8_t *arena = nullptr;
@@ -398,8 +616,10 @@ struct gru_int_model {
 namespace {
 
 // carve-up of the workspace for (T, B)
+constexpr size_t kGruSyncBytes = 256 * 64 * 4;  // group counters [256][64 words]; the placement words lie inside
+
 struct GruWs {
-  size_t xpad, tx, out[2], hop[2], h16, total;
+  size_t xpad, tx, out[2], hop[2], h16, sync, hop_seq, total;
 };
 GruWs gru_workspace(const gru_int_model *m, int64_t T, int64_t B) {
   GruWs w{};
@@ -419,6 +639,8 @@ GruWs gru_workspace(const gru_int_model *m, int64_t T, int64_t B) {
   w.hop[0] = off; off += align256(max_hop);
   w.hop[1] = off; off += align256(max_hop);
   w.h16 = off; off += align256(sum_h16);
+  w.sync = off; off += kGruSyncBytes;
+  w.hop_seq = off; off += align256(max_hop * (size_t)T);  // the persistent kernel's exchange buffer: one copy per step
   w.total = off;
   return w;
 }
@@ -458,7 +680,7 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
       img.resize(off + bytes, 0);
       return off;
     };
-    const size_t o_sig = reserve(kTab * 2), o_tanh = reserve(kTab * 2);
+    const size_t o_sig = reserve(kTab * 2), o_tanh = reserve(kTab * 2), o_status = reserve(256);
     fill_sigmoid_table(3, reinterpret_cast<uint16_t *>(img.data() + o_sig));
     fill_tanh_table(3, reinterpret_cast<uint16_t *>(img.data() + o_tanh));
     struct Off { size_t W, bx, R, bh; };
@@ -500,6 +722,11 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
       (void)hipFree(m->arena);
       delete m;
       return LSTM_INT_E_DEVICE;
+    }
+    m->status = reinterpret_cast<int *>(m->arena + o_status);
+    {
+      hipDeviceProp_t prop;
+      m->num_cus = hipGetDeviceProperties(&prop, device) == hipSuccess ? prop.multiProcessorCount : 0;
     }
     m->sig_tab = reinterpret_cast<const uint16_t *>(m->arena + o_sig);
     m->tanh_tab = reinterpret_cast<const uint16_t *>(m->arena + o_tanh);
@@ -604,11 +831,42 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
     launch_gemm_i16(s, in, ld_in, (int)TB, dv.W, d.Ip, 3 * N, dv.bx, rq, tx, 3 * N);
     timed_end();
 
+    // One launch for all steps (gru_seq_kernel) where the layer fits: depth up to 1024 in registers, one workgroup
+    // per tile of 32 cells and group of 32 rows, a group inside one XCD of 32 compute units, all groups resident.
+    const int ctiles = d.Ncp / 32;
+    const int groups = (B + 31) / 32;
+    const bool seq = m->persistent && !tr && m->num_cus == 256 && d.Kp <= 128 * kSeqMaxPer && ctiles <= 32 &&
+                     groups <= 8 * (32 / ctiles) && T < (1 << 20);
     {
       const int64_t n = (int64_t)B * d.Kp;  // the state before step 0 goes where step "-1" would have put it
-      hipLaunchKernelGGL(gru_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, h16, B, N, d.Kp, hop[1],
-                         h_state ? 0 : 1);
+      const int sync_vec = seq ? (int)(kGruSyncBytes / 16) : 0;
+      const int64_t work = std::max<int64_t>(n, sync_vec);
+      hipLaunchKernelGGL(gru_init_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, h16, B, N, d.Kp, hop[1],
+                         h_state ? 0 : 1, reinterpret_cast<int4 *>(ws + w.sync), sync_vec);
     }
+    if (seq) {
+      GruSeqArgs q2{};
+      q2.B = B; q2.N = N; q2.Kp = d.Kp; q2.KS32 = d.Kp / 32; q2.T = T;
+      q2.GS = ctiles; q2.groups = groups;
+      q2.hop0 = hop[1];
+      q2.hop_seq = reinterpret_cast<int8_t *>(ws + w.hop_seq);
+      q2.hop_step = hop_bytes(B, d.Kp);
+      q2.Rop = dv.Rop; q2.bh = dv.bh; q2.tx = tx; q2.h16 = h16; q2.h8_seq = out;
+      q2.y = l == L - 1 ? y : nullptr;
+      for (int g = 0; g < 3; ++g) {
+        q2.Mh[g] = q.Mh[g];
+        q2.rh[g] = 31 - q.eh[g];
+      }
+      q2.sig_tab = m->sig_tab; q2.tanh_tab = m->tanh_tab;
+      q2.counters = reinterpret_cast<unsigned *>(ws + w.sync);
+      q2.tickets = reinterpret_cast<unsigned long long *>(q2.counters + 2);
+      q2.status = m->status;
+      q2.spin_limit = m->spin_limit; q2.sync_sleep = m->sync_sleep;
+      q2.extra_arrivals = m->extra_arrivals;
+      timed_begin(GRU_INT_K_STEP, T);
+      hipLaunchKernelGGL(gru_seq_kernel, dim3((unsigned)(8 * ctiles * ((groups + 7) / 8))), dim3(256), 0, s, q2);
+      timed_end();
+    } else {
     GruStepArgs a{};
     a.B = B; a.N = N; a.Kp = d.Kp; a.KS32 = d.Kp / 32;
     a.ctiles = d.Ncp / 32;
@@ -640,11 +898,56 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
       hipLaunchKernelGGL(gru_step_kernel<rb>, grid, dim3(256), lds, s, a);
     }
     timed_end();
+    }
     in = out;
     ld_in = d.Kp;
     h_off += (size_t)B * N;
   }
   return hipGetLastError() == hipSuccess ? LSTM_INT_OK : LSTM_INT_E_DEVICE;
+}
+
+int gru_int_set_option(gru_int_model *m, const char *key, int64_t value) {
+  if (!m || !key) return LSTM_INT_E_INVALID_ARG;
+  if (!strcmp(key, "persistent")) {
+    if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
+    m->persistent = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "spin_limit")) {
+    if (value < 1 || value > (1 << 30)) return LSTM_INT_E_INVALID_ARG;
+    m->spin_limit = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "sync_sleep")) {
+    if (value < 0 || value > 1024) return LSTM_INT_E_INVALID_ARG;
+    m->sync_sleep = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "barrier_never_completes")) {
+    if (value < 0 || value > 1) return LSTM_INT_E_INVALID_ARG;
+    m->extra_arrivals = (int)value;
+    return LSTM_INT_OK;
+  }
+  if (!strcmp(key, "reset_status")) {
+    if (m->device < 0) return LSTM_INT_E_DEVICE;
+    const int zero = 0;
+    if (hipSetDevice(m->device) != hipSuccess || hipDeviceSynchronize() != hipSuccess ||
+        hipMemcpy(m->status, &zero, sizeof(zero), hipMemcpyHostToDevice) != hipSuccess)
+      return LSTM_INT_E_DEVICE;
+    return LSTM_INT_OK;
+  }
+  return LSTM_INT_E_INVALID_ARG;
+}
+
+int gru_int_device_status(const gru_int_model *m, int32_t *status) {
+  if (!m || !status) return LSTM_INT_E_INVALID_ARG;
+  if (m->device < 0) return LSTM_INT_E_DEVICE;
+  int v = 0;
+  if (hipSetDevice(m->device) != hipSuccess || hipDeviceSynchronize() != hipSuccess ||
+      hipMemcpy(&v, m->status, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess)
+    return LSTM_INT_E_DEVICE;
+  *status = v;
+  return LSTM_INT_OK;
 }
 
 int gru_int_profile_begin(gru_int_model *m) {

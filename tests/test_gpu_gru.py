@@ -165,3 +165,86 @@ def test_forward_captured_in_a_hip_graph(gru):
             want, _ = orc_m.forward(xq[part * T:(part + 1) * T], h_state=hs_o)
             equal(f"gru_graph.rep{rep}.part{part}.y", y.cpu().numpy(), want)
             equal(f"gru_graph.rep{rep}.part{part}.h", hs.cpu().numpy(), hs_o)
+
+
+def run_both_paths(gru, layers, x, name, rows=None, splits=None):
+    """Untraced forward with carried state on the persistent launch (default) and with option "persistent" = 0 (one
+    launch per step): both against the oracle, device status 0."""
+    import torch
+
+    lib_m, orc_m = both(gru, layers)
+    xq = quantize_x(x, orc_m.get_quant(0))
+    T, B, _ = xq.shape
+    sel = np.arange(B) if rows is None else np.asarray(rows)
+    Ntot = sum(s.num_cells for s in layers)
+    xd = torch.from_numpy(xq).cuda()
+    hs_o = np.zeros(len(sel) * Ntot, dtype=np.int16)
+    want, _ = orc_m.forward(xq[:, sel], h_state=hs_o, threads=8)
+    for persistent in (1, 0):
+        lib_m.set_option("persistent", persistent)
+        hs = torch.zeros(B * Ntot, dtype=torch.int16, device="cuda")
+        parts = []
+        for a, b in (splits or [(0, T)]):
+            parts.append(lib_m.forward(xd[a:b].contiguous(), h_state=hs).cpu().numpy())
+        torch.cuda.synchronize()
+        assert lib_m.device_status() == 0
+        equal(f"{name}.p{persistent}.y", np.concatenate(parts)[:, sel], want)
+        off_g = off_o = 0
+        for s in layers:
+            n = s.num_cells
+            equal(f"{name}.p{persistent}.h_state", hs.cpu().numpy()[off_g:off_g + B * n].reshape(B, n)[sel],
+                  hs_o[off_o:off_o + len(sel) * n].reshape(len(sel), n))
+            off_g += B * n
+            off_o += len(sel) * n
+    return lib_m
+
+
+@pytest.mark.parametrize("case", [
+    ([24], 40, 3, 6, 0.2),            # two cell tiles, the second ragged
+    ([64], 32, 16, 5, 0.2),           # a group of one workgroup
+    ([17, 37, 37], 37, 5, 7, 0.3),    # N not a multiple of 4, three layers
+    ([32, 128], 128, 33, 9, 0.1),     # two groups of rows, the second with one row
+    ([100], 200, 1, 12, 0.15),        # a single row
+    ([48, 96], 96, 70, 40, 0.12),     # three groups, 40 steps
+])
+def test_persistent_launch_small_shapes(gru, case):
+    inputs, N, B, T, wp = case
+    layers, x = wl.make_gru(inputs, N, B, T, seed=23, weight_param=wp, input_param=1.5)
+    run_both_paths(gru, layers, x, f"gru_seq{inputs}x{N}", splits=[(0, 1), (1, T)] if T > 6 else None)
+
+
+def test_persistent_launch_full_chip_and_beyond(gru):
+    """N = 1024 at B = 256: 8 groups x 32 workgroups = every compute unit; N = 512 at B = 300: 10 groups of 16
+    workgroups; N = 1024 at B = 288 does not fit one launch and runs one launch per step."""
+    layers, x = wl.make_gru([256, 1024], 1024, 256, 10, seed=6, weight_param=0.04)
+    run_both_paths(gru, layers, x, "gru_seq1024", rows=[0, 31, 32, 100, 127, 128, 200, 224, 255])
+    layers, x = wl.make_gru([128], 512, 300, 8, seed=7, weight_param=0.05)
+    run_both_paths(gru, layers, x, "gru_seq512", rows=[0, 15, 31, 32, 159, 160, 287, 288, 299])
+    layers, x = wl.make_gru([64], 1024, 288, 4, seed=8, weight_param=0.04)
+    run_both_paths(gru, layers, x, "gru_1024_b288", rows=[0, 100, 255, 256, 287])
+
+
+def test_persistent_wait_gives_up_and_model_recovers(gru):
+    """The kernel's waits are bounded: with the test hook every barrier waits for an arrival that never comes, each
+    wait ends at its (small) limit, the kernel exits normally and the status word says so; after a reset the same
+    model computes the right result.  (That the status becomes 1 also shows that the persistent launch ran.)"""
+    import torch
+
+    layers, x = wl.make_gru([32], 96, 40, 5, seed=9, weight_param=0.2)
+    lib_m, orc_m = both(gru, layers)
+    xq = quantize_x(x, orc_m.get_quant(0))
+    xd = torch.from_numpy(xq).cuda()
+    lib_m.set_option("spin_limit", 64)
+    lib_m.set_option("barrier_never_completes", 1)
+    lib_m.forward(xd)
+    torch.cuda.synchronize()
+    assert lib_m.device_status() == 1
+    lib_m.set_option("barrier_never_completes", 0)
+    lib_m.set_option("spin_limit", 1 << 21)
+    lib_m.set_option("reset_status", 1)
+    assert lib_m.device_status() == 0
+    y = lib_m.forward(xd)
+    torch.cuda.synchronize()
+    want, _ = orc_m.forward(xq, threads=8)
+    assert lib_m.device_status() == 0
+    equal("gru_recovered.y", y.cpu().numpy(), want)

@@ -19,8 +19,8 @@ def test_library_exports_every_declared_gru_symbol():
     text = open(os.path.join(ROOT, "include", "gru_int.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(gru_int_[a-z_]+)\s*\(", text)))
-    assert names == ["gru_int_destroy", "gru_int_forward", "gru_int_get_quant", "gru_int_prepare",
-                     "gru_int_profile_begin", "gru_int_profile_end", "gru_int_workspace_bytes"]
+    assert names == ["gru_int_destroy", "gru_int_device_status", "gru_int_forward", "gru_int_get_quant", "gru_int_prepare",
+                     "gru_int_profile_begin", "gru_int_profile_end", "gru_int_set_option", "gru_int_workspace_bytes"]
     lib = binding.gru_lib()
     for n in names:
         assert hasattr(lib, n), n
