@@ -81,6 +81,9 @@ def bench_gru(args, np, torch, wl, binding):
     prof = model.profile_end()
     step_us = prof["step"]["total_ms"] / prof["step"]["launches"] * 1e3
     gemm_us = prof["input_gemm"]["total_ms"] / prof["input_gemm"]["launches"] * 1e3
+    # which form of the recurrent part the library runs for this shape (include/gru_int.h: gru_int_forward)
+    ctiles = (N + 31) // 32
+    persistent = ((N + 63) // 64) * 64 <= 1024 and ctiles <= 32 and (B + 31) // 32 <= 8 * (32 // ctiles)
     step_bytes = 3.0 * N * N + 2.0 * B * 3 * N + 4.0 * B * N + B * N + 3.0 * B * N
     gemm_ops = sum(2.0 * T * B * 3 * N * (I if l == 0 else N) for l in range(L)) / L
     out = {"metric": "gru_cell_steps_per_sec", "value": B * T * L / dt, "unit": "cell-steps/s", "n_gpus": 1,
@@ -88,7 +91,10 @@ def bench_gru(args, np, torch, wl, binding):
            "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
            "config": {"workload": f"integer GRU: L={L} I={I} N={N} B={B} T={T}", "cell_steps_per_step": B * T * L},
            "roofline": {"bound": "hbm", "achieved": step_bytes / step_us * 1e-3, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                        "frac": step_bytes / step_us * 1e-3 / PEAK_HBM_GBS, "kernel": "gru_step_kernel",
+                        "frac": step_bytes / step_us * 1e-3 / PEAK_HBM_GBS,
+                        "kernel": "gru_seq_kernel" if persistent else "gru_step_kernel",
+                        "path": "persistent: one launch per layer, avg_launch_us is its time per step" if persistent
+                        else "one launch per step",
                         "avg_launch_us": step_us, "traffic": None,
                         "kernels": {"input_gemm": {"avg_us": gemm_us, "tops": gemm_ops / gemm_us * 1e-6,
                                                    "frac_mfma": gemm_ops / gemm_us * 1e-6 / PEAK_INT8_TOPS}}}}
