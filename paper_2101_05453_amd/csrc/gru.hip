@@ -15,6 +15,11 @@
 //      (rescale, sigma/tanh tables, reset product, coupled update, the int8
 //      form of the new state) follows in the same kernel with one LDS
 //      reduction and no exchange between workgroups.
+//   3. where the layer fits (up to 1024 cells), steps 2 of all T steps as ONE
+//      persistent launch, gru_seq_kernel: weights in registers, one barrier
+//      per step among the workgroups of an XCD that share 32 batch rows; the
+//      input term then comes from the LSTM path's register-resident input GEMM
+//      (in_gemm.hip) in its tile order.
 // The state is read and written in place (each (row, cell) belongs to one
 // thread); its int8 form is written three times: in operand order for the
 // next step, row-major for the next layer's matmul, dense for the caller.
@@ -30,6 +35,7 @@
 #include "kernels.h"
 #include "lstm_int_math.h"
 #include "model.h"
+#include "persistent.h"
 
 namespace lstm_int {
 
@@ -62,6 +68,11 @@ struct GruLayerDev {
   const int32_t *bx = nullptr;    // [cols_pad] folded input bias
   const int8_t *Rop = nullptr;    // [Ncp/32][3][Kp/32][64 lanes][16 B]: operand order of the 32x32x32 MFMA
   const int32_t *bh = nullptr;    // [3][Ncp]
+  // input depth up to 1024: W once more as the register-resident input GEMM reads it (in_gemm.hip): tiles of 8 cells
+  // x 4 gate slots (slot 0 empty, slots 1-3 = r, u, n), row 8 slot + cell % 8, [tile][Ip/32][64 lanes][16 B]
+  const int8_t *W2f = nullptr;
+  const int32_t *bx2 = nullptr;   // [tiles][32]
+  int tiles = 0;                  // a multiple of 8 (cells padded to 64)
 };
 
 bool finite_all(const float *a, size_t n) {
@@ -416,7 +427,9 @@ struct GruSeqArgs {
   size_t hop_step;            // bytes of one step of hop_seq
   const int8_t *Rop;          // [GS][3][KS32][64 lanes][16 B]
   const int32_t *bh;          // [3][32 GS]
-  const int16_t *tx;          // [T][B][3N]
+  const int16_t *tx;          // [T][B][3N], or NULL:
+  const int4 *tx2;            // the input term in the input GEMM's tile order [(t Bp + b) / 32][tile of 8 cells][half][lane][8]
+  int32_t tiles, bp_blocks;   // of tx2: tiles of 8 cells per row block; row blocks per step (Bp / 32)
   int16_t *h16;               // [B][N]: read before step 0, written after step T - 1
   int8_t *h8_seq;             // [T][B][Kp] row-major
   int8_t *y;                  // [T][B][N] or NULL
@@ -507,7 +520,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   for (int t = 0; t < a.T; ++t) {
     // W x terms of this thread's cells: from memory, not needed before the matmul is done
     int32_t txe[3][4];
-    {
+    if (a.tx2) {
+      // tile order: lane (row % 32, half b2) of tile n / 8 holds value 4 slot + c for cell 8 (n / 8) + 4 b2 + c, values
+      // 0-7 in the first 16 bytes of the lane, 8-15 in the second
+      const int4 *tp = a.tx2 + (((size_t)t * a.bp_blocks + group) * a.tiles + (ct * 4 + (cg >> 1))) * 128 + ((cg & 1) << 5) + rsub;
+#pragma unroll
+      for (int g = 0; g < 3; ++g) {
+        const int slot = g + 1;
+        const short4 t4 = *reinterpret_cast<const short4 *>(reinterpret_cast<const int16_t *>(tp + (slot >> 1) * 64) + (slot & 1) * 4);
+        txe[g][0] = t4.x; txe[g][1] = t4.y; txe[g][2] = t4.z; txe[g][3] = t4.w;
+      }
+    } else {
       const int16_t *txp = a.tx + ((size_t)t * a.B + rowc) * 3 * N + n0;
       if (vec && n0 < N) {
 #pragma unroll
@@ -627,12 +650,14 @@ GruWs gru_workspace(const gru_int_model *m, int64_t T, int64_t B) {
   for (const GruLayerHost &q : m->host) {
     const GruDims d = gru_dims(q.I, q.N);
     max_tx = std::max(max_tx, (size_t)T * B * 3 * q.N * 2);
-    max_out = std::max(max_out, (size_t)T * B * d.Kp);
+    // the same terms in the register-resident input GEMM's tile order: rows padded to 32 per step, cells to 64, 4 gate slots
+    max_tx = std::max(max_tx, (size_t)T * ((B + 31) / 32 * 32) * ((q.N + 63) / 64 * 64) * 4 * 2);
+    max_out = std::max(max_out, ((size_t)T * B + 32) * d.Kp);  // 32 rows of slack: that GEMM reads whole blocks of 32 rows
     max_hop = std::max(max_hop, hop_bytes((int)B, d.Kp));
     sum_h16 = std::max(sum_h16, (size_t)B * q.N * 2);
   }
   const GruDims d0 = gru_dims(m->host[0].I, m->host[0].N);
-  w.xpad = off; off += align256((size_t)T * B * d0.Ip);
+  w.xpad = off; off += align256(((size_t)T * B + 32) * d0.Ip);
   w.tx = off; off += align256(max_tx);
   w.out[0] = off; off += align256(max_out);
   w.out[1] = off; off += align256(max_out);
@@ -683,7 +708,7 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
     const size_t o_sig = reserve(kTab * 2), o_tanh = reserve(kTab * 2), o_status = reserve(256);
     fill_sigmoid_table(3, reinterpret_cast<uint16_t *>(img.data() + o_sig));
     fill_tanh_table(3, reinterpret_cast<uint16_t *>(img.data() + o_tanh));
-    struct Off { size_t W, bx, R, bh; };
+    struct Off { size_t W, bx, R, bh, W2f, bx2; int tiles; };
     std::vector<Off> offs(num_layers);
     for (int l = 0; l < num_layers; ++l) {
       const GruLayerHost &q = m->host[l];
@@ -695,6 +720,21 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
       o.bx = reserve((size_t)d.cols_pad * 4);
       o.R = reserve((size_t)(d.Ncp / 32) * 3 * KS * 1024);
       o.bh = reserve((size_t)3 * d.Ncp * 4);
+      o.tiles = 0;
+      o.W2f = o.bx2 = 0;
+      if (d.Ip <= 1024) {
+        o.tiles = (N + 63) / 64 * 8;
+        o.W2f = reserve((size_t)o.tiles * 32 * d.Ip);
+        o.bx2 = reserve((size_t)o.tiles * 32 * 4);
+        for (int g = 0; g < 3; ++g)
+          for (int n = 0; n < N; ++n) {
+            const int tile = n / 8, rho = 8 * (g + 1) + n % 8;
+            const int8_t *w = q.Wq.data() + ((size_t)g * N + n) * I;
+            for (int k = 0; k < I; ++k)
+              img[o.W2f + ((((size_t)tile * (d.Ip / 32) + k / 32) * 64) + rho + 32 * ((k % 32) / 16)) * 16 + k % 16] = (uint8_t)w[k];
+            reinterpret_cast<int32_t *>(img.data() + o.bx2)[tile * 32 + rho] = q.bx_fold[g * N + n];
+          }
+      }
       for (int r = 0; r < 3 * N; ++r) std::memcpy(img.data() + o.W + (size_t)r * d.Ip, q.Wq.data() + (size_t)r * I, I);
       std::memcpy(img.data() + o.bx, q.bx_fold.data(), (size_t)3 * N * 4);
       // first operand of the 32x32x32 MFMA: lane (row = lane % 32, half = lane / 32) holds, for k step ks, bytes
@@ -712,7 +752,7 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
         std::memcpy(img.data() + o.bh + (size_t)g * d.Ncp * 4, q.bhq.data() + (size_t)g * N, (size_t)N * 4);
       offs[l] = o;
     }
-    if (hipSetDevice(device) != hipSuccess ||
+    if (hipSetDevice(device) != hipSuccess || in_gemm_init() != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&m->arena), img.size()) != hipSuccess) {
       m->arena = nullptr;
       delete m;
@@ -736,6 +776,11 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
       m->dev[l].bx = reinterpret_cast<const int32_t *>(m->arena + offs[l].bx);
       m->dev[l].Rop = reinterpret_cast<const int8_t *>(m->arena + offs[l].R);
       m->dev[l].bh = reinterpret_cast<const int32_t *>(m->arena + offs[l].bh);
+      if (offs[l].tiles) {
+        m->dev[l].W2f = reinterpret_cast<const int8_t *>(m->arena + offs[l].W2f);
+        m->dev[l].bx2 = reinterpret_cast<const int32_t *>(m->arena + offs[l].bx2);
+        m->dev[l].tiles = offs[l].tiles;
+      }
     }
   } catch (const std::bad_alloc &) {
     delete m;
@@ -786,7 +831,9 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
   {
     // the matmul reads rows of Ip bytes in 16-byte pieces: a padded copy unless x already has that shape
     const GruDims d0 = gru_dims(m->host[0].I, m->host[0].N);
-    if (d0.Ip != m->host[0].I || (reinterpret_cast<uintptr_t>(x) & 15)) {
+    // (or, for the input GEMM that reads whole blocks of 32 rows, unless the batch is a multiple of 32: the copy has
+    // 32 rows of slack behind it)
+    if (d0.Ip != m->host[0].I || (reinterpret_cast<uintptr_t>(x) & 15) || (B & 31)) {
       int8_t *xp = reinterpret_cast<int8_t *>(ws + w.xpad);
       launch_copy_rows_i8(s, x, m->host[0].I, xp, d0.Ip, (int)TB, m->host[0].I, 0);
       in = xp;
@@ -827,16 +874,30 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
     auto timed_end = [&]() {
       if (m->profiling && !mm->timed.empty()) (void)hipEventRecord(mm->timed.back().stop, s);
     };
-    timed_begin(GRU_INT_K_INPUT_GEMM, 1);
-    launch_gemm_i16(s, in, ld_in, (int)TB, dv.W, d.Ip, 3 * N, dv.bx, rq, tx, 3 * N);
-    timed_end();
-
     // One launch for all steps (gru_seq_kernel) where the layer fits: depth up to 1024 in registers, one workgroup
     // per tile of 32 cells and group of 32 rows, a group inside one XCD of 32 compute units, all groups resident.
     const int ctiles = d.Ncp / 32;
     const int groups = (B + 31) / 32;
     const bool seq = m->persistent && !tr && m->num_cus == 256 && d.Kp <= 128 * kSeqMaxPer && ctiles <= 32 &&
                      groups <= 8 * (32 / ctiles) && T < (1 << 20);
+    // The input term: for the persistent launch from the LSTM path's input GEMM (weights resident in registers, input
+    // depth up to 1024, output in its tile order, which gru_seq_kernel reads); else from the general matmul, row-major.
+    InGemmArgs ga{};
+    ga.A = in; ga.a_slack = 1; ga.lda = ld_in; ga.T = T; ga.B = B; ga.Bp = (B + 31) / 32 * 32;
+    ga.W2f = dv.W2f; ga.kpad = d.Ip; ga.tiles = dv.tiles; ga.bx2 = dv.bx2;
+    ga.M[0] = 1 << 30; ga.r[0] = 33;  // the empty gate slot
+    for (int g = 0; g < 3; ++g) {
+      ga.M[g + 1] = q.Mx[g];
+      ga.r[g + 1] = 31 - q.ex[g];
+    }
+    ga.tx2 = reinterpret_cast<int4 *>(ws + w.tx);
+    const bool ws_gemm = seq && dv.W2f && in_gemm_ws_supported(ga);
+    timed_begin(GRU_INT_K_INPUT_GEMM, 1);
+    if (ws_gemm)
+      launch_in_gemm_ws(s, ga, m->num_cus);
+    else
+      launch_gemm_i16(s, in, ld_in, (int)TB, dv.W, d.Ip, 3 * N, dv.bx, rq, tx, 3 * N);
+    timed_end();
     {
       const int64_t n = (int64_t)B * d.Kp;  // the state before step 0 goes where step "-1" would have put it
       const int sync_vec = seq ? (int)(kGruSyncBytes / 16) : 0;
@@ -851,7 +912,10 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
       q2.hop0 = hop[1];
       q2.hop_seq = reinterpret_cast<int8_t *>(ws + w.hop_seq);
       q2.hop_step = hop_bytes(B, d.Kp);
-      q2.Rop = dv.Rop; q2.bh = dv.bh; q2.tx = tx; q2.h16 = h16; q2.h8_seq = out;
+      q2.Rop = dv.Rop; q2.bh = dv.bh; q2.h16 = h16; q2.h8_seq = out;
+      q2.tx = ws_gemm ? nullptr : tx;
+      q2.tx2 = ws_gemm ? ga.tx2 : nullptr;
+      q2.tiles = dv.tiles; q2.bp_blocks = ga.Bp / 32;
       q2.y = l == L - 1 ? y : nullptr;
       for (int g = 0; g < 3; ++g) {
         q2.Mh[g] = q.Mh[g];
