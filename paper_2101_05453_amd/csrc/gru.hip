@@ -198,7 +198,9 @@ struct GruStepArgs {
   const int8_t *hop_prev;     // state before the step, operand order
   const int8_t *Rop;          // [ctiles][3][KS32][64 lanes][16 B]
   const int32_t *bh;          // [3][32 ctiles]
-  const int16_t *tx;          // [B][3N] of this step
+  const int16_t *tx;          // [B][3N] of this step, or NULL:
+  const int4 *tx2;            // this step's input terms in the input GEMM's tile order [row block][tile of 8 cells][half][lane][8]
+  int32_t tiles;              // tiles of 8 cells per row block of tx2
   int16_t *h16;               // [B][N] in/out
   int8_t *hop_out;            // state after the step, operand order
   int8_t *h8_out;             // [B][Kp] row-major (the next layer's matmul input)
@@ -244,23 +246,37 @@ __global__ __launch_bounds__(256) void gru_step_kernel(GruStepArgs a) {
   for (int rb = 0; rb < RB; ++rb) {
     rowe[rb] = (rt * RB + rb) * 32 + rsub;
     const int row = rowe[rb] < a.B ? rowe[rb] : a.B - 1;
-    const int16_t *txp = a.tx + (size_t)row * 3 * N + n0;
     const int16_t *hq = a.h16 + (size_t)row * N + n0;
     if (vec && n0 < N) {
-#pragma unroll
-      for (int g = 0; g < 3; ++g) {
-        const short4 t4 = *reinterpret_cast<const short4 *>(txp + (size_t)g * N);
-        txe[rb][g][0] = t4.x; txe[rb][g][1] = t4.y; txe[rb][g][2] = t4.z; txe[rb][g][3] = t4.w;
-      }
       const short4 h4 = *reinterpret_cast<const short4 *>(hq);
       h16e[rb][0] = h4.x; h16e[rb][1] = h4.y; h16e[rb][2] = h4.z; h16e[rb][3] = h4.w;
     } else {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bool in = n0 + c < N;
+      for (int c = 0; c < 4; ++c) h16e[rb][c] = n0 + c < N ? hq[c] : 0;
+    }
+    if (a.tx2) {
+      // the input term in the register-resident input GEMM's tile order (this step's row blocks): lane
+      // (row % 32, half) of tile n / 8 holds value 4 slot + c for cell 8 (n / 8) + 4 half + c; slots 1-3 = r, u, n
+      const int4 *tp = a.tx2 + ((size_t)(rt * RB + rb) * a.tiles + (ct * 4 + (cg >> 1))) * 128 + ((cg & 1) << 5) + rsub;
 #pragma unroll
-        for (int g = 0; g < 3; ++g) txe[rb][g][c] = in ? txp[(size_t)g * N + c] : 0;
-        h16e[rb][c] = in ? hq[c] : 0;
+      for (int g = 0; g < 3; ++g) {
+        const int slot = g + 1;
+        const short4 t4 = *reinterpret_cast<const short4 *>(reinterpret_cast<const int16_t *>(tp + (slot >> 1) * 64) + (slot & 1) * 4);
+        txe[rb][g][0] = t4.x; txe[rb][g][1] = t4.y; txe[rb][g][2] = t4.z; txe[rb][g][3] = t4.w;
+      }
+    } else {
+      const int16_t *txp = a.tx + (size_t)row * 3 * N + n0;
+      if (vec && n0 < N) {
+#pragma unroll
+        for (int g = 0; g < 3; ++g) {
+          const short4 t4 = *reinterpret_cast<const short4 *>(txp + (size_t)g * N);
+          txe[rb][g][0] = t4.x; txe[rb][g][1] = t4.y; txe[rb][g][2] = t4.z; txe[rb][g][3] = t4.w;
+        }
+      } else {
+#pragma unroll
+        for (int g = 0; g < 3; ++g)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) txe[rb][g][c] = n0 + c < N ? txp[(size_t)g * N + c] : 0;
       }
     }
   }
@@ -880,8 +896,9 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
     const int groups = (B + 31) / 32;
     const bool seq = m->persistent && !tr && m->num_cus == 256 && d.Kp <= 128 * kSeqMaxPer && ctiles <= 32 &&
                      groups <= 8 * (32 / ctiles) && T < (1 << 20);
-    // The input term: for the persistent launch from the LSTM path's input GEMM (weights resident in registers, input
-    // depth up to 1024, output in its tile order, which gru_seq_kernel reads); else from the general matmul, row-major.
+    // The input term: from the LSTM path's input GEMM where the input depth allows (weights resident in registers, depth
+    // up to 1024, output in its tile order, which both recurrent kernels read); else, and with a trace, from the
+    // general matmul, row-major.
     InGemmArgs ga{};
     ga.A = in; ga.a_slack = 1; ga.lda = ld_in; ga.T = T; ga.B = B; ga.Bp = (B + 31) / 32 * 32;
     ga.W2f = dv.W2f; ga.kpad = d.Ip; ga.tiles = dv.tiles; ga.bx2 = dv.bx2;
@@ -891,7 +908,9 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
       ga.r[g + 1] = 31 - q.ex[g];
     }
     ga.tx2 = reinterpret_cast<int4 *>(ws + w.tx);
-    const bool ws_gemm = seq && dv.W2f && in_gemm_ws_supported(ga);
+    // (on the launch-per-step path only where the matmul is large: the tile-ordered terms cost the step kernel
+    // 0.5 us per step, measured, which 8192 rows and more of a faster matmul pay for)
+    const bool ws_gemm = !tr && dv.W2f && m->num_cus == 256 && (seq || TB >= 8192) && in_gemm_ws_supported(ga);
     timed_begin(GRU_INT_K_INPUT_GEMM, 1);
     if (ws_gemm)
       launch_in_gemm_ws(s, ga, m->num_cus);
@@ -951,7 +970,9 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
       const size_t tb = (size_t)t * B;
       a.hop_prev = hop[(t + 1) & 1];
       a.hop_out = hop[t & 1];
-      a.tx = tx + tb * 3 * N;
+      a.tx = ws_gemm ? nullptr : tx + tb * 3 * N;
+      a.tx2 = ws_gemm ? ga.tx2 + (size_t)t * (ga.Bp / 32) * dv.tiles * 128 : nullptr;
+      a.tiles = dv.tiles;
       a.h8_out = out + tb * d.Kp;
       a.y = l == L - 1 ? y + tb * N : nullptr;
       a.tr_tx = tr && tr->tx ? tr->tx + tb * 3 * N : nullptr;

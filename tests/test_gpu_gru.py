@@ -248,3 +248,13 @@ def test_persistent_wait_gives_up_and_model_recovers(gru):
     want, _ = orc_m.forward(xq, threads=8)
     assert lib_m.device_status() == 0
     equal("gru_recovered.y", y.cpu().numpy(), want)
+
+
+def test_tile_ordered_input_terms_on_both_recurrent_kernels(gru):
+    """With 8192 and more (t, b) rows the launch-per-step path also takes its input terms from the register-resident
+    input GEMM in that kernel's tile order (the persistent launch always does): 512 rows x 16 steps, two layers, a
+    ragged variant with 515 rows."""
+    layers, x = wl.make_gru([64, 128], 128, 512, 16, seed=12, weight_param=0.15)
+    run_both_paths(gru, layers, x, "gru_tx2")
+    layers, x = wl.make_gru([40, 96], 96, 515, 16, seed=13, weight_param=0.15)
+    run_both_paths(gru, layers, x, "gru_tx2_ragged", splits=[(0, 5), (5, 16)])
