@@ -31,7 +31,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kLdsRow = 80;  // 64 data bytes + 16 pad: conflict-free b128 reads
 
 template <int BM, int BN, int WM, int WN, bool OUT8>
-__global__ __launch_bounds__(256) void gemm_i8_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM == 128 ? 3 : 1, BM == 128 ? 3 : 8))) void gemm_i8_kernel(
     const int8_t *__restrict__ A, int lda, int M, const int8_t *__restrict__ W, int kpad,
     int ncols, const int32_t *__restrict__ bias, Requant rq, void *__restrict__ out, int ldc,
     int8_t *__restrict__ out2, int ldc2) {
@@ -76,47 +76,48 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) acc[ni][mi] = v4i{0, 0, 0, 0};
 
-  int4 xreg[XPT], wreg[WPT];
+  // The next k-tile's chunks wait in named registers between their load and their LDS store.  (As arrays filled
+  // and drained by helper lambdas they were left in scratch memory in some builds: every chunk then went
+  // load -> scratch -> LDS, the loads no longer overlapped the MFMAs, and the kernel ran at half speed.)
+  static_assert(XPT <= 2 && WPT <= 2, "at most two chunks per thread and operand");
+  int4 x0 = {}, x1 = {}, w0 = {}, w1 = {};
   const int KT = kpad >> 6;
+  const int c0 = tid, c1 = tid + 256;
+  const int8_t *xsrc0, *xsrc1, *wsrc0, *wsrc1;
+  {
+    int r0 = row_base + (c0 >> 2), r1 = row_base + (c1 >> 2);
+    r0 = r0 < M ? r0 : M - 1;  // rows past the end repeat the last one; never stored
+    r1 = r1 < M ? r1 : M - 1;
+    xsrc0 = A + (size_t)r0 * lda + ((c0 & 3) << 4);
+    xsrc1 = A + (size_t)r1 * lda + ((c1 & 3) << 4);
+    wsrc0 = W + (size_t)(col_base + (c0 >> 2)) * kpad + ((c0 & 3) << 4);
+    wsrc1 = W + (size_t)(col_base + (c1 >> 2)) * kpad + ((c1 & 3) << 4);
+  }
+  const bool x0_on = XCH >= 256 || c0 < XCH, w0_on = WCH >= 256 || c0 < WCH;
+  int8_t *const xdst0 = Xs + (c0 >> 2) * kLdsRow + ((c0 & 3) << 4);
+  int8_t *const xdst1 = Xs + (c1 >> 2) * kLdsRow + ((c1 & 3) << 4);
+  int8_t *const wdst0 = Ws + (c0 >> 2) * kLdsRow + ((c0 & 3) << 4);
+  int8_t *const wdst1 = Ws + (c1 >> 2) * kLdsRow + ((c1 & 3) << 4);
+#define GEMM_LOAD_TILES(kt)                                                        \
+  do {                                                                             \
+    if (x0_on) x0 = *reinterpret_cast<const int4 *>(xsrc0 + ((kt) << 6));          \
+    if (XPT > 1) x1 = *reinterpret_cast<const int4 *>(xsrc1 + ((kt) << 6));        \
+    if (w0_on) w0 = *reinterpret_cast<const int4 *>(wsrc0 + ((kt) << 6));          \
+    if (WPT > 1) w1 = *reinterpret_cast<const int4 *>(wsrc1 + ((kt) << 6));        \
+  } while (0)
+#define GEMM_STORE_TILES()                                                         \
+  do {                                                                             \
+    if (x0_on) *reinterpret_cast<int4 *>(xdst0) = x0;                              \
+    if (XPT > 1) *reinterpret_cast<int4 *>(xdst1) = x1;                            \
+    if (w0_on) *reinterpret_cast<int4 *>(wdst0) = w0;                              \
+    if (WPT > 1) *reinterpret_cast<int4 *>(wdst1) = w1;                            \
+  } while (0)
 
-  auto load_tiles = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < XPT; ++i) {
-      const int c = tid + i * 256;
-      if (XCH % 256 == 0 || c < XCH) {
-        int r = row_base + (c >> 2);
-        r = r < M ? r : M - 1;  // rows past the end repeat the last one; never stored
-        xreg[i] = *reinterpret_cast<const int4 *>(A + (size_t)r * lda + (kt << 6) + ((c & 3) << 4));
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < WPT; ++i) {
-      const int c = tid + i * 256;
-      if (WCH % 256 == 0 || c < WCH)
-        wreg[i] = *reinterpret_cast<const int4 *>(W + (size_t)(col_base + (c >> 2)) * kpad +
-                                                  (kt << 6) + ((c & 3) << 4));
-    }
-  };
-  auto store_tiles = [&]() {
-#pragma unroll
-    for (int i = 0; i < XPT; ++i) {
-      const int c = tid + i * 256;
-      if (XCH % 256 == 0 || c < XCH)
-        *reinterpret_cast<int4 *>(Xs + (c >> 2) * kLdsRow + ((c & 3) << 4)) = xreg[i];
-    }
-#pragma unroll
-    for (int i = 0; i < WPT; ++i) {
-      const int c = tid + i * 256;
-      if (WCH % 256 == 0 || c < WCH)
-        *reinterpret_cast<int4 *>(Ws + (c >> 2) * kLdsRow + ((c & 3) << 4)) = wreg[i];
-    }
-  };
-
-  load_tiles(0);
+  GEMM_LOAD_TILES(0);
   for (int kt = 0; kt < KT; ++kt) {
-    store_tiles();
+    GEMM_STORE_TILES();
     __syncthreads();
-    if (kt + 1 < KT) load_tiles(kt + 1);  // in flight while the MFMAs run
+    if (kt + 1 < KT) GEMM_LOAD_TILES(kt + 1);  // in flight while the MFMAs run
     v4i xf[MI], wf[NI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
@@ -133,6 +134,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(
         acc[ni][mi] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
     __syncthreads();
   }
+#undef GEMM_LOAD_TILES
+#undef GEMM_STORE_TILES
 
   // epilogue: + bias, rescale, saturate, store
   const int cpg = rq.cols_per_gate;
@@ -149,10 +152,11 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(
     int32_t Mg[4], rg[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      // the column's gate picks its rescale by selects: indexing rq.M / rq.r with a runtime gate would copy the
+      // argument struct into scratch memory
       const int n = n0 + j;
-      const int g = (n >= cpg) + (n >= 2 * cpg) + (n >= 3 * cpg);
-      Mg[j] = rq.M[g];
-      rg[j] = rq.r[g];
+      Mg[j] = n >= 3 * cpg ? rq.M[3] : (n >= 2 * cpg ? rq.M[2] : (n >= cpg ? rq.M[1] : rq.M[0]));
+      rg[j] = n >= 3 * cpg ? rq.r[3] : (n >= 2 * cpg ? rq.r[2] : (n >= cpg ? rq.r[1] : rq.r[0]));
     }
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
@@ -217,6 +221,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(
         } else {
           const int16_t e[8] = {(int16_t)piece.x, (int16_t)(piece.x >> 16), (int16_t)piece.y, (int16_t)(piece.y >> 16),
                                 (int16_t)piece.z, (int16_t)(piece.z >> 16), (int16_t)piece.w, (int16_t)(piece.w >> 16)};
+#pragma unroll
           for (int j = 0; j < 8; ++j)
             if (n + j < ncols) o[j] = e[j];
         }

@@ -55,20 +55,22 @@ __global__ __launch_bounds__(256) void in_gemm_kernel(InGemmArgs a) {
   const int tile_base = blockIdx.y * 4;
   const int rows_total = a.T * a.Bp;
 
-  // the two activation rows and two weight rows this thread stages per k tile
-  const int8_t *xsrc[2];
-  const int8_t *wsrc[2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int c = tid + i * 256;
+  // the two activation rows and two weight rows this thread stages per k tile; pointers and the registers the
+  // next tile waits in are named variables on purpose (as small arrays they were left in scratch memory, and the
+  // loads then no longer overlapped the MFMAs)
+  const int c0 = tid, c1 = tid + 256;
+  auto x_row = [&](int c) {
     int m = row_base + (c >> 2);
     m = m < rows_total ? m : rows_total - 1;
     const int t = m / a.Bp;
     int b = m - t * a.Bp;
     b = b < a.B ? b : a.B - 1;  // padded rows repeat the last real one; never read back
-    xsrc[i] = a.A + ((size_t)t * a.B + b) * a.lda + ((c & 3) << 4);
-    wsrc[i] = a.W2 + ((size_t)tile_base * 32 + (c >> 2)) * a.kpad + ((c & 3) << 4);
-  }
+    return a.A + ((size_t)t * a.B + b) * a.lda + ((c & 3) << 4);
+  };
+  const int8_t *const xsrc0 = x_row(c0), *const xsrc1 = x_row(c1);
+  const int8_t *const wsrc0 = a.W2 + ((size_t)tile_base * 32 + (c0 >> 2)) * a.kpad + ((c0 & 3) << 4);
+  const int8_t *const wsrc1 = a.W2 + ((size_t)tile_base * 32 + (c1 >> 2)) * a.kpad + ((c1 & 3) << 4);
+  const int dst0 = (c0 >> 2) * kLdsRow + ((c0 & 3) << 4), dst1 = (c1 >> 2) * kLdsRow + ((c1 & 3) << 4);
 
   v16i acc[2][2];
 #pragma unroll
@@ -79,26 +81,19 @@ __global__ __launch_bounds__(256) void in_gemm_kernel(InGemmArgs a) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
   const int KT = a.kpad >> 6;
-  int4 xreg[2], wreg[2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    xreg[i] = *reinterpret_cast<const int4 *>(xsrc[i]);
-    wreg[i] = *reinterpret_cast<const int4 *>(wsrc[i]);
-  }
+  int4 x0 = *reinterpret_cast<const int4 *>(xsrc0), x1 = *reinterpret_cast<const int4 *>(xsrc1);
+  int4 w0 = *reinterpret_cast<const int4 *>(wsrc0), w1 = *reinterpret_cast<const int4 *>(wsrc1);
   for (int kt = 0; kt < KT; ++kt) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = tid + i * 256;
-      *reinterpret_cast<int4 *>(Xs + (c >> 2) * kLdsRow + ((c & 3) << 4)) = xreg[i];
-      *reinterpret_cast<int4 *>(Ws + (c >> 2) * kLdsRow + ((c & 3) << 4)) = wreg[i];
-    }
+    *reinterpret_cast<int4 *>(Xs + dst0) = x0;
+    *reinterpret_cast<int4 *>(Xs + dst1) = x1;
+    *reinterpret_cast<int4 *>(Ws + dst0) = w0;
+    *reinterpret_cast<int4 *>(Ws + dst1) = w1;
     __syncthreads();
     if (kt + 1 < KT) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        xreg[i] = *reinterpret_cast<const int4 *>(xsrc[i] + ((kt + 1) << 6));
-        wreg[i] = *reinterpret_cast<const int4 *>(wsrc[i] + ((kt + 1) << 6));
-      }
+      x0 = *reinterpret_cast<const int4 *>(xsrc0 + ((kt + 1) << 6));
+      x1 = *reinterpret_cast<const int4 *>(xsrc1 + ((kt + 1) << 6));
+      w0 = *reinterpret_cast<const int4 *>(wsrc0 + ((kt + 1) << 6));
+      w1 = *reinterpret_cast<const int4 *>(wsrc1 + ((kt + 1) << 6));
     }
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
