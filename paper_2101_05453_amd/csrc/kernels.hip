@@ -34,7 +34,7 @@ template <int BM, int BN, int WM, int WN, bool OUT8>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM == 128 ? 3 : 1, BM == 128 ? 3 : 8))) void gemm_i8_kernel(
     const int8_t *__restrict__ A, int lda, int M, const int8_t *__restrict__ W, int kpad,
     int ncols, const int32_t *__restrict__ bias, Requant rq, void *__restrict__ out, int ldc,
-    int8_t *__restrict__ out2, int ldc2) {
+    int8_t *__restrict__ out2, int ldc2, int nrb, int ncb, int xr_n) {
   static_assert(WM * WN == 4, "four waves per workgroup");
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 16, NI = TN / 16;
@@ -53,19 +53,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM == 128 ?
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  // Workgroup -> tile: bands of kBand row blocks; inside a band the row block runs fastest and the column block
-  // next, so that the workgroups in flight together share kBand activation tiles and sweep the weights once per
-  // band (with the plain grid order every activation tile was fetched from memory once per column block).
-  constexpr int kBand = 16;
+  // Workgroup -> tile.  The hardware deals consecutive workgroups out to the eight XCDs in turn, and every XCD has
+  // an L2 of its own: XCD x = id % 8 gets the tiles of one cell of an xr_n x (8 / xr_n) split of the tile grid (the
+  // host picks the split that moves the fewest bytes: every XCD fetches its rows' activations and its columns'
+  // weights once instead of all of both), and walks them in bands of kBand row blocks, the row block running fastest
+  // and the column block next, so that the workgroups in flight together share kBand activation tiles.  If the
+  // hardware dealt the workgroups differently only the traffic would change: the map is one-to-one whatever runs where.
+  constexpr int kBand = 8;
   int rblk, cblk;
   {
-    const int nrb = gridDim.x;
-    const int id = blockIdx.y * nrb + blockIdx.x;
-    const int per_band = kBand * gridDim.y;
-    const int band = id / per_band, in_band = id - band * per_band;
-    const int rows_here = nrb - band * kBand < kBand ? nrb - band * kBand : kBand;
-    cblk = in_band / rows_here;
-    rblk = band * kBand + (in_band - cblk * rows_here);
+    const int id = blockIdx.x, x = id & 7, j = id >> 3;
+    const int xc_n = 8 / xr_n, xr = x / xc_n, xc = x - xr * xc_n;
+    const int r_lo = xr * nrb / xr_n, r_hi = (xr + 1) * nrb / xr_n;
+    const int c_lo = xc * ncb / xc_n, c_hi = (xc + 1) * ncb / xc_n;
+    const int nr = r_hi - r_lo, nc = c_hi - c_lo;
+    if (j >= nr * nc) return;  // the whole workgroup: the grid is 8 x the largest share
+    const int per_band = kBand * nc;
+    const int band = j / per_band, in_band = j - band * per_band;
+    const int rows_here = nr - band * kBand < kBand ? nr - band * kBand : kBand;
+    const int c = in_band / rows_here;
+    cblk = c_lo + c;
+    rblk = r_lo + band * kBand + (in_band - c * rows_here);
   }
   const int row_base = rblk * BM;  // activation rows
   const int col_base = cblk * BN;  // weight rows = output columns
@@ -230,24 +238,46 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM == 128 ?
   }
 }
 
+// The split of the tile grid over the XCDs: xr_n row shares x (8 / xr_n) column shares.  Among the splits that keep
+// the largest share within 1/8 of an even one, the one for which the XCDs together fetch the fewest bytes.
+static int gemm_xcd_rows(int nrb, int ncb, int bm, int bn, int kpad, unsigned *grid) {
+  const long long even = ((long long)nrb * ncb + 7) / 8;
+  int best = 1;
+  long long best_bytes = -1, best_share = 0;
+  for (int pass = 0; pass < 2 && best_bytes < 0; ++pass)
+    for (int xr = 1; xr <= 8; xr *= 2) {
+      const int xc = 8 / xr;
+      const long long share = (long long)((nrb + xr - 1) / xr) * ((ncb + xc - 1) / xc);
+      if (pass == 0 && share * 8 > even * 9) continue;  // pass 1: nothing is balanced, take the least traffic
+      const long long bytes = ((long long)nrb * bm * xc + (long long)ncb * bn * xr) * kpad;
+      if (best_bytes < 0 || bytes < best_bytes) best = xr, best_bytes = bytes, best_share = share;
+    }
+  *grid = (unsigned)(best_share * 8);
+  return best;
+}
+
 template <bool OUT8>
 static void launch_gemm(hipStream_t s, const int8_t *A, int lda, int M, const int8_t *W, int kpad,
                         int ncols, const int32_t *bias, const Requant &rq, void *out, int ldc,
                         int8_t *out2, int ldc2) {
   if (M <= 0 || ncols <= 0) return;
   const int ncols_pad = (ncols + 127) / 128 * 128;
+  unsigned grid;
   if (M > 256) {
-    dim3 grid((M + 127) / 128, ncols_pad / 128);
-    hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, OUT8>), grid, dim3(256), 0, s, A, lda, M, W,
-                       kpad, ncols, bias, rq, out, ldc, out2, ldc2);
+    const int nrb = (M + 127) / 128, ncb = ncols_pad / 128;
+    const int xr = gemm_xcd_rows(nrb, ncb, 128, 128, kpad, &grid);
+    hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, OUT8>), dim3(grid), dim3(256), 0, s, A, lda, M, W,
+                       kpad, ncols, bias, rq, out, ldc, out2, ldc2, nrb, ncb, xr);
   } else if (M > 32) {
-    dim3 grid((M + 63) / 64, ncols_pad / 64);
-    hipLaunchKernelGGL((gemm_i8_kernel<64, 64, 2, 2, OUT8>), grid, dim3(256), 0, s, A, lda, M, W,
-                       kpad, ncols, bias, rq, out, ldc, out2, ldc2);
+    const int nrb = (M + 63) / 64, ncb = ncols_pad / 64;
+    const int xr = gemm_xcd_rows(nrb, ncb, 64, 64, kpad, &grid);
+    hipLaunchKernelGGL((gemm_i8_kernel<64, 64, 2, 2, OUT8>), dim3(grid), dim3(256), 0, s, A, lda, M, W,
+                       kpad, ncols, bias, rq, out, ldc, out2, ldc2, nrb, ncb, xr);
   } else {
-    dim3 grid((M + 31) / 32, ncols_pad / 128);
-    hipLaunchKernelGGL((gemm_i8_kernel<32, 128, 1, 4, OUT8>), grid, dim3(256), 0, s, A, lda, M, W,
-                       kpad, ncols, bias, rq, out, ldc, out2, ldc2);
+    const int nrb = (M + 31) / 32, ncb = ncols_pad / 128;
+    const int xr = gemm_xcd_rows(nrb, ncb, 32, 128, kpad, &grid);
+    hipLaunchKernelGGL((gemm_i8_kernel<32, 128, 1, 4, OUT8>), dim3(grid), dim3(256), 0, s, A, lda, M, W,
+                       kpad, ncols, bias, rq, out, ldc, out2, ldc2, nrb, ncb, xr);
   }
 }
 
