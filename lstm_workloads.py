@@ -218,6 +218,47 @@ def make_gru(layer_inputs, num_cells, batch, steps, seed=0, weight_dist="normal"
     return layers, x
 
 
+@dataclass
+class SruLayerSpec:
+    """Float parameters of one SRU layer (matmul slots c, f, r, s; W[3] is None when the input itself is
+    the highway term, which needs input_size = num_cells) and the statistics its quantization needs."""
+
+    input_size: int
+    num_cells: int
+    W: List[Optional[np.ndarray]] = field(default_factory=list)  # 4 x [N, I], the last may be None
+    v: List[np.ndarray] = field(default_factory=list)  # 2 x [N]: v_f, v_r
+    b: List[np.ndarray] = field(default_factory=list)  # 2 x [N]: b_f, b_r
+    x_min: float = 0.0
+    x_max: float = 0.0
+    c_absmax: float = 0.0  # largest |c|, |W_c x|, |highway term|
+    h_min: float = 0.0
+    h_max: float = 0.0
+
+
+def make_sru(layer_inputs, num_cells, batch, steps, seed=0, weight_dist="normal", weight_param=0.05,
+             input_dist="normal", input_param=1.0, highway_matrix=None):
+    """Float SRU layers and the float input x [T, B, I0].  Layer l draws from PCG64(seed + l) in the
+    order W_c, W_f, W_r, (W_s,) v_f, v_r (U(-1, 1)), b_f, b_r (U(-0.5, 0.5)); x from
+    PCG64(seed + 100003).  A layer has W_s when its input size differs from num_cells, or always /
+    never with highway_matrix = True / False.  Only the input range of layer 0 is set here: the other
+    statistics come from a float run (Sec. 4)."""
+    layers = []
+    for l, I in enumerate(layer_inputs):
+        rng = np.random.Generator(np.random.PCG64(seed + l))
+        spec = SruLayerSpec(I, num_cells)
+        with_s = (I != num_cells) if highway_matrix is None else highway_matrix
+        spec.W = [_draw(rng, weight_dist, weight_param, (num_cells, I)) for _ in range(4 if with_s else 3)]
+        if not with_s:
+            spec.W.append(None)
+        spec.v = [_draw(rng, "uniform", 1.0, (num_cells,)) for _ in range(2)]
+        spec.b = [_draw(rng, "uniform", 0.5, (num_cells,)) for _ in range(2)]
+        layers.append(spec)
+    rng = np.random.Generator(np.random.PCG64(seed + 100003))
+    x = _draw(rng, input_dist, input_param, (steps, batch, layer_inputs[0]))
+    layers[0].x_min, layers[0].x_max = float(x.min()), float(x.max())
+    return layers, x
+
+
 def describe(name):
     cfg = CONFIGS[name]
     v = [n for bit, n in ((CIFG, "cifg"), (PEEPHOLE, "peephole"), (LAYER_NORM, "layernorm"),

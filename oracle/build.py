@@ -11,8 +11,8 @@ SAN_LIB = os.path.join(HERE, "liblstm_int_oracle_san.so")
 
 
 def _sources():
-    """The LSTM oracle and the GRU assembled from the same primitives."""
-    return [os.path.join(HERE, "lstm_int_oracle.c"), os.path.join(HERE, "gru_int_oracle.c")]
+    """The LSTM oracle, and the GRU and the SRU assembled from the same primitives."""
+    return [os.path.join(HERE, n) for n in ("lstm_int_oracle.c", "gru_int_oracle.c", "sru_int_oracle.c")]
 
 
 def build_sanitized():
@@ -28,7 +28,7 @@ def build_sanitized():
 
 
 def build(force=True):
-    deps = _sources() + [os.path.join(HERE, "lstm_int_oracle.h"), os.path.join(HERE, "gru_int_oracle.h")]
+    deps = _sources() + [os.path.join(HERE, n) for n in ("lstm_int_oracle.h", "gru_int_oracle.h", "sru_int_oracle.h")]
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(d) for d in deps):
         return LIB
     cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
