@@ -117,6 +117,86 @@ def bench_gru(args, np, torch, wl, binding):
     print(json.dumps(out))
 
 
+def sru_float_statistics(layers, x, torch):
+    """The calibration run of Sec. 4 for the SRU: the float cell in float64 on the GPU with torch ops (plumbing
+    outside the timed region), logging what sru_int_prepare needs: the largest magnitude of state, candidate and
+    highway term, and the range of the output, per layer."""
+    inp = torch.from_numpy(x).cuda().double()
+    for s in layers:
+        W = [None if w is None else torch.from_numpy(w).cuda().double() for w in s.W]
+        v = [torch.from_numpy(a).cuda().double() for a in s.v]
+        b = [torch.from_numpy(a).cuda().double() for a in s.b]
+        xc, af, ar = inp @ W[0].T, inp @ W[1].T + b[0], inp @ W[2].T + b[1]
+        hw = inp if W[3] is None else inp @ W[3].T
+        c = torch.zeros_like(xc[0])
+        out = torch.empty_like(xc)
+        cmax = max(float(xc.abs().max()), float(hw.abs().max()))
+        for t in range(inp.shape[0]):
+            f, r = torch.sigmoid(af[t] + v[0] * c), torch.sigmoid(ar[t] + v[1] * c)
+            c = f * c + (1 - f) * xc[t]
+            out[t] = r * c + (1 - r) * hw[t]
+            cmax = max(cmax, float(c.abs().max()))
+        s.c_absmax, s.h_min, s.h_max = cmax, min(float(out.min()), 0.0), max(float(out.max()), 0.0)
+        inp = out
+
+
+def bench_sru(args, np, torch, wl, binding):
+    """One step = one sru_int_forward call on a synthetic batch resident in HBM; checked against the oracle on a
+    few rows in the same run.  Roofline of the scan kernel: the bytes it must stream (the int16 slot terms in, the
+    input bytes of a layer whose highway term is its input, the int8 output) against its HIP-event time."""
+    L, I, N, B, T = (int(v) for v in args.sru.split(","))
+    layers, x = wl.make_sru([I] + [N] * (L - 1), N, B, T, seed=0, weight_param=0.03)
+    sru_float_statistics(layers, x, torch)
+    model = binding.sru_prepare(layers, device=0)
+    q0 = model.get_quant(0)
+    xq = np.clip(np.floor(x.astype(np.float64) / q0["s_x"] + 0.5) + q0["zp_x"], -128, 127).astype(np.int8)
+    xd = torch.from_numpy(xq).cuda()
+    ws = torch.empty(model.workspace_bytes(T, B), dtype=torch.uint8, device="cuda")
+    y = model.forward(xd, workspace=ws)
+    for _ in range(args.warmup):
+        model.forward(xd, y=y, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        model.forward(xd, y=y, workspace=ws)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    model.profile_begin()
+    for _ in range(args.steps):
+        model.forward(xd, y=y, workspace=ws)
+    prof = model.profile_end()
+    scan_us = prof["scan"]["total_ms"] / prof["scan"]["launches"] * 1e3
+    gemm_us = prof["input_gemm"]["total_ms"] / prof["input_gemm"]["launches"] * 1e3
+    G = [4 if s.W[3] is not None else 3 for s in layers]
+    scan_bytes = sum(T * B * N * (2.0 * g + 1 + (1 if g == 3 else 0)) for g in G) / L
+    gemm_ops = sum(2.0 * T * B * g * N * s.input_size for g, s in zip(G, layers)) / L
+    out = {"metric": "sru_cell_steps_per_sec", "value": B * T * L / dt, "unit": "cell-steps/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+           "config": {"workload": f"integer SRU: L={L} I={I} N={N} B={B} T={T}", "cell_steps_per_step": B * T * L},
+           "roofline": {"bound": "hbm", "achieved": scan_bytes / scan_us * 1e-3, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": scan_bytes / scan_us * 1e-3 / PEAK_HBM_GBS, "kernel": "sru_scan_kernel",
+                        "avg_launch_us": scan_us, "traffic": None,
+                        "kernels": {"input_gemm": {"avg_us": gemm_us, "tops": gemm_ops / gemm_us * 1e-6,
+                                                   "frac_mfma": gemm_ops / gemm_us * 1e-6 / PEAK_INT8_TOPS}}}}
+    if not args.no_cpu_baseline:
+        from oracle import sru as osru
+
+        rows = sorted(set(int(r) for r in np.linspace(0, B - 1, min(B, 8))))
+        om = osru.SruModel(layers)
+        t0 = time.perf_counter()
+        yo, _ = om.forward(xq[:, rows], threads=len(rows))
+        ot = time.perf_counter() - t0
+        eq = bool((y.cpu().numpy()[:, rows] == yo).all())
+        out["cpu_baseline"] = {"value": len(rows) * T * L / ot, "unit": "cell-steps/s", "cores": len(rows), "kind": "oracle",
+                               "sample": f"{len(rows)} rows spread over the batch x {T} steps x {L} layers, {ot:.1f} s"}
+        out["parity"] = {"rows": len(rows), "steps": T, "layers": L, "equal": eq}
+        if not eq:
+            print(json.dumps(out))
+            sys.exit("bench.py: the SRU output differs from the oracle's")
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -139,6 +219,9 @@ def main():
     ap.add_argument("--gru", default="", metavar="L,I,N,B,T",
                     help="benchmark the integer GRU instead (the cell Sec. 7 names; gru_int_forward): L layers of N cells, "
                          "layer 0 input I, B rows, T steps, e.g. 2,512,2048,256,64; one JSON line")
+    ap.add_argument("--sru", default="", metavar="L,I,N,B,T",
+                    help="benchmark the integer SRU instead (the other cell Sec. 7 names; sru_int_forward): L layers of N "
+                         "cells, layer 0 input I, B rows, T steps, e.g. 4,512,2048,256,64; one JSON line")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB MiB (a known-size reference for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -164,6 +247,9 @@ def main():
         print(json.dumps({"copy_bytes": n, "copies": 3}))
         return
     binding.lib()
+    if args.sru:
+        bench_sru(args, np, torch, wl, binding)
+        return
     if args.gru:
         bench_gru(args, np, torch, wl, binding)
         return

@@ -88,6 +88,13 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is not built: run python -m paper_2101_05453_amd.build")
+        try:
+            # torch first: it brings a HIP runtime of its own, and the library has to meet that one in the process
+            # (loaded before torch, the library pulled in the system's runtime and every call on a torch tensor
+            # then failed with a device error)
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         L.lstm_int_prepare.restype = C.c_int
         L.lstm_int_prepare.argtypes = [C.POINTER(LayerParams), C.c_int32, C.c_int32,
@@ -590,3 +597,180 @@ def gru_prepare(layers, device=0):
     del keep
     _check(rc, "gru_int_prepare")
     return GruModel(h, len(layers), device)
+
+
+# ---------------------------------------------------------------------------
+# sru_int_* (include/sru_int.h): the integer SRU built from the same blocks
+# ---------------------------------------------------------------------------
+class SruLayerParams(C.Structure):
+    """sru_int_layer_params"""
+    _fields_ = [
+        ("input_size", C.c_int32), ("num_cells", C.c_int32),
+        ("W", _fp * 4), ("v", _fp * 2), ("b", _fp * 2),
+        ("x_min", C.c_float), ("x_max", C.c_float), ("c_absmax", C.c_float),
+        ("h_min", C.c_float), ("h_max", C.c_float),
+    ]
+
+
+class SruLayerQuant(C.Structure):
+    """sru_int_layer_quant"""
+    _fields_ = [
+        ("I", C.c_int32), ("N", C.c_int32), ("G", C.c_int32),
+        ("zp_x", C.c_int32), ("zp_h", C.c_int32), ("m_c", C.c_int32),
+        ("s_x", C.c_double), ("s_h", C.c_double), ("s_W", C.c_double * 4), ("s_v", C.c_double * 2),
+        ("Mx", C.c_int32 * 4), ("ex", C.c_int32 * 4), ("Mv", C.c_int32 * 2), ("ev", C.c_int32 * 2),
+        ("Ms", C.c_int32), ("es", C.c_int32), ("Mh", C.c_int32), ("eh", C.c_int32),
+        ("Wq", C.POINTER(C.c_int8)), ("vq", C.POINTER(C.c_int16)),
+        ("bq", C.POINTER(C.c_int32)), ("b_fold", C.POINTER(C.c_int32)),
+    ]
+
+
+SRU_TRACE_FIELDS = {"tx": 4, "tv": 2, "act": 2, "c": 0, "h16": 0, "y": 0}  # slots per (t, b); 0 = [T,B,N]
+
+
+class SruTrace(C.Structure):
+    """sru_int_trace"""
+    _fields_ = [("layer", C.c_int32)] + [(n, C.c_void_p) for n in SRU_TRACE_FIELDS]
+
+
+_sru_ready = False
+
+
+def sru_lib():
+    global _sru_ready
+    L = lib()
+    if not _sru_ready:
+        L.sru_int_prepare.restype = C.c_int
+        L.sru_int_prepare.argtypes = [C.POINTER(SruLayerParams), C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+        L.sru_int_get_quant.restype = C.c_int
+        L.sru_int_get_quant.argtypes = [C.c_void_p, C.c_int32, C.POINTER(SruLayerQuant)]
+        L.sru_int_workspace_bytes.restype = C.c_size_t
+        L.sru_int_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.sru_int_forward.restype = C.c_int
+        L.sru_int_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(SruTrace)]
+        L.sru_int_set_option.restype = C.c_int
+        L.sru_int_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
+        L.sru_int_profile_begin.restype = C.c_int
+        L.sru_int_profile_begin.argtypes = [C.c_void_p]
+        L.sru_int_profile_end.restype = C.c_int
+        L.sru_int_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+        L.sru_int_destroy.restype = None
+        L.sru_int_destroy.argtypes = [C.c_void_p]
+        _sru_ready = True
+    return L
+
+
+def marshal_sru_layers(layers):
+    arr = (SruLayerParams * len(layers))()
+    keep = []
+
+    def ptr(a):
+        if a is None:
+            return _fp()
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        keep.append(a)
+        return a.ctypes.data_as(_fp)
+
+    for p, s in zip(arr, layers):
+        p.input_size, p.num_cells = s.input_size, s.num_cells
+        for g in range(4):
+            p.W[g] = ptr(s.W[g])
+        for j in range(2):
+            p.v[j], p.b[j] = ptr(s.v[j]), ptr(s.b[j])
+        p.x_min, p.x_max, p.c_absmax, p.h_min, p.h_max = s.x_min, s.x_max, s.c_absmax, s.h_min, s.h_max
+    return arr, keep
+
+
+class SruModel:
+    """Owns one sru_int_model."""
+
+    def __init__(self, handle, num_layers, device):
+        self._h = handle
+        self.num_layers = num_layers
+        self.device = device
+
+    def __del__(self):
+        self.destroy()
+
+    # sru_int_destroy
+    def destroy(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.sru_int_destroy(self._h)
+        self._h = None
+
+    # sru_int_get_quant
+    def get_quant(self, layer):
+        q = SruLayerQuant()
+        _check(sru_lib().sru_int_get_quant(self._h, layer, C.byref(q)), "sru_int_get_quant")
+        N, I, G = q.N, q.I, q.G
+        d = {k: getattr(q, k) for k in ("I", "N", "G", "zp_x", "zp_h", "m_c", "s_x", "s_h", "Ms", "es", "Mh", "eh")}
+        for k in ("s_W", "s_v", "Mx", "ex", "Mv", "ev"):
+            d[k] = list(getattr(q, k))
+        d["Wq"] = _view(q.Wq, (G, N, I), np.int8)
+        d["vq"] = _view(q.vq, (2, N), np.int16)
+        for k in ("bq", "b_fold"):
+            d[k] = _view(getattr(q, k), (G, N), np.int32)
+        return d
+
+    # sru_int_workspace_bytes
+    def workspace_bytes(self, T, B):
+        return sru_lib().sru_int_workspace_bytes(self._h, T, B)
+
+    # sru_int_set_option
+    def set_option(self, key, value):
+        _check(sru_lib().sru_int_set_option(self._h, key.encode(), value), "sru_int_set_option")
+
+    # sru_int_profile_begin / sru_int_profile_end
+    def profile_begin(self):
+        _check(sru_lib().sru_int_profile_begin(self._h), "sru_int_profile_begin")
+
+    def profile_end(self):
+        n = (C.c_int64 * 2)()
+        ms = (C.c_double * 2)()
+        _check(sru_lib().sru_int_profile_end(self._h, n, ms), "sru_int_profile_end")
+        return {k: {"launches": int(n[i]), "total_ms": float(ms[i])} for i, k in enumerate(("input_gemm", "scan"))}
+
+    # sru_int_forward on torch device tensors
+    def forward(self, x, y=None, c_state=None, workspace=None, trace_layer=None):
+        """x: int8 CUDA tensor [T,B,I0].  Returns y (int8 [T,B,N_last]); with trace_layer also a dict of
+        that layer's intermediate tensors.  Asynchronous on torch's current stream."""
+        import torch
+
+        assert x.is_cuda and x.dtype == torch.int8 and x.is_contiguous()
+        T, B, _ = x.shape
+        ql = SruLayerQuant()
+        _check(sru_lib().sru_int_get_quant(self._h, self.num_layers - 1, C.byref(ql)), "sru_int_get_quant")
+        if y is None:
+            y = torch.empty((T, B, ql.N), dtype=torch.int8, device=x.device)
+        if workspace is None:
+            workspace = torch.empty(max(self.workspace_bytes(T, B), 256), dtype=torch.uint8, device=x.device)
+        tr, bufs = None, {}
+        if trace_layer is not None:
+            qt = SruLayerQuant()
+            _check(sru_lib().sru_int_get_quant(self._h, trace_layer, C.byref(qt)), "sru_int_get_quant")
+            tr = SruTrace()
+            tr.layer = trace_layer
+            for f, slots in SRU_TRACE_FIELDS.items():
+                shape = (T, B, slots, qt.N) if slots else (T, B, qt.N)
+                bufs[f] = torch.zeros(shape, dtype=torch.int8 if f == "y" else torch.int16, device=x.device)
+                setattr(tr, f, bufs[f].data_ptr())
+        if c_state is not None:
+            assert c_state.is_cuda and c_state.dtype == torch.int16 and c_state.is_contiguous()
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+        _check(sru_lib().sru_int_forward(self._h, x.data_ptr(), T, B, y.data_ptr(),
+                                         c_state.data_ptr() if c_state is not None else None,
+                                         workspace.data_ptr(), workspace.numel(), stream,
+                                         C.byref(tr) if tr is not None else None), "sru_int_forward")
+        return (y, bufs) if trace_layer is not None else y
+
+
+# sru_int_prepare
+def sru_prepare(layers, device=0):
+    """layers: SruLayerSpec-like objects with their statistics filled in.  device = -1 builds a host-only model."""
+    arr, keep = marshal_sru_layers(layers)
+    h = C.c_void_p()
+    rc = sru_lib().sru_int_prepare(arr, len(layers), device, C.byref(h))
+    del keep
+    _check(rc, "sru_int_prepare")
+    return SruModel(h, len(layers), device)

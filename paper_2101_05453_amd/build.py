@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblstm_int.so")
 SOURCES = ["prepare.cpp", "kernels.hip", "persistent.hip", "in_gemm.hip", "rec_inst_8.hip", "rec_inst_20.hip",
-           "rec_inst_32.hip", "rec_sparse_inst_8.hip", "rec_sparse_inst_20.hip", "rec_sparse_inst_32.hip", "rec16_inst.hip", "rec16_inst_4.hip", "rec16_inst_10.hip", "rec16_inst_16.hip", "stack.hip", "stack_inst_8.hip", "stack_inst_20.hip", "stack_inst_32.hip", "calibrate.hip", "ceiling.hip", "gru.hip", "api.hip"]
+           "rec_inst_32.hip", "rec_sparse_inst_8.hip", "rec_sparse_inst_20.hip", "rec_sparse_inst_32.hip", "rec16_inst.hip", "rec16_inst_4.hip", "rec16_inst_10.hip", "rec16_inst_16.hip", "stack.hip", "stack_inst_8.hip", "stack_inst_20.hip", "stack_inst_32.hip", "calibrate.hip", "ceiling.hip", "gru.hip", "sru.hip", "api.hip"]
 HOSTMATH_LIB = os.path.join(HERE, "liblstm_int_hostmath.so")
 HOSTMATH_SAN_LIB = os.path.join(HERE, "liblstm_int_hostmath_san.so")
 SANITIZE_FLAGS = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g"]

@@ -139,6 +139,31 @@ def main():
     xq = np.where(np.asarray(layers[0].W[0][0])[None, None, :] >= 0, -128, 127).astype(np.int8).repeat(2, 0)
     gm.forward(np.ascontiguousarray(xq), trace_layer=0)
     print("gru ok", flush=True)
+    # 6. the SRU of the same oracle: both forms of the highway term, ragged shapes, saturating values, a state at its bounds
+    from oracle import sru  # noqa: E402
+
+    layers, x = wl.make_sru([19, 37, 37], 37, 3, 9, seed=6, weight_param=0.3, input_dist="uniform", input_param=3.0)
+    sru.calibrate(layers, x)
+    layers[0].x_min, layers[0].x_max = -1.0, 2.0
+    for s in layers:
+        s.b[0] = s.b[0] * 40
+        s.c_absmax *= 0.25
+        s.h_max *= 0.2
+    sm = sru.SruModel(layers)
+    q0 = sm.get_quant(0)
+    xq = np.clip(np.floor(x.astype(np.float64) / q0["s_x"] + 0.5) + q0["zp_x"], -128, 127).astype(np.int8)
+    cs = np.full(3 * 3 * 37, -32768, np.int16)
+    for l in range(3):
+        sm.forward(xq, c_state=cs, trace_layer=l)
+    sm.forward(xq, unfolded=True)
+    layers, x = wl.make_sru([32768], 8, 1, 2, seed=2, weight_param=0.01)
+    for g in range(4):
+        layers[0].W[g] = np.where(layers[0].W[g] >= 0, 0.01, -0.01).astype(np.float32)
+    sru.calibrate(layers, x)
+    sm = sru.SruModel(layers)
+    xq = np.where(np.asarray(layers[0].W[0][0])[None, None, :] >= 0, -128, 127).astype(np.int8).repeat(2, 0)
+    sm.forward(np.ascontiguousarray(xq), trace_layer=0)
+    print("sru ok", flush=True)
     print("SAN DRIVER OK", flush=True)
 
 
