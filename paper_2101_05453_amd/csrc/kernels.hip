@@ -28,7 +28,15 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 // wants from each lane (16 consecutive k bytes of one row); the same k
 // permutation applies to both, so the dot products do not depend on it.
 // ---------------------------------------------------------------------------
-constexpr int kLdsRow = 80;  // 64 data bytes + 16 pad: conflict-free b128 reads
+// LDS row of a staged tile: 64 data bytes + 32 pad.  With the lane -> (row = lane % 16, 16-byte piece = lane / 16)
+// map of the 16x16x64 operands, 16-byte accesses are free of bank conflicts at a row stride of 24 words and take
+// twice as long at 20 (measured with SQ_LDS_BANK_CONFLICT on a probe kernel: 4 against 8 clocks per wave read)
+constexpr int kLdsRow = 96;
+// piece c of a staged tile: row and byte offset in the row.  Four neighbouring lanes fetch the 64 bytes of one row:
+// the order the memory system wants (with the operand map here as well, which would make the LDS stores conflict-free
+// too, the global loads slowed the kernel from 293 to 407 us)
+__device__ __forceinline__ int stage_row(int c) { return c >> 2; }
+__device__ __forceinline__ int stage_col(int c) { return (c & 3) << 4; }
 
 template <int BM, int BN, int WM, int WN, bool OUT8>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM == 128 ? 3 : 1, BM == 128 ? 3 : 8))) void gemm_i8_kernel(
@@ -88,60 +96,70 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM == 128 ?
   // and drained by helper lambdas they were left in scratch memory in some builds: every chunk then went
   // load -> scratch -> LDS, the loads no longer overlapped the MFMAs, and the kernel ran at half speed.)
   static_assert(XPT <= 2 && WPT <= 2, "at most two chunks per thread and operand");
-  int4 x0 = {}, x1 = {}, w0 = {}, w1 = {};
+  // the k tiles kt, kt + 1, kt + 2 on their way from memory to LDS: plain named vector registers
+  v4i sa_x0 = {}, sa_x1 = {}, sa_w0 = {}, sa_w1 = {};
+  v4i sb_x0 = {}, sb_x1 = {}, sb_w0 = {}, sb_w1 = {};
+  v4i sc_x0 = {}, sc_x1 = {}, sc_w0 = {}, sc_w1 = {};
   const int KT = kpad >> 6;
   const int c0 = tid, c1 = tid + 256;
   const int8_t *xsrc0, *xsrc1, *wsrc0, *wsrc1;
   {
-    int r0 = row_base + (c0 >> 2), r1 = row_base + (c1 >> 2);
+    int r0 = row_base + stage_row(c0), r1 = row_base + stage_row(c1);
     r0 = r0 < M ? r0 : M - 1;  // rows past the end repeat the last one; never stored
     r1 = r1 < M ? r1 : M - 1;
-    xsrc0 = A + (size_t)r0 * lda + ((c0 & 3) << 4);
-    xsrc1 = A + (size_t)r1 * lda + ((c1 & 3) << 4);
-    wsrc0 = W + (size_t)(col_base + (c0 >> 2)) * kpad + ((c0 & 3) << 4);
-    wsrc1 = W + (size_t)(col_base + (c1 >> 2)) * kpad + ((c1 & 3) << 4);
+    xsrc0 = A + (size_t)r0 * lda + stage_col(c0);
+    xsrc1 = A + (size_t)r1 * lda + stage_col(c1);
+    wsrc0 = W + (size_t)(col_base + stage_row(c0)) * kpad + stage_col(c0);
+    wsrc1 = W + (size_t)(col_base + stage_row(c1)) * kpad + stage_col(c1);
   }
   const bool x0_on = XCH >= 256 || c0 < XCH, w0_on = WCH >= 256 || c0 < WCH;
-  int8_t *const xdst0 = Xs + (c0 >> 2) * kLdsRow + ((c0 & 3) << 4);
-  int8_t *const xdst1 = Xs + (c1 >> 2) * kLdsRow + ((c1 & 3) << 4);
-  int8_t *const wdst0 = Ws + (c0 >> 2) * kLdsRow + ((c0 & 3) << 4);
-  int8_t *const wdst1 = Ws + (c1 >> 2) * kLdsRow + ((c1 & 3) << 4);
-#define GEMM_LOAD_TILES(kt)                                                        \
-  do {                                                                             \
-    if (x0_on) x0 = *reinterpret_cast<const int4 *>(xsrc0 + ((kt) << 6));          \
-    if (XPT > 1) x1 = *reinterpret_cast<const int4 *>(xsrc1 + ((kt) << 6));        \
-    if (w0_on) w0 = *reinterpret_cast<const int4 *>(wsrc0 + ((kt) << 6));          \
-    if (WPT > 1) w1 = *reinterpret_cast<const int4 *>(wsrc1 + ((kt) << 6));        \
+  int8_t *const xdst0 = Xs + stage_row(c0) * kLdsRow + stage_col(c0);
+  int8_t *const xdst1 = Xs + stage_row(c1) * kLdsRow + stage_col(c1);
+  int8_t *const wdst0 = Ws + stage_row(c0) * kLdsRow + stage_col(c0);
+  int8_t *const wdst1 = Ws + stage_row(c1) * kLdsRow + stage_col(c1);
+#define GEMM_LOAD_TILES(st, kt)                                                       \
+  do {                                                                               \
+    if ((kt) < KT) {                                                                 \
+      if (x0_on) st##_x0 = *reinterpret_cast<const v4i *>(xsrc0 + ((kt) << 6));    \
+      if (XPT > 1) st##_x1 = *reinterpret_cast<const v4i *>(xsrc1 + ((kt) << 6));  \
+      if (w0_on) st##_w0 = *reinterpret_cast<const v4i *>(wsrc0 + ((kt) << 6));    \
+      if (WPT > 1) st##_w1 = *reinterpret_cast<const v4i *>(wsrc1 + ((kt) << 6));  \
+    }                                                                                \
   } while (0)
-#define GEMM_STORE_TILES()                                                         \
-  do {                                                                             \
-    if (x0_on) *reinterpret_cast<int4 *>(xdst0) = x0;                              \
-    if (XPT > 1) *reinterpret_cast<int4 *>(xdst1) = x1;                            \
-    if (w0_on) *reinterpret_cast<int4 *>(wdst0) = w0;                              \
-    if (WPT > 1) *reinterpret_cast<int4 *>(wdst1) = w1;                            \
+#define GEMM_STORE_TILES(st)                                                         \
+  do {                                                                               \
+    if (x0_on) *reinterpret_cast<v4i *>(xdst0) = st##_x0;                           \
+    if (XPT > 1) *reinterpret_cast<v4i *>(xdst1) = st##_x1;                         \
+    if (w0_on) *reinterpret_cast<v4i *>(wdst0) = st##_w0;                           \
+    if (WPT > 1) *reinterpret_cast<v4i *>(wdst1) = st##_w1;                         \
+  } while (0)
+  // one k tile: staged registers -> LDS, the tile three ahead requested (in flight under three tiles of MFMAs: one
+  // tile ahead the loop waited for memory every time round), operands from LDS, MFMAs
+#define GEMM_K_TILE(st, kt)                                                          \
+  do {                                                                               \
+    GEMM_STORE_TILES(st);                                                            \
+    __syncthreads();                                                                 \
+    GEMM_LOAD_TILES(st, (kt) + 3);                                                   \
+    v4i xf[MI], wf[NI];                                                              \
+    _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                                \
+      xf[mi] = *reinterpret_cast<const v4i *>(Xs + (wm * TM + mi * 16 + (lane & 15)) * kLdsRow + ((lane >> 4) << 4)); \
+    _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                \
+      wf[ni] = *reinterpret_cast<const v4i *>(Ws + (wn * TN + ni * 16 + (lane & 15)) * kLdsRow + ((lane >> 4) << 4)); \
+    _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                \
+      _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                              \
+        acc[ni][mi] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0); \
+    __syncthreads();                                                                 \
   } while (0)
 
-  GEMM_LOAD_TILES(0);
-  for (int kt = 0; kt < KT; ++kt) {
-    GEMM_STORE_TILES();
-    __syncthreads();
-    if (kt + 1 < KT) GEMM_LOAD_TILES(kt + 1);  // in flight while the MFMAs run
-    v4i xf[MI], wf[NI];
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-      xf[mi] = *reinterpret_cast<const v4i *>(Xs + (wm * TM + mi * 16 + (lane & 15)) * kLdsRow +
-                                              ((lane >> 4) << 4));
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-      wf[ni] = *reinterpret_cast<const v4i *>(Ws + (wn * TN + ni * 16 + (lane & 15)) * kLdsRow +
-                                              ((lane >> 4) << 4));
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-        acc[ni][mi] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
-    __syncthreads();
+  GEMM_LOAD_TILES(sa, 0);
+  GEMM_LOAD_TILES(sb, 1);
+  GEMM_LOAD_TILES(sc, 2);
+  for (int kt = 0; kt < KT; kt += 3) {
+    GEMM_K_TILE(sa, kt);
+    if (kt + 1 < KT) GEMM_K_TILE(sb, kt + 1);
+    if (kt + 2 < KT) GEMM_K_TILE(sc, kt + 2);
   }
+#undef GEMM_K_TILE
 #undef GEMM_LOAD_TILES
 #undef GEMM_STORE_TILES
 
