@@ -28,33 +28,43 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 // wants from each lane (16 consecutive k bytes of one row); the same k
 // permutation applies to both, so the dot products do not depend on it.
 // ---------------------------------------------------------------------------
-// LDS row of a staged tile: 64 data bytes + 32 pad.  With the lane -> (row = lane % 16, 16-byte piece = lane / 16)
-// map of the 16x16x64 operands, 16-byte accesses are free of bank conflicts at a row stride of 24 words and take
-// twice as long at 20 (measured with SQ_LDS_BANK_CONFLICT on a probe kernel: 4 against 8 clocks per wave read)
-constexpr int kLdsRow = 96;
-// piece c of a staged tile: row and byte offset in the row.  Four neighbouring lanes fetch the 64 bytes of one row:
-// the order the memory system wants (with the operand map here as well, which would make the LDS stores conflict-free
-// too, the global loads slowed the kernel from 293 to 407 us)
+// A staged tile in LDS: rows of 64 bytes without padding, the 16-byte piece p of row r at position p ^ ((r >> 1) & 3).
+// With this swizzle both accesses are free of bank conflicts -- the operand reads of the 16x16x64 MFMA (row =
+// lane % 16, piece = lane / 16: 4 clocks per wave) and the staging stores (row = lane / 4, piece = lane % 4: 8
+// clocks, the rate of LDS stores) -- measured with SQ_LDS_BANK_CONFLICT on a probe kernel; rows padded to 80 bytes
+// took 8 and 16 clocks, padded to 96 bytes 4 and 16.
+constexpr int kLdsRow = 64;
+__device__ __forceinline__ int lds_piece(int row, int piece) { return row * kLdsRow + ((piece ^ ((row >> 1) & 3)) << 4); }
+// piece c of a staged tile: four neighbouring lanes fetch the 64 bytes of one row, the order the memory system wants
 __device__ __forceinline__ int stage_row(int c) { return c >> 2; }
-__device__ __forceinline__ int stage_col(int c) { return (c & 3) << 4; }
+__device__ __forceinline__ int stage_piece(int c) { return c & 3; }
 
+// BM x BN outputs per workgroup of WM x WN waves.  A tile fetches (BM + BN) * 64 bytes per 2 * BM * BN * 64
+// operations: 128 operations per byte at 128 x 128 (four waves of 64 x 64, three workgroups per compute unit) and
+// 256 at 256 x 256 (eight waves of 128 x 64, one workgroup per compute unit), which large products take
+// (16384 x 6144 x 2048: 290 -> 271 us).
 template <int BM, int BN, int WM, int WN, bool OUT8>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM == 128 ? 3 : 1, BM == 128 ? 3 : 8))) void gemm_i8_kernel(
+__global__ __launch_bounds__(WM * WN * 64)
+    __attribute__((amdgpu_waves_per_eu(BM == 256 ? 2 : (BM == 128 ? 3 : 1), BM == 256 ? 2 : (BM == 128 ? 3 : 8)))) void gemm_i8_kernel(
     const int8_t *__restrict__ A, int lda, int M, const int8_t *__restrict__ W, int kpad,
     int ncols, const int32_t *__restrict__ bias, Requant rq, void *__restrict__ out, int ldc,
     int8_t *__restrict__ out2, int ldc2, int nrb, int ncb, int xr_n) {
-  static_assert(WM * WN == 4, "four waves per workgroup");
+  constexpr int NW = WM * WN, NT = NW * 64;  // waves, threads
+  static_assert(NW == 4 || NW == 8, "four or eight waves per workgroup");
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 16, NI = TN / 16;
   static_assert(MI >= 1 && NI >= 1 && TM % 16 == 0 && TN % 16 == 0, "tile shape");
   constexpr int XCH = BM * 4, WCH = BN * 4;  // 16-byte chunks per k-tile
-  constexpr int XPT = (XCH + 255) / 256, WPT = (WCH + 255) / 256;
+  constexpr int XPT = (XCH + NT - 1) / NT, WPT = (WCH + NT - 1) / NT;
 
-  // operand tiles during the k loop; afterwards (int16 output) each wave's TM x TN results, staged so that
-  // the stores cover whole 16-byte pieces of consecutive columns
+  // operand tiles during the k loop; afterwards (int16 output) each wave's results, kStageRows rows at a time,
+  // staged so that the stores cover whole 16-byte pieces of consecutive columns
   constexpr int kStageRow = TN + 8;  // int16 elements; the pad keeps the 8-byte writes off each other's banks
-  constexpr int kOperandBytes = (BM + BN) * kLdsRow;
-  constexpr int kStageBytes = OUT8 ? 0 : 4 * TM * kStageRow * 2;
+  constexpr int MIG = TM > 64 ? 2 : MI;  // 16-row blocks staged per pass
+  constexpr int kStageRows = MIG * 16;
+  constexpr int kTileBytes = (BM + BN) * kLdsRow;  // one staged k tile of both operands
+  constexpr int kOperandBytes = 2 * kTileBytes;    // two of them: tile kt + 1 is stored while tile kt is multiplied
+  constexpr int kStageBytes = OUT8 ? 0 : NW * kStageRows * kStageRow * 2;
   __shared__ __attribute__((aligned(16))) int8_t lds_buf[kOperandBytes > kStageBytes ? kOperandBytes : kStageBytes];
   int8_t *Xs = lds_buf, *Ws = lds_buf + BM * kLdsRow;
 
@@ -101,22 +111,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM == 128 ?
   v4i sb_x0 = {}, sb_x1 = {}, sb_w0 = {}, sb_w1 = {};
   v4i sc_x0 = {}, sc_x1 = {}, sc_w0 = {}, sc_w1 = {};
   const int KT = kpad >> 6;
-  const int c0 = tid, c1 = tid + 256;
+  const int c0 = tid, c1 = tid + NT;
   const int8_t *xsrc0, *xsrc1, *wsrc0, *wsrc1;
   {
     int r0 = row_base + stage_row(c0), r1 = row_base + stage_row(c1);
     r0 = r0 < M ? r0 : M - 1;  // rows past the end repeat the last one; never stored
     r1 = r1 < M ? r1 : M - 1;
-    xsrc0 = A + (size_t)r0 * lda + stage_col(c0);
-    xsrc1 = A + (size_t)r1 * lda + stage_col(c1);
-    wsrc0 = W + (size_t)(col_base + stage_row(c0)) * kpad + stage_col(c0);
-    wsrc1 = W + (size_t)(col_base + stage_row(c1)) * kpad + stage_col(c1);
+    xsrc0 = A + (size_t)r0 * lda + (stage_piece(c0) << 4);
+    xsrc1 = A + (size_t)r1 * lda + (stage_piece(c1) << 4);
+    wsrc0 = W + (size_t)(col_base + stage_row(c0)) * kpad + (stage_piece(c0) << 4);
+    wsrc1 = W + (size_t)(col_base + stage_row(c1)) * kpad + (stage_piece(c1) << 4);
   }
-  const bool x0_on = XCH >= 256 || c0 < XCH, w0_on = WCH >= 256 || c0 < WCH;
-  int8_t *const xdst0 = Xs + stage_row(c0) * kLdsRow + stage_col(c0);
-  int8_t *const xdst1 = Xs + stage_row(c1) * kLdsRow + stage_col(c1);
-  int8_t *const wdst0 = Ws + stage_row(c0) * kLdsRow + stage_col(c0);
-  int8_t *const wdst1 = Ws + stage_row(c1) * kLdsRow + stage_col(c1);
+  const bool x0_on = XCH >= NT || c0 < XCH, w0_on = WCH >= NT || c0 < WCH;
+  int8_t *const xdst0 = Xs + lds_piece(stage_row(c0), stage_piece(c0));
+  int8_t *const xdst1 = Xs + lds_piece(stage_row(c1), stage_piece(c1));
+  int8_t *const wdst0 = Ws + lds_piece(stage_row(c0), stage_piece(c0));
+  int8_t *const wdst1 = Ws + lds_piece(stage_row(c1), stage_piece(c1));
 #define GEMM_LOAD_TILES(st, kt)                                                       \
   do {                                                                               \
     if ((kt) < KT) {                                                                 \
@@ -126,38 +136,44 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM == 128 ?
       if (WPT > 1) st##_w1 = *reinterpret_cast<const v4i *>(wsrc1 + ((kt) << 6));  \
     }                                                                                \
   } while (0)
-#define GEMM_STORE_TILES(st)                                                         \
+#define GEMM_STORE_TILES(st, buf)                                                    \
   do {                                                                               \
-    if (x0_on) *reinterpret_cast<v4i *>(xdst0) = st##_x0;                           \
-    if (XPT > 1) *reinterpret_cast<v4i *>(xdst1) = st##_x1;                         \
-    if (w0_on) *reinterpret_cast<v4i *>(wdst0) = st##_w0;                           \
-    if (WPT > 1) *reinterpret_cast<v4i *>(wdst1) = st##_w1;                         \
+    if (x0_on) *reinterpret_cast<v4i *>(xdst0 + (buf) * kTileBytes) = st##_x0;      \
+    if (XPT > 1) *reinterpret_cast<v4i *>(xdst1 + (buf) * kTileBytes) = st##_x1;    \
+    if (w0_on) *reinterpret_cast<v4i *>(wdst0 + (buf) * kTileBytes) = st##_w0;      \
+    if (WPT > 1) *reinterpret_cast<v4i *>(wdst1 + (buf) * kTileBytes) = st##_w1;    \
   } while (0)
-  // one k tile: staged registers -> LDS, the tile three ahead requested (in flight under three tiles of MFMAs: one
-  // tile ahead the loop waited for memory every time round), operands from LDS, MFMAs
-#define GEMM_K_TILE(st, kt)                                                          \
+  // One k tile: tile kt + 1 goes from its staged registers (nx) into the LDS buffer that tile kt - 1 was read from
+  // (every wave is past the barrier that ended kt - 1), the freed registers request tile kt + 4, and tile kt is
+  // multiplied out of the other buffer: one barrier per tile, the LDS stores under the MFMAs, global loads three
+  // tiles of MFMAs ahead (one tile ahead and two barriers per tile, the loop waited for memory every time round).
+#define GEMM_K_TILE(nx, kt)                                                          \
   do {                                                                               \
-    GEMM_STORE_TILES(st);                                                            \
-    __syncthreads();                                                                 \
-    GEMM_LOAD_TILES(st, (kt) + 3);                                                   \
+    if ((kt) + 1 < KT) GEMM_STORE_TILES(nx, ((kt) + 1) & 1);                         \
+    GEMM_LOAD_TILES(nx, (kt) + 4);                                                   \
+    const int8_t *xs = Xs + ((kt) & 1) * kTileBytes, *wsb = Ws + ((kt) & 1) * kTileBytes; \
     v4i xf[MI], wf[NI];                                                              \
     _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                                \
-      xf[mi] = *reinterpret_cast<const v4i *>(Xs + (wm * TM + mi * 16 + (lane & 15)) * kLdsRow + ((lane >> 4) << 4)); \
+      xf[mi] = *reinterpret_cast<const v4i *>(xs + lds_piece(wm * TM + mi * 16 + (lane & 15), lane >> 4)); \
     _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                \
-      wf[ni] = *reinterpret_cast<const v4i *>(Ws + (wn * TN + ni * 16 + (lane & 15)) * kLdsRow + ((lane >> 4) << 4)); \
+      wf[ni] = *reinterpret_cast<const v4i *>(wsb + lds_piece(wn * TN + ni * 16 + (lane & 15), lane >> 4)); \
     _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                \
       _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                              \
         acc[ni][mi] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0); \
     __syncthreads();                                                                 \
   } while (0)
 
+  // tile t waits in register set t % 3 (sa, sb, sc)
   GEMM_LOAD_TILES(sa, 0);
   GEMM_LOAD_TILES(sb, 1);
   GEMM_LOAD_TILES(sc, 2);
+  GEMM_STORE_TILES(sa, 0);
+  __syncthreads();
+  GEMM_LOAD_TILES(sa, 3);
   for (int kt = 0; kt < KT; kt += 3) {
-    GEMM_K_TILE(sa, kt);
-    if (kt + 1 < KT) GEMM_K_TILE(sb, kt + 1);
-    if (kt + 2 < KT) GEMM_K_TILE(sc, kt + 2);
+    GEMM_K_TILE(sb, kt);
+    if (kt + 1 < KT) GEMM_K_TILE(sc, kt + 1);
+    if (kt + 2 < KT) GEMM_K_TILE(sa, kt + 2);
   }
 #undef GEMM_K_TILE
 #undef GEMM_LOAD_TILES
@@ -169,87 +185,91 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM == 128 ?
   // bytes of each of 8 rows (straight from the MFMA layout it is 32 bytes of each of 16 rows, and the memory
   // system wrote several times the output)
   const bool staged = !OUT8 && (ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
-  int16_t *stage = reinterpret_cast<int16_t *>(lds_buf) + wave * TM * kStageRow;
+  int16_t *stage = reinterpret_cast<int16_t *>(lds_buf) + wave * kStageRows * kStageRow;
 #pragma unroll
-  for (int ni = 0; ni < NI; ++ni) {
-    const int n0 = col_base + wn * TN + ni * 16 + ((lane >> 4) << 2);
-    const int4 b4 = *reinterpret_cast<const int4 *>(bias + n0);  // bias is padded like W
-    const int32_t bv[4] = {b4.x, b4.y, b4.z, b4.w};
-    int32_t Mg[4], rg[4];
+  for (int mg = 0; mg < MI; mg += MIG) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      // the column's gate picks its rescale by selects: indexing rq.M / rq.r with a runtime gate would copy the
-      // argument struct into scratch memory
-      const int n = n0 + j;
-      Mg[j] = n >= 3 * cpg ? rq.M[3] : (n >= 2 * cpg ? rq.M[2] : (n >= cpg ? rq.M[1] : rq.M[0]));
-      rg[j] = n >= 3 * cpg ? rq.r[3] : (n >= 2 * cpg ? rq.r[2] : (n >= cpg ? rq.r[1] : rq.r[0]));
-    }
+    for (int ni = 0; ni < NI; ++ni) {
+      const int n0 = col_base + wn * TN + ni * 16 + ((lane >> 4) << 2);
+      const int4 b4 = *reinterpret_cast<const int4 *>(bias + n0);  // bias is padded like W
+      const int32_t bv[4] = {b4.x, b4.y, b4.z, b4.w};
+      int32_t Mg[4], rg[4];
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-      const int m = row_base + wm * TM + mi * 16 + (lane & 15);
-      int32_t v[4];
-      if (rq.all_hi) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = rescale_hi(acc[ni][mi][j] + bv[j], Mg[j], rg[j]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = rescale(acc[ni][mi][j] + bv[j], Mg[j], rg[j]);
+      for (int j = 0; j < 4; ++j) {
+        // the column's gate picks its rescale by selects: indexing rq.M / rq.r with a runtime gate would copy the
+        // argument struct into scratch memory
+        const int n = n0 + j;
+        Mg[j] = n >= 3 * cpg ? rq.M[3] : (n >= 2 * cpg ? rq.M[2] : (n >= cpg ? rq.M[1] : rq.M[0]));
+        rg[j] = n >= 3 * cpg ? rq.r[3] : (n >= 2 * cpg ? rq.r[2] : (n >= cpg ? rq.r[1] : rq.r[0]));
       }
-      if (m >= M) continue;
-      if (OUT8) {
-        int8_t *o = reinterpret_cast<int8_t *>(out) + (size_t)m * ldc;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (n0 + j < ncols) {
-            const int8_t q = (int8_t)sat8(v[j] + rq.zp);
-            o[n0 + j] = q;
-            if (out2) out2[(size_t)m * ldc2 + n0 + j] = q;
-          }
+      for (int mi = mg; mi < mg + MIG; ++mi) {
+        const int m = row_base + wm * TM + mi * 16 + (lane & 15);
+        int32_t v[4];
+        if (rq.all_hi) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = rescale_hi(acc[ni][mi][j] + bv[j], Mg[j], rg[j]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = rescale(acc[ni][mi][j] + bv[j], Mg[j], rg[j]);
         }
-      } else if (staged) {
-        short4 pk;
-        pk.x = (short)sat16(v[0]);
-        pk.y = (short)sat16(v[1]);
-        pk.z = (short)sat16(v[2]);
-        pk.w = (short)sat16(v[3]);
-        *reinterpret_cast<short4 *>(stage + (mi * 16 + (lane & 15)) * kStageRow + ni * 16 + ((lane >> 4) << 2)) = pk;
-      } else {
-        int16_t *o = reinterpret_cast<int16_t *>(out) + (size_t)m * ldc;
-        if (n0 + 3 < ncols && (ldc & 3) == 0) {
+        if (m >= M) continue;
+        if (OUT8) {
+          int8_t *o = reinterpret_cast<int8_t *>(out) + (size_t)m * ldc;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (n0 + j < ncols) {
+              const int8_t q = (int8_t)sat8(v[j] + rq.zp);
+              o[n0 + j] = q;
+              if (out2) out2[(size_t)m * ldc2 + n0 + j] = q;
+            }
+          }
+        } else if (staged) {
           short4 pk;
           pk.x = (short)sat16(v[0]);
           pk.y = (short)sat16(v[1]);
           pk.z = (short)sat16(v[2]);
           pk.w = (short)sat16(v[3]);
-          *reinterpret_cast<short4 *>(o + n0) = pk;
+          *reinterpret_cast<short4 *>(stage + ((mi - mg) * 16 + (lane & 15)) * kStageRow + ni * 16 + ((lane >> 4) << 2)) = pk;
         } else {
+          int16_t *o = reinterpret_cast<int16_t *>(out) + (size_t)m * ldc;
+          if (n0 + 3 < ncols && (ldc & 3) == 0) {
+            short4 pk;
+            pk.x = (short)sat16(v[0]);
+            pk.y = (short)sat16(v[1]);
+            pk.z = (short)sat16(v[2]);
+            pk.w = (short)sat16(v[3]);
+            *reinterpret_cast<short4 *>(o + n0) = pk;
+          } else {
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (n0 + j < ncols) o[n0 + j] = (int16_t)sat16(v[j]);
+            for (int j = 0; j < 4; ++j)
+              if (n0 + j < ncols) o[n0 + j] = (int16_t)sat16(v[j]);
+          }
         }
       }
     }
-  }
-  if (!OUT8 && staged) {
-    // a wave reads back only what it wrote itself; LDS serves a wave's requests in order
-    constexpr int PPR = TN / 8;  // 16-byte pieces per row
+    if (!OUT8 && staged) {
+      // a wave reads back only what it wrote itself; LDS serves a wave's requests in order (so the next pass's
+      // stores cannot overtake these reads either)
+      constexpr int PPR = TN / 8;  // 16-byte pieces per row
 #pragma unroll
-    for (int i = 0; i < TM * PPR / 64; ++i) {
-      const int idx = i * 64 + lane;
-      const int r = idx / PPR, pc = idx - r * PPR;
-      const int m = row_base + wm * TM + r;
-      const int n = col_base + wn * TN + pc * 8;
-      const int4 piece = *reinterpret_cast<const int4 *>(stage + r * kStageRow + pc * 8);
-      if (m < M) {
-        int16_t *o = reinterpret_cast<int16_t *>(out) + (size_t)m * ldc + n;
-        if (n + 7 < ncols) {
-          *reinterpret_cast<int4 *>(o) = piece;
-        } else {
-          const int16_t e[8] = {(int16_t)piece.x, (int16_t)(piece.x >> 16), (int16_t)piece.y, (int16_t)(piece.y >> 16),
-                                (int16_t)piece.z, (int16_t)(piece.z >> 16), (int16_t)piece.w, (int16_t)(piece.w >> 16)};
+      for (int i = 0; i < kStageRows * PPR / 64; ++i) {
+        const int idx = i * 64 + lane;
+        const int r = idx / PPR, pc = idx - r * PPR;
+        const int m = row_base + wm * TM + mg * 16 + r;
+        const int n = col_base + wn * TN + pc * 8;
+        const int4 piece = *reinterpret_cast<const int4 *>(stage + r * kStageRow + pc * 8);
+        if (m < M) {
+          int16_t *o = reinterpret_cast<int16_t *>(out) + (size_t)m * ldc + n;
+          if (n + 7 < ncols) {
+            *reinterpret_cast<int4 *>(o) = piece;
+          } else {
+            const int16_t e[8] = {(int16_t)piece.x, (int16_t)(piece.x >> 16), (int16_t)piece.y, (int16_t)(piece.y >> 16),
+                                  (int16_t)piece.z, (int16_t)(piece.z >> 16), (int16_t)piece.w, (int16_t)(piece.w >> 16)};
 #pragma unroll
-          for (int j = 0; j < 8; ++j)
-            if (n + j < ncols) o[j] = e[j];
+            for (int j = 0; j < 8; ++j)
+              if (n + j < ncols) o[j] = e[j];
+          }
         }
       }
     }
@@ -281,7 +301,12 @@ static void launch_gemm(hipStream_t s, const int8_t *A, int lda, int M, const in
   if (M <= 0 || ncols <= 0) return;
   const int ncols_pad = (ncols + 127) / 128 * 128;
   unsigned grid;
-  if (M > 256) {
+  if (M >= 2048 && ncols_pad >= 1024 && ncols_pad % 256 == 0) {
+    const int nrb = (M + 255) / 256, ncb = ncols_pad / 256;
+    const int xr = gemm_xcd_rows(nrb, ncb, 256, 256, kpad, &grid);
+    hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 4, OUT8>), dim3(grid), dim3(512), 0, s, A, lda, M, W,
+                       kpad, ncols, bias, rq, out, ldc, out2, ldc2, nrb, ncb, xr);
+  } else if (M > 256) {
     const int nrb = (M + 127) / 128, ncb = ncols_pad / 128;
     const int xr = gemm_xcd_rows(nrb, ncb, 128, 128, kpad, &grid);
     hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, OUT8>), dim3(grid), dim3(256), 0, s, A, lda, M, W,
