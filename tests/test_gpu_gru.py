@@ -97,6 +97,14 @@ def test_speech_encoder_shapes_sampled_rows(gru):
     compare_all(gru, layers, x, "gru1024")
 
 
+def test_large_products_take_the_wide_matmul_tile(gru):
+    """T * B = 2100 rows by 3 * 400 = 1200 output columns (padded to 1280 = 5 blocks of 256): with a trace the input
+    term comes from the general matmul, which gives products of this size to its 256 x 256 tile -- a ragged last row
+    block, columns beyond the real ones, input depths 100 and 400."""
+    layers, x = wl.make_gru([100, 400], 400, 70, 30, seed=12, weight_param=0.08)
+    compare_all(gru, layers, x, "gru_tile256")
+
+
 def test_split_sequence_and_long_run(gru):
     import torch
 

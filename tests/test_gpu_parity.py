@@ -521,3 +521,11 @@ def test_random_shapes(orc, seed):
     print(f"random seed={seed} flags={flags} I={I} N={N} H={H} B={B} T={T}", flush=True)
     layers, x = wl.make_custom([I, H], N, H, flags, B, T, seed=seed + 500, weight_param=0.08)
     run_and_compare(orc, layers, x, f"random{seed}", trace=False, options={"rows16": seed % 3 != 2})
+
+
+def test_large_input_product_on_the_per_step_path(orc):
+    """The general matmul's tile for large products (2048 rows and more, 1024 output columns and more in blocks of
+    256: 256 x 256 outputs per workgroup, eight waves): the hoisted W x of the per-step path with T * B = 2100 rows
+    (a ragged last row block) by 4 * 320 = 1280 columns, every traced tensor against the oracle."""
+    layers, x = wl.make_custom([100], 320, 320, wl.PEEPHOLE, 70, 30, seed=77, weight_param=0.05)
+    run_and_compare(orc, layers, x, "tile256", trace=True, options={"path": 1})
