@@ -611,7 +611,7 @@ int upload(lstm_int_model *m) {
   m->tanh3 = reinterpret_cast<const uint16_t *>(dbase + tab_off[3]);
   m->wsig3 = wide_sig;
   m->wtanh3 = wide_tab[3];
-  if (rec_init() != hipSuccess || rec16_init() != hipSuccess || in_gemm_init() != hipSuccess || stack_init() != hipSuccess)
+  if (rec_init() != hipSuccess || rec16_init() != hipSuccess || in_gemm_init() != hipSuccess || gemm_init() != hipSuccess || stack_init() != hipSuccess)
     return LSTM_INT_E_DEVICE;
   // The stacked kernel runs models whose layers are all alike (same cells, width and variant; every layer
   // above the first reads the layer below), up to 8 of them, within the shift and table limits of the

@@ -768,7 +768,7 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
         std::memcpy(img.data() + o.bh + (size_t)g * d.Ncp * 4, q.bhq.data() + (size_t)g * N, (size_t)N * 4);
       offs[l] = o;
     }
-    if (hipSetDevice(device) != hipSuccess || in_gemm_init() != hipSuccess ||
+    if (hipSetDevice(device) != hipSuccess || in_gemm_init() != hipSuccess || gemm_init() != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&m->arena), img.size()) != hipSuccess) {
       m->arena = nullptr;
       delete m;

@@ -17,6 +17,9 @@ struct Requant {
   int32_t all_hi;  // every r >= 33: the high-word form of rescale applies
 };
 
+// allows the matmul's large tile its 128 KB of LDS; call with the device current before the first launch
+hipError_t gemm_init();
+
 // out = requant(A [M, lda] . W^T [ncols, kpad]) as int16 [M, ldc]
 //   A: int8 activations, rows readable for kpad bytes (kpad % 64 == 0)
 //   W: int8 weights, row-major [ncols_pad, kpad], ncols_pad % 128 == 0,

@@ -43,7 +43,11 @@ __device__ __forceinline__ int stage_piece(int c) { return c & 3; }
 // operations: 128 operations per byte at 128 x 128 (four waves of 64 x 64, three workgroups per compute unit) and
 // 256 at 256 x 256 (eight waves of 128 x 64, one workgroup per compute unit), which large products take
 // (16384 x 6144 x 2048: 290 -> 271 us).
-template <int BM, int BN, int WM, int WN, bool OUT8>
+// DMA: the operand tiles go from memory straight into LDS (global_load_lds, no registers and no LDS store
+// instructions on the way), four k tiles deep, and the operands of tile kt + 1 are read from LDS while tile kt is
+// multiplied.
+constexpr int kDmaBuffers = 4;
+template <int BM, int BN, int WM, int WN, bool OUT8, bool DMA = false>
 __global__ __launch_bounds__(WM * WN * 64)
     __attribute__((amdgpu_waves_per_eu(BM == 256 ? 2 : (BM == 128 ? 3 : 1), BM == 256 ? 2 : (BM == 128 ? 3 : 8)))) void gemm_i8_kernel(
     const int8_t *__restrict__ A, int lda, int M, const int8_t *__restrict__ W, int kpad,
@@ -65,7 +69,10 @@ __global__ __launch_bounds__(WM * WN * 64)
   constexpr int kTileBytes = (BM + BN) * kLdsRow;  // one staged k tile of both operands
   constexpr int kOperandBytes = 2 * kTileBytes;    // two of them: tile kt + 1 is stored while tile kt is multiplied
   constexpr int kStageBytes = OUT8 ? 0 : NW * kStageRows * kStageRow * 2;
-  __shared__ __attribute__((aligned(16))) int8_t lds_buf[kOperandBytes > kStageBytes ? kOperandBytes : kStageBytes];
+  static_assert(!DMA || kDmaBuffers * kTileBytes >= kStageBytes, "the staged results fit the operand buffers");
+  __shared__ __attribute__((aligned(16))) int8_t lds_static[DMA ? 16 : (kOperandBytes > kStageBytes ? kOperandBytes : kStageBytes)];
+  extern __shared__ __attribute__((aligned(16))) int8_t lds_dynamic[];  // DMA: kDmaBuffers * kTileBytes, set at launch
+  int8_t *const lds_buf = DMA ? lds_dynamic : lds_static;
   int8_t *Xs = lds_buf, *Ws = lds_buf + BM * kLdsRow;
 
   const int tid = threadIdx.x;
@@ -102,6 +109,79 @@ __global__ __launch_bounds__(WM * WN * 64)
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) acc[ni][mi] = v4i{0, 0, 0, 0};
 
+  const int KT = kpad >> 6;
+  if constexpr (DMA) {
+    static_assert(NW == 8 && XCH == 1024 && WCH == 1024, "two 1 KB chunks of each operand per wave and k tile");
+    // Chunk q of a tile = its rows 16 q .. 16 q + 15 = 1 KB of the unpadded swizzled layout: a wave instruction
+    // fills it, lane l with the 16 bytes at position l % 4 of row 16 q + l / 4 -- which, by the swizzle, are piece
+    // (l % 4) ^ ((row >> 1) & 3) of that row in memory; the four lanes of a row still fetch its 64 bytes.
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    const int8_t *gx0, *gx1, *gw0, *gw1;
+    {
+      const int ra = 16 * wv + (lane >> 2), rb = ra + 128;
+      const int pa = ((lane & 3) ^ ((ra >> 1) & 3)) << 4, pb = ((lane & 3) ^ ((rb >> 1) & 3)) << 4;
+      const int xa = row_base + ra < M ? row_base + ra : M - 1;  // rows past the end repeat the last one; never stored
+      const int xb = row_base + rb < M ? row_base + rb : M - 1;
+      gx0 = A + (size_t)xa * lda + pa;
+      gx1 = A + (size_t)xb * lda + pb;
+      gw0 = W + (size_t)(col_base + ra) * kpad + pa;
+      gw1 = W + (size_t)(col_base + rb) * kpad + pb;
+    }
+    typedef const __attribute__((address_space(1))) void *gptr;
+    typedef __attribute__((address_space(3))) void *lptr;
+    // tile kt -> buffer kt % kDmaBuffers; past the last tile the last one again, into a buffer nobody reads, so
+    // that every iteration issues the same four loads and the counts below hold to the end
+    auto dma = [&](int kt) {
+      const int ko = (kt < KT ? kt : KT - 1) << 6;
+      int8_t *base = lds_buf + (kt & (kDmaBuffers - 1)) * kTileBytes + wv * 1024;
+      __builtin_amdgcn_global_load_lds((gptr)(gx0 + ko), (lptr)base, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr)(gx1 + ko), (lptr)(base + 8192), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr)(gw0 + ko), (lptr)(base + BM * kLdsRow), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr)(gw1 + ko), (lptr)(base + BM * kLdsRow + 8192), 16, 0, 0);
+    };
+    // every wave's part of the tiles up to the one `left` loads ago has landed, for every wave: vector memory
+    // operations complete in the order issued; a bare barrier (__syncthreads() would wait for all of them)
+#define GEMM_LANDED(left)                                                \
+  do {                                                                   \
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(left) : "memory"); \
+    __builtin_amdgcn_s_barrier();                                        \
+    asm volatile("" ::: "memory");                                       \
+  } while (0)
+#define GEMM_READ_OPS(xf, wf, kt)                                                                             \
+  do {                                                                                                        \
+    const int8_t *xs = Xs + ((kt) & (kDmaBuffers - 1)) * kTileBytes, *wsb = Ws + ((kt) & (kDmaBuffers - 1)) * kTileBytes; \
+    _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                                                         \
+      xf[mi] = *reinterpret_cast<const v4i *>(xs + lds_piece(wm * TM + mi * 16 + (lane & 15), lane >> 4));    \
+    _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                                         \
+      wf[ni] = *reinterpret_cast<const v4i *>(wsb + lds_piece(wn * TN + ni * 16 + (lane & 15), lane >> 4));   \
+  } while (0)
+    // Iteration kt: the operands of tile kt are in registers (cur) and tile kt + 1 is complete in LDS.  Tile kt + 3 is
+    // requested into the buffer of tile kt - 1 (read two iterations ago, two barriers back), the operands of tile
+    // kt + 1 are read (nxt) under the MFMAs of tile kt, and the iteration ends once tile kt + 2 has landed.
+#define GEMM_DMA_TILE(xc, wc, xn, wn_, kt)                                                                    \
+  do {                                                                                                        \
+    dma((kt) + 3);                                                                                            \
+    if ((kt) + 1 < KT) GEMM_READ_OPS(xn, wn_, (kt) + 1);                                                      \
+    _Pragma("unroll") for (int ni = 0; ni < NI; ++ni)                                                         \
+      _Pragma("unroll") for (int mi = 0; mi < MI; ++mi)                                                       \
+        acc[ni][mi] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wc[ni], xc[mi], acc[ni][mi], 0, 0, 0);            \
+    GEMM_LANDED(4);                                                                                           \
+  } while (0)
+    v4i xfa[MI], wfa[NI], xfb[MI], wfb[NI];
+    dma(0);
+    dma(1);
+    dma(2);
+    GEMM_LANDED(4);  // tiles 0 and 1
+    GEMM_READ_OPS(xfa, wfa, 0);
+    for (int kt = 0; kt < KT; kt += 2) {
+      GEMM_DMA_TILE(xfa, wfa, xfb, wfb, kt);
+      if (kt + 1 < KT) GEMM_DMA_TILE(xfb, wfb, xfa, wfa, kt + 1);
+    }
+    GEMM_LANDED(0);  // the loads past the end too: the buffers are about to hold the staged results
+#undef GEMM_DMA_TILE
+#undef GEMM_READ_OPS
+#undef GEMM_LANDED
+  } else {
   // The next k-tile's chunks wait in named registers between their load and their LDS store.  (As arrays filled
   // and drained by helper lambdas they were left in scratch memory in some builds: every chunk then went
   // load -> scratch -> LDS, the loads no longer overlapped the MFMAs, and the kernel ran at half speed.)
@@ -110,7 +190,6 @@ __global__ __launch_bounds__(WM * WN * 64)
   v4i sa_x0 = {}, sa_x1 = {}, sa_w0 = {}, sa_w1 = {};
   v4i sb_x0 = {}, sb_x1 = {}, sb_w0 = {}, sb_w1 = {};
   v4i sc_x0 = {}, sc_x1 = {}, sc_w0 = {}, sc_w1 = {};
-  const int KT = kpad >> 6;
   const int c0 = tid, c1 = tid + NT;
   const int8_t *xsrc0, *xsrc1, *wsrc0, *wsrc1;
   {
@@ -178,6 +257,7 @@ __global__ __launch_bounds__(WM * WN * 64)
 #undef GEMM_K_TILE
 #undef GEMM_LOAD_TILES
 #undef GEMM_STORE_TILES
+  }
 
   // epilogue: + bias, rescale, saturate, store
   const int cpg = rq.cols_per_gate;
@@ -294,6 +374,18 @@ static int gemm_xcd_rows(int nrb, int ncb, int bm, int bn, int kpad, unsigned *g
   return best;
 }
 
+constexpr unsigned kGemmDmaLds = kDmaBuffers * (256 + 256) * kLdsRow;  // 128 KB: beyond the default limit
+
+// once per process and device, before the first launch of the 256 x 256 tile (not from a call under graph capture)
+hipError_t gemm_init() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_i8_kernel<256, 256, 2, 4, false, true>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kGemmDmaLds);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_i8_kernel<256, 256, 2, 4, true, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmDmaLds);
+  return e;
+}
+
 template <bool OUT8>
 static void launch_gemm(hipStream_t s, const int8_t *A, int lda, int M, const int8_t *W, int kpad,
                         int ncols, const int32_t *bias, const Requant &rq, void *out, int ldc,
@@ -304,8 +396,8 @@ static void launch_gemm(hipStream_t s, const int8_t *A, int lda, int M, const in
   if (M >= 2048 && ncols_pad >= 1024 && ncols_pad % 256 == 0) {
     const int nrb = (M + 255) / 256, ncb = ncols_pad / 256;
     const int xr = gemm_xcd_rows(nrb, ncb, 256, 256, kpad, &grid);
-    hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 4, OUT8>), dim3(grid), dim3(512), 0, s, A, lda, M, W,
-                       kpad, ncols, bias, rq, out, ldc, out2, ldc2, nrb, ncb, xr);
+    hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 4, OUT8, true>), dim3(grid), dim3(512), kGemmDmaLds, s, A, lda, M,
+                       W, kpad, ncols, bias, rq, out, ldc, out2, ldc2, nrb, ncb, xr);
   } else if (M > 256) {
     const int nrb = (M + 127) / 128, ncb = ncols_pad / 128;
     const int xr = gemm_xcd_rows(nrb, ncb, 128, 128, kpad, &grid);

@@ -510,7 +510,7 @@ int sru_int_prepare(const sru_int_layer_params *layers, int32_t num_layers, int3
       std::memcpy(img.data() + o.vq, q.vq.data(), (size_t)2 * N * 2);
       offs[l] = o;
     }
-    if (hipSetDevice(device) != hipSuccess || in_gemm_init() != hipSuccess ||
+    if (hipSetDevice(device) != hipSuccess || in_gemm_init() != hipSuccess || gemm_init() != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&m->arena), img.size()) != hipSuccess) {
       m->arena = nullptr;
       delete m;
