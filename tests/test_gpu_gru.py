@@ -103,6 +103,9 @@ def test_large_products_take_the_wide_matmul_tile(gru):
     block, columns beyond the real ones, input depths 100 and 400."""
     layers, x = wl.make_gru([100, 400], 400, 70, 30, seed=12, weight_param=0.08)
     compare_all(gru, layers, x, "gru_tile256")
+    # a depth of one k tile (48 -> 64 bytes): that tile's four-deep load pipeline runs on repeats of the only tile
+    layers, x = wl.make_gru([48], 400, 70, 30, seed=13, weight_param=0.1)
+    compare_all(gru, layers, x, "gru_tile256_k64")
 
 
 def test_split_sequence_and_long_run(gru):
