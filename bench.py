@@ -216,6 +216,8 @@ def main():
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 one launch per operation and step")
     ap.add_argument("--mfma-store-ceiling", action="store_true",
                     help="only measure what the chip sustains for the input GEMM's mix of int8 MFMAs and streaming stores")
+    ap.add_argument("--lds-probe", action="store_true",
+                    help="only launch the LDS access pattern probes of the matmul kernels' lane -> address maps, for rocprofv3 --pmc")
     ap.add_argument("--gru", default="", metavar="L,I,N,B,T",
                     help="benchmark the integer GRU instead (the cell Sec. 7 names; gru_int_forward): L layers of N cells, "
                          "layer 0 input I, B rows, T steps, e.g. 2,512,2048,256,64; one JSON line")
@@ -252,6 +254,19 @@ def main():
         return
     if args.gru:
         bench_gru(args, np, torch, wl, binding)
+        return
+    if args.lds_probe:
+        rows = []
+        for name, mp in (("operand of the 16x16x64 MFMA (row = lane % 16)", 0), ("operand of the 32x32x32 MFMA (row = lane % 32)", 1),
+                         ("staging order (four lanes per row)", 2)):
+            for stride, swz in ((12, 0), (16, 0), (20, 0), (24, 0), (36, 0), (68, 0), (16, 1), (16, 2)):
+                for write in (False, True):
+                    binding.lds_probe(mp, stride, swz, write)
+                    rows.append({"dispatch": len(rows), "map": name, "stride_words": stride, "swizzle": swz, "write": write})
+        print(json.dumps({"lds_probe": rows, "note": "one launch of lds_probe_kernel per row, in this order; run under rocprofv3 "
+                          "--pmc SQ_LDS_IDX_ACTIVE SQ_LDS_BANK_CONFLICT: IDX_ACTIVE / 16384 = LDS clocks per wave access of 16 "
+                          "bytes per lane (4 for a read and 8 for a write without conflicts); swizzle 1 = piece ^ ((row >> 1) & 3), "
+                          "2 = piece ^ ((row >> 2) & 3)"}))
         return
     if args.mfma_store_ceiling:
         rows = [binding.mfma_store_ceiling(s) for s in (0, 1, 2, 4, 8)]

@@ -392,6 +392,22 @@ int lstm_int_profile_end(lstm_int_model *model, int64_t launches[LSTM_INT_K_COUN
 int lstm_int_mfma_store_ceiling(int32_t device, int32_t stores_per_block, int32_t blocks,
                                 double *tops, double *store_gbs, double *clock_ghz);
 
+/*
+ * Measurement aid for the LDS layouts of the matmul kernels (the operand tiles
+ * of the gate matmuls, Sec. 3.2.4): ONE launch of one workgroup of four waves
+ * in which every wave repeats one 16-byte LDS access per lane 4096 times.  What
+ * the access costs is read from the hardware counters of that launch (rocprofv3
+ * --pmc SQ_LDS_IDX_ACTIVE SQ_LDS_BANK_CONFLICT): IDX_ACTIVE / (4 * 4096) = LDS
+ * clocks per wave access.  Rows of `stride_words` 32-bit words; lane -> (row,
+ * 16-byte piece) by `map`: 0 = (lane % 16, lane / 16), the operand of the
+ * 16x16x64 MFMA; 1 = (lane % 32, lane / 32), of the 32x32x32 MFMA; 2 =
+ * (lane / 4, lane % 4), the order in which four lanes fetch a row's 64 bytes;
+ * the piece sits at position piece ^ s(row), s by `swizzle`: 0 = none, 1 =
+ * (row >> 1) & 3, 2 = (row >> 2) & 3; write != 0 stores instead of loading.
+ * Needs stride_words in 4..128 and a multiple of 4.  Synchronizes.
+ */
+int lstm_int_lds_probe(int32_t device, int32_t map, int32_t stride_words, int32_t swizzle, int32_t write);
+
 void lstm_int_destroy(lstm_int_model *model);
 
 const char *lstm_int_strerror(int code);

@@ -133,6 +133,8 @@ def lib():
         L.lstm_int_calibrate.restype = C.c_int
         L.lstm_int_calibrate.argtypes = [C.POINTER(LayerParams), C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
                                          C.c_int32, C.c_void_p, C.POINTER(LayerStats), C.c_void_p]
+        L.lstm_int_lds_probe.restype = C.c_int
+        L.lstm_int_lds_probe.argtypes = [C.c_int32] * 5
         L.lstm_int_mfma_store_ceiling.restype = C.c_int
         L.lstm_int_mfma_store_ceiling.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double),
                                                   C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -407,6 +409,12 @@ def calibrate(layers, x, device=0, want_output=False, apply=True, max_rows=None)
             spec.m_min, spec.m_max, spec.c_absmax = d["m_min"], d["m_max"], d["c_absmax"]
             spec.g_absmax = list(d["g_absmax"])
     return (stats, y) if want_output else stats
+
+
+# lstm_int_lds_probe
+def lds_probe(map, stride_words, swizzle=0, write=False, device=0):
+    """One launch of the LDS access pattern probe (see lstm_int.h); its cost is read from rocprofv3's counters."""
+    _check(lib().lstm_int_lds_probe(device, map, stride_words, swizzle, int(write)), "lstm_int_lds_probe")
 
 
 # lstm_int_mfma_store_ceiling

@@ -1,4 +1,5 @@
-// Measurement aid for the input GEMM's roofline: what the chip sustains when every compute unit issues
+// Measurement aids.
+// 1. For the input GEMM's roofline: what the chip sustains when every compute unit issues
 // int8 MFMAs back to back from registers AND streams results to HBM at a given ratio of bytes per MFMA.
 // The hoisted input GEMM (in_gemm.hip) needs 40 MFMAs and 4 KB of int16 output per wave and block of 32
 // rows at the benchmark shape, which puts it at the ridge of the int8 MFMA and HBM rooflines; this kernel
@@ -49,7 +50,59 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   if (acc[0][0] == 0x7fffffff && acc[1][3] == 0x12345) out[0] = v4i{acc[0][1], acc[1][1], 0, 0};
 }
 
+// 2. For the LDS layouts of the matmul kernels: what a lane -> address map costs in LDS clocks (bank conflicts), read
+// from the hardware counters of the launch.  Every address stays inside the array: row < 32, stride <= 128 words,
+// piece < 4.
+constexpr int kProbeIters = 4096;
+__global__ __launch_bounds__(256) void lds_probe_kernel(int map, int stride_words, int swizzle, int write, int *sink) {
+  __shared__ __attribute__((aligned(16))) int lds[4 * 32 * 128];  // 64 KB: four waves x 32 rows x 128 words
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < 4 * 32 * 128; i += 256) lds[i] = i;
+  __syncthreads();
+  int row, piece;
+  if (map == 0) {
+    row = lane & 15;
+    piece = lane >> 4;
+  } else if (map == 1) {
+    row = lane & 31;
+    piece = lane >> 5;
+  } else {
+    row = lane >> 2;
+    piece = lane & 3;
+  }
+  const int sw = swizzle == 1 ? (row >> 1) & 3 : (swizzle == 2 ? (row >> 2) & 3 : 0);
+  v4i *p = reinterpret_cast<v4i *>(lds + wave * 32 * stride_words + row * stride_words + ((piece ^ sw) << 2));
+  v4i acc = {0, 0, 0, 0};
+  for (int i = 0; i < kProbeIters; ++i) {
+    if (write) {
+      *p = acc;
+      acc.x += i;
+      asm volatile("" ::: "memory");
+    } else {
+      v4i v = *p;
+      asm volatile("" : "+v"(v));
+      acc += v;
+    }
+  }
+  if (acc.x == 0x7fffffff) sink[threadIdx.x] = acc.y + acc.z + acc.w;
+}
+
 }  // namespace
+
+extern "C" int lstm_int_lds_probe(int32_t device, int32_t map, int32_t stride_words, int32_t swizzle, int32_t write) {
+  if (device < 0 || map < 0 || map > 2 || swizzle < 0 || swizzle > 2 || stride_words < 4 || stride_words > 128 ||
+      (stride_words & 3))
+    return LSTM_INT_E_INVALID_ARG;
+  if (hipSetDevice(device) != hipSuccess) return LSTM_INT_E_DEVICE;
+  int *sink = nullptr;
+  int rc = LSTM_INT_E_DEVICE;
+  if (hipMalloc(&sink, 256 * sizeof(int)) == hipSuccess) {
+    hipLaunchKernelGGL(lds_probe_kernel, dim3(1), dim3(256), 0, nullptr, map, stride_words, swizzle, write, sink);
+    if (hipDeviceSynchronize() == hipSuccess) rc = LSTM_INT_OK;
+  }
+  if (sink) (void)hipFree(sink);
+  return rc;
+}
 
 extern "C" int lstm_int_mfma_store_ceiling(int32_t device, int32_t stores_per_block, int32_t blocks, double *tops,
                                            double *store_gbs, double *clock_ghz) {
