@@ -222,6 +222,7 @@ struct GruStepArgs {
 // of R at every step of a sequence and keeps it in its L2 (N = 2048: 1.5 MB of 4 MB).  The mapping only places
 // the work; results do not depend on where a workgroup runs.
 constexpr int kPartTile = 32 * 33;  // one 32 x 32 tile of partial sums in LDS, row stride 33
+constexpr int kSeqSigBytes = 65552;  // the sigma table of the persistent kernel in LDS: 32769 entries, to 16 bytes
 
 template <int RB>
 __global__ __launch_bounds__(256) void gru_step_kernel(GruStepArgs a) {
@@ -474,6 +475,9 @@ constexpr int kSeqMaxPer = 8;  // k steps per wave: depth up to 4 x 8 x 32 = 102
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gru_seq_kernel(GruSeqArgs a) {
   __shared__ __attribute__((aligned(16))) int32_t part[4 * 3 * kPartTile];
   __shared__ int flag[4];
+  // the sigma table (Q3.12, all 32769 entries) in LDS: the reset gate's lookup is the first of two dependent ones on
+  // the chain from the matmul to the new state, and from LDS it no longer costs a round trip to the L2
+  extern __shared__ __attribute__((aligned(16))) uint16_t sig_lds[];  // kSeqSigBytes, set at launch
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, b2 = lane >> 5;
   const int wg = blockIdx.x;
@@ -527,6 +531,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
 #pragma unroll
   for (int c = 0; c < 4; ++c) h16r[c] = n0 + c < N ? a.h16[(size_t)rowc * N + n0 + c] : 0;
+  {
+    const int4 *src = reinterpret_cast<const int4 *>(a.sig_tab);  // readable to a multiple of 16 bytes: the arena goes on
+    int4 *dst = reinterpret_cast<int4 *>(sig_lds);
+    for (int i = tid; i < kSeqSigBytes / 16; i += 256) dst[i] = src[i];
+  }
   if (tid == 0) flag[0] = 1;
   __syncthreads();
 
@@ -593,8 +602,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const int32_t sum = part[o] + part[o + 3 * kPartTile] + part[o + 6 * kPartTile] + part[o + 9 * kPartTile];
         th[g] = sat16(rescale(sum + bhe[g][c], a.Mh[g], a.rh[g]));
       }
-      const int32_t r = sigmoid_from_table(a.sig_tab, sat16(txe[0][c] + th[0]));
-      const int32_t u = sigmoid_from_table(a.sig_tab, sat16(txe[1][c] + th[1]));
+      const int32_t r = sigmoid_from_table(sig_lds, sat16(txe[0][c] + th[0]));
+      const int32_t u = sigmoid_from_table(sig_lds, sat16(txe[1][c] + th[1]));
       const int32_t rn = (r * th[2] + 16384) >> 15;
       const int32_t cand = tanh_from_table(a.tanh_tab, sat16(txe[2][c] + rn));
       const int32_t hn = cell_update32(cifg_input_gate(u), cand, u, h16r[c], 0);
@@ -769,6 +778,8 @@ int gru_int_prepare(const gru_int_layer_params *layers, int32_t num_layers, int3
       offs[l] = o;
     }
     if (hipSetDevice(device) != hipSuccess || in_gemm_init() != hipSuccess || gemm_init() != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&gru_seq_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kSeqSigBytes) != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&m->arena), img.size()) != hipSuccess) {
       m->arena = nullptr;
       delete m;
@@ -947,7 +958,7 @@ int gru_int_forward(const gru_int_model *m, const int8_t *x, int32_t T, int32_t 
       q2.spin_limit = m->spin_limit; q2.sync_sleep = m->sync_sleep;
       q2.extra_arrivals = m->extra_arrivals;
       timed_begin(GRU_INT_K_STEP, T);
-      hipLaunchKernelGGL(gru_seq_kernel, dim3((unsigned)(8 * ctiles * ((groups + 7) / 8))), dim3(256), 0, s, q2);
+      hipLaunchKernelGGL(gru_seq_kernel, dim3((unsigned)(8 * ctiles * ((groups + 7) / 8))), dim3(256), kSeqSigBytes, s, q2);
       timed_end();
     } else {
     GruStepArgs a{};
