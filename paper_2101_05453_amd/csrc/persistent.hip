@@ -38,7 +38,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned long long u64;
 
-constexpr int kLdsRow = 80;  // 64 data bytes + 16 pad
 constexpr int kPrmLdsBytes = 256;  // sizeof(PrmLds) in rec_kernel.inc.h
 
 // ---------------------------------------------------------------------------
@@ -46,9 +45,15 @@ constexpr int kPrmLdsBytes = 256;  // sizeof(PrmLds) in rec_kernel.inc.h
 // each wave 64 rows x 2 tiles = 2x2 MFMA 32x32 blocks.  Weight tile rows are
 // the MFMA's first operand: D[rho][row], rho = 8*gate + 4*(lane/32) + c.
 // ---------------------------------------------------------------------------
+// A staged k tile in LDS: rows of 64 bytes without padding, the 16-byte piece p of row r at position
+// p ^ ((r >> 2) & 3): free of bank conflicts both for the operand reads of the 32x32x32 MFMA (row = lane % 32) and
+// for the staging stores (four lanes per row), by the counters of a probe kernel; rows padded to 80 bytes kept the
+// reads free and cost the stores twice their time.
+__device__ __forceinline__ int in_gemm_piece(int row, int piece) { return row * 64 + ((piece ^ ((row >> 2) & 3)) << 4); }
+
 __global__ __launch_bounds__(256) void in_gemm_kernel(InGemmArgs a) {
-  __shared__ __attribute__((aligned(16))) int8_t Xs[128 * kLdsRow];
-  __shared__ __attribute__((aligned(16))) int8_t Ws[128 * kLdsRow];
+  constexpr int kTile = 2 * 128 * 64;  // one staged k tile: 128 activation rows, then 128 weight rows
+  __shared__ __attribute__((aligned(16))) int8_t lds[2 * kTile];  // tile kt + 1 is stored while tile kt is multiplied
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int row_base = blockIdx.x * 128;  // padded rows m' = t * Bp + b
@@ -56,8 +61,8 @@ __global__ __launch_bounds__(256) void in_gemm_kernel(InGemmArgs a) {
   const int rows_total = a.T * a.Bp;
 
   // the two activation rows and two weight rows this thread stages per k tile; pointers and the registers the
-  // next tile waits in are named variables on purpose (as small arrays they were left in scratch memory, and the
-  // loads then no longer overlapped the MFMAs)
+  // next tiles wait in are named variables of plain vector type on purpose (as small arrays, or as HIP's int4 in a
+  // struct, they were left in scratch memory, and the loads then no longer overlapped the MFMAs)
   const int c0 = tid, c1 = tid + 256;
   auto x_row = [&](int c) {
     int m = row_base + (c >> 2);
@@ -70,7 +75,7 @@ __global__ __launch_bounds__(256) void in_gemm_kernel(InGemmArgs a) {
   const int8_t *const xsrc0 = x_row(c0), *const xsrc1 = x_row(c1);
   const int8_t *const wsrc0 = a.W2 + ((size_t)tile_base * 32 + (c0 >> 2)) * a.kpad + ((c0 & 3) << 4);
   const int8_t *const wsrc1 = a.W2 + ((size_t)tile_base * 32 + (c1 >> 2)) * a.kpad + ((c1 & 3) << 4);
-  const int dst0 = (c0 >> 2) * kLdsRow + ((c0 & 3) << 4), dst1 = (c1 >> 2) * kLdsRow + ((c1 & 3) << 4);
+  const int dst0 = in_gemm_piece(c0 >> 2, c0 & 3), dst1 = in_gemm_piece(c1 >> 2, c1 & 3);
 
   v16i acc[2][2];
 #pragma unroll
@@ -81,38 +86,61 @@ __global__ __launch_bounds__(256) void in_gemm_kernel(InGemmArgs a) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
   const int KT = a.kpad >> 6;
-  int4 x0 = *reinterpret_cast<const int4 *>(xsrc0), x1 = *reinterpret_cast<const int4 *>(xsrc1);
-  int4 w0 = *reinterpret_cast<const int4 *>(wsrc0), w1 = *reinterpret_cast<const int4 *>(wsrc1);
-  for (int kt = 0; kt < KT; ++kt) {
-    *reinterpret_cast<int4 *>(Xs + dst0) = x0;
-    *reinterpret_cast<int4 *>(Xs + dst1) = x1;
-    *reinterpret_cast<int4 *>(Ws + dst0) = w0;
-    *reinterpret_cast<int4 *>(Ws + dst1) = w1;
-    __syncthreads();
-    if (kt + 1 < KT) {
-      x0 = *reinterpret_cast<const int4 *>(xsrc0 + ((kt + 1) << 6));
-      x1 = *reinterpret_cast<const int4 *>(xsrc1 + ((kt + 1) << 6));
-      w0 = *reinterpret_cast<const int4 *>(wsrc0 + ((kt + 1) << 6));
-      w1 = *reinterpret_cast<const int4 *>(wsrc1 + ((kt + 1) << 6));
-    }
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-      v4i xf[2], wf[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        xf[i] = *reinterpret_cast<const v4i *>(Xs + (wm * 64 + i * 32 + (lane & 31)) * kLdsRow +
-                                               kk * 32 + ((lane >> 5) << 4));
-        wf[i] = *reinterpret_cast<const v4i *>(Ws + (wn * 64 + i * 32 + (lane & 31)) * kLdsRow +
-                                               kk * 32 + ((lane >> 5) << 4));
-      }
-#pragma unroll
-      for (int ti = 0; ti < 2; ++ti)
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-          acc[ti][mi] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ti], xf[mi], acc[ti][mi], 0, 0, 0);
-    }
-    __syncthreads();
+  // tile t waits in register set t % 3 (sa, sb, sc) between its load and its LDS store
+  v4i sa_x0 = {}, sa_x1 = {}, sa_w0 = {}, sa_w1 = {};
+  v4i sb_x0 = {}, sb_x1 = {}, sb_w0 = {}, sb_w1 = {};
+  v4i sc_x0 = {}, sc_x1 = {}, sc_w0 = {}, sc_w1 = {};
+#define IN_GEMM_LOAD(st, kt)                                              \
+  do {                                                                    \
+    if ((kt) < KT) {                                                      \
+      st##_x0 = *reinterpret_cast<const v4i *>(xsrc0 + ((kt) << 6));      \
+      st##_x1 = *reinterpret_cast<const v4i *>(xsrc1 + ((kt) << 6));      \
+      st##_w0 = *reinterpret_cast<const v4i *>(wsrc0 + ((kt) << 6));      \
+      st##_w1 = *reinterpret_cast<const v4i *>(wsrc1 + ((kt) << 6));      \
+    }                                                                     \
+  } while (0)
+#define IN_GEMM_STORE(st, buf)                                            \
+  do {                                                                    \
+    int8_t *xs_ = lds + (buf) * kTile, *ws_ = xs_ + 128 * 64;             \
+    *reinterpret_cast<v4i *>(xs_ + dst0) = st##_x0;                       \
+    *reinterpret_cast<v4i *>(xs_ + dst1) = st##_x1;                       \
+    *reinterpret_cast<v4i *>(ws_ + dst0) = st##_w0;                       \
+    *reinterpret_cast<v4i *>(ws_ + dst1) = st##_w1;                       \
+  } while (0)
+  // One k tile: tile kt + 1 goes from its registers (nx) into the LDS buffer tile kt - 1 was read from (every wave is
+  // past the barrier that ended kt - 1), the freed registers request tile kt + 4, tile kt is multiplied out of the
+  // other buffer: one barrier per tile, global loads three tiles ahead.
+#define IN_GEMM_K_TILE(nx, kt)                                                                          \
+  do {                                                                                                  \
+    if ((kt) + 1 < KT) IN_GEMM_STORE(nx, ((kt) + 1) & 1);                                               \
+    IN_GEMM_LOAD(nx, (kt) + 4);                                                                         \
+    const int8_t *xs = lds + ((kt) & 1) * kTile, *wsb = xs + 128 * 64;                                  \
+    _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                  \
+      v4i xf[2], wf[2];                                                                                 \
+      _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                   \
+        xf[i] = *reinterpret_cast<const v4i *>(xs + in_gemm_piece(wm * 64 + i * 32 + (lane & 31), kk * 2 + (lane >> 5))); \
+        wf[i] = *reinterpret_cast<const v4i *>(wsb + in_gemm_piece(wn * 64 + i * 32 + (lane & 31), kk * 2 + (lane >> 5))); \
+      }                                                                                                 \
+      _Pragma("unroll") for (int ti = 0; ti < 2; ++ti)                                                  \
+        _Pragma("unroll") for (int mi = 0; mi < 2; ++mi)                                                \
+          acc[ti][mi] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ti], xf[mi], acc[ti][mi], 0, 0, 0);    \
+    }                                                                                                   \
+    __syncthreads();                                                                                    \
+  } while (0)
+  IN_GEMM_LOAD(sa, 0);
+  IN_GEMM_LOAD(sb, 1);
+  IN_GEMM_LOAD(sc, 2);
+  IN_GEMM_STORE(sa, 0);
+  __syncthreads();
+  IN_GEMM_LOAD(sa, 3);
+  for (int kt = 0; kt < KT; kt += 3) {
+    IN_GEMM_K_TILE(sb, kt);
+    if (kt + 1 < KT) IN_GEMM_K_TILE(sc, kt + 1);
+    if (kt + 2 < KT) IN_GEMM_K_TILE(sa, kt + 2);
   }
+#undef IN_GEMM_K_TILE
+#undef IN_GEMM_STORE
+#undef IN_GEMM_LOAD
 
   // epilogue: lane holds gates 0..3 x cells 4*(lane/32)+0..3 of row (lane%32)
 #pragma unroll
