@@ -142,3 +142,12 @@ def test_calibrate_rejects_bad_arguments_before_touching_a_device():
     arr[0].num_cells = arr[0].output_size = 1 << 20  # T * B * 4 * N beyond the 32-bit index range
     assert lib.lstm_int_calibrate(arr, 1, 0, dummy, 1 << 10, 2, None, st, None) == -2
     del keep
+
+
+def test_lds_probe_rejects_arguments_outside_its_array():
+    """The probe's addresses stay inside its LDS array only for the documented ranges; everything else is refused on
+    the host, before any device call."""
+    lib = binding.lib()
+    for args in ((0, 3, 16, 0, 0), (0, -1, 16, 0, 0), (0, 0, 132, 0, 0), (0, 0, 0, 0, 0), (0, 0, 18, 0, 0), (0, 0, 16, 3, 0),
+                 (-1, 0, 16, 0, 0)):
+        assert lib.lstm_int_lds_probe(*args) == binding.E_INVALID_ARG, args
