@@ -108,6 +108,14 @@ def test_large_products_take_the_wide_matmul_tile(gru):
     compare_all(gru, layers, x, "gru_tile256_k64")
 
 
+def test_benchmark_configuration_sampled_rows(gru):
+    """The configuration bench.py --gru times (2 x 2048 cells, input 512, B = 256, T = 64: 16384-row matmuls on the
+    register-resident GEMM and on the general matmul's widest tile, 128 step launches) on three rows of different
+    row tiles: every traced tensor, the output and the carried state."""
+    layers, x = wl.make_gru([512, 2048], 2048, 256, 64, seed=0, weight_param=0.03)
+    compare_all(gru, layers, x, "gru_bench", rows=[0, 100, 255])
+
+
 def test_split_sequence_and_long_run(gru):
     import torch
 

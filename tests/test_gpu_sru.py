@@ -48,13 +48,13 @@ def state_rows(buf, layers, B, sel):
     return out
 
 
-def compare_all(sru, layers, x, name, rows=None):
+def compare_all(sru, layers, x, name, rows=None, calibration_rows=None):
     """Every traced tensor of every layer, the output and the carried state; then the untraced call (which may
     take the register-resident matmul and the tile-ordered scan) with and without a state buffer, and the
     same with that matmul switched off."""
     import torch
 
-    sru.calibrate(layers, x, threads=8)
+    sru.calibrate(layers, x if calibration_rows is None else np.ascontiguousarray(x[:, :calibration_rows]), threads=8)
     lib_m, orc_m = both(sru, layers)
     xq = quantize_x(x, orc_m.get_quant(0))
     T, B, _ = xq.shape
@@ -131,6 +131,14 @@ def test_speech_encoder_shapes_sampled_rows(sru):
     compare_all(sru, layers, x, "sru2048", rows=[0, 15, 16, 100, 127, 128, 200, 255])
     layers, x = wl.make_sru([256, 1024], 1024, 64, 10, seed=4, weight_param=0.04)
     compare_all(sru, layers, x, "sru1024")
+
+
+def test_benchmark_configuration_sampled_rows(sru):
+    """The configuration bench.py --sru times, two of its four layers (2048 cells, input 512 then 2048, B = 256,
+    T = 64: 16384-row matmuls on the register-resident GEMM and on the general matmul's widest tile, both forms of
+    the scan) on three rows of different row blocks."""
+    layers, x = wl.make_sru([512, 2048], 2048, 256, 64, seed=0, weight_param=0.03)
+    compare_all(sru, layers, x, "sru_bench", rows=[0, 100, 255], calibration_rows=16)  # statistics from 16 rows (Sec. 4)
 
 
 def test_split_sequence_and_long_run(sru):
