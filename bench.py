@@ -177,6 +177,11 @@ def bench_sru(args, np, torch, wl, binding):
            "roofline": {"bound": "hbm", "achieved": scan_bytes / scan_us * 1e-3, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": scan_bytes / scan_us * 1e-3 / PEAK_HBM_GBS, "kernel": "sru_scan_kernel",
                         "avg_launch_us": scan_us, "traffic": None,
+                        # what actually bounds the scan: its instruction stream.  80 instructions per cell and step
+                        # (vector, scalar, LDS and memory instructions of the compiled loops, / 16 cell-steps per
+                        # round) against 256 CUs x 64 lanes x 2.4 GHz, one instruction per lane and clock
+                        "issue": {"bound": "alu", "achieved": T * B * N * 80.0 / scan_us * 1e-6, "peak": 39.3,
+                                  "unit": "T lane-instructions/s", "frac": T * B * N * 80.0 / scan_us * 1e-6 / 39.3},
                         "kernels": {"input_gemm": {"avg_us": gemm_us, "tops": gemm_ops / gemm_us * 1e-6,
                                                    "frac_mfma": gemm_ops / gemm_us * 1e-6 / PEAK_INT8_TOPS}}}}
     if not args.no_cpu_baseline:
